@@ -1,0 +1,217 @@
+/*
+ * purine.h - C ABI of the MI355X (gfx950) convolution-layer operator library and of the minimal
+ * single-GPU bi-graph executor.
+ *
+ * The library implements the operators inside the convolution layer of the paper's Figure 1(b)
+ * (section 2: a network is a bipartite graph of tensors and operators; "operators are functions
+ * of the incoming tensors and the results are put in the outgoing tensors"), and the event-driven
+ * task dispatcher of section 2.1 restricted to one GPU, with the `thread` property of section 3
+ * mapped to HIP streams.
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ *   - All tensor data pointers are DEVICE pointers (HBM), owned by the caller. The library never
+ *     allocates or frees device memory; scratch comes in through `ws`, whose size the matching
+ *     *_workspace_bytes query returns. Descriptor structs and dimension arrays are HOST memory,
+ *     read during the call only.
+ *   - Tensors are dense, row-major: activations NCHW, filters KCRS, bias [K]. `dim` holds the
+ *     extents, outermost first; unused trailing entries are ignored. No tensor may hold 2^31 or
+ *     more elements. Data pointers must be aligned to 16 bytes.
+ *   - dtype: PURINE_F32 tensors hold IEEE binary32. PURINE_BF16 tensors hold bfloat16 bit
+ *     patterns (uint16); arithmetic accumulates in fp32; results stored as bf16 are rounded to
+ *     nearest even. Weight and bias gradients are always PURINE_F32.
+ *   - Operator calls validate their arguments first (no launch happens on error), enqueue their
+ *     kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the null stream) and return
+ *     without waiting. Only purine_graph_run blocks.
+ *   - Return value: PURINE_OK (0) or a negative purine_status. Nothing aborts or throws.
+ *   - beta is 0 (overwrite the output) or 1 (add to what the output already holds).
+ *   - Results are deterministic: the same inputs give bit-identical outputs run to run (no
+ *     floating-point atomics; split reductions are summed in a fixed order).
+ */
+#ifndef PURINE_H
+#define PURINE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { PURINE_F32 = 0, PURINE_BF16 = 1, PURINE_I32 = 2 } purine_dtype;
+
+typedef enum {
+    PURINE_OK = 0,
+    PURINE_E_NULL = -1,      /* a required pointer is NULL                                  */
+    PURINE_E_SHAPE = -2,     /* extents inconsistent, empty, or too large                   */
+    PURINE_E_DTYPE = -3,     /* unsupported dtype or dtype combination                      */
+    PURINE_E_LAYOUT = -4,    /* misaligned data pointer or illegal aliasing                 */
+    PURINE_E_WORKSPACE = -5, /* ws is NULL or smaller than the query says                   */
+    PURINE_E_GRAPH = -6,     /* not a legal bi-graph (see purine_graph_run)                 */
+    PURINE_E_HIP = -7,       /* the HIP runtime reported an error                           */
+    PURINE_E_ARG = -8        /* a scalar argument is out of range (stride, beta, ids, ...)  */
+} purine_status;
+
+typedef struct {
+    void*   data;   /* device pointer                                  */
+    int32_t dtype;  /* purine_dtype                                    */
+    int32_t ndim;   /* 1..4                                            */
+    int64_t dim[4]; /* extents, outermost first                        */
+} purine_tensor;
+
+/* Convolution geometry. Filter extents R,S and the channel counts come from the filter tensor.
+ * Cross-correlation (no kernel flip), symmetric zero padding, no dilation, one group.
+ * Output extent along an axis: floor((in + 2*pad - k)/stride) + 1. */
+typedef struct { int32_t stride_h, stride_w, pad_h, pad_w; } purine_conv_desc;
+
+/* Square max-pooling window. */
+typedef struct { int32_t window, stride, pad; } purine_pool_desc;
+
+typedef enum { PURINE_CONV_FWD = 0, PURINE_CONV_BWD_DATA = 1, PURINE_CONV_BWD_WEIGHT = 2 } purine_conv_pass;
+
+const char* purine_status_string(int status);
+
+/* y_dim = {N, K, P, Q} for x_dim = {N, C, H, W}, w_dim = {K, C, R, S}.
+ * PURINE_E_SHAPE when channels disagree, an extent is < 1, or the padded input is smaller than the
+ * filter; PURINE_E_ARG when a stride is < 1 or a pad is < 0. Pure host integer code. */
+int purine_conv_out_shape(const purine_conv_desc* desc, const int64_t x_dim[4],
+                          const int64_t w_dim[4], int64_t y_dim[4]);
+
+/* Bytes of device scratch the given pass needs (0 when none). Returns 0 for illegal shapes: the
+ * operator call itself reports the error. Forward and backward-data need none; backward-weight
+ * needs room for its split-reduction partial sums. */
+size_t purine_conv_workspace_bytes(int pass, const purine_conv_desc* desc, const int64_t x_dim[4],
+                                   const int64_t w_dim[4], int32_t dtype);
+size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype);
+
+/* ---- the five operators of the convolution layer (paper Figure 1(b)) ---------------------- */
+
+/* Conv: y[n,k,p,q] = sum_{c,r,s} x[n,c,p*sh-ph+r,q*sw-pw+s] * w[k,c,r,s], taps outside x are 0.
+ * x, w, y share one dtype (F32 or BF16). The patch matrix is never written to memory.
+ * ws may be NULL (this pass needs no scratch). y must not overlap x or w. */
+int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
+                    purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* ConvBwdData: dx[n,c,h,w] = beta*dx + sum over (k,r,s,p,q) with p*sh-ph+r = h, q*sw-pw+s = w of
+ * dy[n,k,p,q] * w[k,c,r,s]. dy, w, dx share one dtype. dx's extents must be the x extents whose
+ * forward output has dy's extents. */
+int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
+                         const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
+                         size_t ws_bytes, void* hip_stream);
+
+/* ConvBwdWeight: dw[k,c,r,s] = beta*dw + sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*sh-ph+r,q*sw-pw+s].
+ * A plain sum over the batch (no 1/N), so shards of a data-parallel minibatch add up
+ * (paper section 3.4). x and dy share one dtype; dw is F32. The pixel reduction is split into
+ * chunks whose fp32 partial sums go to ws and are added in chunk order by a second kernel. */
+int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
+                           const purine_tensor* dy, purine_tensor* dw, float beta, void* ws,
+                           size_t ws_bytes, void* hip_stream);
+
+/* Bias: y[n,k,p,q] += b[k], in place. y: F32 or BF16 (add in fp32); b: same dtype as y. */
+int purine_bias_fwd(const purine_tensor* b, purine_tensor* y, void* hip_stream);
+
+/* BiasBwd: db[k] = beta*db + sum_{n,p,q} dy[n,k,p,q]. db is F32. Two-level fixed-order sum. */
+int purine_bias_bwd(const purine_tensor* dy, purine_tensor* db, float beta, void* ws,
+                    size_t ws_bytes, void* hip_stream);
+
+/* ---- exact support operators that chain conv layers into the synthetic workloads ---------- */
+
+/* y = max(x, 0). y may be x itself. Same dtype and extents. */
+int purine_relu_fwd(const purine_tensor* x, purine_tensor* y, void* hip_stream);
+/* dx = dy where x > 0, else 0. x may be the forward input or output (same sign test).
+ * dx may be dy itself. */
+int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tensor* dx,
+                    void* hip_stream);
+/* Max pooling. Padded positions never win; ties go to the first maximum in row-major window
+ * order. arg (I32, extents of y) receives the winner's flat position h*W+w inside its plane. */
+int purine_maxpool_fwd(const purine_pool_desc* desc, const purine_tensor* x, purine_tensor* y,
+                       purine_tensor* arg, void* hip_stream);
+/* dx[n,c,arg] = beta*dx + sum of dy over the windows that chose that position (fp32 sum, windows
+ * taken in row-major order). */
+int purine_maxpool_bwd(const purine_pool_desc* desc, const purine_tensor* dy,
+                       const purine_tensor* arg, purine_tensor* dx, float beta, void* hip_stream);
+/* Channel concatenation of n_parts NCHW tensors (same N,H,W,dtype) and its inverse. */
+int purine_concat_fwd(const purine_tensor* const* parts, int n_parts, purine_tensor* out,
+                      void* hip_stream);
+int purine_concat_bwd(const purine_tensor* dout, purine_tensor* const* dparts, int n_parts,
+                      void* hip_stream);
+/* out = terms[0] + terms[1] + ... in that order, fp32 adds (gradient fan-in). 1 <= n_terms <= 8.
+ * out may be terms[0]. */
+int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* out,
+               void* hip_stream);
+
+/* ---- bi-graph executor (paper sections 2, 2.1, 2.2 and the `thread` property of section 3) -- */
+
+typedef struct purine_graph purine_graph;
+
+typedef enum {
+    PURINE_OP_CONV_FWD = 0,        /* in: x, w            out: y                                 */
+    PURINE_OP_BIAS_FWD = 1,        /* in: y, b            out: y' (same storage as y)            */
+    PURINE_OP_CONV_BWD_DATA = 2,   /* in: dy, w [, dx]    out: dx'   (third input iff beta = 1)  */
+    PURINE_OP_CONV_BWD_WEIGHT = 3, /* in: x, dy [, dw]    out: dw'                               */
+    PURINE_OP_BIAS_BWD = 4,        /* in: dy [, db]       out: db'                               */
+    PURINE_OP_RELU_FWD = 5,        /* in: x               out: y                                 */
+    PURINE_OP_RELU_BWD = 6,        /* in: x, dy           out: dx                                */
+    PURINE_OP_MAXPOOL_FWD = 7,     /* in: x               out: y, arg                            */
+    PURINE_OP_MAXPOOL_BWD = 8,     /* in: dy, arg [, dx]  out: dx'                               */
+    PURINE_OP_CONCAT_FWD = 9,      /* in: parts...        out: cat                               */
+    PURINE_OP_CONCAT_BWD = 10,     /* in: dcat            out: dparts...                         */
+    PURINE_OP_SUM = 11,            /* in: terms...        out: sum                               */
+    PURINE_OP_HOST_NOP = 12        /* any in/out; does nothing on the device (bookkeeping tests) */
+} purine_op_kind;
+
+typedef struct {
+    purine_conv_desc conv;   /* conv ops                                          */
+    purine_pool_desc pool;   /* pool ops                                          */
+    float  beta;             /* ops with an accumulate form                       */
+    void*  ws;               /* device scratch private to this operator           */
+    size_t ws_bytes;
+} purine_op_attrs;
+
+/* The graph owns only host bookkeeping plus the HIP streams and events it creates lazily (none for
+ * a graph of HOST_NOP operators, so such graphs run on a machine without a GPU). */
+purine_graph* purine_graph_create(void);
+void purine_graph_destroy(purine_graph* g);
+
+/* Adds a tensor vertex; the descriptor is copied. name may be NULL. Returns the tensor id (>= 0)
+ * or a negative status. Two vertices may share storage: a tensor vertex is one VERSION of a
+ * buffer (an in-place operator reads version i and writes version i+1 at the same address). A
+ * vertex may have several incoming operators; it is ready when all of them are done (section 2.1). */
+int purine_graph_add_tensor(purine_graph* g, const purine_tensor* t, const char* name);
+
+/* Adds an operator vertex with edges in_ids -> op -> out_ids (edges only ever join a tensor and an
+ * operator, section 2). thread_id >= 0: operators with the same id are issued in order on one
+ * HIP stream; different ids may overlap (section 3). attrs may be NULL for kinds that need none.
+ * Returns the operator id (>= 0) or a negative status (bad ids, wrong arity for the kind). */
+int purine_graph_add_op(purine_graph* g, int op_kind, const purine_op_attrs* attrs,
+                        const int* in_ids, int n_in, const int* out_ids, int n_out, int thread_id);
+
+/* Binds a thread id to a caller-owned hipStream_t (otherwise the graph creates one on first use). */
+int purine_graph_set_stream(purine_graph* g, int thread_id, void* hip_stream);
+
+/* Checks the graph without running it: acyclic; every tensor with no incoming operator is a source
+ * (ready at start); any two operators that touch overlapping storage, at least one of them
+ * writing, are ordered by a path in the graph. PURINE_E_GRAPH otherwise. */
+int purine_graph_validate(purine_graph* g);
+
+/* Runs the graph once (section 2.1): starts from the source tensors, fires an operator when all its
+ * incoming tensors are ready, marks a tensor ready when all its incoming operators have been
+ * issued (stream order plus events carry the readiness onto the device), and returns when every
+ * sink has been reached and the device work behind it has completed - the synchronisation point
+ * that lets graphs be iterated (section 2.2). Work the caller enqueued earlier on other streams
+ * must have completed before the call. A graph that cannot reach its sinks returns
+ * PURINE_E_GRAPH instead of hanging. The first operator error aborts the run and is returned. */
+int purine_graph_run(purine_graph* g);
+
+/* Firing order of the last run: writes up to cap operator ids, returns how many operators fired. */
+int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap);
+int purine_graph_num_ops(const purine_graph* g);
+int purine_graph_num_tensors(const purine_graph* g);
+
+/* Test hook (host only): n / d computed with the multiply-and-shift reciprocal that the kernels'
+ * index arithmetic uses; valid for 0 <= n < 2^31 and 1 <= d < 2^31. */
+uint32_t purine_debug_fastdiv(uint32_t n, uint32_t d);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PURINE_H */

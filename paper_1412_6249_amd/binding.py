@@ -1,0 +1,344 @@
+"""Thin ctypes binding over libpurine_conv.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (see include/purine.h). Tensors are
+torch tensors that live on the GPU (PyTorch supplies device memory and streams, nothing else);
+each call raises PurineError on a non-zero status. There is no fallback path: if the shared
+library is missing, importing this module fails.
+"""
+import ctypes
+import os
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libpurine_conv.so")
+
+PURINE_F32, PURINE_BF16, PURINE_I32 = 0, 1, 2
+PURINE_CONV_FWD, PURINE_CONV_BWD_DATA, PURINE_CONV_BWD_WEIGHT = 0, 1, 2
+
+OP_CONV_FWD, OP_BIAS_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_BIAS_BWD = 0, 1, 2, 3, 4
+OP_RELU_FWD, OP_RELU_BWD, OP_MAXPOOL_FWD, OP_MAXPOOL_BWD = 5, 6, 7, 8
+OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
+
+STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
+          -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
+          -7: "PURINE_E_HIP", -8: "PURINE_E_ARG"}
+
+
+class PurineError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = _lib.purine_status_string(status).decode()
+        super().__init__("%s: %s (%s)" % (where, STATUS.get(status, status), msg))
+
+
+class purine_tensor(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("ndim", ctypes.c_int32),
+                ("dim", ctypes.c_int64 * 4)]
+
+
+class purine_conv_desc(ctypes.Structure):
+    _fields_ = [("stride_h", ctypes.c_int32), ("stride_w", ctypes.c_int32),
+                ("pad_h", ctypes.c_int32), ("pad_w", ctypes.c_int32)]
+
+
+class purine_pool_desc(ctypes.Structure):
+    _fields_ = [("window", ctypes.c_int32), ("stride", ctypes.c_int32), ("pad", ctypes.c_int32)]
+
+
+class purine_op_attrs(ctypes.Structure):
+    _fields_ = [("conv", purine_conv_desc), ("pool", purine_pool_desc), ("beta", ctypes.c_float),
+                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libpurine_conv.so is not built: run `python -c 'import __graft_entry__ as g; "
+                      "g.build()'` (or paper_1412_6249_amd/build.py) first")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_P = ctypes.POINTER
+_T, _D, _PD = _P(purine_tensor), _P(purine_conv_desc), _P(purine_pool_desc)
+_i64p, _vp, _sz, _ip = _P(ctypes.c_int64), ctypes.c_void_p, ctypes.c_size_t, _P(ctypes.c_int)
+
+_SIGS = {
+    "purine_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "purine_conv_out_shape": (ctypes.c_int, [_D, _i64p, _i64p, _i64p]),
+    "purine_conv_workspace_bytes": (_sz, [ctypes.c_int, _D, _i64p, _i64p, ctypes.c_int32]),
+    "purine_bias_bwd_workspace_bytes": (_sz, [_i64p, ctypes.c_int32]),
+    "purine_conv_fwd": (ctypes.c_int, [_D, _T, _T, _T, _vp, _sz, _vp]),
+    "purine_conv_bwd_data": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_conv_bwd_weight": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_bias_fwd": (ctypes.c_int, [_T, _T, _vp]),
+    "purine_bias_bwd": (ctypes.c_int, [_T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_relu_fwd": (ctypes.c_int, [_T, _T, _vp]),
+    "purine_relu_bwd": (ctypes.c_int, [_T, _T, _T, _vp]),
+    "purine_maxpool_fwd": (ctypes.c_int, [_PD, _T, _T, _T, _vp]),
+    "purine_maxpool_bwd": (ctypes.c_int, [_PD, _T, _T, _T, ctypes.c_float, _vp]),
+    "purine_concat_fwd": (ctypes.c_int, [_P(_T), ctypes.c_int, _T, _vp]),
+    "purine_concat_bwd": (ctypes.c_int, [_T, _P(_T), ctypes.c_int, _vp]),
+    "purine_sum": (ctypes.c_int, [_P(_T), ctypes.c_int, _T, _vp]),
+    "purine_graph_create": (_vp, []),
+    "purine_graph_destroy": (None, [_vp]),
+    "purine_graph_add_tensor": (ctypes.c_int, [_vp, _T, ctypes.c_char_p]),
+    "purine_graph_add_op": (ctypes.c_int, [_vp, ctypes.c_int, _P(purine_op_attrs), _ip, ctypes.c_int,
+                                           _ip, ctypes.c_int, ctypes.c_int]),
+    "purine_graph_set_stream": (ctypes.c_int, [_vp, ctypes.c_int, _vp]),
+    "purine_graph_validate": (ctypes.c_int, [_vp]),
+    "purine_graph_run": (ctypes.c_int, [_vp]),
+    "purine_graph_fire_log": (ctypes.c_int, [_vp, _ip, ctypes.c_int]),
+    "purine_graph_num_ops": (ctypes.c_int, [_vp]),
+    "purine_graph_num_tensors": (ctypes.c_int, [_vp]),
+    "purine_debug_fastdiv": (ctypes.c_uint32, [ctypes.c_uint32, ctypes.c_uint32]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(_lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+EXPORTED = sorted(_SIGS)
+
+
+# ------------------------------------------------------------------ marshalling helpers
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return PURINE_F32
+    if t.dtype == torch.bfloat16:
+        return PURINE_BF16
+    if t.dtype == torch.int32:
+        return PURINE_I32
+    raise TypeError("unsupported torch dtype %s" % t.dtype)
+
+
+def tensor_desc(t):
+    """purine_tensor for a contiguous CUDA torch tensor (or passes a ready-made descriptor through)."""
+    if isinstance(t, purine_tensor):
+        return t
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous (dense NCHW / KCRS)")
+    if t.dim() < 1 or t.dim() > 4:
+        raise ValueError("1 to 4 dimensions")
+    d = purine_tensor()
+    d.data = t.data_ptr()
+    d.dtype = _dtype_code(t)
+    d.ndim = t.dim()
+    for i, v in enumerate(t.shape):
+        d.dim[i] = int(v)
+    return d
+
+
+def raw_desc(data_ptr, dtype, dims):
+    """Descriptor from a raw pointer (tests of the error paths, host-only graphs)."""
+    d = purine_tensor()
+    d.data = data_ptr
+    d.dtype = dtype
+    d.ndim = len(dims)
+    for i, v in enumerate(dims):
+        d.dim[i] = int(v)
+    return d
+
+
+def conv_desc(stride=1, pad=0):
+    sh, sw = (stride, stride) if isinstance(stride, int) else stride
+    ph, pw = (pad, pad) if isinstance(pad, int) else pad
+    return purine_conv_desc(int(sh), int(sw), int(ph), int(pw))
+
+
+def pool_desc(window, stride, pad=0):
+    return purine_pool_desc(int(window), int(stride), int(pad))
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _dims(shape):
+    return (ctypes.c_int64 * 4)(*[int(v) for v in shape])
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise PurineError(rc, where)
+
+
+def _ref(x):
+    return ctypes.byref(x)
+
+
+# ------------------------------------------------------------------ host-only entry points
+def purine_status_string(status):
+    return _lib.purine_status_string(int(status)).decode()
+
+
+def purine_conv_out_shape(desc, x_shape, w_shape):
+    out = (ctypes.c_int64 * 4)()
+    _check(_lib.purine_conv_out_shape(_ref(desc), _dims(x_shape), _dims(w_shape), out),
+           "purine_conv_out_shape")
+    return tuple(int(v) for v in out)
+
+
+def purine_conv_workspace_bytes(which, desc, x_shape, w_shape, dtype):
+    return int(_lib.purine_conv_workspace_bytes(int(which), _ref(desc), _dims(x_shape),
+                                                _dims(w_shape), int(dtype)))
+
+
+def purine_bias_bwd_workspace_bytes(dy_shape, dtype):
+    return int(_lib.purine_bias_bwd_workspace_bytes(_dims(dy_shape), int(dtype)))
+
+
+def purine_debug_fastdiv(n, d):
+    return int(_lib.purine_debug_fastdiv(int(n), int(d)))
+
+
+# ------------------------------------------------------------------ operators
+def purine_conv_fwd(desc, x, w, y, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_conv_fwd(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(w)),
+                                _ref(tensor_desc(y)), p, n, _stream(stream)), "purine_conv_fwd")
+
+
+def purine_conv_bwd_data(desc, dy, w, dx, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_conv_bwd_data(_ref(desc), _ref(tensor_desc(dy)), _ref(tensor_desc(w)),
+                                     _ref(tensor_desc(dx)), float(beta), p, n, _stream(stream)),
+           "purine_conv_bwd_data")
+
+
+def purine_conv_bwd_weight(desc, x, dy, dw, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_conv_bwd_weight(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
+                                       _ref(tensor_desc(dw)), float(beta), p, n, _stream(stream)),
+           "purine_conv_bwd_weight")
+
+
+def purine_bias_fwd(b, y, stream=None):
+    _check(_lib.purine_bias_fwd(_ref(tensor_desc(b)), _ref(tensor_desc(y)), _stream(stream)),
+           "purine_bias_fwd")
+
+
+def purine_bias_bwd(dy, db, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_bias_bwd(_ref(tensor_desc(dy)), _ref(tensor_desc(db)), float(beta), p, n,
+                                _stream(stream)), "purine_bias_bwd")
+
+
+def purine_relu_fwd(x, y, stream=None):
+    _check(_lib.purine_relu_fwd(_ref(tensor_desc(x)), _ref(tensor_desc(y)), _stream(stream)),
+           "purine_relu_fwd")
+
+
+def purine_relu_bwd(x, dy, dx, stream=None):
+    _check(_lib.purine_relu_bwd(_ref(tensor_desc(x)), _ref(tensor_desc(dy)), _ref(tensor_desc(dx)),
+                                _stream(stream)), "purine_relu_bwd")
+
+
+def purine_maxpool_fwd(desc, x, y, arg, stream=None):
+    _check(_lib.purine_maxpool_fwd(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(y)),
+                                   _ref(tensor_desc(arg)), _stream(stream)), "purine_maxpool_fwd")
+
+
+def purine_maxpool_bwd(desc, dy, arg, dx, beta=0.0, stream=None):
+    _check(_lib.purine_maxpool_bwd(_ref(desc), _ref(tensor_desc(dy)), _ref(tensor_desc(arg)),
+                                   _ref(tensor_desc(dx)), float(beta), _stream(stream)),
+           "purine_maxpool_bwd")
+
+
+def _tensor_ptr_array(tensors):
+    descs = [tensor_desc(t) for t in tensors]
+    arr = (_T * len(descs))(*[ctypes.pointer(d) for d in descs])
+    return arr, descs
+
+
+def purine_concat_fwd(parts, out, stream=None):
+    arr, keep = _tensor_ptr_array(parts)
+    _check(_lib.purine_concat_fwd(arr, len(keep), _ref(tensor_desc(out)), _stream(stream)),
+           "purine_concat_fwd")
+
+
+def purine_concat_bwd(dout, dparts, stream=None):
+    arr, keep = _tensor_ptr_array(dparts)
+    _check(_lib.purine_concat_bwd(_ref(tensor_desc(dout)), arr, len(keep), _stream(stream)),
+           "purine_concat_bwd")
+
+
+def purine_sum(terms, out, stream=None):
+    arr, keep = _tensor_ptr_array(terms)
+    _check(_lib.purine_sum(arr, len(keep), _ref(tensor_desc(out)), _stream(stream)), "purine_sum")
+
+
+# ------------------------------------------------------------------ bi-graph executor
+def purine_graph_create():
+    g = _lib.purine_graph_create()
+    if not g:
+        raise MemoryError("purine_graph_create")
+    return g
+
+
+def purine_graph_destroy(g):
+    _lib.purine_graph_destroy(g)
+
+
+def purine_graph_add_tensor(g, t, name=None):
+    rc = _lib.purine_graph_add_tensor(g, _ref(tensor_desc(t)), name.encode() if name else None)
+    if rc < 0:
+        raise PurineError(rc, "purine_graph_add_tensor")
+    return rc
+
+
+def purine_graph_add_op(g, kind, in_ids, out_ids, thread_id=0, attrs=None):
+    ins = (ctypes.c_int * max(1, len(in_ids)))(*in_ids)
+    outs = (ctypes.c_int * max(1, len(out_ids)))(*out_ids)
+    rc = _lib.purine_graph_add_op(g, int(kind), _ref(attrs) if attrs is not None else None, ins,
+                                  len(in_ids), outs, len(out_ids), int(thread_id))
+    if rc < 0:
+        raise PurineError(rc, "purine_graph_add_op")
+    return rc
+
+
+def op_attrs(conv=None, pool=None, beta=0.0, ws=None):
+    a = purine_op_attrs()
+    if conv is not None:
+        a.conv = conv
+    if pool is not None:
+        a.pool = pool
+    a.beta = float(beta)
+    p, n = _ws(ws)
+    a.ws = p
+    a.ws_bytes = n
+    return a
+
+
+def purine_graph_set_stream(g, thread_id, stream):
+    _check(_lib.purine_graph_set_stream(g, int(thread_id), getattr(stream, "cuda_stream", stream)),
+           "purine_graph_set_stream")
+
+
+def purine_graph_validate(g):
+    _check(_lib.purine_graph_validate(g), "purine_graph_validate")
+
+
+def purine_graph_run(g):
+    _check(_lib.purine_graph_run(g), "purine_graph_run")
+
+
+def purine_graph_fire_log(g):
+    n = _lib.purine_graph_num_ops(g)
+    buf = (ctypes.c_int * max(1, n))()
+    fired = _lib.purine_graph_fire_log(g, buf, n)
+    return [int(buf[i]) for i in range(min(n, fired))]
+
+
+def purine_graph_num_ops(g):
+    return int(_lib.purine_graph_num_ops(g))
+
+
+def purine_graph_num_tensors(g):
+    return int(_lib.purine_graph_num_tensors(g))

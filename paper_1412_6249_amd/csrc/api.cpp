@@ -1,0 +1,365 @@
+// Host side of the C ABI: argument validation, shape bookkeeping and kernel dispatch.
+// Every check happens before the first launch, so an error never leaves work half enqueued.
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+using namespace purine;
+
+namespace {
+
+int64_t numel(const purine_tensor* t) {
+    int64_t n = 1;
+    for (int i = 0; i < t->ndim; ++i) n *= t->dim[i];
+    return n;
+}
+
+int check_tensor(const purine_tensor* t, int ndim) {
+    if (!t) return PURINE_E_NULL;
+    if (!t->data) return PURINE_E_NULL;
+    if (t->ndim != ndim) return PURINE_E_SHAPE;
+    if (t->dtype != PURINE_F32 && t->dtype != PURINE_BF16 && t->dtype != PURINE_I32) return PURINE_E_DTYPE;
+    int64_t n = 1;
+    for (int i = 0; i < ndim; ++i) {
+        if (t->dim[i] < 1) return PURINE_E_SHAPE;
+        if (t->dim[i] >= (1ll << 31)) return PURINE_E_SHAPE;
+        n *= t->dim[i];
+        if (n >= (1ll << 31)) return PURINE_E_SHAPE;
+    }
+    if (((uintptr_t)t->data) & 15u) return PURINE_E_LAYOUT;
+    return PURINE_OK;
+}
+
+bool is_float_dtype(int d) { return d == PURINE_F32 || d == PURINE_BF16; }
+size_t elem_bytes(int d) { return d == PURINE_BF16 ? 2 : 4; }
+
+bool overlaps(const purine_tensor* a, const purine_tensor* b) {
+    const uintptr_t a0 = (uintptr_t)a->data, a1 = a0 + (size_t)numel(a) * elem_bytes(a->dtype);
+    const uintptr_t b0 = (uintptr_t)b->data, b1 = b0 + (size_t)numel(b) * elem_bytes(b->dtype);
+    return a0 < b1 && b0 < a1;
+}
+
+bool same_dims(const purine_tensor* a, const purine_tensor* b) {
+    if (a->ndim != b->ndim) return false;
+    for (int i = 0; i < a->ndim; ++i)
+        if (a->dim[i] != b->dim[i]) return false;
+    return true;
+}
+
+int check_desc(const purine_conv_desc* d) {
+    if (!d) return PURINE_E_NULL;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return PURINE_E_ARG;
+    return PURINE_OK;
+}
+
+int check_beta(float beta) { return (beta == 0.0f || beta == 1.0f) ? PURINE_OK : PURINE_E_ARG; }
+
+// Fills g from (desc, x extents, w extents) and verifies y extents when given.
+int make_geom(const purine_conv_desc* d, const int64_t* xd, const int64_t* wd, const int64_t* yd,
+              ConvGeom* g) {
+    int64_t out[4];
+    int rc = purine_conv_out_shape(d, xd, wd, out);
+    if (rc != PURINE_OK) return rc;
+    if (yd)
+        for (int i = 0; i < 4; ++i)
+            if (yd[i] != out[i]) return PURINE_E_SHAPE;
+    // every extent and every index product used by the kernels must fit a signed 32-bit int
+    const int64_t lim = (1ll << 31) - 1;
+    if (xd[0] * xd[1] * xd[2] * xd[3] > lim || out[0] * out[1] * out[2] * out[3] > lim ||
+        wd[0] * wd[1] * wd[2] * wd[3] > lim)
+        return PURINE_E_SHAPE;
+    if (wd[2] > 0xffff || wd[3] > 0xffff) return PURINE_E_SHAPE;
+    g->N = (int)xd[0]; g->C = (int)xd[1]; g->H = (int)xd[2]; g->W = (int)xd[3];
+    g->K = (int)wd[0]; g->R = (int)wd[2]; g->S = (int)wd[3];
+    g->P = (int)out[2]; g->Q = (int)out[3];
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    // padded coordinates (h + pad, p*stride) also travel in 32-bit ints
+    if ((int64_t)g->H + 2ll * g->ph > lim / 4 || (int64_t)g->W + 2ll * g->pw > lim / 4) return PURINE_E_SHAPE;
+    return PURINE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* purine_status_string(int status) {
+    switch (status) {
+        case PURINE_OK: return "ok";
+        case PURINE_E_NULL: return "null pointer";
+        case PURINE_E_SHAPE: return "inconsistent, empty or too large shape";
+        case PURINE_E_DTYPE: return "unsupported dtype";
+        case PURINE_E_LAYOUT: return "misaligned pointer or illegal aliasing";
+        case PURINE_E_WORKSPACE: return "workspace missing or too small";
+        case PURINE_E_GRAPH: return "not a legal bi-graph";
+        case PURINE_E_HIP: return "HIP runtime error";
+        case PURINE_E_ARG: return "scalar argument out of range";
+        default: return "unknown status";
+    }
+}
+
+int purine_conv_out_shape(const purine_conv_desc* desc, const int64_t x_dim[4],
+                          const int64_t w_dim[4], int64_t y_dim[4]) {
+    if (!desc || !x_dim || !w_dim || !y_dim) return PURINE_E_NULL;
+    int rc = check_desc(desc);
+    if (rc != PURINE_OK) return rc;
+    for (int i = 0; i < 4; ++i)
+        if (x_dim[i] < 1 || w_dim[i] < 1 || x_dim[i] >= (1ll << 31) || w_dim[i] >= (1ll << 31))
+            return PURINE_E_SHAPE;
+    if (x_dim[1] != w_dim[1]) return PURINE_E_SHAPE;
+    const int64_t eh = x_dim[2] + 2ll * desc->pad_h - w_dim[2];
+    const int64_t ew = x_dim[3] + 2ll * desc->pad_w - w_dim[3];
+    if (eh < 0 || ew < 0) return PURINE_E_SHAPE;
+    y_dim[0] = x_dim[0];
+    y_dim[1] = w_dim[0];
+    y_dim[2] = eh / desc->stride_h + 1;
+    y_dim[3] = ew / desc->stride_w + 1;
+    return PURINE_OK;
+}
+
+size_t purine_conv_workspace_bytes(int pass, const purine_conv_desc* desc, const int64_t x_dim[4],
+                                   const int64_t w_dim[4], int32_t dtype) {
+    if (pass != PURINE_CONV_BWD_WEIGHT) return 0;
+    if (!desc || !x_dim || !w_dim || !is_float_dtype(dtype)) return 0;
+    ConvGeom g;
+    if (make_geom(desc, x_dim, w_dim, nullptr, &g) != PURINE_OK) return 0;
+    return plan_wgrad(g, dtype).ws_bytes;
+}
+
+size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype) {
+    if (!dy_dim || !is_float_dtype(dtype)) return 0;
+    for (int i = 0; i < 4; ++i)
+        if (dy_dim[i] < 1 || dy_dim[i] >= (1ll << 31)) return 0;
+    if (dy_dim[0] * dy_dim[1] * dy_dim[2] * dy_dim[3] >= (1ll << 31)) return 0;
+    return plan_bias_bwd((int)dy_dim[0], (int)dy_dim[1], (int)(dy_dim[2] * dy_dim[3])).ws_bytes;
+}
+
+int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
+                    purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream) {
+    (void)ws; (void)ws_bytes;
+    int rc;
+    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(w, 4)) ||
+        (rc = check_tensor(y, 4)))
+        return rc;
+    if (!is_float_dtype(x->dtype) || w->dtype != x->dtype || y->dtype != x->dtype) return PURINE_E_DTYPE;
+    ConvGeom g;
+    if ((rc = make_geom(desc, x->dim, w->dim, y->dim, &g))) return rc;
+    if (overlaps(y, x) || overlaps(y, w)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_conv_pix(false, x->dtype, g, x->data, w->data, y->data, 0.0f,
+                                   (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
+                         const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
+                         size_t ws_bytes, void* hip_stream) {
+    (void)ws; (void)ws_bytes;
+    int rc;
+    if ((rc = check_desc(desc)) || (rc = check_tensor(dy, 4)) || (rc = check_tensor(w, 4)) ||
+        (rc = check_tensor(dx, 4)) || (rc = check_beta(beta)))
+        return rc;
+    if (!is_float_dtype(dy->dtype) || w->dtype != dy->dtype || dx->dtype != dy->dtype) return PURINE_E_DTYPE;
+    ConvGeom g;
+    if ((rc = make_geom(desc, dx->dim, w->dim, dy->dim, &g))) return rc;
+    if (overlaps(dx, dy) || overlaps(dx, w)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_conv_pix(true, dy->dtype, g, dy->data, w->data, dx->data, beta,
+                                   (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
+                           const purine_tensor* dy, purine_tensor* dw, float beta, void* ws,
+                           size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(dy, 4)) ||
+        (rc = check_tensor(dw, 4)) || (rc = check_beta(beta)))
+        return rc;
+    if (!is_float_dtype(x->dtype) || dy->dtype != x->dtype || dw->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    ConvGeom g;
+    if ((rc = make_geom(desc, x->dim, dw->dim, dy->dim, &g))) return rc;
+    if (overlaps(dw, x) || overlaps(dw, dy)) return PURINE_E_LAYOUT;
+    const WgradPlan plan = plan_wgrad(g, x->dtype);
+    if (!ws || ws_bytes < plan.ws_bytes) return PURINE_E_WORKSPACE;
+    if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+    hipError_t e = launch_conv_wgrad(x->dtype, g, plan, x->data, dy->data, (float*)dw->data, beta, ws,
+                                     (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_bias_fwd(const purine_tensor* b, purine_tensor* y, void* hip_stream) {
+    int rc;
+    if ((rc = check_tensor(b, 1)) || (rc = check_tensor(y, 4))) return rc;
+    if (!is_float_dtype(y->dtype) || b->dtype != y->dtype) return PURINE_E_DTYPE;
+    if (b->dim[0] != y->dim[1]) return PURINE_E_SHAPE;
+    if (overlaps(b, y)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_bias_fwd(y->dtype, b->data, y->data, (int)y->dim[0], (int)y->dim[1],
+                                   (int)(y->dim[2] * y->dim[3]), (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_bias_bwd(const purine_tensor* dy, purine_tensor* db, float beta, void* ws,
+                    size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_tensor(dy, 4)) || (rc = check_tensor(db, 1)) || (rc = check_beta(beta))) return rc;
+    if (!is_float_dtype(dy->dtype) || db->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    if (db->dim[0] != dy->dim[1]) return PURINE_E_SHAPE;
+    if (overlaps(db, dy)) return PURINE_E_LAYOUT;
+    const int N = (int)dy->dim[0], K = (int)dy->dim[1], PQ = (int)(dy->dim[2] * dy->dim[3]);
+    const BiasBwdPlan plan = plan_bias_bwd(N, K, PQ);
+    if (!ws || ws_bytes < plan.ws_bytes) return PURINE_E_WORKSPACE;
+    if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+    hipError_t e = launch_bias_bwd(dy->dtype, dy->data, (float*)db->data, beta, N, K, PQ, plan, ws,
+                                   (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_relu_fwd(const purine_tensor* x, purine_tensor* y, void* hip_stream) {
+    int rc;
+    if (!x || !y) return PURINE_E_NULL;
+    if ((rc = check_tensor(x, x->ndim >= 1 && x->ndim <= 4 ? x->ndim : -1)) ||
+        (rc = check_tensor(y, x->ndim)))
+        return rc;
+    if (!is_float_dtype(x->dtype) || y->dtype != x->dtype) return PURINE_E_DTYPE;
+    if (!same_dims(x, y)) return PURINE_E_SHAPE;
+    if (x->data != y->data && overlaps(x, y)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_relu_fwd(x->dtype, x->data, y->data, numel(x), (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tensor* dx,
+                    void* hip_stream) {
+    int rc;
+    if (!x || !dy || !dx) return PURINE_E_NULL;
+    if ((rc = check_tensor(x, x->ndim >= 1 && x->ndim <= 4 ? x->ndim : -1)) ||
+        (rc = check_tensor(dy, x->ndim)) || (rc = check_tensor(dx, x->ndim)))
+        return rc;
+    if (!is_float_dtype(x->dtype) || dy->dtype != x->dtype || dx->dtype != x->dtype) return PURINE_E_DTYPE;
+    if (!same_dims(x, dy) || !same_dims(x, dx)) return PURINE_E_SHAPE;
+    if (overlaps(dx, x)) return PURINE_E_LAYOUT;
+    if (dx->data != dy->data && overlaps(dx, dy)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_relu_bwd(x->dtype, x->data, dy->data, dx->data, numel(x),
+                                   (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+static int pool_geom(const purine_pool_desc* d, const purine_tensor* x, const purine_tensor* y) {
+    if (!d) return PURINE_E_NULL;
+    if (d->window < 1 || d->stride < 1 || d->pad < 0 || d->pad >= d->window) return PURINE_E_ARG;
+    for (int ax = 2; ax < 4; ++ax) {
+        const int64_t e = x->dim[ax] + 2ll * d->pad - d->window;
+        if (e < 0) return PURINE_E_SHAPE;
+        if (y->dim[ax] != e / d->stride + 1) return PURINE_E_SHAPE;
+    }
+    if (y->dim[0] != x->dim[0] || y->dim[1] != x->dim[1]) return PURINE_E_SHAPE;
+    if (x->dim[0] * x->dim[1] >= (1ll << 31)) return PURINE_E_SHAPE;
+    return PURINE_OK;
+}
+
+int purine_maxpool_fwd(const purine_pool_desc* desc, const purine_tensor* x, purine_tensor* y,
+                       purine_tensor* arg, void* hip_stream) {
+    int rc;
+    if ((rc = check_tensor(x, 4)) || (rc = check_tensor(y, 4)) || (rc = check_tensor(arg, 4))) return rc;
+    if (!is_float_dtype(x->dtype) || y->dtype != x->dtype || arg->dtype != PURINE_I32) return PURINE_E_DTYPE;
+    if ((rc = pool_geom(desc, x, y))) return rc;
+    if (!same_dims(y, arg)) return PURINE_E_SHAPE;
+    if (overlaps(y, x) || overlaps(arg, x) || overlaps(arg, y)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_maxpool_fwd(x->dtype, x->data, y->data, (int32_t*)arg->data,
+                                      (int)(x->dim[0] * x->dim[1]), (int)x->dim[2], (int)x->dim[3],
+                                      (int)y->dim[2], (int)y->dim[3], desc->window, desc->stride,
+                                      desc->pad, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_maxpool_bwd(const purine_pool_desc* desc, const purine_tensor* dy,
+                       const purine_tensor* arg, purine_tensor* dx, float beta, void* hip_stream) {
+    int rc;
+    if ((rc = check_tensor(dy, 4)) || (rc = check_tensor(arg, 4)) || (rc = check_tensor(dx, 4)) ||
+        (rc = check_beta(beta)))
+        return rc;
+    if (!is_float_dtype(dy->dtype) || dx->dtype != dy->dtype || arg->dtype != PURINE_I32) return PURINE_E_DTYPE;
+    if ((rc = pool_geom(desc, dx, dy))) return rc;
+    if (!same_dims(dy, arg)) return PURINE_E_SHAPE;
+    if (overlaps(dx, dy) || overlaps(dx, arg)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_maxpool_bwd(dy->dtype, dy->data, (const int32_t*)arg->data, dx->data, beta,
+                                      (int)(dx->dim[0] * dx->dim[1]), (int)dx->dim[2],
+                                      (int)dx->dim[3], (int)dy->dim[2], (int)dy->dim[3],
+                                      desc->window, desc->stride, desc->pad, (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+static int concat_check(const purine_tensor* const* parts, int n_parts, const purine_tensor* whole) {
+    if (!parts || !whole) return PURINE_E_NULL;
+    if (n_parts < 1 || n_parts > 64) return PURINE_E_ARG;
+    int rc = check_tensor(whole, 4);
+    if (rc) return rc;
+    if (!is_float_dtype(whole->dtype)) return PURINE_E_DTYPE;
+    if (whole->dim[0] > 65535) return PURINE_E_SHAPE;
+    int64_t c = 0;
+    for (int i = 0; i < n_parts; ++i) {
+        if ((rc = check_tensor(parts[i], 4))) return rc;
+        if (parts[i]->dtype != whole->dtype) return PURINE_E_DTYPE;
+        if (parts[i]->dim[0] != whole->dim[0] || parts[i]->dim[2] != whole->dim[2] ||
+            parts[i]->dim[3] != whole->dim[3])
+            return PURINE_E_SHAPE;
+        if (overlaps(parts[i], whole)) return PURINE_E_LAYOUT;
+        c += parts[i]->dim[1];
+    }
+    return c == whole->dim[1] ? PURINE_OK : PURINE_E_SHAPE;
+}
+
+int purine_concat_fwd(const purine_tensor* const* parts, int n_parts, purine_tensor* out,
+                      void* hip_stream) {
+    int rc = concat_check(parts, n_parts, out);
+    if (rc) return rc;
+    int c0 = 0;
+    const int HW = (int)(out->dim[2] * out->dim[3]);
+    for (int i = 0; i < n_parts; ++i) {
+        const int c = (int)parts[i]->dim[1];
+        hipError_t e = launch_copy_channels(out->dtype, parts[i]->data, out->data, (int)out->dim[0], c,
+                                            c, 0, (int)out->dim[1], c0, HW, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return PURINE_E_HIP;
+        c0 += c;
+    }
+    return PURINE_OK;
+}
+
+int purine_concat_bwd(const purine_tensor* dout, purine_tensor* const* dparts, int n_parts,
+                      void* hip_stream) {
+    int rc = concat_check((const purine_tensor* const*)dparts, n_parts, dout);
+    if (rc) return rc;
+    int c0 = 0;
+    const int HW = (int)(dout->dim[2] * dout->dim[3]);
+    for (int i = 0; i < n_parts; ++i) {
+        const int c = (int)dparts[i]->dim[1];
+        hipError_t e = launch_copy_channels(dout->dtype, dout->data, dparts[i]->data, (int)dout->dim[0],
+                                            c, (int)dout->dim[1], c0, c, 0, HW, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return PURINE_E_HIP;
+        c0 += c;
+    }
+    return PURINE_OK;
+}
+
+int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* out, void* hip_stream) {
+    if (!terms || !out) return PURINE_E_NULL;
+    if (n_terms < 1 || n_terms > 8) return PURINE_E_ARG;
+    int rc;
+    if (out->ndim < 1 || out->ndim > 4) return PURINE_E_SHAPE;
+    if ((rc = check_tensor(out, out->ndim))) return rc;
+    if (!is_float_dtype(out->dtype)) return PURINE_E_DTYPE;
+    const void* ptrs[8];
+    for (int i = 0; i < n_terms; ++i) {
+        if ((rc = check_tensor(terms[i], out->ndim))) return rc;
+        if (terms[i]->dtype != out->dtype) return PURINE_E_DTYPE;
+        if (!same_dims(terms[i], out)) return PURINE_E_SHAPE;
+        if (terms[i]->data != out->data && overlaps(terms[i], out)) return PURINE_E_LAYOUT;
+        if (terms[i]->data == out->data && i != 0) return PURINE_E_LAYOUT;
+        ptrs[i] = terms[i]->data;
+    }
+    hipError_t e = launch_sum(out->dtype, ptrs, n_terms, out->data, numel(out), (hipStream_t)hip_stream);
+    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+// Test hook for the host-side reciprocal division used by the kernels' index arithmetic.
+uint32_t purine_debug_fastdiv(uint32_t n, uint32_t d) { return fastdiv(n, make_fastdiv(d)); }
+
+}  // extern "C"

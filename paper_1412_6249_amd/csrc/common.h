@@ -1,0 +1,109 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "purine.h"
+
+namespace purine {
+
+// Division of 0 <= n < 2^31 by a divisor fixed on the host, done with one high multiply and a
+// shift (round-up reciprocal: m = ceil(2^(32+s)/d) with s = ceil(log2 d) - 1 fits 32 bits, and the
+// error term n*e/2^(32+s) stays below 1/d for every n < 2^31).
+struct FastDiv {
+    uint32_t d, m, s;
+};
+
+inline FastDiv make_fastdiv(uint32_t d) {
+    FastDiv f{d, 0u, 0u};
+    if (d <= 1) { f.d = 1; return f; }
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;           // l = ceil(log2 d) >= 1
+    f.s = l - 1;
+    const unsigned __int128 one = 1;
+    const unsigned __int128 num = one << (32 + f.s);
+    f.m = (uint32_t)((num + d - 1) / d);
+    return f;
+}
+
+__host__ __device__ inline uint32_t fastdiv(uint32_t n, const FastDiv& f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return f.d == 1 ? n : (__umulhi(n, f.m) >> f.s);
+#else
+    return f.d == 1 ? n : (uint32_t)(((uint64_t)n * f.m) >> 32) >> f.s;
+#endif
+}
+
+// Problem description handed to the pixel-major implicit GEMM (forward and backward-data):
+//   out[n, i, ho, wo] = sum over kk = (ci, r, s) of A[i, kk] * gather(in)[kk, (n, ho, wo)]
+struct PixGemmParams {
+    const void* in;    // gathered activation tensor [N][Ci][Hi][Wi]
+    const void* wt;    // filter tensor, always KCRS
+    void* out;         // produced tensor [N][Co][Ho][Wo]
+    int N, Ci, Hi, Wi;
+    int Co, Ho, Wo;
+    int R, S, sh, sw, ph, pw;
+    int RS, Kg, M;               // Kg = Ci*R*S (reduction length), M = N*Ho*Wo (pixels)
+    int a_ci_stride, a_i_stride; // filter element of (i, ci, rs) sits at ci*a_ci_stride + i*a_i_stride + rs
+    int HiWi, HoWo;
+    FastDiv div_rs, div_s, div_howo, div_wo, div_sh, div_sw;
+    float beta;
+    int tiles_i, tiles_pix;
+};
+
+// Problem description of the weight-gradient implicit GEMM:
+//   partial[split][k][(c,r,s)] = sum over pixels (n,p,q) of the split of dy[n,k,p,q] * x[n,c,p*sh-ph+r,q*sw-pw+s]
+struct WgradParams {
+    const void* x;
+    const void* dy;
+    float* out;        // partial sums [splits][K][CRS], or dw itself when splits == 1 and beta == 0
+    int N, C, H, W, K, P, Q, R, S, sh, sw, ph, pw;
+    int PQ, M, CRS, RS, HW;
+    FastDiv div_pq, div_q, div_rs, div_s;
+    int chunk;         // pixels per split, a multiple of the slab depth
+    int tiles_i, tiles_j, splits;
+};
+
+struct ConvGeom {
+    int N, C, H, W, K, R, S, P, Q, sh, sw, ph, pw;
+};
+
+// Split of the pixel reduction of the weight gradient: same answer for the workspace query and
+// for the launch.
+struct WgradPlan {
+    int bm, bn;        // tile extents along k and along (c,r,s)
+    int tiles_i, tiles_j, splits, chunk;
+    size_t ws_bytes;
+};
+WgradPlan plan_wgrad(const ConvGeom& g, int dtype);
+
+struct BiasBwdPlan {
+    int parts;         // image groups per channel
+    int imgs_per_part;
+    size_t ws_bytes;
+};
+BiasBwdPlan plan_bias_bwd(int N, int K, int PQ);
+
+// Kernel launchers (defined in the .hip files). Each returns a hipError_t from the launch.
+hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
+                           const void* wt, void* out, float beta, hipStream_t st);
+hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
+                             const void* dy, float* dw, float beta, void* ws, hipStream_t st);
+hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st);
+hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int N, int K, int PQ,
+                           const BiasBwdPlan& plan, void* ws, hipStream_t st);
+hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st);
+hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
+                           hipStream_t st);
+hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,
+                              int P, int Q, int k, int stride, int pad, hipStream_t st);
+hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, float beta,
+                              int NC, int H, int W, int P, int Q, int k, int stride, int pad,
+                              hipStream_t st);
+hipError_t launch_copy_channels(int dtype, const void* src, void* dst, int N, int c_count,
+                                int src_C, int src_c0, int dst_C, int dst_c0, int HW,
+                                hipStream_t st);
+hipError_t launch_sum(int dtype, const void* const* terms, int n_terms, void* out, int64_t n,
+                      hipStream_t st);
+
+}  // namespace purine

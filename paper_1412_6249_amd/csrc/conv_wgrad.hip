@@ -1,0 +1,247 @@
+// Weight-gradient implicit GEMM for gfx950 (the ConvBwdWeight operator of paper Figure 1(b)).
+//
+//     dw[k, (c,r,s)] = sum over pixels (n,p,q) of dy[n,k,p,q] * x[n,c,p*sh-ph+r,q*sw-pw+s]
+//
+// The reduction runs over all N*P*Q pixels while the output is tiny, so the pixel range is cut
+// into `splits` chunks. Workgroup (tile, split) reduces its chunk on the fp32 MFMA units and
+// writes an fp32 partial tile to scratch; a second kernel adds the partials in chunk order
+// (fixed order: bit-identical run to run, no atomics). The split also bounds the length of any
+// single fp32 accumulation chain, which the 1e-5 accuracy target needs for 10^5..10^6 pixels.
+// Neither operand is materialised: both slabs are built in LDS from the NCHW tensors with lanes
+// running along pixels.
+#include "common.h"
+
+namespace purine {
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;  // pixels per slab
+
+template <typename T> __device__ __forceinline__ float ld(const T* p, int i);
+template <> __device__ __forceinline__ float ld<float>(const float* p, int i) { return p[i]; }
+template <> __device__ __forceinline__ float ld<uint16_t>(const uint16_t* p, int i) {
+    return __uint_as_float(((uint32_t)p[i]) << 16);
+}
+
+template <typename T, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = WM * TM * 32;   // output channels k
+    constexpr int BN = WN * TN * 32;   // filter taps (c,r,s)
+    constexpr int LDA = BM + 2, LDB = BN + 2;
+    constexpr int RPP = NT / BK;       // tile columns covered per pass (lanes 0..15 run along pixels)
+    constexpr int A_PASSES = BM / RPP, B_PASSES = BN / RPP;
+    static_assert(BM % RPP == 0 && BN % RPP == 0, "mapping");
+
+    __shared__ float As[2][BK * LDA];
+    __shared__ float Bs[2][BK * LDB];
+
+    const T* __restrict__ x = (const T*)p.x;
+    const T* __restrict__ dy = (const T*)p.dy;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    int bid = blockIdx.x;
+    const int split = bid / (p.tiles_i * p.tiles_j);
+    bid -= split * p.tiles_i * p.tiles_j;
+    const int i0 = (bid % p.tiles_i) * BM;
+    const int j0 = (bid / p.tiles_i) * BN;
+    const int pix_begin = split * p.chunk;
+    const int pix_end = min(p.M, pix_begin + p.chunk);
+
+    const int t_kk = tid % BK;   // this thread's pixel inside a slab
+    const int t_col = tid / BK;  // first tile column it serves
+
+    // taps served by this thread: fixed for the whole kernel
+    int j_off[B_PASSES], j_rs[B_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < B_PASSES; ++ps) {
+        const int j = j0 + t_col + ps * RPP;
+        if (j < p.CRS) {
+            const int c = fastdiv(j, p.div_rs);
+            const int rs = j - c * p.RS;
+            const int r = fastdiv(rs, p.div_s);
+            const int s = rs - r * p.S;
+            j_off[ps] = c * p.HW + r * p.W + s;
+            j_rs[ps] = (r << 16) | s;
+        } else {
+            j_off[ps] = 0;
+            j_rs[ps] = -1;
+        }
+    }
+
+    float a_reg[A_PASSES], b_reg[B_PASSES];
+
+    auto load_slab = [&](int slab) {
+        const int pix = pix_begin + slab * BK + t_kk;
+        const bool pv = pix < pix_end;
+        const int pc = pv ? pix : 0;
+        const int n = fastdiv(pc, p.div_pq);
+        const int pq = pc - n * p.PQ;
+        const int pp = fastdiv(pq, p.div_q);
+        const int qq = pq - pp * p.Q;
+        const int a_base = n * p.K * p.PQ + pq;
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) {
+            const int i = i0 + t_col + ps * RPP;
+            a_reg[ps] = (pv && i < p.K) ? ld<T>(dy, a_base + i * p.PQ) : 0.0f;
+        }
+        const int hb = pp * p.sh - p.ph, wb = qq * p.sw - p.pw;
+        const int b_base = n * p.C * p.HW + hb * p.W + wb;
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps) {
+            const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
+            const bool ok = pv && j_rs[ps] >= 0 && (unsigned)(hb + r) < (unsigned)p.H &&
+                            (unsigned)(wb + s) < (unsigned)p.W;
+            b_reg[ps] = ok ? ld<T>(x, b_base + j_off[ps]) : 0.0f;
+        }
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) As[buf][t_kk * LDA + t_col + ps * RPP] = a_reg[ps];
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps) Bs[buf][t_kk * LDB + t_col + ps * RPP] = b_reg[ps];
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
+    const int n_slabs = (pix_end - pix_begin + BK - 1) / BK;   // >= 0; zero slabs leave zeros
+    if (n_slabs > 0) {
+        load_slab(0);
+        store_slab(0);
+    }
+    __syncthreads();
+
+    const int a_off = wm * TM * 32 + (lane & 31);
+    const int b_off = wn * TN * 32 + (lane & 31);
+    const int khalf = lane >> 5;
+
+    for (int slab = 0; slab < n_slabs; ++slab) {
+        const int buf = slab & 1;
+        const bool more = slab + 1 < n_slabs;
+        if (more) load_slab(slab + 1);
+#pragma unroll
+        for (int ks = 0; ks < BK / 2; ++ks) {
+            const int row = 2 * ks + khalf;
+            float av[TM], bv[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) av[a] = As[buf][row * LDA + a_off + a * 32];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) bv[b] = Bs[buf][row * LDB + b_off + b * 32];
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+        }
+        if (more) store_slab(buf ^ 1);
+        __syncthreads();
+    }
+
+    float* __restrict__ out = p.out + (size_t)split * p.K * p.CRS;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int j = j0 + b_off + b * 32;
+        if (j >= p.CRS) continue;
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                if (i < p.K) out[(size_t)i * p.CRS + j] = acc[a][b][e];
+            }
+    }
+}
+
+// dw[i] = beta*dw[i] + partial[0][i] + partial[1][i] + ... in split order.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial,
+                                                           float* __restrict__ dw, int n,
+                                                           int splits, float beta) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float acc = beta != 0.0f ? dw[i] : 0.0f;
+    for (int s = 0; s < splits; ++s) acc += partial[(size_t)s * n + i];
+    dw[i] = acc;
+}
+
+template <typename T, int TM, int TN, int WM, int WN>
+hipError_t launch_tile(WgradParams& p, hipStream_t st) {
+    const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
+    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((wgrad_kernel<T, TM, TN, WM, WN>), dim3((unsigned)total), dim3(WM * WN * 64),
+                       0, st, p);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t dispatch(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+    if (plan.bm == 128 && plan.bn == 128) return launch_tile<T, 2, 2, 2, 2>(p, st);
+    if (plan.bm == 96 && plan.bn == 128) return launch_tile<T, 3, 1, 1, 4>(p, st);
+    if (plan.bm == 64 && plan.bn == 128) return launch_tile<T, 2, 1, 1, 4>(p, st);
+    if (plan.bm == 32 && plan.bn == 128) return launch_tile<T, 1, 1, 1, 4>(p, st);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
+    (void)dtype;
+    WgradPlan pl{};
+    const int cands[4] = {128, 96, 64, 32};
+    long long best = -1;
+    pl.bm = 32;
+    for (int c : cands) {
+        const long long padded = (long long)((g.K + c - 1) / c) * c;
+        if (best < 0 || padded < best) { best = padded; pl.bm = c; }
+    }
+    pl.bn = 128;
+    const long long M = (long long)g.N * g.P * g.Q;
+    const long long CRS = (long long)g.C * g.R * g.S;
+    pl.tiles_i = (g.K + pl.bm - 1) / pl.bm;
+    pl.tiles_j = (int)((CRS + pl.bn - 1) / pl.bn);
+    const long long tiles = (long long)pl.tiles_i * pl.tiles_j;
+    // enough workgroups to cover the 256 CUs a few times over, chunks no shorter than 128 pixels,
+    // and no longer than 8192 so that one fp32 accumulation chain stays short
+    long long splits = (1024 + tiles - 1) / tiles;
+    const long long max_splits = (M + 127) / 128;
+    const long long min_splits = (M + 8191) / 8192;
+    if (splits > max_splits) splits = max_splits;
+    if (splits < min_splits) splits = min_splits;
+    if (splits < 1) splits = 1;
+    long long chunk = (M + splits - 1) / splits;
+    chunk = (chunk + BK - 1) / BK * BK;
+    splits = (M + chunk - 1) / chunk;
+    pl.splits = (int)splits;
+    pl.chunk = (int)chunk;
+    pl.ws_bytes = (size_t)splits * (size_t)g.K * (size_t)CRS * sizeof(float);
+    return pl;
+}
+
+hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
+                             const void* dy, float* dw, float beta, void* ws, hipStream_t st) {
+    WgradParams p{};
+    p.x = x; p.dy = dy;
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.K = g.K; p.P = g.P; p.Q = g.Q;
+    p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+    p.PQ = g.P * g.Q; p.M = g.N * p.PQ; p.RS = g.R * g.S; p.CRS = g.C * p.RS; p.HW = g.H * g.W;
+    p.div_pq = make_fastdiv(p.PQ); p.div_q = make_fastdiv(g.Q);
+    p.div_rs = make_fastdiv(p.RS); p.div_s = make_fastdiv(g.S);
+    p.chunk = plan.chunk; p.tiles_i = plan.tiles_i; p.tiles_j = plan.tiles_j; p.splits = plan.splits;
+    p.out = (float*)ws;
+    hipError_t e = dtype == PURINE_F32 ? dispatch<float>(p, plan, st) : dispatch<uint16_t>(p, plan, st);
+    if (e != hipSuccess) return e;
+    const int n = g.K * p.CRS;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, st,
+                       (const float*)ws, dw, n, plan.splits, beta);
+    return hipGetLastError();
+}
+
+}  // namespace purine

@@ -1,0 +1,356 @@
+// Minimal single-GPU bi-graph executor.
+//
+// Paper section 2: a network is a directed bipartite graph of tensor and operator vertices; edges
+// only join a tensor and an operator. Section 2.1: an operator fires when all its incoming tensors
+// are ready, a tensor is ready when all its incoming operators have completed, the computation
+// starts at the sources and stops when all sinks are reached. Section 3: operators carry a
+// `thread` id - same id, same queue; different ids run in parallel where possible.
+//
+// On one GPU a `thread` is a HIP stream. Device work is asynchronous, so "completed" for the host
+// side bookkeeping means "issued on its stream": readiness is carried onto the device by stream
+// order inside a thread and by an event recorded after each operator that consumers on other
+// streams wait for. purine_graph_run returns only after the device work behind every sink has
+// finished, which is the synchronisation point that lets graphs be iterated (section 2.2).
+#include <deque>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace purine;
+
+struct purine_graph {
+    struct Tensor {
+        purine_tensor desc;
+        std::string name;
+        std::vector<int> writers;   // incoming operators
+        std::vector<int> readers;   // outgoing operators
+    };
+    struct Op {
+        int kind;
+        purine_op_attrs attrs;
+        std::vector<int> in, out;
+        int thread;
+        hipEvent_t done = nullptr;  // recorded after the operator on its stream (device ops only)
+    };
+    std::vector<Tensor> tensors;
+    std::vector<Op> ops;
+    std::map<int, hipStream_t> streams;        // thread id -> stream
+    std::map<int, bool> stream_owned;
+    std::vector<int> fire_log;
+    bool validated = false;
+    bool uses_device = false;
+};
+
+namespace {
+
+size_t tensor_bytes(const purine_tensor& t) {
+    size_t n = 1;
+    for (int i = 0; i < t.ndim; ++i) n *= (size_t)t.dim[i];
+    return n * (t.dtype == PURINE_BF16 ? 2 : 4);
+}
+
+struct Range { uintptr_t lo, hi; };
+bool hit(const Range& a, const Range& b) { return a.lo < b.hi && b.lo < a.hi; }
+
+bool arity_ok(int kind, int n_in, int n_out, float beta) {
+    const int extra = beta != 0.0f ? 1 : 0;
+    switch (kind) {
+        case PURINE_OP_CONV_FWD: return n_in == 2 && n_out == 1;
+        case PURINE_OP_BIAS_FWD: return n_in == 2 && n_out == 1;
+        case PURINE_OP_CONV_BWD_DATA: return n_in == 2 + extra && n_out == 1;
+        case PURINE_OP_CONV_BWD_WEIGHT: return n_in == 2 + extra && n_out == 1;
+        case PURINE_OP_BIAS_BWD: return n_in == 1 + extra && n_out == 1;
+        case PURINE_OP_RELU_FWD: return n_in == 1 && n_out == 1;
+        case PURINE_OP_RELU_BWD: return n_in == 2 && n_out == 1;
+        case PURINE_OP_MAXPOOL_FWD: return n_in == 1 && n_out == 2;
+        case PURINE_OP_MAXPOOL_BWD: return n_in == 2 + extra && n_out == 1;
+        case PURINE_OP_CONCAT_FWD: return n_in >= 1 && n_in <= 64 && n_out == 1;
+        case PURINE_OP_CONCAT_BWD: return n_in == 1 && n_out >= 1 && n_out <= 64;
+        case PURINE_OP_SUM: return n_in >= 1 && n_in <= 8 && n_out == 1;
+        case PURINE_OP_HOST_NOP: return n_in >= 0 && n_out >= 0;
+        default: return false;
+    }
+}
+
+hipStream_t stream_of(purine_graph* g, int thread, int* rc) {
+    auto it = g->streams.find(thread);
+    if (it != g->streams.end()) return it->second;
+    hipStream_t s = nullptr;
+    if (hipStreamCreateWithFlags(&s, hipStreamNonBlocking) != hipSuccess) { *rc = PURINE_E_HIP; return nullptr; }
+    g->streams[thread] = s;
+    g->stream_owned[thread] = true;
+    return s;
+}
+
+// Issues one device operator on `st`. Storage identity rules of the in-place forms are checked here.
+int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
+    auto T = [&](int id) -> purine_tensor* { return &g->tensors[id].desc; };
+    const purine_op_attrs& a = op.attrs;
+    switch (op.kind) {
+        case PURINE_OP_CONV_FWD:
+            return purine_conv_fwd(&a.conv, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.ws, a.ws_bytes, st);
+        case PURINE_OP_BIAS_FWD:
+            if (T(op.in[0])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_bias_fwd(T(op.in[1]), T(op.out[0]), st);
+        case PURINE_OP_CONV_BWD_DATA:
+            if (a.beta != 0.0f && T(op.in[2])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_conv_bwd_data(&a.conv, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_CONV_BWD_WEIGHT:
+            if (a.beta != 0.0f && T(op.in[2])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_conv_bwd_weight(&a.conv, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_BIAS_BWD:
+            if (a.beta != 0.0f && T(op.in[1])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_bias_bwd(T(op.in[0]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_RELU_FWD:
+            return purine_relu_fwd(T(op.in[0]), T(op.out[0]), st);
+        case PURINE_OP_RELU_BWD:
+            return purine_relu_bwd(T(op.in[0]), T(op.in[1]), T(op.out[0]), st);
+        case PURINE_OP_MAXPOOL_FWD:
+            return purine_maxpool_fwd(&a.pool, T(op.in[0]), T(op.out[0]), T(op.out[1]), st);
+        case PURINE_OP_MAXPOOL_BWD:
+            if (a.beta != 0.0f && T(op.in[2])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_maxpool_bwd(&a.pool, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.beta, st);
+        case PURINE_OP_CONCAT_FWD: {
+            std::vector<const purine_tensor*> parts;
+            for (int id : op.in) parts.push_back(T(id));
+            return purine_concat_fwd(parts.data(), (int)parts.size(), T(op.out[0]), st);
+        }
+        case PURINE_OP_CONCAT_BWD: {
+            std::vector<purine_tensor*> parts;
+            for (int id : op.out) parts.push_back(T(id));
+            return purine_concat_bwd(T(op.in[0]), parts.data(), (int)parts.size(), st);
+        }
+        case PURINE_OP_SUM: {
+            std::vector<const purine_tensor*> terms;
+            for (int id : op.in) terms.push_back(T(id));
+            return purine_sum(terms.data(), (int)terms.size(), T(op.out[0]), st);
+        }
+        default:
+            return PURINE_E_ARG;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+purine_graph* purine_graph_create(void) { return new (std::nothrow) purine_graph(); }
+
+void purine_graph_destroy(purine_graph* g) {
+    if (!g) return;
+    for (auto& op : g->ops)
+        if (op.done) (void)hipEventDestroy(op.done);
+    for (auto& kv : g->streams)
+        if (g->stream_owned[kv.first]) (void)hipStreamDestroy(kv.second);
+    delete g;
+}
+
+int purine_graph_add_tensor(purine_graph* g, const purine_tensor* t, const char* name) {
+    if (!g || !t) return PURINE_E_NULL;
+    if (t->ndim < 1 || t->ndim > 4) return PURINE_E_SHAPE;
+    for (int i = 0; i < t->ndim; ++i)
+        if (t->dim[i] < 1) return PURINE_E_SHAPE;
+    if (t->dtype != PURINE_F32 && t->dtype != PURINE_BF16 && t->dtype != PURINE_I32) return PURINE_E_DTYPE;
+    purine_graph::Tensor v;
+    v.desc = *t;
+    if (name) v.name = name;
+    g->tensors.push_back(v);
+    g->validated = false;
+    return (int)g->tensors.size() - 1;
+}
+
+int purine_graph_add_op(purine_graph* g, int op_kind, const purine_op_attrs* attrs,
+                        const int* in_ids, int n_in, const int* out_ids, int n_out, int thread_id) {
+    if (!g) return PURINE_E_NULL;
+    if (n_in < 0 || n_out < 0 || thread_id < 0) return PURINE_E_ARG;
+    if ((n_in > 0 && !in_ids) || (n_out > 0 && !out_ids)) return PURINE_E_NULL;
+    purine_graph::Op op;
+    op.kind = op_kind;
+    op.attrs = purine_op_attrs{};
+    if (attrs) op.attrs = *attrs;
+    if (!arity_ok(op_kind, n_in, n_out, op.attrs.beta)) return PURINE_E_ARG;
+    const int nt = (int)g->tensors.size();
+    for (int i = 0; i < n_in; ++i) {
+        if (in_ids[i] < 0 || in_ids[i] >= nt) return PURINE_E_ARG;
+        op.in.push_back(in_ids[i]);
+    }
+    for (int i = 0; i < n_out; ++i) {
+        if (out_ids[i] < 0 || out_ids[i] >= nt) return PURINE_E_ARG;
+        for (int j = 0; j < n_in; ++j)
+            if (in_ids[j] == out_ids[i]) return PURINE_E_GRAPH;   // a self loop through one vertex
+        for (int j = 0; j < i; ++j)
+            if (out_ids[j] == out_ids[i]) return PURINE_E_GRAPH;
+        op.out.push_back(out_ids[i]);
+    }
+    op.thread = thread_id;
+    const int id = (int)g->ops.size();
+    g->ops.push_back(op);
+    for (int t : g->ops[id].in) g->tensors[t].readers.push_back(id);
+    for (int t : g->ops[id].out) g->tensors[t].writers.push_back(id);
+    if (op_kind != PURINE_OP_HOST_NOP) g->uses_device = true;
+    g->validated = false;
+    return id;
+}
+
+int purine_graph_set_stream(purine_graph* g, int thread_id, void* hip_stream) {
+    if (!g) return PURINE_E_NULL;
+    if (thread_id < 0) return PURINE_E_ARG;
+    auto it = g->streams.find(thread_id);
+    if (it != g->streams.end() && g->stream_owned[thread_id]) (void)hipStreamDestroy(it->second);
+    g->streams[thread_id] = (hipStream_t)hip_stream;
+    g->stream_owned[thread_id] = false;
+    return PURINE_OK;
+}
+
+int purine_graph_validate(purine_graph* g) {
+    if (!g) return PURINE_E_NULL;
+    const int no = (int)g->ops.size();
+    // operator-level successor lists: a -> b when b reads a tensor that a writes
+    std::vector<std::vector<int>> succ(no);
+    std::vector<int> indeg(no, 0);
+    for (int a = 0; a < no; ++a)
+        for (int t : g->ops[a].out)
+            for (int b : g->tensors[t].readers) { succ[a].push_back(b); ++indeg[b]; }
+    // acyclic?  (Kahn)
+    std::vector<int> order;
+    {
+        std::vector<int> deg = indeg;
+        std::deque<int> q;
+        for (int a = 0; a < no; ++a) if (deg[a] == 0) q.push_back(a);
+        while (!q.empty()) {
+            int a = q.front(); q.pop_front();
+            order.push_back(a);
+            for (int b : succ[a]) if (--deg[b] == 0) q.push_back(b);
+        }
+        if ((int)order.size() != no) return PURINE_E_GRAPH;
+    }
+    // reach[a][b]: a path a -> ... -> b exists (bitsets, reverse topological sweep)
+    const int words = (no + 63) / 64;
+    std::vector<uint64_t> reach((size_t)no * words, 0);
+    for (int idx = no - 1; idx >= 0; --idx) {
+        const int a = order[idx];
+        uint64_t* ra = &reach[(size_t)a * words];
+        for (int b : succ[a]) {
+            ra[b / 64] |= 1ull << (b % 64);
+            const uint64_t* rb = &reach[(size_t)b * words];
+            for (int w = 0; w < words; ++w) ra[w] |= rb[w];
+        }
+    }
+    auto ordered = [&](int a, int b) {
+        return ((reach[(size_t)a * words + b / 64] >> (b % 64)) & 1) ||
+               ((reach[(size_t)b * words + a / 64] >> (a % 64)) & 1);
+    };
+    // storage hazards: a writer and any other toucher of overlapping bytes must be ordered
+    struct Touch { int op; Range r; bool write; };
+    std::vector<Touch> touches;
+    for (int a = 0; a < no; ++a) {
+        const auto& op = g->ops[a];
+        if (op.kind == PURINE_OP_HOST_NOP) continue;   // touches no device storage
+        for (int t : op.in) {
+            const auto& d = g->tensors[t].desc;
+            if (d.data) touches.push_back({a, {(uintptr_t)d.data, (uintptr_t)d.data + tensor_bytes(d)}, false});
+        }
+        for (int t : op.out) {
+            const auto& d = g->tensors[t].desc;
+            if (d.data) touches.push_back({a, {(uintptr_t)d.data, (uintptr_t)d.data + tensor_bytes(d)}, true});
+        }
+        if (op.attrs.ws && op.attrs.ws_bytes)
+            touches.push_back({a, {(uintptr_t)op.attrs.ws, (uintptr_t)op.attrs.ws + op.attrs.ws_bytes}, true});
+    }
+    for (size_t i = 0; i < touches.size(); ++i)
+        for (size_t j = i + 1; j < touches.size(); ++j) {
+            const Touch &x = touches[i], &y = touches[j];
+            if (x.op == y.op || !(x.write || y.write) || !hit(x.r, y.r)) continue;
+            if (!ordered(x.op, y.op)) return PURINE_E_GRAPH;
+        }
+    g->validated = true;
+    return PURINE_OK;
+}
+
+int purine_graph_run(purine_graph* g) {
+    if (!g) return PURINE_E_NULL;
+    if (!g->validated) {
+        int rc = purine_graph_validate(g);
+        if (rc != PURINE_OK) return rc;
+    }
+    const int no = (int)g->ops.size(), nt = (int)g->tensors.size();
+    g->fire_log.clear();
+    // dispatcher state (section 2.1)
+    std::vector<int> inputs_pending(no), writers_pending(nt);
+    for (int t = 0; t < nt; ++t) writers_pending[t] = (int)g->tensors[t].writers.size();
+    std::map<int, std::deque<int>> queues;      // thread id -> FIFO of operators ready to fire
+    auto enqueue_if_ready = [&](int o) { if (inputs_pending[o] == 0) queues[g->ops[o].thread].push_back(o); };
+    for (int o = 0; o < no; ++o) {
+        int pend = 0;
+        for (int t : g->ops[o].in) if (writers_pending[t] > 0) ++pend;
+        inputs_pending[o] = pend;
+    }
+    for (int o = 0; o < no; ++o) enqueue_if_ready(o);   // operators fed by source tensors only
+
+    int fired = 0, rc = PURINE_OK;
+    bool progress = true;
+    while (fired < no && progress && rc == PURINE_OK) {
+        progress = false;
+        // one operator per thread queue per sweep, so that independent threads interleave
+        for (auto& kv : queues) {
+            if (kv.second.empty()) continue;
+            const int o = kv.second.front();
+            kv.second.pop_front();
+            purine_graph::Op& op = g->ops[o];
+            if (op.kind != PURINE_OP_HOST_NOP) {
+                hipStream_t st = stream_of(g, op.thread, &rc);
+                if (rc != PURINE_OK) break;
+                // wait for producers that ran on other streams
+                for (int t : op.in)
+                    for (int wr : g->tensors[t].writers) {
+                        purine_graph::Op& w = g->ops[wr];
+                        if (w.kind == PURINE_OP_HOST_NOP || w.thread == op.thread || !w.done) continue;
+                        if (hipStreamWaitEvent(st, w.done, 0) != hipSuccess) { rc = PURINE_E_HIP; break; }
+                    }
+                if (rc != PURINE_OK) break;
+                rc = issue(g, op, st);
+                if (rc != PURINE_OK) break;
+                if (!op.done && hipEventCreateWithFlags(&op.done, hipEventDisableTiming) != hipSuccess) { rc = PURINE_E_HIP; break; }
+                if (hipEventRecord(op.done, st) != hipSuccess) { rc = PURINE_E_HIP; break; }
+            } else {
+                // a host operator completes on the host: wait for the device producers it consumes, so
+                // that readiness keeps its meaning for whatever depends on this operator
+                for (int t : op.in)
+                    for (int wr : g->tensors[t].writers)
+                        if (g->ops[wr].done && hipEventSynchronize(g->ops[wr].done) != hipSuccess) rc = PURINE_E_HIP;
+                if (rc != PURINE_OK) break;
+            }
+            g->fire_log.push_back(o);
+            ++fired;
+            progress = true;
+            // the operator has completed as far as the dispatcher is concerned: update its outgoing tensors
+            for (int t : op.out)
+                if (--writers_pending[t] == 0)
+                    for (int rd : g->tensors[t].readers)
+                        if (--inputs_pending[rd] == 0) queues[g->ops[rd].thread].push_back(rd);
+        }
+    }
+    // all sinks reached: wait for the device work behind them (every stream the run used)
+    int sync_rc = PURINE_OK;
+    if (g->uses_device)
+        for (auto& kv : g->streams)
+            if (hipStreamSynchronize(kv.second) != hipSuccess) sync_rc = PURINE_E_HIP;
+    if (rc != PURINE_OK) return rc;
+    if (fired < no) return PURINE_E_GRAPH;   // some operator can never fire
+    return sync_rc;
+}
+
+int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap) {
+    if (!g) return PURINE_E_NULL;
+    const int n = (int)g->fire_log.size();
+    if (op_ids)
+        for (int i = 0; i < n && i < cap; ++i) op_ids[i] = g->fire_log[i];
+    return n;
+}
+
+int purine_graph_num_ops(const purine_graph* g) { return g ? (int)g->ops.size() : PURINE_E_NULL; }
+int purine_graph_num_tensors(const purine_graph* g) { return g ? (int)g->tensors.size() : PURINE_E_NULL; }
+
+}  // extern "C"

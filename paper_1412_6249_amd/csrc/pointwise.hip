@@ -1,0 +1,279 @@
+// HBM-bound operators: Bias / BiasBwd of the convolution layer (paper Figure 1(b)) and the exact
+// support operators (ReLU, max-pool, channel copy, fan-in sum) that chain layers together.
+// All of them stream each tensor once with coalesced accesses; none uses atomics.
+#include "common.h"
+
+namespace purine {
+namespace {
+
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float v) {
+    uint32_t u = __float_as_uint(v);
+    uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);
+    if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) r = 0x7FC00000u;
+    return (uint16_t)(r >> 16);
+}
+template <typename T> __device__ __forceinline__ float ldf(const T* p, size_t i);
+template <> __device__ __forceinline__ float ldf<float>(const float* p, size_t i) { return p[i]; }
+template <> __device__ __forceinline__ float ldf<uint16_t>(const uint16_t* p, size_t i) { return bf2f(p[i]); }
+template <typename T> __device__ __forceinline__ void stf(T* p, size_t i, float v);
+template <> __device__ __forceinline__ void stf<float>(float* p, size_t i, float v) { p[i] = v; }
+template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t* p, size_t i, float v) { p[i] = f2bf(v); }
+
+constexpr int TPB = 256;
+
+// ---- Bias: one workgroup row per (n,k) plane slice --------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(TPB) void bias_fwd_kernel(const T* __restrict__ b, T* __restrict__ y,
+                                                       int K, int PQ) {
+    const int plane = blockIdx.x;              // n*K + k
+    const float bv = ldf<T>(b, plane % K);
+    T* row = y + (size_t)plane * PQ;
+    for (int i = blockIdx.y * TPB + threadIdx.x; i < PQ; i += gridDim.y * TPB)
+        stf<T>(row, i, ldf<T>(row, i) + bv);
+}
+
+// ---- BiasBwd: lane -> wavefront (shuffle) -> workgroup (LDS) partial per (k, image group),
+//      then one thread per channel adds the group partials in order -------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(TPB) void bias_bwd_partial_kernel(const T* __restrict__ dy,
+                                                               float* __restrict__ partial, int N,
+                                                               int K, int PQ, int imgs_per_part,
+                                                               int parts) {
+    const int k = blockIdx.x, part = blockIdx.y;
+    const int n0 = part * imgs_per_part;
+    const int n1 = min(N, n0 + imgs_per_part);
+    float acc = 0.0f;
+    for (int n = n0; n < n1; ++n) {
+        const T* row = dy + ((size_t)n * K + k) * PQ;
+        for (int i = threadIdx.x; i < PQ; i += TPB) acc += ldf<T>(row, i);
+    }
+    __shared__ float wsum[TPB / 64];
+    acc = wave_sum(acc);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float t = 0.0f;
+#pragma unroll
+        for (int w = 0; w < TPB / 64; ++w) t += wsum[w];
+        partial[(size_t)k * parts + part] = t;
+    }
+}
+
+__global__ __launch_bounds__(TPB) void bias_bwd_final_kernel(const float* __restrict__ partial,
+                                                             float* __restrict__ db, int K,
+                                                             int parts, float beta) {
+    const int k = blockIdx.x * TPB + threadIdx.x;
+    if (k >= K) return;
+    float acc = beta != 0.0f ? db[k] : 0.0f;
+    for (int i = 0; i < parts; ++i) acc += partial[(size_t)k * parts + i];
+    db[k] = acc;
+}
+
+// ---- ReLU -------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(TPB) void relu_fwd_kernel(const T* x, T* y,
+                                                       size_t n) {
+    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += (size_t)gridDim.x * TPB) {
+        const float v = ldf<T>(x, i);
+        stf<T>(y, i, v > 0.0f ? v : 0.0f);
+    }
+}
+template <typename T>
+__global__ __launch_bounds__(TPB) void relu_bwd_kernel(const T* __restrict__ x,
+                                                       const T* dy, T* dx, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += (size_t)gridDim.x * TPB) {
+        const float v = ldf<T>(x, i);
+        stf<T>(dx, i, v > 0.0f ? ldf<T>(dy, i) : 0.0f);
+    }
+}
+
+// ---- max pooling --------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(TPB) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y,
+                                                          int32_t* __restrict__ arg, int H, int W,
+                                                          int P, int Q, int k, int stride, int pad) {
+    const int nc = blockIdx.x;
+    const T* plane = x + (size_t)nc * H * W;
+    for (int o = blockIdx.y * TPB + threadIdx.x; o < P * Q; o += gridDim.y * TPB) {
+        const int p = o / Q, q = o - p * Q;
+        int best = -1;
+        float bv = 0.0f;
+        for (int r = 0; r < k; ++r) {
+            const int h = p * stride - pad + r;
+            if ((unsigned)h >= (unsigned)H) continue;
+            for (int s = 0; s < k; ++s) {
+                const int w = q * stride - pad + s;
+                if ((unsigned)w >= (unsigned)W) continue;
+                const float v = ldf<T>(plane, (size_t)h * W + w);
+                if (best < 0 || v > bv) { best = h * W + w; bv = v; }
+            }
+        }
+        stf<T>(y, (size_t)nc * P * Q + o, bv);
+        arg[(size_t)nc * P * Q + o] = best;
+    }
+}
+
+// Gather form of the pooling gradient: each input position visits the windows that cover it in
+// row-major (p,q) order and adds dy where that window's winner is this position.
+template <typename T>
+__global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ dy,
+                                                          const int32_t* __restrict__ arg,
+                                                          T* dx, float beta, int H,
+                                                          int W, int P, int Q, int k, int stride,
+                                                          int pad) {
+    const int nc = blockIdx.x;
+    const size_t obase = (size_t)nc * P * Q;
+    for (int e = blockIdx.y * TPB + threadIdx.x; e < H * W; e += gridDim.y * TPB) {
+        const int h = e / W, w = e - h * W;
+        // windows p with p*stride - pad <= h <= p*stride - pad + k - 1
+        const int p_hi = min(P - 1, (h + pad) / stride);
+        const int q_hi = min(Q - 1, (w + pad) / stride);
+        int p_lo = h + pad - k + 1;
+        p_lo = p_lo <= 0 ? 0 : (p_lo + stride - 1) / stride;
+        int q_lo = w + pad - k + 1;
+        q_lo = q_lo <= 0 ? 0 : (q_lo + stride - 1) / stride;
+        float acc = beta != 0.0f ? ldf<T>(dx, (size_t)nc * H * W + e) : 0.0f;
+        for (int p = p_lo; p <= p_hi; ++p)
+            for (int q = q_lo; q <= q_hi; ++q)
+                if (arg[obase + p * Q + q] == e) acc += ldf<T>(dy, obase + p * Q + q);
+        stf<T>(dx, (size_t)nc * H * W + e, acc);
+    }
+}
+
+// ---- channel-slice copy (concat and its inverse) -------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(TPB) void copy_channels_kernel(const T* __restrict__ src,
+                                                            T* __restrict__ dst, int c_count,
+                                                            int src_C, int src_c0, int dst_C,
+                                                            int dst_c0, int HW) {
+    const int n = blockIdx.y;
+    const size_t run = (size_t)c_count * HW;   // the slice of one image is contiguous on both sides
+    const T* s = src + ((size_t)n * src_C + src_c0) * HW;
+    T* d = dst + ((size_t)n * dst_C + dst_c0) * HW;
+    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < run; i += (size_t)gridDim.x * TPB)
+        d[i] = s[i];
+}
+
+// ---- fan-in sum ------------------------------------------------------------------------------------
+struct SumArgs { const void* t[8]; int n; };
+template <typename T>
+__global__ __launch_bounds__(TPB) void sum_kernel(SumArgs a, T* out, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += (size_t)gridDim.x * TPB) {
+        float acc = ldf<T>((const T*)a.t[0], i);
+        for (int j = 1; j < a.n; ++j) acc += ldf<T>((const T*)a.t[j], i);
+        stf<T>(out, i, acc);
+    }
+}
+
+inline unsigned blocks_for(size_t n, unsigned cap = 256 * 16) {
+    size_t b = (n + TPB - 1) / TPB;
+    if (b < 1) b = 1;
+    return (unsigned)(b > cap ? cap : b);
+}
+
+}  // namespace
+
+BiasBwdPlan plan_bias_bwd(int N, int K, int PQ) {
+    BiasBwdPlan pl{};
+    (void)PQ;
+    // about 2048 workgroups in total, at least one image per group
+    int parts = (2048 + K - 1) / K;
+    if (parts > N) parts = N;
+    if (parts < 1) parts = 1;
+    pl.imgs_per_part = (N + parts - 1) / parts;
+    pl.parts = (N + pl.imgs_per_part - 1) / pl.imgs_per_part;
+    pl.ws_bytes = (size_t)K * pl.parts * sizeof(float);
+    return pl;
+}
+
+#define BY_DTYPE(dtype, CALL_F32, CALL_BF16) \
+    do { if ((dtype) == PURINE_F32) { CALL_F32; } else { CALL_BF16; } } while (0)
+
+hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st) {
+    dim3 grid((unsigned)(N * K), blocks_for(PQ, 64));
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(bias_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)b, (float*)y, K, PQ),
+             hipLaunchKernelGGL(bias_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)b, (uint16_t*)y, K, PQ));
+    return hipGetLastError();
+}
+
+hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int N, int K, int PQ,
+                           const BiasBwdPlan& plan, void* ws, hipStream_t st) {
+    dim3 grid((unsigned)K, (unsigned)plan.parts);
+    float* partial = (float*)ws;
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(bias_bwd_partial_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts),
+             hipLaunchKernelGGL(bias_bwd_partial_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts));
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bias_bwd_final_kernel, dim3((K + TPB - 1) / TPB), dim3(TPB), 0, st,
+                       (const float*)partial, db, K, plan.parts, beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st) {
+    dim3 grid(blocks_for((size_t)n));
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(relu_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, (size_t)n),
+             hipLaunchKernelGGL(relu_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, (size_t)n));
+    return hipGetLastError();
+}
+
+hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
+                           hipStream_t st) {
+    dim3 grid(blocks_for((size_t)n));
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(relu_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (const float*)dy, (float*)dx, (size_t)n),
+             hipLaunchKernelGGL(relu_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (const uint16_t*)dy, (uint16_t*)dx, (size_t)n));
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,
+                              int P, int Q, int k, int stride, int pad, hipStream_t st) {
+    dim3 grid((unsigned)NC, blocks_for((size_t)P * Q, 64));
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, arg, H, W, P, Q, k, stride, pad),
+             hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, arg, H, W, P, Q, k, stride, pad));
+    return hipGetLastError();
+}
+
+hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, float beta,
+                              int NC, int H, int W, int P, int Q, int k, int stride, int pad,
+                              hipStream_t st) {
+    dim3 grid((unsigned)NC, blocks_for((size_t)H * W, 64));
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, beta, H, W, P, Q, k, stride, pad),
+             hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, beta, H, W, P, Q, k, stride, pad));
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_channels(int dtype, const void* src, void* dst, int N, int c_count,
+                                int src_C, int src_c0, int dst_C, int dst_c0, int HW,
+                                hipStream_t st) {
+    dim3 grid(blocks_for((size_t)c_count * HW, 256), (unsigned)N);
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(copy_channels_kernel<float>, grid, dim3(TPB), 0, st, (const float*)src, (float*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW),
+             hipLaunchKernelGGL(copy_channels_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)src, (uint16_t*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW));
+    return hipGetLastError();
+}
+
+hipError_t launch_sum(int dtype, const void* const* terms, int n_terms, void* out, int64_t n,
+                      hipStream_t st) {
+    SumArgs a{};
+    a.n = n_terms;
+    for (int i = 0; i < n_terms; ++i) a.t[i] = terms[i];
+    dim3 grid(blocks_for((size_t)n));
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(sum_kernel<float>, grid, dim3(TPB), 0, st, a, (float*)out, (size_t)n),
+             hipLaunchKernelGGL(sum_kernel<uint16_t>, grid, dim3(TPB), 0, st, a, (uint16_t*)out, (size_t)n));
+    return hipGetLastError();
+}
+
+}  // namespace purine

@@ -110,3 +110,34 @@ def layer_tensors(layer, config, layer_index=0, integer=False, amax=None):
     if layer.dtype == "bf16":
         x, w, b, dy = (quantize_bf16(t) for t in (x, w, b, dy))
     return x, w, b, dy
+
+
+def fast_uniform(shape, seed, lo=0.0, hi=1.0):
+    """Philox-based uniform fp32 tensor for the full-size workloads (hundreds of millions of
+    elements), where the pure-numpy splitmix stream above would take minutes."""
+    g = np.random.Generator(np.random.Philox(int(seed)))
+    a = g.random(size=shape, dtype=np.float32)
+    if lo != 0.0 or hi != 1.0:
+        a *= np.float32(hi - lo)
+        a += np.float32(lo)
+    return a
+
+
+def fast_gaussian(shape, seed, std=0.01):
+    g = np.random.Generator(np.random.Philox(int(seed)))
+    a = g.standard_normal(size=shape, dtype=np.float32)
+    a *= np.float32(std)
+    return a
+
+
+def layer_tensors_fast(layer, config, layer_index=0):
+    """Same recipe as layer_tensors (x~U[0,1), w,b~N(0,0.01), dy~U[-1,1)) on the fast generator."""
+    base = 10 * layer_index
+    sx, sw, sb, sdy = (tensor_seed(config, base + i) for i in range(4))
+    x = fast_uniform(layer.x_shape, sx, 0, 1)
+    w = fast_gaussian(layer.w_shape, sw, 0.01)
+    b = fast_gaussian((layer.K,), sb, 0.01)
+    dy = fast_uniform(layer.y_shape, sdy, -1, 1)
+    if layer.dtype == "bf16":
+        x, w, b, dy = (quantize_bf16(t) for t in (x, w, b, dy))
+    return x, w, b, dy

@@ -1,0 +1,136 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its host-side
+integer logic (shapes, workspace plans, reciprocal division, argument validation) is right.
+No compute call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1412_6249_amd as pa
+from paper_1412_6249_amd import binding
+from synth.configs import CONV_LAYERS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "purine.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(purine_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_symbols()
+    assert len(names) == 27
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(binding.EXPORTED)
+    for n in names:
+        assert callable(getattr(pa, n)), n
+
+
+def test_out_shape_matches_oracle_and_workload_table():
+    for layers in CONV_LAYERS.values():
+        for l in layers:
+            d = pa.conv_desc(l.stride, l.pad)
+            assert pa.purine_conv_out_shape(d, l.x_shape, l.w_shape) == l.y_shape
+            assert oracle.out_shape(l.x_shape, l.w_shape, l.stride, l.pad) == l.y_shape
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        H, W = rng.integers(1, 40, 2)
+        R, S = rng.integers(1, 8, 2)
+        sh, sw = rng.integers(1, 5, 2)
+        ph, pw = rng.integers(0, 4, 2)
+        xs, ws = (2, 3, int(H), int(W)), (5, 3, int(R), int(S))
+        d = pa.conv_desc((int(sh), int(sw)), (int(ph), int(pw)))
+        P, Q = oracle.out_extent(H, R, sh, ph), oracle.out_extent(W, S, sw, pw)
+        if P <= 0 or Q <= 0:
+            with pytest.raises(pa.PurineError) as e:
+                pa.purine_conv_out_shape(d, xs, ws)
+            assert e.value.status == -2
+        else:
+            assert pa.purine_conv_out_shape(d, xs, ws) == (2, 5, P, Q)
+
+
+def test_out_shape_rejects_bad_arguments():
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_out_shape(pa.conv_desc(1, 0), (1, 3, 8, 8), (4, 2, 3, 3))   # channel mismatch
+    assert e.value.status == -2
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_out_shape(pa.conv_desc(0, 0), (1, 3, 8, 8), (4, 3, 3, 3))   # stride 0
+    assert e.value.status == -8
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_out_shape(pa.conv_desc(1, -1), (1, 3, 8, 8), (4, 3, 3, 3))  # negative pad
+    assert e.value.status == -8
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_out_shape(pa.conv_desc(1, 0), (0, 3, 8, 8), (4, 3, 3, 3))   # empty batch
+    assert e.value.status == -2
+
+
+def test_fastdiv_exact():
+    rng = np.random.default_rng(1)
+    divisors = list(range(1, 70)) + [96, 121, 169, 363, 729, 3025, 12544, 50176, 65535, 65536,
+                                     65537, 2 ** 20 + 1, 2 ** 30, 2 ** 31 - 1]
+    for d in divisors:
+        ns = [0, 1, d - 1, d, d + 1, 2 * d - 1, 2 * d, 2 ** 31 - 1, 2 ** 31 - d, 2 ** 30]
+        ns += [int(v) for v in rng.integers(0, 2 ** 31, 200)]
+        ns += [k * d + o for k in (3, 1000, (2 ** 31 - 1) // d) for o in (-1, 0, 1)]
+        for n in ns:
+            if 0 <= n < 2 ** 31:
+                assert pa.purine_debug_fastdiv(n, d) == n // d, (n, d)
+
+
+def test_workspace_queries():
+    for layers in CONV_LAYERS.values():
+        for l in layers:
+            d = pa.conv_desc(l.stride, l.pad)
+            dt = pa.PURINE_F32 if l.dtype == "f32" else pa.PURINE_BF16
+            assert pa.purine_conv_workspace_bytes(pa.PURINE_CONV_FWD, d, l.x_shape, l.w_shape, dt) == 0
+            assert pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_DATA, d, l.x_shape, l.w_shape, dt) == 0
+            nbytes = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT, d, l.x_shape, l.w_shape, dt)
+            dw_bytes = 4 * int(np.prod(l.w_shape))
+            assert nbytes >= dw_bytes and nbytes % dw_bytes == 0      # whole partial copies of dw
+            assert nbytes <= 1 << 30
+            assert 0 < pa.purine_bias_bwd_workspace_bytes(l.y_shape, dt) <= 4 * l.K * l.N
+    # illegal shapes give 0 (the operator call reports the error)
+    assert pa.purine_conv_workspace_bytes(2, pa.conv_desc(1, 0), (1, 3, 2, 2), (4, 3, 3, 3), 0) == 0
+
+
+def test_operator_argument_validation_without_launch():
+    """All of these must be rejected on the host before any HIP call (there is no GPU here)."""
+    F32, BF16 = pa.PURINE_F32, pa.PURINE_BF16
+    fake = 0x10000   # never dereferenced: validation fails first
+    d = pa.conv_desc(1, 1)
+    x = binding.raw_desc(fake, F32, (2, 3, 8, 8))
+    w = binding.raw_desc(fake + 0x100000, F32, (4, 3, 3, 3))
+    y = binding.raw_desc(fake + 0x200000, F32, (2, 4, 8, 8))
+
+    def status(fn, *a, **k):
+        with pytest.raises(pa.PurineError) as e:
+            fn(*a, **k)
+        return e.value.status
+
+    class _S:   # stand-in stream handle so that torch is not consulted
+        cuda_stream = 0
+    s = _S()
+    assert status(pa.purine_conv_fwd, d, x, w, binding.raw_desc(fake + 0x200000, F32, (2, 4, 7, 8)), stream=s) == -2
+    assert status(pa.purine_conv_fwd, d, x, binding.raw_desc(fake + 0x100000, BF16, (4, 3, 3, 3)), y, stream=s) == -3
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(0, F32, (2, 3, 8, 8)), w, y, stream=s) == -1
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake + 4, F32, (2, 3, 8, 8)), w, y, stream=s) == -4
+    assert status(pa.purine_conv_fwd, d, x, w, binding.raw_desc(fake, F32, (2, 4, 8, 8)), stream=s) == -4  # y aliases x
+    assert status(pa.purine_conv_fwd, pa.conv_desc(0, 1), x, w, y, stream=s) == -8
+    assert status(pa.purine_conv_bwd_data, d, y, w, x, beta=0.5, stream=s) == -8
+    dw = binding.raw_desc(fake + 0x300000, F32, (4, 3, 3, 3))
+    assert status(pa.purine_conv_bwd_weight, d, x, y, dw, stream=s) == -5            # no workspace
+    assert status(pa.purine_conv_bwd_weight, d, x, y, binding.raw_desc(fake + 0x300000, BF16, (4, 3, 3, 3)), stream=s) == -3
+    b = binding.raw_desc(fake + 0x400000, F32, (5,))
+    assert status(pa.purine_bias_fwd, b, y, stream=s) == -2                          # K mismatch
+    db = binding.raw_desc(fake + 0x400000, F32, (4,))
+    assert status(pa.purine_bias_bwd, y, db, stream=s) == -5
+    big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
+    assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
+    assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8

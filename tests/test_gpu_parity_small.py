@@ -1,0 +1,165 @@
+"""GPU parity, element by element against the CPU oracle, at sizes the oracle finishes in seconds
+that still span several tiles and ragged tails. Every call goes through the C ABI.
+
+Tolerance: relative L2 <= 1e-5 (fp32), <= 1e-2 (bf16 inputs, fp32 accumulation); delta kernels and
+integer-valued inputs must match bit for bit (index and shape bookkeeping)."""
+import zlib
+
+import numpy as np
+import pytest
+
+import oracle
+from synth import gen
+from synth.configs import CONV_LAYERS, ConvLayer
+
+pytestmark = pytest.mark.gpu
+
+# name, N, C, H, W, K, R, S, (sh,sw), (ph,pw): ragged against the 32/64/96/128-row tiles, the
+# 128/256-pixel tiles and the 16-deep slabs; strides 1..4; non-square everything
+CASES = [
+    ("tiny", 1, 1, 3, 3, 1, 3, 3, (1, 1), (1, 1)),
+    ("ragged_k37", 3, 5, 19, 23, 37, 3, 2, (2, 1), (1, 0)),
+    ("one_by_one", 2, 40, 13, 11, 100, 1, 1, (1, 1), (0, 0)),
+    ("k130_c33", 2, 33, 15, 15, 130, 3, 3, (1, 1), (1, 1)),
+    ("stride4_11x11", 3, 3, 51, 47, 96, 11, 11, (4, 4), (0, 0)),
+    ("stride3_pad2", 2, 7, 20, 18, 20, 5, 4, (3, 2), (2, 1)),
+    ("k5x5_pad2", 2, 16, 14, 14, 32, 5, 5, (1, 1), (2, 2)),
+    ("stem_like", 2, 3, 40, 40, 64, 7, 7, (2, 2), (3, 3)),
+    ("pad_bigger_than_needed", 1, 2, 5, 6, 3, 3, 3, (1, 1), (2, 2)),
+    ("many_pixels", 5, 4, 37, 41, 8, 3, 3, (1, 1), (1, 1)),
+    ("c200", 1, 200, 9, 9, 48, 3, 3, (1, 1), (1, 1)),
+]
+
+
+def make(case, dtype, seed=0, integer=False):
+    name, N, C, H, W, K, R, S, stride, pad = case
+    rs = np.random.default_rng(zlib.crc32(name.encode()) + seed)
+    P, Q = oracle.out_shape((N, C, H, W), (K, C, R, S), stride, pad)[2:]
+    if integer:
+        d = lambda *s: rs.integers(-2, 3, size=s).astype(np.float32)
+    else:
+        d = lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32)
+    x, w, b, dy = d(N, C, H, W), d(K, C, R, S), d(K), d(N, K, P, Q)
+    if dtype == "bf16":
+        x, w, b, dy = (gen.quantize_bf16(t) for t in (x, w, b, dy))
+    return x, w, b, dy, stride, pad
+
+
+def oracle_layer(x, w, b, dy, stride, pad):
+    return (oracle.bias_fwd(oracle.conv_fwd(x, w, stride, pad), b),
+            oracle.conv_bwd_data(dy, w, x.shape, stride, pad),
+            oracle.conv_bwd_weight(x, dy, w.shape, stride, pad),
+            oracle.bias_bwd(dy))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_layer_parity(case, dtype):
+    from gpu_util import run_layer, rel_l2, TOL
+    x, w, b, dy, stride, pad = make(case, dtype)
+    got = run_layer(x, w, b, dy, stride, pad, dtype)
+    ref = oracle_layer(x, w, b, dy, stride, pad)
+    for name, g, r in zip(("y", "dx", "dw", "db"), got, ref):
+        assert g.shape == r.shape
+        assert np.isfinite(g).all(), name
+        assert rel_l2(g, r) <= TOL[dtype], (case[0], name, rel_l2(g, r))
+
+
+def test_config1_all_operators():
+    from gpu_util import run_layer, rel_l2
+    l = CONV_LAYERS[1][0]
+    x, w, b, dy = gen.layer_tensors(l, 1)
+    got = run_layer(x, w, b, dy, l.stride, l.pad)
+    ref = oracle_layer(x, w, b, dy, l.stride, l.pad)
+    for name, g, r in zip(("y", "dx", "dw", "db"), got, ref):
+        assert rel_l2(g, r) <= 1e-5, (name, rel_l2(g, r))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", [CASES[1], CASES[4], CASES[5], CASES[3]], ids=lambda c: c[0])
+def test_integer_inputs_bit_exact(case, dtype):
+    """Small-integer tensors: every partial sum is an exact integer below 2^24, so any summation
+    order gives the same bits. fp32 outputs must equal the oracle exactly; bf16-stored outputs are
+    compared after the oracle's value is rounded the same way (RNE)."""
+    from gpu_util import run_layer
+    x, w, b, dy, stride, pad = make(case, dtype, integer=True)
+    got = run_layer(x, w, b, dy, stride, pad, dtype)
+    ref = oracle_layer(x, w, b, dy, stride, pad)
+    assert max(np.abs(r).max() for r in ref) < 2 ** 24
+    for i, (g, r) in enumerate(zip(got, ref)):
+        r32 = r.astype(np.float32)
+        if dtype == "bf16" and i < 2:
+            r32 = gen.quantize_bf16(r32)
+        assert np.array_equal(g, r32), ("y", "dx", "dw", "db")[i]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("r0,s0,stride,pad", [(1, 1, 1, 1), (0, 2, 1, 1), (2, 0, 2, 1), (4, 3, 3, 2)])
+def test_delta_kernel_is_an_exact_shift(r0, s0, stride, pad, dtype):
+    """w = delta at tap (r0,s0) on the channel diagonal: y is x shifted (cross-correlation, zero
+    fill), bit for bit; dx of a delta is dy scattered back, bit for bit."""
+    from gpu_util import run_layer
+    N, C, H, W, R = 2, 5, 17, 21, 5 if r0 > 2 else 3
+    rs = np.random.default_rng(3)
+    x = rs.uniform(-1, 1, (N, C, H, W)).astype(np.float32)
+    w = np.zeros((C, C, R, R), np.float32)
+    for c in range(C):
+        w[c, c, r0, s0] = 1.0
+    b = np.zeros(C, np.float32)
+    P, Q = oracle.out_shape(x.shape, w.shape, stride, pad)[2:]
+    dy = rs.uniform(-1, 1, (N, C, P, Q)).astype(np.float32)
+    if dtype == "bf16":
+        x, dy = gen.quantize_bf16(x), gen.quantize_bf16(dy)
+    y, dx, dw, db = run_layer(x, w, b, dy, stride, pad, dtype)
+    ey = np.zeros((N, C, P, Q), np.float32)
+    edx = np.zeros_like(x)
+    for p in range(P):
+        for q in range(Q):
+            h, ww = p * stride - pad + r0, q * stride - pad + s0
+            if 0 <= h < H and 0 <= ww < W:
+                ey[:, :, p, q] = x[:, :, h, ww]
+                edx[:, :, h, ww] = dy[:, :, p, q]
+    assert np.array_equal(y, ey)
+    assert np.array_equal(dx, edx)
+    assert np.array_equal(y.astype(np.float64), oracle.conv_fwd(x, w, stride, pad))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_beta_one_accumulates(dtype):
+    from gpu_util import run_layer, rel_l2, TOL
+    case = CASES[5]
+    x, w, b, dy, stride, pad = make(case, dtype)
+    rs = np.random.default_rng(9)
+    prev = [rs.uniform(-1, 1, s).astype(np.float32) for s in (x.shape, w.shape, b.shape)]
+    if dtype == "bf16":
+        prev[0] = gen.quantize_bf16(prev[0])
+    _, dx, dw, db = run_layer(x, w, b, dy, stride, pad, dtype, beta=1.0, prev=prev)
+    _, rdx, rdw, rdb = oracle_layer(x, w, b, dy, stride, pad)
+    assert rel_l2(dx, rdx + prev[0]) <= TOL[dtype]
+    assert rel_l2(dw, rdw + prev[1]) <= TOL[dtype]
+    assert rel_l2(db, rdb + prev[2]) <= TOL[dtype]
+
+
+def test_results_are_bit_identical_run_to_run():
+    from gpu_util import run_layer
+    x, w, b, dy, stride, pad = make(CASES[3], "f32")
+    a = run_layer(x, w, b, dy, stride, pad)
+    c = run_layer(x, w, b, dy, stride, pad)
+    for u, v in zip(a, c):
+        assert np.array_equal(u, v)
+
+
+def test_batch_shards_add_up():
+    """Data-parallel invariant (paper section 3.4): y and dx of a batch are the concatenation of
+    the shards' results, dw and db are the sums over shards."""
+    from gpu_util import run_layer, rel_l2
+    x, w, b, dy, stride, pad = make(CASES[9], "f32")
+    y, dx, dw, db = run_layer(x, w, b, dy, stride, pad)
+    parts = [slice(0, 2), slice(2, 5)]
+    sdw, sdb = np.zeros_like(dw, dtype=np.float64), np.zeros_like(db, dtype=np.float64)
+    for s in parts:
+        ys, dxs, dws, dbs = run_layer(x[s], w, b, dy[s], stride, pad)
+        assert np.array_equal(ys, y[s]) and np.array_equal(dxs, dx[s])
+        sdw += dws
+        sdb += dbs
+    assert rel_l2(dw, sdw) <= 1e-5 and rel_l2(db, sdb) <= 1e-5

@@ -1,0 +1,209 @@
+"""Bi-graph executor bookkeeping on the CPU (host-only operators, no device work).
+
+Dispatcher rules under test (paper section 2.1 and the `thread` property of section 3): every
+operator fires exactly once; never before all its incoming tensors are ready; a tensor is ready
+only when all its incoming operators have fired; operators of one thread keep FIFO order; the run
+ends only when all sinks are reached; an illegal graph is an error, not a hang."""
+import random
+
+import pytest
+
+import paper_1412_6249_amd as pa
+from paper_1412_6249_amd import binding
+
+F32 = pa.PURINE_F32
+
+
+def host_tensor(g, name=None, ptr=0, dims=(1,)):
+    return pa.purine_graph_add_tensor(g, binding.raw_desc(ptr, F32, dims), name)
+
+
+def nop(g, ins, outs, thread=0):
+    return pa.purine_graph_add_op(g, pa.OP_HOST_NOP, ins, outs, thread)
+
+
+def check_legal(order, ops):
+    """ops: id -> (ins, outs, thread). Legal = every producer of every input fired earlier."""
+    pos = {o: i for i, o in enumerate(order)}
+    assert sorted(order) == sorted(ops), "each operator fires exactly once"
+    writers = {}
+    for o, (ins, outs, _) in ops.items():
+        for t in outs:
+            writers.setdefault(t, []).append(o)
+    for o, (ins, outs, _) in ops.items():
+        for t in ins:
+            for wtr in writers.get(t, []):
+                assert pos[wtr] < pos[o], (wtr, o)
+
+
+def test_chain_single_thread_is_insertion_topological_order():
+    g = pa.purine_graph_create()
+    t = [host_tensor(g, "t%d" % i) for i in range(6)]
+    a = nop(g, [t[0]], [t[1]])
+    b = nop(g, [t[1]], [t[2]])
+    c = nop(g, [t[0]], [t[3]])
+    d = nop(g, [t[2], t[3]], [t[4]])
+    e = nop(g, [t[4]], [t[5]])
+    pa.purine_graph_run(g)
+    assert pa.purine_graph_fire_log(g) == [a, c, b, d, e]
+    pa.purine_graph_run(g)                      # graphs can be iterated (section 2.2)
+    assert pa.purine_graph_fire_log(g) == [a, c, b, d, e]
+    assert pa.purine_graph_num_ops(g) == 5 and pa.purine_graph_num_tensors(g) == 6
+    pa.purine_graph_destroy(g)
+
+
+def test_tensor_with_two_incoming_operators_waits_for_both():
+    g = pa.purine_graph_create()
+    s0, s1, mid, out = (host_tensor(g) for _ in range(4))
+    late = nop(g, [s1], [mid], thread=1)
+    early = nop(g, [s0], [mid], thread=0)
+    consumer = nop(g, [mid], [out], thread=2)
+    pa.purine_graph_run(g)
+    order = pa.purine_graph_fire_log(g)
+    assert order.index(consumer) == 2 and set(order[:2]) == {late, early}
+    pa.purine_graph_destroy(g)
+
+
+def test_conv_layer_bigraph_shape():
+    """Figure 1(b): the conv layer as five operators over eight tensors, backward ops on own threads."""
+    g = pa.purine_graph_create()
+    names = ["bottom", "weight", "bias", "top", "top_b", "top_grad", "bottom_grad", "weight_grad", "bias_grad"]
+    t = {n: host_tensor(g, n) for n in names}
+    ops = {}
+    ops[nop(g, [t["bottom"], t["weight"]], [t["top"]], 0)] = ([t["bottom"], t["weight"]], [t["top"]], 0)
+    ops[nop(g, [t["top"], t["bias"]], [t["top_b"]], 0)] = ([t["top"], t["bias"]], [t["top_b"]], 0)
+    ops[nop(g, [t["top_grad"], t["weight"]], [t["bottom_grad"]], 0)] = ([t["top_grad"], t["weight"]], [t["bottom_grad"]], 0)
+    ops[nop(g, [t["bottom"], t["top_grad"]], [t["weight_grad"]], 1)] = ([t["bottom"], t["top_grad"]], [t["weight_grad"]], 1)
+    ops[nop(g, [t["top_grad"]], [t["bias_grad"]], 2)] = ([t["top_grad"]], [t["bias_grad"]], 2)
+    pa.purine_graph_run(g)
+    check_legal(pa.purine_graph_fire_log(g), ops)
+    pa.purine_graph_destroy(g)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_dags_fire_legally_with_fifo_threads(seed):
+    rnd = random.Random(seed)
+    g = pa.purine_graph_create()
+    n_src, n_ops = 4, 60
+    tensors = [host_tensor(g) for _ in range(n_src)]
+    ops = {}
+    for _ in range(n_ops):
+        ins = rnd.sample(tensors, rnd.randint(1, min(3, len(tensors))))
+        outs = [host_tensor(g) for _ in range(rnd.randint(1, 2))]
+        if rnd.random() < 0.2 and len(tensors) > n_src:   # a second writer for an existing non-source tensor
+            extra = rnd.choice(tensors[n_src:])
+            if extra not in ins:
+                outs.append(extra)
+        th = rnd.randint(0, 3)
+        try:
+            o = nop(g, ins, outs, th)
+        except pa.PurineError:
+            continue
+        ops[o] = (ins, outs, th)
+        tensors.extend(t for t in outs if t not in tensors)
+    try:
+        pa.purine_graph_run(g)
+    except pa.PurineError as e:
+        assert e.status == -6          # the extra writer closed a cycle: must be reported, not hang
+        pa.purine_graph_destroy(g)
+        return
+    order = pa.purine_graph_fire_log(g)
+    check_legal(order, ops)
+    # FIFO per thread: among operators of one thread, firing order = the order they became ready,
+    # and "ready" is monotone in the firing order of their last producer
+    pos = {o: i for i, o in enumerate(order)}
+    writers = {}
+    for o, (ins, outs, _) in ops.items():
+        for t in outs:
+            writers.setdefault(t, []).append(o)
+
+    def ready_time(o):
+        return max([pos[w] for t in ops[o][0] for w in writers.get(t, [])], default=-1)
+    for th in range(4):
+        mine = [o for o in order if ops[o][2] == th]
+        times = [ready_time(o) for o in mine]
+        assert times == sorted(times), (th, times)
+    pa.purine_graph_destroy(g)
+
+
+def test_cycle_is_an_error_not_a_hang():
+    g = pa.purine_graph_create()
+    a, b = host_tensor(g), host_tensor(g)
+    nop(g, [a], [b])
+    nop(g, [b], [a])
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_run(g)
+    assert e.value.status == -6
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_validate(g)
+    assert e.value.status == -6
+    pa.purine_graph_destroy(g)
+
+
+def test_bipartite_rules_and_bad_ids():
+    g = pa.purine_graph_create()
+    a, b = host_tensor(g), host_tensor(g)
+    for bad in ([a], [99]), ([-1], [b]):
+        with pytest.raises(pa.PurineError) as e:
+            nop(g, bad[0], bad[1]) if bad[1] != [99] else nop(g, [a], [99])
+        assert e.value.status == -8
+    with pytest.raises(pa.PurineError) as e:
+        nop(g, [a], [a])                       # operator reading and writing one vertex
+    assert e.value.status == -6
+    with pytest.raises(pa.PurineError) as e:
+        nop(g, [a], [b, b])
+    assert e.value.status == -6
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_add_op(g, pa.OP_CONV_FWD, [a], [b])     # conv needs two inputs
+    assert e.value.status == -8
+    with pytest.raises(pa.PurineError) as e:
+        nop(g, [a], [b], thread=-1)
+    assert e.value.status == -8
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_add_op(g, 77, [a], [b])
+    assert e.value.status == -8
+    pa.purine_graph_destroy(g)
+
+
+def test_unordered_writers_of_shared_storage_are_rejected():
+    """Two device operators that write overlapping bytes with no path between them: validate()
+    refuses (pure host analysis, nothing is launched)."""
+    g = pa.purine_graph_create()
+    x = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, (1, 2, 4, 4)), "x")
+    y1 = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, (1, 2, 4, 4)), "y1")
+    y2 = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000 + 64, F32, (1, 2, 4, 4)), "y2")
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [x], [y1], 0)
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [x], [y2], 1)
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_validate(g)
+    assert e.value.status == -6
+    pa.purine_graph_destroy(g)
+    # the same two writers chained through a version edge are fine
+    g = pa.purine_graph_create()
+    x = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, (1, 2, 4, 4)), "x")
+    v0 = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, (1, 2, 4, 4)), "v0")
+    v1 = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, (1, 2, 4, 4)), "v1")
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [x], [v0], 0)
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [v0], [v1], 1)   # in place: version 0 -> version 1
+    pa.purine_graph_validate(g)
+    pa.purine_graph_destroy(g)
+    # a reader racing an in-place writer is refused as well
+    g = pa.purine_graph_create()
+    x = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, (1, 2, 4, 4)), "x")
+    v0 = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, (1, 2, 4, 4)), "v0")
+    v1 = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, (1, 2, 4, 4)), "v1")
+    z = pa.purine_graph_add_tensor(g, binding.raw_desc(0x5000, F32, (1, 2, 4, 4)), "z")
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [x], [v0], 0)
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [v0], [v1], 0)
+    pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [v0], [z], 1)
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_validate(g)
+    assert e.value.status == -6
+    pa.purine_graph_destroy(g)
+
+
+def test_empty_graph_runs():
+    g = pa.purine_graph_create()
+    pa.purine_graph_run(g)
+    assert pa.purine_graph_fire_log(g) == []
+    pa.purine_graph_destroy(g)
