@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Throughput of the conv-layer hot path on one MI355X.
+
+One step = one forward + backward pass of the whole workload bi-graph (every Conv, Bias,
+ConvBwdData, ConvBwdWeight and BiasBwd operator, plus the ReLU/pool/concat glue), driven by the
+C-ABI executor with inputs already resident in HBM. value = conv FLOPs of the step (dense
+convention, 3 passes x 2*N*K*C*R*S*P*Q per layer) / wall time, in TFLOP/s.
+
+Prints ONE JSON line. `roofline` describes the single kernel that takes the most time in the
+step (its FLOPs / its average duration measured with HIP events on its own stream inside the timed
+region); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same layers.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
+# runs of this same command (see profiles/); None until measured for that kernel.
+MEASURED_TRAFFIC_BYTES = {}
+
+KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
+              5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
+              10: "concat_bwd", 11: "sum"}
+
+
+def cpu_baseline(cfg, budget_s=15.0):
+    """The oracle as it stands, on a batch-subset of every conv layer of the workload (standalone
+    layers with synthetic inputs of the same recipe): fwd + bias, bwd-data, bwd-weight, bias-bwd."""
+    import oracle
+    from synth import gen
+    from synth.configs import CONV_LAYERS
+    layers = CONV_LAYERS[cfg]
+
+    def run(n_img):
+        flop = 0
+        for i, L in enumerate(layers):
+            Ls = L.with_batch(n_img)
+            x, w, b, dy = gen.layer_tensors_fast(Ls, cfg, i)
+            ts = time.perf_counter()
+            oracle.bias_fwd(oracle.conv_fwd(x, w, L.stride, L.pad), b)
+            oracle.conv_bwd_data(dy, w, x.shape, L.stride, L.pad)
+            oracle.conv_bwd_weight(x, dy, w.shape, L.stride, L.pad)
+            oracle.bias_bwd(dy)
+            run.compute += time.perf_counter() - ts
+            flop += 3 * Ls.flop_per_pass
+        return flop
+    run.compute = 0.0
+    run(1)
+    t1 = run.compute
+    n_img = int(max(1, min(layers[0].N, budget_s / max(t1, 1e-3))))
+    run.compute = 0.0
+    flop = run(n_img)
+    secs = run.compute
+    if secs < 0.6 * budget_s and n_img < layers[0].N:      # one image under-uses the cores: rescale once
+        n_img = int(max(1, min(layers[0].N, n_img * budget_s / secs)))
+        run.compute = 0.0
+        flop = run(n_img)
+        secs = run.compute
+    return {"value": flop / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(secs, 2),
+            "sample": "%d of %d images of every conv layer of the workload, all five operators, "
+                      "standalone layers with the same input recipe" % (n_img, layers[0].N)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: NIN mlpconv block)")
+    ap.add_argument("--single-stream", action="store_true", help="all operators on one thread id")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ops", action="store_true", help="print the per-operator table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on exactly one GPU (the path has no collectives); "
+                         "--gpus %d is not supported\n" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    import paper_1412_6249_amd as pa
+    from paper_1412_6249_amd.layers import build_workload
+    from synth.configs import CONV_LAYERS, WORKLOAD_NAMES, total_flop
+
+    cfg = args.config
+    torch.cuda.set_device(0)
+    gb = build_workload(cfg, multi_stream=not args.single_stream)
+    for _ in range(args.warmup):
+        gb.run()
+    pa.purine_graph_enable_timing(gb.g, True)
+    op_ms = {op[0]: 0.0 for op in gb.ops}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        gb.run()                      # returns after every sink's device work has completed
+        for oid in op_ms:
+            op_ms[oid] += pa.purine_graph_op_elapsed_ms(gb.g, oid)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flop = total_flop(cfg)
+    dtype = CONV_LAYERS[cfg][0].dtype
+
+    # dominant kernel of the step
+    by_out = {rec[k]: (rec["layer"], k) for rec in gb.conv_records for k in ("y", "dx", "dw")}
+    rows = []
+    for oid, kind, ins, outs, _ in gb.ops:
+        avg = op_ms[oid] / args.steps
+        L = by_out.get(outs[0], (None, None))[0] if kind in (0, 2, 3) else None
+        rows.append((avg, oid, kind, outs[0], L))
+    rows.sort(reverse=True)
+    if args.ops:
+        for avg, oid, kind, out, L in rows:
+            extra = "  %.1f TFLOP/s" % (L.flop_per_pass / avg / 1e9) if L is not None and avg > 0 else ""
+            sys.stderr.write("%9.3f ms  %-16s %s%s\n" % (avg, KIND_NAMES[kind], out, extra))
+        sys.stderr.write("sum of kernels %.3f ms, step %.3f ms\n" % (sum(r[0] for r in rows), ms_per_step))
+    top = next(r for r in rows if r[4] is not None)
+    avg_ms, _, kind, out_name, L = top
+    kname = "%s[%s]" % (KIND_NAMES[kind], out_name)
+    achieved = L.flop_per_pass / (avg_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 3),
+                "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_TFLOPS[dtype], 4),
+                "avg_kernel_ms": round(avg_ms, 4),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, kname))}
+
+    result = {
+        "metric": "conv fwd+bwd TFLOP/s on one MI355X",
+        "value": round(flop / (ms_per_step * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[cfg], "conv_gflop_per_step": round(flop / 1e9, 2),
+                   "executor": "bi-graph, %s" % ("1 stream" if args.single_stream else "3+ streams"),
+                   "frac_of_mfma_peak": round(flop / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[dtype], 4)},
+        "roofline": roofline,
+    }
+    gb.close()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -207,6 +207,19 @@ int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap);
 int purine_graph_num_ops(const purine_graph* g);
 int purine_graph_num_tensors(const purine_graph* g);
 
+/* Per-operator device timing. With timing on, purine_graph_run brackets the main kernel of every
+ * device operator with a pair of HIP events on the operator's own stream (the small second-pass
+ * kernels of the split reductions are outside the bracket). After the run,
+ * purine_graph_op_elapsed_ms gives the elapsed time of that bracket in the last run.
+ * PURINE_E_ARG for a bad id, a host operator, or when the last run was not timed. */
+int purine_graph_enable_timing(purine_graph* g, int on);
+int purine_graph_op_elapsed_ms(purine_graph* g, int op_id, float* ms);
+
+/* The same bracket for direct operator calls: the next operator call made by this host thread
+ * records start_event (a hipEvent_t) just before its main kernel and stop_event just after it, on
+ * the stream it was given, and then forgets the pair. Pass NULLs to cancel. */
+void purine_set_kernel_probe(void* start_event, void* stop_event);
+
 /* Test hook (host only): n / d computed with the multiply-and-shift reciprocal that the kernels'
  * index arithmetic uses; valid for 0 <= n < 2^31 and 1 <= d < 2^31. */
 uint32_t purine_debug_fastdiv(uint32_t n, uint32_t d);

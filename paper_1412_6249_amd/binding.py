@@ -87,6 +87,9 @@ _SIGS = {
     "purine_graph_num_ops": (ctypes.c_int, [_vp]),
     "purine_graph_num_tensors": (ctypes.c_int, [_vp]),
     "purine_debug_fastdiv": (ctypes.c_uint32, [ctypes.c_uint32, ctypes.c_uint32]),
+    "purine_graph_enable_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "purine_graph_op_elapsed_ms": (ctypes.c_int, [_vp, ctypes.c_int, _P(ctypes.c_float)]),
+    "purine_set_kernel_probe": (None, [_vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -342,3 +345,18 @@ def purine_graph_num_ops(g):
 
 def purine_graph_num_tensors(g):
     return int(_lib.purine_graph_num_tensors(g))
+
+
+def purine_graph_enable_timing(g, on=True):
+    _check(_lib.purine_graph_enable_timing(g, 1 if on else 0), "purine_graph_enable_timing")
+
+
+def purine_graph_op_elapsed_ms(g, op_id):
+    ms = ctypes.c_float()
+    _check(_lib.purine_graph_op_elapsed_ms(g, int(op_id), ctypes.byref(ms)), "purine_graph_op_elapsed_ms")
+    return float(ms.value)
+
+
+def purine_set_kernel_probe(start_event, stop_event):
+    """start/stop: raw hipEvent_t handles (ints) or None."""
+    _lib.purine_set_kernel_probe(start_event, stop_event)

@@ -81,7 +81,20 @@ int make_geom(const purine_conv_desc* d, const int64_t* xd, const int64_t* wd, c
 
 }  // namespace
 
+namespace purine {
+static thread_local KernelProbe g_probe{nullptr, nullptr};
+KernelProbe take_kernel_probe() {
+    KernelProbe p = g_probe;
+    g_probe = KernelProbe{nullptr, nullptr};
+    return p;
+}
+}  // namespace purine
+
 extern "C" {
+
+void purine_set_kernel_probe(void* start_event, void* stop_event) {
+    purine::g_probe = KernelProbe{(hipEvent_t)start_event, (hipEvent_t)stop_event};
+}
 
 const char* purine_status_string(int status) {
     switch (status) {

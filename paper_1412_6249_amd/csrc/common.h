@@ -84,6 +84,15 @@ struct BiasBwdPlan {
 };
 BiasBwdPlan plan_bias_bwd(int N, int K, int PQ);
 
+// One-shot event pair that brackets the main kernel of the next operator call of this host thread.
+struct KernelProbe { hipEvent_t start, stop; };
+KernelProbe take_kernel_probe();   // returns the pending pair (or NULLs) and clears it
+struct ProbeScope {                 // records start on construction and stop on destruction
+    KernelProbe p; hipStream_t st;
+    explicit ProbeScope(hipStream_t s) : p(take_kernel_probe()), st(s) { if (p.start) (void)hipEventRecord(p.start, st); }
+    ~ProbeScope() { if (p.stop) (void)hipEventRecord(p.stop, st); }
+};
+
 // Kernel launchers (defined in the .hip files). Each returns a hipError_t from the launch.
 hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
                            const void* wt, void* out, float beta, hipStream_t st);

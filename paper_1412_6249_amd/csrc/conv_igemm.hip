@@ -244,6 +244,7 @@ hipError_t launch_cfg(PixGemmParams& p, hipStream_t st) {
     p.tiles_pix = (p.M + BN - 1) / BN;
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProbeScope probe(st);
     hipLaunchKernelGGL((igemm_pix_kernel<T, MODE, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();

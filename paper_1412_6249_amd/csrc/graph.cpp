@@ -33,6 +33,8 @@ struct purine_graph {
         std::vector<int> in, out;
         int thread;
         hipEvent_t done = nullptr;  // recorded after the operator on its stream (device ops only)
+        hipEvent_t t0 = nullptr, t1 = nullptr;   // timing bracket around the main kernel
+        bool timed = false;
     };
     std::vector<Tensor> tensors;
     std::vector<Op> ops;
@@ -41,6 +43,7 @@ struct purine_graph {
     std::vector<int> fire_log;
     bool validated = false;
     bool uses_device = false;
+    bool timing = false;
 };
 
 namespace {
@@ -141,7 +144,11 @@ purine_graph* purine_graph_create(void) { return new (std::nothrow) purine_graph
 void purine_graph_destroy(purine_graph* g) {
     if (!g) return;
     for (auto& op : g->ops)
+    {
         if (op.done) (void)hipEventDestroy(op.done);
+        if (op.t0) (void)hipEventDestroy(op.t0);
+        if (op.t1) (void)hipEventDestroy(op.t1);
+    }
     for (auto& kv : g->streams)
         if (g->stream_owned[kv.first]) (void)hipStreamDestroy(kv.second);
     delete g;
@@ -310,7 +317,14 @@ int purine_graph_run(purine_graph* g) {
                         if (hipStreamWaitEvent(st, w.done, 0) != hipSuccess) { rc = PURINE_E_HIP; break; }
                     }
                 if (rc != PURINE_OK) break;
+                op.timed = false;
+                if (g->timing) {
+                    if ((!op.t0 && hipEventCreate(&op.t0) != hipSuccess) ||
+                        (!op.t1 && hipEventCreate(&op.t1) != hipSuccess)) { rc = PURINE_E_HIP; break; }
+                    purine_set_kernel_probe(op.t0, op.t1);
+                }
                 rc = issue(g, op, st);
+                if (g->timing) { purine_set_kernel_probe(nullptr, nullptr); op.timed = rc == PURINE_OK; }
                 if (rc != PURINE_OK) break;
                 if (!op.done && hipEventCreateWithFlags(&op.done, hipEventDisableTiming) != hipSuccess) { rc = PURINE_E_HIP; break; }
                 if (hipEventRecord(op.done, st) != hipSuccess) { rc = PURINE_E_HIP; break; }
@@ -340,6 +354,20 @@ int purine_graph_run(purine_graph* g) {
     if (rc != PURINE_OK) return rc;
     if (fired < no) return PURINE_E_GRAPH;   // some operator can never fire
     return sync_rc;
+}
+
+int purine_graph_enable_timing(purine_graph* g, int on) {
+    if (!g) return PURINE_E_NULL;
+    g->timing = on != 0;
+    return PURINE_OK;
+}
+
+int purine_graph_op_elapsed_ms(purine_graph* g, int op_id, float* ms) {
+    if (!g || !ms) return PURINE_E_NULL;
+    if (op_id < 0 || op_id >= (int)g->ops.size()) return PURINE_E_ARG;
+    purine_graph::Op& op = g->ops[op_id];
+    if (!op.timed || !op.t0 || !op.t1) return PURINE_E_ARG;
+    return hipEventElapsedTime(ms, op.t0, op.t1) == hipSuccess ? PURINE_OK : PURINE_E_HIP;
 }
 
 int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap) {

@@ -198,6 +198,7 @@ BiasBwdPlan plan_bias_bwd(int N, int K, int PQ) {
 
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st) {
     dim3 grid((unsigned)(N * K), blocks_for(PQ, 64));
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(bias_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)b, (float*)y, K, PQ),
              hipLaunchKernelGGL(bias_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)b, (uint16_t*)y, K, PQ));
@@ -208,9 +209,12 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
                            const BiasBwdPlan& plan, void* ws, hipStream_t st) {
     dim3 grid((unsigned)K, (unsigned)plan.parts);
     float* partial = (float*)ws;
+    {
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(bias_bwd_partial_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts),
              hipLaunchKernelGGL(bias_bwd_partial_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts));
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(bias_bwd_final_kernel, dim3((K + TPB - 1) / TPB), dim3(TPB), 0, st,
@@ -220,6 +224,7 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
 
 hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st) {
     dim3 grid(blocks_for((size_t)n));
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, (size_t)n),
              hipLaunchKernelGGL(relu_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, (size_t)n));
@@ -229,6 +234,7 @@ hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStre
 hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
                            hipStream_t st) {
     dim3 grid(blocks_for((size_t)n));
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (const float*)dy, (float*)dx, (size_t)n),
              hipLaunchKernelGGL(relu_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (const uint16_t*)dy, (uint16_t*)dx, (size_t)n));
@@ -238,6 +244,7 @@ hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, i
 hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,
                               int P, int Q, int k, int stride, int pad, hipStream_t st) {
     dim3 grid((unsigned)NC, blocks_for((size_t)P * Q, 64));
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, arg, H, W, P, Q, k, stride, pad),
              hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, arg, H, W, P, Q, k, stride, pad));
@@ -248,6 +255,7 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
                               int NC, int H, int W, int P, int Q, int k, int stride, int pad,
                               hipStream_t st) {
     dim3 grid((unsigned)NC, blocks_for((size_t)H * W, 64));
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, beta, H, W, P, Q, k, stride, pad),
              hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, beta, H, W, P, Q, k, stride, pad));
@@ -258,6 +266,7 @@ hipError_t launch_copy_channels(int dtype, const void* src, void* dst, int N, in
                                 int src_C, int src_c0, int dst_C, int dst_c0, int HW,
                                 hipStream_t st) {
     dim3 grid(blocks_for((size_t)c_count * HW, 256), (unsigned)N);
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(copy_channels_kernel<float>, grid, dim3(TPB), 0, st, (const float*)src, (float*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW),
              hipLaunchKernelGGL(copy_channels_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)src, (uint16_t*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW));
@@ -270,6 +279,7 @@ hipError_t launch_sum(int dtype, const void* const* terms, int n_terms, void* ou
     a.n = n_terms;
     for (int i = 0; i < n_terms; ++i) a.t[i] = terms[i];
     dim3 grid(blocks_for((size_t)n));
+    ProbeScope probe(st);
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(sum_kernel<float>, grid, dim3(TPB), 0, st, a, (float*)out, (size_t)n),
              hipLaunchKernelGGL(sum_kernel<uint16_t>, grid, dim3(TPB), 0, st, a, (uint16_t*)out, (size_t)n));

@@ -1,0 +1,256 @@
+"""Bi-graphs of the five synthetic workloads, built on the C-ABI executor.
+
+Each conv layer becomes the operator subgraph of the paper's Figure 1(b): Conv and Bias forward,
+ConvBwdData, ConvBwdWeight and BiasBwd backward, with one tensor vertex per buffer VERSION (an
+in-place operator reads version i and writes version i+1 of the same storage). Operators get
+`thread` ids (paper section 3) so that the three backward operators of a layer, which share only
+inputs, can overlap on separate HIP streams. Only graph wiring lives here: every computation is an
+operator of libpurine_conv.so.
+"""
+import torch
+
+from . import binding as B
+from synth.configs import CONV_LAYERS
+
+T_MAIN, T_WGRAD, T_BGRAD = 0, 1, 2     # default thread ids: data path, weight grads, bias grads
+
+
+def _tdtype(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+def _pcode(dtype):
+    return B.PURINE_BF16 if dtype == "bf16" else B.PURINE_F32
+
+
+class GraphBuilder:
+    """Owns the device tensors (by name) and the purine_graph handle."""
+
+    def __init__(self, device="cuda:0", inplace=True):
+        self.device = torch.device(device)
+        self.inplace = inplace
+        self.g = B.purine_graph_create()
+        self.t = {}          # name -> torch tensor (storage)
+        self.ids = {}        # name -> tensor vertex id
+        self.ops = []        # (op id, kind, in names, out names, attrs kept alive)
+        self.conv_records = []   # one dict per conv layer, naming the vertices around each operator
+        self._keep = []
+
+    def close(self):
+        if self.g is not None:
+            B.purine_graph_destroy(self.g)
+            self.g = None
+
+    # ---- vertices
+    def new(self, name, shape, dtype="f32", fill=None):
+        td = torch.int32 if dtype == "i32" else _tdtype(dtype)
+        ten = torch.empty(tuple(int(s) for s in shape), dtype=td, device=self.device)
+        if fill is not None:
+            ten.fill_(fill)
+        return self.bind(name, ten)
+
+    def bind(self, name, tensor):
+        assert name not in self.ids, name
+        self.t[name] = tensor
+        self.ids[name] = B.purine_graph_add_tensor(self.g, tensor, name)
+        return name
+
+    def version(self, name, of):
+        """A new vertex for the next version of `of`: same storage when in-place, fresh otherwise."""
+        if self.inplace:
+            return self.bind(name, self.t[of])
+        return self.bind(name, torch.empty_like(self.t[of]))
+
+    def workspace(self, nbytes):
+        ws = torch.empty(max(256, int(nbytes)), dtype=torch.uint8, device=self.device)
+        self._keep.append(ws)
+        return ws
+
+    def op(self, kind, ins, outs, thread=T_MAIN, attrs=None):
+        oid = B.purine_graph_add_op(self.g, kind, [self.ids[n] for n in ins],
+                                    [self.ids[n] for n in outs], thread, attrs)
+        self.ops.append((oid, kind, list(ins), list(outs), attrs))
+        return oid
+
+    # ---- layer-level wiring
+    def conv_forward(self, L, x, w, b, prefix, relu, thread=T_MAIN):
+        """x -> Conv -> Bias [-> ReLU]; returns the name of the layer output vertex."""
+        desc = B.conv_desc(L.stride, L.pad)
+        y0 = self.new(prefix + ".y", L.y_shape, L.dtype)
+        self.op(B.OP_CONV_FWD, [x, w], [y0], thread, B.op_attrs(conv=desc))
+        # Bias is in place by definition of the operator (y += b)
+        if self.inplace:
+            y1 = self.bind(prefix + ".yb", self.t[y0])
+            self.op(B.OP_BIAS_FWD, [y0, b], [y1], thread)
+        else:
+            # out-of-place variant for the tests: copy version 0 with a one-term Sum, then add bias
+            yc = self.new(prefix + ".yc", L.y_shape, L.dtype)
+            self.op(B.OP_SUM, [y0], [yc], thread)
+            y1 = self.bind(prefix + ".yb", self.t[yc])
+            self.op(B.OP_BIAS_FWD, [yc, b], [y1], thread)
+        out = y1
+        if relu:
+            out = self.version(prefix + ".a", y1)
+            self.op(B.OP_RELU_FWD, [y1], [out], thread)
+        rec = dict(layer=L, prefix=prefix, x=x, w=w, b=b, y=y0, yb=y1, out=out, relu=relu)
+        self.conv_records.append(rec)
+        return out, rec
+
+    def conv_backward(self, rec, dout, thread=T_MAIN, t_w=T_WGRAD, t_b=T_BGRAD, need_dx=True):
+        """dout is the gradient at the layer output (after ReLU if the layer has one)."""
+        L, p = rec["layer"], rec["prefix"]
+        desc = B.conv_desc(L.stride, L.pad)
+        dy = dout
+        if rec["relu"]:
+            dy = self.version(p + ".dyb", dout)
+            self.op(B.OP_RELU_BWD, [rec["out"], dout], [dy], thread)
+        db = self.new(p + ".db", (L.K,), "f32")
+        self.op(B.OP_BIAS_BWD, [dy], [db], t_b,
+                B.op_attrs(ws=self.workspace(B.purine_bias_bwd_workspace_bytes(L.y_shape, _pcode(L.dtype)))))
+        dw = self.new(p + ".dw", L.w_shape, "f32")
+        ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT, desc, L.x_shape,
+                                                          L.w_shape, _pcode(L.dtype)))
+        self.op(B.OP_CONV_BWD_WEIGHT, [rec["x"], dy], [dw], t_w, B.op_attrs(conv=desc, ws=ws))
+        dx = None
+        if need_dx:
+            dx = self.new(p + ".dx", L.x_shape, L.dtype)
+            self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"]], [dx], thread, B.op_attrs(conv=desc))
+        rec.update(dy=dy, db=db, dw=dw, dx=dx)
+        return dx
+
+    def maxpool_forward(self, x, shape, dtype, window, stride, pad, prefix, thread=T_MAIN):
+        N, C, H, W = shape
+        P = (H + 2 * pad - window) // stride + 1
+        Q = (W + 2 * pad - window) // stride + 1
+        y = self.new(prefix + ".y", (N, C, P, Q), dtype)
+        arg = self.new(prefix + ".arg", (N, C, P, Q), "i32")
+        pd = B.pool_desc(window, stride, pad)
+        self.op(B.OP_MAXPOOL_FWD, [x], [y, arg], thread, B.op_attrs(pool=pd))
+        return y, dict(prefix=prefix, x=x, y=y, arg=arg, desc=pd, x_shape=shape, dtype=dtype)
+
+    def maxpool_backward(self, rec, dy, thread=T_MAIN):
+        dx = self.new(rec["prefix"] + ".dx", rec["x_shape"], rec["dtype"])
+        self.op(B.OP_MAXPOOL_BWD, [dy, rec["arg"]], [dx], thread, B.op_attrs(pool=rec["desc"]))
+        rec.update(dy=dy, dx=dx)
+        return dx
+
+    def run(self):
+        B.purine_graph_run(self.g)
+
+    def fire_log(self):
+        return B.purine_graph_fire_log(self.g)
+
+
+# ------------------------------------------------------------------------------------------------
+def _default_init(seed):
+    """Device-side seeded initialiser: x ~ U[0,1), w, b ~ N(0, 0.01), dy ~ U[-1,1)."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(int(seed))
+
+    def init(name, shape, dtype, kind):
+        if kind == "x":
+            t = torch.rand(shape, generator=gen, device="cuda", dtype=torch.float32)
+        elif kind == "dy":
+            t = torch.rand(shape, generator=gen, device="cuda", dtype=torch.float32) * 2 - 1
+        else:
+            t = torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32) * 0.01
+        return t.to(_tdtype(dtype)).contiguous()
+    return init
+
+
+def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True):
+    """Builds the bi-graph of config `cfg` (1..5). `batch` overrides the batch size (tests).
+    `init(name, shape, dtype, kind)` supplies source tensors (kind in x, w, b, dy); by default they
+    are drawn on the device from the seed. Returns the GraphBuilder; gb.run() performs one full
+    forward + backward step."""
+    init = init or _default_init(seed)
+    layers = [l.with_batch(batch) if batch else l for l in CONV_LAYERS[cfg]]
+    gb = GraphBuilder(inplace=inplace)
+    tw = T_WGRAD if multi_stream else T_MAIN
+    tb = T_BGRAD if multi_stream else T_MAIN
+
+    def src(name, shape, dtype, kind):
+        return gb.bind(name, init(name, tuple(shape), dtype, kind))
+
+    def params(L, p):
+        return src(p + ".w", L.w_shape, L.dtype, "w"), src(p + ".b", (L.K,), L.dtype, "b")
+
+    if cfg in (1, 5):
+        # independent layers, each with its own synthetic input and output gradient
+        for i, L in enumerate(layers):
+            p = L.name
+            th = (3 * i) if multi_stream else 0
+            x = src(p + ".x", L.x_shape, L.dtype, "x")
+            w, b = params(L, p)
+            out, rec = gb.conv_forward(L, x, w, b, p, relu=False, thread=th)
+            dy = src(p + ".dout", L.y_shape, L.dtype, "dy")
+            gb.conv_backward(rec, dy, thread=th, t_w=th + 1 if multi_stream else 0,
+                             t_b=th + 2 if multi_stream else 0)
+    elif cfg == 2:
+        L1, L2, L3 = layers
+        x = src("x", L1.x_shape, L1.dtype, "x")
+        recs = []
+        cur = x
+        for L, relu in ((L1, True), (L2, True), (L3, False)):
+            w, b = params(L, L.name)
+            cur, rec = gb.conv_forward(L, cur, w, b, L.name, relu)
+            recs.append(rec)
+        grad = src("dout", L3.y_shape, L3.dtype, "dy")
+        for rec in reversed(recs):
+            grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb)
+    elif cfg == 3:
+        b1, b2r, b2, b3r, b3, b4 = layers
+        N = b1.N
+        x = src("x", b1.x_shape, "f32", "x")
+        th = (lambda i: i) if multi_stream else (lambda i: 0)
+        P = {}
+        for L in layers:
+            P[L.name] = params(L, L.name)
+        o1, r1 = gb.conv_forward(b1, x, *P[b1.name], b1.name, True, th(0))
+        m2, r2r = gb.conv_forward(b2r, x, *P[b2r.name], b2r.name, True, th(1))
+        o2, r2 = gb.conv_forward(b2, m2, *P[b2.name], b2.name, True, th(1))
+        m3, r3r = gb.conv_forward(b3r, x, *P[b3r.name], b3r.name, True, th(2))
+        o3, r3 = gb.conv_forward(b3, m3, *P[b3.name], b3.name, True, th(2))
+        p4, rp = gb.maxpool_forward(x, b1.x_shape, "f32", 3, 1, 1, "pool", th(3))
+        o4, r4 = gb.conv_forward(b4, p4, *P[b4.name], b4.name, True, th(3))
+        cat = gb.new("cat", (N, 256, 28, 28), "f32")
+        gb.op(B.OP_CONCAT_FWD, [o1, o2, o3, o4], [cat], th(0))
+        dcat = src("dout", (N, 256, 28, 28), "f32", "dy")
+        d = [gb.new("d" + o, gb.t[o].shape, "f32") for o in (o1, o2, o3, o4)]
+        gb.op(B.OP_CONCAT_BWD, [dcat], d, th(0))
+        tw3 = 4 if multi_stream else 0
+        tb3 = 5 if multi_stream else 0
+        dx1 = gb.conv_backward(r1, d[0], th(0), tw3, tb3)
+        dm2 = gb.conv_backward(r2, d[1], th(1), tw3, tb3)
+        dx2 = gb.conv_backward(r2r, dm2, th(1), tw3, tb3)
+        dm3 = gb.conv_backward(r3, d[2], th(2), tw3, tb3)
+        dx3 = gb.conv_backward(r3r, dm3, th(2), tw3, tb3)
+        dp4 = gb.conv_backward(r4, d[3], th(3), tw3, tb3)
+        dx4 = gb.maxpool_backward(rp, dp4, th(3))
+        dx = gb.new("dx", b1.x_shape, "f32")
+        gb.op(B.OP_SUM, [dx1, dx2, dx3, dx4], [dx], th(0))     # gradient fan-in, fixed order
+        gb.pool_records = [rp]
+    elif cfg == 4:
+        c1, c2, c3, c4, c5 = layers
+        x = src("x", c1.x_shape, "f32", "x")
+        recs, pools = [], []
+        cur = x
+        for L, pool in ((c1, True), (c2, True), (c3, False), (c4, False), (c5, True)):
+            w, b = params(L, L.name)
+            cur, rec = gb.conv_forward(L, cur, w, b, L.name, True)
+            recs.append(rec)
+            if pool:
+                cur, prec = gb.maxpool_forward(cur, L.y_shape, "f32", 3, 2, 0, L.name + ".pool")
+                pools.append(prec)
+            else:
+                pools.append(None)
+        grad = src("dout", tuple(gb.t[cur].shape), "f32", "dy")
+        for rec, prec in zip(reversed(recs), reversed(pools)):
+            if prec is not None:
+                grad = gb.maxpool_backward(prec, grad)
+            grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb)
+        gb.pool_records = [p for p in pools if p is not None]
+    else:
+        raise ValueError("config must be 1..5")
+    B.purine_graph_validate(gb.g)
+    return gb
