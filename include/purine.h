@@ -69,6 +69,8 @@ typedef struct { int32_t window, stride, pad; } purine_pool_desc;
 typedef enum { PURINE_CONV_FWD = 0, PURINE_CONV_BWD_DATA = 1, PURINE_CONV_BWD_WEIGHT = 2 } purine_conv_pass;
 
 const char* purine_status_string(int status);
+/* Name of the HIP error behind the last PURINE_E_HIP returned to this host thread. */
+const char* purine_last_hip_error(void);
 
 /* y_dim = {N, K, P, Q} for x_dim = {N, C, H, W}, w_dim = {K, C, R, S}.
  * PURINE_E_SHAPE when channels disagree, an extent is < 1, or the padded input is smaller than the

@@ -8,6 +8,10 @@ library is missing, importing this module fails.
 import ctypes
 import os
 
+# PyTorch-ROCm ships its own HIP runtime; it must be in the process before our library is loaded
+# so that both resolve to that one runtime instance (two instances do not share a device context).
+import torch  # noqa: F401
+
 PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG, "libpurine_conv.so")
 
@@ -27,6 +31,8 @@ class PurineError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
         msg = _lib.purine_status_string(status).decode()
+        if status == -7:
+            msg += ": " + _lib.purine_last_hip_error().decode()
         super().__init__("%s: %s (%s)" % (where, STATUS.get(status, status), msg))
 
 
@@ -60,6 +66,7 @@ _i64p, _vp, _sz, _ip = _P(ctypes.c_int64), ctypes.c_void_p, ctypes.c_size_t, _P(
 
 _SIGS = {
     "purine_status_string": (ctypes.c_char_p, [ctypes.c_int]),
+    "purine_last_hip_error": (ctypes.c_char_p, []),
     "purine_conv_out_shape": (ctypes.c_int, [_D, _i64p, _i64p, _i64p]),
     "purine_conv_workspace_bytes": (_sz, [ctypes.c_int, _D, _i64p, _i64p, ctypes.c_int32]),
     "purine_bias_bwd_workspace_bytes": (_sz, [_i64p, ctypes.c_int32]),
@@ -179,6 +186,10 @@ def _ref(x):
 # ------------------------------------------------------------------ host-only entry points
 def purine_status_string(status):
     return _lib.purine_status_string(int(status)).decode()
+
+
+def purine_last_hip_error():
+    return _lib.purine_last_hip_error().decode()
 
 
 def purine_conv_out_shape(desc, x_shape, w_shape):

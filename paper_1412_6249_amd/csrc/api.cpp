@@ -82,6 +82,12 @@ int make_geom(const purine_conv_desc* d, const int64_t* xd, const int64_t* wd, c
 }  // namespace
 
 namespace purine {
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+int hip_status(hipError_t e) {
+    if (e == hipSuccess) return PURINE_OK;
+    g_last_hip_error = e;
+    return PURINE_E_HIP;
+}
 static thread_local KernelProbe g_probe{nullptr, nullptr};
 KernelProbe take_kernel_probe() {
     KernelProbe p = g_probe;
@@ -91,6 +97,8 @@ KernelProbe take_kernel_probe() {
 }  // namespace purine
 
 extern "C" {
+
+const char* purine_last_hip_error(void) { return hipGetErrorName(purine::g_last_hip_error); }
 
 void purine_set_kernel_probe(void* start_event, void* stop_event) {
     purine::g_probe = KernelProbe{(hipEvent_t)start_event, (hipEvent_t)stop_event};
@@ -160,7 +168,7 @@ int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const 
     if (overlaps(y, x) || overlaps(y, w)) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_pix(false, x->dtype, g, x->data, w->data, y->data, 0.0f,
                                    (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
@@ -177,7 +185,7 @@ int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
     if (overlaps(dx, dy) || overlaps(dx, w)) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_pix(true, dy->dtype, g, dy->data, w->data, dx->data, beta,
                                    (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
@@ -196,7 +204,7 @@ int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
     if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_wgrad(x->dtype, g, plan, x->data, dy->data, (float*)dw->data, beta, ws,
                                      (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_bias_fwd(const purine_tensor* b, purine_tensor* y, void* hip_stream) {
@@ -207,7 +215,7 @@ int purine_bias_fwd(const purine_tensor* b, purine_tensor* y, void* hip_stream) 
     if (overlaps(b, y)) return PURINE_E_LAYOUT;
     hipError_t e = launch_bias_fwd(y->dtype, b->data, y->data, (int)y->dim[0], (int)y->dim[1],
                                    (int)(y->dim[2] * y->dim[3]), (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_bias_bwd(const purine_tensor* dy, purine_tensor* db, float beta, void* ws,
@@ -223,7 +231,7 @@ int purine_bias_bwd(const purine_tensor* dy, purine_tensor* db, float beta, void
     if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
     hipError_t e = launch_bias_bwd(dy->dtype, dy->data, (float*)db->data, beta, N, K, PQ, plan, ws,
                                    (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_relu_fwd(const purine_tensor* x, purine_tensor* y, void* hip_stream) {
@@ -236,7 +244,7 @@ int purine_relu_fwd(const purine_tensor* x, purine_tensor* y, void* hip_stream) 
     if (!same_dims(x, y)) return PURINE_E_SHAPE;
     if (x->data != y->data && overlaps(x, y)) return PURINE_E_LAYOUT;
     hipError_t e = launch_relu_fwd(x->dtype, x->data, y->data, numel(x), (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tensor* dx,
@@ -252,7 +260,7 @@ int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tens
     if (dx->data != dy->data && overlaps(dx, dy)) return PURINE_E_LAYOUT;
     hipError_t e = launch_relu_bwd(x->dtype, x->data, dy->data, dx->data, numel(x),
                                    (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 static int pool_geom(const purine_pool_desc* d, const purine_tensor* x, const purine_tensor* y) {
@@ -280,7 +288,7 @@ int purine_maxpool_fwd(const purine_pool_desc* desc, const purine_tensor* x, pur
                                       (int)(x->dim[0] * x->dim[1]), (int)x->dim[2], (int)x->dim[3],
                                       (int)y->dim[2], (int)y->dim[3], desc->window, desc->stride,
                                       desc->pad, (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 int purine_maxpool_bwd(const purine_pool_desc* desc, const purine_tensor* dy,
@@ -297,7 +305,7 @@ int purine_maxpool_bwd(const purine_pool_desc* desc, const purine_tensor* dy,
                                       (int)(dx->dim[0] * dx->dim[1]), (int)dx->dim[2],
                                       (int)dx->dim[3], (int)dy->dim[2], (int)dy->dim[3],
                                       desc->window, desc->stride, desc->pad, (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 static int concat_check(const purine_tensor* const* parts, int n_parts, const purine_tensor* whole) {
@@ -330,7 +338,7 @@ int purine_concat_fwd(const purine_tensor* const* parts, int n_parts, purine_ten
         const int c = (int)parts[i]->dim[1];
         hipError_t e = launch_copy_channels(out->dtype, parts[i]->data, out->data, (int)out->dim[0], c,
                                             c, 0, (int)out->dim[1], c0, HW, (hipStream_t)hip_stream);
-        if (e != hipSuccess) return PURINE_E_HIP;
+        if (e != hipSuccess) return hip_status(e);
         c0 += c;
     }
     return PURINE_OK;
@@ -346,7 +354,7 @@ int purine_concat_bwd(const purine_tensor* dout, purine_tensor* const* dparts, i
         const int c = (int)dparts[i]->dim[1];
         hipError_t e = launch_copy_channels(dout->dtype, dout->data, dparts[i]->data, (int)dout->dim[0],
                                             c, (int)dout->dim[1], c0, c, 0, HW, (hipStream_t)hip_stream);
-        if (e != hipSuccess) return PURINE_E_HIP;
+        if (e != hipSuccess) return hip_status(e);
         c0 += c;
     }
     return PURINE_OK;
@@ -369,7 +377,7 @@ int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* ou
         ptrs[i] = terms[i]->data;
     }
     hipError_t e = launch_sum(out->dtype, ptrs, n_terms, out->data, numel(out), (hipStream_t)hip_stream);
-    return e == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+    return hip_status(e);
 }
 
 // Test hook for the host-side reciprocal division used by the kernels' index arithmetic.

@@ -84,6 +84,9 @@ struct BiasBwdPlan {
 };
 BiasBwdPlan plan_bias_bwd(int N, int K, int PQ);
 
+// Maps a HIP status to a purine status and remembers the HIP error for purine_last_hip_error().
+int hip_status(hipError_t e);
+
 // One-shot event pair that brackets the main kernel of the next operator call of this host thread.
 struct KernelProbe { hipEvent_t start, stop; };
 KernelProbe take_kernel_probe();   // returns the pending pair (or NULLs) and clears it
@@ -96,6 +99,9 @@ struct ProbeScope {                 // records start on construction and stop on
 // Kernel launchers (defined in the .hip files). Each returns a hipError_t from the launch.
 hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
                            const void* wt, void* out, float beta, hipStream_t st);
+bool conv_bwd_data_smallc_applies(const ConvGeom& g);
+hipError_t launch_conv_bwd_data_smallc(int dtype, const ConvGeom& g, const void* dy, const void* wt,
+                                       void* dx, float beta, hipStream_t st);
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
                              const void* dy, float* dw, float beta, void* ws, hipStream_t st);
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st);

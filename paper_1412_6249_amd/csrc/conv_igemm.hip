@@ -245,6 +245,7 @@ hipError_t launch_cfg(PixGemmParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     hipLaunchKernelGGL((igemm_pix_kernel<T, MODE, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
@@ -275,6 +276,8 @@ hipError_t dispatch_tile(PixGemmParams& p, hipStream_t st) {
 
 hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
                            const void* wt, void* out, float beta, hipStream_t st) {
+    if (bwd_data && conv_bwd_data_smallc_applies(g))
+        return launch_conv_bwd_data_smallc(dtype, g, in, wt, out, beta, st);
     PixGemmParams p{};
     p.in = in; p.wt = wt; p.out = out;
     p.N = g.N;

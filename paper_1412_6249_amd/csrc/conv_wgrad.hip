@@ -177,6 +177,7 @@ hipError_t launch_tile(WgradParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     hipLaunchKernelGGL((wgrad_kernel<T, TM, TN, WM, WN>), dim3((unsigned)total), dim3(WM * WN * 64),
                        0, st, p);
     return hipGetLastError();

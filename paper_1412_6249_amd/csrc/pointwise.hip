@@ -199,6 +199,7 @@ BiasBwdPlan plan_bias_bwd(int N, int K, int PQ) {
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st) {
     dim3 grid((unsigned)(N * K), blocks_for(PQ, 64));
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(bias_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)b, (float*)y, K, PQ),
              hipLaunchKernelGGL(bias_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)b, (uint16_t*)y, K, PQ));
@@ -211,6 +212,7 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
     float* partial = (float*)ws;
     {
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(bias_bwd_partial_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts),
              hipLaunchKernelGGL(bias_bwd_partial_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts));
@@ -225,6 +227,7 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
 hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st) {
     dim3 grid(blocks_for((size_t)n));
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, (size_t)n),
              hipLaunchKernelGGL(relu_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, (size_t)n));
@@ -235,6 +238,7 @@ hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, i
                            hipStream_t st) {
     dim3 grid(blocks_for((size_t)n));
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (const float*)dy, (float*)dx, (size_t)n),
              hipLaunchKernelGGL(relu_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (const uint16_t*)dy, (uint16_t*)dx, (size_t)n));
@@ -245,6 +249,7 @@ hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, i
                               int P, int Q, int k, int stride, int pad, hipStream_t st) {
     dim3 grid((unsigned)NC, blocks_for((size_t)P * Q, 64));
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, arg, H, W, P, Q, k, stride, pad),
              hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, arg, H, W, P, Q, k, stride, pad));
@@ -256,6 +261,7 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
                               hipStream_t st) {
     dim3 grid((unsigned)NC, blocks_for((size_t)H * W, 64));
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, beta, H, W, P, Q, k, stride, pad),
              hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, beta, H, W, P, Q, k, stride, pad));
@@ -267,6 +273,7 @@ hipError_t launch_copy_channels(int dtype, const void* src, void* dst, int N, in
                                 hipStream_t st) {
     dim3 grid(blocks_for((size_t)c_count * HW, 256), (unsigned)N);
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(copy_channels_kernel<float>, grid, dim3(TPB), 0, st, (const float*)src, (float*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW),
              hipLaunchKernelGGL(copy_channels_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)src, (uint16_t*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW));
@@ -280,6 +287,7 @@ hipError_t launch_sum(int dtype, const void* const* terms, int n_terms, void* ou
     for (int i = 0; i < n_terms; ++i) a.t[i] = terms[i];
     dim3 grid(blocks_for((size_t)n));
     ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(sum_kernel<float>, grid, dim3(TPB), 0, st, a, (float*)out, (size_t)n),
              hipLaunchKernelGGL(sum_kernel<uint16_t>, grid, dim3(TPB), 0, st, a, (uint16_t*)out, (size_t)n));

@@ -1,0 +1,101 @@
+"""Per-layer, per-operator timing of the conv-layer operators at the workload shapes.
+
+    python -m paper_1412_6249_amd.layer_bench --config 4 [--layer conv2] [--op fwd] [--iters 20]
+
+Each operator is launched alone on the current stream and bracketed with HIP events through the
+library's kernel probe, so the figure is the main kernel's duration (no concurrency, no launch gaps).
+Useful on its own and as the command to put after `rocprofv3 ... --` for counters of one kernel.
+"""
+import argparse
+import sys
+
+import torch
+
+from . import binding as B
+from synth.configs import CONV_LAYERS
+
+PEAK = {"f32": 157.3, "bf16": 2500.0}
+
+
+def time_op(fn, iters, warmup=3):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(iters)]
+    for i in range(iters):
+        starts[i].record()
+        stops[i].record()     # create the underlying hipEvent handles
+    torch.cuda.synchronize()
+    for i in range(iters):
+        B.purine_set_kernel_probe(starts[i].cuda_event, stops[i].cuda_event)
+        fn()
+    B.purine_set_kernel_probe(None, None)
+    torch.cuda.synchronize()
+    ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
+    return ms[len(ms) // 2], ms[0]
+
+
+def bench_layer(L, ops, iters, out=sys.stdout):
+    td = torch.bfloat16 if L.dtype == "bf16" else torch.float32
+    code = B.PURINE_BF16 if L.dtype == "bf16" else B.PURINE_F32
+    dev = "cuda:0"
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1412)
+    x = torch.rand(L.x_shape, generator=g, device=dev).to(td)
+    w = (torch.randn(L.w_shape, generator=g, device=dev) * 0.01).to(td)
+    b = (torch.randn((L.K,), generator=g, device=dev) * 0.01).to(td)
+    dy = (torch.rand(L.y_shape, generator=g, device=dev) * 2 - 1).to(td)
+    y = torch.empty(L.y_shape, dtype=td, device=dev)
+    dx = torch.empty(L.x_shape, dtype=td, device=dev)
+    dw = torch.empty(L.w_shape, dtype=torch.float32, device=dev)
+    db = torch.empty((L.K,), dtype=torch.float32, device=dev)
+    desc = B.conv_desc(L.stride, L.pad)
+    ws = torch.empty(max(256, B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT, desc, L.x_shape,
+                                                            L.w_shape, code)),
+                     dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(max(256, B.purine_bias_bwd_workspace_bytes(L.y_shape, code)), dtype=torch.uint8,
+                      device=dev)
+    table = {
+        "fwd": (lambda: B.purine_conv_fwd(desc, x, w, y), L.flop_per_pass),
+        "bwd_data": (lambda: B.purine_conv_bwd_data(desc, dy, w, dx), L.flop_per_pass),
+        "bwd_weight": (lambda: B.purine_conv_bwd_weight(desc, x, dy, dw, ws=ws), L.flop_per_pass),
+        "bias_fwd": (lambda: B.purine_bias_fwd(b, y), 0),
+        "bias_bwd": (lambda: B.purine_bias_bwd(dy, db, ws=ws2), 0),
+    }
+    results = {}
+    for name in ops:
+        fn, flop = table[name]
+        med, best = time_op(fn, iters)
+        tf = flop / (med * 1e-3) / 1e12 if flop else 0.0
+        results[name] = (med, tf)
+        if flop:
+            out.write("%-10s %-10s %9.4f ms (best %9.4f)  %8.2f TFLOP/s  %5.1f%% of %s MFMA peak\n"
+                      % (L.name, name, med, best, tf, 100 * tf / PEAK[L.dtype], L.dtype))
+        else:
+            nbytes = y.numel() * y.element_size() * (2 if name == "bias_fwd" else 1)
+            out.write("%-10s %-10s %9.4f ms (best %9.4f)  %8.1f GB/s\n"
+                      % (L.name, name, med, best, nbytes / (med * 1e-3) / 1e9))
+        out.flush()
+    return results
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=4)
+    ap.add_argument("--layer", default=None)
+    ap.add_argument("--op", default="all")
+    ap.add_argument("--iters", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=None)
+    a = ap.parse_args()
+    ops = ["fwd", "bwd_data", "bwd_weight", "bias_fwd", "bias_bwd"] if a.op == "all" else a.op.split(",")
+    for L in CONV_LAYERS[a.config]:
+        if a.layer and L.name != a.layer:
+            continue
+        if a.batch:
+            L = L.with_batch(a.batch)
+        bench_layer(L, ops, a.iters)
+
+
+if __name__ == "__main__":
+    main()

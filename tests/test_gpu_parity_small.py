@@ -28,6 +28,9 @@ CASES = [
     ("pad_bigger_than_needed", 1, 2, 5, 6, 3, 3, 3, (1, 1), (2, 2)),
     ("many_pixels", 5, 4, 37, 41, 8, 3, 3, (1, 1), (1, 1)),
     ("c200", 1, 200, 9, 9, 48, 3, 3, (1, 1), (1, 1)),
+    ("smallc_s3x2", 2, 2, 13, 17, 9, 4, 5, (3, 2), (1, 2)),
+    ("smallc_tiny_h", 1, 3, 2, 9, 4, 3, 3, (4, 2), (1, 1)),
+    ("smallc_s4_pad5", 2, 4, 21, 19, 6, 7, 6, (4, 4), (5, 4)),
 ]
 
 
