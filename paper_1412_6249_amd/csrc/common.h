@@ -39,14 +39,16 @@ __host__ __device__ inline uint32_t fastdiv(uint32_t n, const FastDiv& f) {
 struct PixGemmParams {
     const void* in;    // gathered activation tensor [N][Ci][Hi][Wi]
     const void* wt;    // filter tensor, always KCRS
-    void* out;         // produced tensor [N][Co][Ho][Wo]
+    void* out;         // produced tensor [N][Co][Ho][Wo] (phase-folded backward-data: dx [N][C][H][W])
     int N, Ci, Hi, Wi;
-    int Co, Ho, Wo;
+    int Co, Ho, Wo;              // GEMM rows and the pixel grid the columns enumerate
+    int C, H, W;                 // extents of the layer input (dx)
     int R, S, sh, sw, ph, pw;
-    int RS, Kg, M;               // Kg = Ci*R*S (reduction length), M = N*Ho*Wo (pixels)
+    int RS, Sp, Kg, M;           // taps per input channel of the reduction, its row length, Kg = Ci*RS, M = N*Ho*Wo
     int a_ci_stride, a_i_stride; // filter element of (i, ci, rs) sits at ci*a_ci_stride + i*a_i_stride + rs
     int HiWi, HoWo;
-    FastDiv div_rs, div_s, div_howo, div_wo, div_sh, div_sw;
+    int phases, hq_min, wq_min;  // phase-folded backward-data: sh*sw, first coarse row / column
+    FastDiv div_rs, div_s, div_howo, div_wo, div_phases, div_sw;
     float beta;
     int tiles_i, tiles_pix;
 };
@@ -99,9 +101,6 @@ struct ProbeScope {                 // records start on construction and stop on
 // Kernel launchers (defined in the .hip files). Each returns a hipError_t from the launch.
 hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
                            const void* wt, void* out, float beta, hipStream_t st);
-bool conv_bwd_data_smallc_applies(const ConvGeom& g);
-hipError_t launch_conv_bwd_data_smallc(int dtype, const ConvGeom& g, const void* dy, const void* wt,
-                                       void* dx, float beta, hipStream_t st);
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
                              const void* dy, float* dw, float beta, void* ws, hipStream_t st);
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st);

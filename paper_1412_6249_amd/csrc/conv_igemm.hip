@@ -36,8 +36,9 @@ template <> struct Elem<uint16_t> {  // bfloat16 bit patterns
     }
 };
 
-// MODE 0 = forward, MODE 1 = backward-data. Workgroup = WM x WN wavefronts, each owning TM x TN
-// MFMA tiles of 32 x 32.
+// MODE 0 = forward, MODE 1 = backward-data with unit stride, MODE 2 = backward-data with a stride
+// (phase-folded, see launch_conv_pix). Workgroup = WM x WN wavefronts, each owning TM x TN MFMA
+// tiles of 32 x 32.
 template <typename T, int MODE, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmParams p) {
     constexpr int NT = WM * WN * 64;
@@ -45,13 +46,13 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
     constexpr int BN = WN * TN * 32;
     constexpr int LDA = BM + 2;   // +2: the transposed filter-slab store hits distinct banks
     constexpr int LDB = BN;
-    static_assert(NT % BN == 0 || BN % NT == 0, "pixel mapping");
-    constexpr int B_COLS = BN > NT ? BN / NT : 1;      // pixel columns per thread
-    constexpr int B_RPP = BN > NT ? 1 : NT / BN;       // slab rows covered per pass
+    static_assert(NT % BN == 0 && NT >= BN, "one pixel column per thread");
+    constexpr int B_RPP = NT / BN;       // slab rows covered per pass
     constexpr int B_PASSES = BK / B_RPP;
     static_assert(BK % B_RPP == 0, "row mapping");
-    constexpr int A_RPP = NT / BK;                      // filter rows (channels) per pass
-    constexpr int A_PASSES = (BM + A_RPP - 1) / A_RPP;
+    constexpr int A_RPP = NT / BK;       // filter rows (channels) per pass
+    constexpr int A_PASSES = BM / A_RPP;
+    static_assert(BM % A_RPP == 0, "filter mapping");
 
     __shared__ float As[2][BK * LDA];
     __shared__ float Bs[2][BK * LDB];
@@ -76,54 +77,79 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
     const int i0 = (tile % p.tiles_i) * BM;
     const int j0 = (tile / p.tiles_i) * BN;
 
-    // ---- per-thread pixel bookkeeping for the gather (fixed for the whole kernel) ----
-    int g_base[B_COLS], g_h[B_COLS], g_w[B_COLS];
-    int g_hr[B_COLS], g_wr[B_COLS];   // backward-data with stride > 1: residues of (ho+ph), (wo+pw)
-#pragma unroll
-    for (int cidx = 0; cidx < B_COLS; ++cidx) {
-        const int pix = j0 + (tid % BN) + cidx * NT;
-        if (pix < p.M) {
-            const int n = fastdiv(pix, p.div_howo);
-            const int rem = pix - n * p.HoWo;
-            const int ho = fastdiv(rem, p.div_wo);
-            const int wo = rem - ho * p.Wo;
-            if (MODE == 0) {
-                g_h[cidx] = ho * p.sh - p.ph;
-                g_w[cidx] = wo * p.sw - p.pw;
-                g_hr[cidx] = g_wr[cidx] = 0;
-            } else {
-                const int th = ho + p.ph, tw = wo + p.pw;
-                g_h[cidx] = fastdiv(th, p.div_sh);
-                g_w[cidx] = fastdiv(tw, p.div_sw);
-                g_hr[cidx] = th - g_h[cidx] * p.sh;
-                g_wr[cidx] = tw - g_w[cidx] * p.sw;
-            }
-            g_base[cidx] = n * p.Ci * p.HiWi;
-        } else {
-            g_base[cidx] = -1;  // pixel beyond the tensor: contributes zeros
-            g_h[cidx] = g_w[cidx] = g_hr[cidx] = g_wr[cidx] = 0;
-        }
+    // ---- this thread's pixel column of the patch slab (fixed for the whole kernel) ----
+    // g_off: element offset of the tap (ci=0, r=0, s=0) of this pixel inside `in`; g_h/g_w: the
+    // coordinates that the bounds test compares against.
+    int g_off, g_h, g_w;
+    bool g_live;
+    {
+        const int pix = j0 + (tid % BN);
+        g_live = pix < p.M;
+        const int pc = g_live ? pix : 0;
+        const int n = fastdiv(pc, p.div_howo);
+        const int rem = pc - n * p.HoWo;
+        const int ho = fastdiv(rem, p.div_wo);
+        const int wo = rem - ho * p.Wo;
+        if (MODE == 0) { g_h = ho * p.sh - p.ph; g_w = wo * p.sw - p.pw; }   // hi = g_h + r
+        else if (MODE == 1) { g_h = ho + p.ph; g_w = wo + p.pw; }            // hi = g_h - r
+        else { g_h = ho + p.hq_min; g_w = wo + p.wq_min; }                   // hi = hq - r'
+        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;
     }
     const int b_row = __builtin_amdgcn_readfirstlane(tid / BN);  // uniform per wavefront (BN >= 64)
     const int a_kk = tid % BK;
     const int a_i = tid / BK;
 
+    // ---- this thread's rows of the filter slab ----
+    // a_base: offset of row i at (ci=0, r'=0, s'=0); MODE 2 also keeps the row's phase (a, b)
+    int a_base[A_PASSES], a_ab[A_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps) {
+        const int i = i0 + a_i + ps * A_RPP;
+        if (i < p.Co) {
+            if (MODE == 2) {
+                const int c = fastdiv(i, p.div_phases);
+                const int ab = i - c * p.phases;
+                const int a = fastdiv(ab, p.div_sw);
+                const int b = ab - a * p.sw;
+                a_base[ps] = c * p.R * p.S + a * p.S + b;
+                a_ab[ps] = (a << 16) | b;
+            } else {
+                a_base[ps] = i * p.a_i_stride;
+                a_ab[ps] = 0;
+            }
+        } else {
+            a_base[ps] = 0;
+            a_ab[ps] = -1;
+        }
+    }
+
     float a_reg[A_PASSES];
-    float b_reg[B_PASSES][B_COLS];
+    float b_reg[B_PASSES];
 
     auto load_slab = [&](int slab) {
         // filter slab: A[i, kk] for kk = slab*BK + a_kk
         {
             const int kk = slab * BK + a_kk;
             const bool kv = kk < p.Kg;
-            const int ci = fastdiv(kv ? kk : 0, p.div_rs);
-            const int rs = (kv ? kk : 0) - ci * p.RS;
-            const int base = ci * p.a_ci_stride + rs;
+            const int kq = kv ? kk : 0;
+            const int ci = fastdiv(kq, p.div_rs);
+            const int rs = kq - ci * p.RS;
+            if (MODE == 2) {
+                const int rp = fastdiv(rs, p.div_s);
+                const int sp = rs - rp * p.Sp;
+                const int r0 = rp * p.sh, s0 = sp * p.sw;     // tap of phase (0,0); row adds (a, b)
+                const int off = ci * p.a_ci_stride + r0 * p.S + s0;
 #pragma unroll
-            for (int ps = 0; ps < A_PASSES; ++ps) {
-                const int il = a_i + ps * A_RPP;
-                const int i = i0 + il;
-                a_reg[ps] = (kv && il < BM && i < p.Co) ? Elem<T>::load(wt, base + i * p.a_i_stride) : 0.0f;
+                for (int ps = 0; ps < A_PASSES; ++ps) {
+                    const int a = a_ab[ps] >> 16, b = a_ab[ps] & 0xffff;
+                    const bool ok = kv && a_ab[ps] >= 0 && r0 + a < p.R && s0 + b < p.S;
+                    a_reg[ps] = ok ? Elem<T>::load(wt, off + a_base[ps]) : 0.0f;
+                }
+            } else {
+                const int off = ci * p.a_ci_stride + rs;
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_reg[ps] = (kv && a_ab[ps] >= 0) ? Elem<T>::load(wt, off + a_base[ps]) : 0.0f;
             }
         }
         // patch slab: G[kk, pixel]; kk is uniform across the wavefront, so (ci, r, s) is scalar work
@@ -135,42 +161,22 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
             const int ci = fastdiv(kq, p.div_rs);
             const int rs = kq - ci * p.RS;
             const int r = fastdiv(rs, p.div_s);
-            const int s = rs - r * p.S;
-            int rq = 0, rr = 0, sq = 0, sr = 0;
-            if (MODE == 1) {
-                rq = fastdiv(r, p.div_sh); rr = r - rq * p.sh;
-                sq = fastdiv(s, p.div_sw); sr = s - sq * p.sw;
-            }
-            const int plane = ci * p.HiWi;
-#pragma unroll
-            for (int cidx = 0; cidx < B_COLS; ++cidx) {
-                int hi, wi;
-                bool ok = kv && g_base[cidx] >= 0;
-                if (MODE == 0) {
-                    hi = g_h[cidx] + r;
-                    wi = g_w[cidx] + s;
-                } else {
-                    hi = g_h[cidx] - rq;
-                    wi = g_w[cidx] - sq;
-                    ok = ok && g_hr[cidx] == rr && g_wr[cidx] == sr;
-                }
-                ok = ok && (unsigned)hi < (unsigned)p.Hi && (unsigned)wi < (unsigned)p.Wi;
-                b_reg[ps][cidx] = ok ? Elem<T>::load(in, g_base[cidx] + plane + hi * p.Wi + wi) : 0.0f;
-            }
+            const int s = rs - r * (MODE == 2 ? p.Sp : p.S);
+            const int tap = r * p.Wi + s;
+            int hi, wi, off;
+            if (MODE == 0) { hi = g_h + r; wi = g_w + s; off = ci * p.HiWi + tap; }
+            else           { hi = g_h - r; wi = g_w - s; off = ci * p.HiWi - tap; }
+            const bool ok = kv && g_live && (unsigned)hi < (unsigned)p.Hi && (unsigned)wi < (unsigned)p.Wi;
+            b_reg[ps] = ok ? Elem<T>::load(in, g_off + off) : 0.0f;
         }
     };
 
     auto store_slab = [&](int buf) {
 #pragma unroll
-        for (int ps = 0; ps < A_PASSES; ++ps) {
-            const int il = a_i + ps * A_RPP;
-            if (il < BM) As[buf][a_kk * LDA + il] = a_reg[ps];
-        }
+        for (int ps = 0; ps < A_PASSES; ++ps) As[buf][a_kk * LDA + a_i + ps * A_RPP] = a_reg[ps];
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
-#pragma unroll
-            for (int cidx = 0; cidx < B_COLS; ++cidx)
-                Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN) + cidx * NT] = b_reg[ps][cidx];
+            Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = b_reg[ps];
     };
 
     floatx16 acc[TM][TN];
@@ -220,19 +226,46 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
         if (pix >= p.M) continue;
         const int n = fastdiv(pix, p.div_howo);
         const int rem = pix - n * p.HoWo;
-        const int obase = n * p.Co * p.HoWo + rem;
+        if (MODE != 2) {
+            const int obase = n * p.Co * p.HoWo + rem;
 #pragma unroll
-        for (int a = 0; a < TM; ++a) {
+            for (int a = 0; a < TM; ++a)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                if (i < p.Co) {
-                    const int o = obase + i * p.HoWo;
-                    float v = acc[a][b][e];
-                    if (p.beta != 0.0f) v += Elem<T>::load(out, o);
-                    Elem<T>::store(out, o, v);
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                    if (i < p.Co) {
+                        const int o = obase + i * p.HoWo;
+                        float v = acc[a][b][e];
+                        if (p.beta != 0.0f) v += Elem<T>::load(out, o);
+                        Elem<T>::store(out, o, v);
+                    }
                 }
-            }
+        } else {
+            // depth-to-space: row i = (c, a, b) of pixel (n, hq, wq) is dx[n, c, hq*sh+a-ph, wq*sw+b-pw]
+            const int hq = fastdiv(rem, p.div_wo);
+            const int wq = rem - hq * p.Wo;
+            const int hb = (hq + p.hq_min) * p.sh - p.ph;
+            const int wb = (wq + p.wq_min) * p.sw - p.pw;
+            const int obase = n * p.C * p.H * p.W;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                    if (i < p.Co) {
+                        const int c = fastdiv(i, p.div_phases);
+                        const int ab = i - c * p.phases;
+                        const int pa = fastdiv(ab, p.div_sw);
+                        const int pb = ab - pa * p.sw;
+                        const int h = hb + pa, w = wb + pb;
+                        if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
+                            const int o = obase + (c * p.H + h) * p.W + w;
+                            float v = acc[a][b][e];
+                            if (p.beta != 0.0f) v += Elem<T>::load(out, o);
+                            Elem<T>::store(out, o, v);
+                        }
+                    }
+                }
         }
     }
 }
@@ -276,38 +309,63 @@ hipError_t dispatch_tile(PixGemmParams& p, hipStream_t st) {
 
 hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
                            const void* wt, void* out, float beta, hipStream_t st) {
-    if (bwd_data && conv_bwd_data_smallc_applies(g))
-        return launch_conv_bwd_data_smallc(dtype, g, in, wt, out, beta, st);
     PixGemmParams p{};
     p.in = in; p.wt = wt; p.out = out;
-    p.N = g.N;
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W;
     p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
     p.RS = g.R * g.S;
+    p.Sp = g.S;
+    p.phases = 1;
+    int mode = 0;
     if (!bwd_data) {
         p.Ci = g.C; p.Hi = g.H; p.Wi = g.W;
         p.Co = g.K; p.Ho = g.P; p.Wo = g.Q;
         p.a_ci_stride = p.RS;            // w[k][c][rs]: i = k, ci = c
         p.a_i_stride = g.C * p.RS;
-    } else {
+    } else if (g.sh == 1 && g.sw == 1) {
+        mode = 1;
         p.Ci = g.K; p.Hi = g.P; p.Wi = g.Q;
         p.Co = g.C; p.Ho = g.H; p.Wo = g.W;
         p.a_ci_stride = g.C * p.RS;      // w[k][c][rs]: i = c, ci = k
         p.a_i_stride = p.RS;
+    } else {
+        // Strided backward-data, phase-folded. Write h + ph = hq*sh + a and w + pw = wq*sw + b.
+        // Only taps r = a + sh*r', s = b + sw*s' reach such a position, from p = hq - r',
+        // q = wq - s'. So dx is a unit-stride correlation of dy with ceil(R/sh) x ceil(S/sw) taps that
+        // produces C*sh*sw "channels" (c, a, b) per coarse pixel (hq, wq), followed by a
+        // depth-to-space shuffle in the epilogue. No multiply is spent on the structural zeros of
+        // the strided transposed convolution, and the GEMM's row count grows from C to C*sh*sw.
+        mode = 2;
+        p.Ci = g.K; p.Hi = g.P; p.Wi = g.Q;
+        p.phases = g.sh * g.sw;
+        p.Co = g.C * p.phases;
+        p.hq_min = g.ph / g.sh;
+        p.wq_min = g.pw / g.sw;
+        p.Ho = (g.H - 1 + g.ph) / g.sh - p.hq_min + 1;
+        p.Wo = (g.W - 1 + g.pw) / g.sw - p.wq_min + 1;
+        const int Rp = (g.R + g.sh - 1) / g.sh;
+        p.Sp = (g.S + g.sw - 1) / g.sw;
+        p.RS = Rp * p.Sp;
+        p.a_ci_stride = g.C * g.R * g.S;
+        p.a_i_stride = 0;
     }
     p.Kg = p.Ci * p.RS;
     p.HiWi = p.Hi * p.Wi;
     p.HoWo = p.Ho * p.Wo;
     p.M = p.N * p.HoWo;
     p.div_rs = make_fastdiv(p.RS);
-    p.div_s = make_fastdiv(p.S);
+    p.div_s = make_fastdiv(mode == 2 ? p.Sp : p.S);
     p.div_howo = make_fastdiv(p.HoWo);
     p.div_wo = make_fastdiv(p.Wo);
-    p.div_sh = make_fastdiv(p.sh);
+    p.div_phases = make_fastdiv(p.phases);
     p.div_sw = make_fastdiv(p.sw);
     p.beta = beta;
-    if (dtype == PURINE_F32)
-        return bwd_data ? dispatch_tile<float, 1>(p, st) : dispatch_tile<float, 0>(p, st);
-    return bwd_data ? dispatch_tile<uint16_t, 1>(p, st) : dispatch_tile<uint16_t, 0>(p, st);
+    if (dtype == PURINE_F32) {
+        if (mode == 0) return dispatch_tile<float, 0>(p, st);
+        return mode == 1 ? dispatch_tile<float, 1>(p, st) : dispatch_tile<float, 2>(p, st);
+    }
+    if (mode == 0) return dispatch_tile<uint16_t, 0>(p, st);
+    return mode == 1 ? dispatch_tile<uint16_t, 1>(p, st) : dispatch_tile<uint16_t, 2>(p, st);
 }
 
 }  // namespace purine
