@@ -7,19 +7,21 @@
 
 namespace purine {
 
-// Division of 0 <= n < 2^31 by a divisor fixed on the host, done with one high multiply and a
-// shift (round-up reciprocal: m = ceil(2^(32+s)/d) with s = ceil(log2 d) - 1 fits 32 bits, and the
-// error term n*e/2^(32+s) stays below 1/d for every n < 2^31).
+// Division of 0 <= n < 2^31 by a divisor fixed on the host, done with one high multiply, one masked
+// add and a shift, with no branch (round-up reciprocal: m = ceil(2^(32+s)/d) with
+// s = ceil(log2 d) - 1 fits 32 bits, and the error term n*e/2^(32+s) stays below 1/d for every
+// n < 2^31; d = 1 has no such m, so it takes q = (0 + n) >> 0 through the add mask).
 struct FastDiv {
-    uint32_t d, m, s;
+    uint32_t m, s, add;
 };
 
 inline FastDiv make_fastdiv(uint32_t d) {
-    FastDiv f{d, 0u, 0u};
-    if (d <= 1) { f.d = 1; return f; }
+    FastDiv f{0u, 0u, 0xffffffffu};
+    if (d <= 1) return f;
     uint32_t l = 0;
     while ((1ull << l) < d) ++l;           // l = ceil(log2 d) >= 1
     f.s = l - 1;
+    f.add = 0u;
     const unsigned __int128 one = 1;
     const unsigned __int128 num = one << (32 + f.s);
     f.m = (uint32_t)((num + d - 1) / d);
@@ -28,9 +30,9 @@ inline FastDiv make_fastdiv(uint32_t d) {
 
 __host__ __device__ inline uint32_t fastdiv(uint32_t n, const FastDiv& f) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    return f.d == 1 ? n : (__umulhi(n, f.m) >> f.s);
+    return (__umulhi(n, f.m) + (n & f.add)) >> f.s;
 #else
-    return f.d == 1 ? n : (uint32_t)(((uint64_t)n * f.m) >> 32) >> f.s;
+    return ((uint32_t)(((uint64_t)n * f.m) >> 32) + (n & f.add)) >> f.s;
 #endif
 }
 

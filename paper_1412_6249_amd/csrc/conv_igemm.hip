@@ -123,10 +123,14 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
         }
     }
 
+    // staged slab: raw loaded values plus one validity bit per value (the zero-fill select is
+    // applied when the values go to LDS, so nothing forces an early wait on the loads)
     float a_reg[A_PASSES];
     float b_reg[B_PASSES];
+    unsigned a_ok, b_ok;
 
     auto load_slab = [&](int slab) {
+        a_ok = 0u; b_ok = 0u;
         // filter slab: A[i, kk] for kk = slab*BK + a_kk
         {
             const int kk = slab * BK + a_kk;
@@ -142,14 +146,18 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
 #pragma unroll
                 for (int ps = 0; ps < A_PASSES; ++ps) {
                     const int a = a_ab[ps] >> 16, b = a_ab[ps] & 0xffff;
-                    const bool ok = kv && a_ab[ps] >= 0 && r0 + a < p.R && s0 + b < p.S;
-                    a_reg[ps] = ok ? Elem<T>::load(wt, off + a_base[ps]) : 0.0f;
+                    const bool ok = kv & (a_ab[ps] >= 0) & (r0 + a < p.R) & (s0 + b < p.S);
+                    a_reg[ps] = Elem<T>::load(wt, ok ? off + a_base[ps] : 0);   // clamped, branch-free
+                    a_ok |= (ok ? 1u : 0u) << ps;
                 }
             } else {
                 const int off = ci * p.a_ci_stride + rs;
 #pragma unroll
-                for (int ps = 0; ps < A_PASSES; ++ps)
-                    a_reg[ps] = (kv && a_ab[ps] >= 0) ? Elem<T>::load(wt, off + a_base[ps]) : 0.0f;
+                for (int ps = 0; ps < A_PASSES; ++ps) {
+                    const bool ok = kv & (a_ab[ps] >= 0);
+                    a_reg[ps] = Elem<T>::load(wt, ok ? off + a_base[ps] : 0);
+                    a_ok |= (ok ? 1u : 0u) << ps;
+                }
             }
         }
         // patch slab: G[kk, pixel]; kk is uniform across the wavefront, so (ci, r, s) is scalar work
@@ -166,17 +174,21 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
             int hi, wi, off;
             if (MODE == 0) { hi = g_h + r; wi = g_w + s; off = ci * p.HiWi + tap; }
             else           { hi = g_h - r; wi = g_w - s; off = ci * p.HiWi - tap; }
-            const bool ok = kv && g_live && (unsigned)hi < (unsigned)p.Hi && (unsigned)wi < (unsigned)p.Wi;
-            b_reg[ps] = ok ? Elem<T>::load(in, g_off + off) : 0.0f;
+            // bitwise & on purpose: no short-circuit control flow inside the slab loop
+            const bool ok = kv & g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
+            // clamped index instead of a predicated load: keeps the loop one basic block
+            b_reg[ps] = Elem<T>::load(in, ok ? g_off + off : 0);
+            b_ok |= (ok ? 1u : 0u) << ps;
         }
     };
 
     auto store_slab = [&](int buf) {
 #pragma unroll
-        for (int ps = 0; ps < A_PASSES; ++ps) As[buf][a_kk * LDA + a_i + ps * A_RPP] = a_reg[ps];
+        for (int ps = 0; ps < A_PASSES; ++ps)
+            As[buf][a_kk * LDA + a_i + ps * A_RPP] = ((a_ok >> ps) & 1u) ? a_reg[ps] : 0.0f;
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
-            Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = b_reg[ps];
+            Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = ((b_ok >> ps) & 1u) ? b_reg[ps] : 0.0f;
     };
 
     floatx16 acc[TM][TN];
@@ -198,23 +210,30 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
 
     for (int slab = 0; slab < n_slabs; ++slab) {
         const int buf = slab & 1;
-        const bool more = slab + 1 < n_slabs;
-        if (more) load_slab(slab + 1);   // global loads in flight while the MFMAs below run
+        load_slab(slab + 1);   // global loads in flight while the MFMAs below run (past the end: zeros)
+        float av[2][TM], bv[2][TN];   // operand fragments, double-buffered across k-steps
+#pragma unroll
+        for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * LDA + a_off + a * 32];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * LDB + b_off + b * 32];
 #pragma unroll
         for (int ks = 0; ks < BK / 2; ++ks) {
-            const int row = 2 * ks + khalf;
-            float av[TM], bv[TN];
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < BK / 2) {
+                const int row = 2 * (ks + 1) + khalf;
 #pragma unroll
-            for (int a = 0; a < TM; ++a) av[a] = As[buf][row * LDA + a_off + a * 32];
+                for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * LDA + a_off + a * 32];
 #pragma unroll
-            for (int b = 0; b < TN; ++b) bv[b] = Bs[buf][row * LDB + b_off + b * 32];
+                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * LDB + b_off + b * 32];
+            }
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
         }
-        if (more) store_slab(buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the zero-fill selects (and their load waits) below the MFMAs
+        store_slab(buf ^ 1);
         __syncthreads();
     }
 
