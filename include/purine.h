@@ -79,8 +79,9 @@ int purine_conv_out_shape(const purine_conv_desc* desc, const int64_t x_dim[4],
                           const int64_t w_dim[4], int64_t y_dim[4]);
 
 /* Bytes of device scratch the given pass needs (0 when none). Returns 0 for illegal shapes: the
- * operator call itself reports the error. Forward and backward-data need none; backward-weight
- * needs room for its split-reduction partial sums. */
+ * operator call itself reports the error. Forward and backward-data keep a repacked, zero-padded
+ * copy of the filter there (none for a forward pass with fewer than 16 input channels);
+ * backward-weight keeps its split-reduction partial sums there. */
 size_t purine_conv_workspace_bytes(int pass, const purine_conv_desc* desc, const int64_t x_dim[4],
                                    const int64_t w_dim[4], int32_t dtype);
 size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype);
@@ -89,13 +90,14 @@ size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype);
 
 /* Conv: y[n,k,p,q] = sum_{c,r,s} x[n,c,p*sh-ph+r,q*sw-pw+s] * w[k,c,r,s], taps outside x are 0.
  * x, w, y share one dtype (F32 or BF16). The patch matrix is never written to memory.
- * ws may be NULL (this pass needs no scratch). y must not overlap x or w. */
+ * ws: scratch of at least purine_conv_workspace_bytes(PURINE_CONV_FWD, ...) bytes (may be NULL when
+ * that is 0); it must not overlap any tensor. y must not overlap x or w. */
 int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
                     purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream);
 
 /* ConvBwdData: dx[n,c,h,w] = beta*dx + sum over (k,r,s,p,q) with p*sh-ph+r = h, q*sw-pw+s = w of
  * dy[n,k,p,q] * w[k,c,r,s]. dy, w, dx share one dtype. dx's extents must be the x extents whose
- * forward output has dy's extents. */
+ * forward output has dy's extents. ws as for the forward pass (query with PURINE_CONV_BWD_DATA). */
 int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
                          const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
                          size_t ws_bytes, void* hip_stream);

@@ -140,11 +140,12 @@ int purine_conv_out_shape(const purine_conv_desc* desc, const int64_t x_dim[4],
 
 size_t purine_conv_workspace_bytes(int pass, const purine_conv_desc* desc, const int64_t x_dim[4],
                                    const int64_t w_dim[4], int32_t dtype) {
-    if (pass != PURINE_CONV_BWD_WEIGHT) return 0;
+    if (pass != PURINE_CONV_FWD && pass != PURINE_CONV_BWD_DATA && pass != PURINE_CONV_BWD_WEIGHT) return 0;
     if (!desc || !x_dim || !w_dim || !is_float_dtype(dtype)) return 0;
     ConvGeom g;
     if (make_geom(desc, x_dim, w_dim, nullptr, &g) != PURINE_OK) return 0;
-    return plan_wgrad(g, dtype).ws_bytes;
+    if (pass == PURINE_CONV_BWD_WEIGHT) return plan_wgrad(g, dtype).ws_bytes;
+    return plan_conv_pix(g, pass == PURINE_CONV_BWD_DATA, dtype).ws_bytes;
 }
 
 size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype) {
@@ -157,7 +158,6 @@ size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype) {
 
 int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
                     purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream) {
-    (void)ws; (void)ws_bytes;
     int rc;
     if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(w, 4)) ||
         (rc = check_tensor(y, 4)))
@@ -166,7 +166,10 @@ int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const 
     ConvGeom g;
     if ((rc = make_geom(desc, x->dim, w->dim, y->dim, &g))) return rc;
     if (overlaps(y, x) || overlaps(y, w)) return PURINE_E_LAYOUT;
-    hipError_t e = launch_conv_pix(false, x->dtype, g, x->data, w->data, y->data, 0.0f,
+    const PixPlan plan = plan_conv_pix(g, false, x->dtype);
+    if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
+    if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_conv_pix(x->dtype, g, plan, x->data, w->data, y->data, 0.0f, ws,
                                    (hipStream_t)hip_stream);
     return hip_status(e);
 }
@@ -174,7 +177,6 @@ int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const 
 int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
                          const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
                          size_t ws_bytes, void* hip_stream) {
-    (void)ws; (void)ws_bytes;
     int rc;
     if ((rc = check_desc(desc)) || (rc = check_tensor(dy, 4)) || (rc = check_tensor(w, 4)) ||
         (rc = check_tensor(dx, 4)) || (rc = check_beta(beta)))
@@ -183,7 +185,10 @@ int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
     ConvGeom g;
     if ((rc = make_geom(desc, dx->dim, w->dim, dy->dim, &g))) return rc;
     if (overlaps(dx, dy) || overlaps(dx, w)) return PURINE_E_LAYOUT;
-    hipError_t e = launch_conv_pix(true, dy->dtype, g, dy->data, w->data, dx->data, beta,
+    const PixPlan plan = plan_conv_pix(g, true, dy->dtype);
+    if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
+    if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_conv_pix(dy->dtype, g, plan, dy->data, w->data, dx->data, beta, ws,
                                    (hipStream_t)hip_stream);
     return hip_status(e);
 }

@@ -36,25 +36,6 @@ __host__ __device__ inline uint32_t fastdiv(uint32_t n, const FastDiv& f) {
 #endif
 }
 
-// Problem description handed to the pixel-major implicit GEMM (forward and backward-data):
-//   out[n, i, ho, wo] = sum over kk = (ci, r, s) of A[i, kk] * gather(in)[kk, (n, ho, wo)]
-struct PixGemmParams {
-    const void* in;    // gathered activation tensor [N][Ci][Hi][Wi]
-    const void* wt;    // filter tensor, always KCRS
-    void* out;         // produced tensor [N][Co][Ho][Wo] (phase-folded backward-data: dx [N][C][H][W])
-    int N, Ci, Hi, Wi;
-    int Co, Ho, Wo;              // GEMM rows and the pixel grid the columns enumerate
-    int C, H, W;                 // extents of the layer input (dx)
-    int R, S, sh, sw, ph, pw;
-    int RS, Sp, Kg, M;           // taps per input channel of the reduction, its row length, Kg = Ci*RS, M = N*Ho*Wo
-    int a_ci_stride, a_i_stride; // filter element of (i, ci, rs) sits at ci*a_ci_stride + i*a_i_stride + rs
-    int HiWi, HoWo;
-    int phases, hq_min, wq_min;  // phase-folded backward-data: sh*sw, first coarse row / column
-    FastDiv div_rs, div_s, div_howo, div_wo, div_phases, div_sw;
-    float beta;
-    int tiles_i, tiles_pix;
-};
-
 // Problem description of the weight-gradient implicit GEMM:
 //   partial[split][k][(c,r,s)] = sum over pixels (n,p,q) of the split of dy[n,k,p,q] * x[n,c,p*sh-ph+r,q*sw-pw+s]
 struct WgradParams {
@@ -68,9 +49,23 @@ struct WgradParams {
     int tiles_i, tiles_j, splits;
 };
 
+
 struct ConvGeom {
     int N, C, H, W, K, R, S, P, Q, sh, sw, ph, pw;
 };
+
+// Launch plan of the forward / backward-data implicit GEMM: same answer for the workspace query and
+// for the launch.
+struct PixPlan {
+    int mode;          // 0 forward, 1 backward-data with unit stride, 2 backward-data phase-folded
+    bool flat;         // forward with fewer than 16 input channels: flattened (c,r,s) reduction, no scratch
+    int bm, bn, tiles_i, tiles_pix;
+    int Co, Ci;        // GEMM rows and gathered channels
+    int Rt, St;        // taps of the reduction
+    int Ci_pad, i_pad; // extents of the repacked filter A[Rt*St][Ci_pad][i_pad]
+    size_t ws_bytes;   // scratch for the repacked filter
+};
+PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype);
 
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and
 // for the launch.
@@ -101,8 +96,8 @@ struct ProbeScope {                 // records start on construction and stop on
 };
 
 // Kernel launchers (defined in the .hip files). Each returns a hipError_t from the launch.
-hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
-                           const void* wt, void* out, float beta, hipStream_t st);
+hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& plan, const void* in,
+                           const void* wt, void* out, float beta, void* ws, hipStream_t st);
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
                              const void* dy, float* dw, float beta, void* ws, hipStream_t st);
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st);

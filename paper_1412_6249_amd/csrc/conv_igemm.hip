@@ -1,21 +1,35 @@
-// Pixel-major implicit-GEMM convolution for gfx950: forward and backward-data.
+// Pixel-major implicit-GEMM convolution for gfx950: the Conv and ConvBwdData operators of the
+// convolution layer (paper Figure 1(b)).
 //
-// Both passes of the convolution operators (paper Figure 1(b)) are the contraction
-//     out[n, i, ho, wo] = sum_{kk = (ci, r, s)} A[i, kk] * G[kk, (n, ho, wo)]
-// where G is the patch matrix of the gathered tensor. G is never stored in HBM: each workgroup
-// builds a BK x BN slab of it in LDS straight from the NCHW tensor (lanes run along pixels, so the
-// loads are coalesced along W), multiplies it with a BK x BM slab of the filter matrix on the
-// fp32 MFMA units, and keeps the BM x BN output tile in accumulator registers.
-//   forward       : in = x,  i = k (output channel), kk = (c, r, s), hi = ho*sh - ph + r
-//   backward-data : in = dy, i = c (input channel),  kk = (k, r, s), hi = (ho + ph - r)/sh if exact
-// MFMA operand roles: A rows = channels, B columns = pixels, so each accumulator register holds 32
-// consecutive pixels of one channel and the NCHW stores are 128-byte coalesced.
+// Both passes are the contraction
+//     out[n, i, ho, wo] = sum over taps (r, s) and gathered channels ci of
+//                         A[(r,s), ci, i] * in[n, ci, h(ho, r), w(wo, s)]
+// i.e. a GEMM whose B operand is the patch matrix of the gathered tensor. That matrix is never
+// stored in HBM: each workgroup builds a 16 x BN slab of it in LDS straight from the NCHW tensor
+// (lanes run along pixels, so loads are coalesced along W), multiplies it with a 16 x BM slab of
+// the filter matrix on the fp32 MFMA units and keeps the BM x BN output tile in accumulators.
+//
+//   forward                 : in = x,  i = k,       ci = c, h = ho*sh - ph + r
+//   backward-data, stride 1 : in = dy, i = c,       ci = k, h = ho + ph - r
+//   backward-data, strided  : in = dy, i = (c,a,b), ci = k, h = hq - r'   (phase-folded, below)
+//
+// The reduction runs tap-major: a slab is 16 consecutive channels ci of ONE tap (r, s). Within a
+// slab the bounds test and the tap offset are the same for all 16 rows, so a gathered element
+// costs one add and one load. The filter is first repacked (a tiny kernel, into caller scratch)
+// to A[(r,s)][ci][i], zero padded to whole slabs and tiles, which makes the filter slab a dense
+// block read with unconditional 16-byte loads. Layers with fewer than 16 gathered channels (the
+// first layer of a CNN, forward) would waste most of a slab, so they run a second kernel that
+// flattens (c, r, s) into one reduction index instead.
+//
+// MFMA operand roles: A rows = channels i, B columns = pixels, so each accumulator register holds
+// 32 consecutive pixels of one channel and the NCHW stores are 128-byte coalesced.
 #include "common.h"
 
 namespace purine {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 16;  // slab depth along the reduction
 
@@ -23,6 +37,9 @@ template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float* p, int i) { return p[i]; }
     static __device__ __forceinline__ void store(float* p, int i, float v) { p[i] = v; }
+    static __device__ __forceinline__ floatx4 load4(const float* p, int i) {
+        return *reinterpret_cast<const floatx4*>(p + i);
+    }
 };
 template <> struct Elem<uint16_t> {  // bfloat16 bit patterns
     static __device__ __forceinline__ float load(const uint16_t* p, int i) {
@@ -34,52 +51,127 @@ template <> struct Elem<uint16_t> {  // bfloat16 bit patterns
         if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) r = 0x7FC00000u;  // NaN
         p[i] = (uint16_t)(r >> 16);
     }
+    static __device__ __forceinline__ floatx4 load4(const uint16_t* p, int i) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p + i);
+        floatx4 o;
+        o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        return o;
+    }
 };
 
-// MODE 0 = forward, MODE 1 = backward-data with unit stride, MODE 2 = backward-data with a stride
-// (phase-folded, see launch_conv_pix). Workgroup = WM x WN wavefronts, each owning TM x TN MFMA
-// tiles of 32 x 32.
-template <typename T, int MODE, int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmParams p) {
+struct PixParams {
+    const void* in;     // gathered activation tensor [N][Ci][Hi][Wi]
+    const void* wt;     // tap kernel: repacked filter A[taps][Ci_pad][i_pad]; flat kernel: KCRS filter
+    void* out;          // produced tensor [N][Co][Ho][Wo] (depth-to-space epilogue: dx [N][C][H][W])
+    int N, Ci, Hi, Wi, HiWi;
+    int Co, Ho, Wo, HoWo, M;      // GEMM rows; pixel grid enumerated by the columns; M = N*Ho*Wo
+    int Rt, St;                   // taps of the reduction (ceil(R/sh) x ceil(S/sw) when phase-folded)
+    int Ci_pad, i_pad;            // padded extents of the repacked filter
+    int g_mul_h, g_mul_w, g_add_h, g_add_w;   // gather origin: g_h = ho*g_mul_h + g_add_h (same for w)
+    int C, H, W, sh, sw, ph, pw, phases, hq_min, wq_min;   // depth-to-space epilogue
+    int R, S, RS, Kg;             // flat kernel only: filter extents, Kg = Ci*R*S
+    FastDiv div_howo, div_wo, div_phases, div_sw, div_rs, div_s;
+    float beta;
+    int tiles_i, tiles_pix;
+};
+
+// Epilogue shared by both kernels. Accumulator register e of a 32x32 tile holds row
+// (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
+template <typename T, bool D2S, int TM, int TN>
+__device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
+                                           floatx16 (&acc)[TM][TN], int i_base, int pix_base,
+                                           int khalf) {
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int pix = pix_base + b * 32;
+        if (pix >= p.M) continue;
+        const int n = fastdiv(pix, p.div_howo);
+        const int rem = pix - n * p.HoWo;
+        if (!D2S) {
+            const int obase = n * p.Co * p.HoWo + rem;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                    if (i < p.Co) {
+                        const int o = obase + i * p.HoWo;
+                        float v = acc[a][b][e];
+                        if (p.beta != 0.0f) v += Elem<T>::load(out, o);
+                        Elem<T>::store(out, o, v);
+                    }
+                }
+        } else {
+            // depth-to-space: row i = (c, a, b) of coarse pixel (n, hq, wq) is
+            // dx[n, c, hq*sh + a - ph, wq*sw + b - pw]
+            const int hq = fastdiv(rem, p.div_wo);
+            const int wq = rem - hq * p.Wo;
+            const int hb = (hq + p.hq_min) * p.sh - p.ph;
+            const int wb = (wq + p.wq_min) * p.sw - p.pw;
+            const int obase = n * p.C * p.H * p.W;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                    if (i < p.Co) {
+                        const int c = fastdiv(i, p.div_phases);
+                        const int ab = i - c * p.phases;
+                        const int pa = fastdiv(ab, p.div_sw);
+                        const int pb = ab - pa * p.sw;
+                        const int h = hb + pa, w = wb + pb;
+                        if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
+                            const int o = obase + (c * p.H + h) * p.W + w;
+                            float v = acc[a][b][e];
+                            if (p.beta != 0.0f) v += Elem<T>::load(out, o);
+                            Elem<T>::store(out, o, v);
+                        }
+                    }
+                }
+        }
+    }
+}
+
+// Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). Give each
+// XCD a contiguous run of tiles so that neighbouring pixel tiles share halo rows in one L2.
+__device__ __forceinline__ int xcd_tile(int bid, int total) {
+    const int per = total >> 3;
+    return (per > 0 && bid < per * 8) ? (bid & 7) * per + (bid >> 3) : bid;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Tap-major kernel. MINUS: the gather walks backwards (h = g_h - r), as backward-data does.
+// D2S: depth-to-space epilogue of the phase-folded strided backward-data.
+// Workgroup = WM x WN wavefronts, each owning TM x TN MFMA tiles of 32 x 32.
+template <typename T, bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
     constexpr int BN = WN * TN * 32;
-    constexpr int LDA = BM + 2;   // +2: the transposed filter-slab store hits distinct banks
-    constexpr int LDB = BN;
-    static_assert(NT % BN == 0 && NT >= BN, "one pixel column per thread");
-    constexpr int B_RPP = NT / BN;       // slab rows covered per pass
+    static_assert(NT == 256 && NT % BN == 0, "one pixel column per thread");
+    constexpr int B_RPP = NT / BN;             // slab rows covered per pass
     constexpr int B_PASSES = BK / B_RPP;
-    static_assert(BK % B_RPP == 0, "row mapping");
-    constexpr int A_RPP = NT / BK;       // filter rows (channels) per pass
-    constexpr int A_PASSES = BM / A_RPP;
-    static_assert(BM % A_RPP == 0, "filter mapping");
+    constexpr int A_VEC = BK * BM / 4;         // 16-byte pieces of the filter slab
+    constexpr int A_ITERS = (A_VEC + NT - 1) / NT;
+    constexpr int A_CPR = BM / 4;              // pieces per slab row
 
-    __shared__ float As[2][BK * LDA];
-    __shared__ float Bs[2][BK * LDB];
+    __shared__ __attribute__((aligned(16))) float As[2][BK * BM];
+    __shared__ float Bs[2][BK * BN];
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
-    T* __restrict__ out = (T*)p.out;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    // Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). Give each
-    // XCD a contiguous run of tiles so that neighbouring pixel tiles share halo rows in one L2.
-    int tile = blockIdx.x;
-    {
-        const int total = p.tiles_i * p.tiles_pix;
-        const int per = total >> 3;
-        if (per > 0 && tile < per * 8) tile = (tile & 7) * per + (tile >> 3);
-    }
+    const int tile = xcd_tile(blockIdx.x, p.tiles_i * p.tiles_pix);
     const int i0 = (tile % p.tiles_i) * BM;
     const int j0 = (tile / p.tiles_i) * BN;
 
     // ---- this thread's pixel column of the patch slab (fixed for the whole kernel) ----
-    // g_off: element offset of the tap (ci=0, r=0, s=0) of this pixel inside `in`; g_h/g_w: the
-    // coordinates that the bounds test compares against.
     int g_off, g_h, g_w;
     bool g_live;
     {
@@ -90,77 +182,186 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
         const int rem = pc - n * p.HoWo;
         const int ho = fastdiv(rem, p.div_wo);
         const int wo = rem - ho * p.Wo;
-        if (MODE == 0) { g_h = ho * p.sh - p.ph; g_w = wo * p.sw - p.pw; }   // hi = g_h + r
-        else if (MODE == 1) { g_h = ho + p.ph; g_w = wo + p.pw; }            // hi = g_h - r
-        else { g_h = ho + p.hq_min; g_w = wo + p.wq_min; }                   // hi = hq - r'
-        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;
+        g_h = ho * p.g_mul_h + p.g_add_h;
+        g_w = wo * p.g_mul_w + p.g_add_w;
+        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;   // tap (0,0) of channel 0
     }
     const int b_row = __builtin_amdgcn_readfirstlane(tid / BN);  // uniform per wavefront (BN >= 64)
+
+    // filter slab pieces served by this thread: element offset inside a slab, and LDS slot
+    int a_src[A_ITERS], a_dst[A_ITERS];
+#pragma unroll
+    for (int it = 0; it < A_ITERS; ++it) {
+        const int f = tid + it * NT;
+        const int row = f / A_CPR, col = (f - row * A_CPR) * 4;
+        a_src[it] = (f < A_VEC) ? row * p.i_pad + i0 + col : -1;
+        a_dst[it] = row * BM + col;
+    }
+
+    floatx4 a_reg[A_ITERS];
+    float b_reg[B_PASSES];
+    bool b_ok;
+
+    // scalar walk over the slabs: tap (nx_r, nx_s), first channel nx_c0 of the next slab to load
+    int nx_r = 0, nx_s = 0, nx_c0 = 0;
+    auto load_slab = [&]() {
+        const int tap = nx_r * p.St + nx_s;
+        const int a_slab = (tap * p.Ci_pad + nx_c0) * p.i_pad;
+#pragma unroll
+        for (int it = 0; it < A_ITERS; ++it)
+            if (a_src[it] >= 0) a_reg[it] = Elem<T>::load4(wt, a_slab + a_src[it]);
+        const int hi = MINUS ? g_h - nx_r : g_h + nx_r;
+        const int wi = MINUS ? g_w - nx_s : g_w + nx_s;
+        const int tap_off = nx_r * p.Wi + nx_s;
+        b_ok = g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
+        const int base = b_ok ? (MINUS ? g_off - tap_off : g_off + tap_off) : 0;
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps) {
+            const int ci = nx_c0 + ps * B_RPP + b_row;
+            // rows past Ci (padding of the last slab of a tap) read channel 0 and are zeroed at the store
+            const int plane = (b_ok & (ci < p.Ci)) ? ci * p.HiWi : 0;
+            b_reg[ps] = Elem<T>::load(in, base + plane);
+        }
+        // advance to the next slab (past the last one it wraps to the start; those values are unused)
+        nx_c0 += BK;
+        const bool wrap_c = nx_c0 >= p.Ci_pad;
+        nx_c0 = wrap_c ? 0 : nx_c0;
+        nx_s += wrap_c ? 1 : 0;
+        const bool wrap_s = nx_s >= p.St;
+        nx_s = wrap_s ? 0 : nx_s;
+        nx_r += wrap_s ? 1 : 0;
+        nx_r = nx_r >= p.Rt ? 0 : nx_r;
+    };
+    auto store_slab = [&](int buf, int c0) {
+#pragma unroll
+        for (int it = 0; it < A_ITERS; ++it)
+            if (a_src[it] >= 0) *reinterpret_cast<floatx4*>(&As[buf][a_dst[it]]) = a_reg[it];
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps) {
+            const bool ok = b_ok & (c0 + ps * B_RPP + b_row < p.Ci);
+            Bs[buf][(ps * B_RPP + b_row) * BN + (tid % BN)] = ok ? b_reg[ps] : 0.0f;
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
+    const int n_slabs = p.Rt * p.St * (p.Ci_pad / BK);
+    load_slab();
+    store_slab(0, 0);
+    int st_c0 = BK >= p.Ci_pad ? 0 : BK;   // first channel of the slab staged in registers next
+    __syncthreads();
+
+    const int a_off = wm * TM * 32 + (lane & 31);
+    const int b_off = wn * TN * 32 + (lane & 31);
+    const int khalf = lane >> 5;
+
+    for (int slab = 0; slab < n_slabs; ++slab) {
+        const int buf = slab & 1;
+        load_slab();   // global loads of the next slab fly while the MFMAs below run
+        float av[2][TM], bv[2][TN];   // operand fragments, double-buffered across k-steps
+#pragma unroll
+        for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * BM + a_off + a * 32];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * BN + b_off + b * 32];
+#pragma unroll
+        for (int ks = 0; ks < BK / 2; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < BK / 2) {
+                const int row = 2 * (ks + 1) + khalf;
+#pragma unroll
+                for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * BM + a_off + a * 32];
+#pragma unroll
+                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * BN + b_off + b * 32];
+            }
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS stores (and their load waits) below the MFMAs
+        store_slab(buf ^ 1, st_c0);
+        st_c0 += BK;
+        st_c0 = st_c0 >= p.Ci_pad ? 0 : st_c0;
+        __syncthreads();
+    }
+
+    store_tile<T, D2S, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Flat kernel: forward pass of layers with fewer than 16 input channels. The reduction index is
+// kk = (c, r, s) flattened, which equals the memory order of one filter row, and each slab row
+// decodes its own (c, r, s) on the scalar unit (rows are uniform per wavefront).
+template <typename T, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParams p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = WM * TM * 32;
+    constexpr int BN = WN * TN * 32;
+    constexpr int LDA = BM + 2;   // +2: the transposed filter-slab store hits distinct banks
+    static_assert(NT == 256 && NT % BN == 0, "one pixel column per thread");
+    constexpr int B_RPP = NT / BN;
+    constexpr int B_PASSES = BK / B_RPP;
+    constexpr int A_RPP = NT / BK;
+    constexpr int A_PASSES = BM / A_RPP;
+    static_assert(BM % A_RPP == 0, "filter mapping");
+
+    __shared__ float As[2][BK * LDA];
+    __shared__ float Bs[2][BK * BN];
+
+    const T* __restrict__ in = (const T*)p.in;
+    const T* __restrict__ wt = (const T*)p.wt;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int tile = xcd_tile(blockIdx.x, p.tiles_i * p.tiles_pix);
+    const int i0 = (tile % p.tiles_i) * BM;
+    const int j0 = (tile / p.tiles_i) * BN;
+
+    int g_off, g_h, g_w;
+    bool g_live;
+    {
+        const int pix = j0 + (tid % BN);
+        g_live = pix < p.M;
+        const int pc = g_live ? pix : 0;
+        const int n = fastdiv(pc, p.div_howo);
+        const int rem = pc - n * p.HoWo;
+        const int ho = fastdiv(rem, p.div_wo);
+        const int wo = rem - ho * p.Wo;
+        g_h = ho * p.g_mul_h + p.g_add_h;
+        g_w = wo * p.g_mul_w + p.g_add_w;
+        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;
+    }
+    const int b_row = __builtin_amdgcn_readfirstlane(tid / BN);
     const int a_kk = tid % BK;
     const int a_i = tid / BK;
 
-    // ---- this thread's rows of the filter slab ----
-    // a_base: offset of row i at (ci=0, r'=0, s'=0); MODE 2 also keeps the row's phase (a, b)
-    int a_base[A_PASSES], a_ab[A_PASSES];
-#pragma unroll
-    for (int ps = 0; ps < A_PASSES; ++ps) {
-        const int i = i0 + a_i + ps * A_RPP;
-        if (i < p.Co) {
-            if (MODE == 2) {
-                const int c = fastdiv(i, p.div_phases);
-                const int ab = i - c * p.phases;
-                const int a = fastdiv(ab, p.div_sw);
-                const int b = ab - a * p.sw;
-                a_base[ps] = c * p.R * p.S + a * p.S + b;
-                a_ab[ps] = (a << 16) | b;
-            } else {
-                a_base[ps] = i * p.a_i_stride;
-                a_ab[ps] = 0;
-            }
-        } else {
-            a_base[ps] = 0;
-            a_ab[ps] = -1;
-        }
-    }
-
-    // staged slab: raw loaded values plus one validity bit per value (the zero-fill select is
-    // applied when the values go to LDS, so nothing forces an early wait on the loads)
     float a_reg[A_PASSES];
     float b_reg[B_PASSES];
-    unsigned a_ok, b_ok;
+    unsigned a_ok, b_ok;   // one validity bit per staged value; the zero-fill happens at the LDS store
 
     auto load_slab = [&](int slab) {
         a_ok = 0u; b_ok = 0u;
-        // filter slab: A[i, kk] for kk = slab*BK + a_kk
         {
             const int kk = slab * BK + a_kk;
             const bool kv = kk < p.Kg;
-            const int kq = kv ? kk : 0;
-            const int ci = fastdiv(kq, p.div_rs);
-            const int rs = kq - ci * p.RS;
-            if (MODE == 2) {
-                const int rp = fastdiv(rs, p.div_s);
-                const int sp = rs - rp * p.Sp;
-                const int r0 = rp * p.sh, s0 = sp * p.sw;     // tap of phase (0,0); row adds (a, b)
-                const int off = ci * p.a_ci_stride + r0 * p.S + s0;
 #pragma unroll
-                for (int ps = 0; ps < A_PASSES; ++ps) {
-                    const int a = a_ab[ps] >> 16, b = a_ab[ps] & 0xffff;
-                    const bool ok = kv & (a_ab[ps] >= 0) & (r0 + a < p.R) & (s0 + b < p.S);
-                    a_reg[ps] = Elem<T>::load(wt, ok ? off + a_base[ps] : 0);   // clamped, branch-free
-                    a_ok |= (ok ? 1u : 0u) << ps;
-                }
-            } else {
-                const int off = ci * p.a_ci_stride + rs;
-#pragma unroll
-                for (int ps = 0; ps < A_PASSES; ++ps) {
-                    const bool ok = kv & (a_ab[ps] >= 0);
-                    a_reg[ps] = Elem<T>::load(wt, ok ? off + a_base[ps] : 0);
-                    a_ok |= (ok ? 1u : 0u) << ps;
-                }
+            for (int ps = 0; ps < A_PASSES; ++ps) {
+                const int i = i0 + a_i + ps * A_RPP;
+                const bool ok = kv & (i < p.Co);
+                a_reg[ps] = Elem<T>::load(wt, ok ? i * p.Kg + kk : 0);   // clamped, branch-free
+                a_ok |= (ok ? 1u : 0u) << ps;
             }
         }
-        // patch slab: G[kk, pixel]; kk is uniform across the wavefront, so (ci, r, s) is scalar work
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
             const int kk = slab * BK + ps * B_RPP + b_row;
@@ -169,26 +370,21 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
             const int ci = fastdiv(kq, p.div_rs);
             const int rs = kq - ci * p.RS;
             const int r = fastdiv(rs, p.div_s);
-            const int s = rs - r * (MODE == 2 ? p.Sp : p.S);
-            const int tap = r * p.Wi + s;
-            int hi, wi, off;
-            if (MODE == 0) { hi = g_h + r; wi = g_w + s; off = ci * p.HiWi + tap; }
-            else           { hi = g_h - r; wi = g_w - s; off = ci * p.HiWi - tap; }
+            const int s = rs - r * p.S;
+            const int hi = g_h + r, wi = g_w + s;
             // bitwise & on purpose: no short-circuit control flow inside the slab loop
             const bool ok = kv & g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
-            // clamped index instead of a predicated load: keeps the loop one basic block
-            b_reg[ps] = Elem<T>::load(in, ok ? g_off + off : 0);
+            b_reg[ps] = Elem<T>::load(in, ok ? g_off + ci * p.HiWi + r * p.Wi + s : 0);
             b_ok |= (ok ? 1u : 0u) << ps;
         }
     };
-
     auto store_slab = [&](int buf) {
 #pragma unroll
         for (int ps = 0; ps < A_PASSES; ++ps)
             As[buf][a_kk * LDA + a_i + ps * A_RPP] = ((a_ok >> ps) & 1u) ? a_reg[ps] : 0.0f;
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
-            Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = ((b_ok >> ps) & 1u) ? b_reg[ps] : 0.0f;
+            Bs[buf][(ps * B_RPP + b_row) * BN + (tid % BN)] = ((b_ok >> ps) & 1u) ? b_reg[ps] : 0.0f;
     };
 
     floatx16 acc[TM][TN];
@@ -210,12 +406,12 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
 
     for (int slab = 0; slab < n_slabs; ++slab) {
         const int buf = slab & 1;
-        load_slab(slab + 1);   // global loads in flight while the MFMAs below run (past the end: zeros)
-        float av[2][TM], bv[2][TN];   // operand fragments, double-buffered across k-steps
+        load_slab(slab + 1);   // past the end: every value is masked to zero
+        float av[2][TM], bv[2][TN];
 #pragma unroll
         for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * LDA + a_off + a * 32];
 #pragma unroll
-        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * LDB + b_off + b * 32];
+        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * BN + b_off + b * 32];
 #pragma unroll
         for (int ks = 0; ks < BK / 2; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
@@ -224,7 +420,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
 #pragma unroll
                 for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * LDA + a_off + a * 32];
 #pragma unroll
-                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * LDB + b_off + b * 32];
+                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * BN + b_off + b * 32];
             }
 #pragma unroll
             for (int a = 0; a < TM; ++a)
@@ -232,121 +428,164 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_pix_kernel(const PixGemmPa
                 for (int b = 0; b < TN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
         }
-        __builtin_amdgcn_sched_barrier(0);   // keep the zero-fill selects (and their load waits) below the MFMAs
+        __builtin_amdgcn_sched_barrier(0);
         store_slab(buf ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue: accumulator register e of a 32x32 tile holds row (e/4)*8 + (lane/32)*4 + e%4,
-    //      column lane%32 ----
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-        const int pix = j0 + b_off + b * 32;
-        if (pix >= p.M) continue;
-        const int n = fastdiv(pix, p.div_howo);
-        const int rem = pix - n * p.HoWo;
-        if (MODE != 2) {
-            const int obase = n * p.Co * p.HoWo + rem;
-#pragma unroll
-            for (int a = 0; a < TM; ++a)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                    if (i < p.Co) {
-                        const int o = obase + i * p.HoWo;
-                        float v = acc[a][b][e];
-                        if (p.beta != 0.0f) v += Elem<T>::load(out, o);
-                        Elem<T>::store(out, o, v);
-                    }
-                }
-        } else {
-            // depth-to-space: row i = (c, a, b) of pixel (n, hq, wq) is dx[n, c, hq*sh+a-ph, wq*sw+b-pw]
-            const int hq = fastdiv(rem, p.div_wo);
-            const int wq = rem - hq * p.Wo;
-            const int hb = (hq + p.hq_min) * p.sh - p.ph;
-            const int wb = (wq + p.wq_min) * p.sw - p.pw;
-            const int obase = n * p.C * p.H * p.W;
-#pragma unroll
-            for (int a = 0; a < TM; ++a)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                    if (i < p.Co) {
-                        const int c = fastdiv(i, p.div_phases);
-                        const int ab = i - c * p.phases;
-                        const int pa = fastdiv(ab, p.div_sw);
-                        const int pb = ab - pa * p.sw;
-                        const int h = hb + pa, w = wb + pb;
-                        if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
-                            const int o = obase + (c * p.H + h) * p.W + w;
-                            float v = acc[a][b][e];
-                            if (p.beta != 0.0f) v += Elem<T>::load(out, o);
-                            Elem<T>::store(out, o, v);
-                        }
-                    }
-                }
+    store_tile<T, false, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Filter repack: A[tap][ci][i] with zero padding, from the KCRS filter.
+//   mode 0 (forward)        : tap = (r, s),   ci = c, i = k
+//   mode 1 (bwd, stride 1)  : tap = (r, s),   ci = k, i = c
+//   mode 2 (bwd, strided)   : tap = (r', s'), ci = k, i = (c, a, b) -> w[k, c, a + sh*r', b + sw*s']
+struct RepackParams {
+    const void* w; void* a;
+    int mode, K, C, R, S, sh, sw, St, Ci, Co, Ci_pad, i_pad, total;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q) {
+    const T* __restrict__ w = (const T*)q.w;
+    T* __restrict__ a = (T*)q.a;
+    for (int o = blockIdx.x * 256 + threadIdx.x; o < q.total; o += gridDim.x * 256) {
+        const int i = o % q.i_pad;
+        const int t = o / q.i_pad;
+        const int ci = t % q.Ci_pad;
+        const int tap = t / q.Ci_pad;
+        const int tr = tap / q.St, ts = tap - tr * q.St;
+        T v = (T)0;
+        if (i < q.Co && ci < q.Ci) {
+            int k, c, r, s;
+            if (q.mode == 0) { k = i; c = ci; r = tr; s = ts; }
+            else if (q.mode == 1) { k = ci; c = i; r = tr; s = ts; }
+            else {
+                const int ph = q.sh * q.sw;
+                c = i / ph;
+                const int ab = i - c * ph;
+                const int pa = ab / q.sw, pb = ab - pa * q.sw;
+                k = ci; r = pa + q.sh * tr; s = pb + q.sw * ts;
+            }
+            if (r < q.R && s < q.S) v = w[((k * q.C + c) * q.R + r) * q.S + s];
         }
+        a[o] = v;
     }
 }
 
-template <typename T, int MODE, int TM, int TN, int WM, int WN>
-hipError_t launch_cfg(PixGemmParams& p, hipStream_t st) {
-    constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-    p.tiles_i = (p.Co + BM - 1) / BM;
-    p.tiles_pix = (p.M + BN - 1) / BN;
+// ------------------------------------------------------------------------------------------------
+struct TileCfg { int bm, bn; float eff; };
+constexpr TileCfg kTiles[] = {
+    {128, 128, 1.00f}, {96, 256, 1.00f}, {96, 128, 0.95f}, {64, 256, 0.95f}, {128, 64, 0.90f},
+    {64, 128, 0.90f},  {32, 256, 0.85f}, {64, 64, 0.80f},  {32, 128, 0.75f},
+};
+
+template <typename T, bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+hipError_t launch_tap(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_pix_kernel<T, MODE, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <typename T, int MODE>
-hipError_t dispatch_tile(PixGemmParams& p, hipStream_t st) {
-    // Channel-tile extent: the candidate (128, 96, 64, 32) that wastes the fewest padded rows,
-    // larger on ties. Pixel-tile extent: 256 while that still leaves >= 2 workgroups per CU.
-    const int cands[4] = {128, 96, 64, 32};
-    int bm = 32;
-    long long best = -1;
-    for (int c : cands) {
-        const long long padded = (long long)((p.Co + c - 1) / c) * c;
-        if (best < 0 || padded < best) { best = padded; bm = c; }
+template <typename T, int TM, int TN, int WM, int WN>
+hipError_t launch_flat(PixParams& p, hipStream_t st) {
+    const long long total = (long long)p.tiles_i * p.tiles_pix;
+    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
+    hipLaunchKernelGGL((igemm_flat_kernel<T, TM, TN, WM, WN>), dim3((unsigned)total),
+                       dim3(WM * WN * 64), 0, st, p);
+    return hipGetLastError();
+}
+
+#define TILE_SWITCH(CALL)                                              \
+    switch (bm * 1000 + bn) {                                          \
+        case 128128: return CALL(2, 2, 2, 2);                          \
+        case 96256:  return CALL(3, 2, 1, 4);                          \
+        case 96128:  return CALL(3, 1, 1, 4);                          \
+        case 64256:  return CALL(2, 2, 1, 4);                          \
+        case 128064: return CALL(1, 2, 4, 1);                          \
+        case 64128:  return CALL(2, 1, 1, 4);                          \
+        case 32256:  return CALL(1, 2, 1, 4);                          \
+        case 64064:  return CALL(1, 1, 2, 2);                          \
+        case 32128:  return CALL(1, 1, 1, 4);                          \
+        default: return hipErrorInvalidValue;                          \
     }
-    const long long tiles256 = (long long)((p.Co + bm - 1) / bm) * ((p.M + 255) / 256);
-    const bool wide = tiles256 >= 512;
-    switch (bm) {
-        case 128: return launch_cfg<T, MODE, 2, 2, 2, 2>(p, st);
-        case 96:  return wide ? launch_cfg<T, MODE, 3, 2, 1, 4>(p, st) : launch_cfg<T, MODE, 3, 1, 1, 4>(p, st);
-        case 64:  return wide ? launch_cfg<T, MODE, 2, 2, 1, 4>(p, st) : launch_cfg<T, MODE, 2, 1, 1, 4>(p, st);
-        default:  return wide ? launch_cfg<T, MODE, 1, 2, 1, 4>(p, st) : launch_cfg<T, MODE, 1, 1, 1, 4>(p, st);
-    }
+
+template <typename T, bool MINUS, bool D2S>
+hipError_t dispatch_tap(PixParams& p, int bm, int bn, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_tap<T, MINUS, D2S, TM, TN, WM, WN>(p, st)
+    TILE_SWITCH(CALL)
+#undef CALL
+}
+template <typename T>
+hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_flat<T, TM, TN, WM, WN>(p, st)
+    TILE_SWITCH(CALL)
+#undef CALL
 }
 
 }  // namespace
 
-hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const void* in,
-                           const void* wt, void* out, float beta, hipStream_t st) {
-    PixGemmParams p{};
-    p.in = in; p.wt = wt; p.out = out;
-    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W;
-    p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
-    p.RS = g.R * g.S;
-    p.Sp = g.S;
-    p.phases = 1;
-    int mode = 0;
+// Tile choice: every workgroup costs bm*bn/eff, where eff discounts the smaller tiles for their extra
+// operand traffic per MFMA; the busiest of the 256 CUs gets ceil(workgroups/256) of them. Pick the
+// tile that minimises that CU's load (padding waste is part of it, through the tile counts).
+PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype) {
+    PixPlan pl{};
+    const int elem = dtype == PURINE_BF16 ? 2 : 4;
+    int Co, Ci;
+    long long M;
     if (!bwd_data) {
-        p.Ci = g.C; p.Hi = g.H; p.Wi = g.W;
-        p.Co = g.K; p.Ho = g.P; p.Wo = g.Q;
-        p.a_ci_stride = p.RS;            // w[k][c][rs]: i = k, ci = c
-        p.a_i_stride = g.C * p.RS;
+        pl.mode = 0; Co = g.K; Ci = g.C; M = (long long)g.N * g.P * g.Q;
+        pl.Rt = g.R; pl.St = g.S;
     } else if (g.sh == 1 && g.sw == 1) {
-        mode = 1;
-        p.Ci = g.K; p.Hi = g.P; p.Wi = g.Q;
-        p.Co = g.C; p.Ho = g.H; p.Wo = g.W;
-        p.a_ci_stride = g.C * p.RS;      // w[k][c][rs]: i = c, ci = k
-        p.a_i_stride = p.RS;
+        pl.mode = 1; Co = g.C; Ci = g.K; M = (long long)g.N * g.H * g.W;
+        pl.Rt = g.R; pl.St = g.S;
+    } else {
+        pl.mode = 2; Co = g.C * g.sh * g.sw; Ci = g.K;
+        const int Hq = (g.H - 1 + g.ph) / g.sh - g.ph / g.sh + 1;
+        const int Wq = (g.W - 1 + g.pw) / g.sw - g.pw / g.sw + 1;
+        M = (long long)g.N * Hq * Wq;
+        pl.Rt = (g.R + g.sh - 1) / g.sh; pl.St = (g.S + g.sw - 1) / g.sw;
+    }
+    pl.flat = !bwd_data && Ci < BK;
+    double best = -1.0;
+    for (const TileCfg& t : kTiles) {
+        const long long ti = (Co + t.bm - 1) / t.bm, tp = (M + t.bn - 1) / t.bn;
+        const long long wgs = ti * tp;
+        const double load = (double)((wgs + 255) / 256) * t.bm * t.bn / t.eff;
+        if (best < 0 || load < best) { best = load; pl.bm = t.bm; pl.bn = t.bn; }
+    }
+    pl.Co = Co; pl.Ci = Ci;
+    pl.tiles_i = (Co + pl.bm - 1) / pl.bm;
+    pl.tiles_pix = (int)((M + pl.bn - 1) / pl.bn);
+    pl.Ci_pad = (Ci + BK - 1) / BK * BK;
+    pl.i_pad = pl.tiles_i * pl.bm;
+    pl.ws_bytes = pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * pl.i_pad * elem;
+    return pl;
+}
+
+hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, const void* in,
+                           const void* wt, void* out, float beta, void* ws, hipStream_t st) {
+    PixParams p{};
+    p.in = in; p.out = out;
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+    p.R = g.R; p.S = g.S; p.RS = g.R * g.S;
+    p.Ci = pl.Ci; p.Co = pl.Co; p.Rt = pl.Rt; p.St = pl.St;
+    p.Ci_pad = pl.Ci_pad; p.i_pad = pl.i_pad;
+    p.phases = 1;
+    if (pl.mode == 0) {
+        p.Hi = g.H; p.Wi = g.W; p.Ho = g.P; p.Wo = g.Q;
+        p.g_mul_h = g.sh; p.g_mul_w = g.sw; p.g_add_h = -g.ph; p.g_add_w = -g.pw;
+    } else if (pl.mode == 1) {
+        p.Hi = g.P; p.Wi = g.Q; p.Ho = g.H; p.Wo = g.W;
+        p.g_mul_h = 1; p.g_mul_w = 1; p.g_add_h = g.ph; p.g_add_w = g.pw;
     } else {
         // Strided backward-data, phase-folded. Write h + ph = hq*sh + a and w + pw = wq*sw + b.
         // Only taps r = a + sh*r', s = b + sw*s' reach such a position, from p = hq - r',
@@ -354,37 +593,58 @@ hipError_t launch_conv_pix(bool bwd_data, int dtype, const ConvGeom& g, const vo
         // produces C*sh*sw "channels" (c, a, b) per coarse pixel (hq, wq), followed by a
         // depth-to-space shuffle in the epilogue. No multiply is spent on the structural zeros of
         // the strided transposed convolution, and the GEMM's row count grows from C to C*sh*sw.
-        mode = 2;
-        p.Ci = g.K; p.Hi = g.P; p.Wi = g.Q;
+        p.Hi = g.P; p.Wi = g.Q;
         p.phases = g.sh * g.sw;
-        p.Co = g.C * p.phases;
-        p.hq_min = g.ph / g.sh;
-        p.wq_min = g.pw / g.sw;
+        p.hq_min = g.ph / g.sh; p.wq_min = g.pw / g.sw;
         p.Ho = (g.H - 1 + g.ph) / g.sh - p.hq_min + 1;
         p.Wo = (g.W - 1 + g.pw) / g.sw - p.wq_min + 1;
-        const int Rp = (g.R + g.sh - 1) / g.sh;
-        p.Sp = (g.S + g.sw - 1) / g.sw;
-        p.RS = Rp * p.Sp;
-        p.a_ci_stride = g.C * g.R * g.S;
-        p.a_i_stride = 0;
+        p.g_mul_h = 1; p.g_mul_w = 1; p.g_add_h = p.hq_min; p.g_add_w = p.wq_min;
     }
-    p.Kg = p.Ci * p.RS;
     p.HiWi = p.Hi * p.Wi;
     p.HoWo = p.Ho * p.Wo;
     p.M = p.N * p.HoWo;
-    p.div_rs = make_fastdiv(p.RS);
-    p.div_s = make_fastdiv(mode == 2 ? p.Sp : p.S);
+    p.Kg = p.Ci * p.RS;
     p.div_howo = make_fastdiv(p.HoWo);
     p.div_wo = make_fastdiv(p.Wo);
     p.div_phases = make_fastdiv(p.phases);
     p.div_sw = make_fastdiv(p.sw);
+    p.div_rs = make_fastdiv(p.RS);
+    p.div_s = make_fastdiv(p.S);
     p.beta = beta;
-    if (dtype == PURINE_F32) {
-        if (mode == 0) return dispatch_tile<float, 0>(p, st);
-        return mode == 1 ? dispatch_tile<float, 1>(p, st) : dispatch_tile<float, 2>(p, st);
+    p.tiles_i = pl.tiles_i; p.tiles_pix = pl.tiles_pix;
+
+    if (pl.flat) {
+        p.wt = wt;
+        return dtype == PURINE_F32 ? dispatch_flat<float>(p, pl.bm, pl.bn, st)
+                                   : dispatch_flat<uint16_t>(p, pl.bm, pl.bn, st);
     }
-    if (mode == 0) return dispatch_tile<uint16_t, 0>(p, st);
-    return mode == 1 ? dispatch_tile<uint16_t, 1>(p, st) : dispatch_tile<uint16_t, 2>(p, st);
+    // repack the filter into scratch, then run the tap-major kernel on it
+    RepackParams q{};
+    q.w = wt; q.a = ws; q.mode = pl.mode;
+    q.K = g.K; q.C = g.C; q.R = g.R; q.S = g.S; q.sh = g.sh; q.sw = g.sw;
+    q.St = pl.St; q.Ci = pl.Ci; q.Co = pl.Co; q.Ci_pad = pl.Ci_pad; q.i_pad = pl.i_pad;
+    const long long total = (long long)pl.Rt * pl.St * pl.Ci_pad * pl.i_pad;
+    if (total > 0x7fffffffLL) return hipErrorInvalidValue;
+    q.total = (int)total;
+    {
+        const unsigned blocks = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+        (void)hipGetLastError();
+        if (dtype == PURINE_F32)
+            hipLaunchKernelGGL(repack_filter_kernel<float>, dim3(blocks), dim3(256), 0, st, q);
+        else
+            hipLaunchKernelGGL(repack_filter_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, q);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    p.wt = ws;
+    if (dtype == PURINE_F32) {
+        if (pl.mode == 0) return dispatch_tap<float, false, false>(p, pl.bm, pl.bn, st);
+        if (pl.mode == 1) return dispatch_tap<float, true, false>(p, pl.bm, pl.bn, st);
+        return dispatch_tap<float, true, true>(p, pl.bm, pl.bn, st);
+    }
+    if (pl.mode == 0) return dispatch_tap<uint16_t, false, false>(p, pl.bm, pl.bn, st);
+    if (pl.mode == 1) return dispatch_tap<uint16_t, true, false>(p, pl.bm, pl.bn, st);
+    return dispatch_tap<uint16_t, true, true>(p, pl.bm, pl.bn, st);
 }
 
 }  // namespace purine

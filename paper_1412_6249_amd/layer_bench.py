@@ -56,9 +56,13 @@ def bench_layer(L, ops, iters, out=sys.stdout):
                      dtype=torch.uint8, device=dev)
     ws2 = torch.empty(max(256, B.purine_bias_bwd_workspace_bytes(L.y_shape, code)), dtype=torch.uint8,
                       device=dev)
+    wsf = torch.empty(max(256, B.purine_conv_workspace_bytes(B.PURINE_CONV_FWD, desc, L.x_shape, L.w_shape,
+                                                             code)), dtype=torch.uint8, device=dev)
+    wsd = torch.empty(max(256, B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_DATA, desc, L.x_shape,
+                                                             L.w_shape, code)), dtype=torch.uint8, device=dev)
     table = {
-        "fwd": (lambda: B.purine_conv_fwd(desc, x, w, y), L.flop_per_pass),
-        "bwd_data": (lambda: B.purine_conv_bwd_data(desc, dy, w, dx), L.flop_per_pass),
+        "fwd": (lambda: B.purine_conv_fwd(desc, x, w, y, ws=wsf), L.flop_per_pass),
+        "bwd_data": (lambda: B.purine_conv_bwd_data(desc, dy, w, dx, ws=wsd), L.flop_per_pass),
         "bwd_weight": (lambda: B.purine_conv_bwd_weight(desc, x, dy, dw, ws=ws), L.flop_per_pass),
         "bias_fwd": (lambda: B.purine_bias_fwd(b, y), 0),
         "bias_bwd": (lambda: B.purine_bias_bwd(dy, db, ws=ws2), 0),

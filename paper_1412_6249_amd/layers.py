@@ -77,7 +77,9 @@ class GraphBuilder:
         """x -> Conv -> Bias [-> ReLU]; returns the name of the layer output vertex."""
         desc = B.conv_desc(L.stride, L.pad)
         y0 = self.new(prefix + ".y", L.y_shape, L.dtype)
-        self.op(B.OP_CONV_FWD, [x, w], [y0], thread, B.op_attrs(conv=desc))
+        ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_FWD, desc, L.x_shape, L.w_shape,
+                                                          _pcode(L.dtype)))
+        self.op(B.OP_CONV_FWD, [x, w], [y0], thread, B.op_attrs(conv=desc, ws=ws))
         # Bias is in place by definition of the operator (y += b)
         if self.inplace:
             y1 = self.bind(prefix + ".yb", self.t[y0])
@@ -114,7 +116,9 @@ class GraphBuilder:
         dx = None
         if need_dx:
             dx = self.new(p + ".dx", L.x_shape, L.dtype)
-            self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"]], [dx], thread, B.op_attrs(conv=desc))
+            ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_DATA, desc, L.x_shape,
+                                                              L.w_shape, _pcode(L.dtype)))
+            self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"]], [dx], thread, B.op_attrs(conv=desc, ws=ws))
         rec.update(dy=dy, db=db, dw=dw, dx=dx)
         return dx
 

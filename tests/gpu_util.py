@@ -65,9 +65,12 @@ def run_layer(x, w, b, dy, stride, pad, dtype="f32", beta=0.0, prev=None):
     ws = workspace(pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT, desc, x.shape, w.shape,
                                                   pcode(dtype)))
     ws2 = workspace(pa.purine_bias_bwd_workspace_bytes(dy.shape, pcode(dtype)))
-    pa.purine_conv_fwd(desc, tx, tw, ty)
+    wsf = workspace(pa.purine_conv_workspace_bytes(pa.PURINE_CONV_FWD, desc, x.shape, w.shape, pcode(dtype)))
+    wsd = workspace(pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_DATA, desc, x.shape, w.shape,
+                                                   pcode(dtype)))
+    pa.purine_conv_fwd(desc, tx, tw, ty, ws=wsf)
     pa.purine_bias_fwd(tb, ty)
-    pa.purine_conv_bwd_data(desc, tdy, tw, tdx, beta=beta)
+    pa.purine_conv_bwd_data(desc, tdy, tw, tdx, beta=beta, ws=wsd)
     pa.purine_conv_bwd_weight(desc, tx, tdy, tdw, beta=beta, ws=ws)
     pa.purine_bias_bwd(tdy, tdb, beta=beta, ws=ws2)
     torch.cuda.synchronize()

@@ -89,8 +89,13 @@ def test_workspace_queries():
         for l in layers:
             d = pa.conv_desc(l.stride, l.pad)
             dt = pa.PURINE_F32 if l.dtype == "f32" else pa.PURINE_BF16
-            assert pa.purine_conv_workspace_bytes(pa.PURINE_CONV_FWD, d, l.x_shape, l.w_shape, dt) == 0
-            assert pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_DATA, d, l.x_shape, l.w_shape, dt) == 0
+            esz = 4 if l.dtype == "f32" else 2
+            fwd = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_FWD, d, l.x_shape, l.w_shape, dt)
+            bwd = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_DATA, d, l.x_shape, l.w_shape, dt)
+            w_bytes = esz * int(np.prod(l.w_shape))
+            # a zero-padded copy of the filter: at least its size, never absurdly more
+            assert (fwd == 0 and l.C < 16) or w_bytes <= fwd <= 8 * w_bytes + (1 << 16)
+            assert w_bytes <= bwd <= 24 * w_bytes + (1 << 16)
             nbytes = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT, d, l.x_shape, l.w_shape, dt)
             dw_bytes = 4 * int(np.prod(l.w_shape))
             assert nbytes >= dw_bytes and nbytes % dw_bytes == 0      # whole partial copies of dw
@@ -124,6 +129,7 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_conv_fwd, d, x, w, binding.raw_desc(fake, F32, (2, 4, 8, 8)), stream=s) == -4  # y aliases x
     assert status(pa.purine_conv_fwd, pa.conv_desc(0, 1), x, w, y, stream=s) == -8
     assert status(pa.purine_conv_bwd_data, d, y, w, x, beta=0.5, stream=s) == -8
+    assert status(pa.purine_conv_bwd_data, d, y, w, x, stream=s) == -5                # no workspace
     dw = binding.raw_desc(fake + 0x300000, F32, (4, 3, 3, 3))
     assert status(pa.purine_conv_bwd_weight, d, x, y, dw, stream=s) == -5            # no workspace
     assert status(pa.purine_conv_bwd_weight, d, x, y, binding.raw_desc(fake + 0x300000, BF16, (4, 3, 3, 3)), stream=s) == -3
