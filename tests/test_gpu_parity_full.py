@@ -1,0 +1,67 @@
+"""GPU parity at the FULL workload shapes (configs 2-5, every conv layer), in the launch
+configuration bench.py times, on outputs the oracle can compute one by one:
+  - forward (+bias) and backward-data: whole images, sampled by seed (these passes are independent
+    per image, so an image of the batch is an exact sub-problem);
+  - backward-weight: sampled elements of dw, each summed by the oracle over the whole batch;
+  - bias gradient: all of it.
+Tolerance: relative L2 <= 1e-5 (fp32), <= 1e-2 (bf16 in, fp32 accumulate), over each sample."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from synth.configs import CONV_LAYERS
+
+pytestmark = pytest.mark.gpu
+
+CASES = [(cfg, i) for cfg in (2, 3, 4, 5) for i in range(len(CONV_LAYERS[cfg]))]
+
+
+@pytest.mark.parametrize("cfg,idx", CASES, ids=["cfg%d_%s" % (c, CONV_LAYERS[c][i].name) for c, i in CASES])
+def test_full_shape_layer(cfg, idx):
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import rel_l2, TOL, to_host, pcode, tdtype, workspace, DEV
+
+    L = CONV_LAYERS[cfg][idx]
+    print("full-shape parity", cfg, L, file=sys.stderr, flush=True)
+    td = tdtype(L.dtype)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(14126249 * 1000 + 100 * cfg + idx)
+    x = torch.rand(L.x_shape, generator=g, device=DEV).to(td)
+    w = (torch.randn(L.w_shape, generator=g, device=DEV) * 0.01).to(td)
+    b = (torch.randn((L.K,), generator=g, device=DEV) * 0.01).to(td)
+    dy = (torch.rand(L.y_shape, generator=g, device=DEV) * 2 - 1).to(td)
+    y = torch.empty(L.y_shape, dtype=td, device=DEV)
+    dx = torch.empty(L.x_shape, dtype=td, device=DEV)
+    dw = torch.empty(L.w_shape, dtype=torch.float32, device=DEV)
+    db = torch.empty((L.K,), dtype=torch.float32, device=DEV)
+    desc = pa.conv_desc(L.stride, L.pad)
+    code = pcode(L.dtype)
+    q = lambda which: workspace(pa.purine_conv_workspace_bytes(which, desc, L.x_shape, L.w_shape, code))
+    pa.purine_conv_fwd(desc, x, w, y, ws=q(pa.PURINE_CONV_FWD))
+    pa.purine_bias_fwd(b, y)
+    pa.purine_conv_bwd_data(desc, dy, w, dx, ws=q(pa.PURINE_CONV_BWD_DATA))
+    pa.purine_conv_bwd_weight(desc, x, dy, dw, ws=q(pa.PURINE_CONV_BWD_WEIGHT))
+    pa.purine_bias_bwd(dy, db, ws=workspace(pa.purine_bias_bwd_workspace_bytes(L.y_shape, code)))
+    torch.cuda.synchronize()
+
+    tol = TOL[L.dtype]
+    rs = np.random.default_rng(1000 * cfg + idx)
+    imgs = sorted(rs.choice(L.N, size=2, replace=False).tolist() + [L.N - 1])
+    hw, hb = to_host(w), to_host(b)
+    hx_s, hdy_s = to_host(x[imgs]), to_host(dy[imgs])
+    ref_y = oracle.bias_fwd(oracle.conv_fwd(hx_s, hw, L.stride, L.pad), hb)
+    assert rel_l2(to_host(y[imgs]), ref_y) <= tol, ("fwd", rel_l2(to_host(y[imgs]), ref_y))
+    ref_dx = oracle.conv_bwd_data(hdy_s, hw, hx_s.shape, L.stride, L.pad)
+    assert rel_l2(to_host(dx[imgs]), ref_dx) <= tol, ("bwd_data", rel_l2(to_host(dx[imgs]), ref_dx))
+    del hx_s, hdy_s
+    hx, hdy = to_host(x), to_host(dy)
+    n_w = int(np.prod(L.w_shape))
+    flat = np.unique(np.concatenate([rs.integers(0, n_w, size=48), [0, n_w - 1]]))
+    ref_dw = oracle.conv_bwd_weight_at(hx, hdy, L.w_shape, flat, L.stride, L.pad)
+    got_dw = dw.cpu().numpy().ravel()[flat]
+    assert rel_l2(got_dw, ref_dw) <= tol, ("bwd_weight", rel_l2(got_dw, ref_dw))
+    ref_db = oracle.bias_bwd(hdy)
+    assert rel_l2(db.cpu().numpy(), ref_db) <= tol, ("bias_bwd", rel_l2(db.cpu().numpy(), ref_db))
