@@ -161,15 +161,36 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
     }
 }
 
-// dw[i] = beta*dw[i] + partial[0][i] + partial[1][i] + ... in split order.
+// dw[i] = beta*dw[i] + partial[0][i] + partial[1][i] + ... summed in a fixed tree: a workgroup owns
+// 16 consecutive elements; each of its 16 "split lanes" adds the partials s = lane, lane+16, ... in
+// order (independent loads, so many are in flight), and the 16 lane sums are then added in lane
+// order through LDS. The order never depends on timing, so the result is bit-identical run to run.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial,
                                                            float* __restrict__ dw, int n,
                                                            int splits, float beta) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    float acc = beta != 0.0f ? dw[i] : 0.0f;
-    for (int s = 0; s < splits; ++s) acc += partial[(size_t)s * n + i];
-    dw[i] = acc;
+    __shared__ float red[16][17];
+    const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
+    const int i = blockIdx.x * 16 + e;
+    float acc = 0.0f;
+    if (i < n) {
+        int s = sl;
+        for (; s + 48 < splits; s += 64) {
+            const float v0 = partial[(size_t)s * n + i];
+            const float v1 = partial[(size_t)(s + 16) * n + i];
+            const float v2 = partial[(size_t)(s + 32) * n + i];
+            const float v3 = partial[(size_t)(s + 48) * n + i];
+            acc += v0; acc += v1; acc += v2; acc += v3;
+        }
+        for (; s < splits; s += 16) acc += partial[(size_t)s * n + i];
+    }
+    red[sl][e] = acc;
+    __syncthreads();
+    if (sl == 0 && i < n) {
+        float t = beta != 0.0f ? dw[i] : 0.0f;
+#pragma unroll
+        for (int l = 0; l < 16; ++l) t += red[l][e];
+        dw[i] = t;
+    }
 }
 
 template <typename T, int TM, int TN, int WM, int WN>
@@ -210,10 +231,11 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     pl.tiles_i = (g.K + pl.bm - 1) / pl.bm;
     pl.tiles_j = (int)((CRS + pl.bn - 1) / pl.bn);
     const long long tiles = (long long)pl.tiles_i * pl.tiles_j;
-    // enough workgroups to cover the 256 CUs a few times over, chunks no shorter than 128 pixels,
-    // and no longer than 8192 so that one fp32 accumulation chain stays short
-    long long splits = (1024 + tiles - 1) / tiles;
-    const long long max_splits = (M + 127) / 128;
+    // enough workgroups for about three per CU, chunks no shorter than 256 pixels (a short chunk is
+    // mostly prologue and epilogue) and no longer than 8192 so that one fp32 accumulation chain
+    // stays short
+    long long splits = (768 + tiles - 1) / tiles;
+    const long long max_splits = (M + 255) / 256;
     const long long min_splits = (M + 8191) / 8192;
     if (splits > max_splits) splits = max_splits;
     if (splits < min_splits) splits = min_splits;
@@ -241,7 +263,7 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     hipError_t e = dtype == PURINE_F32 ? dispatch<float>(p, plan, st) : dispatch<uint16_t>(p, plan, st);
     if (e != hipSuccess) return e;
     const int n = g.K * p.CRS;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 255) / 256), dim3(256), 0, st,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, st,
                        (const float*)ws, dw, n, plan.splits, beta);
     return hipGetLastError();
 }
