@@ -13,11 +13,12 @@
 //   backward-data, stride 1 : in = dy, i = c,       ci = k, h = ho + ph - r
 //   backward-data, strided  : in = dy, i = (c,a,b), ci = k, h = hq - r'   (phase-folded, below)
 //
-// The reduction runs tap-major: a slab is 16 consecutive channels ci of ONE tap (r, s). Within a
-// slab the bounds test and the tap offset are the same for all 16 rows, so a gathered element
-// costs one add and one load. The filter is first repacked (a tiny kernel, into caller scratch)
-// to A[(r,s)][ci][i], zero padded to whole slabs and tiles, which makes the filter slab a dense
-// block read with unconditional 16-byte loads. Layers with fewer than 16 gathered channels (the
+// A slab of the reduction is 16 consecutive channels ci of ONE tap (r, s). Within a slab the bounds
+// test and the tap offset are the same for all 16 rows, so a gathered element costs one add and
+// one load; the slabs of one channel group walk through all its taps before the next group, so the
+// halo rows the taps share stay in L1/L2. The filter is first repacked (a tiny kernel, into caller
+// scratch) to A[(r,s)][ci][i], zero padded to whole slabs and tiles, which makes the filter slab a
+// dense block read with unconditional 16-byte loads. Layers with fewer than 16 gathered channels (the
 // first layer of a CNN, forward) would waste most of a slab, so they run a second kernel that
 // flattens (c, r, s) into one reduction index instead.
 //
@@ -202,9 +203,13 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
     float b_reg[B_PASSES];
     bool b_ok;
 
-    // scalar walk over the slabs: tap (nx_r, nx_s), first channel nx_c0 of the next slab to load
-    int nx_r = 0, nx_s = 0, nx_c0 = 0;
+    // Scalar walk over the slabs: tap (nx_r, nx_s) and first channel nx_c0 of the next slab to load.
+    // Taps are the INNER loop: all taps of one 16-channel group are visited back to back, so the
+    // halo rows they share are re-read while still in L1/L2 (walking the channels inside a tap
+    // re-fetched the gathered tensor from beyond L2 once per tap).
+    int nx_r = 0, nx_s = 0, nx_c0 = 0, staged_c0 = 0;
     auto load_slab = [&]() {
+        staged_c0 = nx_c0;
         const int tap = nx_r * p.St + nx_s;
         const int a_slab = (tap * p.Ci_pad + nx_c0) * p.i_pad;
 #pragma unroll
@@ -223,16 +228,17 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
             b_reg[ps] = Elem<T>::load(in, base + plane);
         }
         // advance to the next slab (past the last one it wraps to the start; those values are unused)
-        nx_c0 += BK;
-        const bool wrap_c = nx_c0 >= p.Ci_pad;
-        nx_c0 = wrap_c ? 0 : nx_c0;
-        nx_s += wrap_c ? 1 : 0;
+        nx_s += 1;
         const bool wrap_s = nx_s >= p.St;
         nx_s = wrap_s ? 0 : nx_s;
         nx_r += wrap_s ? 1 : 0;
-        nx_r = nx_r >= p.Rt ? 0 : nx_r;
+        const bool wrap_r = nx_r >= p.Rt;
+        nx_r = wrap_r ? 0 : nx_r;
+        nx_c0 += wrap_r ? BK : 0;
+        nx_c0 = nx_c0 >= p.Ci_pad ? 0 : nx_c0;
     };
-    auto store_slab = [&](int buf, int c0) {
+    auto store_slab = [&](int buf) {
+        const int c0 = staged_c0;
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
             if (a_src[it] >= 0) *reinterpret_cast<floatx4*>(&As[buf][a_dst[it]]) = a_reg[it];
@@ -253,8 +259,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
 
     const int n_slabs = p.Rt * p.St * (p.Ci_pad / BK);
     load_slab();
-    store_slab(0, 0);
-    int st_c0 = BK >= p.Ci_pad ? 0 : BK;   // first channel of the slab staged in registers next
+    store_slab(0);
     __syncthreads();
 
     const int a_off = wm * TM * 32 + (lane & 31);
@@ -286,9 +291,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the LDS stores (and their load waits) below the MFMAs
-        store_slab(buf ^ 1, st_c0);
-        st_c0 += BK;
-        st_c0 = st_c0 >= p.Ci_pad ? 0 : st_c0;
+        store_slab(buf ^ 1);
         __syncthreads();
     }
 

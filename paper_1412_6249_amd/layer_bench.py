@@ -84,6 +84,20 @@ def bench_layer(L, ops, iters, out=sys.stdout):
     return results
 
 
+def copy_calibration(mib, iters=5):
+    """A plain device copy of known size (the one-term Sum operator): reads mib MiB, writes mib MiB.
+    Run it under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` to get the counter-to-bytes factor."""
+    n = mib * (1 << 20) // 4
+    src = torch.rand(n, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(iters):
+        B.purine_sum([src], dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    print("copy calibration: sum_kernel<float> moved %d bytes in and %d bytes out per launch, %d launches"
+          % (n * 4, n * 4, iters))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=4)
@@ -91,7 +105,12 @@ def main():
     ap.add_argument("--op", default="all")
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--copy-cal", type=int, default=0, metavar="MiB",
+                    help="run only a plain device copy of this many MiB (counter calibration)")
     a = ap.parse_args()
+    if a.copy_cal:
+        copy_calibration(a.copy_cal)
+        return
     ops = ["fwd", "bwd_data", "bwd_weight", "bias_fwd", "bias_bwd"] if a.op == "all" else a.op.split(",")
     for L in CONV_LAYERS[a.config]:
         if a.layer and L.name != a.layer:
