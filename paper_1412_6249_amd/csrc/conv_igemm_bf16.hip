@@ -1,0 +1,201 @@
+// bf16 MFMA variant of the pixel-major implicit GEMM (Conv / ConvBwdData, paper Figure 1(b)):
+// bf16 operands, fp32 accumulation on v_mfma_f32_32x32x16_bf16, bf16 (round-to-nearest-even) output.
+//
+// Same contraction and the same slab walk as the fp32 tap kernel (16-byte filter pieces from the
+// repacked copy, one bounds test per slab for the gathered operand), with the operand layout the
+// bf16 MFMA wants: each lane feeds 8 CONSECUTIVE reduction elements of its row (A) or column (B).
+// So both LDS tiles are stored reduction-major inside a row - As[i][ci], Bs[pixel][ci] - with a
+// slab depth of 32 channels, and the filter is repacked to A[tap][i][ci]. NCHW keeps pixels, not
+// channels, contiguous, so a thread gathers its 8..32 channels of one pixel with 2-byte loads
+// (coalesced along W across the wavefront), packs them and writes 16-byte pieces; rows are padded
+// to 40 elements (80 bytes) so that the 16-byte fragment reads of 32 rows fall in distinct bank
+// groups.
+#include "pix_common.h"
+
+namespace purine {
+namespace pix {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int BKH = 32;        // slab depth (channels)
+constexpr int LDK = BKH + 8;   // LDS row pitch in bf16 elements
+
+template <bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixParams p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = WM * TM * 32;
+    constexpr int BN = WN * TN * 32;
+    static_assert(NT == 256 && NT % BN == 0, "whole threads per pixel column");
+    constexpr int TPP = NT / BN;               // threads sharing one pixel column
+    constexpr int CH = BKH / TPP;              // channels gathered per thread per slab
+    static_assert(CH % 8 == 0, "16-byte LDS pieces");
+    constexpr int A_CPR = BKH / 8;             // 16-byte pieces per filter row
+    constexpr int A_VEC = BM * A_CPR;
+    constexpr int A_ITERS = (A_VEC + NT - 1) / NT;
+
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
+
+    const uint16_t* __restrict__ in = (const uint16_t*)p.in;
+    const uint16_t* __restrict__ wt = (const uint16_t*)p.wt;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int tile = xcd_tile(blockIdx.x, p.tiles_i * p.tiles_pix);
+    const int i0 = (tile % p.tiles_i) * BM;
+    const int j0 = (tile / p.tiles_i) * BN;
+
+    // this thread's pixel column and its share of the slab's channels
+    int g_off, g_h, g_w;
+    bool g_live;
+    {
+        const int pix = j0 + (tid % BN);
+        g_live = pix < p.M;
+        const int pc = g_live ? pix : 0;
+        const int n = fastdiv(pc, p.div_howo);
+        const int rem = pc - n * p.HoWo;
+        const int ho = fastdiv(rem, p.div_wo);
+        const int wo = rem - ho * p.Wo;
+        g_h = ho * p.g_mul_h + p.g_add_h;
+        g_w = wo * p.g_mul_w + p.g_add_w;
+        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;
+    }
+    const int ch_base = __builtin_amdgcn_readfirstlane(tid / BN) * CH;   // uniform per wavefront
+
+    int a_src[A_ITERS], a_dst[A_ITERS];
+#pragma unroll
+    for (int it = 0; it < A_ITERS; ++it) {
+        const int f = tid + it * NT;
+        const int row = f / A_CPR, piece = f - row * A_CPR;
+        a_src[it] = (f < A_VEC) ? (i0 + row) * p.Ci_pad + piece * 8 : -1;
+        a_dst[it] = row * LDK + piece * 8;
+    }
+
+    uint4 a_reg[A_ITERS];
+    uint32_t b_reg[CH];     // raw 16-bit values
+    bool b_ok;
+
+    int nx_r = 0, nx_s = 0, nx_c0 = 0, staged_c0 = 0;
+    auto load_slab = [&]() {
+        staged_c0 = nx_c0;
+        const int tap = nx_r * p.St + nx_s;
+        const int a_slab = tap * p.i_pad * p.Ci_pad + nx_c0;
+#pragma unroll
+        for (int it = 0; it < A_ITERS; ++it)
+            if (a_src[it] >= 0) a_reg[it] = *reinterpret_cast<const uint4*>(wt + a_slab + a_src[it]);
+        const int hi = MINUS ? g_h - nx_r : g_h + nx_r;
+        const int wi = MINUS ? g_w - nx_s : g_w + nx_s;
+        const int tap_off = nx_r * p.Wi + nx_s;
+        b_ok = g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
+        const int base = b_ok ? (MINUS ? g_off - tap_off : g_off + tap_off) : 0;
+#pragma unroll
+        for (int e = 0; e < CH; ++e) {
+            const int ci = nx_c0 + ch_base + e;
+            const int plane = (b_ok & (ci < p.Ci)) ? ci * p.HiWi : 0;   // clamped: masked at the store
+            b_reg[e] = in[base + plane];
+        }
+        // all taps of one channel group back to back (halo rows stay in L1/L2), then the next group
+        nx_s += 1;
+        const bool wrap_s = nx_s >= p.St;
+        nx_s = wrap_s ? 0 : nx_s;
+        nx_r += wrap_s ? 1 : 0;
+        const bool wrap_r = nx_r >= p.Rt;
+        nx_r = wrap_r ? 0 : nx_r;
+        nx_c0 += wrap_r ? BKH : 0;
+        nx_c0 = nx_c0 >= p.Ci_pad ? 0 : nx_c0;
+    };
+    auto store_slab = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < A_ITERS; ++it)
+            if (a_src[it] >= 0) *reinterpret_cast<uint4*>(&As[buf][a_dst[it]]) = a_reg[it];
+        const int c0 = staged_c0 + ch_base;
+        uint16_t* row = &Bs[buf][(tid % BN) * LDK + ch_base];
+#pragma unroll
+        for (int q = 0; q < CH / 8; ++q) {
+            uint32_t w[4];
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const int e = q * 8 + 2 * h;
+                const uint32_t lo = (b_ok & (c0 + e < p.Ci)) ? b_reg[e] : 0u;
+                const uint32_t hi = (b_ok & (c0 + e + 1 < p.Ci)) ? b_reg[e + 1] : 0u;
+                w[h] = lo | (hi << 16);
+            }
+            *reinterpret_cast<uint4*>(row + q * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
+    const int n_slabs = p.Rt * p.St * (p.Ci_pad / BKH);
+    load_slab();
+    store_slab(0);
+    __syncthreads();
+
+    const int a_row = (wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+    const int b_row = (wn * TN * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+
+    for (int slab = 0; slab < n_slabs; ++slab) {
+        const int buf = slab & 1;
+        load_slab();
+#pragma unroll
+        for (int ks = 0; ks < BKH / 16; ++ks) {
+            bf16x8 av[TM], bv[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+                av[a] = *reinterpret_cast<const bf16x8*>(&As[buf][a_row + a * 32 * LDK + ks * 16]);
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                bv[b] = *reinterpret_cast<const bf16x8*>(&Bs[buf][b_row + b * 32 * LDK + ks * 16]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        store_slab(buf ^ 1);
+        __syncthreads();
+    }
+
+    store_tile<uint16_t, D2S, TM, TN>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
+                                      j0 + wn * TN * 32 + (lane & 31), lane >> 5);
+}
+
+template <bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+hipError_t launch_one(PixParams& p, hipStream_t st) {
+    const long long total = (long long)p.tiles_i * p.tiles_pix;
+    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
+    hipLaunchKernelGGL((igemm_tap_bf16_kernel<MINUS, D2S, TM, TN, WM, WN>), dim3((unsigned)total),
+                       dim3(WM * WN * 64), 0, st, p);
+    return hipGetLastError();
+}
+
+template <bool MINUS, bool D2S>
+hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_one<MINUS, D2S, TM, TN, WM, WN>(p, st)
+    PURINE_TILE_SWITCH(CALL)
+#undef CALL
+}
+
+}  // namespace
+
+hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
+    if (mode == 0) return by_tile<false, false>(p, bm, bn, st);
+    if (mode == 1) return by_tile<true, false>(p, bm, bn, st);
+    return by_tile<true, true>(p, bm, bn, st);
+}
+
+}  // namespace pix
+}  // namespace purine

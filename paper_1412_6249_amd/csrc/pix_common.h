@@ -1,0 +1,140 @@
+// Device-side pieces shared by the forward / backward-data implicit-GEMM kernels (fp32 and bf16 MFMA).
+#pragma once
+#include "common.h"
+
+namespace purine {
+namespace pix {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float* p, int i) { return p[i]; }
+    static __device__ __forceinline__ void store(float* p, int i, float v) { p[i] = v; }
+    static __device__ __forceinline__ floatx4 load4(const float* p, int i) {
+        return *reinterpret_cast<const floatx4*>(p + i);
+    }
+};
+template <> struct Elem<uint16_t> {  // bfloat16 bit patterns
+    static __device__ __forceinline__ float load(const uint16_t* p, int i) {
+        return __uint_as_float(((uint32_t)p[i]) << 16);
+    }
+    static __device__ __forceinline__ void store(uint16_t* p, int i, float v) {
+        uint32_t u = __float_as_uint(v);
+        uint32_t r = u + 0x7FFFu + ((u >> 16) & 1u);          // round to nearest even
+        if ((u & 0x7F800000u) == 0x7F800000u && (u & 0x007FFFFFu)) r = 0x7FC00000u;  // NaN
+        p[i] = (uint16_t)(r >> 16);
+    }
+    static __device__ __forceinline__ floatx4 load4(const uint16_t* p, int i) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p + i);
+        floatx4 o;
+        o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        return o;
+    }
+};
+
+struct PixParams {
+    const void* in;     // gathered activation tensor [N][Ci][Hi][Wi]
+    const void* wt;     // tap kernel: repacked filter A[taps][Ci_pad][i_pad]; flat kernel: KCRS filter
+    void* out;          // produced tensor [N][Co][Ho][Wo] (depth-to-space epilogue: dx [N][C][H][W])
+    int N, Ci, Hi, Wi, HiWi;
+    int Co, Ho, Wo, HoWo, M;      // GEMM rows; pixel grid enumerated by the columns; M = N*Ho*Wo
+    int Rt, St;                   // taps of the reduction (ceil(R/sh) x ceil(S/sw) when phase-folded)
+    int Ci_pad, i_pad;            // padded extents of the repacked filter
+    int g_mul_h, g_mul_w, g_add_h, g_add_w;   // gather origin: g_h = ho*g_mul_h + g_add_h (same for w)
+    int C, H, W, sh, sw, ph, pw, phases, hq_min, wq_min;   // depth-to-space epilogue
+    int R, S, RS, Kg;             // flat kernel only: filter extents, Kg = Ci*R*S
+    FastDiv div_howo, div_wo, div_phases, div_sw, div_rs, div_s;
+    float beta;
+    int tiles_i, tiles_pix;
+};
+
+// Epilogue shared by both kernels. Accumulator register e of a 32x32 tile holds row
+// (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
+template <typename T, bool D2S, int TM, int TN>
+__device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
+                                           floatx16 (&acc)[TM][TN], int i_base, int pix_base,
+                                           int khalf) {
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int pix = pix_base + b * 32;
+        if (pix >= p.M) continue;
+        const int n = fastdiv(pix, p.div_howo);
+        const int rem = pix - n * p.HoWo;
+        if (!D2S) {
+            const int obase = n * p.Co * p.HoWo + rem;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                    if (i < p.Co) {
+                        const int o = obase + i * p.HoWo;
+                        float v = acc[a][b][e];
+                        if (p.beta != 0.0f) v += Elem<T>::load(out, o);
+                        Elem<T>::store(out, o, v);
+                    }
+                }
+        } else {
+            // depth-to-space: row i = (c, a, b) of coarse pixel (n, hq, wq) is
+            // dx[n, c, hq*sh + a - ph, wq*sw + b - pw]
+            const int hq = fastdiv(rem, p.div_wo);
+            const int wq = rem - hq * p.Wo;
+            const int hb = (hq + p.hq_min) * p.sh - p.ph;
+            const int wb = (wq + p.wq_min) * p.sw - p.pw;
+            const int obase = n * p.C * p.H * p.W;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int i = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                    if (i < p.Co) {
+                        const int c = fastdiv(i, p.div_phases);
+                        const int ab = i - c * p.phases;
+                        const int pa = fastdiv(ab, p.div_sw);
+                        const int pb = ab - pa * p.sw;
+                        const int h = hb + pa, w = wb + pb;
+                        if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
+                            const int o = obase + (c * p.H + h) * p.W + w;
+                            float v = acc[a][b][e];
+                            if (p.beta != 0.0f) v += Elem<T>::load(out, o);
+                            Elem<T>::store(out, o, v);
+                        }
+                    }
+                }
+        }
+    }
+}
+
+// Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). Give each
+// XCD a contiguous run of tiles so that neighbouring pixel tiles share halo rows in one L2.
+__device__ __forceinline__ int xcd_tile(int bid, int total) {
+    const int per = total >> 3;
+    return (per > 0 && bid < per * 8) ? (bid & 7) * per + (bid >> 3) : bid;
+}
+
+
+struct TileCfg { int bm, bn; float eff; };
+
+// (TM, TN, WM, WN) for each tile extent: workgroup = WM x WN wavefronts of TM x TN MFMA tiles (32x32)
+#define PURINE_TILE_SWITCH(CALL)                                       \
+    switch (bm * 1000 + bn) {                                          \
+        case 128128: return CALL(2, 2, 2, 2);                          \
+        case 96256:  return CALL(3, 2, 1, 4);                          \
+        case 96128:  return CALL(3, 1, 1, 4);                          \
+        case 64256:  return CALL(2, 2, 1, 4);                          \
+        case 128064: return CALL(1, 2, 4, 1);                          \
+        case 64128:  return CALL(2, 1, 1, 4);                          \
+        case 32256:  return CALL(1, 2, 1, 4);                          \
+        case 64064:  return CALL(1, 1, 2, 2);                          \
+        case 32128:  return CALL(1, 1, 1, 4);                          \
+        default: return hipErrorInvalidValue;                          \
+    }
+
+// bf16 MFMA variant of the tap kernel (conv_igemm_bf16.hip). mode: 0 fwd, 1 bwd unit stride, 2 bwd phase-folded.
+hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st);
+
+}  // namespace pix
+}  // namespace purine
