@@ -161,6 +161,213 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// bf16 MFMA variant (v_mfma_f32_32x32x16_bf16): the reduction runs over pixels, and NCHW keeps the
+// pixels of one channel contiguous, so both operands are reduction-major already: the LDS tiles are
+// As[k][pixel] and Bs[(c,r,s)][pixel] with a slab of 32 pixels, rows padded to 40 elements so the
+// 16-byte fragment reads of 32 rows fall in distinct bank groups. VEC_A: a slab never straddles an
+// image and stays 16-byte aligned (P*Q a multiple of 32), so dy rows are read with 16-byte loads.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int BKP = 32;
+constexpr int LDP = BKP + 8;
+
+template <bool VEC_A, int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradParams p) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = WM * TM * 32;
+    constexpr int BN = WN * TN * 32;
+    constexpr int RPP = NT / BKP;      // tile rows covered per pass (lanes 0..31 run along pixels)
+    constexpr int A_PASSES = BM / RPP, B_PASSES = BN / RPP;
+    constexpr int A_VEC = BM * (BKP / 8);
+    constexpr int A_ITERS = (A_VEC + NT - 1) / NT;
+    static_assert(NT == 256 && BM % RPP == 0 && BN % RPP == 0, "mapping");
+
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDP];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDP];
+
+    const uint16_t* __restrict__ x = (const uint16_t*)p.x;
+    const uint16_t* __restrict__ dy = (const uint16_t*)p.dy;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    int bid = blockIdx.x;
+    const int split = bid / (p.tiles_i * p.tiles_j);
+    bid -= split * p.tiles_i * p.tiles_j;
+    const int i0 = (bid % p.tiles_i) * BM;
+    const int j0 = (bid / p.tiles_i) * BN;
+    const int pix_begin = split * p.chunk;
+    const int pix_end = min(p.M, pix_begin + p.chunk);
+
+    const int t_px = tid % BKP;   // this thread's pixel inside a slab
+    const int t_row = tid / BKP;  // first tile row it serves
+
+    int j_off[B_PASSES], j_rs[B_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < B_PASSES; ++ps) {
+        const int j = j0 + t_row + ps * RPP;
+        if (j < p.CRS) {
+            const int c = fastdiv(j, p.div_rs);
+            const int rs = j - c * p.RS;
+            const int r = fastdiv(rs, p.div_s);
+            const int s = rs - r * p.S;
+            j_off[ps] = c * p.HW + r * p.W + s;
+            j_rs[ps] = (r << 16) | s;
+        } else {
+            j_off[ps] = 0;
+            j_rs[ps] = -1;
+        }
+    }
+
+    uint32_t a_reg[VEC_A ? 1 : A_PASSES];
+    uint4 a_vec[VEC_A ? A_ITERS : 1];
+    uint32_t b_reg[B_PASSES];
+    unsigned a_ok = 0u, b_ok = 0u;
+
+    auto load_slab = [&](int slab) {
+        const int pix0 = pix_begin + slab * BKP;
+        const int pix = pix0 + t_px;
+        const bool pv = pix < pix_end;
+        const int pc = pv ? pix : 0;
+        const int n = fastdiv(pc, p.div_pq);
+        const int pq = pc - n * p.PQ;
+        const int pp = fastdiv(pq, p.div_q);
+        const int qq = pq - pp * p.Q;
+        if (VEC_A) {
+            // whole slab inside one image: n0/pq0 are uniform; pixels past pix_end are masked at the store
+            const int n0 = fastdiv(pix0 < p.M ? pix0 : 0, p.div_pq);
+            const int pq0 = (pix0 < p.M ? pix0 : 0) - n0 * p.PQ;
+#pragma unroll
+            for (int it = 0; it < A_ITERS; ++it) {
+                const int f = tid + it * NT;
+                const int row = f / (BKP / 8), piece = f - row * (BKP / 8);
+                const bool ok = (f < A_VEC) & (i0 + row < p.K) & (pix0 + piece * 8 < pix_end);
+                a_vec[it] = *reinterpret_cast<const uint4*>(
+                    dy + (ok ? (n0 * p.K + i0 + row) * p.PQ + pq0 + piece * 8 : 0));
+                a_ok = ok ? (a_ok | (1u << it)) : (a_ok & ~(1u << it));
+            }
+        } else {
+            a_ok = 0u;
+            const int a_base = n * p.K * p.PQ + pq;
+#pragma unroll
+            for (int ps = 0; ps < A_PASSES; ++ps) {
+                const int i = i0 + t_row + ps * RPP;
+                const bool ok = pv & (i < p.K);
+                a_reg[ps] = dy[ok ? a_base + i * p.PQ : 0];
+                a_ok |= (ok ? 1u : 0u) << ps;
+            }
+        }
+        b_ok = 0u;
+        const int hb = pp * p.sh - p.ph, wb = qq * p.sw - p.pw;
+        const int b_base = n * p.C * p.HW + hb * p.W + wb;
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps) {
+            const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
+            const bool ok = pv & (j_rs[ps] >= 0) & ((unsigned)(hb + r) < (unsigned)p.H) &
+                            ((unsigned)(wb + s) < (unsigned)p.W);
+            b_reg[ps] = x[ok ? b_base + j_off[ps] : 0];
+            b_ok |= (ok ? 1u : 0u) << ps;
+        }
+    };
+    auto store_slab = [&](int buf) {
+        if (VEC_A) {
+#pragma unroll
+            for (int it = 0; it < A_ITERS; ++it) {
+                const int f = tid + it * NT;
+                const int row = f / (BKP / 8), piece = f - row * (BKP / 8);
+                if (f < A_VEC)
+                    *reinterpret_cast<uint4*>(&As[buf][row * LDP + piece * 8]) =
+                        ((a_ok >> it) & 1u) ? a_vec[it] : make_uint4(0u, 0u, 0u, 0u);
+            }
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < A_PASSES; ++ps)
+                As[buf][(t_row + ps * RPP) * LDP + t_px] = ((a_ok >> ps) & 1u) ? (uint16_t)a_reg[ps] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps)
+            Bs[buf][(t_row + ps * RPP) * LDP + t_px] = ((b_ok >> ps) & 1u) ? (uint16_t)b_reg[ps] : (uint16_t)0;
+    };
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
+    const int n_slabs = (pix_end - pix_begin + BKP - 1) / BKP;
+    if (n_slabs > 0) {
+        load_slab(0);
+        store_slab(0);
+    }
+    __syncthreads();
+
+    const int a_row = (wm * TM * 32 + (lane & 31)) * LDP + (lane >> 5) * 8;
+    const int b_row = (wn * TN * 32 + (lane & 31)) * LDP + (lane >> 5) * 8;
+    const int khalf = lane >> 5;
+
+    for (int slab = 0; slab < n_slabs; ++slab) {
+        const int buf = slab & 1;
+        load_slab(slab + 1);   // past the chunk: every value is masked to zero
+#pragma unroll
+        for (int ks = 0; ks < BKP / 16; ++ks) {
+            bf16x8 av[TM], bv[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+                av[a] = *reinterpret_cast<const bf16x8*>(&As[buf][a_row + a * 32 * LDP + ks * 16]);
+#pragma unroll
+            for (int b = 0; b < TN; ++b)
+                bv[b] = *reinterpret_cast<const bf16x8*>(&Bs[buf][b_row + b * 32 * LDP + ks * 16]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        store_slab(buf ^ 1);
+        __syncthreads();
+    }
+
+    float* __restrict__ out = p.out + (size_t)split * p.K * p.CRS;
+    const int jb = j0 + wn * TN * 32 + (lane & 31);
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int j = jb + b * 32;
+        if (j >= p.CRS) continue;
+#pragma unroll
+        for (int a = 0; a < TM; ++a)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+                if (i < p.K) out[(size_t)i * p.CRS + j] = acc[a][b][e];
+            }
+    }
+}
+
+template <bool VEC_A, int TM, int TN, int WM, int WN>
+hipError_t launch_tile_bf16(WgradParams& p, hipStream_t st) {
+    const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
+    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
+    hipLaunchKernelGGL((wgrad_bf16_kernel<VEC_A, TM, TN, WM, WN>), dim3((unsigned)total),
+                       dim3(WM * WN * 64), 0, st, p);
+    return hipGetLastError();
+}
+
+template <bool VEC_A>
+hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+    if (plan.bm == 128 && plan.bn == 128) return launch_tile_bf16<VEC_A, 2, 2, 2, 2>(p, st);
+    if (plan.bm == 96 && plan.bn == 128) return launch_tile_bf16<VEC_A, 3, 1, 1, 4>(p, st);
+    if (plan.bm == 64 && plan.bn == 128) return launch_tile_bf16<VEC_A, 2, 1, 1, 4>(p, st);
+    if (plan.bm == 32 && plan.bn == 128) return launch_tile_bf16<VEC_A, 1, 1, 1, 4>(p, st);
+    return hipErrorInvalidValue;
+}
+
 // dw[i] = beta*dw[i] + partial[0][i] + partial[1][i] + ... summed in a fixed tree: a workgroup owns
 // 16 consecutive elements; each of its 16 "split lanes" adds the partials s = lane, lane+16, ... in
 // order (independent loads, so many are in flight), and the 16 lane sums are then added in lane
@@ -241,7 +448,7 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     if (splits < min_splits) splits = min_splits;
     if (splits < 1) splits = 1;
     long long chunk = (M + splits - 1) / splits;
-    chunk = (chunk + BK - 1) / BK * BK;
+    chunk = (chunk + 31) / 32 * 32;   // whole slabs of either kernel (16 or 32 pixels), 16-byte aligned rows
     splits = (M + chunk - 1) / chunk;
     pl.splits = (int)splits;
     pl.chunk = (int)chunk;
@@ -260,7 +467,10 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     p.div_rs = make_fastdiv(p.RS); p.div_s = make_fastdiv(g.S);
     p.chunk = plan.chunk; p.tiles_i = plan.tiles_i; p.tiles_j = plan.tiles_j; p.splits = plan.splits;
     p.out = (float*)ws;
-    hipError_t e = dtype == PURINE_F32 ? dispatch<float>(p, plan, st) : dispatch<uint16_t>(p, plan, st);
+    hipError_t e;
+    if (dtype == PURINE_F32) e = dispatch<float>(p, plan, st);
+    else if (p.PQ % 32 == 0 && (((uintptr_t)dy) & 15u) == 0) e = dispatch_bf16<true>(p, plan, st);
+    else e = dispatch_bf16<false>(p, plan, st);
     if (e != hipSuccess) return e;
     const int n = g.K * p.CRS;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, st,

@@ -31,6 +31,8 @@ CASES = [
     ("smallc_s3x2", 2, 2, 13, 17, 9, 4, 5, (3, 2), (1, 2)),
     ("smallc_tiny_h", 1, 3, 2, 9, 4, 3, 3, (4, 2), (1, 1)),
     ("smallc_s4_pad5", 2, 4, 21, 19, 6, 7, 6, (4, 4), (5, 4)),
+    ("pq_multiple_of_32", 3, 8, 16, 16, 40, 3, 3, (1, 1), (1, 1)),
+    ("c70_k70_5x5", 2, 70, 12, 12, 70, 5, 5, (1, 1), (2, 2)),
 ]
 
 
