@@ -22,15 +22,59 @@ template <> __device__ __forceinline__ void stf<uint16_t>(uint16_t* p, size_t i,
 
 constexpr int TPB = 256;
 
-// ---- Bias: one workgroup row per (n,k) plane slice --------------------------------------------
-template <typename T>
+// 16-byte packets: 4 floats or 8 bfloat16. The vector kernels below move one packet per lane
+// (1 KiB per wavefront instruction); the scalar forms handle rows whose length or start is not a
+// multiple of a packet.
+template <typename T> struct Pk;
+template <> struct Pk<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
+        f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&f)[4]) {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+};
+template <> struct Pk<uint16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f[2 * i] = __uint_as_float(w[i] << 16);
+            f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ uint4 pack(const float (&f)[8]) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = (uint32_t)f2bf(f[2 * i]) | ((uint32_t)f2bf(f[2 * i + 1]) << 16);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+
+// ---- Bias: y[n,k,:,:] += b[k]; grid.x = plane (n*K + k), grid.y = chunks of the plane ------------
+template <typename T, bool VEC>
 __global__ __launch_bounds__(TPB) void bias_fwd_kernel(const T* __restrict__ b, T* __restrict__ y,
                                                        int K, int PQ) {
-    const int plane = blockIdx.x;              // n*K + k
+    const int plane = blockIdx.x;
     const float bv = ldf<T>(b, plane % K);
     T* row = y + (size_t)plane * PQ;
-    for (int i = blockIdx.y * TPB + threadIdx.x; i < PQ; i += gridDim.y * TPB)
-        stf<T>(row, i, ldf<T>(row, i) + bv);
+    if (VEC) {
+        constexpr int V = Pk<T>::N;
+        uint4* r4 = reinterpret_cast<uint4*>(row);
+        for (int i = blockIdx.y * TPB + threadIdx.x; i < PQ / V; i += gridDim.y * TPB) {
+            float f[V];
+            Pk<T>::unpack(r4[i], f);
+#pragma unroll
+            for (int e = 0; e < V; ++e) f[e] += bv;
+            r4[i] = Pk<T>::pack(f);
+        }
+    } else {
+        for (int i = blockIdx.y * TPB + threadIdx.x; i < PQ; i += gridDim.y * TPB)
+            stf<T>(row, i, ldf<T>(row, i) + bv);
+    }
 }
 
 // ---- BiasBwd: lane -> wavefront (shuffle) -> workgroup (LDS) partial per (k, image group),
@@ -41,7 +85,7 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(TPB) void bias_bwd_partial_kernel(const T* __restrict__ dy,
                                                                float* __restrict__ partial, int N,
                                                                int K, int PQ, int imgs_per_part,
@@ -52,7 +96,18 @@ __global__ __launch_bounds__(TPB) void bias_bwd_partial_kernel(const T* __restri
     float acc = 0.0f;
     for (int n = n0; n < n1; ++n) {
         const T* row = dy + ((size_t)n * K + k) * PQ;
-        for (int i = threadIdx.x; i < PQ; i += TPB) acc += ldf<T>(row, i);
+        if (VEC) {
+            constexpr int V = Pk<T>::N;
+            const uint4* r4 = reinterpret_cast<const uint4*>(row);
+            for (int i = threadIdx.x; i < PQ / V; i += TPB) {
+                float f[V];
+                Pk<T>::unpack(r4[i], f);
+#pragma unroll
+                for (int e = 0; e < V; ++e) acc += f[e];
+            }
+        } else {
+            for (int i = threadIdx.x; i < PQ; i += TPB) acc += ldf<T>(row, i);
+        }
     }
     __shared__ float wsum[TPB / 64];
     acc = wave_sum(acc);
@@ -76,19 +131,42 @@ __global__ __launch_bounds__(TPB) void bias_bwd_final_kernel(const float* __rest
     db[k] = acc;
 }
 
-// ---- ReLU -------------------------------------------------------------------------------------
+// ---- ReLU: packets for the bulk, scalars for the tail ------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(TPB) void relu_fwd_kernel(const T* x, T* y,
-                                                       size_t n) {
-    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += (size_t)gridDim.x * TPB) {
+__global__ __launch_bounds__(TPB) void relu_fwd_kernel(const T* x, T* y, size_t n) {
+    constexpr int V = Pk<T>::N;
+    const size_t nv = n / V, stride = (size_t)gridDim.x * TPB, t0 = (size_t)blockIdx.x * TPB + threadIdx.x;
+    const uint4* x4 = reinterpret_cast<const uint4*>(x);
+    uint4* y4 = reinterpret_cast<uint4*>(y);
+    for (size_t i = t0; i < nv; i += stride) {
+        float f[V];
+        Pk<T>::unpack(x4[i], f);
+#pragma unroll
+        for (int e = 0; e < V; ++e) f[e] = f[e] > 0.0f ? f[e] : 0.0f;
+        y4[i] = Pk<T>::pack(f);
+    }
+    for (size_t i = nv * V + t0; i < n; i += stride) {
         const float v = ldf<T>(x, i);
         stf<T>(y, i, v > 0.0f ? v : 0.0f);
     }
 }
 template <typename T>
-__global__ __launch_bounds__(TPB) void relu_bwd_kernel(const T* __restrict__ x,
-                                                       const T* dy, T* dx, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += (size_t)gridDim.x * TPB) {
+__global__ __launch_bounds__(TPB) void relu_bwd_kernel(const T* __restrict__ x, const T* dy, T* dx,
+                                                       size_t n) {
+    constexpr int V = Pk<T>::N;
+    const size_t nv = n / V, stride = (size_t)gridDim.x * TPB, t0 = (size_t)blockIdx.x * TPB + threadIdx.x;
+    const uint4* x4 = reinterpret_cast<const uint4*>(x);
+    const uint4* g4 = reinterpret_cast<const uint4*>(dy);
+    uint4* o4 = reinterpret_cast<uint4*>(dx);
+    for (size_t i = t0; i < nv; i += stride) {
+        float f[V], g[V];
+        Pk<T>::unpack(x4[i], f);
+        Pk<T>::unpack(g4[i], g);
+#pragma unroll
+        for (int e = 0; e < V; ++e) g[e] = f[e] > 0.0f ? g[e] : 0.0f;
+        o4[i] = Pk<T>::pack(g);
+    }
+    for (size_t i = nv * V + t0; i < n; i += stride) {
         const float v = ldf<T>(x, i);
         stf<T>(dx, i, v > 0.0f ? ldf<T>(dy, i) : 0.0f);
     }
@@ -148,7 +226,7 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
 }
 
 // ---- channel-slice copy (concat and its inverse) -------------------------------------------------
-template <typename T>
+template <typename T, bool VEC>
 __global__ __launch_bounds__(TPB) void copy_channels_kernel(const T* __restrict__ src,
                                                             T* __restrict__ dst, int c_count,
                                                             int src_C, int src_c0, int dst_C,
@@ -157,15 +235,36 @@ __global__ __launch_bounds__(TPB) void copy_channels_kernel(const T* __restrict_
     const size_t run = (size_t)c_count * HW;   // the slice of one image is contiguous on both sides
     const T* s = src + ((size_t)n * src_C + src_c0) * HW;
     T* d = dst + ((size_t)n * dst_C + dst_c0) * HW;
-    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < run; i += (size_t)gridDim.x * TPB)
-        d[i] = s[i];
+    if (VEC) {   // HW is a multiple of a packet, so every slice starts and ends on a packet
+        const uint4* s4 = reinterpret_cast<const uint4*>(s);
+        uint4* d4 = reinterpret_cast<uint4*>(d);
+        const size_t nv = run / Pk<T>::N;
+        for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < nv; i += (size_t)gridDim.x * TPB)
+            d4[i] = s4[i];
+    } else {
+        for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < run; i += (size_t)gridDim.x * TPB)
+            d[i] = s[i];
+    }
 }
 
 // ---- fan-in sum ------------------------------------------------------------------------------------
 struct SumArgs { const void* t[8]; int n; };
 template <typename T>
 __global__ __launch_bounds__(TPB) void sum_kernel(SumArgs a, T* out, size_t n) {
-    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += (size_t)gridDim.x * TPB) {
+    constexpr int V = Pk<T>::N;
+    const size_t nv = n / V, stride = (size_t)gridDim.x * TPB, t0 = (size_t)blockIdx.x * TPB + threadIdx.x;
+    for (size_t i = t0; i < nv; i += stride) {
+        float acc[V];
+        Pk<T>::unpack(reinterpret_cast<const uint4*>(a.t[0])[i], acc);
+        for (int j = 1; j < a.n; ++j) {
+            float f[V];
+            Pk<T>::unpack(reinterpret_cast<const uint4*>(a.t[j])[i], f);
+#pragma unroll
+            for (int e = 0; e < V; ++e) acc[e] += f[e];
+        }
+        reinterpret_cast<uint4*>(out)[i] = Pk<T>::pack(acc);
+    }
+    for (size_t i = nv * V + t0; i < n; i += stride) {
         float acc = ldf<T>((const T*)a.t[0], i);
         for (int j = 1; j < a.n; ++j) acc += ldf<T>((const T*)a.t[j], i);
         stf<T>(out, i, acc);
@@ -197,12 +296,19 @@ BiasBwdPlan plan_bias_bwd(int N, int K, int PQ) {
     do { if ((dtype) == PURINE_F32) { CALL_F32; } else { CALL_BF16; } } while (0)
 
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st) {
-    dim3 grid((unsigned)(N * K), blocks_for(PQ, 64));
+    const int V = dtype == PURINE_F32 ? 4 : 8;
+    const bool vec = PQ % V == 0;
+    dim3 grid((unsigned)(N * K), blocks_for(vec ? PQ / V : PQ, 64));
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    BY_DTYPE(dtype,
-             hipLaunchKernelGGL(bias_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)b, (float*)y, K, PQ),
-             hipLaunchKernelGGL(bias_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)b, (uint16_t*)y, K, PQ));
+    if (vec)
+        BY_DTYPE(dtype,
+                 hipLaunchKernelGGL((bias_fwd_kernel<float, true>), grid, dim3(TPB), 0, st, (const float*)b, (float*)y, K, PQ),
+                 hipLaunchKernelGGL((bias_fwd_kernel<uint16_t, true>), grid, dim3(TPB), 0, st, (const uint16_t*)b, (uint16_t*)y, K, PQ));
+    else
+        BY_DTYPE(dtype,
+                 hipLaunchKernelGGL((bias_fwd_kernel<float, false>), grid, dim3(TPB), 0, st, (const float*)b, (float*)y, K, PQ),
+                 hipLaunchKernelGGL((bias_fwd_kernel<uint16_t, false>), grid, dim3(TPB), 0, st, (const uint16_t*)b, (uint16_t*)y, K, PQ));
     return hipGetLastError();
 }
 
@@ -213,9 +319,14 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
     {
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    BY_DTYPE(dtype,
-             hipLaunchKernelGGL(bias_bwd_partial_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts),
-             hipLaunchKernelGGL(bias_bwd_partial_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts));
+    if (PQ % (dtype == PURINE_F32 ? 4 : 8) == 0)
+        BY_DTYPE(dtype,
+                 hipLaunchKernelGGL((bias_bwd_partial_kernel<float, true>), grid, dim3(TPB), 0, st, (const float*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts),
+                 hipLaunchKernelGGL((bias_bwd_partial_kernel<uint16_t, true>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts));
+    else
+        BY_DTYPE(dtype,
+                 hipLaunchKernelGGL((bias_bwd_partial_kernel<float, false>), grid, dim3(TPB), 0, st, (const float*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts),
+                 hipLaunchKernelGGL((bias_bwd_partial_kernel<uint16_t, false>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, partial, N, K, PQ, plan.imgs_per_part, plan.parts));
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -225,7 +336,7 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
 }
 
 hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st) {
-    dim3 grid(blocks_for((size_t)n));
+    dim3 grid(blocks_for((size_t)n / 4 + 1));
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
@@ -236,7 +347,7 @@ hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStre
 
 hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
                            hipStream_t st) {
-    dim3 grid(blocks_for((size_t)n));
+    dim3 grid(blocks_for((size_t)n / 4 + 1));
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
@@ -274,9 +385,14 @@ hipError_t launch_copy_channels(int dtype, const void* src, void* dst, int N, in
     dim3 grid(blocks_for((size_t)c_count * HW, 256), (unsigned)N);
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    BY_DTYPE(dtype,
-             hipLaunchKernelGGL(copy_channels_kernel<float>, grid, dim3(TPB), 0, st, (const float*)src, (float*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW),
-             hipLaunchKernelGGL(copy_channels_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)src, (uint16_t*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW));
+    if (HW % (dtype == PURINE_F32 ? 4 : 8) == 0)
+        BY_DTYPE(dtype,
+                 hipLaunchKernelGGL((copy_channels_kernel<float, true>), grid, dim3(TPB), 0, st, (const float*)src, (float*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW),
+                 hipLaunchKernelGGL((copy_channels_kernel<uint16_t, true>), grid, dim3(TPB), 0, st, (const uint16_t*)src, (uint16_t*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW));
+    else
+        BY_DTYPE(dtype,
+                 hipLaunchKernelGGL((copy_channels_kernel<float, false>), grid, dim3(TPB), 0, st, (const float*)src, (float*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW),
+                 hipLaunchKernelGGL((copy_channels_kernel<uint16_t, false>), grid, dim3(TPB), 0, st, (const uint16_t*)src, (uint16_t*)dst, c_count, src_C, src_c0, dst_C, dst_c0, HW));
     return hipGetLastError();
 }
 
@@ -285,7 +401,7 @@ hipError_t launch_sum(int dtype, const void* const* terms, int n_terms, void* ou
     SumArgs a{};
     a.n = n_terms;
     for (int i = 0; i < n_terms; ++i) a.t[i] = terms[i];
-    dim3 grid(blocks_for((size_t)n));
+    dim3 grid(blocks_for((size_t)n / 4 + 1));
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
     BY_DTYPE(dtype,
