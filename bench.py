@@ -28,7 +28,7 @@ MEASURED_TRAFFIC_BYTES = {}
 
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
               5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
-              10: "concat_bwd", 11: "sum"}
+              10: "concat_bwd", 11: "sum", 13: "conv_fwd_bias_relu", 14: "conv_bwd_data_relu"}
 
 
 def cpu_baseline(cfg, budget_s=15.0):
@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: NIN mlpconv block)")
     ap.add_argument("--single-stream", action="store_true", help="all operators on one thread id")
+    ap.add_argument("--unfused", action="store_true",
+                    help="separate Bias / ReLU / ReLU-gradient operators instead of the fused conv vertices")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ops", action="store_true", help="print the per-operator table to stderr")
     args = ap.parse_args()
@@ -92,7 +94,7 @@ def main():
 
     cfg = args.config
     torch.cuda.set_device(0)
-    gb = build_workload(cfg, multi_stream=not args.single_stream)
+    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused)
     for _ in range(args.warmup):
         gb.run()
     pa.purine_graph_enable_timing(gb.g, True)
@@ -110,11 +112,12 @@ def main():
     dtype = CONV_LAYERS[cfg][0].dtype
 
     # dominant kernel of the step
-    by_out = {rec[k]: (rec["layer"], k) for rec in gb.conv_records for k in ("y", "dx", "dw")}
+    by_out = {rec[k]: (rec["layer"], k) for rec in gb.conv_records for k in ("y", "out", "dx", "dw")
+              if rec[k] is not None}
     rows = []
     for oid, kind, ins, outs, _ in gb.ops:
         avg = op_ms[oid] / args.steps
-        L = by_out.get(outs[0], (None, None))[0] if kind in (0, 2, 3) else None
+        L = by_out.get(outs[0], (None, None))[0] if kind in (0, 2, 3, 13, 14) else None
         rows.append((avg, oid, kind, outs[0], L))
     rows.sort(reverse=True)
     if args.ops:
@@ -141,7 +144,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[cfg], "conv_gflop_per_step": round(flop / 1e9, 2),
-                   "executor": "bi-graph, %s" % ("1 stream" if args.single_stream else "3+ streams"),
+                   "executor": "bi-graph, %s, %s" % ("1 stream" if args.single_stream else "3+ streams",
+                                                      "separate bias/relu ops" if args.unfused
+                                                      else "bias+relu fused into conv vertices"),
                    "frac_of_mfma_peak": round(flop / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[dtype], 4)},
         "roofline": roofline,
     }

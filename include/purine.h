@@ -102,6 +102,20 @@ int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
                          const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
                          size_t ws_bytes, void* hip_stream);
 
+/* Fused operator vertices (an operator is any function of its incoming tensors, section 2): the
+ * same kernels with the elementwise neighbours of Figure 1(b) folded into their epilogues, which
+ * saves one read and one write of the whole activation tensor per folded operator.
+ *   purine_conv_fwd_bias_relu : y = conv(x, w) + b[k]  (b may be NULL), then y = max(y, 0) if relu = 1.
+ *   purine_conv_bwd_data_relu : dx = beta*dx + (act > 0 ? ConvBwdData(dy, w) : 0); act has dx's
+ *       extents and dtype and is the OUTPUT of the ReLU that produced this layer's input (the ReLU
+ *       gradient of the layer below, applied where its input gradient is produced). */
+int purine_conv_fwd_bias_relu(const purine_conv_desc* desc, const purine_tensor* x,
+                              const purine_tensor* w, const purine_tensor* b, purine_tensor* y,
+                              int relu, void* ws, size_t ws_bytes, void* hip_stream);
+int purine_conv_bwd_data_relu(const purine_conv_desc* desc, const purine_tensor* dy,
+                              const purine_tensor* w, const purine_tensor* act, purine_tensor* dx,
+                              float beta, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ConvBwdWeight: dw[k,c,r,s] = beta*dw + sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*sh-ph+r,q*sw-pw+s].
  * A plain sum over the batch (no 1/N), so shards of a data-parallel minibatch add up
  * (paper section 3.4). x and dy share one dtype; dw is F32. The pixel reduction is split into
@@ -160,13 +174,16 @@ typedef enum {
     PURINE_OP_CONCAT_FWD = 9,      /* in: parts...        out: cat                               */
     PURINE_OP_CONCAT_BWD = 10,     /* in: dcat            out: dparts...                         */
     PURINE_OP_SUM = 11,            /* in: terms...        out: sum                               */
-    PURINE_OP_HOST_NOP = 12        /* any in/out; does nothing on the device (bookkeeping tests) */
+    PURINE_OP_HOST_NOP = 12,       /* any in/out; does nothing on the device (bookkeeping tests) */
+    PURINE_OP_CONV_FWD_BIAS_RELU = 13, /* in: x, w, b     out: y   (attrs.relu selects the ReLU)    */
+    PURINE_OP_CONV_BWD_DATA_RELU = 14  /* in: dy, w, act [, dx]  out: dx'                           */
 } purine_op_kind;
 
 typedef struct {
     purine_conv_desc conv;   /* conv ops                                          */
     purine_pool_desc pool;   /* pool ops                                          */
     float  beta;             /* ops with an accumulate form                       */
+    int32_t relu;            /* PURINE_OP_CONV_FWD_BIAS_RELU: apply max(y, 0)     */
     void*  ws;               /* device scratch private to this operator           */
     size_t ws_bytes;
 } purine_op_attrs;

@@ -21,6 +21,7 @@ PURINE_CONV_FWD, PURINE_CONV_BWD_DATA, PURINE_CONV_BWD_WEIGHT = 0, 1, 2
 OP_CONV_FWD, OP_BIAS_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_BIAS_BWD = 0, 1, 2, 3, 4
 OP_RELU_FWD, OP_RELU_BWD, OP_MAXPOOL_FWD, OP_MAXPOOL_BWD = 5, 6, 7, 8
 OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
+OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU = 13, 14
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
@@ -52,7 +53,7 @@ class purine_pool_desc(ctypes.Structure):
 
 class purine_op_attrs(ctypes.Structure):
     _fields_ = [("conv", purine_conv_desc), ("pool", purine_pool_desc), ("beta", ctypes.c_float),
-                ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+                ("relu", ctypes.c_int32), ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -73,6 +74,8 @@ _SIGS = {
     "purine_conv_fwd": (ctypes.c_int, [_D, _T, _T, _T, _vp, _sz, _vp]),
     "purine_conv_bwd_data": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_bwd_weight": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_conv_fwd_bias_relu": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_int, _vp, _sz, _vp]),
+    "purine_conv_bwd_data_relu": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_bias_fwd": (ctypes.c_int, [_T, _T, _vp]),
     "purine_bias_bwd": (ctypes.c_int, [_T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_relu_fwd": (ctypes.c_int, [_T, _T, _vp]),
@@ -226,6 +229,21 @@ def purine_conv_bwd_data(desc, dy, w, dx, beta=0.0, ws=None, stream=None):
            "purine_conv_bwd_data")
 
 
+def purine_conv_fwd_bias_relu(desc, x, w, b, y, relu=True, ws=None, stream=None):
+    p, n = _ws(ws)
+    bd = _ref(tensor_desc(b)) if b is not None else None
+    _check(_lib.purine_conv_fwd_bias_relu(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(w)), bd,
+                                          _ref(tensor_desc(y)), 1 if relu else 0, p, n, _stream(stream)),
+           "purine_conv_fwd_bias_relu")
+
+
+def purine_conv_bwd_data_relu(desc, dy, w, act, dx, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_conv_bwd_data_relu(_ref(desc), _ref(tensor_desc(dy)), _ref(tensor_desc(w)),
+                                          _ref(tensor_desc(act)), _ref(tensor_desc(dx)), float(beta), p, n,
+                                          _stream(stream)), "purine_conv_bwd_data_relu")
+
+
 def purine_conv_bwd_weight(desc, x, dy, dw, beta=0.0, ws=None, stream=None):
     p, n = _ws(ws)
     _check(_lib.purine_conv_bwd_weight(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
@@ -317,8 +335,9 @@ def purine_graph_add_op(g, kind, in_ids, out_ids, thread_id=0, attrs=None):
     return rc
 
 
-def op_attrs(conv=None, pool=None, beta=0.0, ws=None):
+def op_attrs(conv=None, pool=None, beta=0.0, ws=None, relu=False):
     a = purine_op_attrs()
+    a.relu = 1 if relu else 0
     if conv is not None:
         a.conv = conv
     if pool is not None:

@@ -156,8 +156,9 @@ size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype) {
     return plan_bias_bwd((int)dy_dim[0], (int)dy_dim[1], (int)(dy_dim[2] * dy_dim[3])).ws_bytes;
 }
 
-int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
-                    purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream) {
+static int conv_fwd_impl(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
+                         const purine_tensor* b, purine_tensor* y, int relu, void* ws, size_t ws_bytes,
+                         void* hip_stream) {
     int rc;
     if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(w, 4)) ||
         (rc = check_tensor(y, 4)))
@@ -166,17 +167,38 @@ int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const 
     ConvGeom g;
     if ((rc = make_geom(desc, x->dim, w->dim, y->dim, &g))) return rc;
     if (overlaps(y, x) || overlaps(y, w)) return PURINE_E_LAYOUT;
+    PixEpilogue epi;
+    if (b) {
+        if ((rc = check_tensor(b, 1))) return rc;
+        if (b->dtype != y->dtype) return PURINE_E_DTYPE;
+        if (b->dim[0] != y->dim[1]) return PURINE_E_SHAPE;
+        if (overlaps(b, y)) return PURINE_E_LAYOUT;
+        epi.bias = b->data;
+    }
+    if (relu != 0 && relu != 1) return PURINE_E_ARG;
+    epi.relu = relu;
     const PixPlan plan = plan_conv_pix(g, false, x->dtype);
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
-    hipError_t e = launch_conv_pix(x->dtype, g, plan, x->data, w->data, y->data, 0.0f, ws,
+    hipError_t e = launch_conv_pix(x->dtype, g, plan, x->data, w->data, y->data, 0.0f, ws, epi,
                                    (hipStream_t)hip_stream);
     return hip_status(e);
 }
 
-int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
-                         const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
-                         size_t ws_bytes, void* hip_stream) {
+int purine_conv_fwd(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
+                    purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream) {
+    return conv_fwd_impl(desc, x, w, nullptr, y, 0, ws, ws_bytes, hip_stream);
+}
+
+int purine_conv_fwd_bias_relu(const purine_conv_desc* desc, const purine_tensor* x,
+                              const purine_tensor* w, const purine_tensor* b, purine_tensor* y,
+                              int relu, void* ws, size_t ws_bytes, void* hip_stream) {
+    return conv_fwd_impl(desc, x, w, b, y, relu, ws, ws_bytes, hip_stream);
+}
+
+static int conv_bwd_data_impl(const purine_conv_desc* desc, const purine_tensor* dy,
+                              const purine_tensor* w, const purine_tensor* act, purine_tensor* dx,
+                              float beta, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc;
     if ((rc = check_desc(desc)) || (rc = check_tensor(dy, 4)) || (rc = check_tensor(w, 4)) ||
         (rc = check_tensor(dx, 4)) || (rc = check_beta(beta)))
@@ -185,12 +207,33 @@ int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
     ConvGeom g;
     if ((rc = make_geom(desc, dx->dim, w->dim, dy->dim, &g))) return rc;
     if (overlaps(dx, dy) || overlaps(dx, w)) return PURINE_E_LAYOUT;
+    PixEpilogue epi;
+    if (act) {
+        if ((rc = check_tensor(act, 4))) return rc;
+        if (act->dtype != dx->dtype) return PURINE_E_DTYPE;
+        if (!same_dims(act, dx)) return PURINE_E_SHAPE;
+        if (overlaps(act, dx)) return PURINE_E_LAYOUT;
+        epi.mask = act->data;
+    }
     const PixPlan plan = plan_conv_pix(g, true, dy->dtype);
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
-    hipError_t e = launch_conv_pix(dy->dtype, g, plan, dy->data, w->data, dx->data, beta, ws,
+    hipError_t e = launch_conv_pix(dy->dtype, g, plan, dy->data, w->data, dx->data, beta, ws, epi,
                                    (hipStream_t)hip_stream);
     return hip_status(e);
+}
+
+int purine_conv_bwd_data(const purine_conv_desc* desc, const purine_tensor* dy,
+                         const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
+                         size_t ws_bytes, void* hip_stream) {
+    return conv_bwd_data_impl(desc, dy, w, nullptr, dx, beta, ws, ws_bytes, hip_stream);
+}
+
+int purine_conv_bwd_data_relu(const purine_conv_desc* desc, const purine_tensor* dy,
+                              const purine_tensor* w, const purine_tensor* act, purine_tensor* dx,
+                              float beta, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!act) return PURINE_E_NULL;
+    return conv_bwd_data_impl(desc, dy, w, act, dx, beta, ws, ws_bytes, hip_stream);
 }
 
 int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,

@@ -96,8 +96,15 @@ struct ProbeScope {                 // records start on construction and stop on
 };
 
 // Kernel launchers (defined in the .hip files). Each returns a hipError_t from the launch.
+// Optional fused epilogue of the forward / backward-data kernels.
+struct PixEpilogue {
+    const void* bias = nullptr;   // forward: y = conv + bias[k]
+    int relu = 0;                 // forward: y = max(y, 0)
+    const void* mask = nullptr;   // backward-data: dx = mask > 0 ? dx : 0 (mask has dx's extents)
+};
 hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& plan, const void* in,
-                           const void* wt, void* out, float beta, void* ws, hipStream_t st);
+                           const void* wt, void* out, float beta, void* ws, const PixEpilogue& epi,
+                           hipStream_t st);
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
                              const void* dy, float* dw, float beta, void* ws, hipStream_t st);
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st);

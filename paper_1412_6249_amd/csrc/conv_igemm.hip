@@ -462,9 +462,11 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype) {
 }
 
 hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, const void* in,
-                           const void* wt, void* out, float beta, void* ws, hipStream_t st) {
+                           const void* wt, void* out, float beta, void* ws, const PixEpilogue& epi,
+                           hipStream_t st) {
     PixParams p{};
     p.in = in; p.out = out;
+    p.bias = epi.bias; p.relu = epi.relu; p.mask = epi.mask;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W;
     p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
     p.R = g.R; p.S = g.S; p.RS = g.R * g.S;

@@ -73,6 +73,8 @@ bool arity_ok(int kind, int n_in, int n_out, float beta) {
         case PURINE_OP_CONCAT_BWD: return n_in == 1 && n_out >= 1 && n_out <= 64;
         case PURINE_OP_SUM: return n_in >= 1 && n_in <= 8 && n_out == 1;
         case PURINE_OP_HOST_NOP: return n_in >= 0 && n_out >= 0;
+        case PURINE_OP_CONV_FWD_BIAS_RELU: return n_in == 3 && n_out == 1;
+        case PURINE_OP_CONV_BWD_DATA_RELU: return n_in == 3 + extra && n_out == 1;
         default: return false;
     }
 }
@@ -94,6 +96,13 @@ int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
     switch (op.kind) {
         case PURINE_OP_CONV_FWD:
             return purine_conv_fwd(&a.conv, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.ws, a.ws_bytes, st);
+        case PURINE_OP_CONV_FWD_BIAS_RELU:
+            return purine_conv_fwd_bias_relu(&a.conv, T(op.in[0]), T(op.in[1]), T(op.in[2]), T(op.out[0]),
+                                             a.relu, a.ws, a.ws_bytes, st);
+        case PURINE_OP_CONV_BWD_DATA_RELU:
+            if (a.beta != 0.0f && T(op.in[3])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_conv_bwd_data_relu(&a.conv, T(op.in[0]), T(op.in[1]), T(op.in[2]), T(op.out[0]),
+                                             a.beta, a.ws, a.ws_bytes, st);
         case PURINE_OP_BIAS_FWD:
             if (T(op.in[0])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
             return purine_bias_fwd(T(op.in[1]), T(op.out[0]), st);

@@ -48,62 +48,97 @@ struct PixParams {
     int R, S, RS, Kg;             // flat kernel only: filter extents, Kg = Ci*R*S
     FastDiv div_howo, div_wo, div_phases, div_sw, div_rs, div_s;
     float beta;
+    // fused epilogue (all optional): out = relu?(acc + bias[row]) and/or out = (mask[o] > 0 ? acc : 0)
+    const void* bias;   // [Co], same dtype as out; forward only
+    const void* mask;   // same extents and dtype as out: ReLU output whose gradient this pass produces
+    int relu;
     int tiles_i, tiles_pix;
 };
 
-// Epilogue shared by both kernels. Accumulator register e of a 32x32 tile holds row
-// (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
-template <typename T, bool D2S, int TM, int TN>
-__device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
-                                           floatx16 (&acc)[TM][TN], int i_base, int pix_base,
-                                           int khalf) {
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-        const int pix = pix_base + b * 32;
-        if (pix >= p.M) continue;
-        const int n = fastdiv(pix, p.div_howo);
-        const int rem = pix - n * p.HoWo;
+// Epilogue shared by the kernels. Accumulator register e of a 32x32 tile holds row
+// (e/4)*8 + (lane/32)*4 + e%4, column lane%32. Optional pieces (bias, ReLU, ReLU-gradient mask,
+// accumulate) are uniform branches; what an element needs from memory (bias or mask value, old
+// output) is fetched for the 16 elements of one MFMA tile BEFORE its 16 stores, so the loads
+// overlap instead of forming sixteen load-wait-store round trips, while only 16-32 extra registers
+// are live.
+template <typename T, bool D2S>
+struct TileAddr {
+    const PixParams& p;
+    int obase, hb, wb;
+    __device__ __forceinline__ TileAddr(const PixParams& p_, int n, int rem) : p(p_), hb(0), wb(0) {
         if (!D2S) {
-            const int obase = n * p.Co * p.HoWo + rem;
-#pragma unroll
-            for (int a = 0; a < TM; ++a)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int i = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                    if (i < p.Co) {
-                        const int o = obase + i * p.HoWo;
-                        float v = acc[a][b][e];
-                        if (p.beta != 0.0f) v += Elem<T>::load(out, o);
-                        Elem<T>::store(out, o, v);
-                    }
-                }
+            obase = n * p.Co * p.HoWo + rem;
         } else {
             // depth-to-space: row i = (c, a, b) of coarse pixel (n, hq, wq) is
             // dx[n, c, hq*sh + a - ph, wq*sw + b - pw]
             const int hq = fastdiv(rem, p.div_wo);
             const int wq = rem - hq * p.Wo;
-            const int hb = (hq + p.hq_min) * p.sh - p.ph;
-            const int wb = (wq + p.wq_min) * p.sw - p.pw;
-            const int obase = n * p.C * p.H * p.W;
+            hb = (hq + p.hq_min) * p.sh - p.ph;
+            wb = (wq + p.wq_min) * p.sw - p.pw;
+            obase = n * p.C * p.H * p.W;
+        }
+    }
+    // element offset of row i (0 when the row or position does not exist) and whether it exists
+    __device__ __forceinline__ int at(int i, bool& ok) const {
+        int off;
+        if (!D2S) {
+            ok = i < p.Co;
+            off = obase + i * p.HoWo;
+        } else {
+            const int c = fastdiv(i, p.div_phases);
+            const int ab = i - c * p.phases;
+            const int pa = fastdiv(ab, p.div_sw);
+            const int pb = ab - pa * p.sw;
+            const int h = hb + pa, w = wb + pb;
+            ok = (i < p.Co) & ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
+            off = obase + (c * p.H + h) * p.W + w;
+        }
+        return ok ? off : 0;
+    }
+};
+
+template <typename T, bool D2S, int TM, int TN>
+__device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
+                                           floatx16 (&acc)[TM][TN], int i_base, int pix_base,
+                                           int khalf) {
+    const T* __restrict__ bias = (const T*)p.bias;
+    const T* __restrict__ mask = (const T*)p.mask;
+    const bool has_bias = !D2S && bias != nullptr, has_mask = mask != nullptr, has_beta = p.beta != 0.0f;
 #pragma unroll
-            for (int a = 0; a < TM; ++a)
+    for (int b = 0; b < TN; ++b) {
+        const int pix = pix_base + b * 32;
+        if (pix >= p.M) continue;
+        const int n = fastdiv(pix, p.div_howo);
+        const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const int row0 = i_base + a * 32 + khalf * 4;
+            float t[16], o[16];
+            bool ok;
+            if (has_bias) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    const int i = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                    if (i < p.Co) {
-                        const int c = fastdiv(i, p.div_phases);
-                        const int ab = i - c * p.phases;
-                        const int pa = fastdiv(ab, p.div_sw);
-                        const int pb = ab - pa * p.sw;
-                        const int h = hb + pa, w = wb + pb;
-                        if ((unsigned)h < (unsigned)p.H && (unsigned)w < (unsigned)p.W) {
-                            const int o = obase + (c * p.H + h) * p.W + w;
-                            float v = acc[a][b][e];
-                            if (p.beta != 0.0f) v += Elem<T>::load(out, o);
-                            Elem<T>::store(out, o, v);
-                        }
-                    }
+                    const int i = row0 + (e >> 2) * 8 + (e & 3);
+                    t[e] = Elem<T>::load(bias, i < p.Co ? i : 0);
                 }
+            } else if (has_mask) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
+            }
+            if (has_beta) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[e] = Elem<T>::load(out, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int off = addr.at(row0 + (e >> 2) * 8 + (e & 3), ok);
+                float v = acc[a][b][e];
+                if (has_bias) v += t[e];
+                if (p.relu) v = v > 0.0f ? v : 0.0f;
+                if (has_mask) v = t[e] > 0.0f ? v : 0.0f;
+                if (has_beta) v += o[e];
+                if (ok) Elem<T>::store(out, off, v);
+            }
         }
     }
 }

@@ -26,9 +26,12 @@ def _pcode(dtype):
 class GraphBuilder:
     """Owns the device tensors (by name) and the purine_graph handle."""
 
-    def __init__(self, device="cuda:0", inplace=True):
+    def __init__(self, device="cuda:0", inplace=True, fuse=False):
         self.device = torch.device(device)
         self.inplace = inplace
+        self.fuse = fuse                 # fold Bias/ReLU and the ReLU gradient into the conv operators
+        self.relu_outputs = set()        # tensors that are the output of a ReLU
+        self.masked_grads = set()        # gradients that already carry their layer's ReLU mask
         self.g = B.purine_graph_create()
         self.t = {}          # name -> torch tensor (storage)
         self.ids = {}        # name -> tensor vertex id
@@ -76,9 +79,19 @@ class GraphBuilder:
     def conv_forward(self, L, x, w, b, prefix, relu, thread=T_MAIN):
         """x -> Conv -> Bias [-> ReLU]; returns the name of the layer output vertex."""
         desc = B.conv_desc(L.stride, L.pad)
-        y0 = self.new(prefix + ".y", L.y_shape, L.dtype)
         ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_FWD, desc, L.x_shape, L.w_shape,
                                                           _pcode(L.dtype)))
+        if self.fuse:
+            out = self.new(prefix + (".a" if relu else ".yb"), L.y_shape, L.dtype)
+            self.op(B.OP_CONV_FWD_BIAS_RELU, [x, w, b], [out], thread,
+                    B.op_attrs(conv=desc, ws=ws, relu=relu))
+            if relu:
+                self.relu_outputs.add(out)
+            rec = dict(layer=L, prefix=prefix, x=x, w=w, b=b, y=None, yb=None, out=out, relu=relu,
+                       fused_fwd=True)
+            self.conv_records.append(rec)
+            return out, rec
+        y0 = self.new(prefix + ".y", L.y_shape, L.dtype)
         self.op(B.OP_CONV_FWD, [x, w], [y0], thread, B.op_attrs(conv=desc, ws=ws))
         # Bias is in place by definition of the operator (y += b)
         if self.inplace:
@@ -94,7 +107,9 @@ class GraphBuilder:
         if relu:
             out = self.version(prefix + ".a", y1)
             self.op(B.OP_RELU_FWD, [y1], [out], thread)
-        rec = dict(layer=L, prefix=prefix, x=x, w=w, b=b, y=y0, yb=y1, out=out, relu=relu)
+            self.relu_outputs.add(out)
+        rec = dict(layer=L, prefix=prefix, x=x, w=w, b=b, y=y0, yb=y1, out=out, relu=relu,
+                   fused_fwd=False)
         self.conv_records.append(rec)
         return out, rec
 
@@ -103,9 +118,11 @@ class GraphBuilder:
         L, p = rec["layer"], rec["prefix"]
         desc = B.conv_desc(L.stride, L.pad)
         dy = dout
-        if rec["relu"]:
+        rec["relu_bwd_op"] = False
+        if rec["relu"] and dout not in self.masked_grads:
             dy = self.version(p + ".dyb", dout)
             self.op(B.OP_RELU_BWD, [rec["out"], dout], [dy], thread)
+            rec["relu_bwd_op"] = True
         db = self.new(p + ".db", (L.K,), "f32")
         self.op(B.OP_BIAS_BWD, [dy], [db], t_b,
                 B.op_attrs(ws=self.workspace(B.purine_bias_bwd_workspace_bytes(L.y_shape, _pcode(L.dtype)))))
@@ -118,7 +135,15 @@ class GraphBuilder:
             dx = self.new(p + ".dx", L.x_shape, L.dtype)
             ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_DATA, desc, L.x_shape,
                                                               L.w_shape, _pcode(L.dtype)))
-            self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"]], [dx], thread, B.op_attrs(conv=desc, ws=ws))
+            if self.fuse and rec["x"] in self.relu_outputs:
+                # the layer below ends in a ReLU whose output is our input: apply its gradient mask here
+                self.op(B.OP_CONV_BWD_DATA_RELU, [dy, rec["w"], rec["x"]], [dx], thread,
+                        B.op_attrs(conv=desc, ws=ws))
+                self.masked_grads.add(dx)
+                rec["fused_bwd"] = True
+            else:
+                self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"]], [dx], thread, B.op_attrs(conv=desc, ws=ws))
+                rec["fused_bwd"] = False
         rec.update(dy=dy, db=db, dw=dw, dx=dx)
         return dx
 
@@ -162,14 +187,15 @@ def _default_init(seed):
     return init
 
 
-def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True):
+def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True,
+                   fuse=False):
     """Builds the bi-graph of config `cfg` (1..5). `batch` overrides the batch size (tests).
     `init(name, shape, dtype, kind)` supplies source tensors (kind in x, w, b, dy); by default they
     are drawn on the device from the seed. Returns the GraphBuilder; gb.run() performs one full
     forward + backward step."""
     init = init or _default_init(seed)
     layers = [l.with_batch(batch) if batch else l for l in CONV_LAYERS[cfg]]
-    gb = GraphBuilder(inplace=inplace)
+    gb = GraphBuilder(inplace=inplace, fuse=fuse)
     tw = T_WGRAD if multi_stream else T_MAIN
     tb = T_BGRAD if multi_stream else T_MAIN
 

@@ -21,18 +21,29 @@ def check_conv_record(gb, rec, tol):
     from gpu_util import rel_l2
     L = rec["layer"]
     x, w, b = host(gb, rec["x"]), host(gb, rec["w"]), host(gb, rec["b"])
-    y = host(gb, rec["y"])
-    assert rel_l2(y, oracle.conv_fwd(x, w, L.stride, L.pad)) <= tol, (L.name, "fwd")
-    yb = host(gb, rec["yb"])
-    # Bias works in place on an exact copy of the Conv output, so y is what it read
-    assert rel_l2(yb, oracle.bias_fwd(y, b)) <= tol, (L.name, "bias")
-    if rec["relu"]:
-        assert np.array_equal(host(gb, rec["out"]), oracle.relu_fwd(yb)), (L.name, "relu")
+    if rec["fused_fwd"]:
+        # fused Conv+Bias(+ReLU) vertex: ReLU is continuous, so the composition is compared as one
+        ref = oracle.bias_fwd(oracle.conv_fwd(x, w, L.stride, L.pad), b)
+        if rec["relu"]:
+            ref = np.maximum(ref, 0.0)
+        assert rel_l2(host(gb, rec["out"]), ref) <= tol, (L.name, "fused fwd")
+    else:
+        y = host(gb, rec["y"])
+        assert rel_l2(y, oracle.conv_fwd(x, w, L.stride, L.pad)) <= tol, (L.name, "fwd")
+        yb = host(gb, rec["yb"])
+        # Bias works in place on an exact copy of the Conv output, so y is what it read
+        assert rel_l2(yb, oracle.bias_fwd(y, b)) <= tol, (L.name, "bias")
+        if rec["relu"]:
+            assert np.array_equal(host(gb, rec["out"]), oracle.relu_fwd(yb)), (L.name, "relu")
     dy = host(gb, rec["dy"])
-    if rec["relu"]:
+    if rec["relu_bwd_op"]:
         dout_name = gb.ops_by_out[rec["dy"]][2][1]
         assert np.array_equal(dy, oracle.relu_bwd(host(gb, rec["out"]), host(gb, dout_name))), (L.name, "relu_bwd")
-    assert rel_l2(host(gb, rec["dx"]), oracle.conv_bwd_data(dy, w, x.shape, L.stride, L.pad)) <= tol, (L.name, "dx")
+    ref_dx = oracle.conv_bwd_data(dy, w, x.shape, L.stride, L.pad)
+    if rec.get("fused_bwd"):
+        ref_dx = np.where(x > 0, ref_dx, 0.0)        # mask of the ReLU below, taken from its actual output
+        assert np.array_equal(host(gb, rec["dx"]) != 0, (x > 0) & (host(gb, rec["dx"]) != 0))
+    assert rel_l2(host(gb, rec["dx"]), ref_dx) <= tol, (L.name, "dx")
     assert rel_l2(host(gb, rec["dw"]), oracle.conv_bwd_weight(x, dy, w.shape, L.stride, L.pad)) <= tol, (L.name, "dw")
     assert rel_l2(host(gb, rec["db"]), oracle.bias_bwd(dy)) <= tol, (L.name, "db")
 
@@ -69,10 +80,11 @@ def legal_order(gb):
                 assert pos[wtr] < pos[oid]
 
 
+@pytest.mark.parametrize("fuse", [False, True], ids=["plain", "fused"])
 @pytest.mark.parametrize("cfg,batch", [(1, None), (2, 2), (3, 2), (4, 2), (5, 1)])
-def test_workload_graph_teacher_forced(cfg, batch):
+def test_workload_graph_teacher_forced(cfg, batch, fuse):
     from paper_1412_6249_amd.layers import build_workload
-    gb = build_workload(cfg, batch=batch, inplace=False)
+    gb = build_workload(cfg, batch=batch, inplace=False, fuse=fuse)
     try:
         index_ops(gb)
         gb.run()
@@ -99,8 +111,8 @@ def test_inplace_and_multistream_graphs_give_identical_bits(cfg, batch):
     choices: gradients must be bit-identical to the out-of-place, single-stream run, twice in a row."""
     import torch
     from paper_1412_6249_amd.layers import build_workload
-    ref = build_workload(cfg, batch=batch, inplace=False, multi_stream=False)
-    fast = build_workload(cfg, batch=batch, inplace=True, multi_stream=True)
+    ref = build_workload(cfg, batch=batch, inplace=False, multi_stream=False, fuse=True)
+    fast = build_workload(cfg, batch=batch, inplace=True, multi_stream=True, fuse=True)
     try:
         ref.run()
         for _ in range(2):
