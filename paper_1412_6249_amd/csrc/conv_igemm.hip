@@ -37,7 +37,7 @@ constexpr int BK = 16;  // slab depth along the reduction (fp32 kernels)
 // Tap-major kernel. MINUS: the gather walks backwards (h = g_h - r), as backward-data does.
 // D2S: depth-to-space epilogue of the phase-folded strided backward-data.
 // Workgroup = WM x WN wavefronts, each owning TM x TN MFMA tiles of 32 x 32.
-template <typename T, bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -187,14 +187,14 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
         __syncthreads();
     }
 
-    store_tile<T, D2S, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
+    store_tile<T, D2S, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
 }
 
 // ------------------------------------------------------------------------------------------------
 // Flat kernel: forward pass of layers with fewer than 16 input channels. The reduction index is
 // kk = (c, r, s) flattened, which equals the memory order of one filter row, and each slab row
 // decodes its own (c, r, s) on the scalar unit (rows are uniform per wavefront).
-template <typename T, int TM, int TN, int WM, int WN>
+template <typename T, bool FUSED, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
         __syncthreads();
     }
 
-    store_tile<T, false, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
+    store_tile<T, false, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -385,39 +385,50 @@ constexpr TileCfg kTiles[] = {
     {64, 128, 0.90f},  {32, 256, 0.85f}, {64, 64, 0.80f},  {32, 128, 0.75f},
 };
 
-template <typename T, bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_tap(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <typename T, int TM, int TN, int WM, int WN>
+template <typename T, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_flat(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_flat_kernel<T, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
+template <typename T, bool MINUS, bool D2S, bool FUSED>
+hipError_t dispatch_tap2(PixParams& p, int bm, int bn, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_tap<T, MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
+    PURINE_TILE_SWITCH(CALL)
+#undef CALL
+}
 template <typename T, bool MINUS, bool D2S>
 hipError_t dispatch_tap(PixParams& p, int bm, int bn, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_tap<T, MINUS, D2S, TM, TN, WM, WN>(p, st)
+    const bool fused = p.bias || p.relu || p.mask;
+    return fused ? dispatch_tap2<T, MINUS, D2S, true>(p, bm, bn, st)
+                 : dispatch_tap2<T, MINUS, D2S, false>(p, bm, bn, st);
+}
+template <typename T, bool FUSED>
+hipError_t dispatch_flat2(PixParams& p, int bm, int bn, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_flat<T, FUSED, TM, TN, WM, WN>(p, st)
     PURINE_TILE_SWITCH(CALL)
 #undef CALL
 }
 template <typename T>
 hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_flat<T, TM, TN, WM, WN>(p, st)
-    PURINE_TILE_SWITCH(CALL)
-#undef CALL
+    const bool fused = p.bias || p.relu || p.mask;
+    return fused ? dispatch_flat2<T, true>(p, bm, bn, st) : dispatch_flat2<T, false>(p, bm, bn, st);
 }
 
 }  // namespace

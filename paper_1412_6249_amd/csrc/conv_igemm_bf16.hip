@@ -21,7 +21,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKH = 32;        // slab depth (channels)
 constexpr int LDK = BKH + 8;   // LDS row pitch in bf16 elements
 
-template <bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -167,26 +167,31 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         __syncthreads();
     }
 
-    store_tile<uint16_t, D2S, TM, TN>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
+    store_tile<uint16_t, D2S, FUSED, TM, TN>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
                                       j0 + wn * TN * 32 + (lane & 31), lane >> 5);
 }
 
-template <bool MINUS, bool D2S, int TM, int TN, int WM, int WN>
+template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_one(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_tap_bf16_kernel<MINUS, D2S, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_tap_bf16_kernel<MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <bool MINUS, bool D2S>
-hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_one<MINUS, D2S, TM, TN, WM, WN>(p, st)
+template <bool MINUS, bool D2S, bool FUSED>
+hipError_t by_tile2(PixParams& p, int bm, int bn, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_one<MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
     PURINE_TILE_SWITCH(CALL)
 #undef CALL
+}
+template <bool MINUS, bool D2S>
+hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
+    const bool fused = p.bias || p.relu || p.mask;
+    return fused ? by_tile2<MINUS, D2S, true>(p, bm, bn, st) : by_tile2<MINUS, D2S, false>(p, bm, bn, st);
 }
 
 }  // namespace

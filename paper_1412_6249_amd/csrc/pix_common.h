@@ -97,10 +97,34 @@ struct TileAddr {
     }
 };
 
-template <typename T, bool D2S, int TM, int TN>
+template <typename T, bool D2S, bool FUSED, int TM, int TN>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
                                            int khalf) {
+    if (!FUSED) {
+        // plain store (optionally accumulating): no staging arrays, so the kernels that do not fuse
+        // anything keep their register count and occupancy
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int pix = pix_base + b * 32;
+            if (pix >= p.M) continue;
+            const int n = fastdiv(pix, p.div_howo);
+            const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    bool ok;
+                    const int off = addr.at(i_base + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3), ok);
+                    if (ok) {
+                        float v = acc[a][b][e];
+                        if (p.beta != 0.0f) v += Elem<T>::load(out, off);
+                        Elem<T>::store(out, off, v);
+                    }
+                }
+        }
+        return;
+    }
     const T* __restrict__ bias = (const T*)p.bias;
     const T* __restrict__ mask = (const T*)p.mask;
     const bool has_bias = !D2S && bias != nullptr, has_mask = mask != nullptr, has_beta = p.beta != 0.0f;
