@@ -47,6 +47,7 @@ struct WgradParams {
     FastDiv div_pq, div_q, div_rs, div_s;
     int chunk;         // pixels per split, a multiple of the slab depth
     int tiles_i, tiles_j, splits;
+    int c_tiles;       // per-tap column mode: channel tiles per tap (tiles_j = R*S*c_tiles)
 };
 
 
@@ -70,7 +71,9 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype);
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and
 // for the launch.
 struct WgradPlan {
-    int bm, bn;        // tile extents along k and along (c,r,s)
+    bool tap;          // columns are the channels of one tap (C >= 64) instead of flattened (c,r,s)
+    int c_tiles;
+    int bm, bn;        // tile extents along k and along the columns
     int tiles_i, tiles_j, splits, chunk;
     size_t ws_bytes;
 };

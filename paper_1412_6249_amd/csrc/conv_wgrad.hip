@@ -24,11 +24,55 @@ template <> __device__ __forceinline__ float ld<uint16_t>(const uint16_t* p, int
     return __uint_as_float(((uint32_t)p[i]) << 16);
 }
 
-template <typename T, int TM, int TN, int WM, int WN>
+// tile extents -> (TM, TN, WM, WN)
+#define WGRAD_TILE_SWITCH(CALL)                                                  \
+    switch (plan.bm * 1000 + plan.bn) {                                          \
+        case 128128: return CALL(2, 2, 2, 2);                                    \
+        case 128096: return CALL(1, 3, 4, 1);                                    \
+        case 128064: return CALL(1, 2, 4, 1);                                    \
+        case 96128:  return CALL(3, 1, 1, 4);                                    \
+        case 64128:  return CALL(2, 1, 1, 4);                                    \
+        case 64064:  return CALL(1, 1, 2, 2);                                    \
+        case 32128:  return CALL(1, 1, 1, 4);                                    \
+        default: return hipErrorInvalidValue;                                    \
+    }
+
+// Column modes of the output tile.
+//   TAP = false: columns are the flattened (c, r, s) index; every column has its own tap, so every
+//                gathered element carries its own bounds test (layers with few input channels).
+//   TAP = true : the workgroup owns ONE tap (r, s) and its columns are input channels c. The bounds
+//                test and the tap offset are then per pixel, once per slab, and a gathered element
+//                is one add and one load. Partials are laid out [split][tap][k][c] (coalesced along
+//                c); the reduction kernel writes them back in KCRS order.
+struct TileWhere {
+    int split, i0, j0, tap_r, tap_s, tap;
+};
+template <bool TAP, int BM, int BN>
+__device__ __forceinline__ TileWhere locate_tile(const WgradParams& p) {
+    TileWhere t;
+    int bid = blockIdx.x;
+    const int per_split = p.tiles_i * p.tiles_j;
+    t.split = bid / per_split;
+    bid -= t.split * per_split;
+    t.i0 = (bid % p.tiles_i) * BM;
+    const int jt = bid / p.tiles_i;
+    if (TAP) {
+        t.tap = jt / p.c_tiles;
+        t.j0 = (jt - t.tap * p.c_tiles) * BN;
+        t.tap_r = fastdiv(t.tap, p.div_s);
+        t.tap_s = t.tap - t.tap_r * p.S;
+    } else {
+        t.tap = t.tap_r = t.tap_s = 0;
+        t.j0 = jt * BN;
+    }
+    return t;
+}
+
+template <typename T, bool TAP, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;   // output channels k
-    constexpr int BN = WN * TN * 32;   // filter taps (c,r,s)
+    constexpr int BN = WN * TN * 32;   // columns: (c,r,s) flattened, or channels of one tap
     constexpr int LDA = BM + 2, LDB = BN + 2;
     constexpr int RPP = NT / BK;       // tile columns covered per pass (lanes 0..15 run along pixels)
     constexpr int A_PASSES = BM / RPP, B_PASSES = BN / RPP;
@@ -43,23 +87,23 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    int bid = blockIdx.x;
-    const int split = bid / (p.tiles_i * p.tiles_j);
-    bid -= split * p.tiles_i * p.tiles_j;
-    const int i0 = (bid % p.tiles_i) * BM;
-    const int j0 = (bid / p.tiles_i) * BN;
-    const int pix_begin = split * p.chunk;
+    const TileWhere tw = locate_tile<TAP, BM, BN>(p);
+    const int i0 = tw.i0, j0 = tw.j0;
+    const int pix_begin = tw.split * p.chunk;
     const int pix_end = min(p.M, pix_begin + p.chunk);
 
     const int t_kk = tid % BK;   // this thread's pixel inside a slab
     const int t_col = tid / BK;  // first tile column it serves
 
-    // taps served by this thread: fixed for the whole kernel
+    // columns served by this thread: fixed for the whole kernel
     int j_off[B_PASSES], j_rs[B_PASSES];
 #pragma unroll
     for (int ps = 0; ps < B_PASSES; ++ps) {
         const int j = j0 + t_col + ps * RPP;
-        if (j < p.CRS) {
+        if (TAP) {
+            j_off[ps] = j * p.HW;
+            j_rs[ps] = j < p.C ? 0 : -1;
+        } else if (j < p.CRS) {
             const int c = fastdiv(j, p.div_rs);
             const int rs = j - c * p.RS;
             const int r = fastdiv(rs, p.div_s);
@@ -73,6 +117,7 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
     }
 
     float a_reg[A_PASSES], b_reg[B_PASSES];
+    unsigned a_ok = 0u, b_ok = 0u;   // validity bits; the zero-fill happens at the LDS store
 
     auto load_slab = [&](int slab) {
         const int pix = pix_begin + slab * BK + t_kk;
@@ -83,26 +128,42 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
         const int pp = fastdiv(pq, p.div_q);
         const int qq = pq - pp * p.Q;
         const int a_base = n * p.K * p.PQ + pq;
+        a_ok = 0u; b_ok = 0u;
 #pragma unroll
         for (int ps = 0; ps < A_PASSES; ++ps) {
             const int i = i0 + t_col + ps * RPP;
-            a_reg[ps] = (pv && i < p.K) ? ld<T>(dy, a_base + i * p.PQ) : 0.0f;
+            const bool ok = pv & (i < p.K);
+            a_reg[ps] = ld<T>(dy, ok ? a_base + i * p.PQ : 0);   // clamped, branch-free
+            a_ok |= (ok ? 1u : 0u) << ps;
         }
-        const int hb = pp * p.sh - p.ph, wb = qq * p.sw - p.pw;
+        const int hb = pp * p.sh - p.ph + tw.tap_r, wb = qq * p.sw - p.pw + tw.tap_s;
         const int b_base = n * p.C * p.HW + hb * p.W + wb;
+        if (TAP) {
+            const bool in = pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W);
 #pragma unroll
-        for (int ps = 0; ps < B_PASSES; ++ps) {
-            const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
-            const bool ok = pv && j_rs[ps] >= 0 && (unsigned)(hb + r) < (unsigned)p.H &&
-                            (unsigned)(wb + s) < (unsigned)p.W;
-            b_reg[ps] = ok ? ld<T>(x, b_base + j_off[ps]) : 0.0f;
+            for (int ps = 0; ps < B_PASSES; ++ps) {
+                const bool ok = in & (j_rs[ps] >= 0);
+                b_reg[ps] = ld<T>(x, ok ? b_base + j_off[ps] : 0);
+                b_ok |= (ok ? 1u : 0u) << ps;
+            }
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < B_PASSES; ++ps) {
+                const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
+                const bool ok = pv & (j_rs[ps] >= 0) & ((unsigned)(hb + r) < (unsigned)p.H) &
+                                ((unsigned)(wb + s) < (unsigned)p.W);
+                b_reg[ps] = ld<T>(x, ok ? b_base + j_off[ps] : 0);
+                b_ok |= (ok ? 1u : 0u) << ps;
+            }
         }
     };
     auto store_slab = [&](int buf) {
 #pragma unroll
-        for (int ps = 0; ps < A_PASSES; ++ps) As[buf][t_kk * LDA + t_col + ps * RPP] = a_reg[ps];
+        for (int ps = 0; ps < A_PASSES; ++ps)
+            As[buf][t_kk * LDA + t_col + ps * RPP] = ((a_ok >> ps) & 1u) ? a_reg[ps] : 0.0f;
 #pragma unroll
-        for (int ps = 0; ps < B_PASSES; ++ps) Bs[buf][t_kk * LDB + t_col + ps * RPP] = b_reg[ps];
+        for (int ps = 0; ps < B_PASSES; ++ps)
+            Bs[buf][t_kk * LDB + t_col + ps * RPP] = ((b_ok >> ps) & 1u) ? b_reg[ps] : 0.0f;
     };
 
     floatx16 acc[TM][TN];
@@ -126,41 +187,49 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
 
     for (int slab = 0; slab < n_slabs; ++slab) {
         const int buf = slab & 1;
-        const bool more = slab + 1 < n_slabs;
-        if (more) load_slab(slab + 1);
+        load_slab(slab + 1);   // past the chunk: every value is masked to zero
+        float av[2][TM], bv[2][TN];   // operand fragments, double-buffered across k-steps
+#pragma unroll
+        for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * LDA + a_off + a * 32];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * LDB + b_off + b * 32];
 #pragma unroll
         for (int ks = 0; ks < BK / 2; ++ks) {
-            const int row = 2 * ks + khalf;
-            float av[TM], bv[TN];
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks + 1 < BK / 2) {
+                const int row = 2 * (ks + 1) + khalf;
 #pragma unroll
-            for (int a = 0; a < TM; ++a) av[a] = As[buf][row * LDA + a_off + a * 32];
+                for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * LDA + a_off + a * 32];
 #pragma unroll
-            for (int b = 0; b < TN; ++b) bv[b] = Bs[buf][row * LDB + b_off + b * 32];
+                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * LDB + b_off + b * 32];
+            }
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a], bv[b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
         }
-        if (more) store_slab(buf ^ 1);
+        __builtin_amdgcn_sched_barrier(0);   // keep the LDS stores (and their load waits) below the MFMAs
+        store_slab(buf ^ 1);
         __syncthreads();
     }
 
-    float* __restrict__ out = p.out + (size_t)split * p.K * p.CRS;
+    // partial tile: [split][k][(c,r,s)] or, per tap, [split][tap][k][c]
+    const int ncol = TAP ? p.C : p.CRS;
+    float* __restrict__ out = p.out + (size_t)tw.split * p.K * p.CRS + (TAP ? (size_t)tw.tap * p.K * p.C : 0);
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int j = j0 + b_off + b * 32;
-        if (j >= p.CRS) continue;
+        if (j >= ncol) continue;
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                if (i < p.K) out[(size_t)i * p.CRS + j] = acc[a][b][e];
+                if (i < p.K) out[(size_t)i * ncol + j] = acc[a][b][e];
             }
     }
 }
-
 
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA variant (v_mfma_f32_32x32x16_bf16): the reduction runs over pixels, and NCHW keeps the
@@ -172,7 +241,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKP = 32;
 constexpr int LDP = BKP + 8;
 
-template <bool VEC_A, int TM, int TN, int WM, int WN>
+template <bool VEC_A, bool TAP, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -192,11 +261,8 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    int bid = blockIdx.x;
-    const int split = bid / (p.tiles_i * p.tiles_j);
-    bid -= split * p.tiles_i * p.tiles_j;
-    const int i0 = (bid % p.tiles_i) * BM;
-    const int j0 = (bid / p.tiles_i) * BN;
+    const TileWhere tw = locate_tile<TAP, BM, BN>(p);
+    const int split = tw.split, i0 = tw.i0, j0 = tw.j0;
     const int pix_begin = split * p.chunk;
     const int pix_end = min(p.M, pix_begin + p.chunk);
 
@@ -207,7 +273,10 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
 #pragma unroll
     for (int ps = 0; ps < B_PASSES; ++ps) {
         const int j = j0 + t_row + ps * RPP;
-        if (j < p.CRS) {
+        if (TAP) {
+            j_off[ps] = j * p.HW;
+            j_rs[ps] = j < p.C ? 0 : -1;
+        } else if (j < p.CRS) {
             const int c = fastdiv(j, p.div_rs);
             const int rs = j - c * p.RS;
             const int r = fastdiv(rs, p.div_s);
@@ -259,13 +328,19 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
             }
         }
         b_ok = 0u;
-        const int hb = pp * p.sh - p.ph, wb = qq * p.sw - p.pw;
+        const int hb = pp * p.sh - p.ph + tw.tap_r, wb = qq * p.sw - p.pw + tw.tap_s;
         const int b_base = n * p.C * p.HW + hb * p.W + wb;
+        const bool in = pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W);
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
-            const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
-            const bool ok = pv & (j_rs[ps] >= 0) & ((unsigned)(hb + r) < (unsigned)p.H) &
-                            ((unsigned)(wb + s) < (unsigned)p.W);
+            bool ok;
+            if (TAP) {
+                ok = in & (j_rs[ps] >= 0);
+            } else {
+                const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
+                ok = pv & (j_rs[ps] >= 0) & ((unsigned)(hb + r) < (unsigned)p.H) &
+                     ((unsigned)(wb + s) < (unsigned)p.W);
+            }
             b_reg[ps] = x[ok ? b_base + j_off[ps] : 0];
             b_ok |= (ok ? 1u : 0u) << ps;
         }
@@ -332,40 +407,39 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
         __syncthreads();
     }
 
-    float* __restrict__ out = p.out + (size_t)split * p.K * p.CRS;
+    const int ncol = TAP ? p.C : p.CRS;
+    float* __restrict__ out = p.out + (size_t)split * p.K * p.CRS + (TAP ? (size_t)tw.tap * p.K * p.C : 0);
     const int jb = j0 + wn * TN * 32 + (lane & 31);
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int j = jb + b * 32;
-        if (j >= p.CRS) continue;
+        if (j >= ncol) continue;
 #pragma unroll
         for (int a = 0; a < TM; ++a)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-                if (i < p.K) out[(size_t)i * p.CRS + j] = acc[a][b][e];
+                if (i < p.K) out[(size_t)i * ncol + j] = acc[a][b][e];
             }
     }
 }
 
-template <bool VEC_A, int TM, int TN, int WM, int WN>
+template <bool VEC_A, bool TAP, int TM, int TN, int WM, int WN>
 hipError_t launch_tile_bf16(WgradParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((wgrad_bf16_kernel<VEC_A, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((wgrad_bf16_kernel<VEC_A, TAP, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <bool VEC_A>
+template <bool VEC_A, bool TAP>
 hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
-    if (plan.bm == 128 && plan.bn == 128) return launch_tile_bf16<VEC_A, 2, 2, 2, 2>(p, st);
-    if (plan.bm == 96 && plan.bn == 128) return launch_tile_bf16<VEC_A, 3, 1, 1, 4>(p, st);
-    if (plan.bm == 64 && plan.bn == 128) return launch_tile_bf16<VEC_A, 2, 1, 1, 4>(p, st);
-    if (plan.bm == 32 && plan.bn == 128) return launch_tile_bf16<VEC_A, 1, 1, 1, 4>(p, st);
-    return hipErrorInvalidValue;
+#define CALL(TM, TN, WM, WN) launch_tile_bf16<VEC_A, TAP, TM, TN, WM, WN>(p, st)
+    WGRAD_TILE_SWITCH(CALL)
+#undef CALL
 }
 
 // dw[i] = beta*dw[i] + partial[0][i] + partial[1][i] + ... summed in a fixed tree: a workgroup owns
@@ -374,10 +448,11 @@ hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) 
 // order through LDS. The order never depends on timing, so the result is bit-identical run to run.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial,
                                                            float* __restrict__ dw, int n,
-                                                           int splits, float beta) {
+                                                           int splits, float beta, int tap_major,
+                                                           int K, int C, int RS) {
     __shared__ float red[16][17];
     const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
-    const int i = blockIdx.x * 16 + e;
+    const int i = blockIdx.x * 16 + e;      // index in the partials' own order (coalesced reads)
     float acc = 0.0f;
     if (i < n) {
         int s = sl;
@@ -393,31 +468,35 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     red[sl][e] = acc;
     __syncthreads();
     if (sl == 0 && i < n) {
-        float t = beta != 0.0f ? dw[i] : 0.0f;
+        int dst = i;
+        if (tap_major) {   // partials are [tap][k][c]; dw is [k][c][tap]
+            const int tap = i / (K * C);
+            const int kc = i - tap * (K * C);
+            dst = kc * RS + tap;
+        }
+        float t = beta != 0.0f ? dw[dst] : 0.0f;
 #pragma unroll
         for (int l = 0; l < 16; ++l) t += red[l][e];
-        dw[i] = t;
+        dw[dst] = t;
     }
 }
 
-template <typename T, int TM, int TN, int WM, int WN>
+template <typename T, bool TAP, int TM, int TN, int WM, int WN>
 hipError_t launch_tile(WgradParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((wgrad_kernel<T, TM, TN, WM, WN>), dim3((unsigned)total), dim3(WM * WN * 64),
+    hipLaunchKernelGGL((wgrad_kernel<T, TAP, TM, TN, WM, WN>), dim3((unsigned)total), dim3(WM * WN * 64),
                        0, st, p);
     return hipGetLastError();
 }
 
-template <typename T>
-hipError_t dispatch(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
-    if (plan.bm == 128 && plan.bn == 128) return launch_tile<T, 2, 2, 2, 2>(p, st);
-    if (plan.bm == 96 && plan.bn == 128) return launch_tile<T, 3, 1, 1, 4>(p, st);
-    if (plan.bm == 64 && plan.bn == 128) return launch_tile<T, 2, 1, 1, 4>(p, st);
-    if (plan.bm == 32 && plan.bn == 128) return launch_tile<T, 1, 1, 1, 4>(p, st);
-    return hipErrorInvalidValue;
+template <bool TAP>
+hipError_t dispatch_f32(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_tile<float, TAP, TM, TN, WM, WN>(p, st)
+    WGRAD_TILE_SWITCH(CALL)
+#undef CALL
 }
 
 }  // namespace
@@ -425,18 +504,32 @@ hipError_t dispatch(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
 WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     (void)dtype;
     WgradPlan pl{};
-    const int cands[4] = {128, 96, 64, 32};
-    long long best = -1;
-    pl.bm = 32;
-    for (int c : cands) {
-        const long long padded = (long long)((g.K + c - 1) / c) * c;
-        if (best < 0 || padded < best) { best = padded; pl.bm = c; }
-    }
-    pl.bn = 128;
     const long long M = (long long)g.N * g.P * g.Q;
     const long long CRS = (long long)g.C * g.R * g.S;
+    pl.tap = g.C >= 64;   // enough channels to fill the columns of a per-tap tile
+    if (pl.tap) {
+        // (bm, bn) with the least padded area, larger tile on ties
+        const int cand[7][2] = {{128, 128}, {128, 96}, {96, 128}, {128, 64}, {64, 128}, {64, 64}, {32, 128}};
+        long long best = -1;
+        for (const auto& c : cand) {
+            const long long area = (long long)((g.K + c[0] - 1) / c[0]) * c[0] * ((g.C + c[1] - 1) / c[1]) * c[1];
+            if (best < 0 || area < best) { best = area; pl.bm = c[0]; pl.bn = c[1]; }
+        }
+        pl.c_tiles = (g.C + pl.bn - 1) / pl.bn;
+        pl.tiles_j = g.R * g.S * pl.c_tiles;
+    } else {
+        const int cands[4] = {128, 96, 64, 32};
+        long long best = -1;
+        pl.bm = 32;
+        for (int c : cands) {
+            const long long padded = (long long)((g.K + c - 1) / c) * c;
+            if (best < 0 || padded < best) { best = padded; pl.bm = c; }
+        }
+        pl.bn = 128;
+        pl.c_tiles = 0;
+        pl.tiles_j = (int)((CRS + pl.bn - 1) / pl.bn);
+    }
     pl.tiles_i = (g.K + pl.bm - 1) / pl.bm;
-    pl.tiles_j = (int)((CRS + pl.bn - 1) / pl.bn);
     const long long tiles = (long long)pl.tiles_i * pl.tiles_j;
     // enough workgroups for about three per CU, chunks no shorter than 256 pixels (a short chunk is
     // mostly prologue and epilogue) and no longer than 8192 so that one fp32 accumulation chain
@@ -466,15 +559,17 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     p.div_pq = make_fastdiv(p.PQ); p.div_q = make_fastdiv(g.Q);
     p.div_rs = make_fastdiv(p.RS); p.div_s = make_fastdiv(g.S);
     p.chunk = plan.chunk; p.tiles_i = plan.tiles_i; p.tiles_j = plan.tiles_j; p.splits = plan.splits;
+    p.c_tiles = plan.c_tiles;
     p.out = (float*)ws;
     hipError_t e;
-    if (dtype == PURINE_F32) e = dispatch<float>(p, plan, st);
-    else if (p.PQ % 32 == 0 && (((uintptr_t)dy) & 15u) == 0) e = dispatch_bf16<true>(p, plan, st);
-    else e = dispatch_bf16<false>(p, plan, st);
+    const bool vec = p.PQ % 32 == 0 && (((uintptr_t)dy) & 15u) == 0;
+    if (dtype == PURINE_F32) e = plan.tap ? dispatch_f32<true>(p, plan, st) : dispatch_f32<false>(p, plan, st);
+    else if (plan.tap) e = vec ? dispatch_bf16<true, true>(p, plan, st) : dispatch_bf16<false, true>(p, plan, st);
+    else e = vec ? dispatch_bf16<true, false>(p, plan, st) : dispatch_bf16<false, false>(p, plan, st);
     if (e != hipSuccess) return e;
     const int n = g.K * p.CRS;
     hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, st,
-                       (const float*)ws, dw, n, plan.splits, beta);
+                       (const float*)ws, dw, n, plan.splits, beta, plan.tap ? 1 : 0, g.K, g.C, p.RS);
     return hipGetLastError();
 }
 
