@@ -531,15 +531,31 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     }
     pl.tiles_i = (g.K + pl.bm - 1) / pl.bm;
     const long long tiles = (long long)pl.tiles_i * pl.tiles_j;
-    // enough workgroups for about three per CU, chunks no shorter than 256 pixels (a short chunk is
-    // mostly prologue and epilogue) and no longer than 8192 so that one fp32 accumulation chain
-    // stays short
-    long long splits = (768 + tiles - 1) / tiles;
+    // Number of splits. A CU holds three of these workgroups at a time, so the chip runs them in
+    // rounds of 768; a grid just over a multiple of 768 leaves the chip almost idle for a whole
+    // extra round, and a grid under 512 leaves too few wavefronts to hide latency. Score every
+    // admissible split count by the fraction of workgroup slots it keeps busy (discounted when a
+    // CU would hold fewer than three) and take the best; chunks stay within 256..8192 pixels (a
+    // short chunk is mostly prologue and epilogue, a long one lengthens the fp32 accumulation chain).
     const long long max_splits = (M + 255) / 256;
-    const long long min_splits = (M + 8191) / 8192;
-    if (splits > max_splits) splits = max_splits;
-    if (splits < min_splits) splits = min_splits;
-    if (splits < 1) splits = 1;
+    long long min_splits = (M + 8191) / 8192;
+    if (min_splits < 1) min_splits = 1;
+    long long splits = min_splits;
+    double best_score = -1.0;
+    for (long long sp = min_splits; sp <= max_splits && sp <= min_splits + 4096; ++sp) {
+        const long long wgs = tiles * sp;
+        double score;
+        if (wgs <= 768) {
+            const long long per_cu = (wgs + 255) / 256;              // 1..3 workgroups on the busiest CU
+            const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.85 : 0.55);
+            score = (double)wgs / (double)(per_cu * 256) * hide;
+        } else {
+            score = (double)wgs / (double)((wgs + 767) / 768 * 768);
+            if (wgs > 6 * 768) score = score > 0.97 ? score : 0.97;   // many rounds: the tail no longer matters
+        }
+        if (score > best_score + 1e-9) { best_score = score; splits = sp; }
+        if (wgs > 8 * 768) break;
+    }
     long long chunk = (M + splits - 1) / splits;
     chunk = (chunk + 31) / 32 * 32;   // whole slabs of either kernel (16 or 32 pixels), 16-byte aligned rows
     splits = (M + chunk - 1) / chunk;
