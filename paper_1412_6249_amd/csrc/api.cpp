@@ -145,7 +145,7 @@ size_t purine_conv_workspace_bytes(int pass, const purine_conv_desc* desc, const
     ConvGeom g;
     if (make_geom(desc, x_dim, w_dim, nullptr, &g) != PURINE_OK) return 0;
     if (pass == PURINE_CONV_BWD_WEIGHT) return plan_wgrad(g, dtype).ws_bytes;
-    return plan_conv_pix(g, pass == PURINE_CONV_BWD_DATA, dtype).ws_bytes;
+    return plan_conv_pix(g, pass == PURINE_CONV_BWD_DATA, dtype, false).ws_bytes;
 }
 
 size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype) {
@@ -177,7 +177,7 @@ static int conv_fwd_impl(const purine_conv_desc* desc, const purine_tensor* x, c
     }
     if (relu != 0 && relu != 1) return PURINE_E_ARG;
     epi.relu = relu;
-    const PixPlan plan = plan_conv_pix(g, false, x->dtype);
+    const PixPlan plan = plan_conv_pix(g, false, x->dtype, epi.bias || epi.relu);
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_pix(x->dtype, g, plan, x->data, w->data, y->data, 0.0f, ws, epi,
@@ -215,7 +215,7 @@ static int conv_bwd_data_impl(const purine_conv_desc* desc, const purine_tensor*
         if (overlaps(act, dx)) return PURINE_E_LAYOUT;
         epi.mask = act->data;
     }
-    const PixPlan plan = plan_conv_pix(g, true, dy->dtype);
+    const PixPlan plan = plan_conv_pix(g, true, dy->dtype, epi.mask != nullptr);
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_pix(dy->dtype, g, plan, dy->data, w->data, dx->data, beta, ws, epi,

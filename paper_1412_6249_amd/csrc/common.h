@@ -66,7 +66,7 @@ struct PixPlan {
     int Ci_pad, i_pad; // extents of the repacked filter A[Rt*St][Ci_pad][i_pad]
     size_t ws_bytes;   // scratch for the repacked filter
 };
-PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype);
+PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
 
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and
 // for the launch.

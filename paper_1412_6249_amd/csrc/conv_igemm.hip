@@ -380,9 +380,12 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q
 }
 
 // ------------------------------------------------------------------------------------------------
+// eff: throughput of a tile shape relative to 128x128, measured on MFMA-bound layers with many
+// workgroups per CU (smaller tiles move more operand bytes per MFMA and spend more issue slots on
+// the gather).
 constexpr TileCfg kTiles[] = {
-    {128, 128, 1.00f}, {96, 256, 1.00f}, {96, 128, 0.95f}, {64, 256, 0.95f}, {128, 64, 0.90f},
-    {64, 128, 0.90f},  {32, 256, 0.85f}, {64, 64, 0.80f},  {32, 128, 0.75f},
+    {128, 128, 1.00f}, {96, 256, 1.00f}, {96, 128, 0.95f}, {64, 256, 0.88f}, {128, 64, 0.93f},
+    {64, 128, 0.87f},  {32, 256, 0.76f}, {64, 64, 0.875f}, {32, 128, 0.75f},
 };
 
 template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
@@ -436,7 +439,7 @@ hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
 // Tile choice: every workgroup costs bm*bn/eff, where eff discounts the smaller tiles for their extra
 // operand traffic per MFMA; the busiest of the 256 CUs gets ceil(workgroups/256) of them. Pick the
 // tile that minimises that CU's load (padding waste is part of it, through the tile counts).
-PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype) {
+PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     PixPlan pl{};
     const int elem = dtype == PURINE_BF16 ? 2 : 4;
     int Co, Ci;
@@ -455,11 +458,19 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype) {
         pl.Rt = (g.R + g.sh - 1) / g.sh; pl.St = (g.S + g.sw - 1) / g.sw;
     }
     pl.flat = !bwd_data && Ci < BK;
+    // Time model per tile shape: workgroups are dealt round-robin to the 256 CUs and a CU's MFMA pipe
+    // is shared by whatever it holds, so the kernel lasts as long as the busiest CU:
+    // ceil(workgroups/256) * bm*bn/eff. A CU holding one or two workgroups has too few wavefronts to
+    // hide memory latency (measured: about 5% and 40% slower). Every row tile gathers its pixel
+    // columns again, which matters for the flat kernel, whose gather decodes (c,r,s) per row.
+    (void)fused;
+    const double gather = pl.flat ? 15.0 : 3.0;
     double best = -1.0;
     for (const TileCfg& t : kTiles) {
         const long long ti = (Co + t.bm - 1) / t.bm, tp = (M + t.bn - 1) / t.bn;
-        const long long wgs = ti * tp;
-        const double load = (double)((wgs + 255) / 256) * t.bm * t.bn / t.eff;
+        const long long per_cu = (ti * tp + 255) / 256;
+        const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.95 : 0.6);
+        const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (t.eff * hide);
         if (best < 0 || load < best) { best = load; pl.bm = t.bm; pl.bn = t.bn; }
     }
     pl.Co = Co; pl.Ci = Ci;
@@ -468,7 +479,11 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype) {
     const int depth = dtype == PURINE_BF16 ? 32 : BK;   // slab depth of the kernel that will run
     pl.Ci_pad = (Ci + depth - 1) / depth * depth;
     pl.i_pad = pl.tiles_i * pl.bm;
-    pl.ws_bytes = pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * pl.i_pad * elem;
+    // scratch is sized for the widest row padding any tile shape could ask for (96- or 128-row
+    // tiles), so the size does not depend on which shape, plain or fused, ends up running
+    const long long pad96 = (long long)(Co + 95) / 96 * 96, pad128 = (long long)(Co + 127) / 128 * 128;
+    const long long i_pad_max = pad96 > pad128 ? pad96 : pad128;
+    pl.ws_bytes = pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
     return pl;
 }
 
