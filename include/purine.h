@@ -241,6 +241,12 @@ int purine_graph_op_elapsed_ms(purine_graph* g, int op_id, float* ms);
  * the stream it was given, and then forgets the pair. Pass NULLs to cancel. */
 void purine_set_kernel_probe(void* start_event, void* stop_event);
 
+/* Tuning hook (host only, process-wide, not thread safe): forces the (rows, pixels) tile of the
+ * forward / backward-data kernels to one of 128x128, 96x256, 96x128, 64x256, 128x64, 64x128, 32x256,
+ * 64x64, 32x128; any other pair (e.g. 0, 0) restores the automatic choice. Results are bit-identical
+ * for every shape: the reduction order per output element does not depend on it. */
+void purine_debug_force_tile(int bm, int bn);
+
 /* Test hook (host only): n / d computed with the multiply-and-shift reciprocal that the kernels'
  * index arithmetic uses; valid for 0 <= n < 2^31 and 1 <= d < 2^31. */
 uint32_t purine_debug_fastdiv(uint32_t n, uint32_t d);

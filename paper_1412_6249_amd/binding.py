@@ -97,6 +97,7 @@ _SIGS = {
     "purine_graph_num_ops": (ctypes.c_int, [_vp]),
     "purine_graph_num_tensors": (ctypes.c_int, [_vp]),
     "purine_debug_fastdiv": (ctypes.c_uint32, [ctypes.c_uint32, ctypes.c_uint32]),
+    "purine_debug_force_tile": (None, [ctypes.c_int, ctypes.c_int]),
     "purine_graph_enable_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
     "purine_graph_op_elapsed_ms": (ctypes.c_int, [_vp, ctypes.c_int, _P(ctypes.c_float)]),
     "purine_set_kernel_probe": (None, [_vp, _vp]),
@@ -209,6 +210,10 @@ def purine_conv_workspace_bytes(which, desc, x_shape, w_shape, dtype):
 
 def purine_bias_bwd_workspace_bytes(dy_shape, dtype):
     return int(_lib.purine_bias_bwd_workspace_bytes(_dims(dy_shape), int(dtype)))
+
+
+def purine_debug_force_tile(bm=0, bn=0):
+    _lib.purine_debug_force_tile(int(bm), int(bn))
 
 
 def purine_debug_fastdiv(n, d):

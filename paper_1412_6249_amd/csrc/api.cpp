@@ -428,6 +428,9 @@ int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* ou
     return hip_status(e);
 }
 
+// Tuning hook: force the tile shape of the forward / backward-data kernels (0, 0 = automatic).
+void purine_debug_force_tile(int bm, int bn) { force_pix_tile(bm, bn); }
+
 // Test hook for the host-side reciprocal division used by the kernels' index arithmetic.
 uint32_t purine_debug_fastdiv(uint32_t n, uint32_t d) { return fastdiv(n, make_fastdiv(d)); }
 

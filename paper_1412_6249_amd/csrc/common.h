@@ -67,6 +67,7 @@ struct PixPlan {
     size_t ws_bytes;   // scratch for the repacked filter
 };
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
+void force_pix_tile(int bm, int bn);
 
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and
 // for the launch.

@@ -384,8 +384,8 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q
 // workgroups per CU (smaller tiles move more operand bytes per MFMA and spend more issue slots on
 // the gather).
 constexpr TileCfg kTiles[] = {
-    {128, 128, 1.00f}, {96, 256, 1.00f}, {96, 128, 0.95f}, {64, 256, 0.88f}, {128, 64, 0.93f},
-    {64, 128, 0.87f},  {32, 256, 0.76f}, {64, 64, 0.875f}, {32, 128, 0.75f},
+    {128, 128, 1.00f}, {96, 256, 0.85f}, {96, 128, 1.00f}, {64, 256, 0.85f}, {128, 64, 0.93f},
+    {64, 128, 0.90f},  {32, 256, 0.78f}, {64, 64, 0.92f},  {32, 128, 0.80f},
 };
 
 template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
@@ -439,6 +439,9 @@ hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
 // Tile choice: every workgroup costs bm*bn/eff, where eff discounts the smaller tiles for their extra
 // operand traffic per MFMA; the busiest of the 256 CUs gets ceil(workgroups/256) of them. Pick the
 // tile that minimises that CU's load (padding waste is part of it, through the tile counts).
+static int g_force_bm = 0, g_force_bn = 0;   // tuning hook, see purine_debug_force_tile
+void force_pix_tile(int bm, int bn) { g_force_bm = bm; g_force_bn = bn; }
+
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     PixPlan pl{};
     const int elem = dtype == PURINE_BF16 ? 2 : 4;
@@ -473,6 +476,8 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
         const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (t.eff * hide);
         if (best < 0 || load < best) { best = load; pl.bm = t.bm; pl.bn = t.bn; }
     }
+    for (const TileCfg& t : kTiles)
+        if (t.bm == g_force_bm && t.bn == g_force_bn) { pl.bm = t.bm; pl.bn = t.bn; }
     pl.Co = Co; pl.Ci = Ci;
     pl.tiles_i = (Co + pl.bm - 1) / pl.bm;
     pl.tiles_pix = (int)((M + pl.bn - 1) / pl.bn);

@@ -17,7 +17,7 @@ from synth.configs import CONV_LAYERS
 PEAK = {"f32": 157.3, "bf16": 2500.0}
 
 
-def time_op(fn, iters, warmup=3):
+def time_op(fn, iters, warmup=10):
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
@@ -105,12 +105,16 @@ def main():
     ap.add_argument("--op", default="all")
     ap.add_argument("--iters", type=int, default=20)
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--tile", default=None, metavar="BM,BN",
+                    help="force the forward / backward-data tile shape (tuning)")
     ap.add_argument("--copy-cal", type=int, default=0, metavar="MiB",
                     help="run only a plain device copy of this many MiB (counter calibration)")
     a = ap.parse_args()
     if a.copy_cal:
         copy_calibration(a.copy_cal)
         return
+    if a.tile:
+        B.purine_debug_force_tile(*[int(v) for v in a.tile.split(",")])
     ops = ["fwd", "bwd_data", "bwd_weight", "bias_fwd", "bias_bwd"] if a.op == "all" else a.op.split(",")
     for L in CONV_LAYERS[a.config]:
         if a.layer and L.name != a.layer:
