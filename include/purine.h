@@ -234,6 +234,11 @@ int purine_graph_num_tensors(const purine_graph* g);
  * purine_graph_op_elapsed_ms gives the elapsed time of that bracket in the last run.
  * PURINE_E_ARG for a bad id, a host operator, or when the last run was not timed. */
 int purine_graph_enable_timing(purine_graph* g, int on);
+/* Timing on, but only operator op_id is bracketed (two event records per run instead of two per
+ * operator, so the measurement does not perturb the run it measures). That operator also gets the
+ * device to itself: its stream first waits for everything already issued on the graph's other
+ * streams, and they wait for it, so the bracket measures the kernel alone. */
+int purine_graph_time_only(purine_graph* g, int op_id);
 int purine_graph_op_elapsed_ms(purine_graph* g, int op_id, float* ms);
 
 /* The same bracket for direct operator calls: the next operator call made by this host thread

@@ -44,6 +44,8 @@ struct purine_graph {
     bool validated = false;
     bool uses_device = false;
     bool timing = false;
+    int timing_only = -1;   // >= 0: bracket this operator only, and give it the device to itself
+    std::map<int, hipEvent_t> drain;   // per stream: marks the work issued before the exclusive operator
 };
 
 namespace {
@@ -158,6 +160,7 @@ void purine_graph_destroy(purine_graph* g) {
         if (op.t0) (void)hipEventDestroy(op.t0);
         if (op.t1) (void)hipEventDestroy(op.t1);
     }
+    for (auto& kv : g->drain) if (kv.second) (void)hipEventDestroy(kv.second);
     for (auto& kv : g->streams)
         if (g->stream_owned[kv.first]) (void)hipStreamDestroy(kv.second);
     delete g;
@@ -327,16 +330,34 @@ int purine_graph_run(purine_graph* g) {
                     }
                 if (rc != PURINE_OK) break;
                 op.timed = false;
-                if (g->timing) {
+                const bool timed_op = g->timing && (g->timing_only < 0 || g->timing_only == o);
+                const bool exclusive = g->timing && g->timing_only == o;
+                if (exclusive) {
+                    // the one measured operator runs alone: its stream waits for everything issued so
+                    // far on the other streams, and (below) they wait for it
+                    for (auto& sk : g->streams) {
+                        if (sk.first == op.thread) continue;
+                        hipEvent_t& ev = g->drain[sk.first];
+                        if ((!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) ||
+                            hipEventRecord(ev, sk.second) != hipSuccess ||
+                            hipStreamWaitEvent(st, ev, 0) != hipSuccess) { rc = PURINE_E_HIP; break; }
+                    }
+                    if (rc != PURINE_OK) break;
+                }
+                if (timed_op) {
                     if ((!op.t0 && hipEventCreate(&op.t0) != hipSuccess) ||
                         (!op.t1 && hipEventCreate(&op.t1) != hipSuccess)) { rc = PURINE_E_HIP; break; }
                     purine_set_kernel_probe(op.t0, op.t1);
                 }
                 rc = issue(g, op, st);
-                if (g->timing) { purine_set_kernel_probe(nullptr, nullptr); op.timed = rc == PURINE_OK; }
+                if (timed_op) { purine_set_kernel_probe(nullptr, nullptr); op.timed = rc == PURINE_OK; }
                 if (rc != PURINE_OK) break;
                 if (!op.done && hipEventCreateWithFlags(&op.done, hipEventDisableTiming) != hipSuccess) { rc = PURINE_E_HIP; break; }
                 if (hipEventRecord(op.done, st) != hipSuccess) { rc = PURINE_E_HIP; break; }
+                if (exclusive)
+                    for (auto& sk : g->streams)
+                        if (sk.first != op.thread && hipStreamWaitEvent(sk.second, op.done, 0) != hipSuccess) rc = PURINE_E_HIP;
+                if (rc != PURINE_OK) break;
             } else {
                 // a host operator completes on the host: wait for the device producers it consumes, so
                 // that readiness keeps its meaning for whatever depends on this operator
@@ -368,6 +389,15 @@ int purine_graph_run(purine_graph* g) {
 int purine_graph_enable_timing(purine_graph* g, int on) {
     if (!g) return PURINE_E_NULL;
     g->timing = on != 0;
+    g->timing_only = -1;
+    return PURINE_OK;
+}
+
+int purine_graph_time_only(purine_graph* g, int op_id) {
+    if (!g) return PURINE_E_NULL;
+    if (op_id < 0 || op_id >= (int)g->ops.size()) return PURINE_E_ARG;
+    g->timing = true;
+    g->timing_only = op_id;
     return PURINE_OK;
 }
 
