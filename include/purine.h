@@ -249,7 +249,10 @@ void purine_set_kernel_probe(void* start_event, void* stop_event);
 /* Tuning hook (host only, process-wide, not thread safe): forces the (rows, pixels) tile of the
  * forward / backward-data kernels to one of 128x128, 96x256, 96x128, 64x256, 128x64, 64x128, 32x256,
  * 64x64, 32x128; any other pair (e.g. 0, 0) restores the automatic choice. Results are bit-identical
- * for every shape: the reduction order per output element does not depend on it. */
+ * for every shape: the reduction order per output element does not depend on it.
+ * For 1x1 / stride-1 / unpadded layers, which run the streaming GEMM kernel instead: (32|64|96, 2) or
+ * (32|64, 4) force its rows per workgroup and pixels per lane, and (-1, anything) sends those layers
+ * through the general kernel. */
 void purine_debug_force_tile(int bm, int bn);
 
 /* Test hook (host only): n / d computed with the multiply-and-shift reciprocal that the kernels'

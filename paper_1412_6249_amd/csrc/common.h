@@ -65,6 +65,10 @@ struct PixPlan {
     int Rt, St;        // taps of the reduction
     int Ci_pad, i_pad; // extents of the repacked filter A[Rt*St][Ci_pad][i_pad]
     size_t ws_bytes;   // scratch for the repacked filter
+    // 1x1 / stride 1 / unpadded layers: streaming GEMM kernel (used when the pointers are aligned
+    // to gemm_tn elements; the fields above stay valid for the general kernel otherwise)
+    bool gemm1x1;
+    int gemm_tm, gemm_tn, gemm_tiles_i, gemm_tiles_pix;
 };
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
 void force_pix_tile(int bm, int bn);

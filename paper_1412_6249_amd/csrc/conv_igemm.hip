@@ -489,6 +489,25 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     const long long pad96 = (long long)(Co + 95) / 96 * 96, pad128 = (long long)(Co + 127) / 128 * 128;
     const long long i_pad_max = pad96 > pad128 ? pad96 : pad128;
     pl.ws_bytes = pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
+    // identity gather: the streaming GEMM applies
+    const long long HW = (long long)g.H * g.W;
+    const bool forced = (g_force_bn == 1 || g_force_bn == 2 || g_force_bn == 4) && g_force_bm >= 32 &&
+                        g_force_bm <= 96 && g_force_bm % 32 == 0 && HW % g_force_bn == 0 &&
+                        !(g_force_bn == 4 && g_force_bm == 96) && !(g_force_bn == 1 && g_force_bm == 32);
+    // bf16 layers do better on the bf16 MFMA kernel: they take this one only when told to
+    pl.gemm1x1 = g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0 &&
+                 Ci >= 16 && Ci % 16 == 0 && HW % 2 == 0 && g_force_bm != -1 &&
+                 (dtype == PURINE_F32 || forced);
+    if (pl.gemm1x1) {
+        // One row tile of 96 that covers every output channel reads the activations once; otherwise
+        // 32-row tiles with four pixels per lane (16-byte loads and stores) measured best, the
+        // repeated activation reads being served by L2.
+        if (Co > 64 && Co <= 96) { pl.gemm_tm = 3; pl.gemm_tn = 2; }
+        else { pl.gemm_tm = 1; pl.gemm_tn = HW % 4 == 0 ? 4 : 2; }
+        if (forced) { pl.gemm_tm = g_force_bm / 32; pl.gemm_tn = g_force_bn; }
+        pl.gemm_tiles_i = (Co + pl.gemm_tm * 32 - 1) / (pl.gemm_tm * 32);
+        pl.gemm_tiles_pix = (int)((M + 4 * 32 * pl.gemm_tn - 1) / (4 * 32 * pl.gemm_tn));
+    }
     return pl;
 }
 
@@ -537,6 +556,15 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
     p.beta = beta;
     p.tiles_i = pl.tiles_i; p.tiles_pix = pl.tiles_pix;
 
+    if (pl.gemm1x1) {
+        const uintptr_t align = (uintptr_t)pl.gemm_tn * (dtype == PURINE_BF16 ? 2 : 4) - 1;
+        if ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)epi.mask) & align) == 0) {
+            PixParams q = p;
+            q.wt = wt;
+            q.tiles_i = pl.gemm_tiles_i; q.tiles_pix = pl.gemm_tiles_pix;
+            return dispatch_gemm1x1(q, dtype, pl.mode == 1, pl.gemm_tm, pl.gemm_tn, st);
+        }
+    }
     if (pl.flat) {
         p.wt = wt;
         return dtype == PURINE_F32 ? dispatch_flat<float>(p, pl.bm, pl.bn, st)

@@ -33,7 +33,15 @@ CASES = [
     ("smallc_s4_pad5", 2, 4, 21, 19, 6, 7, 6, (4, 4), (5, 4)),
     ("pq_multiple_of_32", 3, 8, 16, 16, 40, 3, 3, (1, 1), (1, 1)),
     ("c70_k70_5x5", 2, 70, 12, 12, 70, 5, 5, (1, 1), (2, 2)),
+    # 1x1 / stride 1 / no padding with channel counts that are multiples of 16 and an even pixel
+    # count: the streaming GEMM kernel (forward when C qualifies, backward-data when K does)
+    ("pw_c48_k100", 3, 48, 10, 14, 100, 1, 1, (1, 1), (0, 0)),
+    ("pw_c192_k96", 2, 192, 6, 10, 96, 1, 1, (1, 1), (0, 0)),
+    ("pw_c16_k32", 5, 16, 9, 8, 32, 1, 1, (1, 1), (0, 0)),
+    ("pw_c64_k64_hw42", 2, 64, 7, 6, 64, 1, 1, (1, 1), (0, 0)),
+    ("pw_c160_k16_m_tail", 7, 160, 5, 14, 16, 1, 1, (1, 1), (0, 0)),
 ]
+PW = [c for c in CASES if c[0].startswith("pw_")]
 
 
 def make(case, dtype, seed=0, integer=False):
@@ -81,7 +89,7 @@ def test_config1_all_operators():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("case", [CASES[1], CASES[4], CASES[5], CASES[3]], ids=lambda c: c[0])
+@pytest.mark.parametrize("case", [CASES[1], CASES[4], CASES[5], CASES[3]] + PW[:3], ids=lambda c: c[0])
 def test_integer_inputs_bit_exact(case, dtype):
     """Small-integer tensors: every partial sum is an exact integer below 2^24, so any summation
     order gives the same bits. fp32 outputs must equal the oracle exactly; bf16-stored outputs are
@@ -130,9 +138,9 @@ def test_delta_kernel_is_an_exact_shift(r0, s0, stride, pad, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_beta_one_accumulates(dtype):
+@pytest.mark.parametrize("case", [CASES[5], PW[1]], ids=lambda c: c[0])
+def test_beta_one_accumulates(case, dtype):
     from gpu_util import run_layer, rel_l2, TOL
-    case = CASES[5]
     x, w, b, dy, stride, pad = make(case, dtype)
     rs = np.random.default_rng(9)
     prev = [rs.uniform(-1, 1, s).astype(np.float32) for s in (x.shape, w.shape, b.shape)]
@@ -143,6 +151,24 @@ def test_beta_one_accumulates(dtype):
     assert rel_l2(dx, rdx + prev[0]) <= TOL[dtype]
     assert rel_l2(dw, rdw + prev[1]) <= TOL[dtype]
     assert rel_l2(db, rdb + prev[2]) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("shape", [(32, 2), (64, 2), (96, 2), (32, 4), (64, 4), (64, 1), (96, 1), (-1, 0)])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pointwise_kernel_shapes_agree(shape, dtype):
+    """Every (rows per workgroup, pixels per lane) variant of the streaming 1x1 kernel, and the
+    general kernel on the same layer, against the oracle. HW = 60 is a multiple of 4."""
+    import paper_1412_6249_amd as pa
+    from gpu_util import run_layer, rel_l2, TOL
+    x, w, b, dy, stride, pad = make(PW[1], dtype)
+    ref = oracle_layer(x, w, b, dy, stride, pad)
+    pa.purine_debug_force_tile(*shape)
+    try:
+        got = run_layer(x, w, b, dy, stride, pad, dtype)
+    finally:
+        pa.purine_debug_force_tile(0, 0)
+    for name, g, r in zip(("y", "dx"), got, ref):
+        assert rel_l2(g, r) <= TOL[dtype], (shape, name, rel_l2(g, r))
 
 
 def test_results_are_bit_identical_run_to_run():
