@@ -216,31 +216,32 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     const size_t obase = (size_t)n * p.Co * p.HoWo + pix;
     const bool has_mask = FUSED && mask != nullptr, has_beta = p.beta != 0.0f;
 #pragma unroll
-    for (int a = 0; a < TM; ++a) {
-        // what the 16 rows of this MFMA tile need from memory is requested before the first store,
-        // so the loads overlap instead of forming sixteen load-wait-store round trips
-        raw_t mk[16], old[16];
+    for (int ah = 0; ah < TM * 2; ++ah) {
+        // what 8 rows of an MFMA tile need from memory is requested before the first of their
+        // stores, so the loads overlap instead of forming load-wait-store round trips
+        const int a = ah >> 1, e0 = (ah & 1) * 8;
+        raw_t mk[8], old[8];
         if (has_mask) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int i = i0 + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3);
+            for (int e = 0; e < 8; ++e) {
+                const int i = i0 + a * 32 + khalf * 4 + ((e0 + e) >> 2) * 8 + (e & 3);
                 mk[e] = *reinterpret_cast<const raw_t*>(mask + obase + (size_t)(i < p.Co ? i : 0) * p.HoWo);
             }
         }
         if (has_beta) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int i = i0 + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3);
+            for (int e = 0; e < 8; ++e) {
+                const int i = i0 + a * 32 + khalf * 4 + ((e0 + e) >> 2) * 8 + (e & 3);
                 old[e] = *reinterpret_cast<const raw_t*>(out + obase + (size_t)(i < p.Co ? i : 0) * p.HoWo);
             }
         }
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int i = i0 + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3);
+        for (int e = 0; e < 8; ++e) {
+            const int i = i0 + a * 32 + khalf * 4 + ((e0 + e) >> 2) * 8 + (e & 3);
             if (i >= p.Co) continue;
             float v[TN];
 #pragma unroll
-            for (int b = 0; b < TN; ++b) v[b] = acc[a][b][e];
+            for (int b = 0; b < TN; ++b) v[b] = acc[a][b][e0 + e];
             if (FUSED) {
                 if (bias) {
                     const float bi = Elem<T>::load(bias, i);

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
 // Flat kernel: forward pass of layers with fewer than 16 input channels. The reduction index is
 // kk = (c, r, s) flattened, which equals the memory order of one filter row, and each slab row
 // decodes its own (c, r, s) on the scalar unit (rows are uniform per wavefront).
-template <typename T, bool FUSED, int TM, int TN, int WM, int WN>
+template <typename T, bool FUSED, bool NOPAD, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -244,6 +244,19 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
     float b_reg[B_PASSES];
     unsigned a_ok, b_ok;   // one validity bit per staged value; the zero-fill happens at the LDS store
 
+    // walking state of this wavefront's gather rows: row index, its (r, s) and its offset
+    // c*Hi*Wi + r*Wi + s inside one image
+    int w_kk = b_row, w_r, w_s, w_off;
+    {
+        const int c = fastdiv(w_kk, p.div_rs);
+        const int rs = w_kk - c * p.RS;
+        w_r = fastdiv(rs, p.div_s);
+        w_s = rs - w_r * p.S;
+        w_off = c * p.HiWi + w_r * p.Wi + w_s;
+        w_kk = __builtin_amdgcn_readfirstlane(w_kk); w_r = __builtin_amdgcn_readfirstlane(w_r);
+        w_s = __builtin_amdgcn_readfirstlane(w_s); w_off = __builtin_amdgcn_readfirstlane(w_off);
+    }
+
     auto load_slab = [&](int slab) {
         a_ok = 0u; b_ok = 0u;
         {
@@ -257,20 +270,32 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
                 a_ok |= (ok ? 1u : 0u) << ps;
             }
         }
+        // Row kk = (c, r, s) of the flattened reduction is walked incrementally on the scalar unit
+        // (rows are uniform per wavefront): this wavefront's rows are kk0, kk0 + B_RPP, ... and the
+        // state carries over from slab to slab, so no row is ever decoded by division.
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
-            const int kk = slab * BK + ps * B_RPP + b_row;
-            const bool kv = kk < p.Kg;
-            const int kq = kv ? kk : 0;
-            const int ci = fastdiv(kq, p.div_rs);
-            const int rs = kq - ci * p.RS;
-            const int r = fastdiv(rs, p.div_s);
-            const int s = rs - r * p.S;
-            const int hi = g_h + r, wi = g_w + s;
-            // bitwise & on purpose: no short-circuit control flow inside the slab loop
-            const bool ok = kv & g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
-            b_reg[ps] = Elem<T>::load(in, ok ? g_off + ci * p.HiWi + r * p.Wi + s : 0);
+            const bool kv = w_kk < p.Kg;
+            bool ok = kv & g_live;
+            if (!NOPAD) {
+                const int hi = g_h + w_r, wi = g_w + w_s;
+                // bitwise & on purpose: no short-circuit control flow inside the slab loop
+                ok = ok & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
+            }
+            b_reg[ps] = Elem<T>::load(in, ok ? g_off + w_off : 0);
             b_ok |= (ok ? 1u : 0u) << ps;
+            // advance by B_RPP rows, one at a time and branch-free (selects on the scalar unit)
+            w_kk += B_RPP;
+#pragma unroll
+            for (int t = 0; t < B_RPP; ++t) {
+                w_s += 1;
+                const bool wrap_s = w_s >= p.S;
+                w_s = wrap_s ? 0 : w_s;
+                w_r += wrap_s ? 1 : 0;
+                const bool wrap_r = w_r >= p.R;
+                w_r = wrap_r ? 0 : w_r;
+                w_off += 1 + (wrap_s ? p.Wi - p.S : 0) + (wrap_r ? p.HiWi - p.R * p.Wi : 0);
+            }
         }
     };
     auto store_slab = [&](int buf) {
@@ -401,12 +426,19 @@ hipError_t launch_tap(PixParams& p, hipStream_t st) {
 
 template <typename T, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_flat(PixParams& p, hipStream_t st) {
+    // no padding: every tap of every output pixel lies inside the image, no bounds tests needed
+    const bool nopad = p.g_add_h == 0 && p.g_add_w == 0 &&
+                       (p.Ho - 1) * p.g_mul_h + p.R <= p.Hi && (p.Wo - 1) * p.g_mul_w + p.S <= p.Wi;
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
-                       dim3(WM * WN * 64), 0, st, p);
+    if (nopad)
+        hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, true, TM, TN, WM, WN>), dim3((unsigned)total),
+                           dim3(WM * WN * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, false, TM, TN, WM, WN>), dim3((unsigned)total),
+                           dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
