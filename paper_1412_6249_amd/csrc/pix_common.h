@@ -58,9 +58,8 @@ struct PixParams {
 // Epilogue shared by the kernels. Accumulator register e of a 32x32 tile holds row
 // (e/4)*8 + (lane/32)*4 + e%4, column lane%32. Optional pieces (bias, ReLU, ReLU-gradient mask,
 // accumulate) are uniform branches; what an element needs from memory (bias or mask value, old
-// output) is fetched for the 16 elements of one MFMA tile BEFORE its 16 stores, so the loads
-// overlap instead of forming sixteen load-wait-store round trips, while only 16-32 extra registers
-// are live.
+// output) is fetched for 8 rows of one MFMA tile BEFORE their 8 stores, so the loads overlap
+// instead of forming load-wait-store round trips, while only 8-16 extra registers are live.
 template <typename T, bool D2S>
 struct TileAddr {
     const PixParams& p;
@@ -135,34 +134,39 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
         const int n = fastdiv(pix, p.div_howo);
         const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
 #pragma unroll
-        for (int a = 0; a < TM; ++a) {
-            const int row0 = i_base + a * 32 + khalf * 4;
-            float t[16], o[16];
+        for (int ah = 0; ah < TM * 2; ++ah) {
+            // half an MFMA tile (8 rows) at a time: its bias / mask / old values are requested
+            // before the first of its stores, and 8..16 staging registers are all this adds
+            const int a = ah >> 1, e0 = (ah & 1) * 8;
+            const int row0 = i_base + a * 32 + khalf * 4 + (ah & 1) * 16;
+            float t[8], o[8];
             bool ok;
             if (has_bias) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
+                for (int e = 0; e < 8; ++e) {
                     const int i = row0 + (e >> 2) * 8 + (e & 3);
                     t[e] = Elem<T>::load(bias, i < p.Co ? i : 0);
                 }
             } else if (has_mask) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
+                for (int e = 0; e < 8; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
             }
             if (has_beta) {
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[e] = Elem<T>::load(out, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
+                for (int e = 0; e < 8; ++e) o[e] = Elem<T>::load(out, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
             }
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
+            for (int e = 0; e < 8; ++e) {
                 const int off = addr.at(row0 + (e >> 2) * 8 + (e & 3), ok);
-                float v = acc[a][b][e];
+                float v = acc[a][b][e0 + e];
                 if (has_bias) v += t[e];
                 if (p.relu) v = v > 0.0f ? v : 0.0f;
                 if (has_mask) v = t[e] > 0.0f ? v : 0.0f;
                 if (has_beta) v += o[e];
                 if (ok) Elem<T>::store(out, off, v);
             }
+            // keep the next half tile's loads from being hoisted above these stores
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
