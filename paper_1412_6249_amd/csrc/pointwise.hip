@@ -173,55 +173,108 @@ __global__ __launch_bounds__(TPB) void relu_bwd_kernel(const T* __restrict__ x, 
 }
 
 // ---- max pooling --------------------------------------------------------------------------------
-template <typename T>
+// Work is cut into runs of consecutive planes: a workgroup owns POOL_CHUNK consecutive elements of a
+// group of `ppw` planes (grid.x: group, grid.y: chunk) (small planes are batched so that every workgroup has a few thousand
+// elements; large planes are split). Outputs are written in memory order (coalesced); the window
+// reads overlap between neighbours and are served by L1. Index arithmetic uses the reciprocal
+// division; window size and stride are template constants for the common shapes (K = 0: runtime).
+constexpr int POOL_CHUNK = 2048;
+
+struct PoolParams {
+    int NC, H, W, P, Q, HW, PQ, k, stride, pad, ppw;
+    FastDiv div_pq, div_q, div_hw, div_w;
+    float beta;
+};
+
+template <typename T, int K, int S>
 __global__ __launch_bounds__(TPB) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y,
-                                                          int32_t* __restrict__ arg, int H, int W,
-                                                          int P, int Q, int k, int stride, int pad) {
-    const int nc = blockIdx.x;
-    const T* plane = x + (size_t)nc * H * W;
-    for (int o = blockIdx.y * TPB + threadIdx.x; o < P * Q; o += gridDim.y * TPB) {
-        const int p = o / Q, q = o - p * Q;
+                                                          int32_t* __restrict__ arg, const PoolParams pp) {
+    const int k = K ? K : pp.k, st = K ? S : pp.stride;
+    const int lim = min(pp.ppw * pp.PQ, ((int)blockIdx.y + 1) * POOL_CHUNK);
+    for (int l = blockIdx.y * POOL_CHUNK + threadIdx.x; l < lim; l += TPB) {
+        const int pl = fastdiv(l, pp.div_pq);
+        const int o = l - pl * pp.PQ;
+        const int nc = blockIdx.x * pp.ppw + pl;
+        if (nc >= pp.NC) break;
+        const int p = fastdiv(o, pp.div_q), q = o - p * pp.Q;
+        const int h0 = p * st - pp.pad, w0 = q * st - pp.pad;
+        const T* plane = x + (size_t)nc * pp.HW;
         int best = -1;
         float bv = 0.0f;
-        for (int r = 0; r < k; ++r) {
-            const int h = p * stride - pad + r;
-            if ((unsigned)h >= (unsigned)H) continue;
-            for (int s = 0; s < k; ++s) {
-                const int w = q * stride - pad + s;
-                if ((unsigned)w >= (unsigned)W) continue;
-                const float v = ldf<T>(plane, (size_t)h * W + w);
-                if (best < 0 || v > bv) { best = h * W + w; bv = v; }
+        if (K) {
+#pragma unroll
+            for (int r = 0; r < (K ? K : 1); ++r)
+#pragma unroll
+                for (int c = 0; c < (K ? K : 1); ++c) {
+                    const int h = h0 + r, w = w0 + c;
+                    const bool ok = ((unsigned)h < (unsigned)pp.H) & ((unsigned)w < (unsigned)pp.W);
+                    const int at = ok ? h * pp.W + w : 0;          // clamped, branch-free
+                    const float v = ldf<T>(plane, at);
+                    const bool take = ok & ((best < 0) | (v > bv));
+                    best = take ? at : best;
+                    bv = take ? v : bv;
+                }
+        } else {
+            for (int r = 0; r < k; ++r) {
+                const int h = h0 + r;
+                if ((unsigned)h >= (unsigned)pp.H) continue;
+                for (int c = 0; c < k; ++c) {
+                    const int w = w0 + c;
+                    if ((unsigned)w >= (unsigned)pp.W) continue;
+                    const float v = ldf<T>(plane, (size_t)h * pp.W + w);
+                    if (best < 0 || v > bv) { best = h * pp.W + w; bv = v; }
+                }
             }
         }
-        stf<T>(y, (size_t)nc * P * Q + o, bv);
-        arg[(size_t)nc * P * Q + o] = best;
+        const size_t out = (size_t)nc * pp.PQ + o;
+        stf<T>(y, out, bv);
+        arg[out] = best;
     }
 }
 
 // Gather form of the pooling gradient: each input position visits the windows that cover it in
 // row-major (p,q) order and adds dy where that window's winner is this position.
-template <typename T>
+template <typename T, int K, int S>
 __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ dy,
                                                           const int32_t* __restrict__ arg,
-                                                          T* dx, float beta, int H,
-                                                          int W, int P, int Q, int k, int stride,
-                                                          int pad) {
-    const int nc = blockIdx.x;
-    const size_t obase = (size_t)nc * P * Q;
-    for (int e = blockIdx.y * TPB + threadIdx.x; e < H * W; e += gridDim.y * TPB) {
-        const int h = e / W, w = e - h * W;
+                                                          T* dx, const PoolParams pp) {
+    const int k = K ? K : pp.k, st = K ? S : pp.stride;
+    constexpr int NW = K ? (K + S - 1) / (S ? S : 1) : 1;   // windows per axis that can cover a position
+    const int lim = min(pp.ppw * pp.HW, ((int)blockIdx.y + 1) * POOL_CHUNK);
+    for (int l = blockIdx.y * POOL_CHUNK + threadIdx.x; l < lim; l += TPB) {
+        const int pl = fastdiv(l, pp.div_hw);
+        const int e = l - pl * pp.HW;
+        const int nc = blockIdx.x * pp.ppw + pl;
+        if (nc >= pp.NC) break;
+        const int h = fastdiv(e, pp.div_w), w = e - h * pp.W;
         // windows p with p*stride - pad <= h <= p*stride - pad + k - 1
-        const int p_hi = min(P - 1, (h + pad) / stride);
-        const int q_hi = min(Q - 1, (w + pad) / stride);
-        int p_lo = h + pad - k + 1;
-        p_lo = p_lo <= 0 ? 0 : (p_lo + stride - 1) / stride;
-        int q_lo = w + pad - k + 1;
-        q_lo = q_lo <= 0 ? 0 : (q_lo + stride - 1) / stride;
-        float acc = beta != 0.0f ? ldf<T>(dx, (size_t)nc * H * W + e) : 0.0f;
-        for (int p = p_lo; p <= p_hi; ++p)
-            for (int q = q_lo; q <= q_hi; ++q)
-                if (arg[obase + p * Q + q] == e) acc += ldf<T>(dy, obase + p * Q + q);
-        stf<T>(dx, (size_t)nc * H * W + e, acc);
+        const int p_hi = min(pp.P - 1, (h + pp.pad) / st);
+        const int q_hi = min(pp.Q - 1, (w + pp.pad) / st);
+        int p_lo = h + pp.pad - k + 1;
+        p_lo = p_lo <= 0 ? 0 : (p_lo + st - 1) / st;
+        int q_lo = w + pp.pad - k + 1;
+        q_lo = q_lo <= 0 ? 0 : (q_lo + st - 1) / st;
+        const size_t obase = (size_t)nc * pp.PQ;
+        const size_t at = (size_t)nc * pp.HW + e;
+        float acc = pp.beta != 0.0f ? ldf<T>(dx, at) : 0.0f;
+        if (K) {
+#pragma unroll
+            for (int a = 0; a < NW; ++a)
+#pragma unroll
+                for (int b = 0; b < NW; ++b) {
+                    const int p = p_lo + a, q = q_lo + b;
+                    const bool in = (p <= p_hi) & (q <= q_hi);
+                    const int o = in ? p * pp.Q + q : 0;           // clamped, branch-free
+                    const bool hit = in & (arg[obase + o] == e);
+                    const float g = ldf<T>(dy, obase + o);
+                    acc += hit ? g : 0.0f;
+                }
+        } else {
+            for (int p = p_lo; p <= p_hi; ++p)
+                for (int q = q_lo; q <= q_hi; ++q)
+                    if (arg[obase + p * pp.Q + q] == e) acc += ldf<T>(dy, obase + p * pp.Q + q);
+        }
+        stf<T>(dx, at, acc);
     }
 }
 
@@ -356,26 +409,62 @@ hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, i
     return hipGetLastError();
 }
 
+namespace {
+PoolParams pool_params(int NC, int H, int W, int P, int Q, int k, int stride, int pad, int per_plane, float beta) {
+    PoolParams pp{};
+    pp.NC = NC; pp.H = H; pp.W = W; pp.P = P; pp.Q = Q; pp.HW = H * W; pp.PQ = P * Q;
+    pp.k = k; pp.stride = stride; pp.pad = pad; pp.beta = beta;
+    pp.ppw = per_plane >= POOL_CHUNK ? 1 : POOL_CHUNK / per_plane;
+    if (pp.ppw > NC) pp.ppw = NC;
+    pp.div_pq = make_fastdiv(pp.PQ); pp.div_q = make_fastdiv(Q);
+    pp.div_hw = make_fastdiv(pp.HW); pp.div_w = make_fastdiv(W);
+    return pp;
+}
+dim3 pool_grid(const PoolParams& pp, int per_plane) {
+    const long long per_group = (long long)pp.ppw * per_plane;
+    // x: plane groups (up to 2^31 - 1), y: chunks of one group (up to 65535)
+    return dim3((unsigned)((pp.NC + pp.ppw - 1) / pp.ppw), (unsigned)((per_group + POOL_CHUNK - 1) / POOL_CHUNK));
+}
+#define POOL_SHAPES(CALL)                                           \
+    if (k == 3 && stride == 1) { CALL(3, 1); }                      \
+    else if (k == 3 && stride == 2) { CALL(3, 2); }                 \
+    else if (k == 2 && stride == 2) { CALL(2, 2); }                 \
+    else { CALL(0, 0); }
+}  // namespace
+
 hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,
                               int P, int Q, int k, int stride, int pad, hipStream_t st) {
-    dim3 grid((unsigned)NC, blocks_for((size_t)P * Q, 64));
+    // a group of planes is indexed with 32-bit arithmetic; groups go to grid.y
+    if ((long long)H * W > 0x3fffffffLL || (long long)P * Q > 0x3fffffffLL) return hipErrorInvalidValue;
+    const PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, P * Q, 0.0f);
+    const dim3 grid = pool_grid(pp, P * Q);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    BY_DTYPE(dtype,
-             hipLaunchKernelGGL(maxpool_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, arg, H, W, P, Q, k, stride, pad),
-             hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, arg, H, W, P, Q, k, stride, pad));
+#define CALL(K, S)                                                                                              \
+    BY_DTYPE(dtype,                                                                                             \
+             hipLaunchKernelGGL((maxpool_fwd_kernel<float, K, S>), grid, dim3(TPB), 0, st, (const float*)x, (float*)y, arg, pp),       \
+             hipLaunchKernelGGL((maxpool_fwd_kernel<uint16_t, K, S>), grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, arg, pp))
+    POOL_SHAPES(CALL)
+#undef CALL
     return hipGetLastError();
 }
 
 hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, float beta,
                               int NC, int H, int W, int P, int Q, int k, int stride, int pad,
                               hipStream_t st) {
-    dim3 grid((unsigned)NC, blocks_for((size_t)H * W, 64));
+    if ((long long)H * W > 0x3fffffffLL || (long long)P * Q > 0x3fffffffLL) return hipErrorInvalidValue;
+    const PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, H * W, beta);
+    const dim3 grid = pool_grid(pp, H * W);
+    if (grid.y > 65535u) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    BY_DTYPE(dtype,
-             hipLaunchKernelGGL(maxpool_bwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, beta, H, W, P, Q, k, stride, pad),
-             hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, beta, H, W, P, Q, k, stride, pad));
+#define CALL(K, S)                                                                                              \
+    BY_DTYPE(dtype,                                                                                             \
+             hipLaunchKernelGGL((maxpool_bwd_kernel<float, K, S>), grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, pp),     \
+             hipLaunchKernelGGL((maxpool_bwd_kernel<uint16_t, K, S>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, pp))
+    POOL_SHAPES(CALL)
+#undef CALL
     return hipGetLastError();
 }
 
