@@ -70,6 +70,136 @@ template <> struct Vec<uint16_t, 4> {
     }
 };
 
+// Filter part into LDS: As[k][m] = A[i0 + m][c0 + k] for k < ck (ck <= CKMAX), m < TM*32, zero beyond
+// the last output channel. Threads walk the contiguous direction of W; loads go out in batches of
+// FILL before any of them is stored, so a batch costs one memory latency, not FILL of them.
+template <typename T, bool TRANS, int TM, int CKMAX>
+__device__ __forceinline__ void fill_filter(float* __restrict__ As, const T* __restrict__ wt, int i0, int c0,
+                                            int ck, int Ci, int Co, int tid) {
+    constexpr int BM = TM * 32, LD = BM + 1, FILL = 8;
+    static_assert((CKMAX & (CKMAX - 1)) == 0 && CKMAX >= 32 && CKMAX <= 256, "thread mapping");
+    if (!TRANS) {
+        // W[i][j], j contiguous: thread = (k, m mod MSTEP); m advances by MSTEP per iteration
+        constexpr int MSTEP = 256 / CKMAX;
+        static_assert(BM % (MSTEP * FILL) == 0, "whole batches");
+        const int k = tid & (CKMAX - 1), mh = tid / CKMAX;
+        const bool k_ok = k < ck;
+        const T* wk = wt + c0 + (k_ok ? k : 0);
+#pragma unroll 1
+        for (int it0 = 0; it0 < BM / MSTEP; it0 += FILL) {
+            float tmp[FILL];
+#pragma unroll
+            for (int j = 0; j < FILL; ++j) {
+                const int i = i0 + MSTEP * (it0 + j) + mh;
+                const bool ok = k_ok & (i < Co);
+                tmp[j] = Elem<T>::load(wk, ok ? i * Ci : 0);
+                tmp[j] = ok ? tmp[j] : 0.0f;
+            }
+            if (k_ok) {
+#pragma unroll
+                for (int j = 0; j < FILL; ++j) As[k * LD + MSTEP * (it0 + j) + mh] = tmp[j];
+            }
+        }
+    } else {
+        // W[j][i], i contiguous: thread = (m within a 32-row block, k mod 8)
+        const int tm = tid & 31, tk = tid >> 5;
+#pragma unroll 1
+        for (int it = 0; it < TM * (CKMAX / 8 / FILL); ++it) {
+            const int a = it / (CKMAX / 8 / FILL), kb = (it % (CKMAX / 8 / FILL)) * FILL;
+            const int m = a * 32 + tm;
+            const bool i_ok = i0 + m < Co;
+            const T* wm = wt + (i_ok ? i0 + m : 0);
+            float tmp[FILL];
+#pragma unroll
+            for (int j = 0; j < FILL; ++j) {
+                const int k = (kb + j) * 8 + tk;
+                const bool ok = i_ok & (k < ck);
+                tmp[j] = Elem<T>::load(wm, ok ? (c0 + k) * Co : 0);
+                tmp[j] = ok ? tmp[j] : 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < FILL; ++j) {
+                const int k = (kb + j) * 8 + tk;
+                if (k < ck) As[k * LD + m] = tmp[j];
+            }
+        }
+    }
+}
+
+// Epilogue of one 32-row MFMA tile whose TN pixel tiles are a lane's TN adjacent pixels: optional
+// bias, ReLU, ReLU-gradient mask, accumulate; vector stores. What 8 rows need from memory is
+// requested before the first of their stores, so the loads overlap instead of forming
+// load-wait-store round trips.
+template <typename T, bool FUSED, int TN>
+__device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[TN], int row0, size_t obase) {
+    typedef typename Vec<T, TN>::raw raw_t;
+    const T* __restrict__ bias = (const T*)p.bias;
+    const bool has_mask = FUSED && p.mask != nullptr, has_beta = p.beta != 0.0f;
+    // One per-lane pointer to (row0, this lane's pixels); the 16 rows of the tile are uniform
+    // multiples of the plane size away. The pointers are made opaque so that the compiler does not
+    // turn every row's address into a 64-bit induction variable of the loops around the epilogue.
+    T* orow = (T*)p.out + obase + (size_t)row0 * p.HoWo;
+    const T* mrow = (const T*)p.mask + (has_mask ? obase + (size_t)row0 * p.HoWo : 0);
+    asm volatile("" : "+v"(orow));
+    asm volatile("" : "+v"(mrow));
+    // rows per batch: what a batch needs from memory (mask, old output) is requested before the
+    // first of its stores; fewer rows per batch where a row is four pixels wide (registers)
+    constexpr int G = TN >= 4 ? 4 : 8;
+#pragma unroll
+    for (int part = 0; part < 16 / G; ++part) {
+        const int e0 = part * G;
+        raw_t mk[G], old[FUSED ? 1 : G];   // the fused kernels rarely accumulate: no staging there
+        if (has_mask) {
+#pragma unroll
+            for (int e = 0; e < G; ++e) {
+                const int d = ((e0 + e) >> 2) * 8 + ((e0 + e) & 3);
+                mk[e] = *reinterpret_cast<const raw_t*>(mrow + (row0 + d < p.Co ? d * p.HoWo : 0));
+            }
+        }
+        if (!FUSED && has_beta) {
+#pragma unroll
+            for (int e = 0; e < G; ++e) {
+                const int d = ((e0 + e) >> 2) * 8 + ((e0 + e) & 3);
+                old[e] = *reinterpret_cast<const raw_t*>(orow + (row0 + d < p.Co ? d * p.HoWo : 0));
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < G; ++e) {
+            const int d = ((e0 + e) >> 2) * 8 + ((e0 + e) & 3);
+            const int i = row0 + d;
+            if (i >= p.Co) continue;
+            float v[TN];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) v[b] = acc[b][e0 + e];
+            if (FUSED) {
+                if (bias) {
+                    const float bi = Elem<T>::load(bias, i);
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) v[b] += bi;
+                }
+                if (p.relu) {
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) v[b] = v[b] > 0.0f ? v[b] : 0.0f;
+                }
+                if (has_mask) {
+                    float m[TN];
+                    Vec<T, TN>::unpack(mk[e], m);
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) v[b] = m[b] > 0.0f ? v[b] : 0.0f;
+                }
+            }
+            if (has_beta) {
+                float o[TN];
+                if (FUSED) old[0] = *reinterpret_cast<const raw_t*>(orow + d * p.HoWo);
+                Vec<T, TN>::unpack(old[FUSED ? 0 : e], o);
+#pragma unroll
+                for (int b = 0; b < TN; ++b) v[b] += o[b];
+            }
+            *reinterpret_cast<raw_t*>(orow + d * p.HoWo) = Vec<T, TN>::pack(v);
+        }
+    }
+}
+
 // p.wt is the KCRS filter itself (R = S = 1, so [K][C]); TRANS: backward-data (A = W^T).
 template <typename T, bool TRANS, bool FUSED, int TM, int TN>
 __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(const PixParams p) {
@@ -82,8 +212,6 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
-    T* __restrict__ out = (T*)p.out;
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
@@ -128,56 +256,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     for (int c0 = 0; c0 < p.Ci; c0 += CK) {
         const int ck = p.Ci - c0 < CK ? p.Ci - c0 : CK;
         if (c0 > 0) __syncthreads();       // everyone is done with the previous part of the filter
-        // filter part: As[k][m] = A[i0 + m][c0 + k], zero beyond the last output channel. Threads
-        // walk the contiguous direction of W; loads go out in batches of FILL before any of them is
-        // stored, so a batch costs one memory latency, not FILL of them.
-        constexpr int FILL = 8;
-        if (!TRANS) {
-            // W[i][j], j contiguous: thread = (k, m parity); m advances by 2 per iteration
-            const int k = tid & (CK - 1), mh = tid >> 7;
-            const bool k_ok = k < ck;
-            const T* wk = wt + c0 + (k_ok ? k : 0);
-#pragma unroll 1
-            for (int it0 = 0; it0 < BM / 2; it0 += FILL) {
-                float tmp[FILL];
-#pragma unroll
-                for (int j = 0; j < FILL; ++j) {
-                    const int i = i0 + 2 * (it0 + j) + mh;
-                    const bool ok = k_ok & (i < p.Co);
-                    tmp[j] = Elem<T>::load(wk, ok ? i * p.Ci : 0);
-                    tmp[j] = ok ? tmp[j] : 0.0f;
-                }
-                if (k_ok) {
-#pragma unroll
-                    for (int j = 0; j < FILL; ++j) As[k * LD + 2 * (it0 + j) + mh] = tmp[j];
-                }
-            }
-        } else {
-            // W[j][i], i contiguous: thread = (m within a 32-row block, k mod 8)
-            const int tm = tid & 31, tk = tid >> 5;
-#pragma unroll 1
-            for (int it = 0; it < TM * (CK / 8 / FILL); ++it) {
-                const int a = it / (CK / 8 / FILL), kb = (it % (CK / 8 / FILL)) * FILL;
-                const int m = a * 32 + tm;
-                const bool i_ok = i0 + m < p.Co;
-                const T* wm = wt + (i_ok ? i0 + m : 0);
-                {
-                    float tmp[FILL];
-#pragma unroll
-                    for (int j = 0; j < FILL; ++j) {
-                        const int k = (kb + j) * 8 + tk;
-                        const bool ok = i_ok & (k < ck);
-                        tmp[j] = Elem<T>::load(wm, ok ? (c0 + k) * p.Co : 0);
-                        tmp[j] = ok ? tmp[j] : 0.0f;
-                    }
-#pragma unroll
-                    for (int j = 0; j < FILL; ++j) {
-                        const int k = (kb + j) * 8 + tk;
-                        if (k < ck) As[k * LD + m] = tmp[j];
-                    }
-                }
-            }
-        }
+        fill_filter<T, TRANS, TM, CK>(As, wt, i0, c0, ck, p.Ci, p.Co, tid);
         __syncthreads();
 
         const float* a_ptr = &As[khalf * LD + col];
@@ -211,63 +290,9 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     }
 
     if (!live) return;
-    const T* __restrict__ bias = (const T*)p.bias;
-    const T* __restrict__ mask = (const T*)p.mask;
     const size_t obase = (size_t)n * p.Co * p.HoWo + pix;
-    const bool has_mask = FUSED && mask != nullptr, has_beta = p.beta != 0.0f;
 #pragma unroll
-    for (int ah = 0; ah < TM * 2; ++ah) {
-        // what 8 rows of an MFMA tile need from memory is requested before the first of their
-        // stores, so the loads overlap instead of forming load-wait-store round trips
-        const int a = ah >> 1, e0 = (ah & 1) * 8;
-        raw_t mk[8], old[8];
-        if (has_mask) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = i0 + a * 32 + khalf * 4 + ((e0 + e) >> 2) * 8 + (e & 3);
-                mk[e] = *reinterpret_cast<const raw_t*>(mask + obase + (size_t)(i < p.Co ? i : 0) * p.HoWo);
-            }
-        }
-        if (has_beta) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = i0 + a * 32 + khalf * 4 + ((e0 + e) >> 2) * 8 + (e & 3);
-                old[e] = *reinterpret_cast<const raw_t*>(out + obase + (size_t)(i < p.Co ? i : 0) * p.HoWo);
-            }
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int i = i0 + a * 32 + khalf * 4 + ((e0 + e) >> 2) * 8 + (e & 3);
-            if (i >= p.Co) continue;
-            float v[TN];
-#pragma unroll
-            for (int b = 0; b < TN; ++b) v[b] = acc[a][b][e0 + e];
-            if (FUSED) {
-                if (bias) {
-                    const float bi = Elem<T>::load(bias, i);
-#pragma unroll
-                    for (int b = 0; b < TN; ++b) v[b] += bi;
-                }
-                if (p.relu) {
-#pragma unroll
-                    for (int b = 0; b < TN; ++b) v[b] = v[b] > 0.0f ? v[b] : 0.0f;
-                }
-                if (has_mask) {
-                    float m[TN];
-                    Vec<T, TN>::unpack(mk[e], m);
-#pragma unroll
-                    for (int b = 0; b < TN; ++b) v[b] = m[b] > 0.0f ? v[b] : 0.0f;
-                }
-            }
-            if (has_beta) {
-                float o[TN];
-                Vec<T, TN>::unpack(old[e], o);
-#pragma unroll
-                for (int b = 0; b < TN; ++b) v[b] += o[b];
-            }
-            *reinterpret_cast<raw_t*>(out + obase + (size_t)i * p.HoWo) = Vec<T, TN>::pack(v);
-        }
-    }
+    for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN>(p, acc[a], i0 + a * 32 + khalf * 4, obase);
 }
 
 template <typename T, bool TRANS, bool FUSED, int TM, int TN>
