@@ -362,6 +362,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
 //   mode 0 (forward)        : tap = (r, s),   ci = c, i = k
 //   mode 1 (bwd, stride 1)  : tap = (r, s),   ci = k, i = c
 //   mode 2 (bwd, strided)   : tap = (r', s'), ci = k, i = (c, a, b) -> w[k, c, a + sh*r', b + sw*s']
+//   mode 3 (fwd, flattened) : one tap, ci = (c, r, s) flattened (Ci = C*R*S), i = k
 struct RepackParams {
     const void* w; void* a;
     int mode, K, C, R, S, sh, sw, St, Ci, Co, Ci_pad, i_pad, total;
@@ -389,6 +390,7 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q
         T v = (T)0;
         if (i < q.Co && ci < q.Ci) {
             int k, c, r, s;
+            if (q.mode == 3) { a[o] = w[i * q.Ci + ci]; continue; }   // flattened: ci runs over (c, r, s)
             if (q.mode == 0) { k = i; c = ci; r = tr; s = ts; }
             else if (q.mode == 1) { k = ci; c = i; r = tr; s = ts; }
             else {
@@ -514,13 +516,17 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     pl.tiles_i = (Co + pl.bm - 1) / pl.bm;
     pl.tiles_pix = (int)((M + pl.bn - 1) / pl.bn);
     const int depth = dtype == PURINE_BF16 ? 32 : BK;   // slab depth of the kernel that will run
-    pl.Ci_pad = (Ci + depth - 1) / depth * depth;
+    // the bf16 flattened kernel reads a padded filter copy A[i][C*R*S rounded up]
+    const bool flat_copy = pl.flat && dtype == PURINE_BF16;
+    const int red = flat_copy ? Ci * g.R * g.S : Ci;
+    pl.Ci_pad = (red + depth - 1) / depth * depth;
     pl.i_pad = pl.tiles_i * pl.bm;
     // scratch is sized for the widest row padding any tile shape could ask for (96- or 128-row
     // tiles), so the size does not depend on which shape, plain or fused, ends up running
     const long long pad96 = (long long)(Co + 95) / 96 * 96, pad128 = (long long)(Co + 127) / 128 * 128;
     const long long i_pad_max = pad96 > pad128 ? pad96 : pad128;
-    pl.ws_bytes = pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
+    pl.ws_bytes = flat_copy ? (size_t)pl.Ci_pad * (size_t)i_pad_max * elem
+                  : pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
     // identity gather: the streaming GEMM applies
     const long long HW = (long long)g.H * g.W;
     const bool forced = (g_force_bn == 1 || g_force_bn == 2 || g_force_bn == 4) && g_force_bm >= 32 &&
@@ -596,6 +602,25 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
             q.tiles_i = pl.gemm_tiles_i; q.tiles_pix = pl.gemm_tiles_pix;
             return dispatch_gemm1x1(q, dtype, pl.mode == 1, pl.gemm_tm, pl.gemm_tn, st);
         }
+    }
+    if (pl.flat && dtype == PURINE_BF16) {
+        // bf16 MFMA on the flattened reduction: padded filter copy A[i][Kg_pad] into scratch first
+        RepackParams q{};
+        q.w = wt; q.a = ws; q.mode = 3;
+        q.K = g.K; q.C = g.C; q.R = g.R; q.S = g.S; q.sh = g.sh; q.sw = g.sw;
+        q.St = 1; q.Ci = p.Kg; q.Co = pl.Co; q.Ci_pad = pl.Ci_pad; q.i_pad = pl.i_pad;
+        const long long total = (long long)pl.Ci_pad * pl.i_pad;
+        if (total > 0x7fffffffLL || !ws) return hipErrorInvalidValue;
+        q.total = (int)total;
+        q.i_major = 1;
+        const unsigned blocks = (unsigned)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+        (void)hipGetLastError();
+        hipLaunchKernelGGL(repack_filter_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, q);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        p.wt = ws;
+        p.Rt = 1; p.St = 1;
+        return dispatch_flat_bf16(p, pl.bm, pl.bn, st);
     }
     if (pl.flat) {
         p.wt = wt;

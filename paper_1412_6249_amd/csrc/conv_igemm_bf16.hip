@@ -21,7 +21,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKH = 32;        // slab depth (channels)
 constexpr int LDK = BKH + 8;   // LDS row pitch in bf16 elements
 
-template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+// FLAT (forward with fewer than 16 input channels): the reduction is (c, r, s) flattened, Kg = Ci*R*S
+// values padded to a multiple of 32, the filter copy is A[i][Kg_pad], and every gathered element
+// has its own tap, walked incrementally on the scalar unit (the rows of a slab are uniform per
+// wavefront) and its own bounds test, recorded as one validity bit.
+template <bool FLAT, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -78,15 +82,46 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     uint4 a_reg[A_ITERS];
     uint32_t b_reg[CH];     // raw 16-bit values
     bool b_ok;
+    uint32_t b_bits = 0;    // FLAT: validity of each gathered element
 
     int nx_r = 0, nx_s = 0, nx_c0 = 0, staged_c0 = 0;
     auto load_slab = [&]() {
         staged_c0 = nx_c0;
-        const int tap = nx_r * p.St + nx_s;
+        const int tap = FLAT ? 0 : nx_r * p.St + nx_s;
         const int a_slab = tap * p.i_pad * p.Ci_pad + nx_c0;
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
             if (a_src[it] >= 0) a_reg[it] = *reinterpret_cast<const uint4*>(wt + a_slab + a_src[it]);
+        if (FLAT) {
+            // this wavefront's run of CH flattened rows starts at kk0 = (c, r, s)
+            int kk = nx_c0 + ch_base;
+            const int kq = kk < p.Kg ? kk : 0;
+            int w_c = fastdiv(kq, p.div_rs);
+            const int rs = kq - w_c * p.RS;
+            int w_r = fastdiv(rs, p.div_s);
+            int w_s = rs - w_r * p.S;
+            int w_off = w_c * p.HiWi + w_r * p.Wi + w_s;
+            b_bits = 0;
+#pragma unroll
+            for (int e = 0; e < CH; ++e) {
+                const int hi = g_h + w_r, wi = g_w + w_s;
+                // bitwise & on purpose: no short-circuit control flow inside the slab loop
+                const bool ok = g_live & (kk < p.Kg) & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
+                b_reg[e] = in[ok ? g_off + w_off : 0];     // clamped: masked at the store
+                b_bits |= (ok ? 1u : 0u) << e;
+                // next row, branch-free (selects on the scalar unit)
+                kk += 1; w_s += 1;
+                const bool wrap_s = w_s >= p.S;
+                w_s = wrap_s ? 0 : w_s;
+                w_r += wrap_s ? 1 : 0;
+                const bool wrap_r = w_r >= p.R;
+                w_r = wrap_r ? 0 : w_r;
+                w_off += 1 + (wrap_s ? p.Wi - p.S : 0) + (wrap_r ? p.HiWi - p.R * p.Wi : 0);
+            }
+            nx_c0 += BKH;
+            nx_c0 = nx_c0 >= p.Ci_pad ? 0 : nx_c0;
+            return;
+        }
         const int hi = MINUS ? g_h - nx_r : g_h + nx_r;
         const int wi = MINUS ? g_w - nx_s : g_w + nx_s;
         const int tap_off = nx_r * p.Wi + nx_s;
@@ -120,8 +155,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 const int e = q * 8 + 2 * h;
-                const uint32_t lo = (b_ok & (c0 + e < p.Ci)) ? b_reg[e] : 0u;
-                const uint32_t hi = (b_ok & (c0 + e + 1 < p.Ci)) ? b_reg[e + 1] : 0u;
+                const uint32_t lo = (FLAT ? ((b_bits >> e) & 1u) != 0 : (b_ok & (c0 + e < p.Ci))) ? b_reg[e] : 0u;
+                const uint32_t hi = (FLAT ? ((b_bits >> (e + 1)) & 1u) != 0 : (b_ok & (c0 + e + 1 < p.Ci))) ? b_reg[e + 1] : 0u;
                 w[h] = lo | (hi << 16);
             }
             *reinterpret_cast<uint4*>(row + q * 8) = make_uint4(w[0], w[1], w[2], w[3]);
@@ -136,7 +171,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
 
-    const int n_slabs = p.Rt * p.St * (p.Ci_pad / BKH);
+    const int n_slabs = (FLAT ? 1 : p.Rt * p.St) * (p.Ci_pad / BKH);
     load_slab();
     store_slab(0);
     __syncthreads();
@@ -171,35 +206,41 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
                                       j0 + wn * TN * 32 + (lane & 31), lane >> 5);
 }
 
-template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+template <bool FLAT, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_one(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_tap_bf16_kernel<MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_tap_bf16_kernel<FLAT, MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <bool MINUS, bool D2S, bool FUSED>
+template <bool FLAT, bool MINUS, bool D2S, bool FUSED>
 hipError_t by_tile2(PixParams& p, int bm, int bn, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_one<MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
+#define CALL(TM, TN, WM, WN) launch_one<FLAT, MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
     PURINE_TILE_SWITCH(CALL)
 #undef CALL
 }
-template <bool MINUS, bool D2S>
+template <bool FLAT, bool MINUS, bool D2S>
 hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
     const bool fused = p.bias || p.relu || p.mask;
-    return fused ? by_tile2<MINUS, D2S, true>(p, bm, bn, st) : by_tile2<MINUS, D2S, false>(p, bm, bn, st);
+    return fused ? by_tile2<FLAT, MINUS, D2S, true>(p, bm, bn, st) : by_tile2<FLAT, MINUS, D2S, false>(p, bm, bn, st);
 }
 
 }  // namespace
 
 hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
-    if (mode == 0) return by_tile<false, false>(p, bm, bn, st);
-    if (mode == 1) return by_tile<true, false>(p, bm, bn, st);
-    return by_tile<true, true>(p, bm, bn, st);
+    if (mode == 0) return by_tile<false, false, false>(p, bm, bn, st);
+    if (mode == 1) return by_tile<false, true, false>(p, bm, bn, st);
+    return by_tile<false, true, true>(p, bm, bn, st);
+}
+
+// forward, flattened (c, r, s) reduction; p.wt is the filter copy A[i_pad][Ci_pad] with Ci_pad = Kg
+// rounded up to a multiple of 32, p.Rt = p.St = 1
+hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st) {
+    return by_tile<true, false, false>(p, bm, bn, st);
 }
 
 }  // namespace pix

@@ -198,6 +198,8 @@ struct TileCfg { int bm, bn; float eff; };
 
 // bf16 MFMA variant of the tap kernel (conv_igemm_bf16.hip). mode: 0 fwd, 1 bwd unit stride, 2 bwd phase-folded.
 hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st);
+// bf16 MFMA forward with a flattened (c,r,s) reduction (fewer than 16 input channels)
+hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st);
 // streaming GEMM for 1x1 / stride 1 / unpadded layers (conv_gemm1x1.hip); p.wt is the KCRS filter
 hipError_t dispatch_gemm1x1(const PixParams& p, int dtype, bool trans, int tm, int tn, hipStream_t st);
 
