@@ -24,7 +24,11 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
 # runs of this same command (see profiles/); None until measured for that kernel.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # (config, kernel): HBM bytes per launch = FETCH_SIZE * 2047.77 + WRITE_SIZE * 1024 (the factors a
+    # plain 256 MiB copy gives these counters), from the rocprofv3 --pmc runs summarised in profiles/
+    (2, "conv_bwd_data[conv1.dx]"): 83.68e6 + 38.54e6,
+}
 
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
               5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
@@ -80,6 +84,8 @@ def main():
     ap.add_argument("--unfused", action="store_true",
                     help="separate Bias / ReLU / ReLU-gradient operators instead of the fused conv vertices")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-every", type=int, default=4,
+                    help="bracket the dominant kernel (which then runs alone) on every n-th timed step")
     ap.add_argument("--ops", action="store_true", help="print the per-operator table to stderr")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -95,8 +101,11 @@ def main():
     cfg = args.config
     torch.cuda.set_device(0)
     gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused)
-    # Warm-up, then one step per operator with that operator's main kernel bracketed and running
-    # alone (twice, keeping the shorter): the per-operator table, and which kernel dominates.
+    # Warm-up and one step per operator with that operator's main kernel bracketed (twice, keeping
+    # the shorter): the per-operator table, and which kernel dominates. These steps run serially
+    # (every operator alone on the device), so that each bracket measures its kernel and so that a
+    # profiler's per-kernel averages over the whole run are of kernels that ran alone.
+    pa.purine_graph_set_serial(gb.g, True)
     pa.purine_graph_enable_timing(gb.g, False)
     for _ in range(max(1, args.warmup)):
         gb.run()
@@ -110,23 +119,25 @@ def main():
         warm_ms[op[0]] = best
     conv_kinds = (0, 2, 3, 13, 14)
     dominant = max((op for op in gb.ops if op[1] in conv_kinds), key=lambda op: warm_ms[op[0]])[0]
-    # Timed region: only the dominant kernel is bracketed (one event pair), and only on every
-    # fourth step, because the bracketed operator runs with the device to itself and so costs the
-    # step the overlap it would otherwise have had with the other streams.
-    SAMPLE_EVERY = 4
+    # Timed region: the graph runs on its streams with operators overlapping as their thread ids
+    # allow. On every n-th step (default 4) the dominant kernel is bracketed (one event pair) and
+    # keeps the device to itself, so the bracket measures the kernel's own duration. Such a step
+    # loses the overlap this one operator would otherwise have had (about 6 % of the step when
+    # done every step, 1.5 % at every fourth); that cost is part of the reported value.
+    pa.purine_graph_set_serial(gb.g, False)
     dom_ms, dom_n = 0.0, 0
-    pa.purine_graph_enable_timing(gb.g, False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        sampled = i % SAMPLE_EVERY == 0
+        sampled = i % args.sample_every == 0
         if sampled:
             pa.purine_graph_time_only(gb.g, dominant)
+        else:
+            pa.purine_graph_enable_timing(gb.g, False)
         gb.run()                      # returns after every sink's device work has completed
         if sampled:
             dom_ms += pa.purine_graph_op_elapsed_ms(gb.g, dominant)
             dom_n += 1
-            pa.purine_graph_enable_timing(gb.g, False)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps

@@ -239,6 +239,10 @@ int purine_graph_enable_timing(purine_graph* g, int on);
  * device to itself: its stream first waits for everything already issued on the graph's other
  * streams, and they wait for it, so the bracket measures the kernel alone. */
 int purine_graph_time_only(purine_graph* g, int op_id);
+/* on != 0: every operator runs with the device to itself (its stream waits for everything issued
+ * before it on the graph's other streams, and they wait for it): kernels never overlap, whatever
+ * their thread ids. Results are unchanged; meant for per-operator measurements. */
+int purine_graph_set_serial(purine_graph* g, int on);
 int purine_graph_op_elapsed_ms(purine_graph* g, int op_id, float* ms);
 
 /* The same bracket for direct operator calls: the next operator call made by this host thread

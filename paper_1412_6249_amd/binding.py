@@ -100,6 +100,7 @@ _SIGS = {
     "purine_debug_force_tile": (None, [ctypes.c_int, ctypes.c_int]),
     "purine_graph_enable_timing": (ctypes.c_int, [_vp, ctypes.c_int]),
     "purine_graph_time_only": (ctypes.c_int, [_vp, ctypes.c_int]),
+    "purine_graph_set_serial": (ctypes.c_int, [_vp, ctypes.c_int]),
     "purine_graph_op_elapsed_ms": (ctypes.c_int, [_vp, ctypes.c_int, _P(ctypes.c_float)]),
     "purine_set_kernel_probe": (None, [_vp, _vp]),
 }
@@ -389,6 +390,10 @@ def purine_graph_enable_timing(g, on=True):
 
 def purine_graph_time_only(g, op_id):
     _check(_lib.purine_graph_time_only(g, int(op_id)), "purine_graph_time_only")
+
+
+def purine_graph_set_serial(g, on):
+    _check(_lib.purine_graph_set_serial(g, 1 if on else 0), "purine_graph_set_serial")
 
 
 def purine_graph_op_elapsed_ms(g, op_id):

@@ -45,6 +45,7 @@ struct purine_graph {
     bool uses_device = false;
     bool timing = false;
     int timing_only = -1;   // >= 0: bracket this operator only, and give it the device to itself
+    bool serial = false;    // every operator gets the device to itself
     std::map<int, hipEvent_t> drain;   // per stream: marks the work issued before the exclusive operator
 };
 
@@ -331,7 +332,7 @@ int purine_graph_run(purine_graph* g) {
                 if (rc != PURINE_OK) break;
                 op.timed = false;
                 const bool timed_op = g->timing && (g->timing_only < 0 || g->timing_only == o);
-                const bool exclusive = g->timing && g->timing_only == o;
+                const bool exclusive = g->serial || (g->timing && g->timing_only == o);
                 if (exclusive) {
                     // the one measured operator runs alone: its stream waits for everything issued so
                     // far on the other streams, and (below) they wait for it
@@ -390,6 +391,12 @@ int purine_graph_enable_timing(purine_graph* g, int on) {
     if (!g) return PURINE_E_NULL;
     g->timing = on != 0;
     g->timing_only = -1;
+    return PURINE_OK;
+}
+
+int purine_graph_set_serial(purine_graph* g, int on) {
+    if (!g) return PURINE_E_NULL;
+    g->serial = on != 0;
     return PURINE_OK;
 }
 
