@@ -36,12 +36,16 @@ constexpr int BK = 16;  // slab depth along the reduction (fp32 kernels)
 // ------------------------------------------------------------------------------------------------
 // Tap-major kernel. MINUS: the gather walks backwards (h = g_h - r), as backward-data does.
 // D2S: depth-to-space epilogue of the phase-folded strided backward-data.
-// Workgroup = WM x WN wavefronts, each owning TM x TN MFMA tiles of 32 x 32.
-template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+// Workgroup = WM x WN wavefronts, each owning TM x TN MFMA tiles of MT x MT: 32 (v_mfma 32x32x2) or
+// 16 (v_mfma 16x16x4, same flop rate, for GEMMs whose row count would waste half a 32-row tile).
+template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
-    constexpr int BM = WM * TM * 32;
-    constexpr int BN = WN * TN * 32;
+    constexpr int BM = WM * TM * MT;
+    constexpr int BN = WN * TN * MT;
+    constexpr int KSTEP = MT == 32 ? 2 : 4;    // reduction elements per MFMA
+    constexpr int LDB = BN + (MT == 16 ? 16 : 0);   // 16-wide tiles: rows 16 banks apart
+    static_assert(MT == 32 || MT == 16, "MFMA tile edge");
     static_assert(NT == 256 && NT % BN == 0, "one pixel column per thread");
     constexpr int B_RPP = NT / BN;             // slab rows covered per pass
     constexpr int B_PASSES = BK / B_RPP;
@@ -50,7 +54,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
     constexpr int A_CPR = BM / 4;              // pieces per slab row
 
     __shared__ __attribute__((aligned(16))) float As[2][BK * BM];
-    __shared__ float Bs[2][BK * BN];
+    __shared__ float Bs[2][BK * LDB];
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
@@ -137,57 +141,58 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
             const bool ok = b_ok & (c0 + ps * B_RPP + b_row < p.Ci);
-            Bs[buf][(ps * B_RPP + b_row) * BN + (tid % BN)] = ok ? b_reg[ps] : 0.0f;
+            Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = ok ? b_reg[ps] : 0.0f;
         }
     };
 
-    floatx16 acc[TM][TN];
+    typedef typename AccT<MT>::type acc_t;
+    acc_t acc[TM][TN];
 #pragma unroll
     for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+            for (int e = 0; e < AccT<MT>::N; ++e) acc[a][b][e] = 0.0f;
 
     const int n_slabs = p.Rt * p.St * (p.Ci_pad / BK);
     load_slab();
     store_slab(0);
     __syncthreads();
 
-    const int a_off = wm * TM * 32 + (lane & 31);
-    const int b_off = wn * TN * 32 + (lane & 31);
-    const int khalf = lane >> 5;
+    const int a_off = wm * TM * MT + (lane & (MT - 1));
+    const int b_off = wn * TN * MT + (lane & (MT - 1));
+    const int khalf = lane / MT;      // which of the KSTEP reduction elements this lane feeds
 
     for (int slab = 0; slab < n_slabs; ++slab) {
         const int buf = slab & 1;
         load_slab();   // global loads of the next slab fly while the MFMAs below run
         float av[2][TM], bv[2][TN];   // operand fragments, double-buffered across k-steps
 #pragma unroll
-        for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * BM + a_off + a * 32];
+        for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * BM + a_off + a * MT];
 #pragma unroll
-        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * BN + b_off + b * 32];
+        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * LDB + b_off + b * MT];
 #pragma unroll
-        for (int ks = 0; ks < BK / 2; ++ks) {
+        for (int ks = 0; ks < BK / KSTEP; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks + 1 < BK / 2) {
-                const int row = 2 * (ks + 1) + khalf;
+            if (ks + 1 < BK / KSTEP) {
+                const int row = KSTEP * (ks + 1) + khalf;
 #pragma unroll
-                for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * BM + a_off + a * 32];
+                for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * BM + a_off + a * MT];
 #pragma unroll
-                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * BN + b_off + b * 32];
+                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * LDB + b_off + b * MT];
             }
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = AccT<MT>::mfma(av[cur][a], bv[cur][b], acc[a][b]);
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the LDS stores (and their load waits) below the MFMAs
         store_slab(buf ^ 1);
         __syncthreads();
     }
 
-    store_tile<T, D2S, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
+    store_tile<T, D2S, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * MT, j0 + b_off, khalf);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -410,18 +415,19 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q
 // eff: throughput of a tile shape relative to 128x128, measured on MFMA-bound layers with many
 // workgroups per CU (smaller tiles move more operand bytes per MFMA and spend more issue slots on
 // the gather).
+constexpr float kEff16 = 0.96f;   // 16x16x4 tiles, 256 pixels per workgroup (measured like the table below)
 constexpr TileCfg kTiles[] = {
     {128, 128, 1.00f}, {96, 256, 0.85f}, {96, 128, 1.00f}, {64, 256, 0.85f}, {128, 64, 0.93f},
     {64, 128, 0.90f},  {32, 256, 0.78f}, {64, 64, 0.92f},  {32, 128, 0.80f},
 };
 
-template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32>
 hipError_t launch_tap(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, FUSED, TM, TN, WM, WN, MT>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
@@ -446,6 +452,11 @@ hipError_t launch_flat(PixParams& p, hipStream_t st) {
 
 template <typename T, bool MINUS, bool D2S, bool FUSED>
 hipError_t dispatch_tap2(PixParams& p, int bm, int bn, hipStream_t st) {
+    // 16-row granular tiles (16x16x4 MFMA): 48 or 16 rows, 256 or 128 pixels
+    if (bm == 48 && bn == 256) return launch_tap<T, MINUS, D2S, FUSED, 3, 4, 1, 4, 16>(p, st);
+    if (bm == 48 && bn == 128) return launch_tap<T, MINUS, D2S, FUSED, 3, 2, 1, 4, 16>(p, st);
+    if (bm == 16 && bn == 256) return launch_tap<T, MINUS, D2S, FUSED, 1, 4, 1, 4, 16>(p, st);
+    if (bm == 16 && bn == 128) return launch_tap<T, MINUS, D2S, FUSED, 1, 2, 1, 4, 16>(p, st);
 #define CALL(TM, TN, WM, WN) launch_tap<T, MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
     PURINE_TILE_SWITCH(CALL)
 #undef CALL
@@ -510,8 +521,24 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
         const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (t.eff * hide);
         if (best < 0 || load < best) { best = load; pl.bm = t.bm; pl.bn = t.bn; }
     }
+    // GEMMs with at most 16, or 33..48, rows (first-layer backward-data after phase folding): tiles of
+    // 16x16x4 MFMAs waste no half tile of rows
+    const bool rows16 = dtype == PURINE_F32 && !pl.flat && (Co <= 16 || (Co > 32 && Co <= 48));
+    if (rows16) {
+        const int bm16 = Co <= 16 ? 16 : 48;
+        for (int bn16 = 256; bn16 >= 128; bn16 /= 2) {
+            const long long per_cu = ((M + bn16 - 1) / bn16 + 255) / 256;
+            const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.95 : 0.6);
+            const double eff = bn16 == 256 ? kEff16 : kEff16 * 0.96;
+            const double load = (double)per_cu * bm16 * bn16 * (1.0 + gather / bm16) / (eff * hide);
+            if (load < best) { best = load; pl.bm = bm16; pl.bn = bn16; }
+        }
+    }
     for (const TileCfg& t : kTiles)
         if (t.bm == g_force_bm && t.bn == g_force_bn) { pl.bm = t.bm; pl.bn = t.bn; }
+    if (rows16 && (g_force_bn == 256 || g_force_bn == 128) && g_force_bm == (Co <= 16 ? 16 : 48)) {
+        pl.bm = g_force_bm; pl.bn = g_force_bn;
+    }
     pl.Co = Co; pl.Ci = Ci;
     pl.tiles_i = (Co + pl.bm - 1) / pl.bm;
     pl.tiles_pix = (int)((M + pl.bn - 1) / pl.bn);

@@ -8,6 +8,24 @@ namespace pix {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Accumulator of one MFMA tile and the matching fp32 instruction: 32x32x2 (16 values per lane) or
+// 16x16x4 (4 values per lane).
+template <int MT> struct AccT;
+template <> struct AccT<32> {
+    typedef floatx16 type;
+    static constexpr int N = 16;
+    static __device__ __forceinline__ type mfma(float a, float b, type c) {
+        return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct AccT<16> {
+    typedef floatx4 type;
+    static constexpr int N = 4;
+    static __device__ __forceinline__ type mfma(float a, float b, type c) {
+        return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+    }
+};
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
     static __device__ __forceinline__ float load(const float* p, int i) { return p[i]; }
@@ -167,6 +185,51 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             }
             // keep the next half tile's loads from being hoisted above these stores
             __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// Same epilogue for 16x16 MFMA tiles: accumulator register e holds row (lane/16)*4 + e, column
+// lane%16; `kq` is lane/16.
+template <typename T, bool D2S, bool FUSED, int TM, int TN>
+__device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
+                                           floatx4 (&acc)[TM][TN], int i_base, int pix_base, int kq) {
+    const T* __restrict__ bias = (const T*)p.bias;
+    const T* __restrict__ mask = (const T*)p.mask;
+    const bool has_bias = FUSED && !D2S && bias != nullptr, has_mask = FUSED && mask != nullptr;
+    const bool has_beta = p.beta != 0.0f;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int pix = pix_base + b * 16;
+        if (pix >= p.M) continue;
+        const int n = fastdiv(pix, p.div_howo);
+        const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const int row0 = i_base + a * 16 + kq * 4;
+            float t[4], o[4];
+            bool ok;
+            if (has_bias) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t[e] = Elem<T>::load(bias, row0 + e < p.Co ? row0 + e : 0);
+            } else if (has_mask) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + e, ok));
+            }
+            if (has_beta) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = Elem<T>::load(out, addr.at(row0 + e, ok));
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int off = addr.at(row0 + e, ok);
+                float v = acc[a][b][e];
+                if (has_bias) v += t[e];
+                if (FUSED && p.relu) v = v > 0.0f ? v : 0.0f;
+                if (has_mask) v = t[e] > 0.0f ? v : 0.0f;
+                if (has_beta) v += o[e];
+                if (ok) Elem<T>::store(out, off, v);
+            }
         }
     }
 }
