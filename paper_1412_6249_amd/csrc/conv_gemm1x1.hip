@@ -131,7 +131,8 @@ __device__ __forceinline__ void fill_filter(float* __restrict__ As, const T* __r
 // requested before the first of their stores, so the loads overlap instead of forming
 // load-wait-store round trips.
 template <typename T, bool FUSED, int TN>
-__device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[TN], int row0, size_t obase) {
+__device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[TN], int row0, size_t obase,
+                                           const float* bias_lds, int i_tile0) {
     typedef typename Vec<T, TN>::raw raw_t;
     const T* __restrict__ bias = (const T*)p.bias;
     const bool has_mask = FUSED && p.mask != nullptr, has_beta = p.beta != 0.0f;
@@ -173,7 +174,7 @@ __device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[T
             for (int b = 0; b < TN; ++b) v[b] = acc[b][e0 + e];
             if (FUSED) {
                 if (bias) {
-                    const float bi = Elem<T>::load(bias, i);
+                    const float bi = bias_lds[i - i_tile0];
 #pragma unroll
                     for (int b = 0; b < TN; ++b) v[b] += bi;
                 }
@@ -209,6 +210,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     typedef typename Vec<T, TN>::raw raw_t;
 
     __shared__ float As[CK * LD];
+    __shared__ float bias_s[FUSED ? BM : 1];
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
@@ -244,6 +246,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
         }
     };
     issue_group(bcur);
+    if (FUSED) stage_bias<T, BM, 256>(bias_s, p, i0, tid);   // ordered by the barrier after the filter fill
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -292,7 +295,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     if (!live) return;
     const size_t obase = (size_t)n * p.Co * p.HoWo + pix;
 #pragma unroll
-    for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN>(p, acc[a], i0 + a * 32 + khalf * 4, obase);
+    for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN>(p, acc[a], i0 + a * 32 + khalf * 4, obase, bias_s, i0);
 }
 
 template <typename T, bool TRANS, bool FUSED, int TM, int TN>

@@ -55,6 +55,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
 
     __shared__ __attribute__((aligned(16))) float As[2][BK * BM];
     __shared__ float Bs[2][BK * LDB];
+    __shared__ float bias_s[FUSED ? BM : 1];
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
@@ -156,6 +157,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
 
     const int n_slabs = p.Rt * p.St * (p.Ci_pad / BK);
     load_slab();
+    if (FUSED) stage_bias<T, BM, NT>(bias_s, p, i0, tid);
     store_slab(0);
     __syncthreads();
 
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
         __syncthreads();
     }
 
-    store_tile<T, D2S, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * MT, j0 + b_off, khalf);
+    store_tile<T, D2S, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * MT, j0 + b_off, khalf, bias_s, i0);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -214,6 +216,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
 
     __shared__ float As[2][BK * LDA];
     __shared__ float Bs[2][BK * BN];
+    __shared__ float bias_s[FUSED ? BM : 1];
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
@@ -322,6 +325,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
 
     const int n_slabs = (p.Kg + BK - 1) / BK;
     load_slab(0);
+    if (FUSED) stage_bias<T, BM, NT>(bias_s, p, i0, tid);
     store_slab(0);
     __syncthreads();
 
@@ -358,7 +362,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
         __syncthreads();
     }
 
-    store_tile<T, false, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf);
+    store_tile<T, false, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf, bias_s, i0);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -40,6 +40,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
+    __shared__ float bias_s[FUSED ? BM : 1];
 
     const uint16_t* __restrict__ in = (const uint16_t*)p.in;
     const uint16_t* __restrict__ wt = (const uint16_t*)p.wt;
@@ -173,6 +174,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 
     const int n_slabs = (FLAT ? 1 : p.Rt * p.St) * (p.Ci_pad / BKH);
     load_slab();
+    if (FUSED) stage_bias<uint16_t, BM, NT>(bias_s, p, i0, tid);
     store_slab(0);
     __syncthreads();
 
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     }
 
     store_tile<uint16_t, D2S, FUSED, TM, TN>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
-                                      j0 + wn * TN * 32 + (lane & 31), lane >> 5);
+                                      j0 + wn * TN * 32 + (lane & 31), lane >> 5, bias_s, i0);
 }
 
 template <bool FLAT, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>

@@ -73,6 +73,16 @@ struct PixParams {
     int tiles_i, tiles_pix;
 };
 
+// The fused forward kernels stage their row tile's bias values in LDS at kernel start (zero past the
+// last output channel), so the epilogue does not wait on global memory for them. The caller's
+// first barrier orders the fill before any use.
+template <typename T, int BM, int NT>
+__device__ __forceinline__ void stage_bias(float* bias_lds, const PixParams& p, int i0, int tid) {
+    const T* __restrict__ bias = (const T*)p.bias;
+    if (bias)
+        for (int r = tid; r < BM; r += NT) bias_lds[r] = i0 + r < p.Co ? Elem<T>::load(bias, i0 + r) : 0.0f;
+}
+
 // Epilogue shared by the kernels. Accumulator register e of a 32x32 tile holds row
 // (e/4)*8 + (lane/32)*4 + e%4, column lane%32. Optional pieces (bias, ReLU, ReLU-gradient mask,
 // accumulate) are uniform branches; what an element needs from memory (bias or mask value, old
@@ -117,7 +127,7 @@ struct TileAddr {
 template <typename T, bool D2S, bool FUSED, int TM, int TN>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
-                                           int khalf) {
+                                           int khalf, const float* bias_lds, int i_tile0) {
     if (!FUSED) {
         // plain store (optionally accumulating): no staging arrays, so the kernels that do not fuse
         // anything keep their register count and occupancy
@@ -161,10 +171,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             bool ok;
             if (has_bias) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int i = row0 + (e >> 2) * 8 + (e & 3);
-                    t[e] = Elem<T>::load(bias, i < p.Co ? i : 0);
-                }
+                for (int e = 0; e < 8; ++e) t[e] = bias_lds[row0 + (e >> 2) * 8 + (e & 3) - i_tile0];
             } else if (has_mask) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
@@ -193,7 +200,8 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
 // lane%16; `kq` is lane/16.
 template <typename T, bool D2S, bool FUSED, int TM, int TN>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
-                                           floatx4 (&acc)[TM][TN], int i_base, int pix_base, int kq) {
+                                           floatx4 (&acc)[TM][TN], int i_base, int pix_base, int kq,
+                                           const float* bias_lds, int i_tile0) {
     const T* __restrict__ bias = (const T*)p.bias;
     const T* __restrict__ mask = (const T*)p.mask;
     const bool has_bias = FUSED && !D2S && bias != nullptr, has_mask = FUSED && mask != nullptr;
@@ -211,7 +219,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             bool ok;
             if (has_bias) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) t[e] = Elem<T>::load(bias, row0 + e < p.Co ? row0 + e : 0);
+                for (int e = 0; e < 4; ++e) t[e] = bias_lds[row0 + e - i_tile0];
             } else if (has_mask) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + e, ok));
