@@ -169,6 +169,26 @@ def main():
                 "avg_kernel_ms": round(avg_ms, 4),
                 "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, kname))}
 
+    # secondary figure: the same step without the first layer's backward-data (the gradient with
+    # respect to the images, which training does not need); its flops leave the numerator too
+    secondary = None
+    if cfg in (2, 4):
+        gb.close()
+        gb2 = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, first_layer_dx=False)
+        for _ in range(max(1, args.warmup)):
+            gb2.run()
+        torch.cuda.synchronize()
+        s0 = time.perf_counter()
+        n2 = max(5, args.steps // 2)
+        for _ in range(n2):
+            gb2.run()
+        torch.cuda.synchronize()
+        ms2 = (time.perf_counter() - s0) * 1e3 / n2
+        flop2 = flop - CONV_LAYERS[cfg][0].flop_per_pass
+        secondary = {"without_first_layer_dx": {"ms_per_step": round(ms2, 4),
+                                                "value": round(flop2 / (ms2 * 1e-3) / 1e12, 3)}}
+        gb = gb2
+
     result = {
         "metric": "conv fwd+bwd TFLOP/s on one MI355X",
         "value": round(flop / (ms_per_step * 1e-3) / 1e12, 3),
@@ -184,6 +204,8 @@ def main():
                    "frac_of_mfma_peak": round(flop / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[dtype], 4)},
         "roofline": roofline,
     }
+    if secondary:
+        result["secondary"] = secondary
     gb.close()
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)

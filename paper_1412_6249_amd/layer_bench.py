@@ -15,6 +15,7 @@ from . import binding as B
 from synth.configs import CONV_LAYERS
 
 PEAK = {"f32": 157.3, "bf16": 2500.0}
+HBM_TBS = 8.0   # TB/s
 
 
 def time_op(fn, iters, warmup=10):
@@ -74,8 +75,18 @@ def bench_layer(L, ops, iters, out=sys.stdout):
         tf = flop / (med * 1e-3) / 1e12 if flop else 0.0
         results[name] = (med, tf)
         if flop:
-            out.write("%-10s %-10s %9.4f ms (best %9.4f)  %8.2f TFLOP/s  %5.1f%% of %s MFMA peak\n"
-                      % (L.name, name, med, best, tf, 100 * tf / PEAK[L.dtype], L.dtype))
+            # algorithmic bytes of the pass: each operand tensor once; attainable = min(MFMA peak,
+            # arithmetic intensity x 8 TB/s)
+            es = x.element_size()
+            nb = {"fwd": (x.numel() + w.numel() + y.numel()) * es,
+                  "bwd_data": (dy.numel() + w.numel() + dx.numel()) * es,
+                  "bwd_weight": (x.numel() + dy.numel()) * es + dw.numel() * 4}[name]
+            attainable = min(PEAK[L.dtype], flop / nb * HBM_TBS)
+            out.write("%-10s %-10s %9.4f ms (best %9.4f)  %8.2f TFLOP/s  %5.1f%% of %s MFMA peak  "
+                      "%5.1f%% of attainable (%s-bound)  %7.1f GB/s algorithmic\n"
+                      % (L.name, name, med, best, tf, 100 * tf / PEAK[L.dtype], L.dtype,
+                         100 * tf / attainable, "MFMA" if attainable >= PEAK[L.dtype] else "HBM",
+                         nb / (med * 1e-3) / 1e9))
         else:
             nbytes = y.numel() * y.element_size() * (2 if name == "bias_fwd" else 1)
             out.write("%-10s %-10s %9.4f ms (best %9.4f)  %8.1f GB/s\n"

@@ -188,11 +188,13 @@ def _default_init(seed):
 
 
 def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True,
-                   fuse=False):
+                   fuse=False, first_layer_dx=True):
     """Builds the bi-graph of config `cfg` (1..5). `batch` overrides the batch size (tests).
     `init(name, shape, dtype, kind)` supplies source tensors (kind in x, w, b, dy); by default they
-    are drawn on the device from the seed. Returns the GraphBuilder; gb.run() performs one full
-    forward + backward step."""
+    are drawn on the device from the seed. `first_layer_dx=False` leaves out the backward-data
+    operator of the layer that reads the images in the chained configs 2 and 4 (a training step
+    does not need that gradient). Returns the GraphBuilder; gb.run() performs one full forward +
+    backward step."""
     init = init or _default_init(seed)
     layers = [l.with_batch(batch) if batch else l for l in CONV_LAYERS[cfg]]
     gb = GraphBuilder(inplace=inplace, fuse=fuse)
@@ -227,7 +229,7 @@ def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, mult
             recs.append(rec)
         grad = src("dout", L3.y_shape, L3.dtype, "dy")
         for rec in reversed(recs):
-            grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb)
+            grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb, need_dx=first_layer_dx or rec is not recs[0])
     elif cfg == 3:
         b1, b2r, b2, b3r, b3, b4 = layers
         N = b1.N
@@ -278,7 +280,7 @@ def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, mult
         for rec, prec in zip(reversed(recs), reversed(pools)):
             if prec is not None:
                 grad = gb.maxpool_backward(prec, grad)
-            grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb)
+            grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb, need_dx=first_layer_dx or rec is not recs[0])
         gb.pool_records = [p for p in pools if p is not None]
     else:
         raise ValueError("config must be 1..5")
