@@ -64,7 +64,8 @@ struct PixPlan {
     int Co, Ci;        // GEMM rows and gathered channels
     int Rt, St;        // taps of the reduction
     int Ci_pad, i_pad; // extents of the repacked filter A[Rt*St][Ci_pad][i_pad]
-    size_t ws_bytes;   // scratch for the repacked filter
+    size_t ws_bytes;   // scratch: repacked filter, then (bf16 tap kernels) the channels-blocked input copy
+    size_t blk_offset; // byte offset of that copy inside the scratch (0: none)
     // 1x1 / stride 1 / unpadded layers: streaming GEMM kernel (used when the pointers are aligned
     // to gemm_tn elements; the fields above stay valid for the general kernel otherwise)
     bool gemm1x1;
@@ -100,6 +101,10 @@ KernelProbe take_kernel_probe();   // returns the pending pair (or NULLs) and cl
 struct ProbeScope {                 // records start on construction and stop on destruction
     KernelProbe p; hipStream_t st;
     explicit ProbeScope(hipStream_t s) : p(take_kernel_probe()), st(s) { if (p.start) (void)hipEventRecord(p.start, st); }
+    // armed = false: an inert scope (the pending pair is left for an inner scope to take)
+    ProbeScope(hipStream_t s, bool armed) : p(armed ? take_kernel_probe() : KernelProbe{nullptr, nullptr}), st(s) {
+        if (p.start) (void)hipEventRecord(p.start, st);
+    }
     ~ProbeScope() { if (p.stop) (void)hipEventRecord(p.stop, st); }
 };
 

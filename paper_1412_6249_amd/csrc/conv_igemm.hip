@@ -419,8 +419,15 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q
 // eff: throughput of a tile shape relative to 128x128, measured on MFMA-bound layers with many
 // workgroups per CU (smaller tiles move more operand bytes per MFMA and spend more issue slots on
 // the gather).
+// bf16 MFMA kernels (measured on the 3x3 64->192 layer at 56x56, batch 256): they are bound by the
+// per-slab instruction overhead, not by the MFMA pipe, so 64-row tiles with many pixels win.
+constexpr TileCfg kTilesBf16[] = {
+    {64, 256, 1.00f}, {64, 128, 0.97f}, {64, 64, 0.83f}, {96, 256, 0.81f}, {32, 256, 0.77f},
+    {32, 128, 0.77f}, {128, 128, 0.64f}, {96, 128, 0.58f}, {128, 64, 0.30f},
+};
 constexpr float kEff16 = 0.96f;   // 16x16x4 tiles, 256 pixels per workgroup (measured like the table below)
 constexpr TileCfg kTiles[] = {
+    {192, 128, 0.0f},   // only when forced, until calibrated
     {128, 128, 1.00f}, {96, 256, 0.85f}, {96, 128, 1.00f}, {64, 256, 0.85f}, {128, 64, 0.93f},
     {64, 128, 0.90f},  {32, 256, 0.78f}, {64, 64, 0.92f},  {32, 128, 0.80f},
 };
@@ -518,11 +525,19 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     (void)fused;
     const double gather = pl.flat ? 15.0 : 3.0;
     double best = -1.0;
-    for (const TileCfg& t : kTiles) {
+    const bool flat_bf16 = pl.flat && dtype == PURINE_BF16;
+    const TileCfg* table = dtype == PURINE_BF16 ? kTilesBf16 : kTiles;
+    const int n_table = dtype == PURINE_BF16 ? (int)(sizeof(kTilesBf16) / sizeof(TileCfg)) : (int)(sizeof(kTiles) / sizeof(TileCfg));
+    for (int ti_ = 0; ti_ < n_table; ++ti_) {
+        const TileCfg& t = table[ti_];
+        if (t.eff <= 0.0f) continue;
         const long long ti = (Co + t.bm - 1) / t.bm, tp = (M + t.bn - 1) / t.bn;
         const long long per_cu = (ti * tp + 255) / 256;
         const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.95 : 0.6);
-        const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (t.eff * hide);
+        // the bf16 flattened kernel gathers 32 elements per thread and slab at 256 pixels per
+        // workgroup, which measured a third slower than 16 at 128
+        const double eff = (flat_bf16 && t.bn == 256) ? t.eff * 0.65 : t.eff;
+        const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (eff * hide);
         if (best < 0 || load < best) { best = load; pl.bm = t.bm; pl.bn = t.bn; }
     }
     // GEMMs with at most 16, or 33..48, rows (first-layer backward-data after phase folding): tiles of
@@ -555,9 +570,19 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     // scratch is sized for the widest row padding any tile shape could ask for (96- or 128-row
     // tiles), so the size does not depend on which shape, plain or fused, ends up running
     const long long pad96 = (long long)(Co + 95) / 96 * 96, pad128 = (long long)(Co + 127) / 128 * 128;
-    const long long i_pad_max = pad96 > pad128 ? pad96 : pad128;
+    const long long pad192 = (long long)(Co + 191) / 192 * 192;
+    long long i_pad_max = pad96 > pad128 ? pad96 : pad128;
+    if (pad192 > i_pad_max) i_pad_max = pad192;
     pl.ws_bytes = flat_copy ? (size_t)pl.Ci_pad * (size_t)i_pad_max * elem
                   : pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
+    pl.blk_offset = 0;
+    if (dtype == PURINE_BF16 && !pl.flat && pl.Rt * pl.St > 1) {
+        // channels-blocked copy of the gathered tensor behind the filter copy (single-tap layers
+        // gather each element once, straight from NCHW)
+        const size_t gathered = (size_t)g.N * pl.Ci_pad * (bwd_data ? (size_t)g.P * g.Q : (size_t)g.H * g.W);
+        pl.blk_offset = (pl.ws_bytes + 255) / 256 * 256;
+        pl.ws_bytes = pl.blk_offset + gathered * elem;
+    }
     // identity gather: the streaming GEMM applies
     const long long HW = (long long)g.H * g.W;
     const bool forced = (g_force_bn == 1 || g_force_bn == 2 || g_force_bn == 4) && g_force_bm >= 32 &&
@@ -658,6 +683,14 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
         return dtype == PURINE_F32 ? dispatch_flat<float>(p, pl.bm, pl.bn, st)
                                    : dispatch_flat<uint16_t>(p, pl.bm, pl.bn, st);
     }
+    // bf16: the whole operator (input copy, filter repack, main kernel) is what a timing probe brackets
+    ProbeScope whole_op(dtype == PURINE_BF16 ? st : nullptr, dtype == PURINE_BF16);
+    const bool blocked = dtype == PURINE_BF16 && pl.Rt * pl.St > 1;
+    if (blocked) {
+        if (!pl.blk_offset || !ws) return hipErrorInvalidValue;
+        hipError_t e = blockify_input(p, (char*)ws + pl.blk_offset, st);
+        if (e != hipSuccess) return e;
+    }
     // repack the filter into scratch, then run the tap-major kernel on it
     RepackParams q{};
     q.w = wt; q.a = ws; q.mode = pl.mode;
@@ -683,7 +716,8 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
         if (pl.mode == 1) return dispatch_tap<float, true, false>(p, pl.bm, pl.bn, st);
         return dispatch_tap<float, true, true>(p, pl.bm, pl.bn, st);
     }
-    return dispatch_tap_bf16(p, pl.mode, pl.bm, pl.bn, st);
+    return blocked ? dispatch_tap_bf16(p, pl.mode, pl.bm, pl.bn, st)
+                   : dispatch_tap_bf16_nchw(p, pl.mode, pl.bm, pl.bn, st);
 }
 
 }  // namespace purine

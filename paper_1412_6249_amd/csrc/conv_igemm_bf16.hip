@@ -6,10 +6,12 @@
 // bf16 MFMA wants: each lane feeds 8 CONSECUTIVE reduction elements of its row (A) or column (B).
 // So both LDS tiles are stored reduction-major inside a row - As[i][ci], Bs[pixel][ci] - with a
 // slab depth of 32 channels, and the filter is repacked to A[tap][i][ci]. NCHW keeps pixels, not
-// channels, contiguous, so a thread gathers its 8..32 channels of one pixel with 2-byte loads
-// (coalesced along W across the wavefront), packs them and writes 16-byte pieces; rows are padded
-// to 40 elements (80 bytes) so that the 16-byte fragment reads of 32 rows fall in distinct bank
-// groups.
+// channels, contiguous, so the gathered tensor is first copied into a channels-blocked layout
+// [N][Ci_pad/8][H][W][8] in scratch (blockify_kernel, one pass at HBM speed): a thread then gathers
+// 8 channels of its pixel with one 16-byte load (coalesced along W across the wavefront) and writes
+// it to LDS as it is. Rows are padded to 40 elements (80 bytes) so that the 16-byte fragment reads
+// of 32 rows fall in distinct bank groups. The flattened mode (fewer than 16 input channels) has
+// nothing to block and gathers 2-byte elements from NCHW.
 #include "pix_common.h"
 
 namespace purine {
@@ -25,7 +27,9 @@ constexpr int LDK = BKH + 8;   // LDS row pitch in bf16 elements
 // values padded to a multiple of 32, the filter copy is A[i][Kg_pad], and every gathered element
 // has its own tap, walked incrementally on the scalar unit (the rows of a slab are uniform per
 // wavefront) and its own bounds test, recorded as one validity bit.
-template <bool FLAT, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+// NCHW (single-tap layers, where every element is gathered exactly once and a blocked copy would
+// only add traffic): tap-major walk, 2-byte gathers straight from the NCHW tensor.
+template <bool FLAT, bool NCHW, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -37,6 +41,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     constexpr int A_CPR = BKH / 8;             // 16-byte pieces per filter row
     constexpr int A_VEC = BM * A_CPR;
     constexpr int A_ITERS = (A_VEC + NT - 1) / NT;
+    constexpr bool ELEMS = FLAT || NCHW;       // 2-byte gathers with per-element validity bits
+    static_assert(!(FLAT && NCHW), "one gather mode");
 
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
@@ -67,7 +73,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         const int wo = rem - ho * p.Wo;
         g_h = ho * p.g_mul_h + p.g_add_h;
         g_w = wo * p.g_mul_w + p.g_add_w;
-        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;
+        // FLAT: element offset in NCHW; otherwise offset in 8-channel blocks of the blocked copy
+        g_off = n * (ELEMS ? p.Ci : p.Ci_pad / 8) * p.HiWi + g_h * p.Wi + g_w;
     }
     const int ch_base = __builtin_amdgcn_readfirstlane(tid / BN) * CH;   // uniform per wavefront
 
@@ -81,12 +88,14 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     }
 
     uint4 a_reg[A_ITERS];
-    uint32_t b_reg[CH];     // raw 16-bit values
-    bool b_ok;
-    uint32_t b_bits = 0;    // FLAT: validity of each gathered element
+    uint32_t b_reg[ELEMS ? CH : 1];  // FLAT / NCHW: raw 16-bit values
+    uint4 blk_reg[CH / 8];           // blocked input: 8 channels of this thread's pixel per piece
+    bool b_ok = false;
+    uint32_t b_bits = 0;             // FLAT / NCHW: validity of each gathered element
 
     int nx_r = 0, nx_s = 0, nx_c0 = 0, staged_c0 = 0;
     auto load_slab = [&]() {
+        (void)staged_c0;
         staged_c0 = nx_c0;
         const int tap = FLAT ? 0 : nx_r * p.St + nx_s;
         const int a_slab = tap * p.i_pad * p.Ci_pad + nx_c0;
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
                 const int hi = g_h + w_r, wi = g_w + w_s;
                 // bitwise & on purpose: no short-circuit control flow inside the slab loop
                 const bool ok = g_live & (kk < p.Kg) & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
-                b_reg[e] = in[ok ? g_off + w_off : 0];     // clamped: masked at the store
+                b_reg[ELEMS ? e : 0] = in[ok ? g_off + w_off : 0];     // clamped: masked at the store
                 b_bits |= (ok ? 1u : 0u) << e;
                 // next row, branch-free (selects on the scalar unit)
                 kk += 1; w_s += 1;
@@ -127,12 +136,22 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         const int wi = MINUS ? g_w - nx_s : g_w + nx_s;
         const int tap_off = nx_r * p.Wi + nx_s;
         b_ok = g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
-        const int base = b_ok ? (MINUS ? g_off - tap_off : g_off + tap_off) : 0;
+        const int base = MINUS ? g_off - tap_off : g_off + tap_off;
+        if (NCHW) {
+            b_bits = 0;
 #pragma unroll
-        for (int e = 0; e < CH; ++e) {
-            const int ci = nx_c0 + ch_base + e;
-            const int plane = (b_ok & (ci < p.Ci)) ? ci * p.HiWi : 0;   // clamped: masked at the store
-            b_reg[e] = in[base + plane];
+            for (int e = 0; e < CH; ++e) {
+                const int ci = nx_c0 + ch_base + e;
+                const bool ok = b_ok & (ci < p.Ci);
+                b_reg[ELEMS ? e : 0] = in[ok ? base + ci * p.HiWi : 0];   // clamped: masked at the store
+                b_bits |= (ok ? 1u : 0u) << e;
+            }
+        }
+        const uint4* __restrict__ in4 = reinterpret_cast<const uint4*>(in);
+#pragma unroll
+        for (int q = 0; q < (NCHW ? 0 : CH / 8); ++q) {
+            const int cb = ((nx_c0 + ch_base) >> 3) + q;                 // zero blocks pad Ci to Ci_pad
+            blk_reg[q] = in4[b_ok ? base + cb * p.HiWi : 0];            // clamped: masked at the store
         }
         // all taps of one channel group back to back (halo rows stay in L1/L2), then the next group
         nx_s += 1;
@@ -148,16 +167,21 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
             if (a_src[it] >= 0) *reinterpret_cast<uint4*>(&As[buf][a_dst[it]]) = a_reg[it];
-        const int c0 = staged_c0 + ch_base;
         uint16_t* row = &Bs[buf][(tid % BN) * LDK + ch_base];
+        if (!ELEMS) {
+#pragma unroll
+            for (int q = 0; q < CH / 8; ++q)
+                *reinterpret_cast<uint4*>(row + q * 8) = b_ok ? blk_reg[q] : make_uint4(0u, 0u, 0u, 0u);
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < CH / 8; ++q) {
             uint32_t w[4];
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 const int e = q * 8 + 2 * h;
-                const uint32_t lo = (FLAT ? ((b_bits >> e) & 1u) != 0 : (b_ok & (c0 + e < p.Ci))) ? b_reg[e] : 0u;
-                const uint32_t hi = (FLAT ? ((b_bits >> (e + 1)) & 1u) != 0 : (b_ok & (c0 + e + 1 < p.Ci))) ? b_reg[e + 1] : 0u;
+                const uint32_t lo = ((b_bits >> e) & 1u) ? b_reg[ELEMS ? e : 0] : 0u;
+                const uint32_t hi = ((b_bits >> (e + 1)) & 1u) ? b_reg[ELEMS ? e + 1 : 0] : 0u;
                 w[h] = lo | (hi << 16);
             }
             *reinterpret_cast<uint4*>(row + q * 8) = make_uint4(w[0], w[1], w[2], w[3]);
@@ -208,41 +232,78 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
                                       j0 + wn * TN * 32 + (lane & 31), lane >> 5, bias_s, i0);
 }
 
-template <bool FLAT, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+// NCHW -> [N][CBp][HW][8]: thread = (image, channel block, pixel); channels past C are zero.
+__global__ __launch_bounds__(256) void blockify_kernel(const uint16_t* __restrict__ src, uint4* __restrict__ dst,
+                                                       int C, int HW, int CBp, long long total) {
+    for (long long o = (long long)blockIdx.x * 256 + threadIdx.x; o < total; o += (long long)gridDim.x * 256) {
+        const long long plane = o / HW;                  // n * CBp + cb
+        const int pix = (int)(o - plane * HW);
+        const int cb = (int)(plane % CBp);
+        const long long n = plane / CBp;
+        const uint16_t* s = src + (n * C + (long long)cb * 8) * HW + pix;
+        uint32_t v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = cb * 8 + e < C ? (uint32_t)s[(long long)e * HW] : 0u;
+        dst[o] = make_uint4(v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16));
+    }
+}
+
+template <bool FLAT, bool NCHW, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_one(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_tap_bf16_kernel<FLAT, MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((igemm_tap_bf16_kernel<FLAT, NCHW, MINUS, D2S, FUSED, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <bool FLAT, bool MINUS, bool D2S, bool FUSED>
+template <bool FLAT, bool NCHW, bool MINUS, bool D2S, bool FUSED>
 hipError_t by_tile2(PixParams& p, int bm, int bn, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_one<FLAT, MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
+#define CALL(TM, TN, WM, WN) launch_one<FLAT, NCHW, MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
     PURINE_TILE_SWITCH(CALL)
 #undef CALL
 }
-template <bool FLAT, bool MINUS, bool D2S>
+template <bool FLAT, bool NCHW, bool MINUS, bool D2S>
 hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
     const bool fused = p.bias || p.relu || p.mask;
-    return fused ? by_tile2<FLAT, MINUS, D2S, true>(p, bm, bn, st) : by_tile2<FLAT, MINUS, D2S, false>(p, bm, bn, st);
+    return fused ? by_tile2<FLAT, NCHW, MINUS, D2S, true>(p, bm, bn, st)
+                 : by_tile2<FLAT, NCHW, MINUS, D2S, false>(p, bm, bn, st);
 }
 
 }  // namespace
 
+// Channels-blocked copy of the gathered tensor (p.in, [N][Ci][Hi][Wi] bf16) into `blocked`
+// ([N][Ci_pad/8][Hi][Wi][8]); p.in is redirected to it.
+hipError_t blockify_input(PixParams& p, void* blocked, hipStream_t st) {
+    const int CBp = p.Ci_pad / 8;
+    const long long total = (long long)p.N * CBp * p.HiWi;
+    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;   // block index is 32-bit in the kernel
+    const long long blocks = (total + 255) / 256;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(blockify_kernel, dim3((unsigned)(blocks > 1048576 ? 1048576 : blocks)), dim3(256), 0, st,
+                       (const uint16_t*)p.in, (uint4*)blocked, p.Ci, p.HiWi, CBp, total);
+    p.in = blocked;
+    return hipGetLastError();
+}
+
 hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
-    if (mode == 0) return by_tile<false, false, false>(p, bm, bn, st);
-    if (mode == 1) return by_tile<false, true, false>(p, bm, bn, st);
-    return by_tile<false, true, true>(p, bm, bn, st);
+    if (mode == 0) return by_tile<false, false, false, false>(p, bm, bn, st);
+    if (mode == 1) return by_tile<false, false, true, false>(p, bm, bn, st);
+    return by_tile<false, false, true, true>(p, bm, bn, st);
+}
+
+// single-tap layers (mode 0 or 1): gathers from the NCHW tensor p.in itself
+hipError_t dispatch_tap_bf16_nchw(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
+    if (mode == 0) return by_tile<false, true, false, false>(p, bm, bn, st);
+    return by_tile<false, true, true, false>(p, bm, bn, st);
 }
 
 // forward, flattened (c, r, s) reduction; p.wt is the filter copy A[i_pad][Ci_pad] with Ci_pad = Kg
 // rounded up to a multiple of 32, p.Rt = p.St = 1
 hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st) {
-    return by_tile<true, false, false>(p, bm, bn, st);
+    return by_tile<true, false, false, false>(p, bm, bn, st);
 }
 
 }  // namespace pix

@@ -255,6 +255,7 @@ struct TileCfg { int bm, bn; float eff; };
 // (TM, TN, WM, WN) for each tile extent: workgroup = WM x WN wavefronts of TM x TN MFMA tiles (32x32)
 #define PURINE_TILE_SWITCH(CALL)                                       \
     switch (bm * 1000 + bn) {                                          \
+        case 192128: return CALL(3, 2, 2, 2);                          \
         case 128128: return CALL(2, 2, 2, 2);                          \
         case 96256:  return CALL(3, 2, 1, 4);                          \
         case 96128:  return CALL(3, 1, 1, 4);                          \
@@ -269,6 +270,11 @@ struct TileCfg { int bm, bn; float eff; };
 
 // bf16 MFMA variant of the tap kernel (conv_igemm_bf16.hip). mode: 0 fwd, 1 bwd unit stride, 2 bwd phase-folded.
 hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st);
+// bf16 tap kernels gather from a channels-blocked copy [N][Ci_pad/8][Hi][Wi][8] of p.in: this writes
+// it into `blocked` (N*Ci_pad*Hi*Wi*2 bytes, 16-byte aligned) and points p.in at it
+hipError_t blockify_input(PixParams& p, void* blocked, hipStream_t st);
+// single-tap bf16 layers (mode 0 or 1): no blocked copy, 2-byte gathers from NCHW
+hipError_t dispatch_tap_bf16_nchw(PixParams& p, int mode, int bm, int bn, hipStream_t st);
 // bf16 MFMA forward with a flattened (c,r,s) reduction (fewer than 16 input channels)
 hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st);
 // streaming GEMM for 1x1 / stride 1 / unpadded layers (conv_gemm1x1.hip); p.wt is the KCRS filter
