@@ -29,6 +29,7 @@ template <> __device__ __forceinline__ float ld<uint16_t>(const uint16_t* p, int
     switch (plan.bm * 1000 + plan.bn) {                                          \
         case 128128: return CALL(2, 2, 2, 2);                                    \
         case 128096: return CALL(1, 3, 4, 1);                                    \
+        case 192064: return CALL(3, 1, 2, 2);                                    \
         case 128064: return CALL(1, 2, 4, 1);                                    \
         case 96128:  return CALL(3, 1, 1, 4);                                    \
         case 64128:  return CALL(2, 1, 1, 4);                                    \
@@ -509,7 +510,7 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     pl.tap = g.C >= 64;   // enough channels to fill the columns of a per-tap tile
     if (pl.tap) {
         // (bm, bn) with the least padded area, larger tile on ties
-        const int cand[7][2] = {{128, 128}, {128, 96}, {96, 128}, {128, 64}, {64, 128}, {64, 64}, {32, 128}};
+        const int cand[8][2] = {{128, 128}, {128, 96}, {96, 128}, {192, 64}, {128, 64}, {64, 128}, {64, 64}, {32, 128}};
         long long best = -1;
         for (const auto& c : cand) {
             const long long area = (long long)((g.K + c[0] - 1) / c[0]) * c[0] * ((g.C + c[1] - 1) / c[1]) * c[1];
