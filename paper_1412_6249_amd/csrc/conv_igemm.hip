@@ -199,8 +199,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams
 
 // ------------------------------------------------------------------------------------------------
 // Flat kernel: forward pass of layers with fewer than 16 input channels. The reduction index is
-// kk = (c, r, s) flattened, which equals the memory order of one filter row, and each slab row
-// decodes its own (c, r, s) on the scalar unit (rows are uniform per wavefront).
+// kk = (c, r, s) flattened, which equals the memory order of one filter row; the offset and tap of
+// every row are decoded once per workgroup into an LDS table.
 template <typename T, bool FUSED, bool NOPAD, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
@@ -217,6 +217,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
     __shared__ float As[2][BK * LDA];
     __shared__ float Bs[2][BK * BN];
     __shared__ float bias_s[FUSED ? BM : 1];
+    __shared__ int tab_off[FLAT_MAX_KG];
+    __shared__ int tab_rs[NOPAD ? 1 : FLAT_MAX_KG];
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
@@ -252,18 +254,20 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
     float b_reg[B_PASSES];
     unsigned a_ok, b_ok;   // one validity bit per staged value; the zero-fill happens at the LDS store
 
-    // walking state of this wavefront's gather rows: row index, its (r, s) and its offset
-    // c*Hi*Wi + r*Wi + s inside one image
-    int w_kk = b_row, w_r, w_s, w_off;
-    {
-        const int c = fastdiv(w_kk, p.div_rs);
-        const int rs = w_kk - c * p.RS;
-        w_r = fastdiv(rs, p.div_s);
-        w_s = rs - w_r * p.S;
-        w_off = c * p.HiWi + w_r * p.Wi + w_s;
-        w_kk = __builtin_amdgcn_readfirstlane(w_kk); w_r = __builtin_amdgcn_readfirstlane(w_r);
-        w_s = __builtin_amdgcn_readfirstlane(w_s); w_off = __builtin_amdgcn_readfirstlane(w_off);
+    // Row kk = (c, r, s) of the flattened reduction: offset c*Hi*Wi + r*Wi + s inside one image and
+    // its tap, decoded once per workgroup into LDS (the host guarantees Kg <= FLAT_MAX_KG); a
+    // wavefront's rows are uniform across its lanes, so the lookups are broadcast reads.
+    const int n_rows = (p.Kg + BK - 1) / BK * BK;
+    for (int k = tid; k < n_rows; k += NT) {
+        const int kq = k < p.Kg ? k : 0;
+        const int c = fastdiv(kq, p.div_rs);
+        const int rs = kq - c * p.RS;
+        const int r = fastdiv(rs, p.div_s);
+        const int sx = rs - r * p.S;
+        tab_off[k] = c * p.HiWi + r * p.Wi + sx;
+        if (!NOPAD) tab_rs[k] = (r << 16) | sx;
     }
+    __syncthreads();
 
     auto load_slab = [&](int slab) {
         a_ok = 0u; b_ok = 0u;
@@ -278,32 +282,19 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
                 a_ok |= (ok ? 1u : 0u) << ps;
             }
         }
-        // Row kk = (c, r, s) of the flattened reduction is walked incrementally on the scalar unit
-        // (rows are uniform per wavefront): this wavefront's rows are kk0, kk0 + B_RPP, ... and the
-        // state carries over from slab to slab, so no row is ever decoded by division.
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
-            const bool kv = w_kk < p.Kg;
-            bool ok = kv & g_live;
+            const int kk = slab * BK + ps * B_RPP + b_row;       // uniform per wavefront
+            const int kc = kk < n_rows ? kk : 0;                 // the slab past the end is all masked
+            bool ok = (kk < p.Kg) & g_live;
             if (!NOPAD) {
-                const int hi = g_h + w_r, wi = g_w + w_s;
+                const int rs = tab_rs[kc];
+                const int hi = g_h + (rs >> 16), wi = g_w + (rs & 0xffff);
                 // bitwise & on purpose: no short-circuit control flow inside the slab loop
                 ok = ok & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
             }
-            b_reg[ps] = Elem<T>::load(in, ok ? g_off + w_off : 0);
+            b_reg[ps] = Elem<T>::load(in, ok ? g_off + tab_off[kc] : 0);
             b_ok |= (ok ? 1u : 0u) << ps;
-            // advance by B_RPP rows, one at a time and branch-free (selects on the scalar unit)
-            w_kk += B_RPP;
-#pragma unroll
-            for (int t = 0; t < B_RPP; ++t) {
-                w_s += 1;
-                const bool wrap_s = w_s >= p.S;
-                w_s = wrap_s ? 0 : w_s;
-                w_r += wrap_s ? 1 : 0;
-                const bool wrap_r = w_r >= p.R;
-                w_r = wrap_r ? 0 : w_r;
-                w_off += 1 + (wrap_s ? p.Wi - p.S : 0) + (wrap_r ? p.HiWi - p.R * p.Wi : 0);
-            }
         }
     };
     auto store_slab = [&](int buf) {
@@ -516,7 +507,7 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
         M = (long long)g.N * Hq * Wq;
         pl.Rt = (g.R + g.sh - 1) / g.sh; pl.St = (g.S + g.sw - 1) / g.sw;
     }
-    pl.flat = !bwd_data && Ci < BK;
+    pl.flat = !bwd_data && Ci < BK && (dtype == PURINE_BF16 || Ci * g.R * g.S <= FLAT_MAX_KG);
     // Time model per tile shape: workgroups are dealt round-robin to the 256 CUs and a CU's MFMA pipe
     // is shared by whatever it holds, so the kernel lasts as long as the busiest CU:
     // ceil(workgroups/256) * bm*bn/eff. A CU holding one or two workgroups has too few wavefronts to
@@ -680,8 +671,7 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
     }
     if (pl.flat) {
         p.wt = wt;
-        return dtype == PURINE_F32 ? dispatch_flat<float>(p, pl.bm, pl.bn, st)
-                                   : dispatch_flat<uint16_t>(p, pl.bm, pl.bn, st);
+        return dispatch_flat<float>(p, pl.bm, pl.bn, st);   // bf16 took the branch above
     }
     // bf16: the whole operator (input copy, filter repack, main kernel) is what a timing probe brackets
     ProbeScope whole_op(dtype == PURINE_BF16 ? st : nullptr, dtype == PURINE_BF16);

@@ -53,6 +53,10 @@ template <> struct Elem<uint16_t> {  // bfloat16 bit patterns
     }
 };
 
+// Longest flattened reduction C*R*S the fp32 flat forward kernel keeps a row table for (a multiple of
+// the slab depth); longer ones take the tap-major kernel.
+constexpr int FLAT_MAX_KG = 2048;
+
 struct PixParams {
     const void* in;     // gathered activation tensor [N][Ci][Hi][Wi]
     const void* wt;     // tap kernel: repacked filter A[taps][Ci_pad][i_pad]; flat kernel: KCRS filter

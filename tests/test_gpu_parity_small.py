@@ -33,6 +33,8 @@ CASES = [
     ("smallc_s4_pad5", 2, 4, 21, 19, 6, 7, 6, (4, 4), (5, 4)),
     ("pq_multiple_of_32", 3, 8, 16, 16, 40, 3, 3, (1, 1), (1, 1)),
     ("c70_k70_5x5", 2, 70, 12, 12, 70, 5, 5, (1, 1), (2, 2)),
+    # fewer than 16 channels but C*R*S beyond the flattened kernel's row table: tap-major kernel
+    ("c15_12x12_long_reduction", 2, 15, 15, 14, 8, 12, 12, (1, 1), (1, 0)),
     # 1x1 / stride 1 / no padding with channel counts that are multiples of 16 and an even pixel
     # count: the streaming GEMM kernel (forward when C qualifies, backward-data when K does)
     ("pw_c48_k100", 3, 48, 10, 14, 100, 1, 1, (1, 1), (0, 0)),
