@@ -93,9 +93,27 @@ def test_workspace_queries():
             fwd = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_FWD, d, l.x_shape, l.w_shape, dt)
             bwd = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_DATA, d, l.x_shape, l.w_shape, dt)
             w_bytes = esz * int(np.prod(l.w_shape))
-            # a zero-padded copy of the filter: at least its size, never absurdly more
-            assert (fwd == 0 and l.C < 16) or w_bytes <= fwd <= 8 * w_bytes + (1 << 16)
-            assert w_bytes <= bwd <= 24 * w_bytes + (1 << 16)
+
+            def bound(rows, red, taps, gathered_elems):
+                """A zero-padded filter copy (rows up to the widest row tile, reduction up to a
+                whole slab more), plus, for bf16 layers with more than one tap, a channels-blocked
+                copy of the gathered tensor."""
+                pad_rows = max(192, (rows + 191) // 192 * 192)
+                filt = esz * taps * (red + 32) * pad_rows
+                blocked = 2 * gathered_elems if (l.dtype == "bf16" and taps > 1 and red >= 16) else 0
+                return filt + blocked + 256
+
+            taps = l.R * l.S
+            c_pad = (l.C + 31) // 32 * 32
+            k_pad = (l.K + 31) // 32 * 32
+            if l.C < 16 and l.dtype == "f32":
+                assert fwd == 0                                   # the flattened fp32 kernel reads KCRS
+            else:
+                assert w_bytes <= fwd <= bound(l.K, l.C * taps if l.C < 16 else l.C, 1 if l.C < 16 else taps,
+                                               l.N * c_pad * l.H * l.W)
+            s2 = l.stride * l.stride
+            taps_b = taps if l.stride == 1 else ((l.R + l.stride - 1) // l.stride) * ((l.S + l.stride - 1) // l.stride)
+            assert w_bytes <= bwd <= bound(l.C * s2, l.K, taps_b, l.N * k_pad * l.P * l.Q)
             nbytes = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT, d, l.x_shape, l.w_shape, dt)
             dw_bytes = 4 * int(np.prod(l.w_shape))
             assert nbytes >= dw_bytes and nbytes % dw_bytes == 0      # whole partial copies of dw
