@@ -93,10 +93,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     bool b_ok = false;
     uint32_t b_bits = 0;             // FLAT / NCHW: validity of each gathered element
 
-    int nx_r = 0, nx_s = 0, nx_c0 = 0, staged_c0 = 0;
+    int nx_r = 0, nx_s = 0, nx_c0 = 0;
     auto load_slab = [&]() {
-        (void)staged_c0;
-        staged_c0 = nx_c0;
         const int tap = FLAT ? 0 : nx_r * p.St + nx_s;
         const int a_slab = tap * p.i_pad * p.Ci_pad + nx_c0;
 #pragma unroll
