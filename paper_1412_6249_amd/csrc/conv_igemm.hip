@@ -39,7 +39,7 @@ constexpr int BK = 16;  // slab depth along the reduction (fp32 kernels)
 // Workgroup = WM x WN wavefronts, each owning TM x TN MFMA tiles of MT x MT: 32 (v_mfma 32x32x2) or
 // 16 (v_mfma 16x16x4, same flop rate, for GEMMs whose row count would waste half a 32-row tile).
 template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32>
-__global__ __launch_bounds__(WM * WN * 64) void igemm_tap_kernel(const PixParams p) {
+__global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM == 2 ? 4 : 1)) void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * MT;
     constexpr int BN = WN * TN * MT;
