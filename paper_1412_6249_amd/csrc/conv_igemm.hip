@@ -38,7 +38,12 @@ constexpr int BK = 16;  // slab depth along the reduction (fp32 kernels)
 // D2S: depth-to-space epilogue of the phase-folded strided backward-data.
 // Workgroup = WM x WN wavefronts, each owning TM x TN MFMA tiles of MT x MT: 32 (v_mfma 32x32x2) or
 // 16 (v_mfma 16x16x4, same flop rate, for GEMMs whose row count would waste half a 32-row tile).
-template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32>
+// BUF: the gathered operand is read with raw buffer loads. The hardware range check (byte offset =
+// per-lane part + scalar part against the tensor's size) returns zero for an out-of-range offset,
+// so a masked lane carries offset 2^31 and a padding channel a scalar offset of 2^31 - 1, and the
+// slab loop needs neither the clamped addresses nor the zero-fill selects. The host enables it for
+// tensors below 2^31 bytes.
+template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32, bool BUF = false>
 __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM == 2 ? 4 : 1)) void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * MT;
@@ -85,6 +90,9 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
         g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;   // tap (0,0) of channel 0
     }
     const int b_row = __builtin_amdgcn_readfirstlane(tid / BN);  // uniform per wavefront (BN >= 64)
+    // descriptor of the gathered tensor as a raw buffer of p.in_bytes bytes (BUF only)
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(in), (short)0, BUF ? (int)p.in_bytes : 0, 0x00020000);
 
     // filter slab pieces served by this thread: element offset inside a slab, and LDS slot
     int a_src[A_ITERS], a_dst[A_ITERS];
@@ -116,13 +124,23 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
         const int wi = MINUS ? g_w - nx_s : g_w + nx_s;
         const int tap_off = nx_r * p.Wi + nx_s;
         b_ok = g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
-        const int base = b_ok ? (MINUS ? g_off - tap_off : g_off + tap_off) : 0;
+        if (BUF) {
+            const unsigned vbase = b_ok ? (unsigned)(MINUS ? g_off - tap_off : g_off + tap_off) * 4u : 0x80000000u;
 #pragma unroll
-        for (int ps = 0; ps < B_PASSES; ++ps) {
-            const int ci = nx_c0 + ps * B_RPP + b_row;
-            // rows past Ci (padding of the last slab of a tap) read channel 0 and are zeroed at the store
-            const int plane = (b_ok & (ci < p.Ci)) ? ci * p.HiWi : 0;
-            b_reg[ps] = Elem<T>::load(in, base + plane);
+            for (int ps = 0; ps < B_PASSES; ++ps) {
+                const int ci = nx_c0 + ps * B_RPP + b_row;                   // uniform per wavefront
+                const int soff = ci < p.Ci ? ci * p.HiWi * 4 : 0x7fffffff;   // scalar part of the offset
+                b_reg[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, vbase, soff, 0));
+            }
+        } else {
+            const int base = b_ok ? (MINUS ? g_off - tap_off : g_off + tap_off) : 0;
+#pragma unroll
+            for (int ps = 0; ps < B_PASSES; ++ps) {
+                const int ci = nx_c0 + ps * B_RPP + b_row;
+                // rows past Ci (padding of the last slab of a tap) read channel 0 and are zeroed at the store
+                const int plane = (b_ok & (ci < p.Ci)) ? ci * p.HiWi : 0;
+                b_reg[ps] = Elem<T>::load(in, base + plane);
+            }
         }
         // advance to the next slab (past the last one it wraps to the start; those values are unused)
         nx_s += 1;
@@ -141,7 +159,7 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
             if (a_src[it] >= 0) *reinterpret_cast<floatx4*>(&As[buf][a_dst[it]]) = a_reg[it];
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
-            const bool ok = b_ok & (c0 + ps * B_RPP + b_row < p.Ci);
+            const bool ok = BUF | (b_ok & (c0 + ps * B_RPP + b_row < p.Ci));   // BUF: zeros came from the loads
             Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = ok ? b_reg[ps] : 0.0f;
         }
     };
@@ -425,12 +443,17 @@ constexpr TileCfg kTiles[] = {
 
 template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32>
 hipError_t launch_tap(PixParams& p, hipStream_t st) {
+    const bool buf = p.in_bytes != 0;
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, FUSED, TM, TN, WM, WN, MT>), dim3((unsigned)total),
-                       dim3(WM * WN * 64), 0, st, p);
+    if (buf)
+        hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, FUSED, TM, TN, WM, WN, MT, true>), dim3((unsigned)total),
+                           dim3(WM * WN * 64), 0, st, p);
+    else
+        hipLaunchKernelGGL((igemm_tap_kernel<T, MINUS, D2S, FUSED, TM, TN, WM, WN, MT, false>), dim3((unsigned)total),
+                           dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
@@ -487,7 +510,11 @@ hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
 // operand traffic per MFMA; the busiest of the 256 CUs gets ceil(workgroups/256) of them. Pick the
 // tile that minimises that CU's load (padding waste is part of it, through the tile counts).
 static int g_force_bm = 0, g_force_bn = 0;   // tuning hook, see purine_debug_force_tile
-void force_pix_tile(int bm, int bn) { g_force_bm = bm; g_force_bn = bn; }
+static int g_no_buffer_loads = 0;            // tuning hook: bn == -1 in purine_debug_force_tile
+void force_pix_tile(int bm, int bn) {
+    g_no_buffer_loads = bn == -1 ? 1 : 0;
+    g_force_bm = bm; g_force_bn = bn;
+}
 
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     PixPlan pl{};
@@ -640,6 +667,12 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
     p.div_s = make_fastdiv(p.S);
     p.beta = beta;
     p.tiles_i = pl.tiles_i; p.tiles_pix = pl.tiles_pix;
+    {
+        // raw-buffer gather of the fp32 tap kernels: the whole tensor must be addressable with byte
+        // offsets below 2^31
+        const long long in_bytes = (long long)p.N * p.Ci * p.HiWi * 4;
+        p.in_bytes = (dtype == PURINE_F32 && in_bytes < 0x7fffffffLL && g_no_buffer_loads == 0) ? (unsigned)in_bytes : 0u;
+    }
 
     if (pl.gemm1x1) {
         const uintptr_t align = (uintptr_t)pl.gemm_tn * (dtype == PURINE_BF16 ? 2 : 4) - 1;

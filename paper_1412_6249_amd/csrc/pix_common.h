@@ -75,6 +75,7 @@ struct PixParams {
     const void* mask;   // same extents and dtype as out: ReLU output whose gradient this pass produces
     int relu;
     int tiles_i, tiles_pix;
+    unsigned in_bytes;   // size of the gathered tensor when the fp32 tap kernels may read it as a raw buffer, else 0
 };
 
 // The fused forward kernels stage their row tile's bias values in LDS at kernel start (zero past the
