@@ -48,6 +48,7 @@ struct WgradParams {
     int chunk;         // pixels per split, a multiple of the slab depth
     int tiles_i, tiles_j, splits;
     int c_tiles;       // per-tap column mode: channel tiles per tap (tiles_j = R*S*c_tiles)
+    unsigned x_bytes, dy_bytes;   // tensor sizes when the fp32 kernel may read them as raw buffers, else 0
 };
 
 

@@ -69,7 +69,15 @@ __device__ __forceinline__ TileWhere locate_tile(const WgradParams& p) {
     return t;
 }
 
-template <typename T, bool TAP, int TM, int TN, int WM, int WN>
+// BUF: both operands are read with raw buffer loads, whose hardware range check returns zero for a
+// byte offset at or beyond the tensor's size. A thread's offset is the sum of a per-slab pixel part
+// (2^31 when the pixel does not exist or, per-tap mode, its tap falls outside the image) and a
+// per-row part fixed for the kernel (2^30 when the row or column does not exist); the host enables
+// BUF for tensors below 2^30 bytes, so every such sum is out of range without wrapping, and the slab
+// loop needs no clamped addresses, validity bits or zero-fill selects. NOPAD (flattened columns of
+// an unpadded layer): every tap of an existing pixel is inside the image, so the flattened mode
+// gets the same two-part offsets.
+template <typename T, bool TAP, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;   // output channels k
@@ -120,6 +128,26 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
     float a_reg[A_PASSES], b_reg[B_PASSES];
     unsigned a_ok = 0u, b_ok = 0u;   // validity bits; the zero-fill happens at the LDS store
 
+    constexpr bool B_TWO_PART = BUF && (TAP || NOPAD);   // x offsets split into pixel part + column part
+    const __amdgpu_buffer_rsrc_t rs_dy =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(dy), (short)0, BUF ? (int)p.dy_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(x), (short)0, BUF ? (int)p.x_bytes : 0, 0x00020000);
+    // per-row / per-column byte offsets, fixed for the kernel
+    unsigned a_voff[BUF ? A_PASSES : 1], b_voff[B_TWO_PART ? B_PASSES : 1];
+    if (BUF) {
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) {
+            const int i = i0 + t_col + ps * RPP;
+            a_voff[BUF ? ps : 0] = i < p.K ? (unsigned)(i * p.PQ) * 4u : 0x40000000u;
+        }
+    }
+    if (B_TWO_PART) {
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps)
+            b_voff[B_TWO_PART ? ps : 0] = j_rs[ps] >= 0 ? (unsigned)j_off[ps] * 4u : 0x40000000u;
+    }
+
     auto load_slab = [&](int slab) {
         const int pix = pix_begin + slab * BK + t_kk;
         const bool pv = pix < pix_end;
@@ -130,16 +158,30 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
         const int qq = pq - pp * p.Q;
         const int a_base = n * p.K * p.PQ + pq;
         a_ok = 0u; b_ok = 0u;
+        if (BUF) {
+            const unsigned a_pix = pv ? (unsigned)a_base * 4u : 0x80000000u;
 #pragma unroll
-        for (int ps = 0; ps < A_PASSES; ++ps) {
-            const int i = i0 + t_col + ps * RPP;
-            const bool ok = pv & (i < p.K);
-            a_reg[ps] = ld<T>(dy, ok ? a_base + i * p.PQ : 0);   // clamped, branch-free
-            a_ok |= (ok ? 1u : 0u) << ps;
+            for (int ps = 0; ps < A_PASSES; ++ps)
+                a_reg[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_dy, a_pix + a_voff[BUF ? ps : 0], 0, 0));
+        } else {
+#pragma unroll
+            for (int ps = 0; ps < A_PASSES; ++ps) {
+                const int i = i0 + t_col + ps * RPP;
+                const bool ok = pv & (i < p.K);
+                a_reg[ps] = ld<T>(dy, ok ? a_base + i * p.PQ : 0);   // clamped, branch-free
+                a_ok |= (ok ? 1u : 0u) << ps;
+            }
         }
         const int hb = pp * p.sh - p.ph + tw.tap_r, wb = qq * p.sw - p.pw + tw.tap_s;
         const int b_base = n * p.C * p.HW + hb * p.W + wb;
-        if (TAP) {
+        if (B_TWO_PART) {
+            // per-tap mode: one bounds test for the pixel's tap; unpadded flattened mode: none
+            const bool in = TAP ? (pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W)) : pv;
+            const unsigned b_pix = in ? (unsigned)b_base * 4u : 0x80000000u;
+#pragma unroll
+            for (int ps = 0; ps < B_PASSES; ++ps)
+                b_reg[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_x, b_pix + b_voff[B_TWO_PART ? ps : 0], 0, 0));
+        } else if (TAP) {
             const bool in = pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W);
 #pragma unroll
             for (int ps = 0; ps < B_PASSES; ++ps) {
@@ -153,18 +195,23 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
                 const int r = j_rs[ps] >> 16, s = j_rs[ps] & 0xffff;
                 const bool ok = pv & (j_rs[ps] >= 0) & ((unsigned)(hb + r) < (unsigned)p.H) &
                                 ((unsigned)(wb + s) < (unsigned)p.W);
-                b_reg[ps] = ld<T>(x, ok ? b_base + j_off[ps] : 0);
-                b_ok |= (ok ? 1u : 0u) << ps;
+                if (BUF) {
+                    b_reg[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                        rs_x, ok ? (unsigned)(b_base + j_off[ps]) * 4u : 0x80000000u, 0, 0));
+                } else {
+                    b_reg[ps] = ld<T>(x, ok ? b_base + j_off[ps] : 0);
+                    b_ok |= (ok ? 1u : 0u) << ps;
+                }
             }
         }
     };
     auto store_slab = [&](int buf) {
 #pragma unroll
         for (int ps = 0; ps < A_PASSES; ++ps)
-            As[buf][t_kk * LDA + t_col + ps * RPP] = ((a_ok >> ps) & 1u) ? a_reg[ps] : 0.0f;
+            As[buf][t_kk * LDA + t_col + ps * RPP] = (BUF || ((a_ok >> ps) & 1u)) ? a_reg[ps] : 0.0f;
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
-            Bs[buf][t_kk * LDB + t_col + ps * RPP] = ((b_ok >> ps) & 1u) ? b_reg[ps] : 0.0f;
+            Bs[buf][t_kk * LDB + t_col + ps * RPP] = (BUF || ((b_ok >> ps) & 1u)) ? b_reg[ps] : 0.0f;
     };
 
     floatx16 acc[TM][TN];
@@ -482,22 +529,31 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
     }
 }
 
-template <typename T, bool TAP, int TM, int TN, int WM, int WN>
+template <typename T, bool TAP, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
 hipError_t launch_tile(WgradParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((wgrad_kernel<T, TAP, TM, TN, WM, WN>), dim3((unsigned)total), dim3(WM * WN * 64),
+    hipLaunchKernelGGL((wgrad_kernel<T, TAP, NOPAD, BUF, TM, TN, WM, WN>), dim3((unsigned)total), dim3(WM * WN * 64),
                        0, st, p);
     return hipGetLastError();
 }
 
-template <bool TAP>
-hipError_t dispatch_f32(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_tile<float, TAP, TM, TN, WM, WN>(p, st)
+template <bool TAP, bool NOPAD, bool BUF>
+hipError_t dispatch_f32_mode(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_tile<float, TAP, NOPAD, BUF, TM, TN, WM, WN>(p, st)
     WGRAD_TILE_SWITCH(CALL)
 #undef CALL
+}
+template <bool TAP>
+hipError_t dispatch_f32(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+    const bool buf = p.x_bytes != 0 && p.dy_bytes != 0;
+    // unpadded layer: every tap of every output pixel lies inside the image
+    const bool nopad = !TAP && p.ph == 0 && p.pw == 0 && (p.P - 1) * p.sh + p.R <= p.H && (p.Q - 1) * p.sw + p.S <= p.W;
+    if (TAP) return buf ? dispatch_f32_mode<TAP, false, true>(p, plan, st) : dispatch_f32_mode<TAP, false, false>(p, plan, st);
+    if (!buf) return dispatch_f32_mode<false, false, false>(p, plan, st);
+    return nopad ? dispatch_f32_mode<false, true, true>(p, plan, st) : dispatch_f32_mode<false, false, true>(p, plan, st);
 }
 
 }  // namespace
@@ -578,6 +634,13 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     p.chunk = plan.chunk; p.tiles_i = plan.tiles_i; p.tiles_j = plan.tiles_j; p.splits = plan.splits;
     p.c_tiles = plan.c_tiles;
     p.out = (float*)ws;
+    {
+        // raw-buffer loads of the fp32 kernel: two-part offsets need both tensors below 2^30 bytes
+        const long long xb = (long long)g.N * g.C * p.HW * 4, dyb = (long long)p.M * g.K * 4;
+        const bool ok = dtype == PURINE_F32 && xb < (1LL << 30) && dyb < (1LL << 30);
+        p.x_bytes = ok ? (unsigned)xb : 0u;
+        p.dy_bytes = ok ? (unsigned)dyb : 0u;
+    }
     hipError_t e;
     const bool vec = p.PQ % 32 == 0 && (((uintptr_t)dy) & 15u) == 0;
     if (dtype == PURINE_F32) e = plan.tap ? dispatch_f32<true>(p, plan, st) : dispatch_f32<false>(p, plan, st);
