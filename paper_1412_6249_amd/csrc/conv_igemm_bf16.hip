@@ -77,6 +77,9 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         g_off = n * (ELEMS ? p.Ci : p.Ci_pad / 8) * p.HiWi + g_h * p.Wi + g_w;
     }
     const int ch_base = __builtin_amdgcn_readfirstlane(tid / BN) * CH;   // uniform per wavefront
+    // the blocked copy as a raw buffer (not used by the 2-byte gather modes)
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(in), (short)0, ELEMS ? 0 : (int)p.in_bytes, 0x00020000);
 
     int a_src[A_ITERS], a_dst[A_ITERS];
 #pragma unroll
@@ -145,11 +148,15 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
                 b_bits |= (ok ? 1u : 0u) << e;
             }
         }
-        const uint4* __restrict__ in4 = reinterpret_cast<const uint4*>(in);
+        // blocked copy, read as a raw buffer: a masked lane carries byte offset 2^31, which the
+        // hardware range check answers with zeros (the copy is below 2^31 bytes, checked on the host)
+        const unsigned vbase = b_ok ? (unsigned)base * 16u : 0x80000000u;
 #pragma unroll
         for (int q = 0; q < (NCHW ? 0 : CH / 8); ++q) {
             const int cb = ((nx_c0 + ch_base) >> 3) + q;                 // zero blocks pad Ci to Ci_pad
-            blk_reg[q] = in4[b_ok ? base + cb * p.HiWi : 0];            // clamped: masked at the store
+            typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, vbase, cb * p.HiWi * 16, 0);
+            blk_reg[q] = make_uint4(v[0], v[1], v[2], v[3]);
         }
         // all taps of one channel group back to back (halo rows stay in L1/L2), then the next group
         nx_s += 1;
@@ -169,7 +176,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         if (!ELEMS) {
 #pragma unroll
             for (int q = 0; q < CH / 8; ++q)
-                *reinterpret_cast<uint4*>(row + q * 8) = b_ok ? blk_reg[q] : make_uint4(0u, 0u, 0u, 0u);
+                *reinterpret_cast<uint4*>(row + q * 8) = blk_reg[q];   // zeros came from the loads
             return;
         }
 #pragma unroll
@@ -277,7 +284,9 @@ hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
 hipError_t blockify_input(PixParams& p, void* blocked, hipStream_t st) {
     const int CBp = p.Ci_pad / 8;
     const long long total = (long long)p.N * CBp * p.HiWi;
-    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;   // block index is 32-bit in the kernel
+    // the kernels address the copy with byte offsets below 2^31
+    if (total <= 0 || total * 16 >= 0x7fffffffLL) return hipErrorInvalidValue;
+    p.in_bytes = (unsigned)(total * 16);
     const long long blocks = (total + 255) / 256;
     (void)hipGetLastError();
     hipLaunchKernelGGL(blockify_kernel, dim3((unsigned)(blocks > 1048576 ? 1048576 : blocks)), dim3(256), 0, st,
