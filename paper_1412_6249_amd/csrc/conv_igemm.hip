@@ -219,7 +219,10 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
 // Flat kernel: forward pass of layers with fewer than 16 input channels. The reduction index is
 // kk = (c, r, s) flattened, which equals the memory order of one filter row; the offset and tap of
 // every row are decoded once per workgroup into an LDS table.
-template <typename T, bool FUSED, bool NOPAD, int TM, int TN, int WM, int WN>
+// BUF: raw buffer loads as in the tap kernel; a row past the end of the reduction carries byte offset
+// 2^30 in the table and a pixel that does not exist 2^31, so (tensor below 2^30 bytes) their sums
+// are out of range and read as zero.
+template <typename T, bool FUSED, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -282,10 +285,13 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
         const int rs = kq - c * p.RS;
         const int r = fastdiv(rs, p.div_s);
         const int sx = rs - r * p.S;
-        tab_off[k] = c * p.HiWi + r * p.Wi + sx;
+        tab_off[k] = BUF ? (k < p.Kg ? (c * p.HiWi + r * p.Wi + sx) * 4 : 0x40000000) : c * p.HiWi + r * p.Wi + sx;
         if (!NOPAD) tab_rs[k] = (r << 16) | sx;
     }
     __syncthreads();
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(in), (short)0, BUF ? (int)p.in_bytes : 0, 0x00020000);
+    const unsigned g_voff = g_live ? (unsigned)g_off * 4u : 0x80000000u;
 
     auto load_slab = [&](int slab) {
         a_ok = 0u; b_ok = 0u;
@@ -311,8 +317,13 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
                 // bitwise & on purpose: no short-circuit control flow inside the slab loop
                 ok = ok & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
             }
-            b_reg[ps] = Elem<T>::load(in, ok ? g_off + tab_off[kc] : 0);
-            b_ok |= (ok ? 1u : 0u) << ps;
+            if (BUF) {
+                const unsigned v = g_voff + (unsigned)tab_off[kc];
+                b_reg[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, (NOPAD || ok) ? v : 0x80000000u, 0, 0));
+            } else {
+                b_reg[ps] = Elem<T>::load(in, ok ? g_off + tab_off[kc] : 0);
+                b_ok |= (ok ? 1u : 0u) << ps;
+            }
         }
     };
     auto store_slab = [&](int buf) {
@@ -321,7 +332,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
             As[buf][a_kk * LDA + a_i + ps * A_RPP] = ((a_ok >> ps) & 1u) ? a_reg[ps] : 0.0f;
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
-            Bs[buf][(ps * B_RPP + b_row) * BN + (tid % BN)] = ((b_ok >> ps) & 1u) ? b_reg[ps] : 0.0f;
+            Bs[buf][(ps * B_RPP + b_row) * BN + (tid % BN)] = (BUF || ((b_ok >> ps) & 1u)) ? b_reg[ps] : 0.0f;
     };
 
     floatx16 acc[TM][TN];
@@ -466,12 +477,13 @@ hipError_t launch_flat(PixParams& p, hipStream_t st) {
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    if (nopad)
-        hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, true, TM, TN, WM, WN>), dim3((unsigned)total),
-                           dim3(WM * WN * 64), 0, st, p);
-    else
-        hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, false, TM, TN, WM, WN>), dim3((unsigned)total),
-                           dim3(WM * WN * 64), 0, st, p);
+    const bool buf = p.in_bytes != 0 && p.in_bytes < (1u << 30);   // two-part offsets: tensor below 2^30 bytes
+#define FLAT_LAUNCH(NOPAD_, BUF_)                                                                          \
+    hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, NOPAD_, BUF_, TM, TN, WM, WN>), dim3((unsigned)total),     \
+                       dim3(WM * WN * 64), 0, st, p)
+    if (nopad) { if (buf) FLAT_LAUNCH(true, true); else FLAT_LAUNCH(true, false); }
+    else       { if (buf) FLAT_LAUNCH(false, true); else FLAT_LAUNCH(false, false); }
+#undef FLAT_LAUNCH
     return hipGetLastError();
 }
 
