@@ -48,7 +48,7 @@ struct WgradParams {
     int chunk;         // pixels per split, a multiple of the slab depth
     int tiles_i, tiles_j, splits;
     int c_tiles;       // per-tap column mode: channel tiles per tap (tiles_j = R*S*c_tiles)
-    unsigned x_bytes, dy_bytes;   // tensor sizes when the fp32 kernel may read them as raw buffers, else 0
+    unsigned x_bytes, dy_bytes;   // tensor sizes when the kernels may read them as raw buffers, else 0
 };
 
 
@@ -74,6 +74,7 @@ struct PixPlan {
 };
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
 void force_pix_tile(int bm, int bn);
+bool buffer_loads_disabled();   // tuning hook: (anything, -1) given to force_pix_tile
 
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and
 // for the launch.

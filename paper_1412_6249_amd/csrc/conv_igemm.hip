@@ -523,6 +523,7 @@ hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
 // tile that minimises that CU's load (padding waste is part of it, through the tile counts).
 static int g_force_bm = 0, g_force_bn = 0;   // tuning hook, see purine_debug_force_tile
 static int g_no_buffer_loads = 0;            // tuning hook: bn == -1 in purine_debug_force_tile
+bool buffer_loads_disabled() { return g_no_buffer_loads != 0; }
 void force_pix_tile(int bm, int bn) {
     g_no_buffer_loads = bn == -1 ? 1 : 0;
     g_force_bm = bm; g_force_bn = bn;

@@ -236,6 +236,7 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
     for (int slab = 0; slab < n_slabs; ++slab) {
         const int buf = slab & 1;
         load_slab(slab + 1);   // past the chunk: every value is masked to zero
+        __builtin_amdgcn_sched_barrier(0);   // the loads stay ahead of this slab's MFMAs
         float av[2][TM], bv[2][TN];   // operand fragments, double-buffered across k-steps
 #pragma unroll
         for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * LDA + a_off + a * 32];
@@ -289,7 +290,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 constexpr int BKP = 32;
 constexpr int LDP = BKP + 8;
 
-template <bool VEC_A, bool TAP, int TM, int TN, int WM, int WN>
+// BUF / NOPAD as in the fp32 kernel: the gathered x elements (and dy, when it is read element by
+// element) come through raw buffer loads with two-part byte offsets, zeros from the range check.
+template <bool VEC_A, bool TAP, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -342,6 +345,26 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
     uint32_t b_reg[B_PASSES];
     unsigned a_ok = 0u, b_ok = 0u;
 
+    constexpr bool A_BUF = BUF && !VEC_A;
+    constexpr bool B_TWO_PART = BUF && (TAP || NOPAD);
+    const __amdgpu_buffer_rsrc_t rs_dy =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(dy), (short)0, BUF ? (int)p.dy_bytes : 0, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_x =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x), (short)0, BUF ? (int)p.x_bytes : 0, 0x00020000);
+    unsigned a_voff[A_BUF ? A_PASSES : 1], b_voff[B_TWO_PART ? B_PASSES : 1];
+    if (A_BUF) {
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) {
+            const int i = i0 + t_row + ps * RPP;
+            a_voff[A_BUF ? ps : 0] = i < p.K ? (unsigned)(i * p.PQ) * 2u : 0x40000000u;
+        }
+    }
+    if (B_TWO_PART) {
+#pragma unroll
+        for (int ps = 0; ps < B_PASSES; ++ps)
+            b_voff[B_TWO_PART ? ps : 0] = j_rs[ps] >= 0 ? (unsigned)j_off[ps] * 2u : 0x40000000u;
+    }
+
     auto load_slab = [&](int slab) {
         const int pix0 = pix_begin + slab * BKP;
         const int pix = pix0 + t_px;
@@ -367,18 +390,32 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
         } else {
             a_ok = 0u;
             const int a_base = n * p.K * p.PQ + pq;
+            if (A_BUF) {
+                const unsigned a_pix = pv ? (unsigned)a_base * 2u : 0x80000000u;
 #pragma unroll
-            for (int ps = 0; ps < A_PASSES; ++ps) {
-                const int i = i0 + t_row + ps * RPP;
-                const bool ok = pv & (i < p.K);
-                a_reg[ps] = dy[ok ? a_base + i * p.PQ : 0];
-                a_ok |= (ok ? 1u : 0u) << ps;
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_reg[ps] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs_dy, a_pix + a_voff[A_BUF ? ps : 0], 0, 0);
+            } else {
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps) {
+                    const int i = i0 + t_row + ps * RPP;
+                    const bool ok = pv & (i < p.K);
+                    a_reg[ps] = dy[ok ? a_base + i * p.PQ : 0];
+                    a_ok |= (ok ? 1u : 0u) << ps;
+                }
             }
         }
         b_ok = 0u;
         const int hb = pp * p.sh - p.ph + tw.tap_r, wb = qq * p.sw - p.pw + tw.tap_s;
         const int b_base = n * p.C * p.HW + hb * p.W + wb;
         const bool in = pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W);
+        if (B_TWO_PART) {
+            const unsigned b_pix = (TAP ? in : pv) ? (unsigned)b_base * 2u : 0x80000000u;
+#pragma unroll
+            for (int ps = 0; ps < B_PASSES; ++ps)
+                b_reg[ps] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(rs_x, b_pix + b_voff[B_TWO_PART ? ps : 0], 0, 0);
+            return;
+        }
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
             bool ok;
@@ -389,8 +426,13 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
                 ok = pv & (j_rs[ps] >= 0) & ((unsigned)(hb + r) < (unsigned)p.H) &
                      ((unsigned)(wb + s) < (unsigned)p.W);
             }
-            b_reg[ps] = x[ok ? b_base + j_off[ps] : 0];
-            b_ok |= (ok ? 1u : 0u) << ps;
+            if (BUF) {
+                b_reg[ps] = (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(
+                    rs_x, ok ? (unsigned)(b_base + j_off[ps]) * 2u : 0x80000000u, 0, 0);
+            } else {
+                b_reg[ps] = x[ok ? b_base + j_off[ps] : 0];
+                b_ok |= (ok ? 1u : 0u) << ps;
+            }
         }
     };
     auto store_slab = [&](int buf) {
@@ -406,11 +448,11 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
         } else {
 #pragma unroll
             for (int ps = 0; ps < A_PASSES; ++ps)
-                As[buf][(t_row + ps * RPP) * LDP + t_px] = ((a_ok >> ps) & 1u) ? (uint16_t)a_reg[ps] : (uint16_t)0;
+                As[buf][(t_row + ps * RPP) * LDP + t_px] = (A_BUF || ((a_ok >> ps) & 1u)) ? (uint16_t)a_reg[ps] : (uint16_t)0;
         }
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
-            Bs[buf][(t_row + ps * RPP) * LDP + t_px] = ((b_ok >> ps) & 1u) ? (uint16_t)b_reg[ps] : (uint16_t)0;
+            Bs[buf][(t_row + ps * RPP) * LDP + t_px] = (BUF || ((b_ok >> ps) & 1u)) ? (uint16_t)b_reg[ps] : (uint16_t)0;
     };
 
     floatx16 acc[TM][TN];
@@ -472,22 +514,33 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
     }
 }
 
-template <bool VEC_A, bool TAP, int TM, int TN, int WM, int WN>
+template <bool VEC_A, bool TAP, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
 hipError_t launch_tile_bf16(WgradParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_j * p.splits;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((wgrad_bf16_kernel<VEC_A, TAP, TM, TN, WM, WN>), dim3((unsigned)total),
+    hipLaunchKernelGGL((wgrad_bf16_kernel<VEC_A, TAP, NOPAD, BUF, TM, TN, WM, WN>), dim3((unsigned)total),
                        dim3(WM * WN * 64), 0, st, p);
     return hipGetLastError();
 }
 
-template <bool VEC_A, bool TAP>
-hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
-#define CALL(TM, TN, WM, WN) launch_tile_bf16<VEC_A, TAP, TM, TN, WM, WN>(p, st)
+template <bool VEC_A, bool TAP, bool NOPAD, bool BUF>
+hipError_t dispatch_bf16_mode(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+#define CALL(TM, TN, WM, WN) launch_tile_bf16<VEC_A, TAP, NOPAD, BUF, TM, TN, WM, WN>(p, st)
     WGRAD_TILE_SWITCH(CALL)
 #undef CALL
+}
+template <bool VEC_A, bool TAP>
+hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
+    // measured: the per-tap mode with several taps (3x3 64->192 at 56x56) runs 15 % slower with
+    // 2-byte buffer loads than with plain loads; single-tap and flattened layers run 6-10 % faster
+    const bool buf = p.x_bytes != 0 && p.dy_bytes != 0 && !(TAP && p.RS > 1);
+    const bool nopad = !TAP && p.ph == 0 && p.pw == 0 && (p.P - 1) * p.sh + p.R <= p.H && (p.Q - 1) * p.sw + p.S <= p.W;
+    if (!buf) return dispatch_bf16_mode<VEC_A, TAP, false, false>(p, plan, st);
+    if (TAP) return dispatch_bf16_mode<VEC_A, TAP, false, true>(p, plan, st);
+    return nopad ? dispatch_bf16_mode<VEC_A, false, true, true>(p, plan, st)
+                 : dispatch_bf16_mode<VEC_A, false, false, true>(p, plan, st);
 }
 
 // dw[i] = beta*dw[i] + partial[0][i] + partial[1][i] + ... summed in a fixed tree: a workgroup owns
@@ -635,9 +688,10 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     p.c_tiles = plan.c_tiles;
     p.out = (float*)ws;
     {
-        // raw-buffer loads of the fp32 kernel: two-part offsets need both tensors below 2^30 bytes
-        const long long xb = (long long)g.N * g.C * p.HW * 4, dyb = (long long)p.M * g.K * 4;
-        const bool ok = dtype == PURINE_F32 && xb < (1LL << 30) && dyb < (1LL << 30);
+        // raw-buffer loads: two-part offsets need both tensors below 2^30 bytes
+        const int es = dtype == PURINE_F32 ? 4 : 2;
+        const long long xb = (long long)g.N * g.C * p.HW * es, dyb = (long long)p.M * g.K * es;
+        const bool ok = xb < (1LL << 30) && dyb < (1LL << 30) && !buffer_loads_disabled();
         p.x_bytes = ok ? (unsigned)xb : 0u;
         p.dy_bytes = ok ? (unsigned)dyb : 0u;
     }
