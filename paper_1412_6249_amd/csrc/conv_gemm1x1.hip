@@ -145,7 +145,7 @@ __device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[T
     asm volatile("" : "+v"(mrow));
     // rows per batch: what a batch needs from memory (mask, old output) is requested before the
     // first of its stores; fewer rows per batch where a row is four pixels wide (registers)
-    constexpr int G = TN >= 4 ? 4 : 8;
+    constexpr int G = TN >= 4 ? 4 : (FUSED ? 16 : 8);
 #pragma unroll
     for (int part = 0; part < 16 / G; ++part) {
         const int e0 = part * G;
