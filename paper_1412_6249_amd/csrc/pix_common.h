@@ -90,9 +90,9 @@ __device__ __forceinline__ void stage_bias(float* bias_lds, const PixParams& p, 
 
 // Epilogue shared by the kernels. Accumulator register e of a 32x32 tile holds row
 // (e/4)*8 + (lane/32)*4 + e%4, column lane%32. Optional pieces (bias, ReLU, ReLU-gradient mask,
-// accumulate) are uniform branches; what an element needs from memory (bias or mask value, old
-// output) is fetched for 8 rows of one MFMA tile BEFORE their 8 stores, so the loads overlap
-// instead of forming load-wait-store round trips, while only 8-16 extra registers are live.
+// accumulate) are uniform branches; what an element needs from memory (mask value, old output) is
+// fetched for a batch of rows of one MFMA tile BEFORE their stores, so the loads overlap instead of
+// forming load-wait-store round trips, while few extra registers are live.
 template <typename T, bool D2S>
 struct TileAddr {
     const PixParams& p;
@@ -160,6 +160,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     const T* __restrict__ bias = (const T*)p.bias;
     const T* __restrict__ mask = (const T*)p.mask;
     const bool has_bias = !D2S && bias != nullptr, has_mask = mask != nullptr, has_beta = p.beta != 0.0f;
+    constexpr int G = TM * TN <= 3 ? 16 : 8;   // rows per staged batch
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int pix = pix_base + b * 32;
@@ -167,35 +168,34 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
         const int n = fastdiv(pix, p.div_howo);
         const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
 #pragma unroll
-        for (int ah = 0; ah < TM * 2; ++ah) {
-            // half an MFMA tile (8 rows) at a time: its bias / mask / old values are requested
-            // before the first of its stores, and 8..16 staging registers are all this adds
-            const int a = ah >> 1, e0 = (ah & 1) * 8;
-            const int row0 = i_base + a * 32 + khalf * 4 + (ah & 1) * 16;
-            float t[8], o[8];
+        for (int ag = 0; ag < TM * (16 / G); ++ag) {
+            // The mask / old output values of G rows of an MFMA tile are requested before the first
+            // of their stores, so that their latency is paid once per batch; bias values come from
+            // LDS. G = 16 where the accumulators leave room, 8 for the four-tile wavefronts.
+            const int a = ag / (16 / G), e0 = (ag % (16 / G)) * G;
+            const int rowa = i_base + a * 32 + khalf * 4;
+            float t[G], o[G];
             bool ok;
-            if (has_bias) {
+            if (has_mask && !has_bias) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) t[e] = bias_lds[row0 + (e >> 2) * 8 + (e & 3) - i_tile0];
-            } else if (has_mask) {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) t[e] = Elem<T>::load(mask, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
+                for (int e = 0; e < G; ++e) t[e] = Elem<T>::load(mask, addr.at(rowa + ((e0 + e) >> 2) * 8 + (e & 3), ok));
             }
             if (has_beta) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = Elem<T>::load(out, addr.at(row0 + (e >> 2) * 8 + (e & 3), ok));
+                for (int e = 0; e < G; ++e) o[e] = Elem<T>::load(out, addr.at(rowa + ((e0 + e) >> 2) * 8 + (e & 3), ok));
             }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int off = addr.at(row0 + (e >> 2) * 8 + (e & 3), ok);
+            for (int e = 0; e < G; ++e) {
+                const int row = rowa + ((e0 + e) >> 2) * 8 + (e & 3);
+                const int off = addr.at(row, ok);
                 float v = acc[a][b][e0 + e];
-                if (has_bias) v += t[e];
+                if (has_bias) v += bias_lds[row - i_tile0];
                 if (p.relu) v = v > 0.0f ? v : 0.0f;
-                if (has_mask) v = t[e] > 0.0f ? v : 0.0f;
+                if (has_mask && !has_bias) v = t[e] > 0.0f ? v : 0.0f;
                 if (has_beta) v += o[e];
                 if (ok) Elem<T>::store(out, off, v);
             }
-            // keep the next half tile's loads from being hoisted above these stores
+            // keep the next batch's loads from being hoisted above these stores
             __builtin_amdgcn_sched_barrier(0);
         }
     }
