@@ -33,7 +33,8 @@ MEASURED_TRAFFIC_BYTES = {
 
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
               5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
-              10: "concat_bwd", 11: "sum", 13: "conv_fwd_bias_relu", 14: "conv_bwd_data_relu"}
+              10: "concat_bwd", 11: "sum", 13: "conv_fwd_bias_relu", 14: "conv_bwd_data_relu",
+              15: "conv_bwd_weight_bias"}
 
 
 def cpu_baseline(cfg, budget_s=15.0):
@@ -142,7 +143,7 @@ def main():
     # the bracketed durations below, so that they are kernel durations as a profiler reports them.
     bracket_ms = bracket_overhead_ms()
     warm_ms = {k: max(v - bracket_ms, 1e-4) for k, v in warm_ms.items()}
-    conv_kinds = (0, 2, 3, 13, 14)
+    conv_kinds = (0, 2, 3, 13, 14, 15)
     dominant = max((op for op in gb.ops if op[1] in conv_kinds), key=lambda op: warm_ms[op[0]])[0]
     # Timed region: the graph runs on its streams with operators overlapping as their thread ids
     # allow. On every n-th step (default 4) the dominant kernel is bracketed (one event pair) and

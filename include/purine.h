@@ -66,7 +66,10 @@ typedef struct { int32_t stride_h, stride_w, pad_h, pad_w; } purine_conv_desc;
 /* Square max-pooling window. */
 typedef struct { int32_t window, stride, pad; } purine_pool_desc;
 
-typedef enum { PURINE_CONV_FWD = 0, PURINE_CONV_BWD_DATA = 1, PURINE_CONV_BWD_WEIGHT = 2 } purine_conv_pass;
+typedef enum {
+    PURINE_CONV_FWD = 0, PURINE_CONV_BWD_DATA = 1, PURINE_CONV_BWD_WEIGHT = 2,
+    PURINE_CONV_BWD_WEIGHT_BIAS = 3   /* purine_conv_bwd_weight_bias: both sets of partial sums */
+} purine_conv_pass;
 
 const char* purine_status_string(int status);
 /* Name of the HIP error behind the last PURINE_E_HIP returned to this host thread. */
@@ -124,6 +127,16 @@ int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
                            const purine_tensor* dy, purine_tensor* dw, float beta, void* ws,
                            size_t ws_bytes, void* hip_stream);
 
+/* ConvBwdWeight and BiasBwd of one layer as a single operator (both read all of dy; paper
+ * Figure 1(b) draws them as two vertices on the same incoming tensor): dw as above and
+ * db[k] = beta*db + sum_{n,p,q} dy[n,k,p,q], db F32 of K elements. The dy fragments that feed the
+ * matrix cores are summed on the way, so dy is read once. Partial sums per chunk for both, added
+ * in chunk order by the second kernel. ws: purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT_BIAS).
+ * db must not overlap x, dy or dw. */
+int purine_conv_bwd_weight_bias(const purine_conv_desc* desc, const purine_tensor* x,
+                                const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
+                                float beta, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* Bias: y[n,k,p,q] += b[k], in place. y: F32 or BF16 (add in fp32); b: same dtype as y. */
 int purine_bias_fwd(const purine_tensor* b, purine_tensor* y, void* hip_stream);
 
@@ -176,7 +189,8 @@ typedef enum {
     PURINE_OP_SUM = 11,            /* in: terms...        out: sum                               */
     PURINE_OP_HOST_NOP = 12,       /* any in/out; does nothing on the device (bookkeeping tests) */
     PURINE_OP_CONV_FWD_BIAS_RELU = 13, /* in: x, w, b     out: y   (attrs.relu selects the ReLU)    */
-    PURINE_OP_CONV_BWD_DATA_RELU = 14  /* in: dy, w, act [, dx]  out: dx'                           */
+    PURINE_OP_CONV_BWD_DATA_RELU = 14, /* in: dy, w, act [, dx]  out: dx'                           */
+    PURINE_OP_CONV_BWD_WEIGHT_BIAS = 15 /* in: x, dy [, dw, db]   out: dw', db'                      */
 } purine_op_kind;
 
 typedef struct {

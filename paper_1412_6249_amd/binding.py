@@ -16,12 +16,12 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG, "libpurine_conv.so")
 
 PURINE_F32, PURINE_BF16, PURINE_I32 = 0, 1, 2
-PURINE_CONV_FWD, PURINE_CONV_BWD_DATA, PURINE_CONV_BWD_WEIGHT = 0, 1, 2
+PURINE_CONV_FWD, PURINE_CONV_BWD_DATA, PURINE_CONV_BWD_WEIGHT, PURINE_CONV_BWD_WEIGHT_BIAS = 0, 1, 2, 3
 
 OP_CONV_FWD, OP_BIAS_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_BIAS_BWD = 0, 1, 2, 3, 4
 OP_RELU_FWD, OP_RELU_BWD, OP_MAXPOOL_FWD, OP_MAXPOOL_BWD = 5, 6, 7, 8
 OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
-OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU = 13, 14
+OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS = 13, 14, 15
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
@@ -74,6 +74,7 @@ _SIGS = {
     "purine_conv_fwd": (ctypes.c_int, [_D, _T, _T, _T, _vp, _sz, _vp]),
     "purine_conv_bwd_data": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_bwd_weight": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_conv_bwd_weight_bias": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_fwd_bias_relu": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_int, _vp, _sz, _vp]),
     "purine_conv_bwd_data_relu": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_bias_fwd": (ctypes.c_int, [_T, _T, _vp]),
@@ -256,6 +257,13 @@ def purine_conv_bwd_weight(desc, x, dy, dw, beta=0.0, ws=None, stream=None):
     _check(_lib.purine_conv_bwd_weight(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
                                        _ref(tensor_desc(dw)), float(beta), p, n, _stream(stream)),
            "purine_conv_bwd_weight")
+
+
+def purine_conv_bwd_weight_bias(desc, x, dy, dw, db, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_conv_bwd_weight_bias(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
+                                            _ref(tensor_desc(dw)), _ref(tensor_desc(db)), float(beta), p, n,
+                                            _stream(stream)), "purine_conv_bwd_weight_bias")
 
 
 def purine_bias_fwd(b, y, stream=None):

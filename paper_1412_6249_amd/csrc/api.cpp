@@ -140,11 +140,15 @@ int purine_conv_out_shape(const purine_conv_desc* desc, const int64_t x_dim[4],
 
 size_t purine_conv_workspace_bytes(int pass, const purine_conv_desc* desc, const int64_t x_dim[4],
                                    const int64_t w_dim[4], int32_t dtype) {
-    if (pass != PURINE_CONV_FWD && pass != PURINE_CONV_BWD_DATA && pass != PURINE_CONV_BWD_WEIGHT) return 0;
+    if (pass < PURINE_CONV_FWD || pass > PURINE_CONV_BWD_WEIGHT_BIAS) return 0;
     if (!desc || !x_dim || !w_dim || !is_float_dtype(dtype)) return 0;
     ConvGeom g;
     if (make_geom(desc, x_dim, w_dim, nullptr, &g) != PURINE_OK) return 0;
     if (pass == PURINE_CONV_BWD_WEIGHT) return plan_wgrad(g, dtype).ws_bytes;
+    if (pass == PURINE_CONV_BWD_WEIGHT_BIAS) {
+        const WgradPlan pl = plan_wgrad(g, dtype);
+        return wgrad_db_offset(pl) + pl.db_ws_bytes;
+    }
     return plan_conv_pix(g, pass == PURINE_CONV_BWD_DATA, dtype, false).ws_bytes;
 }
 
@@ -236,23 +240,43 @@ int purine_conv_bwd_data_relu(const purine_conv_desc* desc, const purine_tensor*
     return conv_bwd_data_impl(desc, dy, w, act, dx, beta, ws, ws_bytes, hip_stream);
 }
 
+namespace {
+// db == nullptr: ConvBwdWeight alone
+int conv_bwd_weight_impl(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* dy,
+                         purine_tensor* dw, purine_tensor* db, float beta, void* ws, size_t ws_bytes,
+                         void* hip_stream) {
+    int rc;
+    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(dy, 4)) ||
+        (rc = check_tensor(dw, 4)) || (db && (rc = check_tensor(db, 1))) || (rc = check_beta(beta)))
+        return rc;
+    if (!is_float_dtype(x->dtype) || dy->dtype != x->dtype || dw->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    if (db && db->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    ConvGeom g;
+    if ((rc = make_geom(desc, x->dim, dw->dim, dy->dim, &g))) return rc;
+    if (db && db->dim[0] != dy->dim[1]) return PURINE_E_SHAPE;
+    if (overlaps(dw, x) || overlaps(dw, dy)) return PURINE_E_LAYOUT;
+    if (db && (overlaps(db, x) || overlaps(db, dy) || overlaps(db, dw))) return PURINE_E_LAYOUT;
+    const WgradPlan plan = plan_wgrad(g, x->dtype);
+    const size_t need = db ? wgrad_db_offset(plan) + plan.db_ws_bytes : plan.ws_bytes;
+    if (!ws || ws_bytes < need) return PURINE_E_WORKSPACE;
+    if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+    hipError_t e = launch_conv_wgrad(x->dtype, g, plan, x->data, dy->data, (float*)dw->data,
+                                     db ? (float*)db->data : nullptr, beta, ws, (hipStream_t)hip_stream);
+    return hip_status(e);
+}
+}  // namespace
+
 int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
                            const purine_tensor* dy, purine_tensor* dw, float beta, void* ws,
                            size_t ws_bytes, void* hip_stream) {
-    int rc;
-    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(dy, 4)) ||
-        (rc = check_tensor(dw, 4)) || (rc = check_beta(beta)))
-        return rc;
-    if (!is_float_dtype(x->dtype) || dy->dtype != x->dtype || dw->dtype != PURINE_F32) return PURINE_E_DTYPE;
-    ConvGeom g;
-    if ((rc = make_geom(desc, x->dim, dw->dim, dy->dim, &g))) return rc;
-    if (overlaps(dw, x) || overlaps(dw, dy)) return PURINE_E_LAYOUT;
-    const WgradPlan plan = plan_wgrad(g, x->dtype);
-    if (!ws || ws_bytes < plan.ws_bytes) return PURINE_E_WORKSPACE;
-    if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
-    hipError_t e = launch_conv_wgrad(x->dtype, g, plan, x->data, dy->data, (float*)dw->data, beta, ws,
-                                     (hipStream_t)hip_stream);
-    return hip_status(e);
+    return conv_bwd_weight_impl(desc, x, dy, dw, nullptr, beta, ws, ws_bytes, hip_stream);
+}
+
+int purine_conv_bwd_weight_bias(const purine_conv_desc* desc, const purine_tensor* x,
+                                const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
+                                float beta, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!db) return PURINE_E_NULL;
+    return conv_bwd_weight_impl(desc, x, dy, dw, db, beta, ws, ws_bytes, hip_stream);
 }
 
 int purine_bias_fwd(const purine_tensor* b, purine_tensor* y, void* hip_stream) {

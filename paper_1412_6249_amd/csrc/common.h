@@ -49,6 +49,7 @@ struct WgradParams {
     int tiles_i, tiles_j, splits;
     int c_tiles;       // per-tap column mode: channel tiles per tap (tiles_j = R*S*c_tiles)
     unsigned x_bytes, dy_bytes;   // tensor sizes when the kernels may read them as raw buffers, else 0
+    float* db_out;     // fused bias gradient: partial sums [splits][K], or null
 };
 
 
@@ -83,9 +84,11 @@ struct WgradPlan {
     int c_tiles;
     int bm, bn;        // tile extents along k and along the columns
     int tiles_i, tiles_j, splits, chunk;
-    size_t ws_bytes;
+    size_t ws_bytes;      // weight-gradient partials
+    size_t db_ws_bytes;   // bias-gradient partials of the fused operator, placed behind them
 };
 WgradPlan plan_wgrad(const ConvGeom& g, int dtype);
+inline size_t wgrad_db_offset(const WgradPlan& pl) { return (pl.ws_bytes + 255) & ~(size_t)255; }
 
 struct BiasBwdPlan {
     int parts;         // image groups per channel
@@ -120,8 +123,9 @@ struct PixEpilogue {
 hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& plan, const void* in,
                            const void* wt, void* out, float beta, void* ws, const PixEpilogue& epi,
                            hipStream_t st);
+// db != null: also db = beta*db + sum of dy over pixels (fused BiasBwd), scratch behind dw's partials
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
-                             const void* dy, float* dw, float beta, void* ws, hipStream_t st);
+                             const void* dy, float* dw, float* db, float beta, void* ws, hipStream_t st);
 hipError_t launch_bias_fwd(int dtype, const void* b, void* y, int N, int K, int PQ, hipStream_t st);
 hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int N, int K, int PQ,
                            const BiasBwdPlan& plan, void* ws, hipStream_t st);

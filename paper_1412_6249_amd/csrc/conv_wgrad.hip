@@ -221,6 +221,13 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+    // Fused bias gradient: the dy fragments that feed the MFMAs are also summed per lane (one add per
+    // fragment; masked pixels and rows are zeros in LDS). Only the wavefronts that hold the first
+    // column block of the first column tile write their sums, so every (split, k) is written once.
+    float dbacc[TM];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) dbacc[a] = 0.0f;
+    const bool do_db = p.db_out != nullptr && j0 == 0 && tw.tap == 0 && wn == 0;
 
     const int n_slabs = (pix_end - pix_begin + BK - 1) / BK;   // >= 0; zero slabs leave zeros
     if (n_slabs > 0) {
@@ -257,6 +264,8 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][a], bv[cur][b], acc[a][b], 0, 0, 0);
+#pragma unroll
+            for (int a = 0; a < TM; ++a) dbacc[a] += av[cur][a];
         }
         __builtin_amdgcn_sched_barrier(0);   // keep the LDS stores (and their load waits) below the MFMAs
         store_slab(buf ^ 1);
@@ -278,6 +287,23 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
                 if (i < p.K) out[(size_t)i * ncol + j] = acc[a][b][e];
             }
     }
+    if (do_db) {   // wavefront-uniform: lanes l and l+32 hold the even and odd pixels of row l
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const float tot = dbacc[a] + __shfl_xor(dbacc[a], 32);
+            const int i = i0 + wm * TM * 32 + a * 32 + (lane & 31);
+            if (khalf == 0 && i < p.K) p.db_out[(size_t)tw.split * p.K + i] = tot;
+        }
+    }
+}
+
+// sum of the eight bf16 values of an MFMA operand fragment, in a fixed order
+__device__ __forceinline__ float sum8(const uint4 u) {
+    const float s0 = __uint_as_float(u.x << 16) + __uint_as_float(u.x & 0xffff0000u);
+    const float s1 = __uint_as_float(u.y << 16) + __uint_as_float(u.y & 0xffff0000u);
+    const float s2 = __uint_as_float(u.z << 16) + __uint_as_float(u.z & 0xffff0000u);
+    const float s3 = __uint_as_float(u.w << 16) + __uint_as_float(u.w & 0xffff0000u);
+    return (s0 + s1) + (s2 + s3);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -462,6 +488,12 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+    // fused bias gradient as in the fp32 kernel; here summing a fragment costs 16 VALU operations, so
+    // only the wavefronts that write the sums (do_db is uniform over a wavefront) take it
+    float dbacc[TM];
+#pragma unroll
+    for (int a = 0; a < TM; ++a) dbacc[a] = 0.0f;
+    const bool do_db = p.db_out != nullptr && j0 == 0 && tw.tap == 0 && wn == 0;
 
     const int n_slabs = (pix_end - pix_begin + BKP - 1) / BKP;
     if (n_slabs > 0) {
@@ -491,6 +523,10 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
+            if (do_db) {
+#pragma unroll
+                for (int a = 0; a < TM; ++a) dbacc[a] += sum8(__builtin_bit_cast(uint4, av[a]));
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         store_slab(buf ^ 1);
@@ -511,6 +547,14 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
                 const int i = i0 + wm * TM * 32 + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
                 if (i < p.K) out[(size_t)i * ncol + j] = acc[a][b][e];
             }
+    }
+    if (do_db) {   // lanes l and l+32 hold the two 8-pixel halves of row l's 16-pixel steps
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+            const float tot = dbacc[a] + __shfl_xor(dbacc[a], 32);
+            const int i = i0 + wm * TM * 32 + a * 32 + (lane & 31);
+            if (khalf == 0 && i < p.K) p.db_out[(size_t)split * p.K + i] = tot;
+        }
     }
 }
 
@@ -547,13 +591,21 @@ hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) 
 // 16 consecutive elements; each of its 16 "split lanes" adds the partials s = lane, lane+16, ... in
 // order (independent loads, so many are in flight), and the 16 lane sums are then added in lane
 // order through LDS. The order never depends on timing, so the result is bit-identical run to run.
+// Workgroups past dw_blocks do the same for the fused bias gradient: partials [split][K] into db[K].
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restrict__ partial,
                                                            float* __restrict__ dw, int n,
                                                            int splits, float beta, int tap_major,
-                                                           int K, int C, int RS) {
+                                                           int K, int C, int RS, int dw_blocks,
+                                                           const float* __restrict__ db_partial,
+                                                           float* __restrict__ db) {
     __shared__ float red[16][17];
     const int e = threadIdx.x & 15, sl = threadIdx.x >> 4;
-    const int i = blockIdx.x * 16 + e;      // index in the partials' own order (coalesced reads)
+    int blk = blockIdx.x;
+    if (blk >= dw_blocks) {   // uniform over the workgroup
+        blk -= dw_blocks;
+        partial = db_partial; dw = db; n = K; tap_major = 0;
+    }
+    const int i = blk * 16 + e;      // index in the partials' own order (coalesced reads)
     float acc = 0.0f;
     if (i < n) {
         int s = sl;
@@ -578,6 +630,62 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
         float t = beta != 0.0f ? dw[dst] : 0.0f;
 #pragma unroll
         for (int l = 0; l < 16; ++l) t += red[l][e];
+        dw[dst] = t;
+    }
+}
+
+// The same reduction for n a multiple of 4 (rows of the partials 16-byte aligned): a workgroup owns
+// 32 consecutive elements (one 128-byte line per split, so no line is fetched by two workgroups on
+// different L2s), 8 lanes x 16 bytes wide, and 32 split lanes deep; the 32 lane sums are added in
+// lane order. Also a fixed order; `vec4` is a property of the layer, so a layer always takes the
+// same one of the two kernels.
+__global__ __launch_bounds__(256) void wgrad_reduce_vec_kernel(const float* __restrict__ partial,
+                                                               float* __restrict__ dw, int n,
+                                                               int splits, float beta, int tap_major,
+                                                               int K, int C, int RS, int dw_blocks,
+                                                               const float* __restrict__ db_partial,
+                                                               float* __restrict__ db) {
+    __shared__ float red[32][33];
+    const int e4 = threadIdx.x & 7, sl = threadIdx.x >> 3;
+    int blk = blockIdx.x;
+    if (blk >= dw_blocks) {   // uniform over the workgroup: the fused bias gradient's partials
+        blk -= dw_blocks;
+        partial = db_partial; dw = db; n = K; tap_major = 0;
+    }
+    const int i = blk * 32 + e4 * 4;
+    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (i < n) {   // n and i are multiples of 4: the whole packet exists
+        int s = sl;
+        for (; s + 96 < splits; s += 128) {
+            const float4 v0 = *reinterpret_cast<const float4*>(partial + (size_t)s * n + i);
+            const float4 v1 = *reinterpret_cast<const float4*>(partial + (size_t)(s + 32) * n + i);
+            const float4 v2 = *reinterpret_cast<const float4*>(partial + (size_t)(s + 64) * n + i);
+            const float4 v3 = *reinterpret_cast<const float4*>(partial + (size_t)(s + 96) * n + i);
+            acc.x += v0.x; acc.y += v0.y; acc.z += v0.z; acc.w += v0.w;
+            acc.x += v1.x; acc.y += v1.y; acc.z += v1.z; acc.w += v1.w;
+            acc.x += v2.x; acc.y += v2.y; acc.z += v2.z; acc.w += v2.w;
+            acc.x += v3.x; acc.y += v3.y; acc.z += v3.z; acc.w += v3.w;
+        }
+        for (; s < splits; s += 32) {
+            const float4 v = *reinterpret_cast<const float4*>(partial + (size_t)s * n + i);
+            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+        }
+    }
+    red[sl][e4 * 4 + 0] = acc.x; red[sl][e4 * 4 + 1] = acc.y;
+    red[sl][e4 * 4 + 2] = acc.z; red[sl][e4 * 4 + 3] = acc.w;
+    __syncthreads();
+    const int e = threadIdx.x;
+    const int j = blk * 32 + e;
+    if (e < 32 && j < n) {
+        int dst = j;
+        if (tap_major) {   // partials are [tap][k][c]; dw is [k][c][tap]
+            const int tap = j / (K * C);
+            const int kc = j - tap * (K * C);
+            dst = kc * RS + tap;
+        }
+        float t = beta != 0.0f ? dw[dst] : 0.0f;
+#pragma unroll
+        for (int l = 0; l < 32; ++l) t += red[l][e];
         dw[dst] = t;
     }
 }
@@ -672,13 +780,16 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     pl.splits = (int)splits;
     pl.chunk = (int)chunk;
     pl.ws_bytes = (size_t)splits * (size_t)g.K * (size_t)CRS * sizeof(float);
+    pl.db_ws_bytes = (size_t)splits * (size_t)g.K * sizeof(float);
     return pl;
 }
 
 hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan, const void* x,
-                             const void* dy, float* dw, float beta, void* ws, hipStream_t st) {
+                             const void* dy, float* dw, float* db, float beta, void* ws, hipStream_t st) {
     WgradParams p{};
     p.x = x; p.dy = dy;
+    // bias-gradient partials [split][K] sit behind the weight-gradient partials
+    p.db_out = db ? (float*)((char*)ws + wgrad_db_offset(plan)) : nullptr;
     p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W; p.K = g.K; p.P = g.P; p.Q = g.Q;
     p.R = g.R; p.S = g.S; p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
     p.PQ = g.P * g.Q; p.M = g.N * p.PQ; p.RS = g.R * g.S; p.CRS = g.C * p.RS; p.HW = g.H * g.W;
@@ -702,8 +813,19 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     else e = vec ? dispatch_bf16<true, false>(p, plan, st) : dispatch_bf16<false, false>(p, plan, st);
     if (e != hipSuccess) return e;
     const int n = g.K * p.CRS;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((n + 15) / 16), dim3(256), 0, st,
-                       (const float*)ws, dw, n, plan.splits, beta, plan.tap ? 1 : 0, g.K, g.C, p.RS);
+    // 16-byte packets need aligned rows in both sets of partials (the scratch itself is aligned)
+    const bool vec4 = n % 4 == 0 && (!db || g.K % 4 == 0);
+    if (vec4) {
+        const int dw_blocks = (n + 31) / 32, db_blocks = db ? (g.K + 31) / 32 : 0;
+        hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, st,
+                           (const float*)ws, dw, n, plan.splits, beta, plan.tap ? 1 : 0, g.K, g.C, p.RS,
+                           dw_blocks, (const float*)p.db_out, db);
+        return hipGetLastError();
+    }
+    const int dw_blocks = (n + 15) / 16, db_blocks = db ? (g.K + 15) / 16 : 0;
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, st,
+                       (const float*)ws, dw, n, plan.splits, beta, plan.tap ? 1 : 0, g.K, g.C, p.RS,
+                       dw_blocks, (const float*)p.db_out, db);
     return hipGetLastError();
 }
 

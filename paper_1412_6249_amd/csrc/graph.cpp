@@ -78,6 +78,7 @@ bool arity_ok(int kind, int n_in, int n_out, float beta) {
         case PURINE_OP_HOST_NOP: return n_in >= 0 && n_out >= 0;
         case PURINE_OP_CONV_FWD_BIAS_RELU: return n_in == 3 && n_out == 1;
         case PURINE_OP_CONV_BWD_DATA_RELU: return n_in == 3 + extra && n_out == 1;
+        case PURINE_OP_CONV_BWD_WEIGHT_BIAS: return n_in == 2 + 2 * extra && n_out == 2;
         default: return false;
     }
 }
@@ -115,6 +116,11 @@ int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
         case PURINE_OP_CONV_BWD_WEIGHT:
             if (a.beta != 0.0f && T(op.in[2])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
             return purine_conv_bwd_weight(&a.conv, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_CONV_BWD_WEIGHT_BIAS:
+            if (a.beta != 0.0f && (T(op.in[2])->data != T(op.out[0])->data || T(op.in[3])->data != T(op.out[1])->data))
+                return PURINE_E_LAYOUT;
+            return purine_conv_bwd_weight_bias(&a.conv, T(op.in[0]), T(op.in[1]), T(op.out[0]), T(op.out[1]),
+                                               a.beta, a.ws, a.ws_bytes, st);
         case PURINE_OP_BIAS_BWD:
             if (a.beta != 0.0f && T(op.in[1])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
             return purine_bias_bwd(T(op.in[0]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);

@@ -124,12 +124,18 @@ class GraphBuilder:
             self.op(B.OP_RELU_BWD, [rec["out"], dout], [dy], thread)
             rec["relu_bwd_op"] = True
         db = self.new(p + ".db", (L.K,), "f32")
-        self.op(B.OP_BIAS_BWD, [dy], [db], t_b,
-                B.op_attrs(ws=self.workspace(B.purine_bias_bwd_workspace_bytes(L.y_shape, _pcode(L.dtype)))))
         dw = self.new(p + ".dw", L.w_shape, "f32")
-        ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT, desc, L.x_shape,
-                                                          L.w_shape, _pcode(L.dtype)))
-        self.op(B.OP_CONV_BWD_WEIGHT, [rec["x"], dy], [dw], t_w, B.op_attrs(conv=desc, ws=ws))
+        if self.fuse:
+            # both gradients of the layer's parameters from one pass over dy
+            ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT_BIAS, desc, L.x_shape,
+                                                              L.w_shape, _pcode(L.dtype)))
+            self.op(B.OP_CONV_BWD_WEIGHT_BIAS, [rec["x"], dy], [dw, db], t_w, B.op_attrs(conv=desc, ws=ws))
+        else:
+            self.op(B.OP_BIAS_BWD, [dy], [db], t_b,
+                    B.op_attrs(ws=self.workspace(B.purine_bias_bwd_workspace_bytes(L.y_shape, _pcode(L.dtype)))))
+            ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT, desc, L.x_shape,
+                                                              L.w_shape, _pcode(L.dtype)))
+            self.op(B.OP_CONV_BWD_WEIGHT, [rec["x"], dy], [dw], t_w, B.op_attrs(conv=desc, ws=ws))
         dx = None
         if need_dx:
             dx = self.new(p + ".dx", L.x_shape, L.dtype)

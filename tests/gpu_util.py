@@ -48,9 +48,10 @@ def workspace(nbytes):
     return torch.empty(max(256, int(nbytes)), dtype=torch.uint8, device=DEV)
 
 
-def run_layer(x, w, b, dy, stride, pad, dtype="f32", beta=0.0, prev=None):
+def run_layer(x, w, b, dy, stride, pad, dtype="f32", beta=0.0, prev=None, fused_wb=False):
     """One conv layer through the five operators. Inputs are numpy fp32 (bf16-valued if dtype is
-    bf16). Returns y (with bias), dx, dw, db as numpy arrays."""
+    bf16). Returns y (with bias), dx, dw, db as numpy arrays. fused_wb: dw and db come from the
+    single ConvBwdWeight+BiasBwd operator instead of the two separate ones."""
     desc = pa.conv_desc(stride, pad)
     tx, tw, tb, tdy = to_dev(x, dtype), to_dev(w, dtype), to_dev(b, dtype), to_dev(dy, dtype)
     ys = pa.purine_conv_out_shape(desc, x.shape, w.shape)
@@ -71,7 +72,12 @@ def run_layer(x, w, b, dy, stride, pad, dtype="f32", beta=0.0, prev=None):
     pa.purine_conv_fwd(desc, tx, tw, ty, ws=wsf)
     pa.purine_bias_fwd(tb, ty)
     pa.purine_conv_bwd_data(desc, tdy, tw, tdx, beta=beta, ws=wsd)
-    pa.purine_conv_bwd_weight(desc, tx, tdy, tdw, beta=beta, ws=ws)
-    pa.purine_bias_bwd(tdy, tdb, beta=beta, ws=ws2)
+    if fused_wb:
+        wsb = workspace(pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT_BIAS, desc, x.shape, w.shape,
+                                                       pcode(dtype)))
+        pa.purine_conv_bwd_weight_bias(desc, tx, tdy, tdw, tdb, beta=beta, ws=wsb)
+    else:
+        pa.purine_conv_bwd_weight(desc, tx, tdy, tdw, beta=beta, ws=ws)
+        pa.purine_bias_bwd(tdy, tdb, beta=beta, ws=ws2)
     torch.cuda.synchronize()
     return to_host(ty), to_host(tdx), to_host(tdw), to_host(tdb)

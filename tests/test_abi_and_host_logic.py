@@ -24,7 +24,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = declared_symbols()
-    assert len(names) == 36
+    assert len(names) == 37
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -118,6 +118,9 @@ def test_workspace_queries():
             dw_bytes = 4 * int(np.prod(l.w_shape))
             assert nbytes >= dw_bytes and nbytes % dw_bytes == 0      # whole partial copies of dw
             assert nbytes <= 1 << 30
+            both = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT_BIAS, d, l.x_shape, l.w_shape, dt)
+            splits = nbytes // dw_bytes
+            assert nbytes + 4 * splits * l.K <= both <= nbytes + 4 * splits * l.K + 256   # + bias partials
             assert 0 < pa.purine_bias_bwd_workspace_bytes(l.y_shape, dt) <= 4 * l.K * l.N
     # illegal shapes give 0 (the operator call reports the error)
     assert pa.purine_conv_workspace_bytes(2, pa.conv_desc(1, 0), (1, 3, 2, 2), (4, 3, 3, 3), 0) == 0
@@ -151,6 +154,10 @@ def test_operator_argument_validation_without_launch():
     dw = binding.raw_desc(fake + 0x300000, F32, (4, 3, 3, 3))
     assert status(pa.purine_conv_bwd_weight, d, x, y, dw, stream=s) == -5            # no workspace
     assert status(pa.purine_conv_bwd_weight, d, x, y, binding.raw_desc(fake + 0x300000, BF16, (4, 3, 3, 3)), stream=s) == -3
+    db4 = binding.raw_desc(fake + 0x400000, F32, (4,))
+    assert status(pa.purine_conv_bwd_weight_bias, d, x, y, dw, db4, stream=s) == -5     # no workspace
+    assert status(pa.purine_conv_bwd_weight_bias, d, x, y, dw, binding.raw_desc(fake + 0x400000, F32, (5,)), stream=s) == -2
+    assert status(pa.purine_conv_bwd_weight_bias, d, x, y, dw, binding.raw_desc(fake + 0x300000, F32, (4,)), stream=s) == -4  # db aliases dw
     b = binding.raw_desc(fake + 0x400000, F32, (5,))
     assert status(pa.purine_bias_fwd, b, y, stream=s) == -2                          # K mismatch
     db = binding.raw_desc(fake + 0x400000, F32, (4,))

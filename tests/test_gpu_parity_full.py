@@ -4,7 +4,8 @@ configuration bench.py times, on outputs the oracle can compute one by one:
     per image, so an image of the batch is an exact sub-problem);
   - backward-weight: sampled elements of dw, each summed by the oracle over the whole batch;
   - bias gradient: all of it.
-The fused operators bench.py's graphs use (Conv+Bias+ReLU, ConvBwdData through a ReLU mask) are
+The fused operators bench.py's graphs use (Conv+Bias+ReLU, ConvBwdData through a ReLU mask,
+ConvBwdWeight+BiasBwd) are
 checked on the same samples. A second test feeds small-integer tensors at full shape, where every
 partial sum is an exact integer below 2^24, so the sampled outputs must match bit for bit whatever
 the summation order (index and shape bookkeeping at the real sizes).
@@ -82,6 +83,12 @@ def test_full_shape_layer(cfg, idx):
     assert rel_l2(got_dw, ref_dw) <= tol, ("bwd_weight", rel_l2(got_dw, ref_dw))
     ref_db = oracle.bias_bwd(hdy)
     assert rel_l2(db.cpu().numpy(), ref_db) <= tol, ("bias_bwd", rel_l2(db.cpu().numpy(), ref_db))
+    # the two parameter gradients from the single fused operator
+    dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+    pa.purine_conv_bwd_weight_bias(desc, x, dy, dw2, db2, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))
+    torch.cuda.synchronize()
+    assert torch.equal(dw2, dw), "fused bwd_weight"
+    assert rel_l2(db2.cpu().numpy(), ref_db) <= tol, ("fused bias_bwd", rel_l2(db2.cpu().numpy(), ref_db))
 
 
 INT_CASES = [(2, 0), (2, 1), (3, 4), (4, 2), (5, 0), (5, 2)]
@@ -136,3 +143,7 @@ def test_full_shape_integer_inputs_bit_exact(cfg, idx):
     assert np.abs(ref_dw).max() < 2 ** 24
     assert np.array_equal(dw.cpu().numpy().ravel()[flat], ref_dw.astype(np.float32)), "bwd_weight"
     assert np.array_equal(db.cpu().numpy(), oracle.bias_bwd(hdy).astype(np.float32)), "bias_bwd"
+    dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
+    pa.purine_conv_bwd_weight_bias(desc, x, dy, dw2, db2, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))
+    torch.cuda.synchronize()
+    assert torch.equal(dw2, dw) and torch.equal(db2, db), "fused bwd_weight + bias_bwd"

@@ -80,6 +80,32 @@ def test_layer_parity(case, dtype):
         assert rel_l2(g, r) <= TOL[dtype], (case[0], name, rel_l2(g, r))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", CASES, ids=[c[0] for c in CASES])
+def test_fused_weight_and_bias_gradient(case, dtype):
+    """ConvBwdWeight+BiasBwd as one operator: db against the oracle, on random and on
+    small-integer inputs (exact), and dw bit-identical to the separate operator's (the bias sums
+    ride along the same kernel). Also with beta = 1."""
+    from gpu_util import run_layer, rel_l2, TOL
+    x, w, b, dy, stride, pad = make(case, dtype)
+    _, _, dw0, _ = run_layer(x, w, b, dy, stride, pad, dtype)
+    _, _, dw, db = run_layer(x, w, b, dy, stride, pad, dtype, fused_wb=True)
+    assert np.array_equal(dw, dw0)
+    assert np.isfinite(db).all()
+    assert rel_l2(db, oracle.bias_bwd(dy)) <= TOL[dtype], rel_l2(db, oracle.bias_bwd(dy))
+    xi, wi, bi, dyi, _, _ = make(case, dtype, integer=True)
+    _, _, dwi, dbi = run_layer(xi, wi, bi, dyi, stride, pad, dtype, fused_wb=True)
+    assert np.array_equal(dbi, oracle.bias_bwd(dyi).astype(np.float32))
+    assert np.array_equal(dwi, oracle.conv_bwd_weight(xi, dyi, wi.shape, stride, pad).astype(np.float32))
+    rs = np.random.default_rng(11)
+    prev = [rs.uniform(-1, 1, s).astype(np.float32) for s in (x.shape, w.shape, b.shape)]
+    if dtype == "bf16":
+        prev[0] = gen.quantize_bf16(prev[0])
+    _, _, dw1, db1 = run_layer(x, w, b, dy, stride, pad, dtype, beta=1.0, prev=prev, fused_wb=True)
+    assert rel_l2(db1, oracle.bias_bwd(dy) + prev[2]) <= TOL[dtype]
+    assert rel_l2(dw1, oracle.conv_bwd_weight(x, dy, w.shape, stride, pad) + prev[1]) <= TOL[dtype]
+
+
 def test_config1_all_operators():
     from gpu_util import run_layer, rel_l2
     l = CONV_LAYERS[1][0]
