@@ -216,6 +216,23 @@ def main():
                                                 "value": round(flop2 / (ms2 * 1e-3) / 1e12, 3)}}
         gb = gb2
 
+    # third figure: whole training iterations (paper section 2.2): the step above plus one SGD update
+    # operator per parameter tensor and the swap of old and new parameters, iterated natively
+    gb.close()
+    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused,
+                        first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6)
+    gb.iterate(max(2, args.warmup))
+    torch.cuda.synchronize()
+    s0 = time.perf_counter()
+    n3 = max(6, args.steps // 2) // 2 * 2
+    gb.iterate(n3)
+    torch.cuda.synchronize()
+    ms3 = (time.perf_counter() - s0) * 1e3 / n3
+    flop3 = flop - (CONV_LAYERS[cfg][0].flop_per_pass if cfg in (2, 4) else 0)
+    secondary = dict(secondary or {})
+    secondary["sgd_iterations"] = {"ms_per_iteration": round(ms3, 4), "value": round(flop3 / (ms3 * 1e-3) / 1e12, 3),
+                                   "first_layer_dx": cfg not in (2, 4)}
+
     result = {
         "metric": "conv fwd+bwd TFLOP/s on one MI355X",
         "value": round(flop / (ms_per_step * 1e-3) / 1e12, 3),

@@ -170,6 +170,15 @@ int purine_concat_bwd(const purine_tensor* dout, purine_tensor* const* dparts, i
 int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* out,
                void* hip_stream);
 
+/* SGD step on one parameter tensor (paper section 2.2, Figure 3(a): the network graph leaves the
+ * updated parameters in a separate "new params" tensor so that the graph stays acyclic):
+ * new_w = w - lr * dw, element by element, one fused multiply-add in fp32 (bf16 parameters are
+ * widened, updated, and rounded to nearest even). w and new_w: same dtype (F32 or BF16) and
+ * extents, 1 to 4 axes; dw: F32, same extents. new_w may be w itself (update in place) but may
+ * not overlap it partially, nor dw. */
+int purine_sgd_update(const purine_tensor* w, const purine_tensor* dw, purine_tensor* new_w,
+                      float lr, void* hip_stream);
+
 /* ---- bi-graph executor (paper sections 2, 2.1, 2.2 and the `thread` property of section 3) -- */
 
 typedef struct purine_graph purine_graph;
@@ -190,7 +199,8 @@ typedef enum {
     PURINE_OP_HOST_NOP = 12,       /* any in/out; does nothing on the device (bookkeeping tests) */
     PURINE_OP_CONV_FWD_BIAS_RELU = 13, /* in: x, w, b     out: y   (attrs.relu selects the ReLU)    */
     PURINE_OP_CONV_BWD_DATA_RELU = 14, /* in: dy, w, act [, dx]  out: dx'                           */
-    PURINE_OP_CONV_BWD_WEIGHT_BIAS = 15 /* in: x, dy [, dw, db]   out: dw', db'                      */
+    PURINE_OP_CONV_BWD_WEIGHT_BIAS = 15, /* in: x, dy [, dw, db]  out: dw', db'                      */
+    PURINE_OP_SGD_UPDATE = 16          /* in: w, dw           out: new_w   (attrs.lr)                */
 } purine_op_kind;
 
 typedef struct {
@@ -200,6 +210,7 @@ typedef struct {
     int32_t relu;            /* PURINE_OP_CONV_FWD_BIAS_RELU: apply max(y, 0)     */
     void*  ws;               /* device scratch private to this operator           */
     size_t ws_bytes;
+    float  lr;               /* PURINE_OP_SGD_UPDATE: step size                   */
 } purine_op_attrs;
 
 /* The graph owns only host bookkeeping plus the HIP streams and events it creates lazily (none for
@@ -236,6 +247,23 @@ int purine_graph_validate(purine_graph* g);
  * must have completed before the call. A graph that cannot reach its sinks returns
  * PURINE_E_GRAPH instead of hanging. The first operator error aborts the run and is returned. */
 int purine_graph_run(purine_graph* g);
+
+/* The swap step of graph iteration (section 2.2, Figure 3(b)): exchanges the storage addresses of
+ * two tensor vertices with the same dtype and extents ("old" and "new" parameters), so that the
+ * next run of the graph reads what the last run wrote. Every vertex bound to either address moves
+ * with it. PURINE_E_SHAPE when the two differ in dtype or extents; PURINE_E_LAYOUT when the two
+ * ranges overlap, or some other vertex or operator scratch overlaps one of them without covering
+ * exactly the same bytes (the exchange would then change which operators conflict). Host only;
+ * call between runs. */
+int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b);
+/* Storage address a tensor vertex is bound to at the moment (NULL for a bad id). */
+void* purine_graph_tensor_data(const purine_graph* g, int tensor_id);
+
+/* Graph iteration (section 2.2, Figure 3(c)): n_iters times { purine_graph_run; then
+ * purine_graph_swap_storage(swap_a[i], swap_b[i]) for i < n_swaps }. The end of each run is the
+ * synchronisation point between iterations. Stops at the first error and returns it. */
+int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const int* swap_b,
+                         int n_swaps);
 
 /* Firing order of the last run: writes up to cap operator ids, returns how many operators fired. */
 int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap);

@@ -21,7 +21,7 @@ PURINE_CONV_FWD, PURINE_CONV_BWD_DATA, PURINE_CONV_BWD_WEIGHT, PURINE_CONV_BWD_W
 OP_CONV_FWD, OP_BIAS_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_BIAS_BWD = 0, 1, 2, 3, 4
 OP_RELU_FWD, OP_RELU_BWD, OP_MAXPOOL_FWD, OP_MAXPOOL_BWD = 5, 6, 7, 8
 OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
-OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS = 13, 14, 15
+OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS, OP_SGD_UPDATE = 13, 14, 15, 16
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
@@ -53,7 +53,8 @@ class purine_pool_desc(ctypes.Structure):
 
 class purine_op_attrs(ctypes.Structure):
     _fields_ = [("conv", purine_conv_desc), ("pool", purine_pool_desc), ("beta", ctypes.c_float),
-                ("relu", ctypes.c_int32), ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t)]
+                ("relu", ctypes.c_int32), ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t),
+                ("lr", ctypes.c_float)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -94,6 +95,10 @@ _SIGS = {
     "purine_graph_set_stream": (ctypes.c_int, [_vp, ctypes.c_int, _vp]),
     "purine_graph_validate": (ctypes.c_int, [_vp]),
     "purine_graph_run": (ctypes.c_int, [_vp]),
+    "purine_graph_swap_storage": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int]),
+    "purine_graph_tensor_data": (_vp, [_vp, ctypes.c_int]),
+    "purine_graph_iterate": (ctypes.c_int, [_vp, ctypes.c_int, _ip, _ip, ctypes.c_int]),
+    "purine_sgd_update": (ctypes.c_int, [_T, _T, _T, ctypes.c_float, _vp]),
     "purine_graph_fire_log": (ctypes.c_int, [_vp, _ip, ctypes.c_int]),
     "purine_graph_num_ops": (ctypes.c_int, [_vp]),
     "purine_graph_num_tensors": (ctypes.c_int, [_vp]),
@@ -266,6 +271,11 @@ def purine_conv_bwd_weight_bias(desc, x, dy, dw, db, beta=0.0, ws=None, stream=N
                                             _stream(stream)), "purine_conv_bwd_weight_bias")
 
 
+def purine_sgd_update(w, dw, new_w, lr, stream=None):
+    _check(_lib.purine_sgd_update(_ref(tensor_desc(w)), _ref(tensor_desc(dw)), _ref(tensor_desc(new_w)),
+                                  float(lr), _stream(stream)), "purine_sgd_update")
+
+
 def purine_bias_fwd(b, y, stream=None):
     _check(_lib.purine_bias_fwd(_ref(tensor_desc(b)), _ref(tensor_desc(y)), _stream(stream)),
            "purine_bias_fwd")
@@ -350,9 +360,10 @@ def purine_graph_add_op(g, kind, in_ids, out_ids, thread_id=0, attrs=None):
     return rc
 
 
-def op_attrs(conv=None, pool=None, beta=0.0, ws=None, relu=False):
+def op_attrs(conv=None, pool=None, beta=0.0, ws=None, relu=False, lr=0.0):
     a = purine_op_attrs()
     a.relu = 1 if relu else 0
+    a.lr = float(lr)
     if conv is not None:
         a.conv = conv
     if pool is not None:
@@ -375,6 +386,22 @@ def purine_graph_validate(g):
 
 def purine_graph_run(g):
     _check(_lib.purine_graph_run(g), "purine_graph_run")
+
+
+def purine_graph_swap_storage(g, tensor_a, tensor_b):
+    _check(_lib.purine_graph_swap_storage(g, int(tensor_a), int(tensor_b)), "purine_graph_swap_storage")
+
+
+def purine_graph_tensor_data(g, tensor_id):
+    return int(_lib.purine_graph_tensor_data(g, int(tensor_id)) or 0)
+
+
+def purine_graph_iterate(g, n_iters, swaps=()):
+    """swaps: pairs of tensor ids whose storage addresses are exchanged after every run."""
+    n = len(swaps)
+    a = (ctypes.c_int * max(1, n))(*[int(s[0]) for s in swaps])
+    b = (ctypes.c_int * max(1, n))(*[int(s[1]) for s in swaps])
+    _check(_lib.purine_graph_iterate(g, int(n_iters), a, b, n), "purine_graph_iterate")
 
 
 def purine_graph_fire_log(g):

@@ -335,6 +335,23 @@ int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tens
     return hip_status(e);
 }
 
+int purine_sgd_update(const purine_tensor* w, const purine_tensor* dw, purine_tensor* new_w,
+                      float lr, void* hip_stream) {
+    int rc;
+    if (!w || !dw || !new_w) return PURINE_E_NULL;
+    if ((rc = check_tensor(w, w->ndim >= 1 && w->ndim <= 4 ? w->ndim : -1)) ||
+        (rc = check_tensor(dw, w->ndim)) || (rc = check_tensor(new_w, w->ndim)))
+        return rc;
+    if (!is_float_dtype(w->dtype) || new_w->dtype != w->dtype || dw->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    if (!same_dims(w, dw) || !same_dims(w, new_w)) return PURINE_E_SHAPE;
+    if (!(lr == lr) || lr - lr != 0.0f) return PURINE_E_ARG;   // NaN or infinite step
+    if (new_w->data != w->data && overlaps(new_w, w)) return PURINE_E_LAYOUT;
+    if (overlaps(new_w, dw)) return PURINE_E_LAYOUT;
+    hipError_t e = launch_sgd_update(w->dtype, w->data, (const float*)dw->data, new_w->data, lr, numel(w),
+                                     (hipStream_t)hip_stream);
+    return hip_status(e);
+}
+
 static int pool_geom(const purine_pool_desc* d, const purine_tensor* x, const purine_tensor* y) {
     if (!d) return PURINE_E_NULL;
     if (d->window < 1 || d->stride < 1 || d->pad < 0 || d->pad >= d->window) return PURINE_E_ARG;

@@ -132,6 +132,8 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
 hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st);
 hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
                            hipStream_t st);
+hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* new_w, float lr,
+                             int64_t n, hipStream_t st);
 hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,
                               int P, int Q, int k, int stride, int pad, hipStream_t st);
 hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, float beta,

@@ -24,10 +24,11 @@ template <> __device__ __forceinline__ float ld<uint16_t>(const uint16_t* p, int
     return __uint_as_float(((uint32_t)p[i]) << 16);
 }
 
-// tile extents -> (TM, TN, WM, WN)
-#define WGRAD_TILE_SWITCH(CALL)                                                  \
+// tile extents -> (TM, TN, WM, WN); CALL3 serves the one tile of three wavefronts (fp32 only)
+#define WGRAD_TILE_SWITCH(CALL, CALL3)                                           \
     switch (plan.bm * 1000 + plan.bn) {                                          \
         case 128128: return CALL(2, 2, 2, 2);                                    \
+        case 96096:  return CALL3(3, 1, 1, 3);                                   \
         case 128096: return CALL(1, 3, 4, 1);                                    \
         case 192064: return CALL(3, 1, 2, 2);                                    \
         case 128064: return CALL(1, 2, 4, 1);                                    \
@@ -572,7 +573,9 @@ hipError_t launch_tile_bf16(WgradParams& p, hipStream_t st) {
 template <bool VEC_A, bool TAP, bool NOPAD, bool BUF>
 hipError_t dispatch_bf16_mode(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
 #define CALL(TM, TN, WM, WN) launch_tile_bf16<VEC_A, TAP, NOPAD, BUF, TM, TN, WM, WN>(p, st)
-    WGRAD_TILE_SWITCH(CALL)
+#define CALL3(TM, TN, WM, WN) hipErrorInvalidValue   // the plan gives bf16 layers no such tile
+    WGRAD_TILE_SWITCH(CALL, CALL3)
+#undef CALL3
 #undef CALL
 }
 template <bool VEC_A, bool TAP>
@@ -704,7 +707,7 @@ hipError_t launch_tile(WgradParams& p, hipStream_t st) {
 template <bool TAP, bool NOPAD, bool BUF>
 hipError_t dispatch_f32_mode(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
 #define CALL(TM, TN, WM, WN) launch_tile<float, TAP, NOPAD, BUF, TM, TN, WM, WN>(p, st)
-    WGRAD_TILE_SWITCH(CALL)
+    WGRAD_TILE_SWITCH(CALL, CALL)
 #undef CALL
 }
 template <bool TAP>
@@ -720,16 +723,17 @@ hipError_t dispatch_f32(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
 }  // namespace
 
 WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
-    (void)dtype;
     WgradPlan pl{};
     const long long M = (long long)g.N * g.P * g.Q;
     const long long CRS = (long long)g.C * g.R * g.S;
     pl.tap = g.C >= 64;   // enough channels to fill the columns of a per-tap tile
     if (pl.tap) {
         // (bm, bn) with the least padded area, larger tile on ties
-        const int cand[8][2] = {{128, 128}, {128, 96}, {96, 128}, {192, 64}, {128, 64}, {64, 128}, {64, 64}, {32, 128}};
+        // 96x96: three wavefronts of 96x32 each, for the 96-channel layers (fp32 kernel only)
+        const int cand[9][2] = {{128, 128}, {128, 96}, {96, 128}, {192, 64}, {128, 64}, {64, 128}, {64, 64}, {32, 128}, {96, 96}};
         long long best = -1;
         for (const auto& c : cand) {
+            if (c[0] == 96 && c[1] == 96 && dtype != PURINE_F32) continue;
             const long long area = (long long)((g.K + c[0] - 1) / c[0]) * c[0] * ((g.C + c[1] - 1) / c[1]) * c[1];
             if (best < 0 || area < best) { best = area; pl.bm = c[0]; pl.bn = c[1]; }
         }

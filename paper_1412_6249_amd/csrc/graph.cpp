@@ -79,6 +79,7 @@ bool arity_ok(int kind, int n_in, int n_out, float beta) {
         case PURINE_OP_CONV_FWD_BIAS_RELU: return n_in == 3 && n_out == 1;
         case PURINE_OP_CONV_BWD_DATA_RELU: return n_in == 3 + extra && n_out == 1;
         case PURINE_OP_CONV_BWD_WEIGHT_BIAS: return n_in == 2 + 2 * extra && n_out == 2;
+        case PURINE_OP_SGD_UPDATE: return n_in == 2 && n_out == 1;
         default: return false;
     }
 }
@@ -124,6 +125,8 @@ int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
         case PURINE_OP_BIAS_BWD:
             if (a.beta != 0.0f && T(op.in[1])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
             return purine_bias_bwd(T(op.in[0]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_SGD_UPDATE:
+            return purine_sgd_update(T(op.in[0]), T(op.in[1]), T(op.out[0]), a.lr, st);
         case PURINE_OP_RELU_FWD:
             return purine_relu_fwd(T(op.in[0]), T(op.out[0]), st);
         case PURINE_OP_RELU_BWD:
@@ -391,6 +394,56 @@ int purine_graph_run(purine_graph* g) {
     if (rc != PURINE_OK) return rc;
     if (fired < no) return PURINE_E_GRAPH;   // some operator can never fire
     return sync_rc;
+}
+
+int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b) {
+    if (!g) return PURINE_E_NULL;
+    const int nt = (int)g->tensors.size();
+    if (tensor_a < 0 || tensor_a >= nt || tensor_b < 0 || tensor_b >= nt || tensor_a == tensor_b) return PURINE_E_ARG;
+    const purine_tensor& A = g->tensors[tensor_a].desc;
+    const purine_tensor& B = g->tensors[tensor_b].desc;
+    if (A.dtype != B.dtype || A.ndim != B.ndim) return PURINE_E_SHAPE;
+    for (int i = 0; i < A.ndim; ++i) if (A.dim[i] != B.dim[i]) return PURINE_E_SHAPE;
+    if (!A.data || !B.data) return PURINE_E_NULL;
+    void* const pa = A.data;
+    void* const pb = B.data;
+    const Range ra{(uintptr_t)pa, (uintptr_t)pa + tensor_bytes(A)}, rb{(uintptr_t)pb, (uintptr_t)pb + tensor_bytes(B)};
+    if (hit(ra, rb)) return PURINE_E_LAYOUT;
+    // The exchange renames two storage ranges. It leaves the set of conflicting operator pairs as
+    // it was (so the graph stays valid) only if everything that touches one of the ranges covers
+    // exactly that range.
+    auto clean = [&](const Range& r) {
+        return (!hit(r, ra) || (r.lo == ra.lo && r.hi == ra.hi)) && (!hit(r, rb) || (r.lo == rb.lo && r.hi == rb.hi));
+    };
+    for (const auto& t : g->tensors)
+        if (t.desc.data && !clean({(uintptr_t)t.desc.data, (uintptr_t)t.desc.data + tensor_bytes(t.desc)})) return PURINE_E_LAYOUT;
+    for (const auto& op : g->ops)
+        if (op.attrs.ws && op.attrs.ws_bytes) {
+            const Range r{(uintptr_t)op.attrs.ws, (uintptr_t)op.attrs.ws + op.attrs.ws_bytes};
+            if (hit(r, ra) || hit(r, rb)) return PURINE_E_LAYOUT;
+        }
+    for (auto& t : g->tensors) {
+        if (t.desc.data == pa) t.desc.data = pb;
+        else if (t.desc.data == pb) t.desc.data = pa;
+    }
+    return PURINE_OK;
+}
+
+void* purine_graph_tensor_data(const purine_graph* g, int tensor_id) {
+    if (!g || tensor_id < 0 || tensor_id >= (int)g->tensors.size()) return nullptr;
+    return g->tensors[tensor_id].desc.data;
+}
+
+int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const int* swap_b, int n_swaps) {
+    if (!g) return PURINE_E_NULL;
+    if (n_iters < 0 || n_swaps < 0 || (n_swaps > 0 && (!swap_a || !swap_b))) return PURINE_E_ARG;
+    for (int it = 0; it < n_iters; ++it) {
+        int rc = purine_graph_run(g);   // returns at the synchronisation point: all sinks reached
+        if (rc != PURINE_OK) return rc;
+        for (int s = 0; s < n_swaps; ++s)
+            if ((rc = purine_graph_swap_storage(g, swap_a[s], swap_b[s])) != PURINE_OK) return rc;
+    }
+    return PURINE_OK;
 }
 
 int purine_graph_enable_timing(purine_graph* g, int on) {

@@ -150,6 +150,33 @@ __global__ __launch_bounds__(TPB) void relu_fwd_kernel(const T* x, T* y, size_t 
         stf<T>(y, i, v > 0.0f ? v : 0.0f);
     }
 }
+// ---- SGD update: new_w = w - lr * dw (one fused multiply-add in fp32 per element) ---------------
+// Packets of the parameter tensor (4 floats or 8 bfloat16) against 4-float packets of the fp32
+// gradient. new_w may be w itself: every element is read before it is written by the same lane.
+template <typename T>
+__global__ __launch_bounds__(TPB) void sgd_update_kernel(const T* w, const float* __restrict__ dw,
+                                                         T* nw, float lr, size_t n) {
+    constexpr int V = Pk<T>::N;
+    const size_t nv = n / V, stride = (size_t)gridDim.x * TPB, t0 = (size_t)blockIdx.x * TPB + threadIdx.x;
+    const uint4* w4 = reinterpret_cast<const uint4*>(w);
+    const float4* g4 = reinterpret_cast<const float4*>(dw);
+    uint4* o4 = reinterpret_cast<uint4*>(nw);
+    for (size_t i = t0; i < nv; i += stride) {
+        float f[V];
+        Pk<T>::unpack(w4[i], f);
+#pragma unroll
+        for (int q = 0; q < V / 4; ++q) {
+            const float4 g = g4[i * (V / 4) + q];
+            f[4 * q + 0] = fmaf(-lr, g.x, f[4 * q + 0]);
+            f[4 * q + 1] = fmaf(-lr, g.y, f[4 * q + 1]);
+            f[4 * q + 2] = fmaf(-lr, g.z, f[4 * q + 2]);
+            f[4 * q + 3] = fmaf(-lr, g.w, f[4 * q + 3]);
+        }
+        o4[i] = Pk<T>::pack(f);
+    }
+    for (size_t i = nv * V + t0; i < n; i += stride) stf<T>(nw, i, fmaf(-lr, dw[i], ldf<T>(w, i)));
+}
+
 template <typename T>
 __global__ __launch_bounds__(TPB) void relu_bwd_kernel(const T* __restrict__ x, const T* dy, T* dx,
                                                        size_t n) {
@@ -395,6 +422,17 @@ hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStre
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, (size_t)n),
              hipLaunchKernelGGL(relu_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, (size_t)n));
+    return hipGetLastError();
+}
+
+hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* new_w, float lr,
+                             int64_t n, hipStream_t st) {
+    dim3 grid(blocks_for((size_t)n / 4 + 1));
+    ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
+    BY_DTYPE(dtype,
+             hipLaunchKernelGGL(sgd_update_kernel<float>, grid, dim3(TPB), 0, st, (const float*)w, dw, (float*)new_w, lr, (size_t)n),
+             hipLaunchKernelGGL(sgd_update_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)w, dw, (uint16_t*)new_w, lr, (size_t)n));
     return hipGetLastError();
 }
 

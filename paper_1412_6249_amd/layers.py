@@ -150,8 +150,28 @@ class GraphBuilder:
             else:
                 self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"]], [dx], thread, B.op_attrs(conv=desc, ws=ws))
                 rec["fused_bwd"] = False
-        rec.update(dy=dy, db=db, dw=dw, dx=dx)
+        rec.update(dy=dy, db=db, dw=dw, dx=dx, t_w=t_w, t_b=t_w if self.fuse else t_b)
         return dx
+
+    def add_sgd(self, lr):
+        """SGD by graph iteration (paper section 2.2, Figure 3): for every parameter tensor one
+        operator leaves w - lr*dw in a separate "new" tensor (writing w itself would close a cycle);
+        `swaps` lists the (old, new) vertex pairs whose storage addresses the swap step exchanges
+        between two runs of the graph."""
+        self.swaps = []
+        for rec in self.conv_records:
+            for par, grad, th in ((rec["w"], rec["dw"], rec["t_w"]), (rec["b"], rec["db"], rec["t_b"])):
+                new = self.bind(par + ".new", torch.empty_like(self.t[par]))
+                self.op(B.OP_SGD_UPDATE, [par, grad], [new], th, B.op_attrs(lr=lr))
+                self.swaps.append((par, new))
+
+    def iterate(self, n):
+        """n times: run the graph, then swap old and new parameters. Afterwards the "old" vertices
+        (and this object's tensors of the same names) hold the latest parameters."""
+        B.purine_graph_iterate(self.g, n, [(self.ids[a], self.ids[b]) for a, b in self.swaps])
+        if n % 2:
+            for a, b in self.swaps:
+                self.t[a], self.t[b] = self.t[b], self.t[a]
 
     def maxpool_forward(self, x, shape, dtype, window, stride, pad, prefix, thread=T_MAIN):
         N, C, H, W = shape
@@ -194,13 +214,14 @@ def _default_init(seed):
 
 
 def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True,
-                   fuse=False, first_layer_dx=True):
+                   fuse=False, first_layer_dx=True, sgd_lr=None):
     """Builds the bi-graph of config `cfg` (1..5). `batch` overrides the batch size (tests).
     `init(name, shape, dtype, kind)` supplies source tensors (kind in x, w, b, dy); by default they
     are drawn on the device from the seed. `first_layer_dx=False` leaves out the backward-data
     operator of the layer that reads the images in the chained configs 2 and 4 (a training step
-    does not need that gradient). Returns the GraphBuilder; gb.run() performs one full forward +
-    backward step."""
+    does not need that gradient). `sgd_lr`: also add one SGD update operator per parameter tensor
+    (gb.iterate(n) then runs n training iterations). Returns the GraphBuilder; gb.run() performs one
+    full forward + backward step."""
     init = init or _default_init(seed)
     layers = [l.with_batch(batch) if batch else l for l in CONV_LAYERS[cfg]]
     gb = GraphBuilder(inplace=inplace, fuse=fuse)
@@ -290,5 +311,7 @@ def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, mult
         gb.pool_records = [p for p in pools if p is not None]
     else:
         raise ValueError("config must be 1..5")
+    if sgd_lr is not None:
+        gb.add_sgd(sgd_lr)
     B.purine_graph_validate(gb.g)
     return gb

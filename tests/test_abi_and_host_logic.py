@@ -24,7 +24,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = declared_symbols()
-    assert len(names) == 37
+    assert len(names) == 41
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -162,6 +162,15 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_bias_fwd, b, y, stream=s) == -2                          # K mismatch
     db = binding.raw_desc(fake + 0x400000, F32, (4,))
     assert status(pa.purine_bias_bwd, y, db, stream=s) == -5
+    wd = binding.raw_desc(fake + 0x600000, F32, (4, 3, 3, 3))
+    nw = binding.raw_desc(fake + 0x700000, F32, (4, 3, 3, 3))
+    assert status(pa.purine_sgd_update, w, wd, binding.raw_desc(fake + 0x700000, BF16, (4, 3, 3, 3)), 0.1, stream=s) == -3
+    assert status(pa.purine_sgd_update, w, binding.raw_desc(fake + 0x600000, BF16, (4, 3, 3, 3)), nw, 0.1, stream=s) == -3
+    assert status(pa.purine_sgd_update, w, wd, binding.raw_desc(fake + 0x700000, F32, (4, 3, 3, 2)), 0.1, stream=s) == -2
+    assert status(pa.purine_sgd_update, w, wd, nw, float("nan"), stream=s) == -8
+    assert status(pa.purine_sgd_update, w, wd, nw, float("inf"), stream=s) == -8
+    assert status(pa.purine_sgd_update, w, wd, binding.raw_desc(fake + 0x100000 + 16, F32, (4, 3, 3, 3)), 0.1, stream=s) == -4  # partial overlap with w
+    assert status(pa.purine_sgd_update, w, wd, wd, 0.1, stream=s) == -4                # new_w is dw
     big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
     assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
     assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8

@@ -1,0 +1,117 @@
+"""SGD by graph iteration (paper section 2.2, Figure 3) on the GPU: the update operator against the
+oracle, and iterated workload graphs (network graph with one update operator per parameter, then
+the swap of old and new parameters) checked iteration by iteration with teacher forcing: the
+parameters an iteration starts from and the gradients it computed are downloaded, the oracle's
+update of those is compared with the device's new parameters, and after the swap the next run's
+first-layer output must be the convolution with the UPDATED filter."""
+import numpy as np
+import pytest
+
+import oracle
+from synth import gen
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [(1,), (7,), (96, 3, 11, 11), (33, 5), (4, 3, 3, 3), (256, 96, 5, 5)])
+def test_sgd_update_operator(shape, dtype):
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import to_dev, to_host, DEV
+    rs = np.random.default_rng(len(shape) * 1000 + shape[0])
+    w = rs.uniform(-1, 1, shape).astype(np.float32)
+    dw = rs.uniform(-4, 4, shape).astype(np.float32)
+    if dtype == "bf16":
+        w = gen.quantize_bf16(w)
+    lr = 0.0123
+    tw, tdw = to_dev(w, dtype), to_dev(dw)
+    tn = torch.full(shape, float("nan"), dtype=tw.dtype, device=DEV)
+    pa.purine_sgd_update(tw, tdw, tn, lr)
+    torch.cuda.synchronize()
+    ref = oracle.sgd_update(w, dw, np.float32(lr))
+    got = to_host(tn)
+    if dtype == "f32":
+        # one fused multiply-add in fp32: within half an ulp of the exact value
+        assert np.all(np.abs(got - ref) <= np.spacing(np.abs(ref).astype(np.float32)) * 0.5 + 1e-45)
+    else:
+        # the fp32 value rounded to bf16 (nearest even); the fp64 value may round the other way
+        # only when it sits within an fp32 rounding error of a bf16 tie
+        q = gen.quantize_bf16(ref.astype(np.float32))
+        bad = got != q
+        assert bad.mean() <= 1e-3
+        assert np.all(np.abs(got - ref)[bad] <= np.abs(ref)[bad] * 2.0 ** -8 + 1e-30)
+    assert np.array_equal(to_host(tw), w)                      # w untouched
+    pa.purine_sgd_update(tw, tdw, tw, lr)                       # in place
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(tw), got)
+    # lr = 0 returns the parameters bit for bit
+    pa.purine_sgd_update(tn, tdw, tw, 0.0)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(tw), got)
+
+
+@pytest.mark.parametrize("cfg,batch,fuse", [(2, 2, True), (4, 2, True), (4, 2, False), (5, 1, True)])
+def test_graph_iteration_teacher_forced(cfg, batch, fuse):
+    from gpu_util import rel_l2, to_host
+    from paper_1412_6249_amd.layers import build_workload
+    lr = 1e-3
+    gb = build_workload(cfg, batch=batch, inplace=True, fuse=fuse, sgd_lr=lr)
+    tol = 1e-2 if cfg == 5 else 1e-5
+    try:
+        rec0 = gb.conv_records[0]
+        L0 = rec0["layer"]
+        for it in range(3):
+            before = {p: to_host(gb.t[p]) for p, _ in gb.swaps}
+            gb.iterate(1)                                   # run + swap: "old" names now hold the update
+            for rec in gb.conv_records:
+                for par, grad in ((rec["w"], rec["dw"]), (rec["b"], rec["db"])):
+                    ref = oracle.sgd_update(before[par], to_host(gb.t[grad]), np.float32(lr))
+                    got = to_host(gb.t[par])
+                    assert rel_l2(got, ref) <= (2.0 ** -8 if cfg == 5 else 1e-6), (it, par)
+                    assert not np.array_equal(got, before[par]), (it, par)       # it did move
+                    # the vertex that held the old parameters now names the other buffer
+                    assert np.array_equal(to_host(gb.t[par + ".new"]), before[par]), (it, par)
+            # the forward pass of THIS iteration used the parameters from before the update
+            x, w, b = to_host(gb.t[rec0["x"]]), before[rec0["w"]], before[rec0["b"]]
+            ref = oracle.bias_fwd(oracle.conv_fwd(x, w, L0.stride, L0.pad), b)
+            if rec0["relu"]:
+                ref = np.maximum(ref, 0.0)
+            assert rel_l2(to_host(gb.t[rec0["out"]]), ref) <= tol, (it, "first layer forward")
+        # and one more run reads the latest ones
+        latest = {p: to_host(gb.t[p]) for p, _ in gb.swaps}
+        gb.run()
+        x = to_host(gb.t[rec0["x"]])
+        ref = oracle.bias_fwd(oracle.conv_fwd(x, latest[rec0["w"]], L0.stride, L0.pad), latest[rec0["b"]])
+        if rec0["relu"]:
+            ref = np.maximum(ref, 0.0)
+        assert rel_l2(to_host(gb.t[rec0["out"]]), ref) <= tol
+    finally:
+        gb.close()
+
+
+def test_iterate_in_one_call_equals_run_and_swap_by_hand():
+    """purine_graph_iterate(n) against n separate run + swap calls: same bits, also for an odd n."""
+    import paper_1412_6249_amd as pa
+    from gpu_util import to_host
+    from paper_1412_6249_amd.layers import build_workload
+    a = build_workload(2, batch=2, fuse=True, sgd_lr=1e-3)
+    b = build_workload(2, batch=2, fuse=True, sgd_lr=1e-3)
+    try:
+        a.iterate(3)
+        for _ in range(3):
+            b.run()
+            for old, new in b.swaps:
+                pa.purine_graph_swap_storage(b.g, b.ids[old], b.ids[new])
+                b.t[old], b.t[new] = b.t[new], b.t[old]
+        for old, new in a.swaps:
+            assert np.array_equal(to_host(a.t[old]), to_host(b.t[old])), old
+            assert np.array_equal(to_host(a.t[new]), to_host(b.t[new])), new
+        start = build_workload(2, batch=2, fuse=True)
+        try:
+            assert not np.array_equal(to_host(a.t["conv1.w"]), to_host(start.t["conv1.w"]))
+        finally:
+            start.close()
+    finally:
+        a.close()
+        b.close()

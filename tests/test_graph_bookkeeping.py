@@ -207,3 +207,56 @@ def test_empty_graph_runs():
     pa.purine_graph_run(g)
     assert pa.purine_graph_fire_log(g) == []
     pa.purine_graph_destroy(g)
+
+
+def test_swap_storage_and_iteration_bookkeeping():
+    """The swap step of graph iteration (paper section 2.2, Figure 3(b)) as host bookkeeping: every
+    vertex bound to either address moves with it, the graph stays valid, and what would change the
+    set of conflicting operators is refused."""
+    g = pa.purine_graph_create()
+    dims = (1, 2, 4, 4)                                              # 128 bytes
+    old = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, dims), "old")
+    old_v = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, dims), "old.v1")   # second version
+    new = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, dims), "new")
+    other = pa.purine_graph_add_tensor(g, binding.raw_desc(0x5000, F32, dims), "other")
+    half = pa.purine_graph_add_tensor(g, binding.raw_desc(0x5000, F32, (1, 1, 4, 4)), "other.half")
+    small = pa.purine_graph_add_tensor(g, binding.raw_desc(0x7000, F32, (1, 1, 4, 4)), "small")
+    near = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1040, F32, dims), "straddles old")
+    nop(g, [old], [old_v])
+    nop(g, [old_v], [new])
+    addr = lambda t: pa.purine_graph_tensor_data(g, t)
+
+    def status(a, b):
+        with pytest.raises(pa.PurineError) as e:
+            pa.purine_graph_swap_storage(g, a, b)
+        return e.value.status
+
+    assert status(old, small) == -2          # extents differ
+    assert status(old, old) == -8
+    assert status(old, 99) == -8
+    assert status(old, old_v) == -4          # same storage
+    assert status(old, near) == -4           # overlapping ranges
+    assert status(other, new) == -4          # `half` covers part of `other`
+    assert status(old, new) == -4            # `near` straddles old's range
+    pa.purine_graph_destroy(g)
+
+    g = pa.purine_graph_create()
+    old = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, dims), "old")
+    old_v = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, dims), "old.v1")
+    new = pa.purine_graph_add_tensor(g, binding.raw_desc(0x9000, F32, dims), "new")
+    other = pa.purine_graph_add_tensor(g, binding.raw_desc(0x5000, F32, dims), "other")
+    nop(g, [old], [old_v])
+    nop(g, [old_v, other], [new])
+    addr = lambda t: pa.purine_graph_tensor_data(g, t)
+    pa.purine_graph_swap_storage(g, old, new)
+    assert (addr(old), addr(old_v), addr(new), addr(other)) == (0x9000, 0x9000, 0x1000, 0x5000)
+    pa.purine_graph_validate(g)
+    pa.purine_graph_iterate(g, 3, [(old, new)])                      # three runs, three more swaps
+    assert (addr(old), addr(old_v), addr(new)) == (0x1000, 0x1000, 0x9000)
+    assert pa.purine_graph_fire_log(g) == [0, 1]
+    pa.purine_graph_iterate(g, 2, [])                                # no swaps: plain repetition
+    assert addr(old) == 0x1000
+    assert pa.purine_graph_tensor_data(g, 77) == 0
+    with pytest.raises(pa.PurineError):
+        pa.purine_graph_iterate(g, -1, [])
+    pa.purine_graph_destroy(g)

@@ -365,3 +365,28 @@ def test_relu_and_pool_and_concat():
     cat = oracle.concat_channels([a, b])
     assert cat.shape == (2, 7, 3, 3) and np.array_equal(cat[:, 2:], b)
     assert np.array_equal(oracle.fan_in_sum([a, a]), 2 * a.astype(np.float64))
+
+
+# ---------------------------------------------------------------- SGD step (section 2.2)
+def test_sgd_update_descends_a_linear_and_a_quadratic_loss():
+    """Pins sign and scale of the update with functions other than itself. (1) L(w) = <conv(x, w), g>
+    is linear in w with gradient dw = conv_bwd_weight(x, g), so a step changes it by exactly
+    -lr * |dw|^2. (2) For L(w) = |w - t|^2 / 2 the gradient is w - t: a step with lr = 1 lands on
+    t, lr = 0 stays, and lr = 1/2 halves the distance."""
+    x, w, g = rnd(2, 3, 6, 5), rnd(4, 3, 3, 2), rnd(2, 4, 4, 4)
+    stride, pad = (1, 1), (0, 0)
+    loss = lambda ww: float((oracle.conv_fwd(x, ww.astype(np.float32), stride, pad) * g).sum())
+    dw = oracle.conv_bwd_weight(x, g, w.shape, stride, pad)
+    lr = 2.0 ** -6                                       # exact in fp32, keeps w_new close to fp32 grid
+    w_new = oracle.sgd_update(w, dw, lr)
+    # linearity: evaluate the loss change through the oracle's own forward pass on the DIFFERENCE
+    step = (w_new - w.astype(np.float64)).astype(np.float32)
+    change = float((oracle.conv_fwd(x, step, stride, pad) * g).sum())
+    assert abs(change + lr * float((dw ** 2).sum())) <= 1e-5 * lr * float((dw ** 2).sum())
+    assert loss(w_new) < loss(w.astype(np.float64))
+    t = rnd(5, 7)
+    v = rnd(5, 7)
+    assert np.allclose(oracle.sgd_update(v, v.astype(np.float64) - t, 1.0), t, rtol=0, atol=1e-15)
+    assert np.array_equal(oracle.sgd_update(v, v - t, 0.0), v.astype(np.float64))
+    half = oracle.sgd_update(v, v.astype(np.float64) - t, 0.5)
+    assert np.allclose(half - t, 0.5 * (v.astype(np.float64) - t), rtol=0, atol=1e-15)
