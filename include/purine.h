@@ -16,6 +16,14 @@
  *   - Tensors are dense, row-major: activations NCHW, filters KCRS, bias [K]. `dim` holds the
  *     extents, outermost first; unused trailing entries are ignored. No tensor may hold 2^31 or
  *     more elements. Data pointers must be aligned to 16 bytes.
+ *   - Channel-slice views: a 4-axis F32 activation tensor may set `nstride`, the distance in
+ *     elements between consecutive images, to more than C*H*W: the tensor is then channels
+ *     c0..c0+C-1 of a larger NCHW buffer with `data` pointing at channel c0 of image 0 (inside an
+ *     image the layout stays dense). nstride must be a multiple of 4 and the span
+ *     (N-1)*nstride + C*H*W must stay below 2^31 elements. Views are accepted where an entry
+ *     point says so (the activation arguments of the convolution operators and of ReLU); every
+ *     other argument must be dense (PURINE_E_LAYOUT otherwise). Two views of one buffer with the
+ *     same nstride overlap only if their channel ranges do.
  *   - dtype: PURINE_F32 tensors hold IEEE binary32. PURINE_BF16 tensors hold bfloat16 bit
  *     patterns (uint16); arithmetic accumulates in fp32; results stored as bf16 are rounded to
  *     nearest even. Weight and bias gradients are always PURINE_F32.
@@ -56,6 +64,7 @@ typedef struct {
     int32_t dtype;  /* purine_dtype                                    */
     int32_t ndim;   /* 1..4                                            */
     int64_t dim[4]; /* extents, outermost first                        */
+    int64_t nstride; /* 0 (dense) or elements between images, see above */
 } purine_tensor;
 
 /* Convolution geometry. Filter extents R,S and the channel counts come from the filter tensor.

@@ -39,7 +39,7 @@ class PurineError(RuntimeError):
 
 class purine_tensor(ctypes.Structure):
     _fields_ = [("data", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("ndim", ctypes.c_int32),
-                ("dim", ctypes.c_int64 * 4)]
+                ("dim", ctypes.c_int64 * 4), ("nstride", ctypes.c_int64)]
 
 
 class purine_conv_desc(ctypes.Structure):
@@ -130,16 +130,22 @@ def _dtype_code(t):
 
 
 def tensor_desc(t):
-    """purine_tensor for a contiguous CUDA torch tensor (or passes a ready-made descriptor through)."""
+    """purine_tensor for a CUDA torch tensor that is contiguous or a channel slice of a contiguous
+    NCHW tensor (or passes a ready-made descriptor through)."""
     if isinstance(t, purine_tensor):
         return t
     if not t.is_cuda:
         raise ValueError("tensor must live on the GPU")
-    if not t.is_contiguous():
-        raise ValueError("tensor must be contiguous (dense NCHW / KCRS)")
     if t.dim() < 1 or t.dim() > 4:
         raise ValueError("1 to 4 dimensions")
+    nstride = 0
+    if not t.is_contiguous():
+        n, c, h, w = t.shape if t.dim() == 4 else (0, 0, 0, 0)
+        if t.dim() != 4 or tuple(t.stride()[1:]) != (h * w, w, 1) or t.stride(0) < c * h * w:
+            raise ValueError("tensor must be contiguous (dense NCHW / KCRS) or a channel slice of one")
+        nstride = int(t.stride(0))
     d = purine_tensor()
+    d.nstride = nstride
     d.data = t.data_ptr()
     d.dtype = _dtype_code(t)
     d.ndim = t.dim()
@@ -148,9 +154,10 @@ def tensor_desc(t):
     return d
 
 
-def raw_desc(data_ptr, dtype, dims):
+def raw_desc(data_ptr, dtype, dims, nstride=0):
     """Descriptor from a raw pointer (tests of the error paths, host-only graphs)."""
     d = purine_tensor()
+    d.nstride = int(nstride)
     d.data = data_ptr
     d.dtype = dtype
     d.ndim = len(dims)

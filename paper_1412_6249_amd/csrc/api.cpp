@@ -15,7 +15,22 @@ int64_t numel(const purine_tensor* t) {
     return n;
 }
 
-int check_tensor(const purine_tensor* t, int ndim) {
+// elements of one image (all axes but the first)
+int64_t image_elems(const purine_tensor* t) {
+    int64_t n = 1;
+    for (int i = 1; i < t->ndim; ++i) n *= t->dim[i];
+    return n;
+}
+// elements between consecutive images: the dense distance unless the tensor is a channel-slice view
+int64_t nstride_of(const purine_tensor* t) {
+    return (t->ndim == 4 && t->nstride != 0) ? t->nstride : image_elems(t);
+}
+bool is_view(const purine_tensor* t) { return nstride_of(t) != image_elems(t); }
+// elements from the first to one past the last element of the tensor
+int64_t span_elems(const purine_tensor* t) { return (t->dim[0] - 1) * nstride_of(t) + image_elems(t); }
+
+// allow_view: the argument may be a channel-slice view (F32, 4 axes)
+int check_tensor(const purine_tensor* t, int ndim, bool allow_view = false) {
     if (!t) return PURINE_E_NULL;
     if (!t->data) return PURINE_E_NULL;
     if (t->ndim != ndim) return PURINE_E_SHAPE;
@@ -28,16 +43,33 @@ int check_tensor(const purine_tensor* t, int ndim) {
         if (n >= (1ll << 31)) return PURINE_E_SHAPE;
     }
     if (((uintptr_t)t->data) & 15u) return PURINE_E_LAYOUT;
+    if (t->nstride != 0) {
+        if (t->ndim != 4 || t->nstride < image_elems(t)) return PURINE_E_SHAPE;
+        if (is_view(t)) {
+            if (!allow_view || t->dtype != PURINE_F32 || (t->nstride & 3)) return PURINE_E_LAYOUT;
+            if (t->nstride >= (1ll << 31) || span_elems(t) >= (1ll << 31)) return PURINE_E_SHAPE;
+        }
+    }
     return PURINE_OK;
 }
 
 bool is_float_dtype(int d) { return d == PURINE_F32 || d == PURINE_BF16; }
 size_t elem_bytes(int d) { return d == PURINE_BF16 ? 2 : 4; }
 
+// Do the two tensors share a byte? Exact for dense tensors; for two views with the same distance
+// between images the per-image ranges are compared modulo that distance (channel slices of one
+// buffer); anything else falls back to the spans.
 bool overlaps(const purine_tensor* a, const purine_tensor* b) {
-    const uintptr_t a0 = (uintptr_t)a->data, a1 = a0 + (size_t)numel(a) * elem_bytes(a->dtype);
-    const uintptr_t b0 = (uintptr_t)b->data, b1 = b0 + (size_t)numel(b) * elem_bytes(b->dtype);
-    return a0 < b1 && b0 < a1;
+    const uintptr_t a0 = (uintptr_t)a->data, a1 = a0 + (size_t)span_elems(a) * elem_bytes(a->dtype);
+    const uintptr_t b0 = (uintptr_t)b->data, b1 = b0 + (size_t)span_elems(b) * elem_bytes(b->dtype);
+    if (!(a0 < b1 && b0 < a1)) return false;
+    const uint64_t sa = (uint64_t)nstride_of(a) * elem_bytes(a->dtype), sb = (uint64_t)nstride_of(b) * elem_bytes(b->dtype);
+    if (is_view(a) && is_view(b) && sa == sb) {
+        const uint64_t la = (uint64_t)image_elems(a) * elem_bytes(a->dtype), lb = (uint64_t)image_elems(b) * elem_bytes(b->dtype);
+        const uint64_t d = a0 >= b0 ? (a0 - b0) % sa : (sa - (b0 - a0) % sa) % sa;   // (a0 - b0) mod s
+        return d < lb || sa - d < la;
+    }
+    return true;
 }
 
 bool same_dims(const purine_tensor* a, const purine_tensor* b) {
@@ -74,6 +106,8 @@ int make_geom(const purine_conv_desc* d, const int64_t* xd, const int64_t* wd, c
     g->K = (int)wd[0]; g->R = (int)wd[2]; g->S = (int)wd[3];
     g->P = (int)out[2]; g->Q = (int)out[3];
     g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->x_ns = g->C * g->H * g->W;
+    g->y_ns = g->K * g->P * g->Q;
     // padded coordinates (h + pad, p*stride) also travel in 32-bit ints
     if ((int64_t)g->H + 2ll * g->ph > lim / 4 || (int64_t)g->W + 2ll * g->pw > lim / 4) return PURINE_E_SHAPE;
     return PURINE_OK;
@@ -164,12 +198,14 @@ static int conv_fwd_impl(const purine_conv_desc* desc, const purine_tensor* x, c
                          const purine_tensor* b, purine_tensor* y, int relu, void* ws, size_t ws_bytes,
                          void* hip_stream) {
     int rc;
-    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(w, 4)) ||
-        (rc = check_tensor(y, 4)))
+    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4, true)) || (rc = check_tensor(w, 4)) ||
+        (rc = check_tensor(y, 4, true)))
         return rc;
     if (!is_float_dtype(x->dtype) || w->dtype != x->dtype || y->dtype != x->dtype) return PURINE_E_DTYPE;
     ConvGeom g;
     if ((rc = make_geom(desc, x->dim, w->dim, y->dim, &g))) return rc;
+    g.x_ns = (int)nstride_of(x);
+    g.y_ns = (int)nstride_of(y);
     if (overlaps(y, x) || overlaps(y, w)) return PURINE_E_LAYOUT;
     PixEpilogue epi;
     if (b) {
@@ -204,18 +240,21 @@ static int conv_bwd_data_impl(const purine_conv_desc* desc, const purine_tensor*
                               const purine_tensor* w, const purine_tensor* act, purine_tensor* dx,
                               float beta, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc;
-    if ((rc = check_desc(desc)) || (rc = check_tensor(dy, 4)) || (rc = check_tensor(w, 4)) ||
-        (rc = check_tensor(dx, 4)) || (rc = check_beta(beta)))
+    if ((rc = check_desc(desc)) || (rc = check_tensor(dy, 4, true)) || (rc = check_tensor(w, 4)) ||
+        (rc = check_tensor(dx, 4, true)) || (rc = check_beta(beta)))
         return rc;
     if (!is_float_dtype(dy->dtype) || w->dtype != dy->dtype || dx->dtype != dy->dtype) return PURINE_E_DTYPE;
     ConvGeom g;
     if ((rc = make_geom(desc, dx->dim, w->dim, dy->dim, &g))) return rc;
+    g.x_ns = (int)nstride_of(dx);
+    g.y_ns = (int)nstride_of(dy);
     if (overlaps(dx, dy) || overlaps(dx, w)) return PURINE_E_LAYOUT;
     PixEpilogue epi;
     if (act) {
-        if ((rc = check_tensor(act, 4))) return rc;
+        if ((rc = check_tensor(act, 4, true))) return rc;
         if (act->dtype != dx->dtype) return PURINE_E_DTYPE;
         if (!same_dims(act, dx)) return PURINE_E_SHAPE;
+        if (nstride_of(act) != nstride_of(dx)) return PURINE_E_LAYOUT;   // one set of offsets serves both
         if (overlaps(act, dx)) return PURINE_E_LAYOUT;
         epi.mask = act->data;
     }
@@ -246,13 +285,15 @@ int conv_bwd_weight_impl(const purine_conv_desc* desc, const purine_tensor* x, c
                          purine_tensor* dw, purine_tensor* db, float beta, void* ws, size_t ws_bytes,
                          void* hip_stream) {
     int rc;
-    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4)) || (rc = check_tensor(dy, 4)) ||
+    if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4, true)) || (rc = check_tensor(dy, 4, true)) ||
         (rc = check_tensor(dw, 4)) || (db && (rc = check_tensor(db, 1))) || (rc = check_beta(beta)))
         return rc;
     if (!is_float_dtype(x->dtype) || dy->dtype != x->dtype || dw->dtype != PURINE_F32) return PURINE_E_DTYPE;
     if (db && db->dtype != PURINE_F32) return PURINE_E_DTYPE;
     ConvGeom g;
     if ((rc = make_geom(desc, x->dim, dw->dim, dy->dim, &g))) return rc;
+    g.x_ns = (int)nstride_of(x);
+    g.y_ns = (int)nstride_of(dy);
     if (db && db->dim[0] != dy->dim[1]) return PURINE_E_SHAPE;
     if (overlaps(dw, x) || overlaps(dw, dy)) return PURINE_E_LAYOUT;
     if (db && (overlaps(db, x) || overlaps(db, dy) || overlaps(db, dw))) return PURINE_E_LAYOUT;
@@ -309,13 +350,20 @@ int purine_bias_bwd(const purine_tensor* dy, purine_tensor* db, float beta, void
 int purine_relu_fwd(const purine_tensor* x, purine_tensor* y, void* hip_stream) {
     int rc;
     if (!x || !y) return PURINE_E_NULL;
-    if ((rc = check_tensor(x, x->ndim >= 1 && x->ndim <= 4 ? x->ndim : -1)) ||
-        (rc = check_tensor(y, x->ndim)))
+    if ((rc = check_tensor(x, x->ndim >= 1 && x->ndim <= 4 ? x->ndim : -1, true)) ||
+        (rc = check_tensor(y, x->ndim, true)))
         return rc;
     if (!is_float_dtype(x->dtype) || y->dtype != x->dtype) return PURINE_E_DTYPE;
     if (!same_dims(x, y)) return PURINE_E_SHAPE;
-    if (x->data != y->data && overlaps(x, y)) return PURINE_E_LAYOUT;
-    hipError_t e = launch_relu_fwd(x->dtype, x->data, y->data, numel(x), (hipStream_t)hip_stream);
+    if (x->data == y->data ? nstride_of(x) != nstride_of(y) : overlaps(x, y)) return PURINE_E_LAYOUT;
+    hipError_t e;
+    if (is_view(x) || is_view(y)) {
+        if (x->dim[0] > 65535) return PURINE_E_SHAPE;
+        e = launch_relu_view(false, (const float*)x->data, nullptr, (float*)y->data, (int)x->dim[0],
+                             (int)image_elems(x), nstride_of(x), 0, nstride_of(y), (hipStream_t)hip_stream);
+    } else {
+        e = launch_relu_fwd(x->dtype, x->data, y->data, numel(x), (hipStream_t)hip_stream);
+    }
     return hip_status(e);
 }
 
@@ -323,15 +371,22 @@ int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tens
                     void* hip_stream) {
     int rc;
     if (!x || !dy || !dx) return PURINE_E_NULL;
-    if ((rc = check_tensor(x, x->ndim >= 1 && x->ndim <= 4 ? x->ndim : -1)) ||
-        (rc = check_tensor(dy, x->ndim)) || (rc = check_tensor(dx, x->ndim)))
+    if ((rc = check_tensor(x, x->ndim >= 1 && x->ndim <= 4 ? x->ndim : -1, true)) ||
+        (rc = check_tensor(dy, x->ndim, true)) || (rc = check_tensor(dx, x->ndim, true)))
         return rc;
     if (!is_float_dtype(x->dtype) || dy->dtype != x->dtype || dx->dtype != x->dtype) return PURINE_E_DTYPE;
     if (!same_dims(x, dy) || !same_dims(x, dx)) return PURINE_E_SHAPE;
     if (overlaps(dx, x)) return PURINE_E_LAYOUT;
-    if (dx->data != dy->data && overlaps(dx, dy)) return PURINE_E_LAYOUT;
-    hipError_t e = launch_relu_bwd(x->dtype, x->data, dy->data, dx->data, numel(x),
-                                   (hipStream_t)hip_stream);
+    if (dx->data == dy->data ? nstride_of(dx) != nstride_of(dy) : overlaps(dx, dy)) return PURINE_E_LAYOUT;
+    hipError_t e;
+    if (is_view(x) || is_view(dy) || is_view(dx)) {
+        if (x->dim[0] > 65535) return PURINE_E_SHAPE;
+        e = launch_relu_view(true, (const float*)x->data, (const float*)dy->data, (float*)dx->data,
+                             (int)x->dim[0], (int)image_elems(x), nstride_of(x), nstride_of(dy),
+                             nstride_of(dx), (hipStream_t)hip_stream);
+    } else {
+        e = launch_relu_bwd(x->dtype, x->data, dy->data, dx->data, numel(x), (hipStream_t)hip_stream);
+    }
     return hip_status(e);
 }
 

@@ -48,13 +48,17 @@ struct WgradParams {
     int chunk;         // pixels per split, a multiple of the slab depth
     int tiles_i, tiles_j, splits;
     int c_tiles;       // per-tap column mode: channel tiles per tap (tiles_j = R*S*c_tiles)
-    unsigned x_bytes, dy_bytes;   // tensor sizes when the kernels may read them as raw buffers, else 0
+    int x_ns, dy_ns;   // elements between consecutive images of x and of dy
+    unsigned x_bytes, dy_bytes;   // tensor spans when the kernels may read them as raw buffers, else 0
     float* db_out;     // fused bias gradient: partial sums [splits][K], or null
 };
 
 
 struct ConvGeom {
     int N, C, H, W, K, R, S, P, Q, sh, sw, ph, pw;
+    // elements between consecutive images of the x-shaped tensors (x, dx, the ReLU mask of dx) and
+    // of the y-shaped ones (y, dy): C*H*W and K*P*Q unless the tensor is a channel-slice view
+    int x_ns, y_ns;
 };
 
 // Launch plan of the forward / backward-data implicit GEMM: same answer for the workspace query and
@@ -132,6 +136,8 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
 hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st);
 hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
                            hipStream_t st);
+hipError_t launch_relu_view(bool bwd, const float* x, const float* dy, float* out, int N, int run,
+                            int64_t x_ns, int64_t dy_ns, int64_t out_ns, hipStream_t st);
 hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* new_w, float lr,
                              int64_t n, hipStream_t st);
 hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,

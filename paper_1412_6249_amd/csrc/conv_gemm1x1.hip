@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     }
     // reduction step ks reads channel rows 2*ks + khalf; KS steps in all (Ci is a multiple of 16)
     const int KS = p.Ci >> 1;
-    const T* src = in + ((size_t)n * p.Ci + khalf) * p.HoWo + pix;
+    const T* src = in + (size_t)n * p.in_ns + (size_t)khalf * p.HoWo + pix;
     const size_t step = (size_t)2 * p.HoWo;
 
     // Two register sets of DEPTH reduction steps each: the loads of the next group are all issued
@@ -293,7 +293,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     }
 
     if (!live) return;
-    const size_t obase = (size_t)n * p.Co * p.HoWo + pix;
+    const size_t obase = (size_t)n * p.out_ns + pix;
 #pragma unroll
     for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN>(p, acc[a], i0 + a * 32 + khalf * 4, obase, bias_s, i0);
 }

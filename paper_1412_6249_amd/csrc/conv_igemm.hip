@@ -87,7 +87,7 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
         const int wo = rem - ho * p.Wo;
         g_h = ho * p.g_mul_h + p.g_add_h;
         g_w = wo * p.g_mul_w + p.g_add_w;
-        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;   // tap (0,0) of channel 0
+        g_off = n * p.in_ns + g_h * p.Wi + g_w;   // tap (0,0) of channel 0
     }
     const int b_row = __builtin_amdgcn_readfirstlane(tid / BN);  // uniform per wavefront (BN >= 64)
     // descriptor of the gathered tensor as a raw buffer of p.in_bytes bytes (BUF only)
@@ -265,7 +265,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
         const int wo = rem - ho * p.Wo;
         g_h = ho * p.g_mul_h + p.g_add_h;
         g_w = wo * p.g_mul_w + p.g_add_w;
-        g_off = n * p.Ci * p.HiWi + g_h * p.Wi + g_w;
+        g_off = n * p.in_ns + g_h * p.Wi + g_w;
     }
     const int b_row = __builtin_amdgcn_readfirstlane(tid / BN);
     const int a_kk = tid % BK;
@@ -671,6 +671,8 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
     p.HiWi = p.Hi * p.Wi;
     p.HoWo = p.Ho * p.Wo;
     p.M = p.N * p.HoWo;
+    p.in_ns = pl.mode == 0 ? g.x_ns : g.y_ns;    // forward gathers x, backward-data gathers dy
+    p.out_ns = pl.mode == 0 ? g.y_ns : g.x_ns;
     p.Kg = p.Ci * p.RS;
     p.div_howo = make_fastdiv(p.HoWo);
     p.div_wo = make_fastdiv(p.Wo);
@@ -683,7 +685,7 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
     {
         // raw-buffer gather of the fp32 tap kernels: the whole tensor must be addressable with byte
         // offsets below 2^31
-        const long long in_bytes = (long long)p.N * p.Ci * p.HiWi * 4;
+        const long long in_bytes = ((long long)(p.N - 1) * p.in_ns + (long long)p.Ci * p.HiWi) * 4;
         p.in_bytes = (dtype == PURINE_F32 && in_bytes < 0x7fffffffLL && g_no_buffer_loads == 0) ? (unsigned)in_bytes : 0u;
     }
 

@@ -157,7 +157,7 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
         const int pq = pc - n * p.PQ;
         const int pp = fastdiv(pq, p.div_q);
         const int qq = pq - pp * p.Q;
-        const int a_base = n * p.K * p.PQ + pq;
+        const int a_base = n * p.dy_ns + pq;
         a_ok = 0u; b_ok = 0u;
         if (BUF) {
             const unsigned a_pix = pv ? (unsigned)a_base * 4u : 0x80000000u;
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_kernel(const WgradParams p
             }
         }
         const int hb = pp * p.sh - p.ph + tw.tap_r, wb = qq * p.sw - p.pw + tw.tap_s;
-        const int b_base = n * p.C * p.HW + hb * p.W + wb;
+        const int b_base = n * p.x_ns + hb * p.W + wb;
         if (B_TWO_PART) {
             // per-tap mode: one bounds test for the pixel's tap; unpadded flattened mode: none
             const bool in = TAP ? (pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W)) : pv;
@@ -411,12 +411,12 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
                 const int row = f / (BKP / 8), piece = f - row * (BKP / 8);
                 const bool ok = (f < A_VEC) & (i0 + row < p.K) & (pix0 + piece * 8 < pix_end);
                 a_vec[it] = *reinterpret_cast<const uint4*>(
-                    dy + (ok ? (n0 * p.K + i0 + row) * p.PQ + pq0 + piece * 8 : 0));
+                    dy + (ok ? n0 * p.dy_ns + (i0 + row) * p.PQ + pq0 + piece * 8 : 0));
                 a_ok = ok ? (a_ok | (1u << it)) : (a_ok & ~(1u << it));
             }
         } else {
             a_ok = 0u;
-            const int a_base = n * p.K * p.PQ + pq;
+            const int a_base = n * p.dy_ns + pq;
             if (A_BUF) {
                 const unsigned a_pix = pv ? (unsigned)a_base * 2u : 0x80000000u;
 #pragma unroll
@@ -434,7 +434,7 @@ __global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradPar
         }
         b_ok = 0u;
         const int hb = pp * p.sh - p.ph + tw.tap_r, wb = qq * p.sw - p.pw + tw.tap_s;
-        const int b_base = n * p.C * p.HW + hb * p.W + wb;
+        const int b_base = n * p.x_ns + hb * p.W + wb;
         const bool in = pv & ((unsigned)hb < (unsigned)p.H) & ((unsigned)wb < (unsigned)p.W);
         if (B_TWO_PART) {
             const unsigned b_pix = (TAP ? in : pv) ? (unsigned)b_base * 2u : 0x80000000u;
@@ -801,11 +801,13 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     p.div_rs = make_fastdiv(p.RS); p.div_s = make_fastdiv(g.S);
     p.chunk = plan.chunk; p.tiles_i = plan.tiles_i; p.tiles_j = plan.tiles_j; p.splits = plan.splits;
     p.c_tiles = plan.c_tiles;
+    p.x_ns = g.x_ns; p.dy_ns = g.y_ns;
     p.out = (float*)ws;
     {
         // raw-buffer loads: two-part offsets need both tensors below 2^30 bytes
         const int es = dtype == PURINE_F32 ? 4 : 2;
-        const long long xb = (long long)g.N * g.C * p.HW * es, dyb = (long long)p.M * g.K * es;
+        const long long xb = ((long long)(g.N - 1) * g.x_ns + (long long)g.C * p.HW) * es;
+        const long long dyb = ((long long)(g.N - 1) * g.y_ns + (long long)g.K * p.PQ) * es;
         const bool ok = xb < (1LL << 30) && dyb < (1LL << 30) && !buffer_loads_disabled();
         p.x_bytes = ok ? (unsigned)xb : 0u;
         p.dy_bytes = ok ? (unsigned)dyb : 0u;

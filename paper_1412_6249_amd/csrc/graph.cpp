@@ -51,14 +51,41 @@ struct purine_graph {
 
 namespace {
 
-size_t tensor_bytes(const purine_tensor& t) {
+size_t elem_size(const purine_tensor& t) { return t.dtype == PURINE_BF16 ? 2 : 4; }
+size_t image_bytes(const purine_tensor& t) {
     size_t n = 1;
-    for (int i = 0; i < t.ndim; ++i) n *= (size_t)t.dim[i];
-    return n * (t.dtype == PURINE_BF16 ? 2 : 4);
+    for (int i = 1; i < t.ndim; ++i) n *= (size_t)t.dim[i];
+    return n * elem_size(t);
+}
+// bytes between consecutive images: more than one image only for a channel-slice view
+size_t stride_bytes(const purine_tensor& t) {
+    return (t.ndim == 4 && t.nstride != 0) ? (size_t)t.nstride * elem_size(t) : image_bytes(t);
+}
+// bytes from the first to one past the last element
+size_t tensor_bytes(const purine_tensor& t) {
+    return ((size_t)t.dim[0] - 1) * stride_bytes(t) + image_bytes(t);
 }
 
-struct Range { uintptr_t lo, hi; };
-bool hit(const Range& a, const Range& b) { return a.lo < b.hi && b.lo < a.hi; }
+// Storage touched by one operand: [lo, hi), and for a channel-slice view the bytes per image and
+// the distance between images (0 for anything dense).
+struct Range { uintptr_t lo, hi; size_t image = 0, stride = 0; };
+Range range_of(const purine_tensor& t) {
+    Range r{(uintptr_t)t.data, (uintptr_t)t.data + tensor_bytes(t)};
+    if (stride_bytes(t) != image_bytes(t)) { r.image = image_bytes(t); r.stride = stride_bytes(t); }
+    return r;
+}
+// Do the two share a byte? Exact for dense ranges; two views with the same distance between images
+// (channel slices of one buffer) are compared per image, modulo that distance; otherwise the spans
+// decide (conservative).
+bool hit(const Range& a, const Range& b) {
+    if (!(a.lo < b.hi && b.lo < a.hi)) return false;
+    if (a.stride != 0 && a.stride == b.stride) {
+        const size_t s = a.stride;
+        const size_t d = a.lo >= b.lo ? (a.lo - b.lo) % s : (s - (b.lo - a.lo) % s) % s;   // (a.lo - b.lo) mod s
+        return d < b.image || s - d < a.image;
+    }
+    return true;
+}
 
 bool arity_ok(int kind, int n_in, int n_out, float beta) {
     const int extra = beta != 0.0f ? 1 : 0;
@@ -182,6 +209,7 @@ int purine_graph_add_tensor(purine_graph* g, const purine_tensor* t, const char*
     for (int i = 0; i < t->ndim; ++i)
         if (t->dim[i] < 1) return PURINE_E_SHAPE;
     if (t->dtype != PURINE_F32 && t->dtype != PURINE_BF16 && t->dtype != PURINE_I32) return PURINE_E_DTYPE;
+    if (t->nstride != 0 && (t->ndim != 4 || t->nstride < t->dim[1] * t->dim[2] * t->dim[3])) return PURINE_E_SHAPE;
     purine_graph::Tensor v;
     v.desc = *t;
     if (name) v.name = name;
@@ -279,11 +307,11 @@ int purine_graph_validate(purine_graph* g) {
         if (op.kind == PURINE_OP_HOST_NOP) continue;   // touches no device storage
         for (int t : op.in) {
             const auto& d = g->tensors[t].desc;
-            if (d.data) touches.push_back({a, {(uintptr_t)d.data, (uintptr_t)d.data + tensor_bytes(d)}, false});
+            if (d.data) touches.push_back({a, range_of(d), false});
         }
         for (int t : op.out) {
             const auto& d = g->tensors[t].desc;
-            if (d.data) touches.push_back({a, {(uintptr_t)d.data, (uintptr_t)d.data + tensor_bytes(d)}, true});
+            if (d.data) touches.push_back({a, range_of(d), true});
         }
         if (op.attrs.ws && op.attrs.ws_bytes)
             touches.push_back({a, {(uintptr_t)op.attrs.ws, (uintptr_t)op.attrs.ws + op.attrs.ws_bytes}, true});
@@ -407,6 +435,7 @@ int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b) {
     if (!A.data || !B.data) return PURINE_E_NULL;
     void* const pa = A.data;
     void* const pb = B.data;
+    if (A.nstride != 0 || B.nstride != 0) return PURINE_E_LAYOUT;   // whole buffers only, not channel slices
     const Range ra{(uintptr_t)pa, (uintptr_t)pa + tensor_bytes(A)}, rb{(uintptr_t)pb, (uintptr_t)pb + tensor_bytes(B)};
     if (hit(ra, rb)) return PURINE_E_LAYOUT;
     // The exchange renames two storage ranges. It leaves the set of conflicting operator pairs as
@@ -416,7 +445,7 @@ int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b) {
         return (!hit(r, ra) || (r.lo == ra.lo && r.hi == ra.hi)) && (!hit(r, rb) || (r.lo == rb.lo && r.hi == rb.hi));
     };
     for (const auto& t : g->tensors)
-        if (t.desc.data && !clean({(uintptr_t)t.desc.data, (uintptr_t)t.desc.data + tensor_bytes(t.desc)})) return PURINE_E_LAYOUT;
+        if (t.desc.data && !clean(range_of(t.desc))) return PURINE_E_LAYOUT;
     for (const auto& op : g->ops)
         if (op.attrs.ws && op.attrs.ws_bytes) {
             const Range r{(uintptr_t)op.attrs.ws, (uintptr_t)op.attrs.ws + op.attrs.ws_bytes};

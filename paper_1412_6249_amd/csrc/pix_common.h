@@ -75,7 +75,10 @@ struct PixParams {
     const void* mask;   // same extents and dtype as out: ReLU output whose gradient this pass produces
     int relu;
     int tiles_i, tiles_pix;
-    unsigned in_bytes;   // size of the gathered tensor when the fp32 tap kernels may read it as a raw buffer, else 0
+    unsigned in_bytes;   // span of the gathered tensor when the fp32 tap kernels may read it as a raw buffer, else 0
+    // elements between consecutive images of the gathered and of the produced tensor (the mask shares
+    // the latter): Ci*Hi*Wi and the dense image size of `out` unless they are channel-slice views
+    int in_ns, out_ns;
 };
 
 // The fused forward kernels stage their row tile's bias values in LDS at kernel start (zero past the
@@ -99,7 +102,7 @@ struct TileAddr {
     int obase, hb, wb;
     __device__ __forceinline__ TileAddr(const PixParams& p_, int n, int rem) : p(p_), hb(0), wb(0) {
         if (!D2S) {
-            obase = n * p.Co * p.HoWo + rem;
+            obase = n * p.out_ns + rem;
         } else {
             // depth-to-space: row i = (c, a, b) of coarse pixel (n, hq, wq) is
             // dx[n, c, hq*sh + a - ph, wq*sw + b - pw]
@@ -107,7 +110,7 @@ struct TileAddr {
             const int wq = rem - hq * p.Wo;
             hb = (hq + p.hq_min) * p.sh - p.ph;
             wb = (wq + p.wq_min) * p.sw - p.pw;
-            obase = n * p.C * p.H * p.W;
+            obase = n * p.out_ns;
         }
     }
     // element offset of row i (0 when the row or position does not exist) and whether it exists

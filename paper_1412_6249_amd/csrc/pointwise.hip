@@ -150,6 +150,32 @@ __global__ __launch_bounds__(TPB) void relu_fwd_kernel(const T* x, T* y, size_t 
         stf<T>(y, i, v > 0.0f ? v : 0.0f);
     }
 }
+// ReLU and its gradient on channel-slice views (fp32): grid.y = image, each image a dense run of
+// `run` elements at its own distance between images. VEC: run and the distances are multiples of 4.
+template <bool BWD, bool VEC>
+__global__ __launch_bounds__(TPB) void relu_view_kernel(const float* x, const float* dy, float* out,
+                                                        int run, size_t x_ns, size_t dy_ns, size_t out_ns) {
+    const size_t n = blockIdx.y;
+    const float* xi = x + n * x_ns;
+    const float* gi = BWD ? dy + n * dy_ns : nullptr;
+    float* oi = out + n * out_ns;
+    const int t0 = blockIdx.x * TPB + threadIdx.x, stride = gridDim.x * TPB;
+    if (VEC) {
+        for (int i = t0; i < run / 4; i += stride) {
+            const float4 v = reinterpret_cast<const float4*>(xi)[i];
+            float4 g = BWD ? reinterpret_cast<const float4*>(gi)[i] : v;
+            g.x = v.x > 0.0f ? g.x : 0.0f; g.y = v.y > 0.0f ? g.y : 0.0f;
+            g.z = v.z > 0.0f ? g.z : 0.0f; g.w = v.w > 0.0f ? g.w : 0.0f;
+            reinterpret_cast<float4*>(oi)[i] = g;
+        }
+    } else {
+        for (int i = t0; i < run; i += stride) {
+            const float v = xi[i];
+            oi[i] = v > 0.0f ? (BWD ? gi[i] : v) : 0.0f;
+        }
+    }
+}
+
 // ---- SGD update: new_w = w - lr * dw (one fused multiply-add in fp32 per element) ---------------
 // Packets of the parameter tensor (4 floats or 8 bfloat16) against 4-float packets of the fp32
 // gradient. new_w may be w itself: every element is read before it is written by the same lane.
@@ -422,6 +448,21 @@ hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStre
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, (size_t)n),
              hipLaunchKernelGGL(relu_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, (size_t)n));
+    return hipGetLastError();
+}
+
+hipError_t launch_relu_view(bool bwd, const float* x, const float* dy, float* out, int N, int run,
+                            int64_t x_ns, int64_t dy_ns, int64_t out_ns, hipStream_t st) {
+    const bool vec = run % 4 == 0 && x_ns % 4 == 0 && dy_ns % 4 == 0 && out_ns % 4 == 0;
+    dim3 grid(blocks_for((size_t)(vec ? run / 4 : run), 64), (unsigned)N);
+    if (N > 65535) return hipErrorInvalidValue;
+    ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
+#define RV(B, V) hipLaunchKernelGGL((relu_view_kernel<B, V>), grid, dim3(TPB), 0, st, x, dy, out, run, \
+                                    (size_t)x_ns, (size_t)dy_ns, (size_t)out_ns)
+    if (bwd) { if (vec) RV(true, true); else RV(true, false); }
+    else     { if (vec) RV(false, true); else RV(false, false); }
+#undef RV
     return hipGetLastError();
 }
 

@@ -171,6 +171,24 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_sgd_update, w, wd, nw, float("inf"), stream=s) == -8
     assert status(pa.purine_sgd_update, w, wd, binding.raw_desc(fake + 0x100000 + 16, F32, (4, 3, 3, 3)), 0.1, stream=s) == -4  # partial overlap with w
     assert status(pa.purine_sgd_update, w, wd, wd, 0.1, stream=s) == -4                # new_w is dw
+    # channel-slice views: x is channels 4..6 of a [2, 12, 8, 8] buffer
+    xv = binding.raw_desc(fake + 4 * 64 * 4, F32, (2, 3, 8, 8), nstride=12 * 64)
+    assert status(pa.purine_conv_bwd_data, d, y, w, xv, stream=s) == -5                # accepted up to the workspace
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, F32, (2, 3, 8, 8), nstride=3 * 64 - 4), w, y, stream=s) == -2
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, F32, (2, 3, 8, 8), nstride=12 * 64 + 2), w, y, stream=s) == -4
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, BF16, (2, 3, 8, 8), nstride=12 * 64),
+                  binding.raw_desc(fake + 0x100000, BF16, (4, 3, 3, 3)), binding.raw_desc(fake + 0x200000, BF16, (2, 4, 8, 8)), stream=s) == -4
+    yv = binding.raw_desc(fake + 0x200000, F32, (2, 4, 8, 8), nstride=16 * 64)
+    assert status(pa.purine_bias_fwd, binding.raw_desc(fake + 0x400000, F32, (4,)), yv, stream=s) == -4   # dense only
+    assert status(pa.purine_bias_bwd, yv, db, stream=s) == -4
+    assert status(pa.purine_conv_bwd_data_relu, d, y, w, x, xv, stream=s) == -4        # mask and dx differ in nstride
+    # two slices of one buffer: disjoint channel ranges do not alias, overlapping ones do
+    lo = binding.raw_desc(fake, F32, (2, 4, 8, 8), nstride=16 * 64)
+    hi = binding.raw_desc(fake + 4 * 64 * 4, F32, (2, 4, 8, 8), nstride=16 * 64)
+    mid = binding.raw_desc(fake + 2 * 64 * 4, F32, (2, 4, 8, 8), nstride=16 * 64)
+    assert status(pa.purine_relu_fwd, lo, mid, stream=s) == -4
+    assert status(pa.purine_relu_bwd, lo, hi, mid, stream=s) == -4
+    assert status(pa.purine_relu_fwd, lo, binding.raw_desc(fake, F32, (2, 4, 8, 8)), stream=s) == -4   # same start, other stride
     big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
     assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
     assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8

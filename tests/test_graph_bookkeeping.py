@@ -260,3 +260,46 @@ def test_swap_storage_and_iteration_bookkeeping():
     with pytest.raises(pa.PurineError):
         pa.purine_graph_iterate(g, -1, [])
     pa.purine_graph_destroy(g)
+
+
+def test_channel_slice_views_in_the_hazard_analysis():
+    """Two operators that write disjoint channel slices of one buffer (same distance between
+    images) do not conflict; overlapping slices, or a slice against the whole buffer, do."""
+    dims, ns = (2, 4, 4, 4), 16 * 16                       # 4 of 16 channels, 16 elements per channel
+    base = 0x20000
+
+    def build(off_a, off_b, whole_reader=False):
+        g = pa.purine_graph_create()
+        x = pa.purine_graph_add_tensor(g, binding.raw_desc(0x1000, F32, dims), "x")
+        a = pa.purine_graph_add_tensor(g, binding.raw_desc(base + off_a * 64, F32, dims, nstride=ns), "a")
+        b = pa.purine_graph_add_tensor(g, binding.raw_desc(base + off_b * 64, F32, dims, nstride=ns), "b")
+        pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [x], [a], 0)
+        pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [x], [b], 1)
+        if whole_reader:
+            whole = pa.purine_graph_add_tensor(g, binding.raw_desc(base, F32, (2, 16, 4, 4)), "whole")
+            z = pa.purine_graph_add_tensor(g, binding.raw_desc(0x90000, F32, (2, 16, 4, 4)), "z")
+            pa.purine_graph_add_op(g, pa.OP_RELU_FWD, [whole], [z], 2)
+        return g
+
+    g = build(0, 4)                                        # channels 0..3 and 4..7
+    pa.purine_graph_validate(g)
+    pa.purine_graph_destroy(g)
+    g = build(0, 12)                                       # first and last slice
+    pa.purine_graph_validate(g)
+    pa.purine_graph_destroy(g)
+    for offs in ((0, 2), (4, 4), (8, 5)):                  # overlapping channel ranges
+        g = build(*offs)
+        with pytest.raises(pa.PurineError) as e:
+            pa.purine_graph_validate(g)
+        assert e.value.status == -6
+        pa.purine_graph_destroy(g)
+    g = build(0, 4, whole_reader=True)                     # an unordered reader of the whole buffer
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_validate(g)
+    assert e.value.status == -6
+    pa.purine_graph_destroy(g)
+    g = pa.purine_graph_create()                           # a view's nstride below its image size
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_add_tensor(g, binding.raw_desc(base, F32, dims, nstride=8))
+    assert e.value.status == -2
+    pa.purine_graph_destroy(g)
