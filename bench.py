@@ -34,7 +34,7 @@ MEASURED_TRAFFIC_BYTES = {
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
               5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
               10: "concat_bwd", 11: "sum", 13: "conv_fwd_bias_relu", 14: "conv_bwd_data_relu",
-              15: "conv_bwd_weight_bias"}
+              15: "conv_bwd_weight_bias", 16: "sgd_update", 17: "alias"}
 
 
 def cpu_baseline(cfg, budget_s=15.0):
@@ -104,6 +104,10 @@ def main():
     ap.add_argument("--single-stream", action="store_true", help="all operators on one thread id")
     ap.add_argument("--unfused", action="store_true",
                     help="separate Bias / ReLU / ReLU-gradient operators instead of the fused conv vertices")
+    ap.add_argument("--no-merge-1x1", action="store_true",
+                    help="config 3: keep the three 1x1 convolutions on the module input as separate operators "
+                         "and the Concat copies (default: one merged operator, concatenation by address "
+                         "through channel-slice views)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-every", type=int, default=4,
                     help="bracket the dominant kernel (which then runs alone) on every n-th timed step")
@@ -121,7 +125,8 @@ def main():
 
     cfg = args.config
     torch.cuda.set_device(0)
-    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused)
+    merge = cfg == 3 and not args.no_merge_1x1 and not args.unfused
+    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, merge_1x1=merge)
     # Warm-up and one step per operator with that operator's main kernel bracketed (twice, keeping
     # the shorter): the per-operator table, and which kernel dominates. These steps run serially
     # (every operator alone on the device), so that each bracket measures its kernel and so that a
@@ -132,6 +137,9 @@ def main():
         gb.run()
     warm_ms = {}
     for op in gb.ops:
+        if op[1] in (12, 17):          # host and alias operators launch nothing
+            warm_ms[op[0]] = 0.0
+            continue
         best = float("inf")
         for _ in range(2):
             pa.purine_graph_time_only(gb.g, op[0])
@@ -220,7 +228,7 @@ def main():
     # operator per parameter tensor and the swap of old and new parameters, iterated natively
     gb.close()
     gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused,
-                        first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6)
+                        first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6, merge_1x1=merge)
     gb.iterate(max(2, args.warmup))
     torch.cuda.synchronize()
     s0 = time.perf_counter()
@@ -244,7 +252,8 @@ def main():
         "config": {"workload": WORKLOAD_NAMES[cfg], "conv_gflop_per_step": round(flop / 1e9, 2),
                    "executor": "bi-graph, %s, %s" % ("1 stream" if args.single_stream else "3+ streams",
                                                       "separate bias/relu ops" if args.unfused
-                                                      else "bias+relu fused into conv vertices"),
+                                                      else "bias+relu fused into conv vertices"
+                                                      + (", merged 1x1 + concat by address" if merge else "")),
                    "frac_of_mfma_peak": round(flop / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[dtype], 4)},
         "roofline": roofline,
     }

@@ -209,8 +209,16 @@ typedef enum {
     PURINE_OP_CONV_FWD_BIAS_RELU = 13, /* in: x, w, b     out: y   (attrs.relu selects the ReLU)    */
     PURINE_OP_CONV_BWD_DATA_RELU = 14, /* in: dy, w, act [, dx]  out: dx'                           */
     PURINE_OP_CONV_BWD_WEIGHT_BIAS = 15, /* in: x, dy [, dw, db]  out: dw', db'                      */
-    PURINE_OP_SGD_UPDATE = 16          /* in: w, dw           out: new_w   (attrs.lr)                */
+    PURINE_OP_SGD_UPDATE = 16,         /* in: w, dw           out: new_w   (attrs.lr)                */
+    PURINE_OP_ALIAS = 17               /* in: 1..64 tensors   out: 1..64 tensors inside their storage */
 } purine_op_kind;
+
+/* PURINE_OP_ALIAS does no device work. It gives storage that other operators have written a tensor
+ * vertex of its own: channel slices of a buffer one operator filled (one input, several outputs),
+ * or the buffer that several operators filled slice by slice (several inputs, one output: the
+ * concatenation, with no copy). Every output must lie inside the span of the inputs
+ * (PURINE_E_LAYOUT from purine_graph_add_op otherwise). It fires like a device operator: its
+ * outputs become ready, in stream order, once all its inputs are. */
 
 typedef struct {
     purine_conv_desc conv;   /* conv ops                                          */

@@ -21,7 +21,7 @@ PURINE_CONV_FWD, PURINE_CONV_BWD_DATA, PURINE_CONV_BWD_WEIGHT, PURINE_CONV_BWD_W
 OP_CONV_FWD, OP_BIAS_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_BIAS_BWD = 0, 1, 2, 3, 4
 OP_RELU_FWD, OP_RELU_BWD, OP_MAXPOOL_FWD, OP_MAXPOOL_BWD = 5, 6, 7, 8
 OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
-OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS, OP_SGD_UPDATE = 13, 14, 15, 16
+OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS, OP_SGD_UPDATE, OP_ALIAS = 13, 14, 15, 16, 17
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",

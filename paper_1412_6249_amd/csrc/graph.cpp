@@ -107,6 +107,7 @@ bool arity_ok(int kind, int n_in, int n_out, float beta) {
         case PURINE_OP_CONV_BWD_DATA_RELU: return n_in == 3 + extra && n_out == 1;
         case PURINE_OP_CONV_BWD_WEIGHT_BIAS: return n_in == 2 + 2 * extra && n_out == 2;
         case PURINE_OP_SGD_UPDATE: return n_in == 2 && n_out == 1;
+        case PURINE_OP_ALIAS: return n_in >= 1 && n_in <= 64 && n_out >= 1 && n_out <= 64;
         default: return false;
     }
 }
@@ -152,6 +153,8 @@ int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
         case PURINE_OP_BIAS_BWD:
             if (a.beta != 0.0f && T(op.in[1])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
             return purine_bias_bwd(T(op.in[0]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_ALIAS:
+            return PURINE_OK;   // names existing storage; ordering is all it contributes
         case PURINE_OP_SGD_UPDATE:
             return purine_sgd_update(T(op.in[0]), T(op.in[1]), T(op.out[0]), a.lr, st);
         case PURINE_OP_RELU_FWD:
@@ -241,6 +244,23 @@ int purine_graph_add_op(purine_graph* g, int op_kind, const purine_op_attrs* att
             if (out_ids[j] == out_ids[i]) return PURINE_E_GRAPH;
         op.out.push_back(out_ids[i]);
     }
+    if (op_kind == PURINE_OP_ALIAS) {
+        // every output lies inside the span of the inputs
+        uintptr_t lo = UINTPTR_MAX, hi = 0;
+        for (int t : op.in) {
+            const purine_tensor& d = g->tensors[t].desc;
+            if (!d.data) return PURINE_E_NULL;
+            const Range r = range_of(d);
+            lo = r.lo < lo ? r.lo : lo;
+            hi = r.hi > hi ? r.hi : hi;
+        }
+        for (int t : op.out) {
+            const purine_tensor& d = g->tensors[t].desc;
+            if (!d.data) return PURINE_E_NULL;
+            const Range r = range_of(d);
+            if (r.lo < lo || r.hi > hi) return PURINE_E_LAYOUT;
+        }
+    }
     op.thread = thread_id;
     const int id = (int)g->ops.size();
     g->ops.push_back(op);
@@ -304,7 +324,7 @@ int purine_graph_validate(purine_graph* g) {
     std::vector<Touch> touches;
     for (int a = 0; a < no; ++a) {
         const auto& op = g->ops[a];
-        if (op.kind == PURINE_OP_HOST_NOP) continue;   // touches no device storage
+        if (op.kind == PURINE_OP_HOST_NOP || op.kind == PURINE_OP_ALIAS) continue;   // touch no device storage
         for (int t : op.in) {
             const auto& d = g->tensors[t].desc;
             if (d.data) touches.push_back({a, range_of(d), false});
@@ -368,7 +388,8 @@ int purine_graph_run(purine_graph* g) {
                     }
                 if (rc != PURINE_OK) break;
                 op.timed = false;
-                const bool timed_op = g->timing && (g->timing_only < 0 || g->timing_only == o);
+                const bool timed_op = g->timing && (g->timing_only < 0 || g->timing_only == o) &&
+                                      op.kind != PURINE_OP_ALIAS;   // launches nothing to bracket
                 const bool exclusive = g->serial || (g->timing && g->timing_only == o);
                 if (exclusive) {
                     // the one measured operator runs alone: its stream waits for everything issued so

@@ -76,13 +76,15 @@ class GraphBuilder:
         return oid
 
     # ---- layer-level wiring
-    def conv_forward(self, L, x, w, b, prefix, relu, thread=T_MAIN):
-        """x -> Conv -> Bias [-> ReLU]; returns the name of the layer output vertex."""
+    def conv_forward(self, L, x, w, b, prefix, relu, thread=T_MAIN, out=None):
+        """x -> Conv -> Bias [-> ReLU]; returns the name of the layer output vertex. `out` (fused
+        operators only): an already bound vertex, e.g. a channel slice of a larger buffer."""
         desc = B.conv_desc(L.stride, L.pad)
         ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_FWD, desc, L.x_shape, L.w_shape,
                                                           _pcode(L.dtype)))
         if self.fuse:
-            out = self.new(prefix + (".a" if relu else ".yb"), L.y_shape, L.dtype)
+            if out is None:
+                out = self.new(prefix + (".a" if relu else ".yb"), L.y_shape, L.dtype)
             self.op(B.OP_CONV_FWD_BIAS_RELU, [x, w, b], [out], thread,
                     B.op_attrs(conv=desc, ws=ws, relu=relu))
             if relu:
@@ -113,14 +115,17 @@ class GraphBuilder:
         self.conv_records.append(rec)
         return out, rec
 
-    def conv_backward(self, rec, dout, thread=T_MAIN, t_w=T_WGRAD, t_b=T_BGRAD, need_dx=True):
-        """dout is the gradient at the layer output (after ReLU if the layer has one)."""
+    def conv_backward(self, rec, dout, thread=T_MAIN, t_w=T_WGRAD, t_b=T_BGRAD, need_dx=True, dx=None,
+                      grad_in_place=False):
+        """dout is the gradient at the layer output (after ReLU if the layer has one). `dx`: an
+        already bound vertex to receive the input gradient (e.g. a channel slice of a larger buffer);
+        `grad_in_place`: the ReLU gradient overwrites dout whatever the builder's default."""
         L, p = rec["layer"], rec["prefix"]
         desc = B.conv_desc(L.stride, L.pad)
         dy = dout
         rec["relu_bwd_op"] = False
         if rec["relu"] and dout not in self.masked_grads:
-            dy = self.version(p + ".dyb", dout)
+            dy = self.bind(p + ".dyb", self.t[dout]) if grad_in_place else self.version(p + ".dyb", dout)
             self.op(B.OP_RELU_BWD, [rec["out"], dout], [dy], thread)
             rec["relu_bwd_op"] = True
         db = self.new(p + ".db", (L.K,), "f32")
@@ -136,9 +141,11 @@ class GraphBuilder:
             ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT, desc, L.x_shape,
                                                               L.w_shape, _pcode(L.dtype)))
             self.op(B.OP_CONV_BWD_WEIGHT, [rec["x"], dy], [dw], t_w, B.op_attrs(conv=desc, ws=ws))
-        dx = None
-        if need_dx:
-            dx = self.new(p + ".dx", L.x_shape, L.dtype)
+        if not need_dx:
+            dx = None
+        else:
+            if dx is None:
+                dx = self.new(p + ".dx", L.x_shape, L.dtype)
             ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_DATA, desc, L.x_shape,
                                                               L.w_shape, _pcode(L.dtype)))
             if self.fuse and rec["x"] in self.relu_outputs:
@@ -213,14 +220,80 @@ def _default_init(seed):
     return init
 
 
+def _build_inception_merged(gb, layers, src, params, multi_stream):
+    """The inception module with its three 1x1 convolutions on the module input merged into one
+    operator (filters stacked along K: 96 + 16 + 64 = 176 output channels) and the concatenation done
+    by address: every branch writes its channel slice of one activation buffer, and the gradients
+    live in a buffer with the same channel map, so neither Concat nor its inverse runs.
+
+    channel map of both buffers (368 channels):
+      [0:96] b2_reduce out | [96:112] b3_reduce out | [112:176] b1 out | [176:304] b2_3x3 out |
+      [304:336] b3_5x5 out | [336:368] b4_proj out
+    merged operator output = [0:176]; module output (concat order b1, b2, b3, b4) = [112:368]."""
+    from synth.configs import ConvLayer
+    b1, b2r, b2, b3r, b3, b4 = layers
+    N, HW = b1.N, (b1.H, b1.W)
+    th = (lambda i: i) if multi_stream else (lambda i: 0)
+    x = src("x", b1.x_shape, "f32", "x")
+    P = {L.name: params(L, L.name) for L in layers}          # same draw order as the plain graph
+    merged = ConvLayer("merged_1x1", N, b1.C, b1.H, b1.W, b2r.K + b3r.K + b1.K, 1, 1, 1, 0)
+    order = (b2r, b3r, b1)
+    w_m = gb.bind("merged_1x1.w", torch.cat([gb.t[P[L.name][0]] for L in order], 0).contiguous())
+    b_m = gb.bind("merged_1x1.b", torch.cat([gb.t[P[L.name][1]] for L in order], 0).contiguous())
+    act = torch.zeros((N, 368) + HW, dtype=torch.float32, device=gb.device)
+    grad = torch.zeros((N, 368) + HW, dtype=torch.float32, device=gb.device)
+    gb.t["act_buffer"], gb.t["grad_buffer"] = act, grad
+    sl = dict(m2=(0, 96), m3=(96, 112), o1=(112, 176), o2=(176, 304), o3=(304, 336), o4=(336, 368),
+              F=(0, 176), cat=(112, 368))
+    A = lambda k, name: gb.bind(name, act[:, sl[k][0]:sl[k][1]])
+    G = lambda k, name: gb.bind(name, grad[:, sl[k][0]:sl[k][1]])
+
+    # forward
+    F, rF = gb.conv_forward(merged, x, w_m, b_m, "merged_1x1", True, th(0), out=A("F", "merged_1x1.a"))
+    m2, m3, o1 = A("m2", "b2_reduce.a"), A("m3", "b3_reduce.a"), A("o1", "b1_1x1.a")
+    gb.op(B.OP_ALIAS, [F], [m2, m3, o1], th(0))               # the three slices of the merged output
+    for v in (m2, m3, o1):
+        gb.relu_outputs.add(v)
+    o2, r2 = gb.conv_forward(b2, m2, *P[b2.name], b2.name, True, th(1), out=A("o2", "b2_3x3.a"))
+    o3, r3 = gb.conv_forward(b3, m3, *P[b3.name], b3.name, True, th(2), out=A("o3", "b3_5x5.a"))
+    p4, rp = gb.maxpool_forward(x, b1.x_shape, "f32", 3, 1, 1, "pool", th(3))
+    o4, r4 = gb.conv_forward(b4, p4, *P[b4.name], b4.name, True, th(3), out=A("o4", "b4_proj.a"))
+    cat = A("cat", "cat")
+    gb.op(B.OP_ALIAS, [o1, o2, o3, o4], [cat], th(0))         # the concatenation: no copy
+
+    # backward: the output gradient arrives in the slice [112:368] of the gradient buffer
+    dcat = G("cat", "dout")
+    gb.t[dcat].copy_(gb.init_value("dout", (N, 256) + HW, "f32", "dy"))
+    d1, d2, d3, d4 = G("o1", "db1"), G("o2", "db2"), G("o3", "db3"), G("o4", "db4")
+    gb.op(B.OP_ALIAS, [dcat], [d1, d2, d3, d4], th(0))
+    tw3 = 4 if multi_stream else 0
+    dm2 = gb.conv_backward(r2, d2, th(1), tw3, tw3, dx=G("m2", "b2_3x3.dx"), grad_in_place=True)
+    dm3 = gb.conv_backward(r3, d3, th(2), tw3, tw3, dx=G("m3", "b3_5x5.dx"), grad_in_place=True)
+    dp4 = gb.conv_backward(r4, d4, th(3), tw3, tw3, grad_in_place=True)
+    dx4 = gb.maxpool_backward(rp, dp4, th(3))
+    d1m = gb.bind("b1_1x1.dyb", gb.t[d1])                     # b1's ReLU gradient, in place on its slice
+    gb.op(B.OP_RELU_BWD, [o1, d1], [d1m], th(0))
+    dF = G("F", "merged_1x1.dout")
+    gb.op(B.OP_ALIAS, [dm2, dm3, d1m], [dF], th(0))
+    gb.masked_grads.add(dF)                                   # every slice already carries its ReLU mask
+    dxF = gb.conv_backward(rF, dF, th(0), tw3, tw3)
+    dx = gb.new("dx", b1.x_shape, "f32")
+    gb.op(B.OP_SUM, [dxF, dx4], [dx], th(0))                  # gradient fan-in, fixed order
+    gb.pool_records = [rp]
+    gb.slices = sl
+    gb.merged_order = [L.name for L in order]
+
+
 def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True,
-                   fuse=False, first_layer_dx=True, sgd_lr=None):
+                   fuse=False, first_layer_dx=True, sgd_lr=None, merge_1x1=False):
     """Builds the bi-graph of config `cfg` (1..5). `batch` overrides the batch size (tests).
     `init(name, shape, dtype, kind)` supplies source tensors (kind in x, w, b, dy); by default they
     are drawn on the device from the seed. `first_layer_dx=False` leaves out the backward-data
     operator of the layer that reads the images in the chained configs 2 and 4 (a training step
     does not need that gradient). `sgd_lr`: also add one SGD update operator per parameter tensor
-    (gb.iterate(n) then runs n training iterations). Returns the GraphBuilder; gb.run() performs one
+    (gb.iterate(n) then runs n training iterations). `merge_1x1` (config 3 with fused operators):
+    the module's three 1x1 convolutions on its input run as one operator and the concatenation is
+    done by address (channel-slice views), see _build_inception_merged. Returns the GraphBuilder; gb.run() performs one
     full forward + backward step."""
     init = init or _default_init(seed)
     layers = [l.with_batch(batch) if batch else l for l in CONV_LAYERS[cfg]]
@@ -257,6 +330,11 @@ def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, mult
         grad = src("dout", L3.y_shape, L3.dtype, "dy")
         for rec in reversed(recs):
             grad = gb.conv_backward(rec, grad, t_w=tw, t_b=tb, need_dx=first_layer_dx or rec is not recs[0])
+    elif cfg == 3 and merge_1x1:
+        if not (fuse and inplace):
+            raise ValueError("merge_1x1 needs the fused operators and in-place buffer versions")
+        gb.init_value = init
+        _build_inception_merged(gb, layers, src, params, multi_stream)
     elif cfg == 3:
         b1, b2r, b2, b3r, b3, b4 = layers
         N = b1.N

@@ -127,3 +127,88 @@ def test_inplace_and_multistream_graphs_give_identical_bits(cfg, batch):
     finally:
         ref.close()
         fast.close()
+
+
+def test_inception_with_merged_1x1_and_concat_by_address():
+    """Config 3 with the three 1x1 convolutions on the module input merged into one operator and the
+    concatenation done through channel-slice views: every operator against the oracle on the device
+    values it actually read (the output gradient is saved before the in-place ReLU gradients
+    overwrite their slices), and the whole step against the plain graph on the same parameters."""
+    from gpu_util import rel_l2, to_host
+    from paper_1412_6249_amd.layers import build_workload
+    plain = build_workload(3, batch=2, inplace=True, fuse=True)
+    gb = build_workload(3, batch=2, inplace=True, fuse=True, merge_1x1=True)
+    tol = 1e-5
+    try:
+        assert not any(op[1] in (9, 10) for op in gb.ops)             # no Concat operator either way
+        dout0 = to_host(gb.t["dout"]).copy()
+        assert np.array_equal(dout0, to_host(plain.t["dout"]))
+        plain.run()
+        gb.run()
+        legal_order(gb)
+        H = lambda name: to_host(gb.t[name])
+        recs = {r["prefix"]: r for r in gb.conv_records}
+        sl = gb.slices
+        x = H("x")
+        # merged forward and its three slices
+        rF = recs["merged_1x1"]
+        w_m, b_m = H(rF["w"]), H(rF["b"])
+        F = H(rF["out"])
+        assert rel_l2(F, np.maximum(oracle.bias_fwd(oracle.conv_fwd(x, w_m, 1, 0), b_m), 0)) <= tol
+        assert np.array_equal(H("b2_reduce.a"), F[:, 0:96]) and np.array_equal(H("b3_reduce.a"), F[:, 96:112])
+        assert np.array_equal(H("b1_1x1.a"), F[:, 112:176])
+        for k, name in enumerate(gb.merged_order):                    # stacked filters = the branches' own
+            lo = sum(plain.t[n + ".w"].shape[0] for n in gb.merged_order[:k])
+            assert np.array_equal(w_m[lo:lo + plain.t[name + ".w"].shape[0]], to_host(plain.t[name + ".w"]))
+        # branch convolutions read slices and write slices
+        for p in ("b2_3x3", "b3_5x5", "b4_proj"):
+            r = recs[p]
+            L = r["layer"]
+            ref = np.maximum(oracle.bias_fwd(oracle.conv_fwd(H(r["x"]), H(r["w"]), L.stride, L.pad), H(r["b"])), 0)
+            assert rel_l2(H(r["out"]), ref) <= tol, p
+        cat = H("cat")
+        assert np.array_equal(cat, oracle.concat_channels([H("b1_1x1.a"), H("b2_3x3.a"), H("b3_5x5.a"), H("b4_proj.a")]))
+        assert rel_l2(cat, to_host(plain.t["cat"])) <= tol
+        # backward of the branches: in-place ReLU gradient on the slice, then the two conv gradients
+        first = {"b1_1x1": 0, "b2_3x3": 64, "b3_5x5": 192, "b4_proj": 224}
+        for p in ("b2_3x3", "b3_5x5", "b4_proj"):
+            r = recs[p]
+            L = r["layer"]
+            dy = H(r["dy"])
+            assert np.array_equal(dy, oracle.relu_bwd(H(r["out"]), dout0[:, first[p]:first[p] + L.K])), p
+            xin = H(r["x"])
+            ref_dx = oracle.conv_bwd_data(dy, H(r["w"]), xin.shape, L.stride, L.pad)
+            if r["fused_bwd"]:
+                ref_dx = np.where(xin > 0, ref_dx, 0.0)
+            assert rel_l2(H(r["dx"]), ref_dx) <= tol, p
+            assert rel_l2(H(r["dw"]), oracle.conv_bwd_weight(xin, dy, H(r["w"]).shape, L.stride, L.pad)) <= tol, p
+            assert rel_l2(H(r["db"]), oracle.bias_bwd(dy)) <= tol, p
+        assert recs["b2_3x3"]["fused_bwd"] and recs["b3_5x5"]["fused_bwd"] and not recs["b4_proj"]["fused_bwd"]
+        assert np.array_equal(H("b1_1x1.dyb"), oracle.relu_bwd(H("b1_1x1.a"), dout0[:, 0:64]))
+        # merged backward on the 176-channel gradient slice
+        dF = H("merged_1x1.dout")
+        assert np.array_equal(dF[:, 0:96], H("b2_3x3.dx")) and np.array_equal(dF[:, 112:176], H("b1_1x1.dyb"))
+        assert rel_l2(H(rF["dw"]), oracle.conv_bwd_weight(x, dF, w_m.shape, 1, 0)) <= tol
+        assert rel_l2(H(rF["db"]), oracle.bias_bwd(dF)) <= tol
+        assert rel_l2(H(rF["dx"]), oracle.conv_bwd_data(dF, w_m, x.shape, 1, 0)) <= tol
+        assert rel_l2(H("dx"), oracle.fan_in_sum([H(rF["dx"]), H("pool.dx")])) <= 1e-6
+        check_pool_record(gb, gb.pool_records[0])
+        # against the plain graph (same parameters, same inputs): the whole step agrees
+        assert rel_l2(H("dx"), to_host(plain.t["dx"])) <= tol
+        lo = 0
+        for name in gb.merged_order:
+            k = plain.t[name + ".w"].shape[0]
+            assert rel_l2(H(rF["dw"])[lo:lo + k], to_host(plain.t[name + ".dw"])) <= tol, name
+            assert rel_l2(H(rF["db"])[lo:lo + k], to_host(plain.t[name + ".db"])) <= tol, name
+            lo += k
+        for p in ("b2_3x3", "b3_5x5", "b4_proj"):
+            assert rel_l2(H(recs[p]["dw"]), to_host(plain.t[p + ".dw"])) <= tol, p
+        # a second run gives the same bits (the gradient slices are rewritten from the saved source)
+        snap = {n: H(n).copy() for n in ("dx", rF["dw"], rF["db"], "b2_3x3.dw")}
+        gb.t["dout"].copy_(__import__("torch").from_numpy(dout0).to(gb.t["dout"].device))
+        gb.run()
+        for n, v in snap.items():
+            assert np.array_equal(H(n), v), n
+    finally:
+        gb.close()
+        plain.close()
