@@ -188,6 +188,46 @@ int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* ou
 int purine_sgd_update(const purine_tensor* w, const purine_tensor* dw, purine_tensor* new_w,
                       float lr, void* hip_stream);
 
+/* ---- grouped convolution and fully-connected layer (the other layer types of the networks the
+ *      paper's parallelisation schemes are discussed on, section 3): compositions of the operators
+ *      above, no kernels of their own ---------------------------------------------------------- */
+
+/* Grouped convolution: x [N,C,H,W], w [K, C/G, R, S], y [N,K,P,Q]; output channels
+ * g*K/G .. (g+1)*K/G-1 see only input channels g*C/G .. (g+1)*C/G-1. Runs the matching operator once
+ * per group on channel-slice views of x, y (dy, dx) and on the group's rows of w (b, dw, db), one
+ * group after the other on the stream, all sharing ws (purine_grouped_conv_workspace_bytes: one
+ * group's need). groups = 1 is the plain operator. For groups > 1: F32 only, and (C/G)*H*W,
+ * (K/G)*P*Q, (K/G)*(C/G)*R*S and K/G must be multiples of 4 so that every slice keeps the
+ * alignment rules (PURINE_E_LAYOUT otherwise). b and db may be NULL. x, y, dy, dx may themselves
+ * be views. */
+size_t purine_grouped_conv_workspace_bytes(int pass, const purine_conv_desc* desc, int groups,
+                                           const int64_t x_dim[4], const int64_t w_dim[4],
+                                           int32_t dtype);
+int purine_grouped_conv_fwd(const purine_conv_desc* desc, int groups, const purine_tensor* x,
+                            const purine_tensor* w, const purine_tensor* b, purine_tensor* y,
+                            int relu, void* ws, size_t ws_bytes, void* hip_stream);
+int purine_grouped_conv_bwd_data(const purine_conv_desc* desc, int groups, const purine_tensor* dy,
+                                 const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
+                                 size_t ws_bytes, void* hip_stream);
+int purine_grouped_conv_bwd_weight(const purine_conv_desc* desc, int groups, const purine_tensor* x,
+                                   const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
+                                   float beta, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* Fully-connected layer on dense 2-axis F32 matrices: x [N,C], w [K,C], b [K], y [N,K].
+ *   fwd:        y = x w^T (+ b)          dx = dy w          dw = beta*dw + dy^T x,  db = beta*db + column sums of dy
+ * Each pass is one of the convolution GEMM kernels on reinterpreted descriptors (a matrix
+ * [rows, features] is one image of `rows` channels whose pixel plane is the feature axis, or a 1x1
+ * filter bank): forward runs the weight-gradient kernel (split reduction over C, fixed-order
+ * second pass), backward-data the forward kernel, backward-weight the backward-data kernel.
+ * pass for the workspace query: PURINE_CONV_FWD, _BWD_DATA, _BWD_WEIGHT. b and db may be NULL. */
+size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K);
+int purine_fc_fwd(const purine_tensor* x, const purine_tensor* w, const purine_tensor* b,
+                  purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream);
+int purine_fc_bwd_data(const purine_tensor* dy, const purine_tensor* w, purine_tensor* dx, void* ws,
+                       size_t ws_bytes, void* hip_stream);
+int purine_fc_bwd_weight(const purine_tensor* x, const purine_tensor* dy, purine_tensor* dw,
+                         purine_tensor* db, float beta, void* ws, size_t ws_bytes, void* hip_stream);
+
 /* ---- bi-graph executor (paper sections 2, 2.1, 2.2 and the `thread` property of section 3) -- */
 
 typedef struct purine_graph purine_graph;
@@ -210,7 +250,13 @@ typedef enum {
     PURINE_OP_CONV_BWD_DATA_RELU = 14, /* in: dy, w, act [, dx]  out: dx'                           */
     PURINE_OP_CONV_BWD_WEIGHT_BIAS = 15, /* in: x, dy [, dw, db]  out: dw', db'                      */
     PURINE_OP_SGD_UPDATE = 16,         /* in: w, dw           out: new_w   (attrs.lr)                */
-    PURINE_OP_ALIAS = 17               /* in: 1..64 tensors   out: 1..64 tensors inside their storage */
+    PURINE_OP_ALIAS = 17,              /* in: 1..64 tensors   out: 1..64 tensors inside their storage */
+    PURINE_OP_FC_FWD = 18,             /* in: x, w, b         out: y                                 */
+    PURINE_OP_FC_BWD_DATA = 19,        /* in: dy, w           out: dx                                */
+    PURINE_OP_FC_BWD_WEIGHT = 20,      /* in: x, dy [, dw, db]  out: dw', db'                        */
+    PURINE_OP_GROUPED_CONV_FWD = 21,   /* in: x, w, b         out: y   (attrs.groups, attrs.relu)    */
+    PURINE_OP_GROUPED_CONV_BWD_DATA = 22,   /* in: dy, w [, dx]      out: dx'  (attrs.groups)        */
+    PURINE_OP_GROUPED_CONV_BWD_WEIGHT = 23  /* in: x, dy [, dw, db]  out: dw', db'  (attrs.groups)   */
 } purine_op_kind;
 
 /* PURINE_OP_ALIAS does no device work. It gives storage that other operators have written a tensor
@@ -228,6 +274,7 @@ typedef struct {
     void*  ws;               /* device scratch private to this operator           */
     size_t ws_bytes;
     float  lr;               /* PURINE_OP_SGD_UPDATE: step size                   */
+    int32_t groups;          /* grouped convolution ops (0 is read as 1)          */
 } purine_op_attrs;
 
 /* The graph owns only host bookkeeping plus the HIP streams and events it creates lazily (none for

@@ -197,3 +197,50 @@ def sgd_update(w, dw, lr):
     a modification of the parameters and applies it before the next one). The paper fixes no
     formula beyond that; the reading taken is the plain rule new = w - lr * dw, in fp64."""
     return np.asarray(w, dtype=np.float64) - float(lr) * np.asarray(dw, dtype=np.float64)
+
+
+# ---- fully-connected layer and grouped convolution (the other layer types of the networks that the
+# paper's section 3 discusses): plain definitions in fp64
+def fc_fwd(x, w, b=None):
+    """y[n,k] = sum_c x[n,c] * w[k,c] (+ b[k])."""
+    y = np.asarray(x, dtype=np.float64) @ np.asarray(w, dtype=np.float64).T
+    return y if b is None else y + np.asarray(b, dtype=np.float64)[None, :]
+
+
+def fc_bwd_data(dy, w):
+    """dx[n,c] = sum_k dy[n,k] * w[k,c]."""
+    return np.asarray(dy, dtype=np.float64) @ np.asarray(w, dtype=np.float64)
+
+
+def fc_bwd_weight(x, dy):
+    """dw[k,c] = sum_n dy[n,k] * x[n,c]; db[k] = sum_n dy[n,k]."""
+    dy64 = np.asarray(dy, dtype=np.float64)
+    return dy64.T @ np.asarray(x, dtype=np.float64), dy64.sum(axis=0)
+
+
+def _group_slices(C, K, groups):
+    cg, kg = C // groups, K // groups
+    return [(slice(g * cg, (g + 1) * cg), slice(g * kg, (g + 1) * kg)) for g in range(groups)]
+
+
+def grouped_conv_fwd(x, w, groups, stride=1, pad=0):
+    """Output channels of group g see only the input channels of group g; w is [K, C/groups, R, S]."""
+    x, w = _f32(x), _f32(w)
+    parts = [conv_fwd(x[:, cs], w[ks], stride, pad) for cs, ks in _group_slices(x.shape[1], w.shape[0], groups)]
+    return np.concatenate(parts, axis=1)
+
+
+def grouped_conv_bwd_data(dy, w, x_shape, groups, stride=1, pad=0):
+    dy, w = _f32(dy), _f32(w)
+    N, C, H, W = x_shape
+    parts = [conv_bwd_data(dy[:, ks], w[ks], (N, C // groups, H, W), stride, pad)
+             for cs, ks in _group_slices(C, w.shape[0], groups)]
+    return np.concatenate(parts, axis=1)
+
+
+def grouped_conv_bwd_weight(x, dy, w_shape, groups, stride=1, pad=0):
+    x, dy = _f32(x), _f32(dy)
+    K, Cg, R, S = w_shape
+    parts = [conv_bwd_weight(x[:, cs], dy[:, ks], (K // groups, Cg, R, S), stride, pad)
+             for cs, ks in _group_slices(x.shape[1], K, groups)]
+    return np.concatenate(parts, axis=0)

@@ -22,6 +22,8 @@ OP_CONV_FWD, OP_BIAS_FWD, OP_CONV_BWD_DATA, OP_CONV_BWD_WEIGHT, OP_BIAS_BWD = 0,
 OP_RELU_FWD, OP_RELU_BWD, OP_MAXPOOL_FWD, OP_MAXPOOL_BWD = 5, 6, 7, 8
 OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
 OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS, OP_SGD_UPDATE, OP_ALIAS = 13, 14, 15, 16, 17
+OP_FC_FWD, OP_FC_BWD_DATA, OP_FC_BWD_WEIGHT = 18, 19, 20
+OP_GROUPED_CONV_FWD, OP_GROUPED_CONV_BWD_DATA, OP_GROUPED_CONV_BWD_WEIGHT = 21, 22, 23
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
@@ -54,7 +56,7 @@ class purine_pool_desc(ctypes.Structure):
 class purine_op_attrs(ctypes.Structure):
     _fields_ = [("conv", purine_conv_desc), ("pool", purine_pool_desc), ("beta", ctypes.c_float),
                 ("relu", ctypes.c_int32), ("ws", ctypes.c_void_p), ("ws_bytes", ctypes.c_size_t),
-                ("lr", ctypes.c_float)]
+                ("lr", ctypes.c_float), ("groups", ctypes.c_int32)]
 
 
 if not os.path.exists(LIB_PATH):
@@ -76,6 +78,14 @@ _SIGS = {
     "purine_conv_bwd_data": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_bwd_weight": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_bwd_weight_bias": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_grouped_conv_workspace_bytes": (_sz, [ctypes.c_int, _D, ctypes.c_int, _i64p, _i64p, ctypes.c_int32]),
+    "purine_grouped_conv_fwd": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, _T, ctypes.c_int, _vp, _sz, _vp]),
+    "purine_grouped_conv_bwd_data": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_grouped_conv_bwd_weight": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_fc_workspace_bytes": (_sz, [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]),
+    "purine_fc_fwd": (ctypes.c_int, [_T, _T, _T, _T, _vp, _sz, _vp]),
+    "purine_fc_bwd_data": (ctypes.c_int, [_T, _T, _T, _vp, _sz, _vp]),
+    "purine_fc_bwd_weight": (ctypes.c_int, [_T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_fwd_bias_relu": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_int, _vp, _sz, _vp]),
     "purine_conv_bwd_data_relu": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_bias_fwd": (ctypes.c_int, [_T, _T, _vp]),
@@ -278,6 +288,58 @@ def purine_conv_bwd_weight_bias(desc, x, dy, dw, db, beta=0.0, ws=None, stream=N
                                             _stream(stream)), "purine_conv_bwd_weight_bias")
 
 
+def _opt(t):
+    return _ref(tensor_desc(t)) if t is not None else None
+
+
+def purine_grouped_conv_workspace_bytes(which, desc, groups, x_shape, w_shape, dtype):
+    return int(_lib.purine_grouped_conv_workspace_bytes(int(which), _ref(desc), int(groups), _dims(x_shape),
+                                                        _dims(w_shape), int(dtype)))
+
+
+def purine_grouped_conv_fwd(desc, groups, x, w, b, y, relu=False, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_grouped_conv_fwd(_ref(desc), int(groups), _ref(tensor_desc(x)), _ref(tensor_desc(w)), _opt(b),
+                                        _ref(tensor_desc(y)), 1 if relu else 0, p, n, _stream(stream)),
+           "purine_grouped_conv_fwd")
+
+
+def purine_grouped_conv_bwd_data(desc, groups, dy, w, dx, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_grouped_conv_bwd_data(_ref(desc), int(groups), _ref(tensor_desc(dy)), _ref(tensor_desc(w)),
+                                             _ref(tensor_desc(dx)), float(beta), p, n, _stream(stream)),
+           "purine_grouped_conv_bwd_data")
+
+
+def purine_grouped_conv_bwd_weight(desc, groups, x, dy, dw, db=None, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_grouped_conv_bwd_weight(_ref(desc), int(groups), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
+                                               _ref(tensor_desc(dw)), _opt(db), float(beta), p, n, _stream(stream)),
+           "purine_grouped_conv_bwd_weight")
+
+
+def purine_fc_workspace_bytes(which, N, C, K):
+    return int(_lib.purine_fc_workspace_bytes(int(which), int(N), int(C), int(K)))
+
+
+def purine_fc_fwd(x, w, b, y, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_fc_fwd(_ref(tensor_desc(x)), _ref(tensor_desc(w)), _opt(b), _ref(tensor_desc(y)), p, n,
+                              _stream(stream)), "purine_fc_fwd")
+
+
+def purine_fc_bwd_data(dy, w, dx, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_fc_bwd_data(_ref(tensor_desc(dy)), _ref(tensor_desc(w)), _ref(tensor_desc(dx)), p, n,
+                                   _stream(stream)), "purine_fc_bwd_data")
+
+
+def purine_fc_bwd_weight(x, dy, dw, db=None, beta=0.0, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.purine_fc_bwd_weight(_ref(tensor_desc(x)), _ref(tensor_desc(dy)), _ref(tensor_desc(dw)), _opt(db),
+                                     float(beta), p, n, _stream(stream)), "purine_fc_bwd_weight")
+
+
 def purine_sgd_update(w, dw, new_w, lr, stream=None):
     _check(_lib.purine_sgd_update(_ref(tensor_desc(w)), _ref(tensor_desc(dw)), _ref(tensor_desc(new_w)),
                                   float(lr), _stream(stream)), "purine_sgd_update")
@@ -367,8 +429,9 @@ def purine_graph_add_op(g, kind, in_ids, out_ids, thread_id=0, attrs=None):
     return rc
 
 
-def op_attrs(conv=None, pool=None, beta=0.0, ws=None, relu=False, lr=0.0):
+def op_attrs(conv=None, pool=None, beta=0.0, ws=None, relu=False, lr=0.0, groups=0):
     a = purine_op_attrs()
+    a.groups = int(groups)
     a.relu = 1 if relu else 0
     a.lr = float(lr)
     if conv is not None:

@@ -524,6 +524,205 @@ int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* ou
     return hip_status(e);
 }
 
+// ---- grouped convolution and fully-connected layer: compositions of the operators above -------
+
+namespace {
+
+// Channel slice [c0, c0 + count) of an NCHW tensor (dense or itself a view), as a view.
+purine_tensor channel_slice(const purine_tensor* t, int64_t c0, int64_t count) {
+    purine_tensor v = *t;
+    v.data = (char*)t->data + (size_t)(c0 * t->dim[2] * t->dim[3]) * elem_bytes(t->dtype);
+    v.dim[1] = count;
+    v.nstride = nstride_of(t);
+    return v;
+}
+// Rows [r0, r0 + count) of a dense tensor whose first axis is rows.
+purine_tensor row_slice(const purine_tensor* t, int64_t r0, int64_t count) {
+    purine_tensor v = *t;
+    int64_t per_row = 1;
+    for (int i = 1; i < t->ndim; ++i) per_row *= t->dim[i];
+    v.data = (char*)t->data + (size_t)(r0 * per_row) * elem_bytes(t->dtype);
+    v.dim[0] = count;
+    return v;
+}
+
+// Everything a grouped call needs to know before its first launch: extents divide by the group
+// count and every group's slices keep the alignment rules of views and dense tensors.
+int check_groups(int groups, const purine_tensor* x, const purine_tensor* w, const purine_tensor* y) {
+    int rc;
+    if (groups < 1) return PURINE_E_ARG;
+    if ((rc = check_tensor(x, 4, true)) || (rc = check_tensor(w, 4)) || (rc = check_tensor(y, 4, true))) return rc;
+    if (x->dim[1] % groups || w->dim[0] % groups || y->dim[1] != w->dim[0] || x->dim[1] / groups != w->dim[1])
+        return PURINE_E_SHAPE;
+    if (groups == 1) return PURINE_OK;
+    if (x->dtype != PURINE_F32) return PURINE_E_DTYPE;   // slices are views, and views are fp32
+    const int64_t cg = x->dim[1] / groups, kg = w->dim[0] / groups;
+    if ((cg * x->dim[2] * x->dim[3]) % 4 || (kg * y->dim[2] * y->dim[3]) % 4 ||
+        (kg * w->dim[1] * w->dim[2] * w->dim[3]) % 4 || kg % 4 || nstride_of(x) % 4 || nstride_of(y) % 4)
+        return PURINE_E_LAYOUT;
+    return PURINE_OK;
+}
+
+// 2-axis matrices of the fully-connected layer seen by the convolution operators: [rows, features]
+// as one image of `rows` channels whose pixel plane is the feature axis, or as a 1x1 filter bank.
+purine_tensor as_plane(const purine_tensor* t) {
+    purine_tensor v = *t;
+    v.ndim = 4; v.dim[0] = 1; v.dim[1] = t->dim[0]; v.dim[2] = 1; v.dim[3] = t->dim[1]; v.nstride = 0;
+    return v;
+}
+purine_tensor as_filter(const purine_tensor* t) {
+    purine_tensor v = *t;
+    v.ndim = 4; v.dim[0] = t->dim[0]; v.dim[1] = t->dim[1]; v.dim[2] = 1; v.dim[3] = 1; v.nstride = 0;
+    return v;
+}
+const purine_conv_desc kUnitConv{1, 1, 0, 0};
+
+int check_fc(const purine_tensor* x, const purine_tensor* w, const purine_tensor* y) {
+    int rc;
+    if ((rc = check_tensor(x, 2)) || (rc = check_tensor(w, 2)) || (rc = check_tensor(y, 2))) return rc;
+    if (x->dtype != PURINE_F32 || w->dtype != PURINE_F32 || y->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    if (x->dim[1] != w->dim[1] || y->dim[0] != x->dim[0] || y->dim[1] != w->dim[0]) return PURINE_E_SHAPE;
+    return PURINE_OK;
+}
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+}  // namespace
+
+size_t purine_grouped_conv_workspace_bytes(int pass, const purine_conv_desc* desc, int groups,
+                                           const int64_t x_dim[4], const int64_t w_dim[4], int32_t dtype) {
+    if (!x_dim || !w_dim || groups < 1 || x_dim[1] % groups || w_dim[0] % groups) return 0;
+    const int64_t xg[4] = {x_dim[0], x_dim[1] / groups, x_dim[2], x_dim[3]};
+    const int64_t wg[4] = {w_dim[0] / groups, w_dim[1], w_dim[2], w_dim[3]};
+    return purine_conv_workspace_bytes(pass, desc, xg, wg, dtype);
+}
+
+int purine_grouped_conv_fwd(const purine_conv_desc* desc, int groups, const purine_tensor* x,
+                            const purine_tensor* w, const purine_tensor* b, purine_tensor* y, int relu,
+                            void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_groups(groups, x, w, y))) return rc;
+    if (b && ((rc = check_tensor(b, 1)) || (b->dim[0] != w->dim[0] ? (rc = PURINE_E_SHAPE) : 0))) return rc;
+    const int64_t cg = x->dim[1] / groups, kg = w->dim[0] / groups;
+    for (int g = 0; g < groups; ++g) {
+        const purine_tensor xs = channel_slice(x, g * cg, cg), wsl = row_slice(w, g * kg, kg);
+        purine_tensor ys = channel_slice(y, g * kg, kg);
+        purine_tensor bs;
+        if (b) bs = row_slice(b, g * kg, kg);
+        if ((rc = conv_fwd_impl(desc, &xs, &wsl, b ? &bs : nullptr, &ys, relu, ws, ws_bytes, hip_stream))) return rc;
+    }
+    return PURINE_OK;
+}
+
+int purine_grouped_conv_bwd_data(const purine_conv_desc* desc, int groups, const purine_tensor* dy,
+                                 const purine_tensor* w, purine_tensor* dx, float beta, void* ws,
+                                 size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_groups(groups, dx, w, dy))) return rc;
+    const int64_t cg = dx->dim[1] / groups, kg = w->dim[0] / groups;
+    for (int g = 0; g < groups; ++g) {
+        const purine_tensor dys = channel_slice(dy, g * kg, kg), wsl = row_slice(w, g * kg, kg);
+        purine_tensor dxs = channel_slice(dx, g * cg, cg);
+        if ((rc = conv_bwd_data_impl(desc, &dys, &wsl, nullptr, &dxs, beta, ws, ws_bytes, hip_stream))) return rc;
+    }
+    return PURINE_OK;
+}
+
+int purine_grouped_conv_bwd_weight(const purine_conv_desc* desc, int groups, const purine_tensor* x,
+                                   const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
+                                   float beta, void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_groups(groups, x, dw, dy))) return rc;
+    if (db && ((rc = check_tensor(db, 1)) || (db->dim[0] != dw->dim[0] ? (rc = PURINE_E_SHAPE) : 0))) return rc;
+    const int64_t cg = x->dim[1] / groups, kg = dw->dim[0] / groups;
+    for (int g = 0; g < groups; ++g) {
+        const purine_tensor xs = channel_slice(x, g * cg, cg), dys = channel_slice(dy, g * kg, kg);
+        purine_tensor dws = row_slice(dw, g * kg, kg);
+        purine_tensor dbs;
+        if (db) dbs = row_slice(db, g * kg, kg);
+        if ((rc = conv_bwd_weight_impl(desc, &xs, &dys, &dws, db ? &dbs : nullptr, beta, ws, ws_bytes, hip_stream)))
+            return rc;
+    }
+    return PURINE_OK;
+}
+
+size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K) {
+    if (N < 1 || C < 1 || K < 1) return 0;
+    // one convolution geometry serves the three passes: a 1x1 filter bank [N, K] over the plane [1, K, 1, C]
+    const int64_t xd[4] = {1, K, 1, C}, wd[4] = {N, K, 1, 1};
+    switch (pass) {
+        case PURINE_CONV_FWD:   // y = x w^T through the weight-gradient kernel (split reduction over C)
+            return purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xd, wd, PURINE_F32);
+        case PURINE_CONV_BWD_DATA:   // dx = dy w through the forward kernel
+            return purine_conv_workspace_bytes(PURINE_CONV_FWD, &kUnitConv, xd, wd, PURINE_F32);
+        case PURINE_CONV_BWD_WEIGHT:
+        case PURINE_CONV_BWD_WEIGHT_BIAS: {   // dw = dy^T x through the backward-data kernel, db by BiasBwd
+            const int64_t dyd[4] = {N, K, 1, 1};
+            return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, PURINE_F32)) +
+                   purine_bias_bwd_workspace_bytes(dyd, PURINE_F32);
+        }
+        default: return 0;
+    }
+}
+
+int purine_fc_fwd(const purine_tensor* x, const purine_tensor* w, const purine_tensor* b, purine_tensor* y,
+                  void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_fc(x, w, y))) return rc;
+    if (b) {
+        if ((rc = check_tensor(b, 1))) return rc;
+        if (b->dtype != PURINE_F32) return PURINE_E_DTYPE;
+        if (b->dim[0] != w->dim[0]) return PURINE_E_SHAPE;
+        if (overlaps(b, y)) return PURINE_E_LAYOUT;
+    }
+    // y[n][k] = sum_c x[n][c] w[k][c]: the weight-gradient contraction with dy := x and x := w,
+    // both matrices as one image whose pixel plane is the feature axis c
+    const purine_tensor wp = as_plane(w), xp = as_plane(x);
+    purine_tensor yf = as_filter(y);
+    if ((rc = conv_bwd_weight_impl(&kUnitConv, &wp, &xp, &yf, nullptr, 0.0f, ws, ws_bytes, hip_stream))) return rc;
+    if (b)
+        return hip_status(launch_bias_rows((const float*)b->data, (float*)y->data, (int)y->dim[0], (int)y->dim[1],
+                                           (hipStream_t)hip_stream));
+    return PURINE_OK;
+}
+
+int purine_fc_bwd_data(const purine_tensor* dy, const purine_tensor* w, purine_tensor* dx, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_fc(dx, w, dy))) return rc;
+    // dx[n][c] = sum_k dy[n][k] w[k][c]: a 1x1 convolution of the plane w [K channels x C pixels] with
+    // the filter bank dy [N x K]
+    const purine_tensor wp = as_plane(w), dyf = as_filter(dy);
+    purine_tensor dxp = as_plane(dx);
+    return conv_fwd_impl(&kUnitConv, &wp, &dyf, nullptr, &dxp, 0, ws, ws_bytes, hip_stream);
+}
+
+int purine_fc_bwd_weight(const purine_tensor* x, const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
+                         float beta, void* ws, size_t ws_bytes, void* hip_stream) {
+    int rc;
+    if ((rc = check_fc(x, dw, dy)) || (rc = check_beta(beta))) return rc;
+    const int64_t xd[4] = {1, dw->dim[0], 1, dw->dim[1]}, wd[4] = {x->dim[0], dw->dim[0], 1, 1};
+    const size_t conv_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, PURINE_F32));
+    const purine_tensor dy4 = as_filter(dy);
+    if (db) {
+        if ((rc = check_tensor(db, 1))) return rc;
+        if (db->dtype != PURINE_F32) return PURINE_E_DTYPE;
+        if (db->dim[0] != dw->dim[0]) return PURINE_E_SHAPE;
+        if (overlaps(db, dy) || overlaps(db, x) || overlaps(db, dw)) return PURINE_E_LAYOUT;
+        if (!ws || ws_bytes < conv_ws + purine_bias_bwd_workspace_bytes(dy4.dim, PURINE_F32)) return PURINE_E_WORKSPACE;
+        if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+    }
+    // dw[k][c] = sum_n dy[n][k] x[n][c]: the backward-data contraction with dy := x (plane of N
+    // channels) and w := dy (filter bank [N x K])
+    const purine_tensor xp = as_plane(x);
+    purine_tensor dwp = as_plane(dw);
+    if ((rc = conv_bwd_data_impl(&kUnitConv, &xp, &dy4, nullptr, &dwp, beta, ws, ws_bytes < conv_ws ? ws_bytes : conv_ws,
+                                 hip_stream)))
+        return rc;
+    if (db)   // column sums of dy: BiasBwd on dy as [N, K, 1, 1]
+        return purine_bias_bwd(&dy4, db, beta, (char*)ws + conv_ws, ws_bytes - conv_ws, hip_stream);
+    return PURINE_OK;
+}
+
 // Tuning hook: force the tile shape of the forward / backward-data kernels (0, 0 = automatic).
 void purine_debug_force_tile(int bm, int bn) { force_pix_tile(bm, bn); }
 

@@ -136,6 +136,7 @@ hipError_t launch_bias_bwd(int dtype, const void* dy, float* db, float beta, int
 hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStream_t st);
 hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
                            hipStream_t st);
+hipError_t launch_bias_rows(const float* b, float* y, int N, int K, hipStream_t st);
 hipError_t launch_relu_view(bool bwd, const float* x, const float* dy, float* out, int N, int run,
                             int64_t x_ns, int64_t dy_ns, int64_t out_ns, hipStream_t st);
 hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* new_w, float lr,

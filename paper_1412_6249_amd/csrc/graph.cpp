@@ -108,6 +108,12 @@ bool arity_ok(int kind, int n_in, int n_out, float beta) {
         case PURINE_OP_CONV_BWD_WEIGHT_BIAS: return n_in == 2 + 2 * extra && n_out == 2;
         case PURINE_OP_SGD_UPDATE: return n_in == 2 && n_out == 1;
         case PURINE_OP_ALIAS: return n_in >= 1 && n_in <= 64 && n_out >= 1 && n_out <= 64;
+        case PURINE_OP_FC_FWD: return n_in == 3 && n_out == 1;
+        case PURINE_OP_FC_BWD_DATA: return n_in == 2 && n_out == 1;
+        case PURINE_OP_FC_BWD_WEIGHT: return n_in == 2 + 2 * extra && n_out == 2;
+        case PURINE_OP_GROUPED_CONV_FWD: return n_in == 3 && n_out == 1;
+        case PURINE_OP_GROUPED_CONV_BWD_DATA: return n_in == 2 + extra && n_out == 1;
+        case PURINE_OP_GROUPED_CONV_BWD_WEIGHT: return n_in == 2 + 2 * extra && n_out == 2;
         default: return false;
     }
 }
@@ -155,6 +161,26 @@ int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
             return purine_bias_bwd(T(op.in[0]), T(op.out[0]), a.beta, a.ws, a.ws_bytes, st);
         case PURINE_OP_ALIAS:
             return PURINE_OK;   // names existing storage; ordering is all it contributes
+        case PURINE_OP_FC_FWD:
+            return purine_fc_fwd(T(op.in[0]), T(op.in[1]), T(op.in[2]), T(op.out[0]), a.ws, a.ws_bytes, st);
+        case PURINE_OP_FC_BWD_DATA:
+            return purine_fc_bwd_data(T(op.in[0]), T(op.in[1]), T(op.out[0]), a.ws, a.ws_bytes, st);
+        case PURINE_OP_FC_BWD_WEIGHT:
+            if (a.beta != 0.0f && (T(op.in[2])->data != T(op.out[0])->data || T(op.in[3])->data != T(op.out[1])->data))
+                return PURINE_E_LAYOUT;
+            return purine_fc_bwd_weight(T(op.in[0]), T(op.in[1]), T(op.out[0]), T(op.out[1]), a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_GROUPED_CONV_FWD:
+            return purine_grouped_conv_fwd(&a.conv, a.groups ? a.groups : 1, T(op.in[0]), T(op.in[1]), T(op.in[2]),
+                                           T(op.out[0]), a.relu, a.ws, a.ws_bytes, st);
+        case PURINE_OP_GROUPED_CONV_BWD_DATA:
+            if (a.beta != 0.0f && T(op.in[2])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_grouped_conv_bwd_data(&a.conv, a.groups ? a.groups : 1, T(op.in[0]), T(op.in[1]), T(op.out[0]),
+                                                a.beta, a.ws, a.ws_bytes, st);
+        case PURINE_OP_GROUPED_CONV_BWD_WEIGHT:
+            if (a.beta != 0.0f && (T(op.in[2])->data != T(op.out[0])->data || T(op.in[3])->data != T(op.out[1])->data))
+                return PURINE_E_LAYOUT;
+            return purine_grouped_conv_bwd_weight(&a.conv, a.groups ? a.groups : 1, T(op.in[0]), T(op.in[1]), T(op.out[0]),
+                                                  T(op.out[1]), a.beta, a.ws, a.ws_bytes, st);
         case PURINE_OP_SGD_UPDATE:
             return purine_sgd_update(T(op.in[0]), T(op.in[1]), T(op.out[0]), a.lr, st);
         case PURINE_OP_RELU_FWD:

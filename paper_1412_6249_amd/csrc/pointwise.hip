@@ -176,6 +176,12 @@ __global__ __launch_bounds__(TPB) void relu_view_kernel(const float* x, const fl
     }
 }
 
+// ---- bias of a fully-connected layer: y[n][k] += b[k] on a dense [N][K] fp32 matrix --------------
+__global__ __launch_bounds__(TPB) void bias_rows_kernel(const float* __restrict__ b, float* y, int K, size_t n) {
+    const size_t stride = (size_t)gridDim.x * TPB;
+    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += stride) y[i] += b[i % (size_t)K];
+}
+
 // ---- SGD update: new_w = w - lr * dw (one fused multiply-add in fp32 per element) ---------------
 // Packets of the parameter tensor (4 floats or 8 bfloat16) against 4-float packets of the fp32
 // gradient. new_w may be w itself: every element is read before it is written by the same lane.
@@ -448,6 +454,13 @@ hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStre
     BY_DTYPE(dtype,
              hipLaunchKernelGGL(relu_fwd_kernel<float>, grid, dim3(TPB), 0, st, (const float*)x, (float*)y, (size_t)n),
              hipLaunchKernelGGL(relu_fwd_kernel<uint16_t>, grid, dim3(TPB), 0, st, (const uint16_t*)x, (uint16_t*)y, (size_t)n));
+    return hipGetLastError();
+}
+
+hipError_t launch_bias_rows(const float* b, float* y, int N, int K, hipStream_t st) {
+    const size_t n = (size_t)N * K;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(bias_rows_kernel, dim3(blocks_for(n)), dim3(TPB), 0, st, b, y, K, n);
     return hipGetLastError();
 }
 

@@ -109,6 +109,64 @@ def copy_calibration(mib, iters=5):
           % (n * 4, n * 4, iters))
 
 
+def time_whole(fn, iters, warmup=5):
+    """Whole-operator time (every kernel of a composed operator), events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(iters):
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        fn()
+        e.record()
+        torch.cuda.synchronize()
+        ms.append(s.elapsed_time(e))
+    ms.sort()
+    return ms[len(ms) // 2], ms[0]
+
+
+def bench_fc(N, C, K, iters, out=sys.stdout):
+    """The three passes of a fully-connected layer [N, C] x [K, C] (fp32)."""
+    dev = "cuda:0"
+    x, w, b = torch.rand(N, C, device=dev), torch.randn(K, C, device=dev) * 0.01, torch.zeros(K, device=dev)
+    dy = torch.rand(N, K, device=dev) * 2 - 1
+    y, dx = torch.empty(N, K, device=dev), torch.empty(N, C, device=dev)
+    dw, db = torch.empty(K, C, device=dev), torch.empty(K, device=dev)
+    ws = [torch.empty(max(256, B.purine_fc_workspace_bytes(p, N, C, K)), dtype=torch.uint8, device=dev) for p in (0, 1, 2)]
+    flop = 2.0 * N * C * K
+    w_bytes = 4.0 * K * C
+    passes = (("fc_fwd", lambda: B.purine_fc_fwd(x, w, b, y, ws=ws[0])),
+              ("fc_bwd_data", lambda: B.purine_fc_bwd_data(dy, w, dx, ws=ws[1])),
+              ("fc_bwd_weight", lambda: B.purine_fc_bwd_weight(x, dy, dw, db, ws=ws[2])))
+    for name, fn in passes:
+        med, best = time_whole(fn, iters)
+        out.write("fc %dx%d->%d  %-14s %8.4f ms (best %8.4f)  %7.2f TFLOP/s  %5.1f%% of f32 MFMA peak  weights at %6.0f GB/s\n"
+                  % (N, C, K, name, med, best, flop / med / 1e9, 100 * flop / med / 1e9 / PEAK["f32"], w_bytes / med / 1e6))
+
+
+def bench_grouped(L, groups, iters, out=sys.stdout):
+    """Grouped variant of a conv layer (fp32): the filter keeps C/groups input channels."""
+    dev = "cuda:0"
+    ws_shape = (L.K, L.C // groups, L.R, L.S)
+    x, w, b = torch.rand(L.x_shape, device=dev), torch.randn(ws_shape, device=dev) * 0.01, torch.zeros(L.K, device=dev)
+    dy = torch.rand(L.y_shape, device=dev) * 2 - 1
+    y, dx = torch.empty(L.y_shape, device=dev), torch.empty(L.x_shape, device=dev)
+    dw, db = torch.empty(ws_shape, device=dev), torch.empty(L.K, device=dev)
+    desc = B.conv_desc(L.stride, L.pad)
+    q = lambda which: torch.empty(max(256, B.purine_grouped_conv_workspace_bytes(which, desc, groups, L.x_shape, ws_shape,
+                                                                                 B.PURINE_F32)), dtype=torch.uint8, device=dev)
+    wsf, wsd, wsw = q(0), q(1), q(3)
+    flop = L.flop_per_pass / groups
+    passes = (("fwd+bias+relu", lambda: B.purine_grouped_conv_fwd(desc, groups, x, w, b, y, relu=True, ws=wsf)),
+              ("bwd_data", lambda: B.purine_grouped_conv_bwd_data(desc, groups, dy, w, dx, ws=wsd)),
+              ("bwd_weight+bias", lambda: B.purine_grouped_conv_bwd_weight(desc, groups, x, dy, dw, db, ws=wsw)))
+    for name, fn in passes:
+        med, best = time_whole(fn, iters)
+        out.write("%-8s groups=%d  %-16s %8.4f ms (best %8.4f)  %7.2f TFLOP/s  %5.1f%% of f32 MFMA peak\n"
+                  % (L.name, groups, name, med, best, flop / med / 1e9, 100 * flop / med / 1e9 / PEAK["f32"]))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=4)
@@ -120,9 +178,14 @@ def main():
                     help="force the forward / backward-data tile shape (tuning)")
     ap.add_argument("--copy-cal", type=int, default=0, metavar="MiB",
                     help="run only a plain device copy of this many MiB (counter calibration)")
+    ap.add_argument("--fc", default=None, metavar="N,C,K", help="time a fully-connected layer instead")
+    ap.add_argument("--groups", type=int, default=0, help="time the grouped variant of the selected layers")
     a = ap.parse_args()
     if a.copy_cal:
         copy_calibration(a.copy_cal)
+        return
+    if a.fc:
+        bench_fc(*[int(v) for v in a.fc.split(",")], a.iters)
         return
     if a.tile:
         B.purine_debug_force_tile(*[int(v) for v in a.tile.split(",")])
@@ -132,6 +195,9 @@ def main():
             continue
         if a.batch:
             L = L.with_batch(a.batch)
+        if a.groups:
+            bench_grouped(L, a.groups, a.iters)
+            continue
         bench_layer(L, ops, a.iters)
 
 

@@ -24,7 +24,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = declared_symbols()
-    assert len(names) == 41
+    assert len(names) == 49
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -189,6 +189,31 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_relu_fwd, lo, mid, stream=s) == -4
     assert status(pa.purine_relu_bwd, lo, hi, mid, stream=s) == -4
     assert status(pa.purine_relu_fwd, lo, binding.raw_desc(fake, F32, (2, 4, 8, 8)), stream=s) == -4   # same start, other stride
+    # grouped convolution and fully-connected compositions: rejected before any launch
+    xg = binding.raw_desc(fake, F32, (2, 8, 6, 6))
+    wg = binding.raw_desc(fake + 0x100000, F32, (8, 4, 3, 3))
+    yg = binding.raw_desc(fake + 0x200000, F32, (2, 8, 6, 6))
+    assert status(pa.purine_grouped_conv_bwd_data, d, 2, yg, wg, xg, stream=s) == -5            # needs scratch
+    assert status(pa.purine_grouped_conv_fwd, d, 3, xg, wg, None, yg, stream=s) == -2           # 8 % 3
+    assert status(pa.purine_grouped_conv_fwd, d, 0, xg, wg, None, yg, stream=s) == -8
+    assert status(pa.purine_grouped_conv_fwd, d, 4, xg, wg, None, yg, stream=s) == -2           # w has C/2 channels
+    assert status(pa.purine_grouped_conv_fwd, d, 2, binding.raw_desc(fake, F32, (2, 6, 5, 5)),
+                  binding.raw_desc(fake + 0x100000, F32, (8, 3, 3, 3)), None,
+                  binding.raw_desc(fake + 0x200000, F32, (2, 8, 5, 5)), stream=s) == -4         # 3*25 elements per slice
+    assert status(pa.purine_grouped_conv_fwd, d, 2, binding.raw_desc(fake, BF16, (2, 8, 6, 6)),
+                  binding.raw_desc(fake + 0x100000, BF16, (8, 4, 3, 3)), None,
+                  binding.raw_desc(fake + 0x200000, BF16, (2, 8, 6, 6)), stream=s) == -3
+    assert pa.purine_grouped_conv_workspace_bytes(0, d, 2, (2, 8, 6, 6), (8, 4, 3, 3), F32) == \
+        pa.purine_conv_workspace_bytes(0, d, (2, 4, 6, 6), (4, 4, 3, 3), F32)
+    fx = binding.raw_desc(fake, F32, (4, 20))
+    fw = binding.raw_desc(fake + 0x100000, F32, (6, 20))
+    fy = binding.raw_desc(fake + 0x200000, F32, (4, 6))
+    assert status(pa.purine_fc_fwd, fx, fw, None, fy, stream=s) == -5
+    assert status(pa.purine_fc_fwd, fx, binding.raw_desc(fake + 0x100000, F32, (6, 21)), None, fy, stream=s) == -2
+    assert status(pa.purine_fc_fwd, fx, fw, None, binding.raw_desc(fake + 0x200000, BF16, (4, 6)), stream=s) == -3
+    assert status(pa.purine_fc_bwd_data, fy, fw, binding.raw_desc(fake, F32, (4, 21)), stream=s) == -2
+    assert status(pa.purine_fc_bwd_weight, fx, fy, binding.raw_desc(fake + 0x300000, F32, (6, 20)), None, beta=0.5, stream=s) == -8
+    assert pa.purine_fc_workspace_bytes(0, 4, 20, 6) > 0 and pa.purine_fc_workspace_bytes(7, 4, 20, 6) == 0
     big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
     assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
     assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8

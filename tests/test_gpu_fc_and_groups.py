@@ -1,0 +1,155 @@
+"""Fully-connected layer and grouped convolution on the GPU (compositions of the convolution
+operators: reinterpreted descriptors and channel-slice views) against the oracle, element by
+element. fp32: relative L2 <= 1e-5; small-integer inputs bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+
+# N, C, K: ragged against the 128-row / 128-column tiles and the split chunks; one AlexNet-like
+FC_CASES = [(1, 1, 1), (3, 5, 4), (7, 300, 33), (128, 1000, 130), (32, 2304, 512), (130, 64, 1000)]
+
+
+@pytest.mark.parametrize("N,C,K", FC_CASES)
+def test_fc_layer(N, C, K):
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import rel_l2, workspace, DEV
+    rs = np.random.default_rng(N * 1000003 + C * 1009 + K)
+    for integer in (False, True):
+        d = (lambda *s: rs.integers(-2, 3, size=s).astype(np.float32)) if integer else \
+            (lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32))
+        x, w, b, dy = d(N, C), d(K, C), d(K), d(N, K)
+        dev = lambda a: torch.from_numpy(a).to(DEV)
+        tx, tw, tb, tdy = dev(x), dev(w), dev(b), dev(dy)
+        ty = torch.full((N, K), float("nan"), device=DEV)
+        tdx = torch.full((N, C), float("nan"), device=DEV)
+        tdw = torch.full((K, C), float("nan"), device=DEV)
+        tdb = torch.full((K,), float("nan"), device=DEV)
+        q = lambda which: workspace(pa.purine_fc_workspace_bytes(which, N, C, K))
+        pa.purine_fc_fwd(tx, tw, tb, ty, ws=q(pa.PURINE_CONV_FWD))
+        pa.purine_fc_bwd_data(tdy, tw, tdx, ws=q(pa.PURINE_CONV_BWD_DATA))
+        pa.purine_fc_bwd_weight(tx, tdy, tdw, tdb, ws=q(pa.PURINE_CONV_BWD_WEIGHT))
+        torch.cuda.synchronize()
+        ref_dw, ref_db = oracle.fc_bwd_weight(x, dy)
+        pairs = (("y", ty, oracle.fc_fwd(x, w, b)), ("dx", tdx, oracle.fc_bwd_data(dy, w)),
+                 ("dw", tdw, ref_dw), ("db", tdb, ref_db))
+        for name, got, ref in pairs:
+            g = got.cpu().numpy()
+            if integer:
+                assert np.abs(ref).max() < 2 ** 24 and np.array_equal(g, ref.astype(np.float32)), name
+            else:
+                assert np.isfinite(g).all() and rel_l2(g, ref) <= 1e-5, (name, rel_l2(g, ref))
+        if not integer:
+            # accumulate form of the weight and bias gradients, and a forward pass without bias
+            pa.purine_fc_bwd_weight(tx, tdy, tdw, tdb, beta=1.0, ws=q(pa.PURINE_CONV_BWD_WEIGHT))
+            pa.purine_fc_fwd(tx, tw, None, ty, ws=q(pa.PURINE_CONV_FWD))
+            torch.cuda.synchronize()
+            assert rel_l2(tdw.cpu().numpy(), 2 * ref_dw) <= 1e-5 and rel_l2(tdb.cpu().numpy(), 2 * ref_db) <= 1e-5
+            assert rel_l2(ty.cpu().numpy(), oracle.fc_fwd(x, w)) <= 1e-5
+
+
+# name, groups, N, C, H, W, K, R, S, stride, pad: AlexNet's two-group layers at reduced size, plus ragged ones
+GROUP_CASES = [
+    ("alexnet_conv2_like", 2, 2, 96, 27, 27, 256, 5, 5, (1, 1), (2, 2)),      # 27*27 odd: (C/G)*HW % 4 == 0 via C/G = 48
+    ("alexnet_conv4_like", 2, 2, 384, 13, 13, 384, 3, 3, (1, 1), (1, 1)),
+    ("four_groups_strided", 4, 3, 16, 12, 10, 32, 3, 2, (2, 1), (1, 0)),
+    ("depthwise_like", 8, 2, 32, 8, 8, 32, 3, 3, (1, 1), (1, 1)),              # C/G = K/G = 4
+    ("one_group", 1, 2, 5, 9, 7, 6, 3, 3, (1, 1), (1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", GROUP_CASES, ids=[c[0] for c in GROUP_CASES])
+def test_grouped_convolution(case):
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import rel_l2, workspace, DEV
+    name, G, N, C, H, W, K, R, S, stride, pad = case
+    rs = np.random.default_rng(len(name) * 7919 + C)
+    u = lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32)
+    x, w, b = u(N, C, H, W), u(K, C // G, R, S), u(K)
+    ref_y = oracle.grouped_conv_fwd(x, w, G, stride, pad)
+    dy = u(*ref_y.shape)
+    dev = lambda a: torch.from_numpy(a).to(DEV)
+    tx, tw, tb, tdy = dev(x), dev(w), dev(b), dev(dy)
+    ty = torch.full(ref_y.shape, float("nan"), device=DEV)
+    tdx = torch.full(x.shape, float("nan"), device=DEV)
+    tdw = torch.full(w.shape, float("nan"), device=DEV)
+    tdb = torch.full((K,), float("nan"), device=DEV)
+    desc = pa.conv_desc(stride, pad)
+    q = lambda which: workspace(pa.purine_grouped_conv_workspace_bytes(which, desc, G, x.shape, w.shape, pa.PURINE_F32))
+    pa.purine_grouped_conv_fwd(desc, G, tx, tw, tb, ty, relu=True, ws=q(pa.PURINE_CONV_FWD))
+    pa.purine_grouped_conv_bwd_data(desc, G, tdy, tw, tdx, ws=q(pa.PURINE_CONV_BWD_DATA))
+    pa.purine_grouped_conv_bwd_weight(desc, G, tx, tdy, tdw, tdb, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))
+    torch.cuda.synchronize()
+    tol = 1e-5
+    assert rel_l2(ty.cpu().numpy(), np.maximum(oracle.bias_fwd(ref_y, b), 0)) <= tol, "fwd"
+    assert rel_l2(tdx.cpu().numpy(), oracle.grouped_conv_bwd_data(dy, w, x.shape, G, stride, pad)) <= tol, "bwd_data"
+    assert rel_l2(tdw.cpu().numpy(), oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)) <= tol, "bwd_weight"
+    assert rel_l2(tdb.cpu().numpy(), oracle.bias_bwd(dy)) <= tol, "bias_bwd"
+    # no bias, no db
+    pa.purine_grouped_conv_fwd(desc, G, tx, tw, None, ty, relu=False, ws=q(pa.PURINE_CONV_FWD))
+    pa.purine_grouped_conv_bwd_weight(desc, G, tx, tdy, tdw, None, beta=1.0, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))
+    torch.cuda.synchronize()
+    assert rel_l2(ty.cpu().numpy(), ref_y) <= tol
+    assert rel_l2(tdw.cpu().numpy(), 2 * oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)) <= tol
+
+
+def test_fc_and_grouped_operators_in_a_graph():
+    """The six composed operator kinds through the executor, on two streams."""
+    import torch
+    import paper_1412_6249_amd as pa
+    from paper_1412_6249_amd import binding as B
+    from gpu_util import rel_l2, workspace, DEV
+    rs = np.random.default_rng(5)
+    u = lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32)
+    G, N, C, H, W, K = 2, 2, 8, 6, 6, 8
+    x, w, b = u(N, C, H, W), u(K, C // G, 3, 3), u(K)
+    wf, bf = u(10, K * H * W), u(10)
+    dout = u(N, 10)
+    dev = lambda a: torch.from_numpy(a).to(DEV)
+    t = dict(x=dev(x), w=dev(w), b=dev(b), wf=dev(wf), bf=dev(bf), dout=dev(dout))
+    t["y"] = torch.empty((N, K, H, W), device=DEV)
+    t["yflat"] = t["y"].view(N, K * H * W)
+    t["z"] = torch.empty((N, 10), device=DEV)
+    t["dyflat"] = torch.empty((N, K * H * W), device=DEV)
+    t["dy"] = t["dyflat"].view(N, K, H, W)
+    for n, s in (("dwf", wf.shape), ("dbf", bf.shape), ("dx", x.shape), ("dw", w.shape), ("db", b.shape)):
+        t[n] = torch.empty(s, device=DEV)
+    g = pa.purine_graph_create()
+    ids = {n: pa.purine_graph_add_tensor(g, v, n) for n, v in t.items()}
+    desc = pa.conv_desc(1, 1)
+    keep = []
+
+    def ws(nbytes):
+        keep.append(workspace(nbytes))
+        return keep[-1]
+    gq = lambda which: ws(pa.purine_grouped_conv_workspace_bytes(which, desc, G, x.shape, w.shape, pa.PURINE_F32))
+    fq = lambda which: ws(pa.purine_fc_workspace_bytes(which, N, K * H * W, 10))
+    op = lambda kind, ins, outs, th, attrs: pa.purine_graph_add_op(g, kind, [ids[i] for i in ins], [ids[o] for o in outs], th, attrs)
+    try:
+        op(B.OP_GROUPED_CONV_FWD, ["x", "w", "b"], ["y"], 0, B.op_attrs(conv=desc, groups=G, relu=True, ws=gq(0)))
+        op(B.OP_ALIAS, ["y"], ["yflat"], 0, None)                       # the flattened view of the same storage
+        op(B.OP_FC_FWD, ["yflat", "wf", "bf"], ["z"], 0, B.op_attrs(ws=fq(0)))
+        op(B.OP_FC_BWD_WEIGHT, ["yflat", "dout"], ["dwf", "dbf"], 1, B.op_attrs(ws=fq(2)))
+        op(B.OP_FC_BWD_DATA, ["dout", "wf"], ["dyflat"], 0, B.op_attrs(ws=fq(1)))
+        op(B.OP_ALIAS, ["dyflat"], ["dy"], 0, None)
+        op(B.OP_GROUPED_CONV_BWD_WEIGHT, ["x", "dy"], ["dw", "db"], 1, B.op_attrs(conv=desc, groups=G, ws=gq(3)))
+        op(B.OP_GROUPED_CONV_BWD_DATA, ["dy", "w"], ["dx"], 0, B.op_attrs(conv=desc, groups=G, ws=gq(1)))
+        pa.purine_graph_run(g)
+        H_ = lambda n: t[n].cpu().numpy()
+        y = H_("y")
+        assert rel_l2(y, np.maximum(oracle.bias_fwd(oracle.grouped_conv_fwd(x, w, G, 1, 1), b), 0)) <= 1e-5
+        yf = y.reshape(N, -1)
+        assert rel_l2(H_("z"), oracle.fc_fwd(yf, wf, bf)) <= 1e-5
+        rdw, rdb = oracle.fc_bwd_weight(yf, dout)
+        assert rel_l2(H_("dwf"), rdw) <= 1e-5 and rel_l2(H_("dbf"), rdb) <= 1e-5
+        dyv = H_("dy")
+        assert rel_l2(dyv.reshape(N, -1), oracle.fc_bwd_data(dout, wf)) <= 1e-5
+        assert rel_l2(H_("dw"), oracle.grouped_conv_bwd_weight(x, dyv, w.shape, G, 1, 1)) <= 1e-5
+        assert rel_l2(H_("db"), oracle.bias_bwd(dyv)) <= 1e-5
+        assert rel_l2(H_("dx"), oracle.grouped_conv_bwd_data(dyv, w, x.shape, G, 1, 1)) <= 1e-5
+    finally:
+        pa.purine_graph_destroy(g)

@@ -390,3 +390,45 @@ def test_sgd_update_descends_a_linear_and_a_quadratic_loss():
     assert np.array_equal(oracle.sgd_update(v, v - t, 0.0), v.astype(np.float64))
     half = oracle.sgd_update(v, v.astype(np.float64) - t, 0.5)
     assert np.allclose(half - t, 0.5 * (v.astype(np.float64) - t), rtol=0, atol=1e-15)
+
+
+# ---------------------------------------------------------------- fully connected, grouped convolution
+def test_fc_against_loops_adjoints_and_the_conv_oracle():
+    x, w, b, dy = rnd(3, 5), rnd(4, 5), rnd(4), rnd(3, 4)
+    y = oracle.fc_fwd(x, w, b)
+    for n in range(3):
+        for k in range(4):
+            assert abs(y[n, k] - (sum(float(x[n, c]) * float(w[k, c]) for c in range(5)) + float(b[k]))) < 1e-12
+    dx = oracle.fc_bwd_data(dy, w)
+    dw, db = oracle.fc_bwd_weight(x, dy)
+    # adjoint identities: <fc(x), dy> = <x, dx> = <w, dw>, and the bias term gives <b, db>
+    lin = float((oracle.fc_fwd(x, w) * dy).sum())
+    assert abs(lin - float((x * dx).sum())) < 1e-12 and abs(lin - float((w * dw).sum())) < 1e-12
+    assert abs(float((b.astype(np.float64)[None, :] * dy).sum()) - float((b * db).sum())) < 1e-12
+    # a fully-connected layer is a convolution whose filter covers the whole input (C-routine route)
+    xi, wi = rnd(2, 3, 4, 5), rnd(6, 3, 4, 5)
+    yc = oracle.conv_fwd(xi, wi, 1, 0)
+    assert yc.shape == (2, 6, 1, 1)
+    assert rel(yc[:, :, 0, 0], oracle.fc_fwd(xi.reshape(2, -1), wi.reshape(6, -1))) < 1e-12
+
+
+def test_grouped_conv_is_a_block_diagonal_plain_conv():
+    """A grouped convolution equals the plain one whose filter is zero outside the diagonal blocks;
+    so do its gradients (the weight gradient restricted to the blocks)."""
+    G, N, C, K, H, W, R, S = 2, 2, 6, 4, 7, 6, 3, 2
+    stride, pad = (2, 1), (1, 0)
+    x, w = rnd(N, C, H, W), rnd(K, C // G, R, S)
+    full = np.zeros((K, C, R, S), np.float32)
+    for g in range(G):
+        full[g * K // G:(g + 1) * K // G, g * C // G:(g + 1) * C // G] = w[g * K // G:(g + 1) * K // G]
+    y = oracle.grouped_conv_fwd(x, w, G, stride, pad)
+    assert rel(y, oracle.conv_fwd(x, full, stride, pad)) < 1e-12
+    dy = rnd(*y.shape)
+    assert rel(oracle.grouped_conv_bwd_data(dy, w, x.shape, G, stride, pad),
+               oracle.conv_bwd_data(dy, full, x.shape, stride, pad)) < 1e-12
+    dfull = oracle.conv_bwd_weight(x, dy, full.shape, stride, pad)
+    dw = oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)
+    for g in range(G):
+        ks, cs = slice(g * K // G, (g + 1) * K // G), slice(g * C // G, (g + 1) * C // G)
+        assert rel(dw[ks], dfull[ks, cs]) < 1e-12
+    assert rel(oracle.grouped_conv_fwd(x, full, 1, stride, pad), oracle.conv_fwd(x, full, stride, pad)) == 0
