@@ -301,10 +301,13 @@ hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t
     return by_tile<false, false, true, true>(p, bm, bn, st);
 }
 
-// single-tap layers (mode 0 or 1): gathers from the NCHW tensor p.in itself
+// single-tap layers: gathers from the NCHW tensor p.in itself. A strided backward-data pass whose
+// filter fits inside one stride step (R <= sh, S <= sw) is phase-folded onto a single tap too, and
+// needs the depth-to-space epilogue like any other phase-folded pass.
 hipError_t dispatch_tap_bf16_nchw(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
     if (mode == 0) return by_tile<false, true, false, false>(p, bm, bn, st);
-    return by_tile<false, true, true, false>(p, bm, bn, st);
+    if (mode == 1) return by_tile<false, true, true, false>(p, bm, bn, st);
+    return by_tile<false, true, true, true>(p, bm, bn, st);
 }
 
 // forward, flattened (c, r, s) reduction; p.wt is the filter copy A[i_pad][Ci_pad] with Ci_pad = Kg

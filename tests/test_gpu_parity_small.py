@@ -42,6 +42,10 @@ CASES = [
     ("pw_c16_k32", 5, 16, 9, 8, 32, 1, 1, (1, 1), (0, 0)),
     ("pw_c64_k64_hw42", 2, 64, 7, 6, 64, 1, 1, (1, 1), (0, 0)),
     ("pw_c160_k16_m_tail", 7, 160, 5, 14, 16, 1, 1, (1, 1), (0, 0)),
+    # strided layers whose filter fits inside one stride step: backward-data folds onto a single tap
+    # and still needs the depth-to-space epilogue
+    ("pw_stride2", 2, 32, 9, 10, 24, 1, 1, (2, 2), (0, 0)),
+    ("filter_inside_stride", 2, 64, 20, 21, 33, 1, 2, (1, 4), (0, 1)),
 ]
 PW = [c for c in CASES if c[0].startswith("pw_")]
 
@@ -222,3 +226,43 @@ def test_batch_shards_add_up():
         sdw += dws
         sdb += dbs
     assert rel_l2(dw, sdw) <= 1e-5 and rel_l2(db, sdb) <= 1e-5
+
+
+def _random_cases(n, seed):
+    """Seeded random layer shapes: every kernel family and ragged edge gets hit without anyone
+    choosing the shapes (channel counts on both sides of the 16 / 64 thresholds, 1x1 layers with
+    and without the streaming kernel's alignment, strides up to 4, pads up to the filter size)."""
+    rs = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        C = int(rs.choice([1, 2, 3, 5, 8, 15, 16, 17, 32, 48, 63, 64, 70, 96]))
+        K = int(rs.choice([1, 3, 8, 16, 31, 32, 33, 48, 64, 96, 100, 130]))
+        R, S = (1, 1) if rs.random() < 0.3 else (int(rs.integers(1, 8)), int(rs.integers(1, 8)))
+        sh, sw = int(rs.integers(1, 5)), int(rs.integers(1, 5))
+        if R == 1 and S == 1 and rs.random() < 0.7:
+            sh = sw = 1
+        ph, pw = int(rs.integers(0, R)), int(rs.integers(0, S))
+        H, W = int(rs.integers(max(1, R - 2 * ph), 26)), int(rs.integers(max(1, S - 2 * pw), 26))
+        N = int(rs.integers(1, 5))
+        if H + 2 * ph < R or W + 2 * pw < S:
+            continue
+        if N * C * H * W > 60000 or C * R * S * K > 120000:
+            continue
+        out.append(("rnd%d_%d_n%d_c%d_%dx%d_k%d_%dx%d_s%d%d_p%d%d" % (seed % 97, len(out), N, C, H, W, K, R, S, sh, sw, ph, pw),
+                    N, C, H, W, K, R, S, (sh, sw), (ph, pw)))
+    return out
+
+
+RANDOM_CASES = _random_cases(48, 1412_6249) + _random_cases(48, 6249_1412)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", RANDOM_CASES, ids=[c[0] for c in RANDOM_CASES])
+def test_random_shapes(case, dtype):
+    from gpu_util import run_layer, rel_l2, TOL
+    x, w, b, dy, stride, pad = make(case, dtype)
+    got = run_layer(x, w, b, dy, stride, pad, dtype, fused_wb=(zlib.crc32(case[0].encode()) & 1) == 1)
+    ref = oracle_layer(x, w, b, dy, stride, pad)
+    for name, g, r in zip(("y", "dx", "dw", "db"), got, ref):
+        assert g.shape == r.shape and np.isfinite(g).all(), name
+        assert rel_l2(g, r) <= TOL[dtype], (case[0], name, rel_l2(g, r))
