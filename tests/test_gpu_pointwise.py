@@ -28,6 +28,24 @@ POOLS = [
 ]
 
 
+def _random_pools(n, seed):
+    rs = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        k = int(rs.integers(1, 6))
+        s = int(rs.integers(1, 5))
+        p = int(rs.integers(0, k))
+        H, W = int(rs.integers(1, 40)), int(rs.integers(1, 40))
+        if H + 2 * p < k or W + 2 * p < k:
+            continue
+        N, C = int(rs.integers(1, 4)), int(rs.integers(1, 9))
+        out.append(("rnd%d_k%ds%dp%d_%dx%dx%dx%d" % (len(out), k, s, p, N, C, H, W), N, C, H, W, k, s, p))
+    return out
+
+
+POOLS += _random_pools(24, 1412)
+
+
 def pool_inputs(case, dtype, ties):
     name, N, C, H, W, k, s, p = case
     rs = np.random.default_rng([N, C, H, W, k, s, p])
