@@ -44,12 +44,17 @@ constexpr int BK = 16;  // slab depth along the reduction (fp32 kernels)
 // slab loop needs neither the clamped addresses nor the zero-fill selects. The host enables it for
 // tensors below 2^31 bytes.
 template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32, bool BUF = false>
-__global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM == 2 ? 4 : 1)) void igemm_tap_kernel(const PixParams p) {
+__global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM == 2 ? 4 : (MT == 16 && TM == 3 && TN == 2 ? 7 : 1)))
+void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * MT;
     constexpr int BN = WN * TN * MT;
     constexpr int KSTEP = MT == 32 ? 2 : 4;    // reduction elements per MFMA
-    constexpr int LDB = BN + (MT == 16 ? 16 : 0);   // 16-wide tiles: rows 16 banks apart
+    // 16-wide tiles: a fragment read takes four consecutive slab rows at once (16 lanes each), so odd
+    // rows are stored with bit 4 of the column flipped: rows r and r+1 then sit 16 banks apart without
+    // padding, and the 48x128 tile's 22.5 KB let seven workgroups share a CU's LDS.
+    constexpr int LDB = BN;
+    constexpr int SWZ = MT == 16 ? 16 : 0;
     static_assert(MT == 32 || MT == 16, "MFMA tile edge");
     static_assert(NT == 256 && NT % BN == 0, "one pixel column per thread");
     constexpr int B_RPP = NT / BN;             // slab rows covered per pass
@@ -160,7 +165,8 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps) {
             const bool ok = BUF | (b_ok & (c0 + ps * B_RPP + b_row < p.Ci));   // BUF: zeros came from the loads
-            Bs[buf][(ps * B_RPP + b_row) * LDB + (tid % BN)] = ok ? b_reg[ps] : 0.0f;
+            const int row = ps * B_RPP + b_row;
+            Bs[buf][row * LDB + ((tid % BN) ^ ((row & 1) * SWZ))] = ok ? b_reg[ps] : 0.0f;
         }
     };
 
@@ -182,6 +188,9 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
     const int a_off = wm * TM * MT + (lane & (MT - 1));
     const int b_off = wn * TN * MT + (lane & (MT - 1));
     const int khalf = lane / MT;      // which of the KSTEP reduction elements this lane feeds
+    int b_col[TN];                    // this lane's column of each of its MFMA tiles (KSTEP is even: row parity = khalf's)
+#pragma unroll
+    for (int b = 0; b < TN; ++b) b_col[b] = (b_off + b * MT) ^ ((khalf & 1) * SWZ);
 
     for (int slab = 0; slab < n_slabs; ++slab) {
         const int buf = slab & 1;
@@ -190,7 +199,7 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
 #pragma unroll
         for (int a = 0; a < TM; ++a) av[0][a] = As[buf][khalf * BM + a_off + a * MT];
 #pragma unroll
-        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * LDB + b_off + b * MT];
+        for (int b = 0; b < TN; ++b) bv[0][b] = Bs[buf][khalf * LDB + b_col[b]];
 #pragma unroll
         for (int ks = 0; ks < BK / KSTEP; ++ks) {
             const int cur = ks & 1, nxt = cur ^ 1;
@@ -199,7 +208,7 @@ __global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM
 #pragma unroll
                 for (int a = 0; a < TM; ++a) av[nxt][a] = As[buf][row * BM + a_off + a * MT];
 #pragma unroll
-                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * LDB + b_off + b * MT];
+                for (int b = 0; b < TN; ++b) bv[nxt][b] = Bs[buf][row * LDB + b_col[b]];
             }
 #pragma unroll
             for (int a = 0; a < TM; ++a)
