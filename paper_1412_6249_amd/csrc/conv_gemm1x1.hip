@@ -164,19 +164,21 @@ __device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[T
                 old[e] = *reinterpret_cast<const raw_t*>(orow + (row0 + d < p.Co ? d * p.HoWo : 0));
             }
         }
+        floatx4 bq = {0.0f, 0.0f, 0.0f, 0.0f};   // bias of four consecutive rows: one 16-byte LDS read per quad
 #pragma unroll
         for (int e = 0; e < G; ++e) {
             const int d = ((e0 + e) >> 2) * 8 + ((e0 + e) & 3);
             const int i = row0 + d;
+            // (row0 + d - i_tile0 is a multiple of 4 at the start of a quad; rows past Co hold zeros)
+            if (FUSED && bias && ((e0 + e) & 3) == 0) bq = *reinterpret_cast<const floatx4*>(&bias_lds[i - i_tile0]);
             if (i >= p.Co) continue;
             float v[TN];
 #pragma unroll
             for (int b = 0; b < TN; ++b) v[b] = acc[b][e0 + e];
             if (FUSED) {
                 if (bias) {
-                    const float bi = bias_lds[i - i_tile0];
 #pragma unroll
-                    for (int b = 0; b < TN; ++b) v[b] += bi;
+                    for (int b = 0; b < TN; ++b) v[b] += bq[(e0 + e) & 3];
                 }
                 if (p.relu) {
 #pragma unroll
@@ -210,7 +212,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     typedef typename Vec<T, TN>::raw raw_t;
 
     __shared__ float As[CK * LD];
-    __shared__ float bias_s[FUSED ? BM : 1];
+    __shared__ __attribute__((aligned(16))) float bias_s[FUSED ? BM : 4];   // read in 16-byte quads
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;

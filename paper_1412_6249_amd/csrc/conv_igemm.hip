@@ -44,7 +44,7 @@ constexpr int BK = 16;  // slab depth along the reduction (fp32 kernels)
 // slab loop needs neither the clamped addresses nor the zero-fill selects. The host enables it for
 // tensors below 2^31 bytes.
 template <typename T, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int MT = 32, bool BUF = false>
-__global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM == 2 ? 4 : (MT == 16 && TM == 3 && TN == 2 ? 7 : 1)))
+__global__ __launch_bounds__(WM * WN * 64, (MT == 32 && TM == 2 && TN == 2 && WM == 2 ? 4 : (MT == 16 && TM == 3 && TN == 2 && BUF ? 7 : 1)))
 void igemm_tap_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * MT;
@@ -65,7 +65,7 @@ void igemm_tap_kernel(const PixParams p) {
 
     __shared__ __attribute__((aligned(16))) float As[2][BK * BM];
     __shared__ float Bs[2][BK * LDB];
-    __shared__ float bias_s[FUSED ? BM : 1];
+    __shared__ __attribute__((aligned(16))) float bias_s[FUSED ? BM : 4];   // read in 16-byte quads
 
     const T* __restrict__ in = (const T*)p.in;
     const T* __restrict__ wt = (const T*)p.wt;
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
 
     __shared__ float As[2][BK * LDA];
     __shared__ float Bs[2][BK * BN];
-    __shared__ float bias_s[FUSED ? BM : 1];
+    __shared__ __attribute__((aligned(16))) float bias_s[FUSED ? BM : 4];   // read in 16-byte quads
     __shared__ int tab_off[FLAT_MAX_KG];
     __shared__ int tab_rs[NOPAD ? 1 : FLAT_MAX_KG];
 

@@ -46,7 +46,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
-    __shared__ float bias_s[FUSED ? BM : 1];
+    __shared__ __attribute__((aligned(16))) float bias_s[FUSED ? BM : 4];   // read in 16-byte quads
 
     const uint16_t* __restrict__ in = (const uint16_t*)p.in;
     const uint16_t* __restrict__ wt = (const uint16_t*)p.wt;
@@ -90,7 +90,8 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         a_dst[it] = row * LDK + piece * 8;
     }
 
-    uint4 a_reg[A_ITERS];
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));   // native vector: stays in registers
+    u32x4_t a_reg[A_ITERS];
     uint32_t b_reg[ELEMS ? CH : 1];  // FLAT / NCHW: raw 16-bit values
     uint4 blk_reg[CH / 8];           // blocked input: 8 channels of this thread's pixel per piece
     bool b_ok = false;
@@ -102,7 +103,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         const int a_slab = tap * p.i_pad * p.Ci_pad + nx_c0;
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
-            if (a_src[it] >= 0) a_reg[it] = *reinterpret_cast<const uint4*>(wt + a_slab + a_src[it]);
+            if (a_src[it] >= 0) a_reg[it] = *reinterpret_cast<const u32x4_t*>(wt + a_slab + a_src[it]);
         if (FLAT) {
             // this wavefront's run of CH flattened rows starts at kk0 = (c, r, s)
             int kk = nx_c0 + ch_base;
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     auto store_slab = [&](int buf) {
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
-            if (a_src[it] >= 0) *reinterpret_cast<uint4*>(&As[buf][a_dst[it]]) = a_reg[it];
+            if (a_src[it] >= 0) *reinterpret_cast<u32x4_t*>(&As[buf][a_dst[it]]) = a_reg[it];
         uint16_t* row = &Bs[buf][(tid % BN) * LDK + ch_base];
         if (!ELEMS) {
 #pragma unroll

@@ -164,6 +164,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     const T* __restrict__ mask = (const T*)p.mask;
     const bool has_bias = !D2S && bias != nullptr, has_mask = mask != nullptr, has_beta = p.beta != 0.0f;
     constexpr int G = TM * TN <= 3 ? 16 : 8;   // rows per staged batch
+    constexpr bool QUAD_BIAS = sizeof(T) == 2;
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int pix = pix_base + b * 32;
@@ -178,6 +179,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             const int a = ag / (16 / G), e0 = (ag % (16 / G)) * G;
             const int rowa = i_base + a * 32 + khalf * 4;
             float t[G], o[G];
+            floatx4 bq = {0.0f, 0.0f, 0.0f, 0.0f};
             bool ok;
             if (has_mask && !has_bias) {
 #pragma unroll
@@ -192,7 +194,17 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
                 const int row = rowa + ((e0 + e) >> 2) * 8 + (e & 3);
                 const int off = addr.at(row, ok);
                 float v = acc[a][b][e0 + e];
-                if (has_bias) v += bias_lds[row - i_tile0];
+                // bias. bf16 kernels (short per wavefront, so the epilogue weighs): the four consecutive
+                // rows e..e+3 of an accumulator quad come from LDS as one 16-byte read, instead of a read
+                // per element that waits for its own round trip between two stores. The fp32 kernels
+                // keep the per-element read: the quads cost the flattened forward kernel 20 registers
+                // and with them a wavefront of occupancy.
+                if (QUAD_BIAS) {
+                    if (has_bias && (e & 3) == 0) bq = *reinterpret_cast<const floatx4*>(&bias_lds[row - i_tile0]);
+                    if (has_bias) v += bq[e & 3];
+                } else if (has_bias) {
+                    v += bias_lds[row - i_tile0];
+                }
                 if (p.relu) v = v > 0.0f ? v : 0.0f;
                 if (has_mask && !has_bias) v = t[e] > 0.0f ? v : 0.0f;
                 if (has_beta) v += o[e];
