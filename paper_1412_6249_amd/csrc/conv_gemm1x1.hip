@@ -130,12 +130,14 @@ __device__ __forceinline__ void fill_filter(float* __restrict__ As, const T* __r
 // bias, ReLU, ReLU-gradient mask, accumulate; vector stores. What 8 rows need from memory is
 // requested before the first of their stores, so the loads overlap instead of forming
 // load-wait-store round trips.
-template <typename T, bool FUSED, int TN>
+// FWD: forward pass (bias / ReLU, no mask, no accumulate); otherwise backward-data (the reverse).
+template <typename T, bool FUSED, int TN, bool FWD>
 __device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[TN], int row0, size_t obase,
                                            const float* bias_lds, int i_tile0) {
     typedef typename Vec<T, TN>::raw raw_t;
-    const T* __restrict__ bias = (const T*)p.bias;
-    const bool has_mask = FUSED && p.mask != nullptr, has_beta = p.beta != 0.0f;
+    const T* __restrict__ bias = FWD ? (const T*)p.bias : nullptr;
+    const bool has_mask = FUSED && !FWD && p.mask != nullptr, has_beta = !FWD && p.beta != 0.0f;
+    const bool relu = FWD && p.relu;
     // One per-lane pointer to (row0, this lane's pixels); the 16 rows of the tile are uniform
     // multiples of the plane size away. The pointers are made opaque so that the compiler does not
     // turn every row's address into a 64-bit induction variable of the loops around the epilogue.
@@ -180,7 +182,7 @@ __device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[T
 #pragma unroll
                     for (int b = 0; b < TN; ++b) v[b] += bq[(e0 + e) & 3];
                 }
-                if (p.relu) {
+                if (relu) {
 #pragma unroll
                     for (int b = 0; b < TN; ++b) v[b] = v[b] > 0.0f ? v[b] : 0.0f;
                 }
@@ -297,7 +299,7 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     if (!live) return;
     const size_t obase = (size_t)n * p.out_ns + pix;
 #pragma unroll
-    for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN>(p, acc[a], i0 + a * 32 + khalf * 4, obase, bias_s, i0);
+    for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN, !TRANS>(p, acc[a], i0 + a * 32 + khalf * 4, obase, bias_s, i0);
 }
 
 template <typename T, bool TRANS, bool FUSED, int TM, int TN>

@@ -221,7 +221,7 @@ void igemm_tap_kernel(const PixParams p) {
         __syncthreads();
     }
 
-    store_tile<T, D2S, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * MT, j0 + b_off, khalf, bias_s, i0);
+    store_tile<T, D2S, FUSED, TM, TN, !MINUS>(p, (T*)p.out, acc, i0 + wm * TM * MT, j0 + b_off, khalf, bias_s, i0);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -391,7 +391,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParam
         __syncthreads();
     }
 
-    store_tile<T, false, FUSED, TM, TN>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf, bias_s, i0);
+    store_tile<T, false, FUSED, TM, TN, true>(p, (T*)p.out, acc, i0 + wm * TM * 32, j0 + b_off, khalf, bias_s, i0);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -234,7 +234,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         __syncthreads();
     }
 
-    store_tile<uint16_t, D2S, FUSED, TM, TN>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
+    store_tile<uint16_t, D2S, FUSED, TM, TN, !MINUS>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
                                       j0 + wn * TN * 32 + (lane & 31), lane >> 5, bias_s, i0);
 }
 

@@ -132,7 +132,10 @@ struct TileAddr {
     }
 };
 
-template <typename T, bool D2S, bool FUSED, int TM, int TN>
+// FWD: the forward pass (bias / ReLU may be fused, never a mask or an accumulate); otherwise
+// backward-data (mask and accumulate possible, never bias / ReLU). Knowing the pass at compile time
+// keeps the other pass's options out of the per-element code.
+template <typename T, bool D2S, bool FUSED, int TM, int TN, bool FWD>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
                                            int khalf, const float* bias_lds, int i_tile0) {
@@ -153,7 +156,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
                     const int off = addr.at(i_base + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3), ok);
                     if (ok) {
                         float v = acc[a][b][e];
-                        if (p.beta != 0.0f) v += Elem<T>::load(out, off);
+                        if (!FWD && p.beta != 0.0f) v += Elem<T>::load(out, off);
                         Elem<T>::store(out, off, v);
                     }
                 }
@@ -162,7 +165,8 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     }
     const T* __restrict__ bias = (const T*)p.bias;
     const T* __restrict__ mask = (const T*)p.mask;
-    const bool has_bias = !D2S && bias != nullptr, has_mask = mask != nullptr, has_beta = p.beta != 0.0f;
+    const bool has_bias = FWD && !D2S && bias != nullptr, has_mask = !FWD && mask != nullptr;
+    const bool has_beta = !FWD && p.beta != 0.0f, relu = FWD && p.relu;
     constexpr int G = TM * TN <= 3 ? 16 : 8;   // rows per staged batch
     constexpr bool QUAD_BIAS = sizeof(T) == 2;
 #pragma unroll
@@ -205,7 +209,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
                 } else if (has_bias) {
                     v += bias_lds[row - i_tile0];
                 }
-                if (p.relu) v = v > 0.0f ? v : 0.0f;
+                if (relu) v = v > 0.0f ? v : 0.0f;
                 if (has_mask && !has_bias) v = t[e] > 0.0f ? v : 0.0f;
                 if (has_beta) v += o[e];
                 if (ok) Elem<T>::store(out, off, v);
@@ -218,14 +222,14 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
 
 // Same epilogue for 16x16 MFMA tiles: accumulator register e holds row (lane/16)*4 + e, column
 // lane%16; `kq` is lane/16.
-template <typename T, bool D2S, bool FUSED, int TM, int TN>
+template <typename T, bool D2S, bool FUSED, int TM, int TN, bool FWD>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx4 (&acc)[TM][TN], int i_base, int pix_base, int kq,
                                            const float* bias_lds, int i_tile0) {
     const T* __restrict__ bias = (const T*)p.bias;
     const T* __restrict__ mask = (const T*)p.mask;
-    const bool has_bias = FUSED && !D2S && bias != nullptr, has_mask = FUSED && mask != nullptr;
-    const bool has_beta = p.beta != 0.0f;
+    const bool has_bias = FUSED && FWD && !D2S && bias != nullptr, has_mask = FUSED && !FWD && mask != nullptr;
+    const bool has_beta = !FWD && p.beta != 0.0f, relu = FUSED && FWD && p.relu;
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int pix = pix_base + b * 16;
@@ -253,7 +257,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
                 const int off = addr.at(row0 + e, ok);
                 float v = acc[a][b][e];
                 if (has_bias) v += t[e];
-                if (FUSED && p.relu) v = v > 0.0f ? v : 0.0f;
+                if (relu) v = v > 0.0f ? v : 0.0f;
                 if (has_mask) v = t[e] > 0.0f ? v : 0.0f;
                 if (has_beta) v += o[e];
                 if (ok) Elem<T>::store(out, off, v);
