@@ -232,7 +232,9 @@ void igemm_tap_kernel(const PixParams p) {
 // 2^30 in the table and a pixel that does not exist 2^31, so (tensor below 2^30 bytes) their sums
 // are out of range and read as zero.
 template <typename T, bool FUSED, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void igemm_flat_kernel(const PixParams p) {
+// 96x256 tile: three workgroups per CU fit the LDS; the bound keeps the fused variant's registers
+// (whose epilogue would otherwise copy all 96 accumulators out at once) within that occupancy too.
+__global__ __launch_bounds__(WM * WN * 64, (TM * TN == 6 && BUF && NOPAD ? 3 : 1)) void igemm_flat_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
     constexpr int BN = WN * TN * 32;

@@ -139,9 +139,12 @@ template <typename T, bool D2S, bool FUSED, int TM, int TN, bool FWD>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
                                            int khalf, const float* bias_lds, int i_tile0) {
-    if (!FUSED) {
-        // plain store (optionally accumulating): no staging arrays, so the kernels that do not fuse
-        // anything keep their register count and occupancy
+    if (!FUSED || FWD) {
+        // Plain store (backward-data: optionally accumulating) and the fused forward epilogue, which
+        // needs nothing from global memory (bias comes from LDS): no staging arrays, so these
+        // kernels keep their register count and occupancy.
+        const bool fwd_bias = FUSED && FWD && !D2S && p.bias != nullptr, fwd_relu = FUSED && FWD && p.relu;
+        constexpr bool QUAD = sizeof(T) == 2;   // bf16: bias of four consecutive rows as one 16-byte LDS read
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
             const int pix = pix_base + b * 32;
@@ -149,17 +152,32 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             const int n = fastdiv(pix, p.div_howo);
             const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
 #pragma unroll
-            for (int a = 0; a < TM; ++a)
+            for (int a = 0; a < TM; ++a) {
+                floatx4 bq = {0.0f, 0.0f, 0.0f, 0.0f};
+                // The fused arithmetic needs the values in VGPRs (the plain store takes them from the
+                // accumulator register file). Pinning the copy of ONE tile here, behind a fence, keeps
+                // the compiler from copying every tile's accumulators out at once (96 VGPRs for a
+                // six-tile wavefront, and a workgroup of occupancy with them).
+                floatx16 tile = acc[a][b];
+                if (FUSED) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    asm volatile("" : "+v"(tile));
+                }
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     bool ok;
-                    const int off = addr.at(i_base + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3), ok);
+                    const int row = i_base + a * 32 + khalf * 4 + (e >> 2) * 8 + (e & 3);
+                    const int off = addr.at(row, ok);
+                    if (QUAD && fwd_bias && (e & 3) == 0) bq = *reinterpret_cast<const floatx4*>(&bias_lds[row - i_tile0]);
                     if (ok) {
-                        float v = acc[a][b][e];
+                        float v = tile[e];
+                        if (fwd_bias) v += QUAD ? bq[e & 3] : bias_lds[row - i_tile0];
+                        if (fwd_relu) v = v > 0.0f ? v : 0.0f;
                         if (!FWD && p.beta != 0.0f) v += Elem<T>::load(out, off);
                         Elem<T>::store(out, off, v);
                     }
                 }
+            }
         }
         return;
     }
