@@ -185,7 +185,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     const T* __restrict__ mask = (const T*)p.mask;
     const bool has_bias = FWD && !D2S && bias != nullptr, has_mask = !FWD && mask != nullptr;
     const bool has_beta = !FWD && p.beta != 0.0f, relu = FWD && p.relu;
-    constexpr int G = TM * TN <= 3 ? 16 : 8;   // rows per staged batch
+    constexpr int G = 4;   // rows per staged batch: one accumulator quad (16 rows cost the 96x128 kernel two wavefronts of occupancy)
     constexpr bool QUAD_BIAS = sizeof(T) == 2;
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
@@ -196,8 +196,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
 #pragma unroll
         for (int ag = 0; ag < TM * (16 / G); ++ag) {
             // The mask / old output values of G rows of an MFMA tile are requested before the first
-            // of their stores, so that their latency is paid once per batch; bias values come from
-            // LDS. G = 16 where the accumulators leave room, 8 for the four-tile wavefronts.
+            // of their stores, so that their latency is paid once per batch.
             const int a = ag / (16 / G), e0 = (ag % (16 / G)) * G;
             const int rowa = i_base + a * 32 + khalf * 4;
             float t[G], o[G];
