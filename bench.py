@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     # (config, kernel): HBM bytes per launch = FETCH_SIZE * 2047.77 + WRITE_SIZE * 1024 (the factors a
     # plain 256 MiB copy gives these counters), from the rocprofv3 --pmc runs summarised in profiles/
-    (2, "conv_bwd_data[conv1.dx]"): 86.22e6 + 38.54e6,
-    (2, "conv_fwd_bias_relu[conv1.a]"): 41.80e6 + 72.12e6,
+    (2, "conv_bwd_data[conv1.dx]"): 85.46e6 + 38.54e6,
+    (2, "conv_fwd_bias_relu[conv1.a]"): 42.17e6 + 72.11e6,
 }
 
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
