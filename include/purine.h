@@ -360,9 +360,13 @@ void purine_set_kernel_probe(void* start_event, void* stop_event);
  * forward / backward-data kernels to one of 128x128, 96x256, 96x128, 64x256, 128x64, 64x128, 32x256,
  * 64x64, 32x128; any other pair (e.g. 0, 0) restores the automatic choice. Results are bit-identical
  * for every shape: the reduction order per output element does not depend on it.
- * For 1x1 / stride-1 / unpadded layers, which run the streaming GEMM kernel instead: (32|64|96, 2) or
- * (32|64, 4) force its rows per workgroup and pixels per lane, and (-1, anything) sends those layers
- * through the general kernel. */
+ * (48|16, 256|128) does the same for the 16-row-granular tiles of GEMMs with at most 16 or 33..48
+ * rows, (192, 128) selects an uncalibrated tile.
+ * For 1x1 / stride-1 / unpadded layers, which run the streaming GEMM kernel instead: (32|64|96, 2),
+ * (64|96, 1) or (32|64, 4) force its rows per workgroup and pixels per lane, and (-1, anything) sends
+ * those layers through the general kernel.
+ * (anything, -1) makes every kernel take ordinary global loads with explicit zero fill instead of
+ * range-checked raw buffer loads (the path tensors of 2 GiB and more take anyway). */
 void purine_debug_force_tile(int bm, int bn);
 
 /* Test hook (host only): n / d computed with the multiply-and-shift reciprocal that the kernels'
