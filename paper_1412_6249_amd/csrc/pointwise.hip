@@ -337,6 +337,99 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
     }
 }
 
+// ---- 3x3 / stride 1 / pad 1 pooling on fp32 planes whose width is a multiple of 4 ----------------
+// (the pooling branch of an inception module). A lane owns four consecutive positions of one row:
+// per window row it needs the aligned packet of those four columns plus the column on either side,
+// so 3 packets + 6 scalars replace 36 scalar loads, and the outputs leave as packets. Winners and
+// sums are taken in the same order as in the general kernels (bit-identical results).
+struct Pool3Params {
+    int NC, H, W, HW, W4;      // W4 = W / 4 packets per row
+    FastDiv div_row4, div_w4;  // by H * W4 (packets per plane) and by W4
+    long long total4;          // packets in all
+    float beta;
+};
+
+__global__ __launch_bounds__(TPB) void maxpool3_fwd_vec_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                               int32_t* __restrict__ arg, const Pool3Params pp) {
+    for (long long i = (long long)blockIdx.x * TPB + threadIdx.x; i < pp.total4; i += (long long)gridDim.x * TPB) {
+        // plane index and packet inside the plane (the host keeps the packet count below 2^31)
+        const int per_plane = pp.H * pp.W4;
+        const int nc = fastdiv((uint32_t)i, pp.div_row4);
+        const int r4 = (int)i - nc * per_plane;
+        const int p = fastdiv(r4, pp.div_w4);
+        const int q0 = (r4 - p * pp.W4) * 4;
+        const float* plane = x + (size_t)nc * pp.HW;
+        float bv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        int best[4] = {-1, -1, -1, -1};
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int h = p - 1 + r;
+            const bool row_ok = (unsigned)h < (unsigned)pp.H;
+            const int hb = (row_ok ? h : p) * pp.W;                 // clamped row: values unused when !row_ok
+            const float4 v4 = *reinterpret_cast<const float4*>(plane + hb + q0);
+            const bool l_ok = row_ok & (q0 > 0), r_ok = row_ok & (q0 + 4 < pp.W);
+            const float vl = plane[hb + (q0 > 0 ? q0 - 1 : q0)];
+            const float vr = plane[hb + (q0 + 4 < pp.W ? q0 + 4 : q0)];
+            const float v[6] = {vl, v4.x, v4.y, v4.z, v4.w, vr};
+            const bool ok[6] = {l_ok, row_ok, row_ok, row_ok, row_ok, r_ok};
+#pragma unroll
+            for (int o = 0; o < 4; ++o)
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {                       // window column c of output o is v[o + c]
+                    const bool take = ok[o + c] & ((best[o] < 0) | (v[o + c] > bv[o]));
+                    best[o] = take ? h * pp.W + q0 + o + c - 1 : best[o];
+                    bv[o] = take ? v[o + c] : bv[o];
+                }
+        }
+        const size_t out = (size_t)nc * pp.HW + (size_t)p * pp.W + q0;
+        *reinterpret_cast<float4*>(y + out) = make_float4(bv[0], bv[1], bv[2], bv[3]);
+        *reinterpret_cast<int4*>(arg + out) = make_int4(best[0], best[1], best[2], best[3]);
+    }
+}
+
+__global__ __launch_bounds__(TPB) void maxpool3_bwd_vec_kernel(const float* __restrict__ dy,
+                                                               const int32_t* __restrict__ arg, float* dx,
+                                                               const Pool3Params pp) {
+    for (long long i = (long long)blockIdx.x * TPB + threadIdx.x; i < pp.total4; i += (long long)gridDim.x * TPB) {
+        const int per_plane = pp.H * pp.W4;
+        const int nc = fastdiv((uint32_t)i, pp.div_row4);
+        const int r4 = (int)i - nc * per_plane;
+        const int h = fastdiv(r4, pp.div_w4);
+        const int w0 = (r4 - h * pp.W4) * 4;
+        const size_t base = (size_t)nc * pp.HW;
+        const size_t at = base + (size_t)h * pp.W + w0;
+        float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (pp.beta != 0.0f) {
+            const float4 o = *reinterpret_cast<const float4*>(dx + at);
+            acc[0] = o.x; acc[1] = o.y; acc[2] = o.z; acc[3] = o.w;
+        }
+        // windows (p, q) with p in h-1..h+1 and q in w-1..w+1 cover position (h, w); visited in (p, q) order
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int p = h - 1 + r;
+            const bool row_ok = (unsigned)p < (unsigned)pp.H;
+            const size_t rb = base + (size_t)(row_ok ? p : h) * pp.W;
+            const float4 g4 = *reinterpret_cast<const float4*>(dy + rb + w0);
+            const int4 a4 = *reinterpret_cast<const int4*>(arg + rb + w0);
+            const int li = w0 > 0 ? w0 - 1 : w0, ri = w0 + 4 < pp.W ? w0 + 4 : w0;
+            const bool l_ok = row_ok & (w0 > 0), r_ok = row_ok & (w0 + 4 < pp.W);
+            const float g[6] = {dy[rb + li], g4.x, g4.y, g4.z, g4.w, dy[rb + ri]};
+            const int a[6] = {arg[rb + li], a4.x, a4.y, a4.z, a4.w, arg[rb + ri]};
+            const bool ok[6] = {l_ok, row_ok, row_ok, row_ok, row_ok, r_ok};
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int e = h * pp.W + w0 + o;                    // this position's index in its plane
+#pragma unroll
+                for (int c = 0; c < 3; ++c) {
+                    const bool hit = ok[o + c] & (a[o + c] == e);
+                    acc[o] += hit ? g[o + c] : 0.0f;
+                }
+            }
+        }
+        *reinterpret_cast<float4*>(dx + at) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    }
+}
+
 // ---- channel-slice copy (concat and its inverse) -------------------------------------------------
 template <typename T, bool VEC>
 __global__ __launch_bounds__(TPB) void copy_channels_kernel(const T* __restrict__ src,
@@ -517,6 +610,22 @@ dim3 pool_grid(const PoolParams& pp, int per_plane) {
     // x: plane groups (up to 2^31 - 1), y: chunks of one group (up to 65535)
     return dim3((unsigned)((pp.NC + pp.ppw - 1) / pp.ppw), (unsigned)((per_group + POOL_CHUNK - 1) / POOL_CHUNK));
 }
+// the packet kernels: fp32, 3x3 / stride 1 / pad 1 (output extents = input extents), rows of whole packets
+bool pool3_vec_applies(int dtype, int NC, int H, int W, int P, int Q, int k, int stride, int pad, const void* a,
+                       const void* b, const void* c) {
+    return dtype == PURINE_F32 && k == 3 && stride == 1 && pad == 1 && P == H && Q == W && W % 4 == 0 &&
+           (long long)NC * H * (W / 4) < 0x7fffffffLL &&
+           (((uintptr_t)a | (uintptr_t)b | (uintptr_t)c) & 15u) == 0;
+}
+Pool3Params pool3_params(int NC, int H, int W, float beta) {
+    Pool3Params p{};
+    p.NC = NC; p.H = H; p.W = W; p.HW = H * W; p.W4 = W / 4;
+    p.div_w4 = make_fastdiv(p.W4);
+    p.div_row4 = make_fastdiv(H * p.W4);
+    p.total4 = (long long)NC * H * p.W4;
+    p.beta = beta;
+    return p;
+}
 #define POOL_SHAPES(CALL)                                           \
     if (k == 3 && stride == 1) { CALL(3, 1); }                      \
     else if (k == 3 && stride == 2) { CALL(3, 2); }                 \
@@ -528,6 +637,14 @@ hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, i
                               int P, int Q, int k, int stride, int pad, hipStream_t st) {
     // a group of planes is indexed with 32-bit arithmetic; groups go to grid.y
     if ((long long)H * W > 0x3fffffffLL || (long long)P * Q > 0x3fffffffLL) return hipErrorInvalidValue;
+    if (pool3_vec_applies(dtype, NC, H, W, P, Q, k, stride, pad, x, y, arg)) {
+        const Pool3Params p3 = pool3_params(NC, H, W, 0.0f);
+        ProbeScope probe(st);
+        (void)hipGetLastError();
+        hipLaunchKernelGGL(maxpool3_fwd_vec_kernel, dim3(blocks_for((size_t)p3.total4)), dim3(TPB), 0, st,
+                           (const float*)x, (float*)y, arg, p3);
+        return hipGetLastError();
+    }
     const PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, P * Q, 0.0f);
     const dim3 grid = pool_grid(pp, P * Q);
     if (grid.y > 65535u) return hipErrorInvalidValue;
@@ -546,6 +663,14 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
                               int NC, int H, int W, int P, int Q, int k, int stride, int pad,
                               hipStream_t st) {
     if ((long long)H * W > 0x3fffffffLL || (long long)P * Q > 0x3fffffffLL) return hipErrorInvalidValue;
+    if (pool3_vec_applies(dtype, NC, H, W, P, Q, k, stride, pad, dy, dx, arg)) {
+        const Pool3Params p3 = pool3_params(NC, H, W, beta);
+        ProbeScope probe(st);
+        (void)hipGetLastError();
+        hipLaunchKernelGGL(maxpool3_bwd_vec_kernel, dim3(blocks_for((size_t)p3.total4)), dim3(TPB), 0, st,
+                           (const float*)dy, arg, (float*)dx, p3);
+        return hipGetLastError();
+    }
     const PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, H * W, beta);
     const dim3 grid = pool_grid(pp, H * W);
     if (grid.y > 65535u) return hipErrorInvalidValue;

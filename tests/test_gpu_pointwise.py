@@ -25,6 +25,11 @@ POOLS = [
     ("k3s1p1_big_plane", 1, 2, 70, 90, 3, 1, 1),   # one plane spans several chunks
     ("k3s2_big_plane", 1, 3, 101, 97, 3, 2, 0),
     ("k1s1_identity", 2, 2, 6, 5, 1, 1, 0),
+    # 3x3 / stride 1 / pad 1 with rows of whole 16-byte packets: the packet kernels (fp32)
+    ("k3s1p1_w8", 3, 5, 5, 8, 3, 1, 1),
+    ("k3s1p1_w4_h1", 2, 3, 1, 4, 3, 1, 1),
+    ("k3s1p1_w4_h2", 1, 1, 2, 4, 3, 1, 1),
+    ("k3s1p1_56x12", 2, 3, 56, 12, 3, 1, 1),
 ]
 
 
