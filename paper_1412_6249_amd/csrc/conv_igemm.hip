@@ -303,18 +303,38 @@ __global__ __launch_bounds__(WM * WN * 64, (TM * TN == 6 && BUF && NOPAD ? 3 : 1
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(in), (short)0, BUF ? (int)p.in_bytes : 0, 0x00020000);
     const unsigned g_voff = g_live ? (unsigned)g_off * 4u : 0x80000000u;
+    // BUF: the filter [Co][Kg] is read the same way: a per-row byte offset fixed for the kernel
+    // (marker 2^30 for a row past Co) plus a per-slab column offset (marker 2^31 past Kg; without it
+    // the column would run on into the next row). The host enables BUF only for filters below 2^30 bytes.
+    const __amdgpu_buffer_rsrc_t rs_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<T*>(wt), (short)0, BUF ? p.Co * p.Kg * 4 : 0, 0x00020000);
+    unsigned a_voff[BUF ? A_PASSES : 1];
+    if (BUF) {
+#pragma unroll
+        for (int ps = 0; ps < A_PASSES; ++ps) {
+            const int i = i0 + a_i + ps * A_RPP;
+            a_voff[BUF ? ps : 0] = i < p.Co ? (unsigned)(i * p.Kg) * 4u : 0x40000000u;
+        }
+    }
 
     auto load_slab = [&](int slab) {
         a_ok = 0u; b_ok = 0u;
         {
             const int kk = slab * BK + a_kk;
             const bool kv = kk < p.Kg;
+            if (BUF) {
+                const unsigned a_k = kv ? (unsigned)kk * 4u : 0x80000000u;
 #pragma unroll
-            for (int ps = 0; ps < A_PASSES; ++ps) {
-                const int i = i0 + a_i + ps * A_RPP;
-                const bool ok = kv & (i < p.Co);
-                a_reg[ps] = Elem<T>::load(wt, ok ? i * p.Kg + kk : 0);   // clamped, branch-free
-                a_ok |= (ok ? 1u : 0u) << ps;
+                for (int ps = 0; ps < A_PASSES; ++ps)
+                    a_reg[ps] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs_w, a_k + a_voff[BUF ? ps : 0], 0, 0));
+            } else {
+#pragma unroll
+                for (int ps = 0; ps < A_PASSES; ++ps) {
+                    const int i = i0 + a_i + ps * A_RPP;
+                    const bool ok = kv & (i < p.Co);
+                    a_reg[ps] = Elem<T>::load(wt, ok ? i * p.Kg + kk : 0);   // clamped, branch-free
+                    a_ok |= (ok ? 1u : 0u) << ps;
+                }
             }
         }
 #pragma unroll
@@ -340,7 +360,7 @@ __global__ __launch_bounds__(WM * WN * 64, (TM * TN == 6 && BUF && NOPAD ? 3 : 1
     auto store_slab = [&](int buf) {
 #pragma unroll
         for (int ps = 0; ps < A_PASSES; ++ps)
-            As[buf][a_kk * LDA + a_i + ps * A_RPP] = ((a_ok >> ps) & 1u) ? a_reg[ps] : 0.0f;
+            As[buf][a_kk * LDA + a_i + ps * A_RPP] = (BUF || ((a_ok >> ps) & 1u)) ? a_reg[ps] : 0.0f;
 #pragma unroll
         for (int ps = 0; ps < B_PASSES; ++ps)
             Bs[buf][(ps * B_RPP + b_row) * BN + (tid % BN)] = (BUF || ((b_ok >> ps) & 1u)) ? b_reg[ps] : 0.0f;
@@ -488,7 +508,8 @@ hipError_t launch_flat(PixParams& p, hipStream_t st) {
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    const bool buf = p.in_bytes != 0 && p.in_bytes < (1u << 30);   // two-part offsets: tensor below 2^30 bytes
+    // two-part offsets: gathered tensor and filter below 2^30 bytes
+    const bool buf = p.in_bytes != 0 && p.in_bytes < (1u << 30) && (long long)p.Co * p.Kg * 4 < (1LL << 30);
 #define FLAT_LAUNCH(NOPAD_, BUF_)                                                                          \
     hipLaunchKernelGGL((igemm_flat_kernel<T, FUSED, NOPAD_, BUF_, TM, TN, WM, WN>), dim3((unsigned)total),     \
                        dim3(WM * WN * 64), 0, st, p)
