@@ -323,9 +323,15 @@ int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b);
 /* Storage address a tensor vertex is bound to at the moment (NULL for a bad id). */
 void* purine_graph_tensor_data(const purine_graph* g, int tensor_id);
 
-/* Graph iteration (section 2.2, Figure 3(c)): n_iters times { purine_graph_run; then
+/* Graph iteration (section 2.2, Figure 3(c)): n_iters times { one run of the graph; then
  * purine_graph_swap_storage(swap_a[i], swap_b[i]) for i < n_swaps }. The end of each run is the
- * synchronisation point between iterations. Stops at the first error and returns it. */
+ * synchronisation point between iterations, and the device keeps it: no operator of an iteration
+ * starts before every operator of the one before has finished (each stream waits for all the
+ * others), while the host goes on issuing and waits once, after the last iteration; results are
+ * those of n_iters calls of purine_graph_run with the swaps between them. Host operators wait for
+ * their device producers as in a single run. The firing log and the timing brackets are those of
+ * the last iteration. Stops issuing at the first error, waits for what was issued and returns
+ * the error. */
 int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const int* swap_b,
                          int n_swaps);
 

@@ -8,9 +8,10 @@
 //
 // On one GPU a `thread` is a HIP stream. Device work is asynchronous, so "completed" for the host
 // side bookkeeping means "issued on its stream": readiness is carried onto the device by stream
-// order inside a thread and by an event recorded after each operator that consumers on other
-// streams wait for. purine_graph_run returns only after the device work behind every sink has
-// finished, which is the synchronisation point that lets graphs be iterated (section 2.2).
+// order inside a thread and by an event recorded after an operator that a consumer on another
+// stream (or a host operator) has to wait for. purine_graph_run returns only after the device work
+// behind every sink has finished, which is the synchronisation point that lets graphs be iterated
+// (section 2.2); purine_graph_iterate keeps that point on the device between its iterations.
 #include <deque>
 #include <map>
 #include <string>
@@ -47,6 +48,11 @@ struct purine_graph {
     int timing_only = -1;   // >= 0: bracket this operator only, and give it the device to itself
     bool serial = false;    // every operator gets the device to itself
     std::map<int, hipEvent_t> drain;   // per stream: marks the work issued before the exclusive operator
+    // Filled by validation from the dispatcher's firing order (which depends on the graph alone):
+    // the producers whose completion event operator o has to wait for, and whether anybody waits
+    // for operator o's event at all (an event nobody waits for is not recorded).
+    std::vector<std::vector<int>> waits;
+    std::vector<char> record;
 };
 
 namespace {
@@ -126,6 +132,45 @@ hipStream_t stream_of(purine_graph* g, int thread, int* rc) {
     g->streams[thread] = s;
     g->stream_owned[thread] = true;
     return s;
+}
+
+// The dispatcher of section 2.1 as host bookkeeping: an operator is queued on its thread when all
+// its incoming tensors are ready, a tensor is ready when all its incoming operators have fired, one
+// operator per thread queue fires per sweep so that independent threads interleave. fire(o) returns
+// a status; the walk stops at the first error. Returns how many operators fired.
+template <class Fire>
+int dispatch(const purine_graph* g, Fire&& fire, int* rc) {
+    const int no = (int)g->ops.size(), nt = (int)g->tensors.size();
+    std::vector<int> inputs_pending(no), writers_pending(nt);
+    for (int t = 0; t < nt; ++t) writers_pending[t] = (int)g->tensors[t].writers.size();
+    std::map<int, std::deque<int>> queues;      // thread id -> FIFO of operators ready to fire
+    for (int o = 0; o < no; ++o) {
+        int pend = 0;
+        for (int t : g->ops[o].in) if (writers_pending[t] > 0) ++pend;
+        inputs_pending[o] = pend;
+    }
+    for (int o = 0; o < no; ++o)
+        if (inputs_pending[o] == 0) queues[g->ops[o].thread].push_back(o);   // fed by source tensors only
+    int fired = 0;
+    bool progress = true;
+    *rc = PURINE_OK;
+    while (fired < no && progress) {
+        progress = false;
+        for (auto& kv : queues) {
+            if (kv.second.empty()) continue;
+            const int o = kv.second.front();
+            kv.second.pop_front();
+            if ((*rc = fire(o)) != PURINE_OK) return fired;
+            ++fired;
+            progress = true;
+            // the operator has completed as far as the dispatcher is concerned: update its outgoing tensors
+            for (int t : g->ops[o].out)
+                if (--writers_pending[t] == 0)
+                    for (int rd : g->tensors[t].readers)
+                        if (--inputs_pending[rd] == 0) queues[g->ops[rd].thread].push_back(rd);
+        }
+    }
+    return fired;
 }
 
 // Issues one device operator on `st`. Storage identity rules of the in-place forms are checked here.
@@ -368,107 +413,143 @@ int purine_graph_validate(purine_graph* g) {
             if (x.op == y.op || !(x.write || y.write) || !hit(x.r, y.r)) continue;
             if (!ordered(x.op, y.op)) return PURINE_E_GRAPH;
         }
+    // Which completion events are needed. Streams are FIFO, so of an operator's producers on one
+    // other stream only the one issued last has to be waited for, and not even that one when an
+    // earlier operator of the consumer's stream has already waited for it or for a later one.
+    g->waits.assign(no, {});
+    g->record.assign(no, 0);
+    {
+        std::vector<int> issued(no, -1);
+        std::map<std::pair<int, int>, int> covered;   // (consumer thread, producer thread) -> issue index waited for
+        int n = 0, rc = PURINE_OK;
+        const int fired = dispatch(g, [&](int o) {
+            const auto& op = g->ops[o];
+            issued[o] = n++;
+            std::map<int, int> last;   // producer thread -> its producer issued last
+            for (int t : op.in)
+                for (int wr : g->tensors[t].writers) {
+                    const auto& w = g->ops[wr];
+                    if (w.kind == PURINE_OP_HOST_NOP) continue;          // completes on the host before this fires
+                    if (op.kind == PURINE_OP_HOST_NOP) {                  // the host waits for every device producer
+                        g->waits[o].push_back(wr);
+                        g->record[wr] = 1;
+                        continue;
+                    }
+                    if (w.thread == op.thread) continue;
+                    auto it = last.find(w.thread);
+                    if (it == last.end() || issued[it->second] < issued[wr]) last[w.thread] = wr;
+                }
+            for (const auto& kv : last) {
+                const auto key = std::make_pair(op.thread, kv.first);
+                auto it = covered.find(key);
+                if (it != covered.end() && it->second >= issued[kv.second]) continue;
+                covered[key] = issued[kv.second];
+                g->waits[o].push_back(kv.second);
+                g->record[kv.second] = 1;
+            }
+            return (int)PURINE_OK;
+        }, &rc);
+        if (fired < no) return PURINE_E_GRAPH;   // some operator can never fire
+    }
     g->validated = true;
     return PURINE_OK;
 }
 
-int purine_graph_run(purine_graph* g) {
-    if (!g) return PURINE_E_NULL;
+namespace {
+
+// Every stream of the graph waits for everything issued so far on all the others: a barrier between
+// two runs that the device keeps, without the host waiting.
+int join_streams(purine_graph* g) {
+    if (g->streams.size() < 2) return PURINE_OK;
+    for (auto& sk : g->streams) {
+        hipEvent_t& ev = g->drain[sk.first];
+        if ((!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) ||
+            hipEventRecord(ev, sk.second) != hipSuccess) return PURINE_E_HIP;
+    }
+    for (auto& sk : g->streams)
+        for (auto& other : g->streams)
+            if (other.first != sk.first && hipStreamWaitEvent(sk.second, g->drain[other.first], 0) != hipSuccess)
+                return PURINE_E_HIP;
+    return PURINE_OK;
+}
+
+int wait_streams(purine_graph* g) {
+    int rc = PURINE_OK;
+    if (g->uses_device)
+        for (auto& kv : g->streams)
+            if (hipStreamSynchronize(kv.second) != hipSuccess) rc = PURINE_E_HIP;
+    return rc;
+}
+
+// One pass of the dispatcher over the graph, issuing device work; the host does not wait for it.
+int run_issue(purine_graph* g) {
     if (!g->validated) {
         int rc = purine_graph_validate(g);
         if (rc != PURINE_OK) return rc;
     }
-    const int no = (int)g->ops.size(), nt = (int)g->tensors.size();
+    const int no = (int)g->ops.size();
     g->fire_log.clear();
-    // dispatcher state (section 2.1)
-    std::vector<int> inputs_pending(no), writers_pending(nt);
-    for (int t = 0; t < nt; ++t) writers_pending[t] = (int)g->tensors[t].writers.size();
-    std::map<int, std::deque<int>> queues;      // thread id -> FIFO of operators ready to fire
-    auto enqueue_if_ready = [&](int o) { if (inputs_pending[o] == 0) queues[g->ops[o].thread].push_back(o); };
-    for (int o = 0; o < no; ++o) {
-        int pend = 0;
-        for (int t : g->ops[o].in) if (writers_pending[t] > 0) ++pend;
-        inputs_pending[o] = pend;
-    }
-    for (int o = 0; o < no; ++o) enqueue_if_ready(o);   // operators fed by source tensors only
-
-    int fired = 0, rc = PURINE_OK;
-    bool progress = true;
-    while (fired < no && progress && rc == PURINE_OK) {
-        progress = false;
-        // one operator per thread queue per sweep, so that independent threads interleave
-        for (auto& kv : queues) {
-            if (kv.second.empty()) continue;
-            const int o = kv.second.front();
-            kv.second.pop_front();
-            purine_graph::Op& op = g->ops[o];
-            if (op.kind != PURINE_OP_HOST_NOP) {
-                hipStream_t st = stream_of(g, op.thread, &rc);
-                if (rc != PURINE_OK) break;
-                // wait for producers that ran on other streams
-                for (int t : op.in)
-                    for (int wr : g->tensors[t].writers) {
-                        purine_graph::Op& w = g->ops[wr];
-                        if (w.kind == PURINE_OP_HOST_NOP || w.thread == op.thread || !w.done) continue;
-                        if (hipStreamWaitEvent(st, w.done, 0) != hipSuccess) { rc = PURINE_E_HIP; break; }
-                    }
-                if (rc != PURINE_OK) break;
-                op.timed = false;
-                const bool timed_op = g->timing && (g->timing_only < 0 || g->timing_only == o) &&
-                                      op.kind != PURINE_OP_ALIAS;   // launches nothing to bracket
-                const bool exclusive = g->serial || (g->timing && g->timing_only == o);
-                if (exclusive) {
-                    // the one measured operator runs alone: its stream waits for everything issued so
-                    // far on the other streams, and (below) they wait for it
-                    for (auto& sk : g->streams) {
-                        if (sk.first == op.thread) continue;
-                        hipEvent_t& ev = g->drain[sk.first];
-                        if ((!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) ||
-                            hipEventRecord(ev, sk.second) != hipSuccess ||
-                            hipStreamWaitEvent(st, ev, 0) != hipSuccess) { rc = PURINE_E_HIP; break; }
-                    }
-                    if (rc != PURINE_OK) break;
+    int rc = PURINE_OK;
+    const int fired = dispatch(g, [&](int o) {
+        purine_graph::Op& op = g->ops[o];
+        int op_rc = PURINE_OK;
+        if (op.kind != PURINE_OP_HOST_NOP) {
+            hipStream_t st = stream_of(g, op.thread, &op_rc);
+            if (op_rc != PURINE_OK) return op_rc;
+            // wait for producers that ran on other streams
+            for (int wr : g->waits[o])
+                if (hipStreamWaitEvent(st, g->ops[wr].done, 0) != hipSuccess) return (int)PURINE_E_HIP;
+            op.timed = false;
+            const bool timed_op = g->timing && (g->timing_only < 0 || g->timing_only == o) &&
+                                  op.kind != PURINE_OP_ALIAS;   // launches nothing to bracket
+            const bool exclusive = g->serial || (g->timing && g->timing_only == o);
+            if (exclusive) {
+                // the one measured operator runs alone: its stream waits for everything issued so
+                // far on the other streams, and (below) they wait for it
+                for (auto& sk : g->streams) {
+                    if (sk.first == op.thread) continue;
+                    hipEvent_t& ev = g->drain[sk.first];
+                    if ((!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) ||
+                        hipEventRecord(ev, sk.second) != hipSuccess ||
+                        hipStreamWaitEvent(st, ev, 0) != hipSuccess) return (int)PURINE_E_HIP;
                 }
-                if (timed_op) {
-                    if ((!op.t0 && hipEventCreate(&op.t0) != hipSuccess) ||
-                        (!op.t1 && hipEventCreate(&op.t1) != hipSuccess)) { rc = PURINE_E_HIP; break; }
-                    purine_set_kernel_probe(op.t0, op.t1);
-                }
-                rc = issue(g, op, st);
-                if (timed_op) { purine_set_kernel_probe(nullptr, nullptr); op.timed = rc == PURINE_OK; }
-                if (rc != PURINE_OK) break;
-                if (!op.done && hipEventCreateWithFlags(&op.done, hipEventDisableTiming) != hipSuccess) { rc = PURINE_E_HIP; break; }
-                if (hipEventRecord(op.done, st) != hipSuccess) { rc = PURINE_E_HIP; break; }
-                if (exclusive)
-                    for (auto& sk : g->streams)
-                        if (sk.first != op.thread && hipStreamWaitEvent(sk.second, op.done, 0) != hipSuccess) rc = PURINE_E_HIP;
-                if (rc != PURINE_OK) break;
-            } else {
-                // a host operator completes on the host: wait for the device producers it consumes, so
-                // that readiness keeps its meaning for whatever depends on this operator
-                for (int t : op.in)
-                    for (int wr : g->tensors[t].writers)
-                        if (g->ops[wr].done && hipEventSynchronize(g->ops[wr].done) != hipSuccess) rc = PURINE_E_HIP;
-                if (rc != PURINE_OK) break;
             }
-            g->fire_log.push_back(o);
-            ++fired;
-            progress = true;
-            // the operator has completed as far as the dispatcher is concerned: update its outgoing tensors
-            for (int t : op.out)
-                if (--writers_pending[t] == 0)
-                    for (int rd : g->tensors[t].readers)
-                        if (--inputs_pending[rd] == 0) queues[g->ops[rd].thread].push_back(rd);
+            if (timed_op) {
+                if ((!op.t0 && hipEventCreate(&op.t0) != hipSuccess) ||
+                    (!op.t1 && hipEventCreate(&op.t1) != hipSuccess)) return (int)PURINE_E_HIP;
+                purine_set_kernel_probe(op.t0, op.t1);
+            }
+            op_rc = issue(g, op, st);
+            if (timed_op) { purine_set_kernel_probe(nullptr, nullptr); op.timed = op_rc == PURINE_OK; }
+            if (op_rc != PURINE_OK) return op_rc;
+            if (g->record[o] || exclusive) {
+                if (!op.done && hipEventCreateWithFlags(&op.done, hipEventDisableTiming) != hipSuccess) return (int)PURINE_E_HIP;
+                if (hipEventRecord(op.done, st) != hipSuccess) return (int)PURINE_E_HIP;
+            }
+            if (exclusive)
+                for (auto& sk : g->streams)
+                    if (sk.first != op.thread && hipStreamWaitEvent(sk.second, op.done, 0) != hipSuccess) return (int)PURINE_E_HIP;
+        } else {
+            // a host operator completes on the host: wait for the device producers it consumes, so
+            // that readiness keeps its meaning for whatever depends on this operator
+            for (int wr : g->waits[o])
+                if (hipEventSynchronize(g->ops[wr].done) != hipSuccess) return (int)PURINE_E_HIP;
         }
-    }
-    // all sinks reached: wait for the device work behind them (every stream the run used)
-    int sync_rc = PURINE_OK;
-    if (g->uses_device)
-        for (auto& kv : g->streams)
-            if (hipStreamSynchronize(kv.second) != hipSuccess) sync_rc = PURINE_E_HIP;
+        g->fire_log.push_back(o);
+        return (int)PURINE_OK;
+    }, &rc);
     if (rc != PURINE_OK) return rc;
-    if (fired < no) return PURINE_E_GRAPH;   // some operator can never fire
-    return sync_rc;
+    return fired < no ? PURINE_E_GRAPH : PURINE_OK;
+}
+
+}  // namespace
+
+int purine_graph_run(purine_graph* g) {
+    if (!g) return PURINE_E_NULL;
+    const int rc = run_issue(g);
+    // all sinks reached: wait for the device work behind them (every stream the run used)
+    const int sync_rc = wait_streams(g);
+    return rc != PURINE_OK ? rc : sync_rc;
 }
 
 int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b) {
@@ -513,13 +594,17 @@ void* purine_graph_tensor_data(const purine_graph* g, int tensor_id) {
 int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const int* swap_b, int n_swaps) {
     if (!g) return PURINE_E_NULL;
     if (n_iters < 0 || n_swaps < 0 || (n_swaps > 0 && (!swap_a || !swap_b))) return PURINE_E_ARG;
-    for (int it = 0; it < n_iters; ++it) {
-        int rc = purine_graph_run(g);   // returns at the synchronisation point: all sinks reached
-        if (rc != PURINE_OK) return rc;
-        for (int s = 0; s < n_swaps; ++s)
-            if ((rc = purine_graph_swap_storage(g, swap_a[s], swap_b[s])) != PURINE_OK) return rc;
+    // Between two iterations the synchronisation point is kept by the device (every stream waits for
+    // all the others), not by the host, which runs ahead issuing the next iteration; the kernels of
+    // an iteration were issued with the addresses bound at that moment, so the swap is safe.
+    int rc = PURINE_OK;
+    for (int it = 0; it < n_iters && rc == PURINE_OK; ++it) {
+        if (it > 0) rc = join_streams(g);
+        if (rc == PURINE_OK) rc = run_issue(g);
+        for (int s = 0; s < n_swaps && rc == PURINE_OK; ++s) rc = purine_graph_swap_storage(g, swap_a[s], swap_b[s]);
     }
-    return PURINE_OK;
+    const int sync_rc = wait_streams(g);
+    return rc != PURINE_OK ? rc : sync_rc;
 }
 
 int purine_graph_enable_timing(purine_graph* g, int on) {

@@ -37,6 +37,7 @@ class GraphBuilder:
         self.ids = {}        # name -> tensor vertex id
         self.ops = []        # (op id, kind, in names, out names, attrs kept alive)
         self.conv_records = []   # one dict per conv layer, naming the vertices around each operator
+        self.swaps = []          # (old, new) parameter vertices exchanged after every iteration
         self._keep = []
 
     def close(self):
