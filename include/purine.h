@@ -335,6 +335,18 @@ void* purine_graph_tensor_data(const purine_graph* g, int tensor_id);
 int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const int* swap_b,
                          int n_swaps);
 
+/* What validation planned for the runs to come (both need a validated graph, PURINE_E_GRAPH
+ * otherwise; the order the dispatcher fires in depends on the graph alone, section 2.1).
+ * purine_graph_issue_plan: that firing order; writes up to cap operator ids, returns their number.
+ * purine_graph_op_waits: the producers whose completion operator op_id will wait for before it is
+ * issued: events on other streams for a device operator, on the host for a host operator.
+ * Producers on the operator's own stream are ordered by the stream, and a producer is left out
+ * when waiting for another one already implies it (a later operator of the same stream, or a wait
+ * made by an earlier operator of the consumer's stream). An operator nobody waits for records no
+ * event. Writes up to cap ids, returns their number; PURINE_E_ARG for a bad id. */
+int purine_graph_issue_plan(const purine_graph* g, int* op_ids, int cap);
+int purine_graph_op_waits(const purine_graph* g, int op_id, int* producer_ids, int cap);
+
 /* Firing order of the last run: writes up to cap operator ids, returns how many operators fired. */
 int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap);
 int purine_graph_num_ops(const purine_graph* g);

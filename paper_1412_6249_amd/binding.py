@@ -110,6 +110,8 @@ _SIGS = {
     "purine_graph_iterate": (ctypes.c_int, [_vp, ctypes.c_int, _ip, _ip, ctypes.c_int]),
     "purine_sgd_update": (ctypes.c_int, [_T, _T, _T, ctypes.c_float, _vp]),
     "purine_graph_fire_log": (ctypes.c_int, [_vp, _ip, ctypes.c_int]),
+    "purine_graph_issue_plan": (ctypes.c_int, [_vp, _ip, ctypes.c_int]),
+    "purine_graph_op_waits": (ctypes.c_int, [_vp, ctypes.c_int, _ip, ctypes.c_int]),
     "purine_graph_num_ops": (ctypes.c_int, [_vp]),
     "purine_graph_num_tensors": (ctypes.c_int, [_vp]),
     "purine_debug_fastdiv": (ctypes.c_uint32, [ctypes.c_uint32, ctypes.c_uint32]),
@@ -472,6 +474,26 @@ def purine_graph_iterate(g, n_iters, swaps=()):
     a = (ctypes.c_int * max(1, n))(*[int(s[0]) for s in swaps])
     b = (ctypes.c_int * max(1, n))(*[int(s[1]) for s in swaps])
     _check(_lib.purine_graph_iterate(g, int(n_iters), a, b, n), "purine_graph_iterate")
+
+
+def purine_graph_issue_plan(g):
+    """Firing order planned by validation (the graph must have been validated)."""
+    n = _lib.purine_graph_num_ops(g)
+    buf = (ctypes.c_int * max(1, n))()
+    got = _lib.purine_graph_issue_plan(g, buf, n)
+    if got < 0:
+        _check(got, "purine_graph_issue_plan")
+    return [int(buf[i]) for i in range(min(n, got))]
+
+
+def purine_graph_op_waits(g, op_id):
+    """Producers whose completion operator op_id waits for before it is issued."""
+    n = _lib.purine_graph_num_ops(g)
+    buf = (ctypes.c_int * max(1, n))()
+    got = _lib.purine_graph_op_waits(g, int(op_id), buf, n)
+    if got < 0:
+        _check(got, "purine_graph_op_waits")
+    return [int(buf[i]) for i in range(min(n, got))]
 
 
 def purine_graph_fire_log(g):

@@ -53,6 +53,7 @@ struct purine_graph {
     // for operator o's event at all (an event nobody waits for is not recorded).
     std::vector<std::vector<int>> waits;
     std::vector<char> record;
+    std::vector<int> plan;   // the firing order itself
 };
 
 namespace {
@@ -418,6 +419,7 @@ int purine_graph_validate(purine_graph* g) {
     // earlier operator of the consumer's stream has already waited for it or for a later one.
     g->waits.assign(no, {});
     g->record.assign(no, 0);
+    g->plan.clear();
     {
         std::vector<int> issued(no, -1);
         std::map<std::pair<int, int>, int> covered;   // (consumer thread, producer thread) -> issue index waited for
@@ -425,6 +427,7 @@ int purine_graph_validate(purine_graph* g) {
         const int fired = dispatch(g, [&](int o) {
             const auto& op = g->ops[o];
             issued[o] = n++;
+            g->plan.push_back(o);
             std::map<int, int> last;   // producer thread -> its producer issued last
             for (int t : op.in)
                 for (int wr : g->tensors[t].writers) {
@@ -634,6 +637,26 @@ int purine_graph_op_elapsed_ms(purine_graph* g, int op_id, float* ms) {
     purine_graph::Op& op = g->ops[op_id];
     if (!op.timed || !op.t0 || !op.t1) return PURINE_E_ARG;
     return hipEventElapsedTime(ms, op.t0, op.t1) == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
+int purine_graph_issue_plan(const purine_graph* g, int* op_ids, int cap) {
+    if (!g) return PURINE_E_NULL;
+    if (!g->validated) return PURINE_E_GRAPH;
+    const int n = (int)g->plan.size();
+    if (op_ids)
+        for (int i = 0; i < n && i < cap; ++i) op_ids[i] = g->plan[i];
+    return n;
+}
+
+int purine_graph_op_waits(const purine_graph* g, int op_id, int* producer_ids, int cap) {
+    if (!g) return PURINE_E_NULL;
+    if (!g->validated) return PURINE_E_GRAPH;
+    if (op_id < 0 || op_id >= (int)g->ops.size()) return PURINE_E_ARG;
+    const auto& w = g->waits[op_id];
+    const int n = (int)w.size();
+    if (producer_ids)
+        for (int i = 0; i < n && i < cap; ++i) producer_ids[i] = w[i];
+    return n;
 }
 
 int purine_graph_fire_log(const purine_graph* g, int* op_ids, int cap) {

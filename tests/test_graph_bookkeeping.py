@@ -303,3 +303,120 @@ def test_channel_slice_views_in_the_hazard_analysis():
         pa.purine_graph_add_tensor(g, binding.raw_desc(base, F32, dims, nstride=8))
     assert e.value.status == -2
     pa.purine_graph_destroy(g)
+
+
+# ---------------------------------------------------------------------------------------------
+# Planned waits: an event is recorded, and waited for, only where stream order does not already
+# give the ordering. Checked against an independent model of what each operator can rely on.
+
+def _random_device_graph(rng, n_ops, n_threads, host_share):
+    """Random bi-graph of Sum operators (device kind, made-up addresses: nothing is launched) and
+    host operators spread over threads. Returns (g, ops) with ops: id -> (ins, outs, thread, kind)."""
+    g = pa.purine_graph_create()
+    dims = (1, 2, 4, 4)
+    nbytes = 1 * 2 * 4 * 4 * 4
+    tensors = [pa.purine_graph_add_tensor(g, binding.raw_desc(0x10000 + i * 0x1000, F32, dims), "src%d" % i)
+               for i in range(3)]
+    next_ptr = 0x100000
+    ops = {}
+    for i in range(n_ops):
+        ins = rng.sample(tensors, rng.randint(1, min(3, len(tensors))))
+        out = pa.purine_graph_add_tensor(g, binding.raw_desc(next_ptr, F32, dims), "t%d" % i)
+        next_ptr += max(0x1000, nbytes)
+        thread = rng.randrange(n_threads)
+        kind = pa.OP_HOST_NOP if rng.random() < host_share else pa.OP_SUM
+        o = pa.purine_graph_add_op(g, kind, ins, [out], thread)
+        ops[o] = (ins, [out], thread, kind)
+        tensors.append(out)
+    return g, ops
+
+
+def _check_planned_waits(g, ops):
+    pa.purine_graph_validate(g)
+    plan = pa.purine_graph_issue_plan(g)
+    check_legal(plan, {o: v[:3] for o, v in ops.items()})
+    writers = {}
+    for o, (ins, outs, _, _) in ops.items():
+        for t in outs:
+            writers.setdefault(t, []).append(o)
+    known = {}            # device operator -> operators certain to have completed when it starts
+    host_known = set()    # what the host has waited for so far
+    last_on_stream = {}
+    n_waits = 0
+    for o in plan:
+        ins, outs, thread, kind = ops[o]
+        waits = pa.purine_graph_op_waits(g, o)
+        producers = {w for t in ins for w in writers.get(t, []) if ops[w][3] != pa.OP_HOST_NOP}
+        assert set(waits) <= producers
+        assert len(set(waits)) == len(waits)
+        if kind == pa.OP_HOST_NOP:
+            for p in waits:
+                host_known |= known[p] | {p}
+            assert producers <= host_known, (o, producers - host_known)
+            continue
+        n_waits += len(waits)
+        assert all(ops[p][2] != thread for p in waits), "same-stream producers need no event"
+        assert len({ops[p][2] for p in waits}) == len(waits), "at most one wait per producer stream"
+        k = set(host_known)
+        prev = last_on_stream.get(thread)
+        if prev is not None:
+            k |= known[prev] | {prev}
+        for p in waits:
+            k |= known[p] | {p}
+        known[o] = k
+        last_on_stream[thread] = o
+        assert producers <= k, (o, producers - k)
+    return n_waits
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_planned_waits_cover_every_cross_stream_dependency(seed):
+    rng = random.Random(1000 + seed)
+    g, ops = _random_device_graph(rng, n_ops=rng.randint(5, 60), n_threads=rng.randint(1, 5),
+                                  host_share=rng.choice([0.0, 0.0, 0.15, 0.4]))
+    try:
+        _check_planned_waits(g, ops)
+    finally:
+        pa.purine_graph_destroy(g)
+
+
+def test_planned_waits_of_a_two_stream_layer_stack():
+    """Data path on thread 0, gradient-like consumers on thread 1: a consumer waits for the LAST
+    producer of the other stream only, and a later consumer does not wait again for what an earlier
+    one on its stream already waited for."""
+    g = pa.purine_graph_create()
+    dims = (1, 2, 4, 4)
+    def T(i, name):
+        return pa.purine_graph_add_tensor(g, binding.raw_desc(0x10000 + i * 0x1000, F32, dims), name)
+    x, a1, a2, a3, g1, g2, g3 = (T(i, n) for i, n in enumerate(["x", "a1", "a2", "a3", "g1", "g2", "g3"]))
+    f1 = pa.purine_graph_add_op(g, pa.OP_SUM, [x], [a1], 0)
+    f2 = pa.purine_graph_add_op(g, pa.OP_SUM, [a1], [a2], 0)
+    f3 = pa.purine_graph_add_op(g, pa.OP_SUM, [a2], [a3], 0)
+    c1 = pa.purine_graph_add_op(g, pa.OP_SUM, [a1, a3], [g1], 1)    # needs f1 and f3: waits for f3 only
+    c2 = pa.purine_graph_add_op(g, pa.OP_SUM, [a2, g1], [g2], 1)    # fires after c1; f2 is older than f3
+    c3 = pa.purine_graph_add_op(g, pa.OP_SUM, [g1, g2], [g3], 1)    # same stream: no event
+    pa.purine_graph_validate(g)
+    assert pa.purine_graph_op_waits(g, f1) == [] and pa.purine_graph_op_waits(g, f2) == []
+    assert pa.purine_graph_op_waits(g, c1) == [f3]
+    assert pa.purine_graph_op_waits(g, c2) == []
+    assert pa.purine_graph_op_waits(g, c3) == []
+    assert sorted(pa.purine_graph_issue_plan(g)) == [f1, f2, f3, c1, c2, c3]
+    pa.purine_graph_destroy(g)
+
+
+def test_plan_queries_need_a_validated_graph():
+    g = pa.purine_graph_create()
+    a, b = host_tensor(g), host_tensor(g)
+    o = nop(g, [a], [b])
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_issue_plan(g)
+    assert e.value.status == -6
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_op_waits(g, o)
+    assert e.value.status == -6
+    pa.purine_graph_validate(g)
+    assert pa.purine_graph_issue_plan(g) == [o]
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_graph_op_waits(g, 5)
+    assert e.value.status == -8
+    pa.purine_graph_destroy(g)
