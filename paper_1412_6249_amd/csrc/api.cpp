@@ -194,6 +194,12 @@ size_t purine_bias_bwd_workspace_bytes(const int64_t dy_dim[4], int32_t dtype) {
     return plan_bias_bwd((int)dy_dim[0], (int)dy_dim[1], (int)(dy_dim[2] * dy_dim[3])).ws_bytes;
 }
 
+// The bf16 multi-tap kernels address their channels-blocked copy of the gathered tensor with
+// 32-bit byte offsets (range-checked raw buffer loads): the copy has to stay below 2^31 bytes.
+static bool blocked_copy_too_large(const PixPlan& plan) {
+    return plan.blk_offset != 0 && plan.ws_bytes - plan.blk_offset >= 0x7fffffffull;
+}
+
 static int conv_fwd_impl(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* w,
                          const purine_tensor* b, purine_tensor* y, int relu, void* ws, size_t ws_bytes,
                          void* hip_stream) {
@@ -218,6 +224,7 @@ static int conv_fwd_impl(const purine_conv_desc* desc, const purine_tensor* x, c
     if (relu != 0 && relu != 1) return PURINE_E_ARG;
     epi.relu = relu;
     const PixPlan plan = plan_conv_pix(g, false, x->dtype, epi.bias || epi.relu);
+    if (blocked_copy_too_large(plan)) return PURINE_E_SHAPE;
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_pix(x->dtype, g, plan, x->data, w->data, y->data, 0.0f, ws, epi,
@@ -259,6 +266,7 @@ static int conv_bwd_data_impl(const purine_conv_desc* desc, const purine_tensor*
         epi.mask = act->data;
     }
     const PixPlan plan = plan_conv_pix(g, true, dy->dtype, epi.mask != nullptr);
+    if (blocked_copy_too_large(plan)) return PURINE_E_SHAPE;
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_pix(dy->dtype, g, plan, dy->data, w->data, dx->data, beta, ws, epi,

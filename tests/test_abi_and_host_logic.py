@@ -171,6 +171,21 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_sgd_update, w, wd, nw, float("inf"), stream=s) == -8
     assert status(pa.purine_sgd_update, w, wd, binding.raw_desc(fake + 0x100000 + 16, F32, (4, 3, 3, 3)), 0.1, stream=s) == -4  # partial overlap with w
     assert status(pa.purine_sgd_update, w, wd, wd, 0.1, stream=s) == -4                # new_w is dw
+    # size limits: no tensor with 2^31 or more elements; the bf16 multi-tap kernels' blocked copy of
+    # the gathered tensor must stay below 2^31 bytes (forward: x, backward-data: dy)
+    big = 1 << 40   # made-up, well separated addresses
+    x_big = binding.raw_desc(big, F32, (2, 64, 4096, 4096))                   # 2^31 elements
+    assert status(pa.purine_conv_fwd, d, x_big, binding.raw_desc(fake, F32, (4, 64, 3, 3)),
+                  binding.raw_desc(3 * big, F32, (2, 4, 4096, 4096)), stream=s) == -2
+    xb = binding.raw_desc(big, BF16, (2, 32, 4096, 4096))                     # 2^30 elements: copy of 2^31 bytes
+    wb = binding.raw_desc(fake, BF16, (8, 32, 3, 3))
+    yb = binding.raw_desc(3 * big, BF16, (2, 8, 4096, 4096))
+    assert status(pa.purine_conv_fwd, d, xb, wb, yb, stream=s) == -2
+    wb2 = binding.raw_desc(fake, BF16, (32, 8, 3, 3))                         # backward-data gathers dy = xb
+    assert status(pa.purine_conv_bwd_data, d, xb, wb2, yb, stream=s) == -2
+    xh = binding.raw_desc(big, BF16, (1, 32, 4096, 4096))                     # half of that passes this check
+    yh = binding.raw_desc(3 * big, BF16, (1, 8, 4096, 4096))
+    assert status(pa.purine_conv_fwd, d, xh, wb, yh, stream=s) == -5          # (stops at the missing workspace)
     # channel-slice views: x is channels 4..6 of a [2, 12, 8, 8] buffer
     xv = binding.raw_desc(fake + 4 * 64 * 4, F32, (2, 3, 8, 8), nstride=12 * 64)
     assert status(pa.purine_conv_bwd_data, d, y, w, xv, stream=s) == -5                # accepted up to the workspace
