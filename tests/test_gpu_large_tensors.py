@@ -127,3 +127,62 @@ def test_layer_near_the_size_limits(case):
     ref_db = oracle.bias_bwd(hdy)
     assert rel_l2(db.cpu().numpy(), ref_db) <= tol, ("fused bias_bwd", rel_l2(db.cpu().numpy(), ref_db))
     assert rel_l2(db2.cpu().numpy(), ref_db) <= tol, ("bias_bwd", rel_l2(db2.cpu().numpy(), ref_db))
+
+
+def test_pointwise_operators_near_the_size_limits():
+    """ReLU, fan-in sum, channel concatenation and both max-pooling forms of the workloads on a
+    1.10e9-element (4.4 GB) tensor: exact operators, compared whole and bit for bit with the oracle
+    (the pooling gradient with small-integer dy, so that its sums are exact in any order)."""
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import DEV
+
+    N, C, H, W = 3, 24, 3900, 3900
+    free, _ = torch.cuda.mem_get_info()
+    if free < 48 * 2 ** 30:
+        pytest.skip("needs 48 GiB of free device memory")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(6249)
+    x = torch.rand((N, C, H, W), generator=g, device=DEV) - 0.5
+    gr = torch.rand((N, C, H, W), generator=g, device=DEV) * 2 - 1
+    hx, hg = x.cpu().numpy(), gr.cpu().numpy()
+    out = torch.empty_like(x)
+
+    say("large pointwise: relu")
+    pa.purine_relu_fwd(x, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.relu_fwd(hx))
+    pa.purine_relu_bwd(x, gr, out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.relu_bwd(hx, hg))
+
+    say("large pointwise: sum")
+    pa.purine_sum([x, gr], out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), oracle.fan_in_sum([hx, hg]).astype(np.float32))
+
+    say("large pointwise: concat")
+    extra = torch.rand((N, 2, H, W), generator=g, device=DEV)
+    cat = torch.empty((N, C + 2, H, W), device=DEV)
+    pa.purine_concat_fwd([x, extra], cat)
+    torch.cuda.synchronize()
+    assert np.array_equal(cat.cpu().numpy(), oracle.concat_channels([hx, extra.cpu().numpy()]))
+    del cat, extra, hg
+
+    for window_, stride, pad in ((3, 1, 1), (3, 2, 0)):
+        say("large pointwise: max-pool", window_, stride, pad)
+        P = (H + 2 * pad - window_) // stride + 1
+        desc = pa.pool_desc(window_, stride, pad)
+        y = torch.empty((N, C, P, P), device=DEV)
+        arg = torch.empty((N, C, P, P), dtype=torch.int32, device=DEV)
+        pa.purine_maxpool_fwd(desc, x, y, arg)
+        torch.cuda.synchronize()
+        ref_y, ref_arg = oracle.maxpool_fwd(hx, window_, stride, pad)
+        assert np.array_equal(y.cpu().numpy(), ref_y)
+        assert np.array_equal(arg.cpu().numpy(), ref_arg)
+        dy = torch.randint(-2, 3, (N, C, P, P), generator=g, device=DEV).float()
+        pa.purine_maxpool_bwd(desc, dy, arg, out)
+        torch.cuda.synchronize()
+        ref_dx = oracle.maxpool_bwd(dy.cpu().numpy(), ref_arg, (N, C, H, W))
+        assert np.array_equal(out.cpu().numpy(), ref_dx.astype(np.float32))
+        del y, arg, dy, ref_y, ref_arg, ref_dx
