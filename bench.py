@@ -108,6 +108,8 @@ def main():
                     help="config 3: keep the three 1x1 convolutions on the module input as separate operators "
                          "and the Concat copies (default: one merged operator, concatenation by address "
                          "through channel-slice views)")
+    ap.add_argument("--replay", action="store_true",
+                    help="executor replay mode: the unbracketed steps launch a recorded HIP graph of the pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sample-every", type=int, default=4,
                     help="bracket the dominant kernel (which then runs alone) on every n-th timed step")
@@ -159,6 +161,10 @@ def main():
     # loses the overlap this one operator would otherwise have had (about 6 % of the step when
     # done every step, 1.5 % at every fourth); that cost is part of the reported value.
     pa.purine_graph_set_serial(gb.g, False)
+    if args.replay:
+        pa.purine_graph_set_replay(gb.g, True)
+        pa.purine_graph_enable_timing(gb.g, False)
+        gb.run()                      # records the pass (outside the timed region)
     dom_ms, dom_n = 0.0, 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -216,6 +222,8 @@ def main():
     if cfg in (2, 4):
         gb.close()
         gb2 = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, first_layer_dx=False)
+        if args.replay:
+            pa.purine_graph_set_replay(gb2.g, True)
         for _ in range(max(1, args.warmup)):
             gb2.run()
         torch.cuda.synchronize()
@@ -234,6 +242,8 @@ def main():
     gb.close()
     gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused,
                         first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6, merge_1x1=merge)
+    if args.replay:
+        pa.purine_graph_set_replay(gb.g, True)
     gb.iterate(max(2, args.warmup))
     torch.cuda.synchronize()
     s0 = time.perf_counter()
@@ -255,7 +265,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": dtype, "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[cfg], "conv_gflop_per_step": round(flop / 1e9, 2),
-                   "executor": "bi-graph, %s, %s" % ("1 stream" if args.single_stream else "3+ streams",
+                   "executor": "bi-graph, %s%s, %s" % ("1 stream" if args.single_stream else "3+ streams",
+                                                        ", recorded pass replayed" if args.replay else "",
                                                       "separate bias/relu ops" if args.unfused
                                                       else "bias+relu fused into conv vertices"
                                                       + (", merged 1x1 + concat by address" if merge else "")),

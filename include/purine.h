@@ -339,6 +339,19 @@ void* purine_graph_tensor_data(const purine_graph* g, int tensor_id);
 int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const int* swap_b,
                          int n_swaps);
 
+/* Replay mode (off by default). on != 0: the next run records the device work of one pass, on all
+ * its streams, into a HIP graph (stream capture; the completion events between operators become
+ * edges of that graph) and launches it; later runs launch the recorded graph again instead of
+ * issuing every operator. One recording is kept per binding of tensor vertices to storage, so
+ * iterations that alternate between two bindings through purine_graph_swap_storage record twice
+ * and replay from then on; adding a vertex or setting a stream discards the recordings. A pass is
+ * replayed only if it is all device work on streams the graph created itself and neither timing
+ * nor serial mode is on; otherwise the run issues its operators directly, as with replay off.
+ * Results are bit-identical either way. Operator arguments are read when a pass is recorded:
+ * change nothing behind the graph's back (contents of tensors may change freely, addresses and
+ * attributes may not). on == 0 discards the recordings. */
+int purine_graph_set_replay(purine_graph* g, int on);
+
 /* What validation planned for the runs to come (both need a validated graph, PURINE_E_GRAPH
  * otherwise; the order the dispatcher fires in depends on the graph alone, section 2.1).
  * purine_graph_issue_plan: that firing order; writes up to cap operator ids, returns their number.

@@ -110,6 +110,7 @@ _SIGS = {
     "purine_graph_iterate": (ctypes.c_int, [_vp, ctypes.c_int, _ip, _ip, ctypes.c_int]),
     "purine_sgd_update": (ctypes.c_int, [_T, _T, _T, ctypes.c_float, _vp]),
     "purine_graph_fire_log": (ctypes.c_int, [_vp, _ip, ctypes.c_int]),
+    "purine_graph_set_replay": (ctypes.c_int, [_vp, ctypes.c_int]),
     "purine_graph_issue_plan": (ctypes.c_int, [_vp, _ip, ctypes.c_int]),
     "purine_graph_op_waits": (ctypes.c_int, [_vp, ctypes.c_int, _ip, ctypes.c_int]),
     "purine_graph_num_ops": (ctypes.c_int, [_vp]),
@@ -474,6 +475,10 @@ def purine_graph_iterate(g, n_iters, swaps=()):
     a = (ctypes.c_int * max(1, n))(*[int(s[0]) for s in swaps])
     b = (ctypes.c_int * max(1, n))(*[int(s[1]) for s in swaps])
     _check(_lib.purine_graph_iterate(g, int(n_iters), a, b, n), "purine_graph_iterate")
+
+
+def purine_graph_set_replay(g, on):
+    _check(_lib.purine_graph_set_replay(g, 1 if on else 0), "purine_graph_set_replay")
 
 
 def purine_graph_issue_plan(g):

@@ -54,6 +54,12 @@ struct purine_graph {
     std::vector<std::vector<int>> waits;
     std::vector<char> record;
     std::vector<int> plan;   // the firing order itself
+    // Replay mode: one pass of the dispatcher recorded into a HIP graph per binding of tensor
+    // vertices to storage (the swap step alternates between two of them).
+    struct Captured { std::vector<void*> key; hipGraph_t graph; hipGraphExec_t exec; };
+    bool replay = false;
+    std::vector<Captured> captured;
+    hipEvent_t fork = nullptr;
 };
 
 namespace {
@@ -133,6 +139,14 @@ hipStream_t stream_of(purine_graph* g, int thread, int* rc) {
     g->streams[thread] = s;
     g->stream_owned[thread] = true;
     return s;
+}
+
+void drop_captured(purine_graph* g) {
+    for (auto& c : g->captured) {
+        if (c.exec) (void)hipGraphExecDestroy(c.exec);
+        if (c.graph) (void)hipGraphDestroy(c.graph);
+    }
+    g->captured.clear();
 }
 
 // The dispatcher of section 2.1 as host bookkeeping: an operator is queued on its thread when all
@@ -272,6 +286,8 @@ void purine_graph_destroy(purine_graph* g) {
         if (op.t0) (void)hipEventDestroy(op.t0);
         if (op.t1) (void)hipEventDestroy(op.t1);
     }
+    drop_captured(g);
+    if (g->fork) (void)hipEventDestroy(g->fork);
     for (auto& kv : g->drain) if (kv.second) (void)hipEventDestroy(kv.second);
     for (auto& kv : g->streams)
         if (g->stream_owned[kv.first]) (void)hipStreamDestroy(kv.second);
@@ -290,6 +306,7 @@ int purine_graph_add_tensor(purine_graph* g, const purine_tensor* t, const char*
     if (name) v.name = name;
     g->tensors.push_back(v);
     g->validated = false;
+    drop_captured(g);
     return (int)g->tensors.size() - 1;
 }
 
@@ -340,6 +357,7 @@ int purine_graph_add_op(purine_graph* g, int op_kind, const purine_op_attrs* att
     for (int t : g->ops[id].out) g->tensors[t].writers.push_back(id);
     if (op_kind != PURINE_OP_HOST_NOP) g->uses_device = true;
     g->validated = false;
+    drop_captured(g);
     return id;
 }
 
@@ -350,6 +368,7 @@ int purine_graph_set_stream(purine_graph* g, int thread_id, void* hip_stream) {
     if (it != g->streams.end() && g->stream_owned[thread_id]) (void)hipStreamDestroy(it->second);
     g->streams[thread_id] = (hipStream_t)hip_stream;
     g->stream_owned[thread_id] = false;
+    drop_captured(g);
     return PURINE_OK;
 }
 
@@ -545,14 +564,97 @@ int run_issue(purine_graph* g) {
     return fired < no ? PURINE_E_GRAPH : PURINE_OK;
 }
 
+// Replay applies to a pass that is all device work on streams of the graph's own, issued the
+// plain way (no brackets, no exclusive operators); anything else is issued directly.
+bool replay_applies(const purine_graph* g) {
+    if (!g->replay || !g->uses_device || g->timing || g->serial) return false;
+    for (const auto& op : g->ops)
+        if (op.kind == PURINE_OP_HOST_NOP) return false;
+    for (const auto& kv : g->stream_owned)
+        if (!kv.second) return false;
+    return true;
+}
+
+// Records one pass of the dispatcher into a HIP graph: the first stream is the origin of the
+// capture, the others join it through an event at the start and hand their tails back through an
+// event at the end, so the completion events between operators become edges of the graph.
+int capture_pass(purine_graph* g, purine_graph::Captured* out) {
+    int rc = PURINE_OK;
+    for (const auto& op : g->ops) {           // every stream must exist before the capture starts
+        (void)stream_of(g, op.thread, &rc);
+        if (rc != PURINE_OK) return rc;
+    }
+    hipStream_t origin = g->streams.begin()->second;
+    if (!g->fork && hipEventCreateWithFlags(&g->fork, hipEventDisableTiming) != hipSuccess) return PURINE_E_HIP;
+    for (auto& sk : g->streams) {
+        hipEvent_t& ev = g->drain[sk.first];
+        if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return PURINE_E_HIP;
+    }
+    if (hipStreamBeginCapture(origin, hipStreamCaptureModeRelaxed) != hipSuccess) return PURINE_E_HIP;
+    bool ok = hipEventRecord(g->fork, origin) == hipSuccess;
+    for (auto& sk : g->streams)
+        if (ok && sk.second != origin) ok = hipStreamWaitEvent(sk.second, g->fork, 0) == hipSuccess;
+    rc = ok ? run_issue(g) : PURINE_E_HIP;
+    for (auto& sk : g->streams) {
+        if (sk.second == origin) continue;
+        hipEvent_t ev = g->drain[sk.first];
+        if (hipEventRecord(ev, sk.second) != hipSuccess || hipStreamWaitEvent(origin, ev, 0) != hipSuccess)
+            rc = rc != PURINE_OK ? rc : PURINE_E_HIP;
+    }
+    hipGraph_t graph = nullptr;
+    const hipError_t e = hipStreamEndCapture(origin, &graph);   // ends the capture also after an error
+    if (rc == PURINE_OK && (e != hipSuccess || !graph)) rc = PURINE_E_HIP;
+    hipGraphExec_t exec = nullptr;
+    if (rc == PURINE_OK && hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) != hipSuccess) rc = PURINE_E_HIP;
+    if (rc != PURINE_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        (void)hipGetLastError();
+        return rc;
+    }
+    out->graph = graph;
+    out->exec = exec;
+    return PURINE_OK;
+}
+
+// Launches the recorded pass for the current binding of vertices to storage (recording it first
+// if there is none yet) on the origin stream. The host does not wait.
+int replay_pass(purine_graph* g) {
+    if (!g->validated) {
+        int rc = purine_graph_validate(g);
+        if (rc != PURINE_OK) return rc;
+    }
+    std::vector<void*> key;
+    key.reserve(g->tensors.size());
+    for (const auto& t : g->tensors) key.push_back(t.desc.data);
+    purine_graph::Captured* hit = nullptr;
+    for (auto& c : g->captured)
+        if (c.key == key) hit = &c;
+    if (!hit) {
+        if (g->captured.size() >= 4) drop_captured(g);   // a swap cycle has two bindings; this is a bound
+        purine_graph::Captured c{key, nullptr, nullptr};
+        const int rc = capture_pass(g, &c);
+        if (rc != PURINE_OK) return rc;
+        g->captured.push_back(c);
+        hit = &g->captured.back();
+    }
+    return hipGraphLaunch(hit->exec, g->streams.begin()->second) == hipSuccess ? PURINE_OK : PURINE_E_HIP;
+}
+
 }  // namespace
 
 int purine_graph_run(purine_graph* g) {
     if (!g) return PURINE_E_NULL;
-    const int rc = run_issue(g);
+    const int rc = replay_applies(g) ? replay_pass(g) : run_issue(g);
     // all sinks reached: wait for the device work behind them (every stream the run used)
     const int sync_rc = wait_streams(g);
     return rc != PURINE_OK ? rc : sync_rc;
+}
+
+int purine_graph_set_replay(purine_graph* g, int on) {
+    if (!g) return PURINE_E_NULL;
+    g->replay = on != 0;
+    if (!g->replay) drop_captured(g);
+    return PURINE_OK;
 }
 
 int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b) {
@@ -601,9 +703,10 @@ int purine_graph_iterate(purine_graph* g, int n_iters, const int* swap_a, const 
     // all the others), not by the host, which runs ahead issuing the next iteration; the kernels of
     // an iteration were issued with the addresses bound at that moment, so the swap is safe.
     int rc = PURINE_OK;
+    const bool replay = replay_applies(g);   // recorded passes follow each other on one stream: no join needed
     for (int it = 0; it < n_iters && rc == PURINE_OK; ++it) {
-        if (it > 0) rc = join_streams(g);
-        if (rc == PURINE_OK) rc = run_issue(g);
+        if (it > 0 && !replay) rc = join_streams(g);
+        if (rc == PURINE_OK) rc = replay ? replay_pass(g) : run_issue(g);
         for (int s = 0; s < n_swaps && rc == PURINE_OK; ++s) rc = purine_graph_swap_storage(g, swap_a[s], swap_b[s]);
     }
     const int sync_rc = wait_streams(g);
