@@ -245,3 +245,43 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=60)
     assert r.returncode != 0
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/purine.h must be usable from C: it compiles as C99 with warnings as errors, and a C
+    program that calls host-only entry points links against the library and runs."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    src = tmp_path / "use_purine.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include "purine.h"
+int main(void) {
+    purine_conv_desc d = {4, 4, 0, 0};
+    int64_t x[4] = {64, 3, 224, 224}, w[4] = {96, 3, 11, 11}, y[4];
+    if (purine_conv_out_shape(&d, x, w, y) != PURINE_OK) return 1;
+    if (y[0] != 64 || y[1] != 96 || y[2] != 54 || y[3] != 54) return 2;
+    purine_graph* g = purine_graph_create();
+    if (!g) return 3;
+    purine_tensor t = {0};
+    t.dtype = PURINE_F32; t.ndim = 1; t.dim[0] = 4;
+    int a = purine_graph_add_tensor(g, &t, "a"), b = purine_graph_add_tensor(g, &t, "b");
+    int op = purine_graph_add_op(g, PURINE_OP_HOST_NOP, NULL, &a, 1, &b, 1, 0);
+    if (a != 0 || b != 1 || op != 0) return 4;
+    if (purine_graph_run(g) != PURINE_OK) return 5;
+    int order[1];
+    if (purine_graph_fire_log(g, order, 1) != 1 || order[0] != 0) return 6;
+    purine_graph_destroy(g);
+    printf("%s\n", purine_status_string(PURINE_E_SHAPE));
+    return 0;
+}
+''')
+    exe = tmp_path / "use_purine"
+    lib_dir = os.path.dirname(binding.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, str(src), "-o", str(exe),
+                    "-L", lib_dir, "-l:libpurine_conv.so", "-Wl,-rpath," + lib_dir], check=True, capture_output=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, (r.returncode, r.stderr)
+    assert "shape" in r.stdout
