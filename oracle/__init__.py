@@ -35,8 +35,12 @@ class _Shape(ctypes.Structure):
 def _load():
     global _lib
     if _lib is None:
-        build()
-        _lib = ctypes.CDLL(_LIB)
+        # ORACLE_LIB_OVERRIDE: a library built elsewhere from a (deliberately altered) copy of the
+        # source; used only by the test that checks that the pins notice planted mistakes
+        override = os.environ.get("ORACLE_LIB_OVERRIDE")
+        if not override:
+            build()
+        _lib = ctypes.CDLL(override or _LIB)
         _lib.oracle_out_extent.restype = ctypes.c_int64
         _lib.oracle_out_extent.argtypes = [ctypes.c_int64] * 4
         _lib.oracle_num_threads.restype = ctypes.c_int
