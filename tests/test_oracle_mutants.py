@@ -29,6 +29,9 @@ MUTANTS = [
     ("bias_bwd_drops_last_pixel", "for (int64_t i = 0; i < PQ; ++i) acc += (double)row[i];",
      "for (int64_t i = 0; i + 1 < PQ || i == 0; ++i) acc += (double)row[i];", 0),
     ("extent_off_by_one", "return (in + 2 * pad - k) / stride + 1;", "return (in + 2 * pad - k + stride - 1) / stride + 1;", 0),
+    ("pool_last_maximum_wins_ties", "if (best < 0 || v > bv) { best = (int32_t)(h * W + w_); bv = v; }",
+     "if (best < 0 || v >= bv) { best = (int32_t)(h * W + w_); bv = v; }", 0),
+    ("pool_gradient_overwrites", "if (a >= 0) plane[a] += (double)dy[nc * PQ + i];", "if (a >= 0) plane[a] = (double)dy[nc * PQ + i];", 0),
     ("relu_passes_zero_gradient", "dx[i] = x[i] > 0.0f ? dy[i] : 0.0f;", "dx[i] = x[i] >= 0.0f ? dy[i] : 0.0f;", 0),
 ]
 
