@@ -258,6 +258,19 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             const int row0 = i_base + a * 16 + kq * 4;
             float t[4], o[4];
             bool ok;
+            if (D2S && sizeof(T) == 4 && !FUSED) {
+                // stride-4 columns: the lane's four rows are four consecutive positions of one output
+                // row (b = 0..3), written as one 16-byte packet (4-byte aligned) when all of them exist
+                bool ok0, ok3;
+                const int off0 = addr.at(row0, ok0);
+                (void)addr.at(row0 + 3, ok3);
+                if (p.sw == 4 && !has_beta && ok0 && ok3) {
+                    typedef float floatx4_u __attribute__((ext_vector_type(4), aligned(4)));
+                    floatx4_u v = {acc[a][b][0], acc[a][b][1], acc[a][b][2], acc[a][b][3]};
+                    *reinterpret_cast<floatx4_u*>(reinterpret_cast<float*>(out) + off0) = v;
+                    continue;
+                }
+            }
             if (has_bias) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) t[e] = bias_lds[row0 + e - i_tile0];
