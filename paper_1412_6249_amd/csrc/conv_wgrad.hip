@@ -49,10 +49,17 @@ template <> __device__ __forceinline__ float ld<uint16_t>(const uint16_t* p, int
 struct TileWhere {
     int split, i0, j0, tap_r, tap_s, tap;
 };
+// Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). The tiles of
+// one split read the same chunk of x and dy, so each XCD gets a contiguous run of (split, tile) ids:
+// a chunk is then fetched into one L2 instead of all eight.
+__device__ __forceinline__ int xcd_run(int bid, int total) {
+    const int per = total >> 3;
+    return (per > 0 && bid < per * 8) ? (bid & 7) * per + (bid >> 3) : bid;
+}
 template <bool TAP, int BM, int BN>
 __device__ __forceinline__ TileWhere locate_tile(const WgradParams& p) {
     TileWhere t;
-    int bid = blockIdx.x;
+    int bid = xcd_run(blockIdx.x, gridDim.x);
     const int per_split = p.tiles_i * p.tiles_j;
     t.split = bid / per_split;
     bid -= t.split * per_split;
