@@ -592,9 +592,9 @@ hipError_t dispatch_bf16_mode(WgradParams& p, const WgradPlan& plan, hipStream_t
 }
 template <bool VEC_A, bool TAP>
 hipError_t dispatch_bf16(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
-    // measured: the per-tap mode with several taps (3x3 64->192 at 56x56) runs 15 % slower with
-    // 2-byte buffer loads than with plain loads; single-tap and flattened layers run 6-10 % faster
-    const bool buf = p.x_bytes != 0 && p.dy_bytes != 0 && !(TAP && p.RS > 1);
+    // measured: 2-byte buffer loads are 6-10 % faster than plain loads in every mode (the per-tap
+    // mode with several taps only since a split's tiles share one XCD's L2)
+    const bool buf = p.x_bytes != 0 && p.dy_bytes != 0;
     const bool nopad = !TAP && p.ph == 0 && p.pw == 0 && (p.P - 1) * p.sh + p.R <= p.H && (p.Q - 1) * p.sw + p.S <= p.W;
     if (!buf) return dispatch_bf16_mode<VEC_A, TAP, false, false>(p, plan, st);
     if (TAP) return dispatch_bf16_mode<VEC_A, TAP, false, true>(p, plan, st);
