@@ -473,7 +473,7 @@ __global__ __launch_bounds__(256) void repack_filter_kernel(const RepackParams q
 // bf16 MFMA kernels (measured on the 3x3 64->192 layer at 56x56, batch 256): they are bound by the
 // per-slab instruction overhead, not by the MFMA pipe, so 64-row tiles with many pixels win.
 constexpr TileCfg kTilesBf16[] = {
-    {64, 256, 1.00f}, {64, 128, 0.97f}, {64, 64, 0.83f}, {96, 256, 0.81f}, {32, 256, 0.77f},
+    {64, 256, 1.00f}, {64, 128, 0.955f}, {64, 64, 0.83f}, {96, 256, 0.81f}, {32, 256, 0.77f},
     {32, 128, 0.77f}, {128, 128, 0.64f}, {96, 128, 0.58f}, {128, 64, 0.30f},
 };
 constexpr float kEff16 = 0.96f;   // 16x16x4 tiles, 256 pixels per workgroup (measured like the table below)
@@ -588,7 +588,8 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     (void)fused;
     const double gather = pl.flat ? 15.0 : 3.0;
     double best = -1.0;
-    const bool flat_bf16 = pl.flat && dtype == PURINE_BF16;
+    // the bf16 modes that gather single 2-byte elements (flattened, and single-tap straight from NCHW)
+    const bool flat_bf16 = dtype == PURINE_BF16 && (pl.flat || pl.Rt * pl.St == 1);
     const TileCfg* table = dtype == PURINE_BF16 ? kTilesBf16 : kTiles;
     const int n_table = dtype == PURINE_BF16 ? (int)(sizeof(kTilesBf16) / sizeof(TileCfg)) : (int)(sizeof(kTiles) / sizeof(TileCfg));
     for (int ti_ = 0; ti_ < n_table; ++ti_) {
@@ -597,7 +598,7 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
         const long long ti = (Co + t.bm - 1) / t.bm, tp = (M + t.bn - 1) / t.bn;
         const long long per_cu = (ti * tp + 255) / 256;
         const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.95 : 0.6);
-        // the bf16 flattened kernel gathers 32 elements per thread and slab at 256 pixels per
+        // the bf16 element-gather modes fetch 32 elements per thread and slab at 256 pixels per
         // workgroup, which measured a third slower than 16 at 128
         const double eff = (flat_bf16 && t.bn == 256) ? t.eff * 0.65 : t.eff;
         const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (eff * hide);
