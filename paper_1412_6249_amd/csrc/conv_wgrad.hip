@@ -327,12 +327,7 @@ constexpr int LDP = BKP + 8;
 // BUF / NOPAD as in the fp32 kernel: the gathered x elements (and dy, when it is read element by
 // element) come through raw buffer loads with two-part byte offsets, zeros from the range check.
 template <bool VEC_A, bool TAP, bool NOPAD, bool BUF, int TM, int TN, int WM, int WN>
-// The per-tap kernels with three MFMA tiles per wavefront are pinned to three wavefronts
-// per SIMD: left alone the compiler squeezes them under 128 registers for a fourth, which costs
-// 20 % on the 3x3 64->192 layer (0.71 against 0.59 ms) because fewer loads stay in flight.
-__global__ __launch_bounds__(WM * WN * 64)
-__attribute__((amdgpu_waves_per_eu(TAP && TM * TN == 3 ? 3 : 1, TAP && TM * TN == 3 ? 3 : 8)))
-void wgrad_bf16_kernel(const WgradParams p) {
+__global__ __launch_bounds__(WM * WN * 64) void wgrad_bf16_kernel(const WgradParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
     constexpr int BN = WN * TN * 32;
