@@ -29,6 +29,11 @@ MEASURED_TRAFFIC_BYTES = {
     # plain 256 MiB copy gives these counters), from the rocprofv3 --pmc runs summarised in profiles/
     (2, "conv_bwd_data[conv1.dx]"): 85.46e6 + 38.54e6,
     (2, "conv_fwd_bias_relu[conv1.a]"): 42.17e6 + 72.11e6,
+    (3, "conv_bwd_data_relu[b2_3x3.dx]"): 102.83e6 + 38.62e6,
+    # the instantiation serves two layers per step; conv2's launches are the ones with 729 workgroups
+    (4, "conv_bwd_data[conv2.dx]"): 132.57e6 + 36.22e6,
+    # main kernel + the blocked copy of dy it reads (the operator's bracket covers both kernels)
+    (5, "conv_bwd_data[stem7x7.dx]"): 420.08e6 + 82.05e6 + 2 * 411.04e6,
 }
 
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
