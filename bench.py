@@ -7,8 +7,8 @@ C-ABI executor with inputs already resident in HBM. value = conv FLOPs of the st
 convention, 3 passes x 2*N*K*C*R*S*P*Q per layer) / wall time, in TFLOP/s.
 
 Prints ONE JSON line. `roofline` describes the single kernel that takes the most time in the
-step (its FLOPs / its average duration measured with HIP events on its own stream inside the timed
-region); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same layers.
+step (its FLOPs, or below the ridge of its dtype its algorithmic bytes, / its average duration
+measured with HIP events on its own stream inside the timed region); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same layers.
 """
 import argparse
 import json
@@ -213,12 +213,30 @@ def main():
     _, _, kind, out_name, L = next(r for r in rows if r[1] == dominant)
     avg_ms = dom_ms / dom_n - bracket_ms
     kname = "%s[%s]" % (KIND_NAMES[kind], out_name)
-    achieved = L.flop_per_pass / (avg_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": kname, "achieved": round(achieved, 3),
-                "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_TFLOPS[dtype], 4),
+    # Which roof bounds this pass: its algorithmic bytes are the three tensors it touches, each once
+    # (the ReLU mask of the fused backward-data counts as a fourth); below the ridge
+    # peak flop/s / peak bytes/s the pass is priced against HBM, else against the MFMA peak.
+    elem = 2 if dtype == "bf16" else 4
+    sizes = {"x": elem, "w": elem, "y": elem}
+    for nm, shp in (("x", L.x_shape), ("w", L.w_shape), ("y", L.y_shape)):
+        for s in shp:
+            sizes[nm] *= s
+    if kind == 15:
+        sizes["w"] = sizes["w"] // elem * 4          # the weight gradient is fp32
+    algo_bytes = sizes["x"] + sizes["w"] + sizes["y"] + (sizes["x"] if kind == 14 else 0)
+    ridge = PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if L.flop_per_pass / algo_bytes >= ridge:
+        achieved = L.flop_per_pass / (avg_ms * 1e-3) / 1e12
+        bound, peak, unit = "mfma", PEAK_TFLOPS[dtype], "TFLOP/s"
+    else:
+        achieved = algo_bytes / (avg_ms * 1e-3) / 1e9
+        bound, peak, unit = "hbm", HBM_PEAK_GBS, "GB/s"
+    roofline = {"bound": bound, "kernel": kname, "achieved": round(achieved, 3),
+                "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4),
                 "avg_kernel_ms": round(avg_ms, 4),
                 "bracket_overhead_ms": round(bracket_ms, 4),
+                "algorithmic_bytes": algo_bytes,
                 "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, kname))}
 
     # secondary figure: the same step without the first layer's backward-data (the gradient with
