@@ -6,9 +6,13 @@ ConvBwdData, ConvBwdWeight and BiasBwd operator, plus the ReLU/pool/concat glue)
 C-ABI executor with inputs already resident in HBM. value = conv FLOPs of the step (dense
 convention, 3 passes x 2*N*K*C*R*S*P*Q per layer) / wall time, in TFLOP/s.
 
-Prints ONE JSON line. `roofline` describes the single kernel that takes the most time in the
-step (its FLOPs, or below the ridge of its dtype its algorithmic bytes, / its average duration
-measured with HIP events on its own stream inside the timed region); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same layers.
+The default run times the AlexNet-shaped five-layer stack at batch 128 (the largest fp32 workload,
+driven end to end by the bi-graph executor) and prints ONE JSON line for it. `roofline` describes
+the single kernel that takes the most time in the step (its FLOPs, or below the ridge of its dtype
+its algorithmic bytes, / its average duration measured with HIP events on its own stream inside
+the timed region); `cpu_baseline` is the CPU oracle timed on a bounded sample of the same layers;
+`per_config` repeats the measurement (same steps, same warm-up, each with its own dominant-kernel
+roofline) for the NIN block, the inception module and the bf16 GoogLeNet stem.
 """
 import argparse
 import json
@@ -22,19 +26,28 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}     # MI355X dense MFMA peaks
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, from `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE`
-# runs of this same command (see profiles/); None until measured for that kernel.
-MEASURED_TRAFFIC_BYTES = {
-    # (config, kernel): HBM bytes per launch = FETCH_SIZE * 2047.77 + WRITE_SIZE * 1024 (the factors a
-    # plain 256 MiB copy gives these counters), from the rocprofv3 --pmc runs summarised in profiles/
-    (2, "conv_bwd_data[conv1.dx]"): 85.46e6 + 38.54e6,
-    (2, "conv_fwd_bias_relu[conv1.a]"): 42.17e6 + 72.11e6,
-    (3, "conv_bwd_data_relu[b2_3x3.dx]"): 102.83e6 + 38.62e6,
-    # the instantiation serves two layers per step; conv2's launches are the ones with 729 workgroups
-    (4, "conv_bwd_data[conv2.dx]"): 132.57e6 + 36.22e6,
-    # main kernel + the blocked copy of dy it reads (the operator's bracket covers both kernels)
-    (5, "conv_bwd_data[stem7x7.dx]"): 420.08e6 + 82.05e6 + 2 * 411.04e6,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_dominant_kernels.md")
+
+
+def measured_traffic():
+    """(config, operator) -> HBM bytes per launch, read from the counter summary kept under
+    profiles/ (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command, scaled by what the
+    counters read for a plain copy of known size). Rows: | cfgN | operator | kernel | fetch_MB | write_MB |.
+    An operator that is not in the table (a kernel changed, another one came out dominant) gets null."""
+    out = {}
+    try:
+        with open(TRAFFIC_TABLE) as f:
+            for line in f:
+                cells = [c.strip() for c in line.strip().strip("|").split("|")]
+                if len(cells) >= 5 and cells[0].startswith("cfg") and cells[0][3:].isdigit():
+                    try:
+                        out[(int(cells[0][3:]), cells[1])] = (float(cells[3]) + float(cells[4])) * 1e6
+                    except ValueError:
+                        pass
+    except OSError:
+        pass
+    return out
+
 
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
               5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
@@ -100,38 +113,14 @@ def bracket_overhead_ms(reps=30):
     return max(ms[len(ms) // 2] - 0.002, 0.0)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: NIN mlpconv block)")
-    ap.add_argument("--single-stream", action="store_true", help="all operators on one thread id")
-    ap.add_argument("--unfused", action="store_true",
-                    help="separate Bias / ReLU / ReLU-gradient operators instead of the fused conv vertices")
-    ap.add_argument("--no-merge-1x1", action="store_true",
-                    help="config 3: keep the three 1x1 convolutions on the module input as separate operators "
-                         "and the Concat copies (default: one merged operator, concatenation by address "
-                         "through channel-slice views)")
-    ap.add_argument("--replay", action="store_true",
-                    help="executor replay mode: the unbracketed steps launch a recorded HIP graph of the pass")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sample-every", type=int, default=4,
-                    help="bracket the dominant kernel (which then runs alone) on every n-th timed step")
-    ap.add_argument("--ops", action="store_true", help="print the per-operator table to stderr")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.stderr.write("bench.py: this build runs on exactly one GPU (the path has no collectives); "
-                         "--gpus %d is not supported\n" % args.gpus)
-        sys.exit(2)
-
+def run_config(cfg, args, secondary_figures):
+    """Times one workload: warm-up, one serial step per operator (per-operator table, dominant
+    kernel), then exactly args.steps timed steps between two device synchronisations."""
     import torch
     import paper_1412_6249_amd as pa
     from paper_1412_6249_amd.layers import build_workload
     from synth.configs import CONV_LAYERS, WORKLOAD_NAMES, total_flop
 
-    cfg = args.config
-    torch.cuda.set_device(0)
     merge = cfg == 3 and not args.no_merge_1x1 and not args.unfused
     gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, merge_1x1=merge)
     # Warm-up and one step per operator with that operator's main kernel bracketed (twice, keeping
@@ -205,6 +194,7 @@ def main():
         rows.append((avg, oid, kind, outs[0], L))
     rows.sort(reverse=True)
     if args.ops:
+        sys.stderr.write("---- %s\n" % WORKLOAD_NAMES[cfg])
         for avg, oid, kind, out, L in rows:
             extra = "  %.1f TFLOP/s" % (L.flop_per_pass / avg / 1e9) if L is not None and avg > 0 else ""
             sys.stderr.write("%9.3f ms  %-16s %s%s\n" % (avg, KIND_NAMES[kind], out, extra))
@@ -221,7 +211,7 @@ def main():
     for nm, shp in (("x", L.x_shape), ("w", L.w_shape), ("y", L.y_shape)):
         for s in shp:
             sizes[nm] *= s
-    if kind == 15:
+    if kind in (3, 15):
         sizes["w"] = sizes["w"] // elem * 4          # the weight gradient is fp32
     algo_bytes = sizes["x"] + sizes["w"] + sizes["y"] + (sizes["x"] if kind == 14 else 0)
     ridge = PEAK_TFLOPS[dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
@@ -237,68 +227,119 @@ def main():
                 "avg_kernel_ms": round(avg_ms, 4),
                 "bracket_overhead_ms": round(bracket_ms, 4),
                 "algorithmic_bytes": algo_bytes,
-                "traffic": MEASURED_TRAFFIC_BYTES.get((cfg, kname))}
+                "traffic": measured_traffic().get((cfg, kname))}
 
-    # secondary figure: the same step without the first layer's backward-data (the gradient with
-    # respect to the images, which training does not need); its flops leave the numerator too
     secondary = None
-    if cfg in (2, 4):
+    if secondary_figures:
+        # secondary figure: the same step without the first layer's backward-data (the gradient with
+        # respect to the images, which training does not need); its flops leave the numerator too
+        if cfg in (2, 4):
+            gb.close()
+            gb2 = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, first_layer_dx=False)
+            if args.replay:
+                pa.purine_graph_set_replay(gb2.g, True)
+            for _ in range(max(1, args.warmup)):
+                gb2.run()
+            torch.cuda.synchronize()
+            s0 = time.perf_counter()
+            n2 = max(5, args.steps // 2)
+            gb2.iterate(n2)
+            torch.cuda.synchronize()
+            ms2 = (time.perf_counter() - s0) * 1e3 / n2
+            flop2 = flop - CONV_LAYERS[cfg][0].flop_per_pass
+            secondary = {"without_first_layer_dx": {"ms_per_step": round(ms2, 4),
+                                                    "value": round(flop2 / (ms2 * 1e-3) / 1e12, 3)}}
+            gb = gb2
+        # third figure: whole training iterations (paper section 2.2): the step above plus one SGD update
+        # operator per parameter tensor and the swap of old and new parameters, iterated natively
         gb.close()
-        gb2 = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, first_layer_dx=False)
+        gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused,
+                            first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6, merge_1x1=merge)
         if args.replay:
-            pa.purine_graph_set_replay(gb2.g, True)
-        for _ in range(max(1, args.warmup)):
-            gb2.run()
+            pa.purine_graph_set_replay(gb.g, True)
+        gb.iterate(max(2, args.warmup))
         torch.cuda.synchronize()
         s0 = time.perf_counter()
-        n2 = max(5, args.steps // 2)
-        gb2.iterate(n2)
+        n3 = max(6, args.steps // 2) // 2 * 2
+        gb.iterate(n3)
         torch.cuda.synchronize()
-        ms2 = (time.perf_counter() - s0) * 1e3 / n2
-        flop2 = flop - CONV_LAYERS[cfg][0].flop_per_pass
-        secondary = {"without_first_layer_dx": {"ms_per_step": round(ms2, 4),
-                                                "value": round(flop2 / (ms2 * 1e-3) / 1e12, 3)}}
-        gb = gb2
-
-    # third figure: whole training iterations (paper section 2.2): the step above plus one SGD update
-    # operator per parameter tensor and the swap of old and new parameters, iterated natively
+        ms3 = (time.perf_counter() - s0) * 1e3 / n3
+        flop3 = flop - (CONV_LAYERS[cfg][0].flop_per_pass if cfg in (2, 4) else 0)
+        secondary = dict(secondary or {})
+        secondary["sgd_iterations"] = {"ms_per_iteration": round(ms3, 4), "value": round(flop3 / (ms3 * 1e-3) / 1e12, 3),
+                                       "first_layer_dx": cfg not in (2, 4)}
     gb.close()
-    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused,
-                        first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6, merge_1x1=merge)
-    if args.replay:
-        pa.purine_graph_set_replay(gb.g, True)
-    gb.iterate(max(2, args.warmup))
-    torch.cuda.synchronize()
-    s0 = time.perf_counter()
-    n3 = max(6, args.steps // 2) // 2 * 2
-    gb.iterate(n3)
-    torch.cuda.synchronize()
-    ms3 = (time.perf_counter() - s0) * 1e3 / n3
-    flop3 = flop - (CONV_LAYERS[cfg][0].flop_per_pass if cfg in (2, 4) else 0)
-    secondary = dict(secondary or {})
-    secondary["sgd_iterations"] = {"ms_per_iteration": round(ms3, 4), "value": round(flop3 / (ms3 * 1e-3) / 1e12, 3),
-                                   "first_layer_dx": cfg not in (2, 4)}
+    del gb
+    torch.cuda.empty_cache()
+    value = flop / (ms_per_step * 1e-3) / 1e12
+    return {"workload": WORKLOAD_NAMES[cfg], "ms_per_step": round(ms_per_step, 4), "value": round(value, 3),
+            "dtype": dtype, "conv_gflop_per_step": round(flop / 1e9, 2),
+            "frac_of_mfma_peak": round(value / PEAK_TFLOPS[dtype], 4),
+            "roofline": roofline, "secondary": secondary, "merge": merge}
 
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4,
+                    help="workload 1..5 of the headline line (default 4: AlexNet-shaped conv stack, batch 128)")
+    ap.add_argument("--no-per-config", action="store_true",
+                    help="leave out the per_config block (workloads 2, 3 and 5 measured the same way)")
+    ap.add_argument("--single-stream", action="store_true", help="all operators on one thread id")
+    ap.add_argument("--unfused", action="store_true",
+                    help="separate Bias / ReLU / ReLU-gradient operators instead of the fused conv vertices")
+    ap.add_argument("--no-merge-1x1", action="store_true",
+                    help="config 3: keep the three 1x1 convolutions on the module input as separate operators "
+                         "and the Concat copies (default: one merged operator, concatenation by address "
+                         "through channel-slice views)")
+    ap.add_argument("--replay", action="store_true",
+                    help="executor replay mode: the unbracketed steps launch a recorded HIP graph of the pass")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sample-every", type=int, default=4,
+                    help="bracket the dominant kernel (which then runs alone) on every n-th timed step")
+    ap.add_argument("--ops", action="store_true", help="print the per-operator tables to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on exactly one GPU (the path has no collectives); "
+                         "--gpus %d is not supported\n" % args.gpus)
+        sys.exit(2)
+
+    import torch
+    torch.cuda.set_device(0)
+    cfg = args.config
+    main_res = run_config(cfg, args, secondary_figures=True)
     result = {
         "metric": "conv fwd+bwd TFLOP/s on one MI355X",
-        "value": round(flop / (ms_per_step * 1e-3) / 1e12, 3),
+        "value": main_res["value"],
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": dtype, "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[cfg], "conv_gflop_per_step": round(flop / 1e9, 2),
+        "dtype": main_res["dtype"], "data": "synthetic",
+        "config": {"workload": main_res["workload"], "conv_gflop_per_step": main_res["conv_gflop_per_step"],
                    "executor": "bi-graph, %s%s, %s" % ("1 stream" if args.single_stream else "3+ streams",
                                                         ", recorded pass replayed" if args.replay else "",
                                                       "separate bias/relu ops" if args.unfused
                                                       else "bias+relu fused into conv vertices"
-                                                      + (", merged 1x1 + concat by address" if merge else "")),
-                   "frac_of_mfma_peak": round(flop / (ms_per_step * 1e-3) / 1e12 / PEAK_TFLOPS[dtype], 4)},
-        "roofline": roofline,
+                                                      + (", merged 1x1 + concat by address" if main_res["merge"] else "")),
+                   "frac_of_mfma_peak": main_res["frac_of_mfma_peak"]},
+        "roofline": main_res["roofline"],
     }
-    if secondary:
-        result["secondary"] = secondary
-    gb.close()
+    if main_res["secondary"]:
+        result["secondary"] = main_res["secondary"]
+    if not args.no_per_config:
+        # the other large workloads, measured the same way (same steps and warm-up): the NIN block and
+        # the inception module in fp32, the GoogLeNet stem in bf16
+        per = {}
+        for c in (2, 3, 4, 5):
+            if c == cfg:
+                continue
+            r = run_config(c, args, secondary_figures=False)
+            per[r["workload"]] = {k: r[k] for k in ("ms_per_step", "value", "dtype", "conv_gflop_per_step",
+                                                    "frac_of_mfma_peak", "roofline")}
+        result["per_config"] = per
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(result))

@@ -183,7 +183,7 @@ int purine_concat_bwd(const purine_tensor* dout, purine_tensor* const* dparts, i
 int purine_sum(const purine_tensor* const* terms, int n_terms, purine_tensor* out,
                void* hip_stream);
 
-/* SGD step on one parameter tensor (paper section 2.2, Figure 3(a): the network graph leaves the
+/* SGD step on one parameter tensor (paper section 2.2, Figure 2(a): the network graph leaves the
  * updated parameters in a separate "new params" tensor so that the graph stays acyclic):
  * new_w = w - lr * dw, element by element, one fused multiply-add in fp32 (bf16 parameters are
  * widened, updated, and rounded to nearest even). w and new_w: same dtype (F32 or BF16) and
@@ -316,7 +316,7 @@ int purine_graph_validate(purine_graph* g);
  * PURINE_E_GRAPH instead of hanging. The first operator error aborts the run and is returned. */
 int purine_graph_run(purine_graph* g);
 
-/* The swap step of graph iteration (section 2.2, Figure 3(b)): exchanges the storage addresses of
+/* The swap step of graph iteration (section 2.2, Figure 2(b)): exchanges the storage addresses of
  * two tensor vertices with the same dtype and extents ("old" and "new" parameters), so that the
  * next run of the graph reads what the last run wrote. Every vertex bound to either address moves
  * with it. PURINE_E_SHAPE when the two differ in dtype or extents; PURINE_E_LAYOUT when the two
@@ -327,7 +327,7 @@ int purine_graph_swap_storage(purine_graph* g, int tensor_a, int tensor_b);
 /* Storage address a tensor vertex is bound to at the moment (NULL for a bad id). */
 void* purine_graph_tensor_data(const purine_graph* g, int tensor_id);
 
-/* Graph iteration (section 2.2, Figure 3(c)): n_iters times { one run of the graph; then
+/* Graph iteration (section 2.2, Figure 2(c)): n_iters times { one run of the graph; then
  * purine_graph_swap_storage(swap_a[i], swap_b[i]) for i < n_swaps }. The end of each run is the
  * synchronisation point between iterations, and the device keeps it: no operator of an iteration
  * starts before every operator of the one before has finished (each stream waits for all the

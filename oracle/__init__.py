@@ -197,7 +197,7 @@ def fan_in_sum(tensors):
 
 
 def sgd_update(w, dw, lr):
-    """One SGD step on a parameter tensor (paper section 2.2, Figure 3(a): every iteration computes
+    """One SGD step on a parameter tensor (paper section 2.2, Figure 2(a): every iteration computes
     a modification of the parameters and applies it before the next one). The paper fixes no
     formula beyond that; the reading taken is the plain rule new = w - lr * dw, in fp64."""
     return np.asarray(w, dtype=np.float64) - float(lr) * np.asarray(dw, dtype=np.float64)

@@ -156,14 +156,16 @@ __device__ __forceinline__ void store_rows(const PixParams& p, floatx16 (&acc)[T
 #pragma unroll
             for (int e = 0; e < G; ++e) {
                 const int d = ((e0 + e) >> 2) * 8 + ((e0 + e) & 3);
-                mk[e] = *reinterpret_cast<const raw_t*>(mrow + (row0 + d < p.Co ? d * p.HoWo : 0));
+                // a row past the last channel reads channel 0 of the same image instead (row0 itself may
+                // already lie past Co, so "offset 0 from mrow" would not be inside the tensor)
+                mk[e] = *reinterpret_cast<const raw_t*>(mrow + (row0 + d < p.Co ? d : -row0) * p.HoWo);
             }
         }
         if (!FUSED && has_beta) {
 #pragma unroll
             for (int e = 0; e < G; ++e) {
                 const int d = ((e0 + e) >> 2) * 8 + ((e0 + e) & 3);
-                old[e] = *reinterpret_cast<const raw_t*>(orow + (row0 + d < p.Co ? d * p.HoWo : 0));
+                old[e] = *reinterpret_cast<const raw_t*>(orow + (row0 + d < p.Co ? d : -row0) * p.HoWo);
             }
         }
         floatx4 bq = {0.0f, 0.0f, 0.0f, 0.0f};   // bias of four consecutive rows: one 16-byte LDS read per quad

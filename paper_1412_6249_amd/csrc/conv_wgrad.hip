@@ -647,8 +647,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float* __restri
 // The same reduction for n a multiple of 4 (rows of the partials 16-byte aligned): a workgroup owns
 // 32 consecutive elements (one 128-byte line per split, so no line is fetched by two workgroups on
 // different L2s), 8 lanes x 16 bytes wide, and 32 split lanes deep; the 32 lane sums are added in
-// lane order. Also a fixed order; `vec4` is a property of the layer, so a layer always takes the
-// same one of the two kernels.
+// lane order. Also a fixed order; which of the two kernels adds dw's partials depends on K*C*R*S
+// alone, so ConvBwdWeight and the fused ConvBwdWeight+BiasBwd give the same bits for dw.
 __global__ __launch_bounds__(256) void wgrad_reduce_vec_kernel(const float* __restrict__ partial,
                                                                float* __restrict__ dw, int n,
                                                                int splits, float beta, int tap_major,
@@ -661,6 +661,26 @@ __global__ __launch_bounds__(256) void wgrad_reduce_vec_kernel(const float* __re
     if (blk >= dw_blocks) {   // uniform over the workgroup: the fused bias gradient's partials
         blk -= dw_blocks;
         partial = db_partial; dw = db; n = K; tap_major = 0;
+    }
+    if (n & 3) {
+        // bias-gradient partials of a layer whose K is not a multiple of 4 (rows not 16-byte aligned):
+        // element by element, 32 elements x 8 split lanes; the rows of `red` the lanes do not fill
+        // hold zeros, so the final sum below serves both forms
+        const int e = threadIdx.x & 31, sl8 = threadIdx.x >> 5;
+        const int j = blk * 32 + e;
+        float a = 0.0f;
+        if (j < n)
+            for (int s = sl8; s < splits; s += 8) a += partial[(size_t)s * n + j];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[sl8 + 8 * r][e] = r == 0 ? a : 0.0f;
+        __syncthreads();
+        if (sl8 == 0 && j < n) {
+            float t = beta != 0.0f ? dw[j] : 0.0f;
+#pragma unroll
+            for (int l = 0; l < 32; ++l) t += red[l][e];
+            dw[j] = t;
+        }
+        return;
     }
     const int i = blk * 32 + e4 * 4;
     float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
@@ -827,7 +847,7 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     if (e != hipSuccess) return e;
     const int n = g.K * p.CRS;
     // 16-byte packets need aligned rows in both sets of partials (the scratch itself is aligned)
-    const bool vec4 = n % 4 == 0 && (!db || g.K % 4 == 0);
+    const bool vec4 = n % 4 == 0;   // (the bias-gradient partials take an element-wise path when K % 4 != 0)
     if (vec4) {
         const int dw_blocks = (n + 31) / 32, db_blocks = db ? (g.K + 31) / 32 : 0;
         hipLaunchKernelGGL(wgrad_reduce_vec_kernel, dim3(dw_blocks + db_blocks), dim3(256), 0, st,

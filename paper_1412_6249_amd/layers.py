@@ -162,7 +162,7 @@ class GraphBuilder:
         return dx
 
     def add_sgd(self, lr):
-        """SGD by graph iteration (paper section 2.2, Figure 3): for every parameter tensor one
+        """SGD by graph iteration (paper section 2.2, Figure 2): for every parameter tensor one
         operator leaves w - lr*dw in a separate "new" tensor (writing w itself would close a cycle);
         `swaps` lists the (old, new) vertex pairs whose storage addresses the swap step exchanges
         between two runs of the graph."""

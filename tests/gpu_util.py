@@ -1,5 +1,6 @@
 """Helpers for the GPU parity tests: upload seeded host tensors, call the operators through the
-C-ABI binding, bring results back as numpy. No arithmetic of the method lives here."""
+C-ABI binding, bring results back as numpy. The only arithmetic here is `pool_bwd_in_order`, the
+fp32 restatement of the pooling gradient's summation order that lets it be compared bit for bit."""
 import numpy as np
 import torch
 
@@ -34,6 +35,26 @@ def to_host(t):
     if t.dtype == torch.bfloat16:
         return t.float().cpu().numpy()
     return t.cpu().numpy()
+
+
+def pool_bwd_in_order(dy, arg, x_shape, dtype="f32", prev=None):
+    """Pooling gradient summed the way the operator is specified to sum it: per input position an
+    fp32 accumulator that starts from the previous gradient (accumulating call) or zero and takes
+    the windows that chose the position in ascending (p, q) order; a bf16 result is that fp32 sum
+    rounded to nearest even once. The fp64 oracle fixes WHERE each gradient lands and the value up
+    to rounding; this fixes the rounding, so the GPU result can be compared exactly."""
+    N, C, H, W = (int(v) for v in x_shape)
+    P, Q = dy.shape[2:]
+    dx = np.zeros((N * C, H * W), np.float32) if prev is None else np.array(prev, np.float32).reshape(N * C, H * W)
+    g = np.ascontiguousarray(dy, np.float32).reshape(N * C, P, Q)
+    a = np.asarray(arg).reshape(N * C, P, Q)
+    planes = np.arange(N * C)
+    for p in range(P):
+        for q in range(Q):
+            ok = a[:, p, q] >= 0
+            dx[planes[ok], a[ok, p, q]] += g[ok, p, q]      # one target per plane: no repeated index
+    dx = dx.reshape(N, C, H, W)
+    return gen.quantize_bf16(dx) if dtype == "bf16" else dx
 
 
 def tdtype(dtype):

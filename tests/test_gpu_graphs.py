@@ -49,14 +49,18 @@ def check_conv_record(gb, rec, tol):
 
 
 def check_pool_record(gb, rec):
-    from gpu_util import rel_l2
+    from gpu_util import rel_l2, pool_bwd_in_order
     x = host(gb, rec["x"])
     d = rec["desc"]
     ey, earg = oracle.maxpool_fwd(x, d.window, d.stride, d.pad)
     assert np.array_equal(host(gb, rec["y"]), ey)
     assert np.array_equal(gb.t[rec["arg"]].cpu().numpy(), earg)
-    edx = oracle.maxpool_bwd(host(gb, rec["dy"]), earg, x.shape)
-    assert rel_l2(host(gb, rec["dx"]), edx) <= 1e-6
+    dy = host(gb, rec["dy"])
+    dx = host(gb, rec["dx"])
+    edx = oracle.maxpool_bwd(dy, earg, x.shape)
+    assert rel_l2(dx, edx) <= 1e-6
+    # exact operator: the fp32 sum over the windows in (p, q) order, bit for bit
+    assert np.array_equal(dx, pool_bwd_in_order(dy, earg, x.shape))
 
 
 def index_ops(gb):
@@ -101,6 +105,41 @@ def test_workload_graph_teacher_forced(cfg, batch, fuse):
             assert np.array_equal(cat, oracle.concat_channels(parts))
             terms = [host(gb, n) for n in ("b1_1x1.dx", "b2_reduce.dx", "b3_reduce.dx", "pool.dx")]
             assert rel_l2(host(gb, "dx"), oracle.fan_in_sum(terms)) <= 1e-6
+    finally:
+        gb.close()
+
+
+def test_benchmark_graph_of_the_five_layer_stack_at_full_batch():
+    """The graph bench.py times by default (config 4 at batch 128: fused vertices, in-place buffers,
+    three streams), teacher-forced per conv layer on the device values each operator actually read:
+    two sampled images of the fused forward and of backward-data, ALL of dw (summed by the oracle
+    over the whole batch) and all of db."""
+    import torch
+    from gpu_util import rel_l2, to_host
+    from paper_1412_6249_amd.layers import build_workload
+    gb = build_workload(4, multi_stream=True, fuse=True)
+    tol = 1e-5
+    try:
+        gb.run()
+        legal_order(gb)
+        rs = np.random.default_rng(404)
+        for rec in gb.conv_records:
+            L = rec["layer"]
+            assert L.N == 128 and rec["fused_fwd"]
+            imgs = sorted(rs.choice(L.N - 1, size=1, replace=False).tolist() + [L.N - 1])
+            w, b = host(gb, rec["w"]), host(gb, rec["b"])
+            x, dy = host(gb, rec["x"]), host(gb, rec["dy"])
+            ref = oracle.bias_fwd(oracle.conv_fwd(x[imgs], w, L.stride, L.pad), b)
+            if rec["relu"]:
+                ref = np.maximum(ref, 0.0)
+            assert rel_l2(to_host(gb.t[rec["out"]][imgs]), ref) <= tol, (L.name, "fused fwd")
+            if rec["dx"] is not None:
+                ref_dx = oracle.conv_bwd_data(dy[imgs], w, x[imgs].shape, L.stride, L.pad)
+                if rec.get("fused_bwd"):
+                    ref_dx = np.where(x[imgs] > 0, ref_dx, 0.0)
+                assert rel_l2(to_host(gb.t[rec["dx"]][imgs]), ref_dx) <= tol, (L.name, "dx")
+            assert rel_l2(host(gb, rec["dw"]), oracle.conv_bwd_weight(x, dy, w.shape, L.stride, L.pad)) <= tol, (L.name, "dw")
+            assert rel_l2(host(gb, rec["db"]), oracle.bias_bwd(dy)) <= tol, (L.name, "db")
     finally:
         gb.close()
 

@@ -1,14 +1,15 @@
 """GPU parity at the FULL workload shapes (configs 2-5, every conv layer), in the launch
 configuration bench.py times, on outputs the oracle can compute one by one:
-  - forward (+bias) and backward-data: whole images, sampled by seed (these passes are independent
-    per image, so an image of the batch is an exact sub-problem);
-  - backward-weight: sampled elements of dw, each summed by the oracle over the whole batch;
+  - forward (+bias) and backward-data: every image of configs 2 and 3; for configs 4 and 5 whole
+    images sampled by seed (these passes are independent per image, so an image of the batch is an
+    exact sub-problem);
+  - backward-weight: EVERY element of dw, summed by the oracle over the whole batch;
   - bias gradient: all of it.
 The fused operators bench.py's graphs use (Conv+Bias+ReLU, ConvBwdData through a ReLU mask,
 ConvBwdWeight+BiasBwd) are
 checked on the same samples. A second test feeds small-integer tensors at full shape, where every
-partial sum is an exact integer below 2^24, so the sampled outputs must match bit for bit whatever
-the summation order (index and shape bookkeeping at the real sizes).
+partial sum is an exact integer below 2^24, so the outputs (sampled images, all of dw and db) must
+match bit for bit whatever the summation order (index and shape bookkeeping at the real sizes).
 Tolerance: relative L2 <= 1e-5 (fp32), <= 1e-2 (bf16 in, fp32 accumulate), over each sample."""
 import sys
 
@@ -54,7 +55,7 @@ def test_full_shape_layer(cfg, idx):
 
     tol = TOL[L.dtype]
     rs = np.random.default_rng(1000 * cfg + idx)
-    imgs = sorted(rs.choice(L.N, size=2, replace=False).tolist() + [L.N - 1])
+    imgs = list(range(L.N)) if cfg in (2, 3) else sorted(rs.choice(L.N - 1, size=2, replace=False).tolist() + [L.N - 1])
     hw, hb = to_host(w), to_host(b)
     hx_s, hdy_s = to_host(x[imgs]), to_host(dy[imgs])
     ref_y = oracle.bias_fwd(oracle.conv_fwd(hx_s, hw, L.stride, L.pad), hb)
@@ -76,11 +77,12 @@ def test_full_shape_layer(cfg, idx):
     assert np.all(got_dx2[~mask] == 0)
     del hx_s, hdy_s, y2, dx2, act
     hx, hdy = to_host(x), to_host(dy)
-    n_w = int(np.prod(L.w_shape))
-    flat = np.unique(np.concatenate([rs.integers(0, n_w, size=48), [0, n_w - 1]]))
-    ref_dw = oracle.conv_bwd_weight_at(hx, hdy, L.w_shape, flat, L.stride, L.pad)
-    got_dw = dw.cpu().numpy().ravel()[flat]
+    ref_dw = oracle.conv_bwd_weight(hx, hdy, L.w_shape, L.stride, L.pad)
+    got_dw = dw.cpu().numpy()
     assert rel_l2(got_dw, ref_dw) <= tol, ("bwd_weight", rel_l2(got_dw, ref_dw))
+    # no single filter (one k: a row of the weight-gradient GEMM) may hide behind the others
+    per_k = [rel_l2(got_dw[k], ref_dw[k]) for k in range(L.K)]
+    assert max(per_k) <= 4 * tol, ("bwd_weight, worst filter", int(np.argmax(per_k)), max(per_k))
     ref_db = oracle.bias_bwd(hdy)
     assert rel_l2(db.cpu().numpy(), ref_db) <= tol, ("bias_bwd", rel_l2(db.cpu().numpy(), ref_db))
     # the two parameter gradients from the single fused operator
@@ -98,7 +100,7 @@ INT_CASES = [(2, 0), (2, 1), (3, 4), (4, 2), (5, 0), (5, 2)]
 def test_full_shape_integer_inputs_bit_exact(cfg, idx):
     """One layer per kernel family (flattened forward + phase-folded backward, 1x1 streaming,
     small-channel 5x5, tap-major 3x3 with per-tap weight gradient, bf16 flattened, bf16 tap-major)
-    at full shape with values in {-2..2}: sampled images of y and dx, sampled elements of dw and all
+    at full shape with values in {-2..2}: sampled images of y and dx, every element of dw and all
     of db must equal the oracle exactly (bf16-stored outputs after the same RNE rounding)."""
     import torch
     import paper_1412_6249_amd as pa
@@ -137,11 +139,9 @@ def test_full_shape_integer_inputs_bit_exact(cfg, idx):
     assert np.array_equal(to_host(dx[imgs]), stored(ref_dx)), "bwd_data"
     del hx_s, hdy_s
     hx, hdy = to_host(x), to_host(dy)
-    n_w = int(np.prod(L.w_shape))
-    flat = np.unique(np.concatenate([rs.integers(0, n_w, size=24), [0, n_w - 1]]))
-    ref_dw = oracle.conv_bwd_weight_at(hx, hdy, L.w_shape, flat, L.stride, L.pad)
+    ref_dw = oracle.conv_bwd_weight(hx, hdy, L.w_shape, L.stride, L.pad)
     assert np.abs(ref_dw).max() < 2 ** 24
-    assert np.array_equal(dw.cpu().numpy().ravel()[flat], ref_dw.astype(np.float32)), "bwd_weight"
+    assert np.array_equal(dw.cpu().numpy(), ref_dw.astype(np.float32)), "bwd_weight"
     assert np.array_equal(db.cpu().numpy(), oracle.bias_bwd(hdy).astype(np.float32)), "bias_bwd"
     dw2, db2 = torch.empty_like(dw), torch.empty_like(db)
     pa.purine_conv_bwd_weight_bias(desc, x, dy, dw2, db2, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))

@@ -46,6 +46,9 @@ CASES = [
     # and still needs the depth-to-space epilogue
     ("pw_stride2", 2, 32, 9, 10, 24, 1, 1, (2, 2), (0, 0)),
     ("filter_inside_stride", 2, 64, 20, 21, 33, 1, 2, (1, 4), (0, 1)),
+    # K % 4 != 0 with K*C*R*S % 4 == 0 and 64 splits of the pixel reduction: dw's partials are added
+    # by the same kernel with and without the fused bias gradient (whose rows are not 16-byte aligned)
+    ("k6_many_splits", 4, 2, 64, 64, 6, 3, 3, (1, 1), (1, 1)),
 ]
 PW = [c for c in CASES if c[0].startswith("pw_")]
 
@@ -201,6 +204,44 @@ def test_pointwise_kernel_shapes_agree(shape, dtype):
         pa.purine_debug_force_tile(0, 0)
     for name, g, r in zip(("y", "dx"), got, ref):
         assert rel_l2(g, r) <= TOL[dtype], (shape, name, rel_l2(g, r))
+
+
+@pytest.mark.parametrize("C", [36, 100, 66, 3])
+def test_pointwise_backward_with_rows_past_the_last_channel(C):
+    """1x1 backward-data on the streaming kernel where the last 32-row tile is mostly empty (C % 32 in
+    1..4): plain, accumulating and through the ReLU mask. dx and the mask are the LAST bytes of their
+    buffers (anything the epilogue touched past the last channel would lie outside them) and the
+    words in front of them must come back untouched."""
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import rel_l2, workspace, DEV
+    N, K, H, W = 2, 32, 6, 6
+    rs = np.random.default_rng(C)
+    u = lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32)
+    w, dy, act, prev = u(K, C, 1, 1), u(N, K, H, W), u(N, C, H, W), u(N, C, H, W)
+    desc = pa.conv_desc(1, 0)
+    guard, n = 64, N * C * H * W
+
+    def at_the_end(values):
+        buf = torch.full((guard + n,), 777.0, dtype=torch.float32, device=DEV)
+        t = buf[guard:].view(N, C, H, W)
+        t.copy_(torch.from_numpy(values).to(DEV))
+        return buf, t
+
+    tw, tdy = torch.from_numpy(w).to(DEV), torch.from_numpy(dy).to(DEV)
+    ws = workspace(pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_DATA, desc, act.shape, w.shape, pa.PURINE_F32))
+    ref = oracle.conv_bwd_data(dy, w, act.shape, 1, 0)
+    mb, tmask = at_the_end(act)
+    for beta, masked in ((0.0, False), (1.0, False), (0.0, True), (1.0, True)):
+        db_, tdx = at_the_end(prev)
+        if masked:
+            pa.purine_conv_bwd_data_relu(desc, tdy, tw, tmask, tdx, beta=beta, ws=ws)
+        else:
+            pa.purine_conv_bwd_data(desc, tdy, tw, tdx, beta=beta, ws=ws)
+        torch.cuda.synchronize()
+        want = (np.where(act > 0, ref, 0.0) if masked else ref) + (prev if beta else 0.0)
+        assert rel_l2(tdx.cpu().numpy(), want) <= 1e-5, (beta, masked)
+        assert bool((db_[:guard] == 777.0).all()) and bool((mb[:guard] == 777.0).all())
 
 
 def test_results_are_bit_identical_run_to_run():

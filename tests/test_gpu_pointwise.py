@@ -73,7 +73,7 @@ def pool_inputs(case, dtype, ties):
 @pytest.mark.parametrize("case", POOLS, ids=[c[0] for c in POOLS])
 def test_maxpool_forward_and_backward(case, dtype, ties):
     import paper_1412_6249_amd as pa
-    from gpu_util import to_dev, to_host, tdtype, rel_l2, DEV
+    from gpu_util import to_dev, to_host, tdtype, rel_l2, pool_bwd_in_order, DEV
     name, N, C, H, W, k, s, p = case
     x, dy = pool_inputs(case, dtype, ties)
     ey, earg = oracle.maxpool_fwd(x, k, s, p)
@@ -94,6 +94,8 @@ def test_maxpool_forward_and_backward(case, dtype, ties):
     assert rel_l2(to_host(tdx), edx) <= tol
     # positions no window chose get exactly zero
     assert np.all(to_host(tdx)[edx == 0] == 0)
+    # and bit for bit the fp32 sum over the windows in (p, q) order
+    assert np.array_equal(to_host(tdx), pool_bwd_in_order(dy, earg, x.shape, dtype))
 
     # accumulate into an existing gradient
     prev = np.random.default_rng(5).uniform(-1, 1, size=x.shape).astype(np.float32)
@@ -103,6 +105,7 @@ def test_maxpool_forward_and_backward(case, dtype, ties):
     pa.purine_maxpool_bwd(desc, tdy, targ, tdx2, beta=1.0)
     torch.cuda.synchronize()
     assert rel_l2(to_host(tdx2), edx + prev) <= tol
+    assert np.array_equal(to_host(tdx2), pool_bwd_in_order(dy, earg, x.shape, dtype, prev=prev))
 
 
 def test_maxpool_backward_is_deterministic():

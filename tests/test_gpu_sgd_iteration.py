@@ -1,4 +1,4 @@
-"""SGD by graph iteration (paper section 2.2, Figure 3) on the GPU: the update operator against the
+"""SGD by graph iteration (paper section 2.2, Figure 2) on the GPU: the update operator against the
 oracle, and iterated workload graphs (network graph with one update operator per parameter, then
 the swap of old and new parameters) checked iteration by iteration with teacher forcing: the
 parameters an iteration starts from and the gradients it computed are downloaded, the oracle's

@@ -210,7 +210,7 @@ def test_empty_graph_runs():
 
 
 def test_swap_storage_and_iteration_bookkeeping():
-    """The swap step of graph iteration (paper section 2.2, Figure 3(b)) as host bookkeeping: every
+    """The swap step of graph iteration (paper section 2.2, Figure 2(b)) as host bookkeeping: every
     vertex bound to either address moves with it, the graph stays valid, and what would change the
     set of conflicting operators is refused."""
     g = pa.purine_graph_create()

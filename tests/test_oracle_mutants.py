@@ -32,6 +32,10 @@ MUTANTS = [
     ("pool_last_maximum_wins_ties", "if (best < 0 || v > bv) { best = (int32_t)(h * W + w_); bv = v; }",
      "if (best < 0 || v >= bv) { best = (int32_t)(h * W + w_); bv = v; }", 0),
     ("pool_gradient_overwrites", "if (a >= 0) plane[a] += (double)dy[nc * PQ + i];", "if (a >= 0) plane[a] = (double)dy[nc * PQ + i];", 0),
+    ("pool_gradient_lands_one_position_off", "if (a >= 0) plane[a] += (double)dy[nc * PQ + i];",
+     "if (a >= 0) plane[(a + 1) % HW] += (double)dy[nc * PQ + i];", 0),
+    ("pool_gradient_reads_another_planes_dy", "if (a >= 0) plane[a] += (double)dy[nc * PQ + i];",
+     "if (a >= 0) plane[a] += (double)dy[((nc + 1) % NC) * PQ + i];", 0),
     ("relu_passes_zero_gradient", "dx[i] = x[i] > 0.0f ? dy[i] : 0.0f;", "dx[i] = x[i] >= 0.0f ? dy[i] : 0.0f;", 0),
 ]
 

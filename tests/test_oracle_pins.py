@@ -367,6 +367,64 @@ def test_relu_and_pool_and_concat():
     assert np.array_equal(oracle.fan_in_sum([a, a]), 2 * a.astype(np.float64))
 
 
+def pool_winners_by_hand(x, k, stride, pad):
+    """Winner of every pooling window found without the oracle: the window is cut out of a copy of
+    the plane padded with -inf and numpy's argmax (first maximum in row-major order) picks it."""
+    N, C, H, W = x.shape
+    P, Q = (H + 2 * pad - k) // stride + 1, (W + 2 * pad - k) // stride + 1
+    xp = np.full((N, C, H + 2 * pad, W + 2 * pad), -np.inf)
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    hh = np.empty((N, C, P, Q), np.int64)
+    ww = np.empty((N, C, P, Q), np.int64)
+    for p in range(P):
+        for q in range(Q):
+            a = xp[:, :, p * stride:p * stride + k, q * stride:q * stride + k].reshape(N, C, k * k).argmax(-1)
+            hh[:, :, p, q] = p * stride - pad + a // k
+            ww[:, :, p, q] = q * stride - pad + a % k
+    return hh, ww
+
+
+@pytest.mark.parametrize("k,stride,pad,H,W", [(3, 1, 1, 6, 7), (3, 2, 0, 9, 7), (3, 2, 1, 8, 8), (2, 2, 0, 6, 4),
+                                               (5, 3, 2, 11, 9)])
+def test_pool_gradient_lands_on_the_winner_of_its_own_window(k, stride, pad, H, W):
+    """Brute force: every window adds its dy to dx[n, c, h*, w*] of ITS plane, (h*, w*) its winner;
+    overlapping windows add up. The winners are found by hand (not by the oracle), the planes hold
+    distinct values and different planes hold different data, so a gradient landing one position
+    off, or read from another plane's dy, changes the result."""
+    N, C = 2, 3
+    x = RNG.permutation(N * C * H * W).reshape(N, C, H, W).astype(np.float32)   # all distinct
+    hh, ww = pool_winners_by_hand(x, k, stride, pad)
+    y, arg = oracle.maxpool_fwd(x, k, stride, pad)
+    assert np.array_equal(arg, hh * W + ww)
+    dy = rnd(*y.shape)
+    want = np.zeros(x.shape, np.float64)
+    for n, c, p, q in itertools.product(range(N), range(C), range(y.shape[2]), range(y.shape[3])):
+        want[n, c, hh[n, c, p, q], ww[n, c, p, q]] += float(dy[n, c, p, q])
+    got = oracle.maxpool_bwd(dy, arg, x.shape)
+    assert np.abs(got - want).max() <= 1e-15
+    if stride < k:      # overlapping windows: some position must have collected several gradients
+        counts = np.zeros(x.shape, np.int64)
+        np.add.at(counts, (np.arange(N)[:, None, None, None], np.arange(C)[None, :, None, None], hh, ww), 1)
+        assert counts.max() >= 2
+
+
+def test_pool_gradient_is_the_derivative_of_the_pooled_loss():
+    """L(x) = <maxpool(x), dy> is piecewise linear; with distinct integer inputs a step of 0.25 at
+    one position never changes a winner, so the one-sided difference quotient is exact and equals
+    maxpool_bwd's element there (through the forward routine only, which has its own pins)."""
+    x = RNG.permutation(2 * 2 * 7 * 7).reshape(2, 2, 7, 7).astype(np.float32)
+    k, stride, pad = 3, 2, 1
+    y, arg = oracle.maxpool_fwd(x, k, stride, pad)
+    dy = np.round(rnd(*y.shape) * 64) / 64          # on a 2^-6 grid: every product below is exact
+    dx = oracle.maxpool_bwd(dy, arg, x.shape)
+    loss = lambda t: float((oracle.maxpool_fwd(t, k, stride, pad)[0].astype(np.float64) * dy).sum())
+    base = loss(x)
+    for idx in itertools.product(range(2), range(2), range(7), range(7)):
+        t = x.copy()
+        t[idx] += 0.25
+        assert (loss(t) - base) / 0.25 == dx[idx], idx
+
+
 # ---------------------------------------------------------------- SGD step (section 2.2)
 def test_sgd_update_descends_a_linear_and_a_quadratic_loss():
     """Pins sign and scale of the update with functions other than itself. (1) L(w) = <conv(x, w), g>
