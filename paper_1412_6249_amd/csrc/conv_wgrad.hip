@@ -782,27 +782,36 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     const long long tiles = (long long)pl.tiles_i * pl.tiles_j;
     // Number of splits. A CU holds three of these workgroups at a time, so the chip runs them in
     // rounds of 768; a grid just over a multiple of 768 leaves the chip almost idle for a whole
-    // extra round, and a grid under 512 leaves too few wavefronts to hide latency. Score every
-    // admissible split count by the fraction of workgroup slots it keeps busy (discounted when a
-    // CU would hold fewer than three) and take the best; chunks stay within 256..8192 pixels (a
-    // short chunk is mostly prologue and epilogue, a long one lengthens the fp32 accumulation chain).
+    // extra round, and a grid under 512 leaves too few wavefronts to hide latency. Every split also
+    // writes a partial copy of dw that the second pass reads back, so more splits mean more HBM
+    // traffic beside the operands. Every admissible split count gets a time estimate
+    //     workgroup slots per CU x pixels per chunk x time of one tile-pixel  +  partials / bandwidth
+    // and the smallest wins; chunks stay within 256..8192 pixels (a short chunk is mostly prologue
+    // and epilogue, a long one lengthens the fp32 accumulation chain).
+    const double rate = dtype == PURINE_F32 ? 110e12 : 450e12;      // what these kernels sustain on the MFMA units
+    const double t_pixel = 2.0 * pl.bm * pl.bn * 256.0 / rate;      // one workgroup alone on a CU, per pixel
+    const double dw_bytes = (double)g.K * (double)CRS * 4.0;
     const long long max_splits = (M + 255) / 256;
     long long min_splits = (M + 8191) / 8192;
     if (min_splits < 1) min_splits = 1;
     long long splits = min_splits;
-    double best_score = -1.0;
+    double best_time = -1.0;
     for (long long sp = min_splits; sp <= max_splits && sp <= min_splits + 4096; ++sp) {
         const long long wgs = tiles * sp;
-        double score;
+        double slots;
         if (wgs <= 768) {
             const long long per_cu = (wgs + 255) / 256;              // 1..3 workgroups on the busiest CU
             const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.85 : 0.55);
-            score = (double)wgs / (double)(per_cu * 256) * hide;
+            slots = (double)per_cu / hide;
         } else {
-            score = (double)wgs / (double)((wgs + 767) / 768 * 768);
-            if (wgs > 6 * 768) score = score > 0.97 ? score : 0.97;   // many rounds: the tail no longer matters
+            const long long rounds = (wgs + 767) / 768;
+            slots = 3.0 * (double)rounds;
+            // many rounds: workgroups of different rounds overlap and the tail no longer matters
+            if (rounds > 6 && (double)wgs / 256.0 / 0.97 < slots) slots = (double)wgs / 256.0 / 0.97;
         }
-        if (score > best_score + 1e-9) { best_score = score; splits = sp; }
+        const double chunk_px = (double)((M + sp - 1) / sp);
+        const double t = slots * chunk_px * t_pixel + 2.0 * (double)sp * dw_bytes / 4e12;
+        if (best_time < 0 || t < best_time - 1e-12) { best_time = t; splits = sp; }
         if (wgs > 8 * 768) break;
     }
     long long chunk = (M + splits - 1) / splits;
