@@ -60,7 +60,9 @@ typedef enum {
     PURINE_E_WORKSPACE = -5, /* ws is NULL or smaller than the query says                   */
     PURINE_E_GRAPH = -6,     /* not a legal bi-graph (see purine_graph_run)                 */
     PURINE_E_HIP = -7,       /* the HIP runtime reported an error                           */
-    PURINE_E_ARG = -8        /* a scalar argument is out of range (stride, beta, ids, ...)  */
+    PURINE_E_ARG = -8,       /* a scalar argument is out of range (stride, beta, ids, ...)  */
+    PURINE_E_STATIC_SCRATCH = -9 /* purine_conv_bwd_weight_static: the layer needs more scratch
+                                    than purine_static_scratch_bytes()                         */
 } purine_status;
 
 typedef struct {
@@ -139,6 +141,23 @@ int purine_conv_bwd_data_relu(const purine_conv_desc* desc, const purine_tensor*
 int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
                            const purine_tensor* dy, purine_tensor* dw, float beta, void* ws,
                            size_t ws_bytes, void* hip_stream);
+
+/* ConvBwdWeight for callers that cannot allocate device memory or bring a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same operator, same
+ * kernels and bit-identical results as purine_conv_bwd_weight, but the split-reduction partial
+ * sums go to a fixed array inside the library's device image (purine_static_scratch_bytes() bytes,
+ * 64 MiB, held by every GPU the library runs on until the process ends). The call allocates
+ * nothing: no hipMalloc / hipFree and no allocating library routine. A layer whose
+ * purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, ...) exceeds that size is refused with
+ * PURINE_E_STATIC_SCRATCH before anything is launched. The first call on a device looks up that
+ * device's address of the array (once; the device current at the call is the one used). Every
+ * call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different streams
+ * with no ordering between them, or different host threads) race on it and must be ordered by the
+ * caller; nothing needs clearing between calls (each call writes every partial sum it later reads). */
+int purine_conv_bwd_weight_static(const purine_conv_desc* desc, const purine_tensor* x,
+                                  const purine_tensor* dy, purine_tensor* dw, float beta,
+                                  void* hip_stream);
+size_t purine_static_scratch_bytes(void);
 
 /* ConvBwdWeight and BiasBwd of one layer as a single operator (both read all of dy; paper
  * Figure 1(b) draws them as two vertices on the same incoming tensor): dw as above and

@@ -27,7 +27,7 @@ OP_GROUPED_CONV_FWD, OP_GROUPED_CONV_BWD_DATA, OP_GROUPED_CONV_BWD_WEIGHT = 21, 
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
-          -7: "PURINE_E_HIP", -8: "PURINE_E_ARG"}
+          -7: "PURINE_E_HIP", -8: "PURINE_E_ARG", -9: "PURINE_E_STATIC_SCRATCH"}
 
 
 class PurineError(RuntimeError):
@@ -78,6 +78,8 @@ _SIGS = {
     "purine_conv_bwd_data": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_bwd_weight": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_conv_bwd_weight_bias": (ctypes.c_int, [_D, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
+    "purine_conv_bwd_weight_static": (ctypes.c_int, [_D, _T, _T, _T, ctypes.c_float, _vp]),
+    "purine_static_scratch_bytes": (_sz, []),
     "purine_grouped_conv_workspace_bytes": (_sz, [ctypes.c_int, _D, ctypes.c_int, _i64p, _i64p, ctypes.c_int32]),
     "purine_grouped_conv_fwd": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, _T, ctypes.c_int, _vp, _sz, _vp]),
     "purine_grouped_conv_bwd_data": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
@@ -282,6 +284,16 @@ def purine_conv_bwd_weight(desc, x, dy, dw, beta=0.0, ws=None, stream=None):
     _check(_lib.purine_conv_bwd_weight(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
                                        _ref(tensor_desc(dw)), float(beta), p, n, _stream(stream)),
            "purine_conv_bwd_weight")
+
+
+def purine_conv_bwd_weight_static(desc, x, dy, dw, beta=0.0, stream=None):
+    _check(_lib.purine_conv_bwd_weight_static(_ref(desc), _ref(tensor_desc(x)), _ref(tensor_desc(dy)),
+                                              _ref(tensor_desc(dw)), float(beta), _stream(stream)),
+           "purine_conv_bwd_weight_static")
+
+
+def purine_static_scratch_bytes():
+    return int(_lib.purine_static_scratch_bytes())
 
 
 def purine_conv_bwd_weight_bias(desc, x, dy, dw, db, beta=0.0, ws=None, stream=None):

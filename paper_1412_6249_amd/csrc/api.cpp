@@ -3,6 +3,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "common.h"
 
 using namespace purine;
@@ -149,6 +151,7 @@ const char* purine_status_string(int status) {
         case PURINE_E_GRAPH: return "not a legal bi-graph";
         case PURINE_E_HIP: return "HIP runtime error";
         case PURINE_E_ARG: return "scalar argument out of range";
+        case PURINE_E_STATIC_SCRATCH: return "needs more scratch than the library's static device array holds";
         default: return "unknown status";
     }
 }
@@ -288,10 +291,38 @@ int purine_conv_bwd_data_relu(const purine_conv_desc* desc, const purine_tensor*
 }
 
 namespace {
-// db == nullptr: ConvBwdWeight alone
+// Scratch of the entry point that allocates nothing: one array in the device image of this
+// library, so every GPU that loads the library holds its own copy until the process ends. In host
+// code the name `scratch` is only a handle for hipGetSymbolAddress: the address a kernel may use
+// is looked up once per device (with that device current) and kept in g_scratch_ptr.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mu;
+
+int static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_status(e);
+    if (dev < 0 || dev >= kMaxDevices) return PURINE_E_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_status(e);
+        if (!p) return hip_status(hipErrorInvalidSymbol);
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PURINE_OK;
+}
+
+// db == nullptr: ConvBwdWeight alone. static_ws: the partial sums go to this device's static
+// scratch array instead of a caller workspace (ws and ws_bytes are ignored).
 int conv_bwd_weight_impl(const purine_conv_desc* desc, const purine_tensor* x, const purine_tensor* dy,
                          purine_tensor* dw, purine_tensor* db, float beta, void* ws, size_t ws_bytes,
-                         void* hip_stream) {
+                         void* hip_stream, bool static_ws = false) {
     int rc;
     if ((rc = check_desc(desc)) || (rc = check_tensor(x, 4, true)) || (rc = check_tensor(dy, 4, true)) ||
         (rc = check_tensor(dw, 4)) || (db && (rc = check_tensor(db, 1))) || (rc = check_beta(beta)))
@@ -307,6 +338,11 @@ int conv_bwd_weight_impl(const purine_conv_desc* desc, const purine_tensor* x, c
     if (db && (overlaps(db, x) || overlaps(db, dy) || overlaps(db, dw))) return PURINE_E_LAYOUT;
     const WgradPlan plan = plan_wgrad(g, x->dtype);
     const size_t need = db ? wgrad_db_offset(plan) + plan.db_ws_bytes : plan.ws_bytes;
+    if (static_ws) {
+        if (need > kStaticScratchBytes) return PURINE_E_STATIC_SCRATCH;
+        if ((rc = static_scratch_of_current_device(&ws))) return rc;
+        ws_bytes = kStaticScratchBytes;
+    }
     if (!ws || ws_bytes < need) return PURINE_E_WORKSPACE;
     if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
     hipError_t e = launch_conv_wgrad(x->dtype, g, plan, x->data, dy->data, (float*)dw->data,
@@ -319,6 +355,14 @@ int purine_conv_bwd_weight(const purine_conv_desc* desc, const purine_tensor* x,
                            const purine_tensor* dy, purine_tensor* dw, float beta, void* ws,
                            size_t ws_bytes, void* hip_stream) {
     return conv_bwd_weight_impl(desc, x, dy, dw, nullptr, beta, ws, ws_bytes, hip_stream);
+}
+
+size_t purine_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int purine_conv_bwd_weight_static(const purine_conv_desc* desc, const purine_tensor* x,
+                                  const purine_tensor* dy, purine_tensor* dw, float beta,
+                                  void* hip_stream) {
+    return conv_bwd_weight_impl(desc, x, dy, dw, nullptr, beta, nullptr, 0, hip_stream, true);
 }
 
 int purine_conv_bwd_weight_bias(const purine_conv_desc* desc, const purine_tensor* x,

@@ -24,7 +24,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported_and_bound():
     names = declared_symbols()
-    assert len(names) == 52
+    assert len(names) == 54
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -232,6 +232,38 @@ def test_operator_argument_validation_without_launch():
     big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
     assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
     assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit():
+    """purine_conv_bwd_weight_static validates like purine_conv_bwd_weight and refuses, before
+    any launch, a layer whose partial sums need more than the library's static device array."""
+    fake = 0x7f0000000000   # never dereferenced: the call is refused on the host
+    F32 = pa.PURINE_F32
+
+    class _S:   # stand-in stream handle so that torch is not consulted
+        cuda_stream = 0
+    s = _S()
+    cap = pa.purine_static_scratch_bytes()
+    assert cap == 64 << 20
+    d = pa.conv_desc(1, 1)
+    # a layer with a large filter and many pixels: its split-reduction partials exceed the array
+    xs, ws_, ys = (8, 512, 64, 64), (512, 512, 3, 3), (8, 512, 64, 64)
+    need = pa.purine_conv_workspace_bytes(pa.PURINE_CONV_BWD_WEIGHT, d, xs, ws_, F32)
+    assert need > cap
+    x = binding.raw_desc(fake, F32, xs)
+    dy = binding.raw_desc(fake + 0x40000000, F32, ys)
+    dw = binding.raw_desc(fake + 0x80000000, F32, ws_)
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_bwd_weight_static(d, x, dy, dw, stream=s)
+    assert e.value.status == -9 and "static" in str(e.value)
+    # argument errors come first, exactly as in the workspace form
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_bwd_weight_static(d, x, dy, dw, beta=0.5, stream=s)
+    assert e.value.status == -8
+    bad = binding.raw_desc(fake + 0x80000000, F32, (512, 511, 3, 3))
+    with pytest.raises(pa.PurineError) as e:
+        pa.purine_conv_bwd_weight_static(d, x, dy, bad, stream=s)
+    assert e.value.status == -2
 
 
 def test_bench_refuses_more_than_one_gpu():
