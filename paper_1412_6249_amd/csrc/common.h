@@ -72,6 +72,7 @@ struct PixPlan {
     int Ci_pad, i_pad; // extents of the repacked filter A[Rt*St][Ci_pad][i_pad]
     size_t ws_bytes;   // scratch: repacked filter, then (bf16 tap kernels) the channels-blocked input copy
     size_t blk_offset; // byte offset of that copy inside the scratch (0: none)
+    bool patch;        // bf16: the kernel that stages the input patch in LDS runs (no blocked copy)
     // 1x1 / stride 1 / unpadded layers: streaming GEMM kernel (used when the pointers are aligned
     // to gemm_tn elements; the fields above stay valid for the general kernel otherwise)
     bool gemm1x1;

@@ -557,8 +557,61 @@ static int g_force_bm = 0, g_force_bn = 0;   // tuning hook, see purine_debug_fo
 static int g_no_buffer_loads = 0;            // tuning hook: bn == -1 in purine_debug_force_tile
 bool buffer_loads_disabled() { return g_no_buffer_loads != 0; }
 void force_pix_tile(int bm, int bn) {
-    g_no_buffer_loads = bn == -1 ? 1 : 0;
+    g_no_buffer_loads = (bn == -1 && bm != -2) ? 1 : 0;
     g_force_bm = bm; g_force_bn = bn;
+}
+
+// Geometry of the implicit GEMM for one pass (everything in PixParams that does not depend on the
+// tensors' addresses, the epilogue options or beta).
+static PixParams make_pix_params(int dtype, const ConvGeom& g, const PixPlan& pl) {
+    PixParams p{};
+    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W;
+    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
+    p.R = g.R; p.S = g.S; p.RS = g.R * g.S;
+    p.Ci = pl.Ci; p.Co = pl.Co; p.Rt = pl.Rt; p.St = pl.St;
+    p.Ci_pad = pl.Ci_pad; p.i_pad = pl.i_pad;
+    p.phases = 1;
+    if (pl.mode == 0) {
+        p.Hi = g.H; p.Wi = g.W; p.Ho = g.P; p.Wo = g.Q;
+        p.g_mul_h = g.sh; p.g_mul_w = g.sw; p.g_add_h = -g.ph; p.g_add_w = -g.pw;
+    } else if (pl.mode == 1) {
+        p.Hi = g.P; p.Wi = g.Q; p.Ho = g.H; p.Wo = g.W;
+        p.g_mul_h = 1; p.g_mul_w = 1; p.g_add_h = g.ph; p.g_add_w = g.pw;
+    } else {
+        // Strided backward-data, phase-folded. Write h + ph = hq*sh + a and w + pw = wq*sw + b.
+        // Only taps r = a + sh*r', s = b + sw*s' reach such a position, from p = hq - r',
+        // q = wq - s'. So dx is a unit-stride correlation of dy with ceil(R/sh) x ceil(S/sw) taps that
+        // produces C*sh*sw "channels" (c, a, b) per coarse pixel (hq, wq), followed by a
+        // depth-to-space shuffle in the epilogue. No multiply is spent on the structural zeros of
+        // the strided transposed convolution, and the GEMM's row count grows from C to C*sh*sw.
+        p.Hi = g.P; p.Wi = g.Q;
+        p.phases = g.sh * g.sw;
+        p.hq_min = g.ph / g.sh; p.wq_min = g.pw / g.sw;
+        p.Ho = (g.H - 1 + g.ph) / g.sh - p.hq_min + 1;
+        p.Wo = (g.W - 1 + g.pw) / g.sw - p.wq_min + 1;
+        p.g_mul_h = 1; p.g_mul_w = 1; p.g_add_h = p.hq_min; p.g_add_w = p.wq_min;
+    }
+    p.HiWi = p.Hi * p.Wi;
+    p.HoWo = p.Ho * p.Wo;
+    p.M = p.N * p.HoWo;
+    p.in_ns = pl.mode == 0 ? g.x_ns : g.y_ns;    // forward gathers x, backward-data gathers dy
+    p.out_ns = pl.mode == 0 ? g.y_ns : g.x_ns;
+    p.Kg = p.Ci * p.RS;
+    p.div_howo = make_fastdiv(p.HoWo);
+    p.div_wo = make_fastdiv(p.Wo);
+    p.div_phases = make_fastdiv(p.phases);
+    p.div_sw = make_fastdiv(p.sw);
+    p.div_rs = make_fastdiv(p.RS);
+    p.div_s = make_fastdiv(p.S);
+    p.tiles_i = pl.tiles_i; p.tiles_pix = pl.tiles_pix;
+    {
+        // raw-buffer gather of the fp32 tap kernels: the whole tensor must be addressable with byte
+        // offsets below 2^31
+        const long long in_bytes = ((long long)(p.N - 1) * p.in_ns + (long long)p.Ci * p.HiWi) * 4;
+        p.in_bytes = (dtype == PURINE_F32 && in_bytes < 0x7fffffffLL && g_no_buffer_loads == 0) ? (unsigned)in_bytes : 0u;
+    }
+
+    return p;
 }
 
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
@@ -640,7 +693,17 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     pl.ws_bytes = flat_copy ? (size_t)pl.Ci_pad * (size_t)i_pad_max * elem
                   : pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
     pl.blk_offset = 0;
-    if (dtype == PURINE_BF16 && !pl.flat && pl.Rt * pl.St > 1) {
+    pl.patch = false;
+    if (dtype == PURINE_BF16 && !pl.flat && pl.Rt * pl.St > 1 && g_force_bm != -2) {
+        // layers whose gathered rows are whole 16-byte packets and whose gather has unit stride stage
+        // the input patch in LDS and need no re-laid-out copy (tuning hook: force_pix_tile(-2, x) keeps
+        // them on the blocked-copy kernel)
+        PixParams probe = make_pix_params(dtype, g, pl);
+        PatchGeom q;
+        pl.patch = plan_patch_bf16(probe, pl.mode, &q);
+        if (pl.patch) pl.ws_bytes = patch_filter_bytes(Co, Ci, pl.Rt * pl.St);
+    }
+    if (dtype == PURINE_BF16 && !pl.flat && pl.Rt * pl.St > 1 && !pl.patch) {
         // channels-blocked copy of the gathered tensor behind the filter copy (single-tap layers
         // gather each element once, straight from NCHW)
         const size_t gathered = (size_t)g.N * pl.Ci_pad * (bwd_data ? (size_t)g.P * g.Q : (size_t)g.H * g.W);
@@ -676,55 +739,10 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
 hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, const void* in,
                            const void* wt, void* out, float beta, void* ws, const PixEpilogue& epi,
                            hipStream_t st) {
-    PixParams p{};
+    PixParams p = make_pix_params(dtype, g, pl);
     p.in = in; p.out = out;
     p.bias = epi.bias; p.relu = epi.relu; p.mask = epi.mask;
-    p.N = g.N; p.C = g.C; p.H = g.H; p.W = g.W;
-    p.sh = g.sh; p.sw = g.sw; p.ph = g.ph; p.pw = g.pw;
-    p.R = g.R; p.S = g.S; p.RS = g.R * g.S;
-    p.Ci = pl.Ci; p.Co = pl.Co; p.Rt = pl.Rt; p.St = pl.St;
-    p.Ci_pad = pl.Ci_pad; p.i_pad = pl.i_pad;
-    p.phases = 1;
-    if (pl.mode == 0) {
-        p.Hi = g.H; p.Wi = g.W; p.Ho = g.P; p.Wo = g.Q;
-        p.g_mul_h = g.sh; p.g_mul_w = g.sw; p.g_add_h = -g.ph; p.g_add_w = -g.pw;
-    } else if (pl.mode == 1) {
-        p.Hi = g.P; p.Wi = g.Q; p.Ho = g.H; p.Wo = g.W;
-        p.g_mul_h = 1; p.g_mul_w = 1; p.g_add_h = g.ph; p.g_add_w = g.pw;
-    } else {
-        // Strided backward-data, phase-folded. Write h + ph = hq*sh + a and w + pw = wq*sw + b.
-        // Only taps r = a + sh*r', s = b + sw*s' reach such a position, from p = hq - r',
-        // q = wq - s'. So dx is a unit-stride correlation of dy with ceil(R/sh) x ceil(S/sw) taps that
-        // produces C*sh*sw "channels" (c, a, b) per coarse pixel (hq, wq), followed by a
-        // depth-to-space shuffle in the epilogue. No multiply is spent on the structural zeros of
-        // the strided transposed convolution, and the GEMM's row count grows from C to C*sh*sw.
-        p.Hi = g.P; p.Wi = g.Q;
-        p.phases = g.sh * g.sw;
-        p.hq_min = g.ph / g.sh; p.wq_min = g.pw / g.sw;
-        p.Ho = (g.H - 1 + g.ph) / g.sh - p.hq_min + 1;
-        p.Wo = (g.W - 1 + g.pw) / g.sw - p.wq_min + 1;
-        p.g_mul_h = 1; p.g_mul_w = 1; p.g_add_h = p.hq_min; p.g_add_w = p.wq_min;
-    }
-    p.HiWi = p.Hi * p.Wi;
-    p.HoWo = p.Ho * p.Wo;
-    p.M = p.N * p.HoWo;
-    p.in_ns = pl.mode == 0 ? g.x_ns : g.y_ns;    // forward gathers x, backward-data gathers dy
-    p.out_ns = pl.mode == 0 ? g.y_ns : g.x_ns;
-    p.Kg = p.Ci * p.RS;
-    p.div_howo = make_fastdiv(p.HoWo);
-    p.div_wo = make_fastdiv(p.Wo);
-    p.div_phases = make_fastdiv(p.phases);
-    p.div_sw = make_fastdiv(p.sw);
-    p.div_rs = make_fastdiv(p.RS);
-    p.div_s = make_fastdiv(p.S);
     p.beta = beta;
-    p.tiles_i = pl.tiles_i; p.tiles_pix = pl.tiles_pix;
-    {
-        // raw-buffer gather of the fp32 tap kernels: the whole tensor must be addressable with byte
-        // offsets below 2^31
-        const long long in_bytes = ((long long)(p.N - 1) * p.in_ns + (long long)p.Ci * p.HiWi) * 4;
-        p.in_bytes = (dtype == PURINE_F32 && in_bytes < 0x7fffffffLL && g_no_buffer_loads == 0) ? (unsigned)in_bytes : 0u;
-    }
 
     if (pl.gemm1x1) {
         const uintptr_t align = (uintptr_t)pl.gemm_tn * (dtype == PURINE_BF16 ? 2 : 4) - 1;
@@ -760,6 +778,14 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
     }
     // bf16: the whole operator (input copy, filter repack, main kernel) is what a timing probe brackets
     ProbeScope whole_op(dtype == PURINE_BF16 ? st : nullptr, dtype == PURINE_BF16);
+    if (pl.patch) {
+        PatchGeom qg;
+        if (!plan_patch_bf16(p, pl.mode, &qg) || !ws) return hipErrorInvalidValue;
+        hipError_t e = repack_patch_filter(p, pl.mode, wt, ws, g.K, g.C, st);
+        if (e != hipSuccess) return e;
+        p.wt = ws;
+        return launch_patch_bf16(p, qg, pl.mode, st);
+    }
     const bool blocked = dtype == PURINE_BF16 && pl.Rt * pl.St > 1;
     if (blocked) {
         if (!pl.blk_offset || !ws) return hipErrorInvalidValue;

@@ -1,0 +1,479 @@
+// bf16 MFMA implicit GEMM with the input patch staged in LDS (Conv / ConvBwdData of paper
+// Figure 1(b), unit-stride gathers: forward with stride 1, backward-data with any stride after
+// phase folding).
+//
+// A workgroup owns BM output rows (channels) and BN consecutive output pixels of ONE image. Those
+// pixels span a few image rows; the input positions all their taps touch form a haloed patch of
+// (rows spanned + Rt - 1) x (Wo + St - 1) positions. Per group of 16 gathered channels (one MFMA
+// reduction step) the patch is brought into LDS ONCE, straight from the NCHW tensor: a lane loads
+// 8 consecutive pixels of one channel as one 16-byte packet (coalesced along W), eight channels'
+// packets are transposed in registers (one byte-permute per output dword) into eight
+// [pixel][8 channels] packets and stored pixel-major, which is the operand layout the bf16 MFMA
+// wants (8 consecutive reduction elements per lane). Every tap then reads its B fragments from the
+// same patch at a shifted position, so the global gathers of the tap-major kernel shrink by the
+// number of taps and no re-laid-out copy of the tensor ever goes to HBM. Rows and columns outside
+// the image are zeros in the patch (the halo columns are cleared once, out-of-image rows come back
+// as zeros from range-checked buffer loads).
+//
+// The filter of the same 16 channels sits beside the patch for ALL taps of a stage (from a copy
+// repacked to A[group][tap][i][16]), so the tap loop runs without barriers: one stage = one channel
+// group x a run of taps, two barriers per stage. The loads of the next stage (filter and, when
+// the group changes, patch) are issued before the stage's MFMAs and land in registers meanwhile.
+// Accumulators stay in registers for the whole reduction.
+#include "pix_common.h"
+
+namespace purine {
+namespace pix {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int GC = 16;              // gathered channels per group: one MFMA reduction step
+constexpr int PITCH = GC * 2 + 16;  // LDS bytes per pixel (patch) or filter row: 32 of data + 16 of padding,
+                                    // so that the 16-byte fragment reads of 8 consecutive rows cover all banks
+constexpr int A_ROUNDS = 8;         // 16-byte filter pieces per thread and stage, at most
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values to two bf16 (round to nearest even) in one dword, first value in the low half.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+__device__ __forceinline__ float swap_with_neighbour(float v) {   // value of lane ^ 1 (quad permute 1,0,3,2)
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
+}
+
+// Epilogue for NCHW outputs whose pixel pairs (2j, 2j+1) are 4-byte aligned (even HoWo and image
+// distance; pixel tiles start at even pixels). An accumulator quad holds four consecutive rows of
+// ONE pixel per lane; neighbouring lanes hold neighbouring pixels. The even lane of a pair hands
+// rows 2,3 to its neighbour and takes the neighbour's rows 0,1 (two DPP moves), so every lane ends
+// up with two rows x two adjacent pixels: two 4-byte stores (and mask / old-value loads) per quad
+// instead of four 2-byte ones, and the fp32 -> bf16 conversion is the packed hardware one.
+template <bool FUSED, int TM, int TN, bool FWD>
+__device__ __forceinline__ void store_pairs(const PixParams& p, floatx16 (&acc)[TM][TN], int i_base, int n,
+                                            int pix_base, int pix_end, int lane, const float* bias_lds, int i_tile0) {
+    uint16_t* __restrict__ out = (uint16_t*)p.out;
+    const uint16_t* __restrict__ mask = (const uint16_t*)p.mask;
+    const bool has_bias = FUSED && FWD && p.bias != nullptr, relu = FUSED && FWD && p.relu;
+    const bool has_mask = FUSED && !FWD && mask != nullptr, has_beta = !FWD && p.beta != 0.0f;
+    const bool odd = lane & 1;
+    const int khalf = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int pix = pix_base + b * 32;                 // this lane's pixel inside the image
+        const int pair = pix & ~1;
+        if (pair >= pix_end) continue;
+        const int obase = n * p.out_ns + pair;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd) {
+                const float v0 = acc[a][b][qd * 4 + 0], v1 = acc[a][b][qd * 4 + 1];
+                const float v2 = acc[a][b][qd * 4 + 2], v3 = acc[a][b][qd * 4 + 3];
+                const float r0 = swap_with_neighbour(odd ? v0 : v2);
+                const float r1 = swap_with_neighbour(odd ? v1 : v3);
+                const float k0 = odd ? v2 : v0, k1 = odd ? v3 : v1;
+                const int row = i_base + a * 32 + qd * 8 + khalf * 4 + (odd ? 2 : 0);   // rows row, row + 1
+                float x[2][2] = {{odd ? r0 : k0, odd ? k0 : r0}, {odd ? r1 : k1, odd ? k1 : r1}};   // [row][pixel]
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr) {
+                    if (row + rr >= p.Co) continue;
+                    const int off = obase + (row + rr) * p.HoWo;
+                    if (has_bias) { const float bv = bias_lds[row + rr - i_tile0]; x[rr][0] += bv; x[rr][1] += bv; }
+                    if (relu) { x[rr][0] = x[rr][0] > 0.0f ? x[rr][0] : 0.0f; x[rr][1] = x[rr][1] > 0.0f ? x[rr][1] : 0.0f; }
+                    if (has_mask) {
+                        const uint32_t m = *reinterpret_cast<const uint32_t*>(mask + off);
+                        x[rr][0] = __uint_as_float(m << 16) > 0.0f ? x[rr][0] : 0.0f;
+                        x[rr][1] = __uint_as_float(m & 0xffff0000u) > 0.0f ? x[rr][1] : 0.0f;
+                    }
+                    if (has_beta) {
+                        const uint32_t o = *reinterpret_cast<const uint32_t*>(out + off);
+                        x[rr][0] += __uint_as_float(o << 16);
+                        x[rr][1] += __uint_as_float(o & 0xffff0000u);
+                    }
+                    *reinterpret_cast<uint32_t*>(out + off) = pack_bf16(x[rr][0], x[rr][1]);
+                }
+            }
+        }
+    }
+}
+
+// ROUNDS: patch fill tasks (8 channels x 8 pixels each) per thread and channel group.
+template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int ROUNDS>
+__global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParams p, const PatchGeom q) {
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = WM * TM * 32;
+    constexpr int BN = WN * TN * 32;
+    static_assert(NT == 256, "four wavefronts");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* bias_s = reinterpret_cast<float*>(smem);                 // [BM]
+    unsigned char* As = smem + BM * 4;                              // [taps per stage][BM] rows of PITCH bytes
+    unsigned char* patch = As + q.a_bytes;                          // [pr_max * pw] pixels of PITCH bytes
+
+    const uint16_t* __restrict__ in = (const uint16_t*)p.in;
+    const uint16_t* __restrict__ wt = (const uint16_t*)p.wt;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int tile = xcd_tile(blockIdx.x, p.tiles_i * p.tiles_pix);
+    const int i0 = (tile % p.tiles_i) * BM;
+    const int tp = tile / p.tiles_i;
+    const int n = fastdiv(tp, q.div_tpi);
+    const int pix0 = (tp - n * q.tiles_per_img) * BN;          // first pixel of the tile inside image n
+    const int pix_end = min(pix0 + BN, p.HoWo);
+    const int ho_first = fastdiv(pix0, p.div_wo);
+    const int h_lo = ho_first + q.h_lo_add;
+
+    // ---- patch fill tasks of this thread: (patch row, 8-channel half of the group, 8-pixel packet)
+    unsigned g_voff[ROUNDS];   // byte offset of the packet in the half's first channel of group 0 (2^31: row outside the image)
+    int l_off[ROUNDS];         // byte offset of its first pixel in the patch; a thread without a task in this
+    int l_step[ROUNDS];        // round parks its packets in the padding of patch pixel 0 (step 0), which nobody
+    int cg8[ROUNDS];           // reads: no branch around the stores
+    const int tasks_per_row = q.chunks * (GC / 8);
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+        const int t = tid + r * NT;
+        const int pr = fastdiv(t, q.div_tpr);
+        const int u = t - pr * tasks_per_row;
+        const int cg = fastdiv(u, q.div_chunks);
+        const int chunk = u - cg * q.chunks;
+        const bool live = pr < q.pr_max;
+        const int hi = h_lo + pr;
+        const bool row_ok = live & ((unsigned)hi < (unsigned)p.Hi);
+        g_voff[r] = row_ok ? (unsigned)(n * p.in_ns + cg * 8 * p.HiWi + hi * p.Wi + chunk * 8) * 2u : 0x80000000u;
+        l_off[r] = live ? (pr * q.pw + chunk * 8 - q.w_lo) * PITCH + cg * 16 : GC * 2;
+        l_step[r] = live ? PITCH : 0;
+        cg8[r] = cg * 8;
+    }
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(in), (short)0, (int)p.in_bytes, 0x00020000);
+
+    u32x4 pre[ROUNDS][8];      // the packets of the next channel group, as loaded (channel-major)
+    auto load_patch = [&](int c0) {
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const unsigned v = (c0 + cg8[r] < p.Ci) ? g_voff[r] : 0x80000000u;   // padding channels read as zeros
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                pre[r][e] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, v, (c0 + e) * p.HiWi * 2, 0);
+        }
+    };
+    auto store_patch = [&]() {
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+#pragma unroll
+            for (int px = 0; px < 8; ++px) {
+                // pixel px of the packet: channel pairs (0,1) (2,3) (4,5) (6,7), low or high halves of dword px/2
+                const unsigned sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 o;
+#pragma unroll
+                for (int c2 = 0; c2 < 4; ++c2)
+                    o[c2] = __builtin_amdgcn_perm(pre[r][2 * c2 + 1][px >> 1], pre[r][2 * c2][px >> 1], sel);
+                *reinterpret_cast<u32x4*>(patch + l_off[r] + px * l_step[r]) = o;
+            }
+        }
+    };
+
+    // ---- filter pieces served by this thread: piece f of a stage = (tap of the stage, row, 8-channel half).
+    // Source offsets are relative to the stage's first tap in A[group][tap][i_pad][16].
+    const int n_taps = p.Rt * p.St;
+    const int n_groups = p.Ci_pad / GC;
+    const int tc = q.taps_per_stage;
+    const int n_chunks = (n_taps + tc - 1) / tc;
+    const int n_stages = n_groups * n_chunks;
+    int a_src[A_ROUNDS], a_dst[A_ROUNDS];
+#pragma unroll
+    for (int it = 0; it < A_ROUNDS; ++it) {
+        const int f = tid + it * NT;
+        const int tap = f / (BM * 2), rem = f - tap * (BM * 2);
+        const int row = rem >> 1, half = rem & 1;
+        const bool live = tap < tc;
+        a_src[it] = live ? (tap * p.i_pad + i0 + row) * GC + half * 8 : -1;
+        a_dst[it] = live ? (tap * BM + row) * PITCH + half * 16 : GC * 2;     // parked in the padding of row 0
+    }
+    u32x4 a_reg[A_ROUNDS];
+    auto load_a = [&](int group, int t0, int nt) {
+        const int base = (group * n_taps + t0) * p.i_pad * GC;
+        const int limit = nt * p.i_pad * GC;                    // taps past the stage's last one re-read piece 0
+#pragma unroll
+        for (int it = 0; it < A_ROUNDS; ++it) {
+            if (it >= q.a_rounds) break;                        // uniform: rounds this tile shape never needs
+            const int off = (a_src[it] >= 0 && a_src[it] < limit) ? a_src[it] : 0;
+            a_reg[it] = *reinterpret_cast<const u32x4*>(wt + base + off);
+        }
+    };
+    auto store_a = [&]() {
+#pragma unroll
+        for (int it = 0; it < A_ROUNDS; ++it) {
+            if (it >= q.a_rounds) break;
+            *reinterpret_cast<u32x4*>(As + a_dst[it]) = a_reg[it];
+        }
+    };
+
+    // ---- this lane's B-fragment positions (byte offsets into the patch at tap (0,0)); columns past the
+    // tile's last pixel re-read that pixel (their results are never stored)
+    int b_pos[TN];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int pix = min(pix0 + wn * TN * 32 + b * 32 + (lane & 31), pix_end - 1);
+        const int ho = fastdiv(pix, p.div_wo);
+        const int wo = pix - ho * p.Wo;
+        b_pos[b] = ((ho - ho_first) * q.pw + wo + q.pos_add) * PITCH + (lane >> 5) * 16;
+    }
+    const int a_row = (wm * TM * 32 + (lane & 31)) * PITCH + (lane >> 5) * 16;
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+
+    // ---- prologue: first stage's loads, halo columns to zero
+    load_patch(0);
+    load_a(0, 0, min(tc, n_taps));
+    {
+        const int halo_w = q.halo_l + q.pw - q.halo_r0;        // halo columns per patch row
+        const int total = q.pr_max * halo_w * (GC / 8);
+        for (int i = tid; i < total; i += NT) {
+            const int half = i & 1;
+            const int hp = i >> 1;
+            const int pr = fastdiv(hp, q.div_halo);
+            const int hc = hp - pr * halo_w;
+            const int pc = hc < q.halo_l ? hc : q.halo_r0 + (hc - q.halo_l);
+            const u32x4 z = {0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4*>(patch + (pr * q.pw + pc) * PITCH + half * 16) = z;
+        }
+    }
+    if (FUSED) stage_bias<uint16_t, BM, NT>(bias_s, p, i0, tid);
+
+    int group = 0, chunk = 0;
+    for (int stage = 0; stage < n_stages; ++stage) {
+        // the barrier that ended the previous stage: nobody reads the filter rows or the patch any more
+        if (chunk == 0) store_patch();
+        store_a();
+        __syncthreads();
+        const int t0 = chunk * tc;
+        const int nt = min(tc, n_taps - t0);
+        // next stage's loads fly during this stage's MFMAs
+        int nx_group = group, nx_chunk = chunk + 1;
+        if (nx_chunk >= n_chunks) { nx_chunk = 0; nx_group += 1; }
+        if (stage + 1 < n_stages) {
+            if (nx_chunk == 0) load_patch(nx_group * GC);
+            load_a(nx_group, nx_chunk * tc, min(tc, n_taps - nx_chunk * tc));
+        }
+        int tap_r = fastdiv(t0, q.div_st);
+        int tap_s = t0 - tap_r * p.St;
+        const unsigned char* asrc = As + a_row;
+        for (int tap = 0; tap < nt; ++tap) {
+            const int tap_off = (tap_r * q.pw + tap_s) * PITCH;
+            const unsigned char* bsrc = patch + (MINUS ? -tap_off : tap_off);
+            bf16x8 av[TM], bv[TN];
+#pragma unroll
+            for (int a = 0; a < TM; ++a) av[a] = *reinterpret_cast<const bf16x8*>(asrc + a * 32 * PITCH);
+#pragma unroll
+            for (int b = 0; b < TN; ++b) bv[b] = *reinterpret_cast<const bf16x8*>(bsrc + b_pos[b]);
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
+            asrc += BM * PITCH;
+            tap_s += 1;
+            const bool wrap = tap_s >= p.St;
+            tap_s = wrap ? 0 : tap_s;
+            tap_r += wrap ? 1 : 0;
+        }
+        __syncthreads();
+        group = nx_group;
+        chunk = nx_chunk;
+    }
+
+    if (!D2S && q.pairs) {
+        store_pairs<FUSED, TM, TN, !MINUS>(p, acc, i0 + wm * TM * 32, n, pix0 + wn * TN * 32 + (lane & 31), pix_end, lane,
+                                           bias_s, i0);
+        return;
+    }
+    store_tile<uint16_t, D2S, FUSED, TM, TN, !MINUS>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
+                                                     n * p.HoWo + pix0 + wn * TN * 32 + (lane & 31), lane >> 5,
+                                                     bias_s, i0, n * p.HoWo + pix_end);
+}
+
+// Filter copy for the kernel above: A[group][tap][i_pad][16] with
+//   mode 0 (forward)        : tap = (r, s),   ci = c, i = k
+//   mode 1 (bwd, stride 1)  : tap = (r, s),   ci = k, i = c
+//   mode 2 (bwd, strided)   : tap = (r', s'), ci = k, i = (c, a, b) -> w[k, c, a + sh*r', b + sw*s']
+// zero beyond the last row / channel and for folded taps that fall outside the filter.
+struct GroupRepack {
+    const uint16_t* w; uint16_t* a;
+    int mode, K, C, R, S, sh, sw, St, n_taps, Ci, Co, i_pad, total;
+};
+__global__ __launch_bounds__(256) void repack_groups_kernel(const GroupRepack g) {
+    for (int o = blockIdx.x * 256 + threadIdx.x; o < g.total; o += gridDim.x * 256) {
+        const int cl = o & (GC - 1);
+        int t = o >> 4;
+        const int i = t % g.i_pad;
+        t /= g.i_pad;
+        const int tap = t % g.n_taps;
+        const int ci = (t / g.n_taps) * GC + cl;
+        const int tr = tap / g.St, ts = tap - tr * g.St;
+        uint16_t v = 0;
+        if (i < g.Co && ci < g.Ci) {
+            int k, c, r, s;
+            if (g.mode == 0) { k = i; c = ci; r = tr; s = ts; }
+            else if (g.mode == 1) { k = ci; c = i; r = tr; s = ts; }
+            else {
+                const int ph = g.sh * g.sw;
+                c = i / ph;
+                const int ab = i - c * ph;
+                const int pa = ab / g.sw, pb = ab - pa * g.sw;
+                k = ci; r = pa + g.sh * tr; s = pb + g.sw * ts;
+            }
+            if (r < g.R && s < g.S) v = g.w[((k * g.C + c) * g.R + r) * g.S + s];
+        }
+        g.a[o] = v;
+    }
+}
+
+template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int ROUNDS>
+hipError_t launch_one(const PixParams& p, const PatchGeom& q, hipStream_t st) {
+    auto kern = igemm_patch_bf16_kernel<MINUS, D2S, FUSED, TM, TN, WM, WN, ROUNDS>;
+    const long long total = (long long)p.tiles_i * p.tiles_pix;
+    if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (q.lds_bytes > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)q.lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    ProbeScope probe(st);
+    (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
+    hipLaunchKernelGGL(kern, dim3((unsigned)total), dim3(256), (size_t)q.lds_bytes, st, p, q);
+    return hipGetLastError();
+}
+
+template <bool MINUS, bool D2S, bool FUSED>
+hipError_t by_tile(const PixParams& p, const PatchGeom& q, hipStream_t st) {
+#define PATCH_CALL(TM, TN, WM, WN)                                                     \
+    (q.rounds == 1 ? launch_one<MINUS, D2S, FUSED, TM, TN, WM, WN, 1>(p, q, st)          \
+                   : launch_one<MINUS, D2S, FUSED, TM, TN, WM, WN, 2>(p, q, st))
+    switch (q.bm * 1000 + q.bn) {
+        case 128128: return PATCH_CALL(2, 2, 2, 2);
+        case 96256:  return PATCH_CALL(3, 2, 1, 4);
+        case 64256:  return PATCH_CALL(2, 2, 1, 4);
+        case 32256:  return PATCH_CALL(1, 2, 1, 4);
+        default: return hipErrorInvalidValue;
+    }
+#undef PATCH_CALL
+}
+
+template <bool MINUS, bool D2S>
+hipError_t by_epilogue(const PixParams& p, const PatchGeom& q, hipStream_t st) {
+    const bool fused = p.bias || p.relu || p.mask;
+    return fused ? by_tile<MINUS, D2S, true>(p, q, st) : by_tile<MINUS, D2S, false>(p, q, st);
+}
+
+}  // namespace
+
+// p: the pass's geometry as the tap-major kernel gets it (Ci, Co, Rt, St, gather origin, extents).
+// On success p.Ci_pad / p.i_pad / p.tiles_i / p.tiles_pix / p.in_bytes describe this kernel's launch
+// and q its patch; the caller repacks the filter (repack_patch_filter) into scratch of at least
+// patch_filter_bytes and launches. mode: 0 forward, 1 backward-data unit stride, 2 phase-folded.
+bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* qg) {
+    const bool minus = mode != 0;
+    if (p.g_mul_h != 1 || p.g_mul_w != 1) return false;
+    if ((p.Wi & 7) || (p.in_ns & 7) || (p.Ci & 7)) return false;
+    if ((((uintptr_t)p.in) & 15u) != 0) return false;
+    const long long in_bytes = ((long long)(p.N - 1) * p.in_ns + (long long)p.Ci * p.HiWi) * 2;
+    if (in_bytes >= 0x7fffffffLL) return false;
+    // row tile: least padded channel count, the larger tile on ties
+    const int cand[4][2] = {{128, 128}, {96, 256}, {64, 256}, {32, 256}};
+    PatchGeom q{};
+    long long best = -1;
+    for (const auto& c : cand) {
+        const long long padded = (long long)((p.Co + c[0] - 1) / c[0]) * c[0];
+        if (best < 0 || padded < best) { best = padded; q.bm = c[0]; q.bn = c[1]; }
+    }
+    const int n_taps = p.Rt * p.St;
+    q.pw = p.Wo + p.St - 1;
+    const int rows_spanned = (q.bn - 2) / p.Wo + 2;
+    q.pr_max = (rows_spanned < p.Ho ? rows_spanned : p.Ho) + p.Rt - 1;
+    q.w_lo = p.g_add_w - (minus ? p.St - 1 : 0);
+    q.h_lo_add = p.g_add_h - (minus ? p.Rt - 1 : 0);
+    q.pos_add = minus ? (p.Rt - 1) * q.pw + (p.St - 1) : 0;
+    q.chunks = p.Wi / 8;
+    q.halo_l = -q.w_lo;
+    q.halo_r0 = p.Wi - q.w_lo;
+    if (q.halo_l < 0 || q.halo_r0 > q.pw) return false;       // image columns outside the patch
+    const long long tasks = (long long)q.pr_max * q.chunks * (GC / 8);
+    if (tasks > 2 * 256) return false;
+    q.rounds = tasks > 256 ? 2 : 1;
+    // taps per stage: as many as the thread's filter registers and 80 KB of LDS (two workgroups per
+    // CU) allow; whole filter rows when a stage cannot hold every tap
+    const long long patch_bytes = (long long)q.pr_max * q.pw * PITCH;
+    const long long fixed = (long long)q.bm * 4 + patch_bytes;
+    long long tc = (long long)A_ROUNDS * 256 / (q.bm * 2);
+    const long long by_lds = (80 * 1024 - fixed) / ((long long)q.bm * PITCH);
+    if (by_lds < tc) tc = by_lds;
+    if (tc > n_taps) tc = n_taps;
+    if (tc < 1) return false;
+    if (tc < n_taps && tc > p.St) tc = tc / p.St * p.St;
+    q.taps_per_stage = (int)tc;
+    q.a_rounds = (int)((tc * q.bm * 2 + 255) / 256);
+    q.a_bytes = (int)(tc * q.bm * PITCH);
+    q.lds_bytes = (int)(fixed + q.a_bytes);
+    q.tiles_per_img = (p.HoWo + q.bn - 1) / q.bn;
+    q.div_tpi = make_fastdiv(q.tiles_per_img);
+    q.div_tpr = make_fastdiv(q.chunks * (GC / 8));
+    q.div_chunks = make_fastdiv(q.chunks);
+    q.div_st = make_fastdiv(p.St);
+    const int halo_w = q.halo_l + q.pw - q.halo_r0;
+    q.div_halo = make_fastdiv(halo_w > 0 ? halo_w : 1);
+    const long long tiles_pix = (long long)p.N * q.tiles_per_img;
+    if (tiles_pix > 0x7fffffffLL) return false;
+    p.tiles_i = (p.Co + q.bm - 1) / q.bm;
+    p.tiles_pix = (int)tiles_pix;
+    p.i_pad = p.tiles_i * q.bm;
+    p.Ci_pad = (p.Ci + GC - 1) / GC * GC;
+    if ((long long)n_taps * p.i_pad * p.Ci_pad > 0x7fffffffLL) return false;
+    p.in_bytes = (unsigned)in_bytes;
+    // 4-byte stores of pixel pairs: every row of every image starts at an even element
+    q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out | (uintptr_t)p.mask) & 3u) == 0;
+    *qg = q;
+    return true;
+}
+
+// bytes of the repacked filter for a layer with Co output rows, Ci gathered channels and n_taps taps,
+// whatever row tile ends up running
+size_t patch_filter_bytes(int Co, int Ci, int n_taps) {
+    const long long i_pad = ((long long)Co + 127) / 128 * 128;   // the row tile picked never pads further than 128-row tiles
+    return (size_t)n_taps * (size_t)i_pad * (size_t)((Ci + GC - 1) / GC * GC) * 2;
+}
+
+hipError_t repack_patch_filter(const PixParams& p, int mode, const void* w, void* a, int K, int C, hipStream_t st) {
+    GroupRepack g{};
+    g.w = (const uint16_t*)w; g.a = (uint16_t*)a;
+    g.mode = mode; g.K = K; g.C = C; g.R = p.R; g.S = p.S; g.sh = p.sh; g.sw = p.sw;
+    g.St = p.St; g.n_taps = p.Rt * p.St; g.Ci = p.Ci; g.Co = p.Co; g.i_pad = p.i_pad;
+    g.total = g.n_taps * p.i_pad * p.Ci_pad;
+    const long long blocks = ((long long)g.total + 255) / 256;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(repack_groups_kernel, dim3((unsigned)(blocks > 4096 ? 4096 : blocks)), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+hipError_t launch_patch_bf16(const PixParams& p, const PatchGeom& q, int mode, hipStream_t st) {
+    if (mode == 0) return by_epilogue<false, false>(p, q, st);
+    if (mode == 1) return by_epilogue<true, false>(p, q, st);
+    return by_epilogue<true, true>(p, q, st);
+}
+
+}  // namespace pix
+}  // namespace purine

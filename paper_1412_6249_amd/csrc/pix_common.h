@@ -91,7 +91,9 @@ __device__ __forceinline__ void stage_bias(float* bias_lds, const PixParams& p, 
         for (int r = tid; r < BM; r += NT) bias_lds[r] = i0 + r < p.Co ? Elem<T>::load(bias, i0 + r) : 0.0f;
 }
 
-// Epilogue shared by the kernels. Accumulator register e of a 32x32 tile holds row
+// Epilogue shared by the kernels (pix_limit: columns at or past this pixel index are not stored;
+// kernels whose pixel tiles stop at image boundaries pass the end of their image).
+// Accumulator register e of a 32x32 tile holds row
 // (e/4)*8 + (lane/32)*4 + e%4, column lane%32. Optional pieces (bias, ReLU, ReLU-gradient mask,
 // accumulate) are uniform branches; what an element needs from memory (mask value, old output) is
 // fetched for a batch of rows of one MFMA tile BEFORE their stores, so the loads overlap instead of
@@ -138,7 +140,8 @@ struct TileAddr {
 template <typename T, bool D2S, bool FUSED, int TM, int TN, bool FWD>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
-                                           int khalf, const float* bias_lds, int i_tile0) {
+                                           int khalf, const float* bias_lds, int i_tile0,
+                                           int pix_limit = 0x7fffffff) {
     if (!FUSED || FWD) {
         // Plain store (backward-data: optionally accumulating) and the fused forward epilogue, which
         // needs nothing from global memory (bias comes from LDS): no staging arrays, so these
@@ -148,7 +151,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
             const int pix = pix_base + b * 32;
-            if (pix >= p.M) continue;
+            if (pix >= p.M || pix >= pix_limit) continue;
             const int n = fastdiv(pix, p.div_howo);
             const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
 #pragma unroll
@@ -190,7 +193,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int pix = pix_base + b * 32;
-        if (pix >= p.M) continue;
+        if (pix >= p.M || pix >= pix_limit) continue;
         const int n = fastdiv(pix, p.div_howo);
         const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
 #pragma unroll
@@ -329,6 +332,33 @@ hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t
 hipError_t blockify_input(PixParams& p, void* blocked, hipStream_t st);
 // single-tap bf16 layers (mode 0 or 1): no blocked copy, 2-byte gathers from NCHW
 hipError_t dispatch_tap_bf16_nchw(PixParams& p, int mode, int bm, int bn, hipStream_t st);
+// bf16 layers whose gather has unit stride and whose gathered rows are whole 16-byte packets: the
+// haloed input patch of a pixel tile is staged in LDS once per 16-channel group and every tap
+// reads it there (conv_patch_bf16.hip). plan_patch_bf16 answers whether the layer qualifies (pure
+// host arithmetic on p's geometry) and, if so, sets p.Ci_pad / p.i_pad / p.tiles_i / p.tiles_pix /
+// p.in_bytes for the tile it picked; the caller then repacks the filter into scratch of at least
+// patch_filter_bytes (repack_patch_filter) and launches.
+// mode: 0 forward, 1 backward-data with unit stride, 2 backward-data phase-folded.
+struct PatchGeom {
+    int bm, bn, rounds;  // tile extents; patch fill tasks per thread and channel group
+    int tiles_per_img;   // pixel tiles per image (a tile never straddles two images)
+    int pw;              // patch columns: Wo + St - 1
+    int pr_max;          // patch rows held in LDS
+    int w_lo;            // input column of patch column 0 (<= 0)
+    int h_lo_add;        // input row of patch row 0 = first output row of the tile + h_lo_add
+    int pos_add;         // backward walk: (Rt-1)*pw + (St-1), else 0
+    int chunks;          // 16-byte packets per input row: Wi / 8
+    int halo_l, halo_r0; // patch columns [0, halo_l) and [halo_r0, pw) lie outside the image
+    int taps_per_stage;  // taps whose filter rows sit in LDS together
+    int a_rounds;        // 16-byte filter pieces per thread and stage
+    int pairs;           // NCHW output written as 4-byte pixel pairs
+    int a_bytes, lds_bytes;
+    FastDiv div_tpi, div_tpr, div_chunks, div_halo, div_st;
+};
+bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* q);
+size_t patch_filter_bytes(int Co, int Ci, int n_taps);
+hipError_t repack_patch_filter(const PixParams& p, int mode, const void* w, void* a, int K, int C, hipStream_t st);
+hipError_t launch_patch_bf16(const PixParams& p, const PatchGeom& q, int mode, hipStream_t st);
 // bf16 MFMA forward with a flattened (c,r,s) reduction (fewer than 16 input channels)
 hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st);
 // streaming GEMM for 1x1 / stride 1 / unpadded layers (conv_gemm1x1.hip); p.wt is the KCRS filter

@@ -49,6 +49,17 @@ CASES = [
     # K % 4 != 0 with K*C*R*S % 4 == 0 and 64 splits of the pixel reduction: dw's partials are added
     # by the same kernel with and without the fused bias gradient (whose rows are not 16-byte aligned)
     ("k6_many_splits", 4, 2, 64, 64, 6, 3, 3, (1, 1), (1, 1)),
+    # bf16: gathered rows of whole 16-byte packets and a unit-stride gather take the kernel that stages
+    # the input patch in LDS (forward when W % 8 == 0 and C % 8 == 0, backward-data when Q and K are):
+    # every row-tile shape (12, 40, 90, 100, 192 output rows), one and two fill rounds, tiles that end
+    # inside an image row, images smaller than a tile, pads 0..2, channel counts that are not multiples of 32
+    ("patch_c24_k40", 2, 24, 16, 24, 40, 3, 3, (1, 1), (1, 1)),
+    ("patch_c64_k192_5x3", 3, 64, 9, 32, 192, 5, 3, (1, 1), (2, 1)),
+    ("patch_c40_k104_wide", 1, 40, 7, 112, 104, 3, 3, (1, 1), (1, 1)),
+    ("patch_c16_k90_nopad", 2, 16, 20, 24, 90, 3, 3, (1, 1), (0, 0)),
+    ("patch_bwd_folded_s2", 2, 3, 32, 32, 32, 7, 7, (2, 2), (3, 3)),
+    ("patch_bwd_folded_s2_k72", 3, 12, 31, 32, 72, 3, 4, (2, 2), (1, 1)),
+    ("patch_c96_k96_56", 2, 96, 56, 56, 96, 3, 3, (1, 1), (1, 1)),
 ]
 PW = [c for c in CASES if c[0].startswith("pw_")]
 
