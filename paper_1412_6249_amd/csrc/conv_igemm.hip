@@ -692,6 +692,10 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     if (pad192 > i_pad_max) i_pad_max = pad192;
     pl.ws_bytes = flat_copy ? (size_t)pl.Ci_pad * (size_t)i_pad_max * elem
                   : pl.flat ? 0 : (size_t)pl.Rt * pl.St * pl.Ci_pad * (size_t)i_pad_max * elem;
+    if (flat_copy) {   // the row-staging kernel's filter copy can be the larger one (short filter rows)
+        const size_t rows_bytes = rows_filter_bytes(g.K, g.C, g.R, g.S);
+        if (rows_bytes > pl.ws_bytes) pl.ws_bytes = rows_bytes;
+    }
     pl.blk_offset = 0;
     pl.patch = false;
     if (dtype == PURINE_BF16 && !pl.flat && pl.Rt * pl.St > 1 && g_force_bm != -2) {
@@ -751,6 +755,16 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
             q.wt = wt;
             q.tiles_i = pl.gemm_tiles_i; q.tiles_pix = pl.gemm_tiles_pix;
             return dispatch_gemm1x1(q, dtype, pl.mode == 1, pl.gemm_tm, pl.gemm_tn, st);
+        }
+    }
+    if (pl.flat && dtype == PURINE_BF16 && g_force_bm != -2) {
+        // input rows staged in LDS (rows of whole 16-byte packets); otherwise the flattened gather below
+        RowsGeom rq;
+        PixParams pr = p;
+        if (plan_rows_bf16(pr, &rq)) {
+            if (!ws) return hipErrorInvalidValue;
+            ProbeScope whole_op(st, true);
+            return launch_rows_bf16(pr, rq, wt, ws, st);
         }
     }
     if (pl.flat && dtype == PURINE_BF16) {

@@ -34,73 +34,6 @@ constexpr int PITCH = GC * 2 + 16;  // LDS bytes per pixel (patch) or filter row
                                     // so that the 16-byte fragment reads of 8 consecutive rows cover all banks
 constexpr int A_ROUNDS = 8;         // 16-byte filter pieces per thread and stage, at most
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-
-// Two fp32 values to two bf16 (round to nearest even) in one dword, first value in the low half.
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    const floatx2 f = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-}
-__device__ __forceinline__ float swap_with_neighbour(float v) {   // value of lane ^ 1 (quad permute 1,0,3,2)
-    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
-}
-
-// Epilogue for NCHW outputs whose pixel pairs (2j, 2j+1) are 4-byte aligned (even HoWo and image
-// distance; pixel tiles start at even pixels). An accumulator quad holds four consecutive rows of
-// ONE pixel per lane; neighbouring lanes hold neighbouring pixels. The even lane of a pair hands
-// rows 2,3 to its neighbour and takes the neighbour's rows 0,1 (two DPP moves), so every lane ends
-// up with two rows x two adjacent pixels: two 4-byte stores (and mask / old-value loads) per quad
-// instead of four 2-byte ones, and the fp32 -> bf16 conversion is the packed hardware one.
-template <bool FUSED, int TM, int TN, bool FWD>
-__device__ __forceinline__ void store_pairs(const PixParams& p, floatx16 (&acc)[TM][TN], int i_base, int n,
-                                            int pix_base, int pix_end, int lane, const float* bias_lds, int i_tile0) {
-    uint16_t* __restrict__ out = (uint16_t*)p.out;
-    const uint16_t* __restrict__ mask = (const uint16_t*)p.mask;
-    const bool has_bias = FUSED && FWD && p.bias != nullptr, relu = FUSED && FWD && p.relu;
-    const bool has_mask = FUSED && !FWD && mask != nullptr, has_beta = !FWD && p.beta != 0.0f;
-    const bool odd = lane & 1;
-    const int khalf = lane >> 5;
-#pragma unroll
-    for (int b = 0; b < TN; ++b) {
-        const int pix = pix_base + b * 32;                 // this lane's pixel inside the image
-        const int pair = pix & ~1;
-        if (pair >= pix_end) continue;
-        const int obase = n * p.out_ns + pair;
-#pragma unroll
-        for (int a = 0; a < TM; ++a) {
-#pragma unroll
-            for (int qd = 0; qd < 4; ++qd) {
-                const float v0 = acc[a][b][qd * 4 + 0], v1 = acc[a][b][qd * 4 + 1];
-                const float v2 = acc[a][b][qd * 4 + 2], v3 = acc[a][b][qd * 4 + 3];
-                const float r0 = swap_with_neighbour(odd ? v0 : v2);
-                const float r1 = swap_with_neighbour(odd ? v1 : v3);
-                const float k0 = odd ? v2 : v0, k1 = odd ? v3 : v1;
-                const int row = i_base + a * 32 + qd * 8 + khalf * 4 + (odd ? 2 : 0);   // rows row, row + 1
-                float x[2][2] = {{odd ? r0 : k0, odd ? k0 : r0}, {odd ? r1 : k1, odd ? k1 : r1}};   // [row][pixel]
-#pragma unroll
-                for (int rr = 0; rr < 2; ++rr) {
-                    if (row + rr >= p.Co) continue;
-                    const int off = obase + (row + rr) * p.HoWo;
-                    if (has_bias) { const float bv = bias_lds[row + rr - i_tile0]; x[rr][0] += bv; x[rr][1] += bv; }
-                    if (relu) { x[rr][0] = x[rr][0] > 0.0f ? x[rr][0] : 0.0f; x[rr][1] = x[rr][1] > 0.0f ? x[rr][1] : 0.0f; }
-                    if (has_mask) {
-                        const uint32_t m = *reinterpret_cast<const uint32_t*>(mask + off);
-                        x[rr][0] = __uint_as_float(m << 16) > 0.0f ? x[rr][0] : 0.0f;
-                        x[rr][1] = __uint_as_float(m & 0xffff0000u) > 0.0f ? x[rr][1] : 0.0f;
-                    }
-                    if (has_beta) {
-                        const uint32_t o = *reinterpret_cast<const uint32_t*>(out + off);
-                        x[rr][0] += __uint_as_float(o << 16);
-                        x[rr][1] += __uint_as_float(o & 0xffff0000u);
-                    }
-                    *reinterpret_cast<uint32_t*>(out + off) = pack_bf16(x[rr][0], x[rr][1]);
-                }
-            }
-        }
-    }
-}
-
 // ROUNDS: patch fill tasks (8 channels x 8 pixels each) per thread and channel group.
 template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int ROUNDS>
 __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParams p, const PatchGeom q) {
@@ -222,7 +155,7 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
     int b_pos[TN];
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
-        const int pix = min(pix0 + wn * TN * 32 + b * 32 + (lane & 31), pix_end - 1);
+        const int pix = min(pix0 + wn * TN * 32 + TN * (lane & 31) + b, pix_end - 1);   // a lane's tiles: adjacent pixels
         const int ho = fastdiv(pix, p.div_wo);
         const int wo = pix - ho * p.Wo;
         b_pos[b] = ((ho - ho_first) * q.pw + wo + q.pos_add) * PITCH + (lane >> 5) * 16;
@@ -298,13 +231,13 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
     }
 
     if (!D2S && q.pairs) {
-        store_pairs<FUSED, TM, TN, !MINUS>(p, acc, i0 + wm * TM * 32, n, pix0 + wn * TN * 32 + (lane & 31), pix_end, lane,
-                                           bias_s, i0);
+        store_adjacent<FUSED, TM, TN, !MINUS>(p, acc, i0 + wm * TM * 32, n, pix0 + wn * TN * 32 + TN * (lane & 31), pix_end,
+                                              lane, bias_s, i0);
         return;
     }
     store_tile<uint16_t, D2S, FUSED, TM, TN, !MINUS>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
-                                                     n * p.HoWo + pix0 + wn * TN * 32 + (lane & 31), lane >> 5,
-                                                     bias_s, i0, n * p.HoWo + pix_end);
+                                                     n * p.HoWo + pix0 + wn * TN * 32 + TN * (lane & 31), lane >> 5,
+                                                     bias_s, i0, n * p.HoWo + pix_end, 1);
 }
 
 // Filter copy for the kernel above: A[group][tap][i_pad][16] with

@@ -92,7 +92,8 @@ __device__ __forceinline__ void stage_bias(float* bias_lds, const PixParams& p, 
 }
 
 // Epilogue shared by the kernels (pix_limit: columns at or past this pixel index are not stored;
-// kernels whose pixel tiles stop at image boundaries pass the end of their image).
+// kernels whose pixel tiles stop at image boundaries pass the end of their image. bstep: distance in
+// pixels between a lane's consecutive column tiles: 32, or 1 for kernels that give a lane adjacent pixels).
 // Accumulator register e of a 32x32 tile holds row
 // (e/4)*8 + (lane/32)*4 + e%4, column lane%32. Optional pieces (bias, ReLU, ReLU-gradient mask,
 // accumulate) are uniform branches; what an element needs from memory (mask value, old output) is
@@ -141,7 +142,7 @@ template <typename T, bool D2S, bool FUSED, int TM, int TN, bool FWD>
 __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ out,
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
                                            int khalf, const float* bias_lds, int i_tile0,
-                                           int pix_limit = 0x7fffffff) {
+                                           int pix_limit = 0x7fffffff, int bstep = 32) {
     if (!FUSED || FWD) {
         // Plain store (backward-data: optionally accumulating) and the fused forward epilogue, which
         // needs nothing from global memory (bias comes from LDS): no staging arrays, so these
@@ -150,7 +151,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
         constexpr bool QUAD = sizeof(T) == 2;   // bf16: bias of four consecutive rows as one 16-byte LDS read
 #pragma unroll
         for (int b = 0; b < TN; ++b) {
-            const int pix = pix_base + b * 32;
+            const int pix = pix_base + b * bstep;
             if (pix >= p.M || pix >= pix_limit) continue;
             const int n = fastdiv(pix, p.div_howo);
             const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
@@ -192,7 +193,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     constexpr bool QUAD_BIAS = sizeof(T) == 2;
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
-        const int pix = pix_base + b * 32;
+        const int pix = pix_base + b * bstep;
         if (pix >= p.M || pix >= pix_limit) continue;
         const int n = fastdiv(pix, p.div_howo);
         const TileAddr<T, D2S> addr(p, n, pix - n * p.HoWo);
@@ -299,6 +300,76 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     }
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values to two bf16 (round to nearest even) in one dword, first value in the low half.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
+// Epilogue for kernels whose lanes own TN ADJACENT pixels (column tile b of lane l is pixel
+// TN * (l % 32) + b of the wavefront's strip) and NCHW bf16 outputs in which such a run is aligned
+// (HoWo and the image distance multiples of TN): a lane writes its TN pixels of one row as one 4- or
+// 8-byte packet, so the 32 lanes of a half-wavefront cover 32 * TN consecutive pixels of one row,
+// whole 128-byte lines, and the fp32 -> bf16 conversion is the packed hardware one. Mask and old
+// values are read the same way.
+template <bool FUSED, int TM, int TN, bool FWD>
+__device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&acc)[TM][TN], int i_base, int n,
+                                               int pix_first, int pix_end, int lane, const float* bias_lds,
+                                               int i_tile0) {
+    static_assert(TN == 2 || TN == 4, "4- or 8-byte packets");
+    typedef uint32_t packet_t __attribute__((ext_vector_type(TN / 2)));
+    uint16_t* __restrict__ out = (uint16_t*)p.out;
+    const uint16_t* __restrict__ mask = (const uint16_t*)p.mask;
+    const bool has_bias = FUSED && FWD && p.bias != nullptr, relu = FUSED && FWD && p.relu;
+    const bool has_mask = FUSED && !FWD && mask != nullptr, has_beta = !FWD && p.beta != 0.0f;
+    if (pix_first >= pix_end) return;
+    const int khalf = lane >> 5;
+    const int obase = n * p.out_ns + pix_first;
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
+            if (row >= p.Co) continue;
+            const int off = obase + row * p.HoWo;
+            float x[TN];
+#pragma unroll
+            for (int b = 0; b < TN; ++b) x[b] = acc[a][b][e];
+            if (has_bias) {
+                const float bv = bias_lds[row - i_tile0];
+#pragma unroll
+                for (int b = 0; b < TN; ++b) x[b] += bv;
+            }
+            if (relu) {
+#pragma unroll
+                for (int b = 0; b < TN; ++b) x[b] = x[b] > 0.0f ? x[b] : 0.0f;
+            }
+            if (has_mask) {
+                const packet_t m = *reinterpret_cast<const packet_t*>(mask + off);
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const uint32_t w = m[b >> 1];
+                    x[b] = __uint_as_float((b & 1) ? (w & 0xffff0000u) : (w << 16)) > 0.0f ? x[b] : 0.0f;
+                }
+            }
+            if (has_beta) {
+                const packet_t o = *reinterpret_cast<const packet_t*>(out + off);
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const uint32_t w = o[b >> 1];
+                    x[b] += __uint_as_float((b & 1) ? (w & 0xffff0000u) : (w << 16));
+                }
+            }
+            packet_t r;
+#pragma unroll
+            for (int b = 0; b < TN; b += 2) r[b >> 1] = pack_bf16(x[b], x[b + 1]);
+            *reinterpret_cast<packet_t*>(out + off) = r;
+        }
+    }
+}
+
 // Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). Give each
 // XCD a contiguous run of tiles so that neighbouring pixel tiles share halo rows in one L2.
 __device__ __forceinline__ int xcd_tile(int bid, int total) {
@@ -359,6 +430,23 @@ bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* q);
 size_t patch_filter_bytes(int Co, int Ci, int n_taps);
 hipError_t repack_patch_filter(const PixParams& p, int mode, const void* w, void* a, int K, int C, hipStream_t st);
 hipError_t launch_patch_bf16(const PixParams& p, const PatchGeom& q, int mode, hipStream_t st);
+// bf16 forward for layers with fewer than 16 input channels whose input rows are whole 16-byte
+// packets (conv_rows_bf16.hip): input rows staged in LDS in their natural layout, the reduction runs
+// over (c, r, block of 8 filter columns), persistent workgroups. plan_rows_bf16 answers whether the
+// layer qualifies and fills q (and p.tiles_i / p.i_pad / p.in_bytes); launch_rows_bf16 repacks the
+// filter into ws (rows_filter_bytes) and launches.
+struct RowsGeom {
+    int SB, n_blocks, n_steps;   // blocks of 8 filter columns per filter row; (c, r, block) count; MFMA steps (2 blocks each)
+    int origin, rowlen;          // element of an LDS row that holds input column 0; elements per LDS row
+    int pr_max;                  // input rows per channel held for one pixel tile
+    int chunks, fill_rounds;     // 16-byte packets per input row; packets per thread and tile
+    int a_pitch, lds_bytes;
+    int tiles_per_img, n_tiles, grid, pairs;
+    FastDiv div_tpi, div_chunks, div_pr;
+};
+bool plan_rows_bf16(PixParams& p, RowsGeom* q);
+size_t rows_filter_bytes(int K, int C, int R, int S);
+hipError_t launch_rows_bf16(const PixParams& p, const RowsGeom& q, const void* w, void* ws, hipStream_t st);
 // bf16 MFMA forward with a flattened (c,r,s) reduction (fewer than 16 input channels)
 hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st);
 // streaming GEMM for 1x1 / stride 1 / unpadded layers (conv_gemm1x1.hip); p.wt is the KCRS filter

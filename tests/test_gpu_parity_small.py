@@ -60,6 +60,14 @@ CASES = [
     ("patch_bwd_folded_s2", 2, 3, 32, 32, 32, 7, 7, (2, 2), (3, 3)),
     ("patch_bwd_folded_s2_k72", 3, 12, 31, 32, 72, 3, 4, (2, 2), (1, 1)),
     ("patch_c96_k96_56", 2, 96, 56, 56, 96, 3, 3, (1, 1), (1, 1)),
+    # bf16 forward with fewer than 16 input channels and rows of whole 16-byte packets: input rows
+    # staged in LDS, reduction over (c, r, block of 8 filter columns): strides 1..4, even and odd
+    # pads, filter rows of one and two blocks, two row tiles, several tiles per image
+    ("rows_s4_11x11_k96", 2, 3, 43, 48, 96, 11, 11, (4, 4), (0, 0)),
+    ("rows_s1_5x5", 2, 5, 12, 24, 20, 5, 5, (1, 1), (2, 2)),
+    ("rows_s3_3x5", 1, 4, 20, 32, 33, 3, 5, (3, 3), (1, 2)),
+    ("rows_9x9_pad4", 1, 2, 10, 16, 8, 9, 9, (1, 1), (4, 4)),
+    ("rows_s2_7x7_many_tiles", 3, 3, 64, 64, 64, 7, 7, (2, 2), (3, 3)),
 ]
 PW = [c for c in CASES if c[0].startswith("pw_")]
 
