@@ -85,6 +85,7 @@ bool buffer_loads_disabled();   // tuning hook: (anything, -1) given to force_pi
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and
 // for the launch.
 struct WgradPlan {
+    bool rows;         // bf16 3x3 layers: the row-staging kernel (one partial tile per persistent workgroup)
     bool tap;          // columns are the channels of one tap (C >= 64) instead of flattened (c,r,s)
     int c_tiles;
     int bm, bn;        // tile extents along k and along the columns
@@ -93,6 +94,9 @@ struct WgradPlan {
     size_t db_ws_bytes;   // bias-gradient partials of the fused operator, placed behind them
 };
 WgradPlan plan_wgrad(const ConvGeom& g, int dtype);
+bool wgrad_rows_bf16_applies(const ConvGeom& g, int* workers);
+hipError_t launch_wgrad_rows_bf16(const ConvGeom& g, int workers, const void* x, const void* dy, float* partials,
+                                  float* db_partials, hipStream_t st);
 inline size_t wgrad_db_offset(const WgradPlan& pl) { return (pl.ws_bytes + 255) & ~(size_t)255; }
 
 struct BiasBwdPlan {

@@ -751,6 +751,21 @@ hipError_t dispatch_f32(WgradParams& p, const WgradPlan& plan, hipStream_t st) {
 
 WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
     WgradPlan pl{};
+    {
+        // bf16 3x3 / stride 1 / pad 1 layers with rows of whole 16-byte packets: operands staged in
+        // LDS row by row, persistent workgroups (conv_wgrad_rows_bf16.hip); one partial tile per worker
+        int workers = 0;
+        if (dtype == PURINE_BF16 && !buffer_loads_disabled() && wgrad_rows_bf16_applies(g, &workers)) {
+            pl.rows = true;
+            pl.tap = true;          // partials are [split][tap][k][c], as in the per-tap mode
+            pl.splits = workers;
+            pl.bm = 64; pl.bn = 64; pl.tiles_i = (g.K + 63) / 64; pl.c_tiles = (g.C + 63) / 64; pl.tiles_j = 9 * pl.c_tiles;
+            pl.chunk = 0;
+            pl.ws_bytes = (size_t)workers * (size_t)g.K * (size_t)g.C * 9 * sizeof(float);
+            pl.db_ws_bytes = (size_t)workers * (size_t)g.K * sizeof(float);
+            return pl;
+        }
+    }
     const long long M = (long long)g.N * g.P * g.Q;
     const long long CRS = (long long)g.C * g.R * g.S;
     pl.tap = g.C >= 64;   // enough channels to fill the columns of a per-tap tile
@@ -850,7 +865,8 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     }
     hipError_t e;
     const bool vec = p.PQ % 32 == 0 && (((uintptr_t)dy) & 15u) == 0;
-    if (dtype == PURINE_F32) e = plan.tap ? dispatch_f32<true>(p, plan, st) : dispatch_f32<false>(p, plan, st);
+    if (plan.rows) e = launch_wgrad_rows_bf16(g, plan.splits, x, dy, (float*)ws, p.db_out, st);
+    else if (dtype == PURINE_F32) e = plan.tap ? dispatch_f32<true>(p, plan, st) : dispatch_f32<false>(p, plan, st);
     else if (plan.tap) e = vec ? dispatch_bf16<true, true>(p, plan, st) : dispatch_bf16<false, true>(p, plan, st);
     else e = vec ? dispatch_bf16<true, false>(p, plan, st) : dispatch_bf16<false, false>(p, plan, st);
     if (e != hipSuccess) return e;

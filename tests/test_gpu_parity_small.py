@@ -68,6 +68,13 @@ CASES = [
     ("rows_s3_3x5", 1, 4, 20, 32, 33, 3, 5, (3, 3), (1, 2)),
     ("rows_9x9_pad4", 1, 2, 10, 16, 8, 9, 9, (1, 1), (4, 4)),
     ("rows_s2_7x7_many_tiles", 3, 3, 64, 64, 64, 7, 7, (2, 2), (3, 3)),
+    # bf16 3x3 / stride 1 / pad 1 with at least 32 channels on both sides and rows of whole packets: the
+    # weight gradient that stages rows in LDS (ranges of rows that cross image boundaries, ragged
+    # channel groups on both sides, a last 16-pixel step that is half empty, one-step rows)
+    ("wgrows_c64_k192_w24", 3, 64, 9, 24, 192, 3, 3, (1, 1), (1, 1)),
+    ("wgrows_c40_k72_w16_h5", 5, 40, 5, 16, 72, 3, 3, (1, 1), (1, 1)),
+    ("wgrows_c130_k33_w40", 2, 130, 7, 40, 33, 3, 3, (1, 1), (1, 1)),
+    ("wgrows_c32_k32_w8_h3", 7, 32, 3, 8, 32, 3, 3, (1, 1), (1, 1)),
 ]
 PW = [c for c in CASES if c[0].startswith("pw_")]
 
