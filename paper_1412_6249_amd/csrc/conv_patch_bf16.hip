@@ -15,6 +15,14 @@
 // the image are zeros in the patch (the halo columns are cleared once, out-of-image rows come back
 // as zeros from range-checked buffer loads).
 //
+// LDS layout of the patch. A lane of the MFMA loop owns adjacent output pixels (so that its stores
+// are whole packets), hence the lanes of one fragment read are TWO patch positions apart. The patch
+// therefore keeps four planes, (position parity, 8-channel half), each holding the 16-byte packets
+// of positions P with index P >> 1: a fragment read covers consecutive packets of one plane and
+// has no bank conflict whatever the tap's shift. Plane sizes are 32 bytes past a multiple of 128,
+// which keeps the fill's stores (four consecutive 8-pixel packets x two halves per 8 lanes) down to
+// a two-way conflict. The filter rows use the same idea: [tap][half][row] packets.
+//
 // The filter of the same 16 channels sits beside the patch for ALL taps of a stage (from a copy
 // repacked to A[group][tap][i][16]), so the tap loop runs without barriers: one stage = one channel
 // group x a run of taps, two barriers per stage. The loads of the next stage (filter and, when
@@ -30,8 +38,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int GC = 16;              // gathered channels per group: one MFMA reduction step
-constexpr int PITCH = GC * 2 + 16;  // LDS bytes per pixel (patch) or filter row: 32 of data + 16 of padding,
-                                    // so that the 16-byte fragment reads of 8 consecutive rows cover all banks
 constexpr int A_ROUNDS = 8;         // 16-byte filter pieces per thread and stage, at most
 
 // ROUNDS: patch fill tasks (8 channels x 8 pixels each) per thread and channel group.
@@ -44,8 +50,12 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* bias_s = reinterpret_cast<float*>(smem);                 // [BM]
-    unsigned char* As = smem + BM * 4;                              // [taps per stage][BM] rows of PITCH bytes
-    unsigned char* patch = As + q.a_bytes;                          // [pr_max * pw] pixels of PITCH bytes
+    unsigned char* As = smem + BM * 4;                              // [taps per stage][half][BM] 16-byte packets
+    unsigned char* patch = As + q.a_bytes;                          // [parity][half][position >> 1] 16-byte packets
+    const int PB = q.plane_bytes;
+    const int APB = BM * 16 + 64;                                   // filter plane (one half of one tap)
+    // byte offset of position P, half h
+    auto patch_at = [&](int P, int h) { return ((P & 1) * 2 + h) * PB + (P >> 1) * 16; };
 
     const uint16_t* __restrict__ in = (const uint16_t*)p.in;
     const uint16_t* __restrict__ wt = (const uint16_t*)p.wt;
@@ -65,24 +75,27 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
     const int h_lo = ho_first + q.h_lo_add;
 
     // ---- patch fill tasks of this thread: (patch row, 8-channel half of the group, 8-pixel packet)
+    // Task t: 4 consecutive packets (t & 3), half (t >> 2) & 1, then the row's remaining packet quads, then rows.
     unsigned g_voff[ROUNDS];   // byte offset of the packet in the half's first channel of group 0 (2^31: row outside the image)
-    int l_off[ROUNDS];         // byte offset of its first pixel in the patch; a thread without a task in this
-    int l_step[ROUNDS];        // round parks its packets in the padding of patch pixel 0 (step 0), which nobody
-    int cg8[ROUNDS];           // reads: no branch around the stores
-    const int tasks_per_row = q.chunks * (GC / 8);
+    int l_even[ROUNDS];        // patch byte offsets of the packet's pixels 0 and 1 (pixels 2j, 2j + 1 follow at
+    int l_odd[ROUNDS];         // 16 * j); a thread without a task in this round writes into the spare packets
+    int l_step[ROUNDS];        // behind the planes (step 0): no branch around the stores
+    int cg8[ROUNDS];
 #pragma unroll
     for (int r = 0; r < ROUNDS; ++r) {
         const int t = tid + r * NT;
         const int pr = fastdiv(t, q.div_tpr);
-        const int u = t - pr * tasks_per_row;
-        const int cg = fastdiv(u, q.div_chunks);
-        const int chunk = u - cg * q.chunks;
-        const bool live = pr < q.pr_max;
+        const int u = t - pr * q.tasks_per_row;
+        const int cg = (u >> 2) & 1;
+        const int chunk = (u >> 3) * 4 + (u & 3);
+        const bool live = pr < q.pr_max && chunk < q.chunks;
         const int hi = h_lo + pr;
         const bool row_ok = live & ((unsigned)hi < (unsigned)p.Hi);
         g_voff[r] = row_ok ? (unsigned)(n * p.in_ns + cg * 8 * p.HiWi + hi * p.Wi + chunk * 8) * 2u : 0x80000000u;
-        l_off[r] = live ? (pr * q.pw + chunk * 8 - q.w_lo) * PITCH + cg * 16 : GC * 2;
-        l_step[r] = live ? PITCH : 0;
+        const int P0 = pr * q.pw + chunk * 8 - q.w_lo;
+        l_even[r] = live ? patch_at(P0, cg) : 4 * PB + (tid & 7) * 16;
+        l_odd[r] = live ? patch_at(P0 + 1, cg) : 4 * PB + (tid & 7) * 16;
+        l_step[r] = live ? 16 : 0;
         cg8[r] = cg * 8;
     }
     const __amdgpu_buffer_rsrc_t rsrc =
@@ -109,7 +122,7 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
 #pragma unroll
                 for (int c2 = 0; c2 < 4; ++c2)
                     o[c2] = __builtin_amdgcn_perm(pre[r][2 * c2 + 1][px >> 1], pre[r][2 * c2][px >> 1], sel);
-                *reinterpret_cast<u32x4*>(patch + l_off[r] + px * l_step[r]) = o;
+                *reinterpret_cast<u32x4*>(patch + ((px & 1) ? l_odd[r] : l_even[r]) + (px >> 1) * l_step[r]) = o;
             }
         }
     };
@@ -129,7 +142,7 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
         const int row = rem >> 1, half = rem & 1;
         const bool live = tap < tc;
         a_src[it] = live ? (tap * p.i_pad + i0 + row) * GC + half * 8 : -1;
-        a_dst[it] = live ? (tap * BM + row) * PITCH + half * 16 : GC * 2;     // parked in the padding of row 0
+        a_dst[it] = live ? (tap * 2 + half) * APB + row * 16 : BM * 16 + (tid & 3) * 16;   // parked in a plane's spare bytes
     }
     u32x4 a_reg[A_ROUNDS];
     auto load_a = [&](int group, int t0, int nt) {
@@ -152,15 +165,19 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
 
     // ---- this lane's B-fragment positions (byte offsets into the patch at tap (0,0)); columns past the
     // tile's last pixel re-read that pixel (their results are never stored)
-    int b_pos[TN];
+    // position P = P_lane + shift sits at half * PB + 8 * P + (P & 1) * (2 * PB - 8): one base per parity of the shift
+    int b_same[TN], b_flip[TN];
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
         const int pix = min(pix0 + wn * TN * 32 + TN * (lane & 31) + b, pix_end - 1);   // a lane's tiles: adjacent pixels
         const int ho = fastdiv(pix, p.div_wo);
         const int wo = pix - ho * p.Wo;
-        b_pos[b] = ((ho - ho_first) * q.pw + wo + q.pos_add) * PITCH + (lane >> 5) * 16;
+        const int P = (ho - ho_first) * q.pw + wo + q.pos_add;
+        const int lin = (lane >> 5) * PB + P * 8;
+        b_same[b] = lin + (P & 1) * (2 * PB - 8);
+        b_flip[b] = lin + ((P & 1) ^ 1) * (2 * PB - 8);
     }
-    const int a_row = (wm * TM * 32 + (lane & 31)) * PITCH + (lane >> 5) * 16;
+    const int a_row = (lane >> 5) * APB + (wm * TM * 32 + (lane & 31)) * 16;
 
     floatx16 acc[TM][TN];
 #pragma unroll
@@ -183,7 +200,7 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
             const int hc = hp - pr * halo_w;
             const int pc = hc < q.halo_l ? hc : q.halo_r0 + (hc - q.halo_l);
             const u32x4 z = {0u, 0u, 0u, 0u};
-            *reinterpret_cast<u32x4*>(patch + (pr * q.pw + pc) * PITCH + half * 16) = z;
+            *reinterpret_cast<u32x4*>(patch + patch_at(pr * q.pw + pc, half)) = z;
         }
     }
     if (FUSED) stage_bias<uint16_t, BM, NT>(bias_s, p, i0, tid);
@@ -207,19 +224,20 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
         int tap_s = t0 - tap_r * p.St;
         const unsigned char* asrc = As + a_row;
         for (int tap = 0; tap < nt; ++tap) {
-            const int tap_off = (tap_r * q.pw + tap_s) * PITCH;
-            const unsigned char* bsrc = patch + (MINUS ? -tap_off : tap_off);
+            const int shift = tap_r * q.pw + tap_s;                 // in patch positions
+            const unsigned char* bsrc = patch + (MINUS ? -shift : shift) * 8;
+            const bool odd = shift & 1;
             bf16x8 av[TM], bv[TN];
 #pragma unroll
-            for (int a = 0; a < TM; ++a) av[a] = *reinterpret_cast<const bf16x8*>(asrc + a * 32 * PITCH);
+            for (int a = 0; a < TM; ++a) av[a] = *reinterpret_cast<const bf16x8*>(asrc + a * 32 * 16);
 #pragma unroll
-            for (int b = 0; b < TN; ++b) bv[b] = *reinterpret_cast<const bf16x8*>(bsrc + b_pos[b]);
+            for (int b = 0; b < TN; ++b) bv[b] = *reinterpret_cast<const bf16x8*>(bsrc + (odd ? b_flip[b] : b_same[b]));
 #pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
-            asrc += BM * PITCH;
+            asrc += 2 * APB;
             tap_s += 1;
             const bool wrap = tap_s >= p.St;
             tap_s = wrap ? 0 : tap_s;
@@ -335,7 +353,7 @@ bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* qg) {
         if (best < 0 || padded < best) { best = padded; q.bm = c[0]; q.bn = c[1]; }
     }
     const int n_taps = p.Rt * p.St;
-    q.pw = p.Wo + p.St - 1;
+    q.pw = p.Wo + p.St - 1;                                   // patch columns (one spare column may follow on the right)
     const int rows_spanned = (q.bn - 2) / p.Wo + 2;
     q.pr_max = (rows_spanned < p.Ho ? rows_spanned : p.Ho) + p.Rt - 1;
     q.w_lo = p.g_add_w - (minus ? p.St - 1 : 0);
@@ -345,26 +363,30 @@ bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* qg) {
     q.halo_l = -q.w_lo;
     q.halo_r0 = p.Wi - q.w_lo;
     if (q.halo_l < 0 || q.halo_r0 > q.pw) return false;       // image columns outside the patch
-    const long long tasks = (long long)q.pr_max * q.chunks * (GC / 8);
+    q.tasks_per_row = (q.chunks + 3) / 4 * 4 * (GC / 8);
+    const long long tasks = (long long)q.pr_max * q.tasks_per_row;
     if (tasks > 2 * 256) return false;
     q.rounds = tasks > 256 ? 2 : 1;
     // taps per stage: as many as the thread's filter registers and 80 KB of LDS (two workgroups per
     // CU) allow; whole filter rows when a stage cannot hold every tap
-    const long long patch_bytes = (long long)q.pr_max * q.pw * PITCH;
+    const long long plane = ((long long)q.pr_max * q.pw + 1) / 2 * 16;
+    q.plane_bytes = (int)((plane + 95) / 128 * 128 + 32);      // 32 past a multiple of 128
+    const long long patch_bytes = 4LL * q.plane_bytes + 128;    // + spare packets for threads without a task
     const long long fixed = (long long)q.bm * 4 + patch_bytes;
+    const long long a_tap = 2LL * (q.bm * 16 + 64);            // LDS bytes of one tap's filter rows
     long long tc = (long long)A_ROUNDS * 256 / (q.bm * 2);
-    const long long by_lds = (80 * 1024 - fixed) / ((long long)q.bm * PITCH);
+    const long long by_lds = (80 * 1024 - fixed) / a_tap;
     if (by_lds < tc) tc = by_lds;
     if (tc > n_taps) tc = n_taps;
     if (tc < 1) return false;
     if (tc < n_taps && tc > p.St) tc = tc / p.St * p.St;
     q.taps_per_stage = (int)tc;
     q.a_rounds = (int)((tc * q.bm * 2 + 255) / 256);
-    q.a_bytes = (int)(tc * q.bm * PITCH);
+    q.a_bytes = (int)(tc * a_tap);
     q.lds_bytes = (int)(fixed + q.a_bytes);
     q.tiles_per_img = (p.HoWo + q.bn - 1) / q.bn;
     q.div_tpi = make_fastdiv(q.tiles_per_img);
-    q.div_tpr = make_fastdiv(q.chunks * (GC / 8));
+    q.div_tpr = make_fastdiv(q.tasks_per_row);
     q.div_chunks = make_fastdiv(q.chunks);
     q.div_st = make_fastdiv(p.St);
     const int halo_w = q.halo_l + q.pw - q.halo_r0;

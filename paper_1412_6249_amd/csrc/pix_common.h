@@ -424,6 +424,8 @@ struct PatchGeom {
     int a_rounds;        // 16-byte filter pieces per thread and stage
     int pairs;           // NCHW output written as 4-byte pixel pairs
     int a_bytes, lds_bytes;
+    int plane_bytes;     // bytes of one (position parity, channel half) plane of the patch
+    int tasks_per_row;   // fill tasks per patch row: packets rounded up to fours x two halves
     FastDiv div_tpi, div_tpr, div_chunks, div_halo, div_st;
 };
 bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* q);
