@@ -86,6 +86,8 @@ bool buffer_loads_disabled();   // tuning hook: (anything, -1) given to force_pi
 // for the launch.
 struct WgradPlan {
     bool rows;         // bf16 3x3 layers: the row-staging kernel (one partial tile per persistent workgroup)
+    bool cols;         // bf16 layers with C*R*S <= 160: whole-filter tiles per wavefront (conv_wgrad_cols_bf16.hip)
+    bool taps;         // bf16 layers with C*R <= 32 and a known filter row shape: one tile per column tap (conv_wgrad_taps_bf16.hip)
     bool tap;          // columns are the channels of one tap (C >= 64) instead of flattened (c,r,s)
     int c_tiles;
     int bm, bn;        // tile extents along k and along the columns
@@ -96,6 +98,12 @@ struct WgradPlan {
 WgradPlan plan_wgrad(const ConvGeom& g, int dtype);
 bool wgrad_rows_bf16_applies(const ConvGeom& g, int* workers);
 hipError_t launch_wgrad_rows_bf16(const ConvGeom& g, int workers, const void* x, const void* dy, float* partials,
+                                  float* db_partials, hipStream_t st);
+bool wgrad_taps_bf16_applies(const ConvGeom& g, int* workers);
+hipError_t launch_wgrad_taps_bf16(const ConvGeom& g, const void* x, const void* dy, float* partials,
+                                  float* db_partials, hipStream_t st);
+bool wgrad_cols_bf16_applies(const ConvGeom& g, int* workers);
+hipError_t launch_wgrad_cols_bf16(const ConvGeom& g, const void* x, const void* dy, float* partials,
                                   float* db_partials, hipStream_t st);
 inline size_t wgrad_db_offset(const WgradPlan& pl) { return (pl.ws_bytes + 255) & ~(size_t)255; }
 

@@ -765,6 +765,23 @@ WgradPlan plan_wgrad(const ConvGeom& g, int dtype) {
             pl.db_ws_bytes = (size_t)workers * (size_t)g.K * sizeof(float);
             return pl;
         }
+        // bf16 layers with at most 160 filter elements per output channel (the first layer of an image
+        // network): every wavefront holds the whole filter tile and the wavefronts split the pixels
+        // (conv_wgrad_cols_bf16.hip); partials are [worker][k][c][r][s]
+        const bool taps = dtype == PURINE_BF16 && !buffer_loads_disabled() && wgrad_taps_bf16_applies(g, &workers);
+        if (taps || (dtype == PURINE_BF16 && !buffer_loads_disabled() && wgrad_cols_bf16_applies(g, &workers))) {
+            // (at most 32 (c, r) pairs and a filter row shape the tap kernel is built for: one accumulator
+            // tile per column tap, conv_wgrad_taps_bf16.hip; same layout of the partials)
+            pl.taps = taps;
+            pl.cols = !taps;
+            pl.tap = false;
+            pl.splits = workers;
+            pl.bm = 64; pl.bn = 160; pl.tiles_i = (g.K + 63) / 64; pl.c_tiles = 0; pl.tiles_j = 1;
+            pl.chunk = 0;
+            pl.ws_bytes = (size_t)workers * (size_t)g.K * (size_t)g.C * g.R * g.S * sizeof(float);
+            pl.db_ws_bytes = (size_t)workers * (size_t)g.K * sizeof(float);
+            return pl;
+        }
     }
     const long long M = (long long)g.N * g.P * g.Q;
     const long long CRS = (long long)g.C * g.R * g.S;
@@ -866,6 +883,8 @@ hipError_t launch_conv_wgrad(int dtype, const ConvGeom& g, const WgradPlan& plan
     hipError_t e;
     const bool vec = p.PQ % 32 == 0 && (((uintptr_t)dy) & 15u) == 0;
     if (plan.rows) e = launch_wgrad_rows_bf16(g, plan.splits, x, dy, (float*)ws, p.db_out, st);
+    else if (plan.taps) e = launch_wgrad_taps_bf16(g, x, dy, (float*)ws, p.db_out, st);
+    else if (plan.cols) e = launch_wgrad_cols_bf16(g, x, dy, (float*)ws, p.db_out, st);
     else if (dtype == PURINE_F32) e = plan.tap ? dispatch_f32<true>(p, plan, st) : dispatch_f32<false>(p, plan, st);
     else if (plan.tap) e = vec ? dispatch_bf16<true, true>(p, plan, st) : dispatch_bf16<false, true>(p, plan, st);
     else e = vec ? dispatch_bf16<true, false>(p, plan, st) : dispatch_bf16<false, false>(p, plan, st);

@@ -75,6 +75,20 @@ CASES = [
     ("wgrows_c40_k72_w16_h5", 5, 40, 5, 16, 72, 3, 3, (1, 1), (1, 1)),
     ("wgrows_c130_k33_w40", 2, 130, 7, 40, 33, 3, 3, (1, 1), (1, 1)),
     ("wgrows_c32_k32_w8_h3", 7, 32, 3, 8, 32, 3, 3, (1, 1), (1, 1)),
+    # bf16 layers with at most 160 filter elements per output channel and a column stride of 1 or 2:
+    # the weight gradient whose wavefronts each hold the whole filter tile (input rows de-interleaved
+    # by column parity in LDS; an odd number of output rows per image, so that a pair of rows
+    # straddles two images; output channels past a multiple of 64; one to five column tiles)
+    ("wgcols_7x7_s2_c3_k64", 3, 3, 36, 64, 64, 7, 7, (2, 2), (3, 3)),
+    ("wgcols_7x7_s2_odd_rows", 5, 3, 18, 32, 64, 7, 7, (2, 2), (3, 3)),
+    ("wgcols_5x5_s1_c3_k40", 2, 3, 12, 32, 40, 5, 5, (1, 1), (2, 2)),
+    ("wgcols_3x3_s2_c8_k96", 2, 8, 10, 64, 96, 3, 3, (2, 2), (1, 1)),
+    ("wgcols_3x5_s21_c4_k33", 3, 4, 9, 16, 33, 3, 5, (2, 1), (1, 2)),
+    ("wgcols_1x1_s2_c16_k32", 2, 16, 6, 32, 32, 1, 1, (2, 2), (0, 0)),
+    # ... and shapes only the general form of that kernel takes (a window per lane): more than 32
+    # (channel, filter row) pairs, an even filter width
+    ("wgcols_3x3_c12_k64", 2, 12, 9, 32, 64, 3, 3, (1, 1), (1, 1)),
+    ("wgcols_4x4_s2_c5_k72", 3, 5, 10, 64, 72, 4, 4, (2, 2), (1, 1)),
 ]
 PW = [c for c in CASES if c[0].startswith("pw_")]
 
