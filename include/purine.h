@@ -17,9 +17,11 @@
  *     extents, outermost first; unused trailing entries are ignored. No tensor may hold 2^31 or
  *     more elements. Data pointers must be aligned to 16 bytes. One tighter limit: a PURINE_BF16
  *     convolution or backward-data pass whose filter has more than one tap and at least 16
- *     channels on the gathered side stages a channels-blocked copy of the gathered tensor (x, or
- *     dy for backward-data; channels rounded up to a multiple of 32) in ws, and that copy must
- *     stay below 2^31 bytes, i.e. 2^30 elements (PURINE_E_SHAPE otherwise).
+ *     channels on the gathered side, and whose gathered tensor (x, or dy for backward-data) has
+ *     rows that are not whole 16-byte packets (W not a multiple of 8, or a channel count or image
+ *     stride not a multiple of 8), stages a channels-blocked copy of that tensor (channels rounded
+ *     up to a multiple of 32) in ws, and that copy must stay below 2^31 bytes, i.e. 2^30 elements
+ *     (PURINE_E_SHAPE otherwise). Layers with whole-packet rows are read in place.
  *   - Channel-slice views: a 4-axis F32 activation tensor may set `nstride`, the distance in
  *     elements between consecutive images, to more than C*H*W: the tensor is then channels
  *     c0..c0+C-1 of a larger NCHW buffer with `data` pointing at channel c0 of image 0 (inside an
