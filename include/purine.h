@@ -22,10 +22,11 @@
  *     stride not a multiple of 8), stages a channels-blocked copy of that tensor (channels rounded
  *     up to a multiple of 32) in ws, and that copy must stay below 2^31 bytes, i.e. 2^30 elements
  *     (PURINE_E_SHAPE otherwise). Layers with whole-packet rows are read in place.
- *   - Channel-slice views: a 4-axis F32 activation tensor may set `nstride`, the distance in
+ *   - Channel-slice views: a 4-axis F32 or BF16 activation tensor may set `nstride`, the distance in
  *     elements between consecutive images, to more than C*H*W: the tensor is then channels
  *     c0..c0+C-1 of a larger NCHW buffer with `data` pointing at channel c0 of image 0 (inside an
- *     image the layout stays dense). nstride must be a multiple of 4 and the span
+ *     image the layout stays dense). nstride must be a whole number of 16-byte packets (a
+ *     multiple of 4 for F32, of 8 for BF16) and the span
  *     (N-1)*nstride + C*H*W must stay below 2^31 elements. Views are accepted where an entry
  *     point says so (the activation arguments of the convolution operators and of ReLU); every
  *     other argument must be dense (PURINE_E_LAYOUT otherwise). Two views of one buffer with the
@@ -221,9 +222,9 @@ int purine_sgd_update(const purine_tensor* w, const purine_tensor* dw, purine_te
  * g*K/G .. (g+1)*K/G-1 see only input channels g*C/G .. (g+1)*C/G-1. Runs the matching operator once
  * per group on channel-slice views of x, y (dy, dx) and on the group's rows of w (b, dw, db), one
  * group after the other on the stream, all sharing ws (purine_grouped_conv_workspace_bytes: one
- * group's need). groups = 1 is the plain operator. For groups > 1: F32 only, and (C/G)*H*W,
- * (K/G)*P*Q, (K/G)*(C/G)*R*S and K/G must be multiples of 4 so that every slice keeps the
- * alignment rules (PURINE_E_LAYOUT otherwise). b and db may be NULL. x, y, dy, dx may themselves
+ * group's need). groups = 1 is the plain operator. For groups > 1: (C/G)*H*W, (K/G)*P*Q,
+ * (K/G)*(C/G)*R*S and K/G must be multiples of 4 (F32 activations) or 8 (BF16) so that every
+ * slice keeps the alignment rules (PURINE_E_LAYOUT otherwise). b and db may be NULL. x, y, dy, dx may themselves
  * be views. */
 size_t purine_grouped_conv_workspace_bytes(int pass, const purine_conv_desc* desc, int groups,
                                            const int64_t x_dim[4], const int64_t w_dim[4],
@@ -238,14 +239,18 @@ int purine_grouped_conv_bwd_weight(const purine_conv_desc* desc, int groups, con
                                    const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
                                    float beta, void* ws, size_t ws_bytes, void* hip_stream);
 
-/* Fully-connected layer on dense 2-axis F32 matrices: x [N,C], w [K,C], b [K], y [N,K].
+/* Fully-connected layer on dense 2-axis matrices: x [N,C], w [K,C], b [K], y [N,K], all F32 or all
+ * BF16; dw and db are F32.
  *   fwd:        y = x w^T (+ b)          dx = dy w          dw = beta*dw + dy^T x,  db = beta*db + column sums of dy
  * Each pass is one of the convolution GEMM kernels on reinterpreted descriptors (a matrix
  * [rows, features] is one image of `rows` channels whose pixel plane is the feature axis, or a 1x1
  * filter bank): forward runs the weight-gradient kernel (split reduction over C, fixed-order
- * second pass), backward-data the forward kernel, backward-weight the backward-data kernel.
+ * second pass; BF16: its fp32 result gets the bias added and is rounded once), backward-data the
+ * forward kernel (with a split reduction over K when its tiles alone would leave most of the chip
+ * idle), backward-weight the backward-data kernel (F32) or the weight-gradient kernel over the
+ * batch as the pixel axis, on transposed copies of x and dy kept in ws (BF16: the result is fp32).
  * pass for the workspace query: PURINE_CONV_FWD, _BWD_DATA, _BWD_WEIGHT. b and db may be NULL. */
-size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K);
+size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K, int32_t dtype);
 int purine_fc_fwd(const purine_tensor* x, const purine_tensor* w, const purine_tensor* b,
                   purine_tensor* y, void* ws, size_t ws_bytes, void* hip_stream);
 int purine_fc_bwd_data(const purine_tensor* dy, const purine_tensor* w, purine_tensor* dx, void* ws,

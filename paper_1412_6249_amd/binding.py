@@ -84,7 +84,7 @@ _SIGS = {
     "purine_grouped_conv_fwd": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, _T, ctypes.c_int, _vp, _sz, _vp]),
     "purine_grouped_conv_bwd_data": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
     "purine_grouped_conv_bwd_weight": (ctypes.c_int, [_D, ctypes.c_int, _T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
-    "purine_fc_workspace_bytes": (_sz, [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]),
+    "purine_fc_workspace_bytes": (_sz, [ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, ctypes.c_int32]),
     "purine_fc_fwd": (ctypes.c_int, [_T, _T, _T, _T, _vp, _sz, _vp]),
     "purine_fc_bwd_data": (ctypes.c_int, [_T, _T, _T, _vp, _sz, _vp]),
     "purine_fc_bwd_weight": (ctypes.c_int, [_T, _T, _T, _T, ctypes.c_float, _vp, _sz, _vp]),
@@ -333,8 +333,8 @@ def purine_grouped_conv_bwd_weight(desc, groups, x, dy, dw, db=None, beta=0.0, w
            "purine_grouped_conv_bwd_weight")
 
 
-def purine_fc_workspace_bytes(which, N, C, K):
-    return int(_lib.purine_fc_workspace_bytes(int(which), int(N), int(C), int(K)))
+def purine_fc_workspace_bytes(which, N, C, K, dtype=PURINE_F32):
+    return int(_lib.purine_fc_workspace_bytes(int(which), int(N), int(C), int(K), int(dtype)))
 
 
 def purine_fc_fwd(x, w, b, y, ws=None, stream=None):

@@ -31,7 +31,8 @@ bool is_view(const purine_tensor* t) { return nstride_of(t) != image_elems(t); }
 // elements from the first to one past the last element of the tensor
 int64_t span_elems(const purine_tensor* t) { return (t->dim[0] - 1) * nstride_of(t) + image_elems(t); }
 
-// allow_view: the argument may be a channel-slice view (F32, 4 axes)
+static bool is_float_dtype_(int d) { return d == PURINE_F32 || d == PURINE_BF16; }
+// allow_view: the argument may be a channel-slice view (F32 or BF16, 4 axes)
 int check_tensor(const purine_tensor* t, int ndim, bool allow_view = false) {
     if (!t) return PURINE_E_NULL;
     if (!t->data) return PURINE_E_NULL;
@@ -48,7 +49,9 @@ int check_tensor(const purine_tensor* t, int ndim, bool allow_view = false) {
     if (t->nstride != 0) {
         if (t->ndim != 4 || t->nstride < image_elems(t)) return PURINE_E_SHAPE;
         if (is_view(t)) {
-            if (!allow_view || t->dtype != PURINE_F32 || (t->nstride & 3)) return PURINE_E_LAYOUT;
+            // images keep the 16-byte alignment of the vector loads and stores: 4 floats, 8 bfloat16
+            const int64_t packet = t->dtype == PURINE_BF16 ? 7 : 3;
+            if (!allow_view || !is_float_dtype_(t->dtype) || (t->nstride & packet)) return PURINE_E_LAYOUT;
             if (t->nstride >= (1ll << 31) || span_elems(t) >= (1ll << 31)) return PURINE_E_SHAPE;
         }
     }
@@ -411,7 +414,7 @@ int purine_relu_fwd(const purine_tensor* x, purine_tensor* y, void* hip_stream) 
     hipError_t e;
     if (is_view(x) || is_view(y)) {
         if (x->dim[0] > 65535) return PURINE_E_SHAPE;
-        e = launch_relu_view(false, (const float*)x->data, nullptr, (float*)y->data, (int)x->dim[0],
+        e = launch_relu_view(x->dtype, false, x->data, nullptr, y->data, (int)x->dim[0],
                              (int)image_elems(x), nstride_of(x), 0, nstride_of(y), (hipStream_t)hip_stream);
     } else {
         e = launch_relu_fwd(x->dtype, x->data, y->data, numel(x), (hipStream_t)hip_stream);
@@ -433,7 +436,7 @@ int purine_relu_bwd(const purine_tensor* x, const purine_tensor* dy, purine_tens
     hipError_t e;
     if (is_view(x) || is_view(dy) || is_view(dx)) {
         if (x->dim[0] > 65535) return PURINE_E_SHAPE;
-        e = launch_relu_view(true, (const float*)x->data, (const float*)dy->data, (float*)dx->data,
+        e = launch_relu_view(x->dtype, true, x->data, dy->data, dx->data,
                              (int)x->dim[0], (int)image_elems(x), nstride_of(x), nstride_of(dy),
                              nstride_of(dx), (hipStream_t)hip_stream);
     } else {
@@ -607,10 +610,13 @@ int check_groups(int groups, const purine_tensor* x, const purine_tensor* w, con
     if (x->dim[1] % groups || w->dim[0] % groups || y->dim[1] != w->dim[0] || x->dim[1] / groups != w->dim[1])
         return PURINE_E_SHAPE;
     if (groups == 1) return PURINE_OK;
-    if (x->dtype != PURINE_F32) return PURINE_E_DTYPE;   // slices are views, and views are fp32
+    if (!is_float_dtype(x->dtype)) return PURINE_E_DTYPE;
+    // every group's slices start on a 16-byte packet (4 floats or 8 bfloat16); the weight and bias
+    // gradients are fp32 whatever the activations are
+    const int64_t pk = x->dtype == PURINE_BF16 ? 8 : 4;
     const int64_t cg = x->dim[1] / groups, kg = w->dim[0] / groups;
-    if ((cg * x->dim[2] * x->dim[3]) % 4 || (kg * y->dim[2] * y->dim[3]) % 4 ||
-        (kg * w->dim[1] * w->dim[2] * w->dim[3]) % 4 || kg % 4 || nstride_of(x) % 4 || nstride_of(y) % 4)
+    if ((cg * x->dim[2] * x->dim[3]) % pk || (kg * y->dim[2] * y->dim[3]) % pk ||
+        (kg * w->dim[1] * w->dim[2] * w->dim[3]) % pk || kg % pk || nstride_of(x) % pk || nstride_of(y) % pk)
         return PURINE_E_LAYOUT;
     return PURINE_OK;
 }
@@ -629,11 +635,16 @@ purine_tensor as_filter(const purine_tensor* t) {
 }
 const purine_conv_desc kUnitConv{1, 1, 0, 0};
 
-int check_fc(const purine_tensor* x, const purine_tensor* w, const purine_tensor* y) {
+// x, w, y (or dx, w, dy / x, dw, dy for the gradients): 2-axis, of one float dtype; `grad`
+// names the fp32 operand of the weight-gradient pass
+int check_fc(const purine_tensor* x, const purine_tensor* w, const purine_tensor* y, bool w_is_grad = false) {
     int rc;
     if ((rc = check_tensor(x, 2)) || (rc = check_tensor(w, 2)) || (rc = check_tensor(y, 2))) return rc;
-    if (x->dtype != PURINE_F32 || w->dtype != PURINE_F32 || y->dtype != PURINE_F32) return PURINE_E_DTYPE;
+    if (!is_float_dtype(x->dtype) || y->dtype != x->dtype) return PURINE_E_DTYPE;
+    if (w->dtype != (w_is_grad ? (int)PURINE_F32 : x->dtype)) return PURINE_E_DTYPE;
     if (x->dim[1] != w->dim[1] || y->dim[0] != x->dim[0] || y->dim[1] != w->dim[0]) return PURINE_E_SHAPE;
+    // the reinterpreted descriptors index rows and features with int
+    if (x->dim[0] > 0x7fffffff || x->dim[1] > 0x7fffffff || w->dim[0] > 0x7fffffff) return PURINE_E_SHAPE;
     return PURINE_OK;
 }
 size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
@@ -697,20 +708,30 @@ int purine_grouped_conv_bwd_weight(const purine_conv_desc* desc, int groups, con
     return PURINE_OK;
 }
 
-size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K) {
-    if (N < 1 || C < 1 || K < 1) return 0;
-    // one convolution geometry serves the three passes: a 1x1 filter bank [N, K] over the plane [1, K, 1, C]
+size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K, int32_t dtype) {
+    if (N < 1 || C < 1 || K < 1 || !is_float_dtype(dtype)) return 0;
+    // one convolution geometry serves the three fp32 passes: a 1x1 filter bank [N, K] over the plane [1, K, 1, C]
     const int64_t xd[4] = {1, K, 1, C}, wd[4] = {N, K, 1, 1};
+    const int64_t dyd[4] = {N, K, 1, 1};
     switch (pass) {
         case PURINE_CONV_FWD:   // y = x w^T through the weight-gradient kernel (split reduction over C)
-            return purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xd, wd, PURINE_F32);
+            return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xd, wd, dtype)) +
+                   (dtype == PURINE_BF16 ? (size_t)N * K * 4 : 0);   // bf16: the fp32 product matrix before the bias
         case PURINE_CONV_BWD_DATA:   // dx = dy w through the forward kernel
-            return purine_conv_workspace_bytes(PURINE_CONV_FWD, &kUnitConv, xd, wd, PURINE_F32);
+            return purine_conv_workspace_bytes(PURINE_CONV_FWD, &kUnitConv, xd, wd, dtype);
         case PURINE_CONV_BWD_WEIGHT:
-        case PURINE_CONV_BWD_WEIGHT_BIAS: {   // dw = dy^T x through the backward-data kernel, db by BiasBwd
-            const int64_t dyd[4] = {N, K, 1, 1};
-            return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, PURINE_F32)) +
-                   purine_bias_bwd_workspace_bytes(dyd, PURINE_F32);
+        case PURINE_CONV_BWD_WEIGHT_BIAS: {
+            if (dtype == PURINE_BF16) {
+                // dw = dy^T x through the weight-gradient kernel on the transposed matrices (the batch
+                // as the pixel axis): both transposes, that kernel's partial sums, BiasBwd's
+                const int64_t xt[4] = {1, C, 1, N}, wt[4] = {K, C, 1, 1};
+                return align256((size_t)N * C * 2) + align256((size_t)N * K * 2) +
+                       align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xt, wt, dtype)) +
+                       purine_bias_bwd_workspace_bytes(dyd, dtype);
+            }
+            // fp32: dw = dy^T x through the backward-data kernel, db by BiasBwd
+            return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, dtype)) +
+                   purine_bias_bwd_workspace_bytes(dyd, dtype);
         }
         default: return 0;
     }
@@ -722,7 +743,7 @@ int purine_fc_fwd(const purine_tensor* x, const purine_tensor* w, const purine_t
     if ((rc = check_fc(x, w, y))) return rc;
     if (b) {
         if ((rc = check_tensor(b, 1))) return rc;
-        if (b->dtype != PURINE_F32) return PURINE_E_DTYPE;
+        if (b->dtype != y->dtype) return PURINE_E_DTYPE;
         if (b->dim[0] != w->dim[0]) return PURINE_E_SHAPE;
         if (overlaps(b, y)) return PURINE_E_LAYOUT;
     }
@@ -730,6 +751,20 @@ int purine_fc_fwd(const purine_tensor* x, const purine_tensor* w, const purine_t
     // both matrices as one image whose pixel plane is the feature axis c
     const purine_tensor wp = as_plane(w), xp = as_plane(x);
     purine_tensor yf = as_filter(y);
+    if (x->dtype == PURINE_BF16) {
+        // that kernel's result is fp32: it goes to the end of the workspace, and a last kernel adds
+        // the bias and rounds once
+        const int64_t N = x->dim[0], K = w->dim[0];
+        const size_t conv_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, wp.dim, yf.dim, PURINE_BF16));
+        if (!ws || ws_bytes < conv_ws + (size_t)N * K * 4) return PURINE_E_WORKSPACE;
+        if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+        purine_tensor acc = yf;
+        acc.dtype = PURINE_F32;
+        acc.data = (char*)ws + conv_ws;
+        if ((rc = conv_bwd_weight_impl(&kUnitConv, &wp, &xp, &acc, nullptr, 0.0f, ws, conv_ws, hip_stream))) return rc;
+        return hip_status(launch_fc_finish_bf16((const float*)acc.data, b ? b->data : nullptr, y->data, (int)N, (int)K,
+                                                (hipStream_t)hip_stream));
+    }
     if ((rc = conv_bwd_weight_impl(&kUnitConv, &wp, &xp, &yf, nullptr, 0.0f, ws, ws_bytes, hip_stream))) return rc;
     if (b)
         return hip_status(launch_bias_rows((const float*)b->data, (float*)y->data, (int)y->dim[0], (int)y->dim[1],
@@ -751,25 +786,52 @@ int purine_fc_bwd_data(const purine_tensor* dy, const purine_tensor* w, purine_t
 int purine_fc_bwd_weight(const purine_tensor* x, const purine_tensor* dy, purine_tensor* dw, purine_tensor* db,
                          float beta, void* ws, size_t ws_bytes, void* hip_stream) {
     int rc;
-    if ((rc = check_fc(x, dw, dy)) || (rc = check_beta(beta))) return rc;
-    const int64_t xd[4] = {1, dw->dim[0], 1, dw->dim[1]}, wd[4] = {x->dim[0], dw->dim[0], 1, 1};
-    const size_t conv_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, PURINE_F32));
+    if ((rc = check_fc(x, dw, dy, true)) || (rc = check_beta(beta))) return rc;
+    const int64_t N = x->dim[0], C = x->dim[1], K = dw->dim[0];
     const purine_tensor dy4 = as_filter(dy);
+    const size_t bias_ws = db ? purine_bias_bwd_workspace_bytes(dy4.dim, x->dtype) : 0;
     if (db) {
         if ((rc = check_tensor(db, 1))) return rc;
         if (db->dtype != PURINE_F32) return PURINE_E_DTYPE;
         if (db->dim[0] != dw->dim[0]) return PURINE_E_SHAPE;
         if (overlaps(db, dy) || overlaps(db, x) || overlaps(db, dw)) return PURINE_E_LAYOUT;
-        if (!ws || ws_bytes < conv_ws + purine_bias_bwd_workspace_bytes(dy4.dim, PURINE_F32)) return PURINE_E_WORKSPACE;
-        if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
     }
-    // dw[k][c] = sum_n dy[n][k] x[n][c]: the backward-data contraction with dy := x (plane of N
-    // channels) and w := dy (filter bank [N x K])
-    const purine_tensor xp = as_plane(x);
-    purine_tensor dwp = as_plane(dw);
-    if ((rc = conv_bwd_data_impl(&kUnitConv, &xp, &dy4, nullptr, &dwp, beta, ws, ws_bytes < conv_ws ? ws_bytes : conv_ws,
-                                 hip_stream)))
-        return rc;
+    size_t conv_ws;   // bytes of ws in front of BiasBwd's part
+    if (x->dtype == PURINE_BF16) {
+        // dw[k][c] = sum_n dy[n][k] x[n][c] with an fp32 result: the weight-gradient contraction over
+        // the batch as the pixel axis, on transposed copies x^T [C x N] and dy^T [K x N]
+        const int64_t xt[4] = {1, C, 1, N}, wt[4] = {K, C, 1, 1};
+        const size_t xt_bytes = align256((size_t)N * C * 2), dyt_bytes = align256((size_t)N * K * 2);
+        const size_t wg_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xt, wt, PURINE_BF16));
+        conv_ws = xt_bytes + dyt_bytes + wg_ws;
+        if (!ws || ws_bytes < conv_ws + bias_ws) return PURINE_E_WORKSPACE;
+        if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+        purine_tensor xT = *x, dyT = *dy;
+        xT.data = ws; dyT.data = (char*)ws + xt_bytes;
+        xT.dim[0] = C; xT.dim[1] = N; dyT.dim[0] = K; dyT.dim[1] = N;
+        hipError_t e = launch_transpose16(x->data, xT.data, (int)N, (int)C, (hipStream_t)hip_stream);
+        if (e == hipSuccess) e = launch_transpose16(dy->data, dyT.data, (int)N, (int)K, (hipStream_t)hip_stream);
+        if (e != hipSuccess) return hip_status(e);
+        const purine_tensor xp = as_plane(&xT), dyp = as_plane(&dyT);
+        purine_tensor dwf = as_filter(dw);
+        if ((rc = conv_bwd_weight_impl(&kUnitConv, &xp, &dyp, &dwf, nullptr, beta, (char*)ws + xt_bytes + dyt_bytes, wg_ws,
+                                       hip_stream)))
+            return rc;
+    } else {
+        const int64_t xd[4] = {1, K, 1, C}, wd[4] = {N, K, 1, 1};
+        conv_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, PURINE_F32));
+        if (db) {
+            if (!ws || ws_bytes < conv_ws + bias_ws) return PURINE_E_WORKSPACE;
+            if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+        }
+        // dw[k][c] = sum_n dy[n][k] x[n][c]: the backward-data contraction with dy := x (plane of N
+        // channels) and w := dy (filter bank [N x K])
+        const purine_tensor xp = as_plane(x);
+        purine_tensor dwp = as_plane(dw);
+        if ((rc = conv_bwd_data_impl(&kUnitConv, &xp, &dy4, nullptr, &dwp, beta, ws, ws_bytes < conv_ws ? ws_bytes : conv_ws,
+                                     hip_stream)))
+            return rc;
+    }
     if (db)   // column sums of dy: BiasBwd on dy as [N, K, 1, 1]
         return purine_bias_bwd(&dy4, db, beta, (char*)ws + conv_ws, ws_bytes - conv_ws, hip_stream);
     return PURINE_OK;

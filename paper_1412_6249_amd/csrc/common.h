@@ -77,6 +77,10 @@ struct PixPlan {
     // to gemm_tn elements; the fields above stay valid for the general kernel otherwise)
     bool gemm1x1;
     int gemm_tm, gemm_tn, gemm_tiles_i, gemm_tiles_pix;
+    // ... with a split reduction when its tiles alone would leave most of the chip idle (the
+    // fully-connected backward-data shape: few rows, few pixels, a long reduction)
+    int gemm_splits, gemm_split_ci;
+    size_t gemm_part_offset;   // byte offset of the fp32 partial tiles inside the scratch
 };
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
 void force_pix_tile(int bm, int bn);
@@ -150,7 +154,9 @@ hipError_t launch_relu_fwd(int dtype, const void* x, void* y, int64_t n, hipStre
 hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, int64_t n,
                            hipStream_t st);
 hipError_t launch_bias_rows(const float* b, float* y, int N, int K, hipStream_t st);
-hipError_t launch_relu_view(bool bwd, const float* x, const float* dy, float* out, int N, int run,
+hipError_t launch_fc_finish_bf16(const float* acc, const void* b, void* y, int N, int K, hipStream_t st);
+hipError_t launch_transpose16(const void* in, void* out, int rows, int cols, hipStream_t st);
+hipError_t launch_relu_view(int dtype, bool bwd, const void* x, const void* dy, void* out, int N, int run,
                             int64_t x_ns, int64_t dy_ns, int64_t out_ns, hipStream_t st);
 hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* new_w, float lr,
                              int64_t n, hipStream_t st);

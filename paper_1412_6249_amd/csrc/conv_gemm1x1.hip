@@ -234,9 +234,12 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
         n = fastdiv(m0, p.div_howo);
         pix = m0 - n * p.HoWo;
     }
-    // reduction step ks reads channel rows 2*ks + khalf; KS steps in all (Ci is a multiple of 16)
-    const int KS = p.Ci >> 1;
-    const T* src = in + (size_t)n * p.in_ns + (size_t)khalf * p.HoWo + pix;
+    // this workgroup's part of the reduction: all of it, or split blockIdx.y's channels
+    const int c_begin = p.splits > 1 ? (int)blockIdx.y * p.split_ci : 0;
+    const int c_end = p.splits > 1 ? min(c_begin + p.split_ci, p.Ci) : p.Ci;
+    // reduction step ks reads channel rows c_begin + 2*ks + khalf; KS steps in all (multiples of 16 channels)
+    const int KS = (c_end - c_begin) >> 1;
+    const T* src = in + (size_t)n * p.in_ns + (size_t)(c_begin + khalf) * p.HoWo + pix;
     const size_t step = (size_t)2 * p.HoWo;
 
     // Two register sets of DEPTH reduction steps each: the loads of the next group are all issued
@@ -262,9 +265,9 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
 
-    for (int c0 = 0; c0 < p.Ci; c0 += CK) {
-        const int ck = p.Ci - c0 < CK ? p.Ci - c0 : CK;
-        if (c0 > 0) __syncthreads();       // everyone is done with the previous part of the filter
+    for (int c0 = c_begin; c0 < c_end; c0 += CK) {
+        const int ck = c_end - c0 < CK ? c_end - c0 : CK;
+        if (c0 > c_begin) __syncthreads(); // everyone is done with the previous part of the filter
         fill_filter<T, TRANS, TM, CK>(As, wt, i0, c0, ck, p.Ci, p.Co, tid);
         __syncthreads();
 
@@ -299,9 +302,62 @@ __global__ __launch_bounds__(256, (TM * TN <= 6 ? 3 : 2)) void gemm1x1_kernel(co
     }
 
     if (!live) return;
+    if (p.splits > 1) {
+        // raw fp32 tile of this split, dense [N][Co][Ho*Wo]; the second kernel applies the epilogue
+        PixParams q = p;
+        q.out = p.partial + (size_t)blockIdx.y * p.N * p.Co * p.HoWo;
+        q.out_ns = p.Co * p.HoWo;
+        q.beta = 0.0f; q.bias = nullptr; q.mask = nullptr; q.relu = 0;
+        const size_t pbase = (size_t)n * q.out_ns + pix;
+#pragma unroll
+        for (int a = 0; a < TM; ++a) store_rows<float, false, TN, true>(q, acc[a], i0 + a * 32 + khalf * 4, pbase, bias_s, i0);
+        return;
+    }
     const size_t obase = (size_t)n * p.out_ns + pix;
 #pragma unroll
     for (int a = 0; a < TM; ++a) store_rows<T, FUSED, TN, !TRANS>(p, acc[a], i0 + a * 32 + khalf * 4, obase, bias_s, i0);
+}
+
+// Second pass of the split reduction: out = epilogue(sum over splits, in order, of partial[s]), V
+// consecutive pixels per thread.
+template <typename T, int V>
+__global__ __launch_bounds__(256) void gemm1x1_reduce_kernel(const PixParams p, int fwd) {
+    const long long groups = (long long)p.N * p.Co * (p.HoWo / V);
+    const size_t split_stride = (size_t)p.N * p.Co * p.HoWo;
+    const int per_row = p.HoWo / V;
+    for (long long gidx = (long long)blockIdx.x * 256 + threadIdx.x; gidx < groups; gidx += (long long)gridDim.x * 256) {
+        const long long row = gidx / per_row;                  // n * Co + i
+        const int pg = (int)(gidx - row * per_row);
+        const int n = (int)(row / p.Co), i = (int)(row - (long long)n * p.Co);
+        const float* src = p.partial + (size_t)row * p.HoWo + (size_t)pg * V;
+        float v[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) v[e] = 0.0f;
+        for (int s = 0; s < p.splits; ++s) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[e] += src[(size_t)s * split_stride + e];
+        }
+        const size_t o = (size_t)n * p.out_ns + (size_t)i * p.HoWo + (size_t)pg * V;
+        if (fwd && p.bias) {
+            const float b = Elem<T>::load((const T*)p.bias, i);
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[e] += b;
+        }
+        if (fwd && p.relu) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[e] = v[e] > 0.0f ? v[e] : 0.0f;
+        }
+        if (!fwd && p.mask) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[e] = Elem<T>::load((const T*)p.mask, (int)(o + e)) > 0.0f ? v[e] : 0.0f;
+        }
+        if (!fwd && p.beta != 0.0f) {
+#pragma unroll
+            for (int e = 0; e < V; ++e) v[e] += Elem<T>::load((const T*)p.out, (int)(o + e));
+        }
+#pragma unroll
+        for (int e = 0; e < V; ++e) Elem<T>::store((T*)p.out, (int)(o + e), v[e]);
+    }
 }
 
 template <typename T, bool TRANS, bool FUSED, int TM, int TN>
@@ -310,7 +366,13 @@ hipError_t launch_one(const PixParams& p, hipStream_t st) {
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-    hipLaunchKernelGGL((gemm1x1_kernel<T, TRANS, FUSED, TM, TN>), dim3((unsigned)total), dim3(256), 0, st, p);
+    const unsigned splits = p.splits > 1 ? (unsigned)p.splits : 1u;
+    hipLaunchKernelGGL((gemm1x1_kernel<T, TRANS, FUSED, TM, TN>), dim3((unsigned)total, splits), dim3(256), 0, st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    const long long groups = (long long)p.N * p.Co * (p.HoWo / TN);
+    const unsigned blocks = (unsigned)((groups + 255) / 256 > 8192 ? 8192 : (groups + 255) / 256);
+    hipLaunchKernelGGL((gemm1x1_reduce_kernel<T, TN>), dim3(blocks), dim3(256), 0, st, p, TRANS ? 0 : 1);
     return hipGetLastError();
 }
 
@@ -342,6 +404,7 @@ hipError_t by_mode(const PixParams& p, bool trans, int tm, int tn, hipStream_t s
 // and mask are aligned to tn elements.
 hipError_t dispatch_gemm1x1(const PixParams& p, int dtype, bool trans, int tm, int tn, hipStream_t st) {
     if (p.Ci < 2 * DEPTH || (p.Ci & 15) || (p.HoWo % tn) != 0) return hipErrorInvalidValue;
+    if (p.splits > 1 && (!p.partial || p.split_ci < CK || p.split_ci % CK != 0)) return hipErrorInvalidValue;
     return dtype == PURINE_F32 ? by_mode<float>(p, trans, tm, tn, st) : by_mode<uint16_t>(p, trans, tm, tn, st);
 }
 

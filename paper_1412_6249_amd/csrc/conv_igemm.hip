@@ -736,6 +736,31 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
         if (forced) { pl.gemm_tm = g_force_bm / 32; pl.gemm_tn = g_force_bn; }
         pl.gemm_tiles_i = (Co + pl.gemm_tm * 32 - 1) / (pl.gemm_tm * 32);
         pl.gemm_tiles_pix = (int)((M + 4 * 32 * pl.gemm_tn - 1) / (4 * 32 * pl.gemm_tn));
+        // Too few tiles for 256 CUs and a long reduction (fully-connected backward-data: 128 rows x 9216
+        // pixels over 4096 channels = 72 tiles): split the channels in whole 128-channel filter stages
+        // so that about 2.5 workgroups per CU run, fp32 partial tiles behind the filter copy.
+        pl.gemm_splits = 1; pl.gemm_split_ci = Ci; pl.gemm_part_offset = 0;
+        const long long tiles = (long long)pl.gemm_tiles_i * pl.gemm_tiles_pix;
+        const int stages = (Ci + 127) / 128;
+        if (tiles < 320 && stages >= 4 && g_force_bm != -3) {
+            // stages per split: the kernel lasts (workgroups of the busiest CU) x (stages per workgroup),
+            // the second pass about 0.15 of a stage per split; at least two stages per split
+            int per = stages;
+            double best_t = -1.0;
+            for (int c = stages; c >= 2; --c) {
+                const int sp = (stages + c - 1) / c;
+                const long long rounds = (tiles * sp + 255) / 256;
+                const double t = (double)rounds * c + 0.15 * sp;
+                if (best_t < 0 || t < best_t) { best_t = t; per = c; }
+            }
+            const int splits = (stages + per - 1) / per;
+            const unsigned long long part = (unsigned long long)splits * (unsigned long long)g.N * Co * HW * 4ull;
+            if (splits > 1 && part <= (256ull << 20)) {
+                pl.gemm_splits = splits; pl.gemm_split_ci = per * 128;
+                pl.gemm_part_offset = (pl.ws_bytes + 255) / 256 * 256;
+                pl.ws_bytes = pl.gemm_part_offset + (size_t)part;
+            }
+        }
     }
     return pl;
 }
@@ -754,6 +779,11 @@ hipError_t launch_conv_pix(int dtype, const ConvGeom& g, const PixPlan& pl, cons
             PixParams q = p;
             q.wt = wt;
             q.tiles_i = pl.gemm_tiles_i; q.tiles_pix = pl.gemm_tiles_pix;
+            if (pl.gemm_splits > 1) {
+                if (!ws) return hipErrorInvalidValue;
+                q.splits = pl.gemm_splits; q.split_ci = pl.gemm_split_ci;
+                q.partial = (float*)((char*)ws + pl.gemm_part_offset);
+            }
             return dispatch_gemm1x1(q, dtype, pl.mode == 1, pl.gemm_tm, pl.gemm_tn, st);
         }
     }

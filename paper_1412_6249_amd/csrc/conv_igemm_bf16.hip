@@ -74,7 +74,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         g_h = ho * p.g_mul_h + p.g_add_h;
         g_w = wo * p.g_mul_w + p.g_add_w;
         // FLAT: element offset in NCHW; otherwise offset in 8-channel blocks of the blocked copy
-        g_off = n * (ELEMS ? p.Ci : p.Ci_pad / 8) * p.HiWi + g_h * p.Wi + g_w;
+        g_off = n * (ELEMS ? p.in_ns : (p.Ci_pad / 8) * p.HiWi) + g_h * p.Wi + g_w;
     }
     const int ch_base = __builtin_amdgcn_readfirstlane(tid / BN) * CH;   // uniform per wavefront
     // the blocked copy as a raw buffer (not used by the 2-byte gather modes)
@@ -240,13 +240,13 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 
 // NCHW -> [N][CBp][HW][8]: thread = (image, channel block, pixel); channels past C are zero.
 __global__ __launch_bounds__(256) void blockify_kernel(const uint16_t* __restrict__ src, uint4* __restrict__ dst,
-                                                       int C, int HW, int CBp, long long total) {
+                                                       int C, int HW, int CBp, long long total, long long src_ns) {
     for (long long o = (long long)blockIdx.x * 256 + threadIdx.x; o < total; o += (long long)gridDim.x * 256) {
         const long long plane = o / HW;                  // n * CBp + cb
         const int pix = (int)(o - plane * HW);
         const int cb = (int)(plane % CBp);
         const long long n = plane / CBp;
-        const uint16_t* s = src + (n * C + (long long)cb * 8) * HW + pix;
+        const uint16_t* s = src + n * src_ns + (long long)cb * 8 * HW + pix;
         uint32_t v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = cb * 8 + e < C ? (uint32_t)s[(long long)e * HW] : 0u;
@@ -291,7 +291,7 @@ hipError_t blockify_input(PixParams& p, void* blocked, hipStream_t st) {
     const long long blocks = (total + 255) / 256;
     (void)hipGetLastError();
     hipLaunchKernelGGL(blockify_kernel, dim3((unsigned)(blocks > 1048576 ? 1048576 : blocks)), dim3(256), 0, st,
-                       (const uint16_t*)p.in, (uint4*)blocked, p.Ci, p.HiWi, CBp, total);
+                       (const uint16_t*)p.in, (uint4*)blocked, p.Ci, p.HiWi, CBp, total, (long long)p.in_ns);
     p.in = blocked;
     return hipGetLastError();
 }

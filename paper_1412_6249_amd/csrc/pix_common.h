@@ -79,6 +79,11 @@ struct PixParams {
     // elements between consecutive images of the gathered and of the produced tensor (the mask shares
     // the latter): Ci*Hi*Wi and the dense image size of `out` unless they are channel-slice views
     int in_ns, out_ns;
+    // split reduction of the 1x1 streaming GEMM (GEMMs with too few tiles to fill the chip): blockIdx.y
+    // takes `split_ci` gathered channels and writes a raw fp32 tile into partial[split][N][Co][Ho*Wo];
+    // a second kernel adds the splits in a fixed order and applies the epilogue. splits <= 1: off.
+    int splits, split_ci;
+    float* partial;
 };
 
 // The fused forward kernels stage their row tile's bias values in LDS at kernel start (zero past the

@@ -150,28 +150,30 @@ __global__ __launch_bounds__(TPB) void relu_fwd_kernel(const T* x, T* y, size_t 
         stf<T>(y, i, v > 0.0f ? v : 0.0f);
     }
 }
-// ReLU and its gradient on channel-slice views (fp32): grid.y = image, each image a dense run of
-// `run` elements at its own distance between images. VEC: run and the distances are multiples of 4.
-template <bool BWD, bool VEC>
-__global__ __launch_bounds__(TPB) void relu_view_kernel(const float* x, const float* dy, float* out,
+// ReLU and its gradient on channel-slice views: grid.y = image, each image a dense run of `run`
+// elements at its own distance between images. VEC: run and the distances are whole 16-byte packets.
+template <typename T, bool BWD, bool VEC>
+__global__ __launch_bounds__(TPB) void relu_view_kernel(const T* x, const T* dy, T* out,
                                                         int run, size_t x_ns, size_t dy_ns, size_t out_ns) {
     const size_t n = blockIdx.y;
-    const float* xi = x + n * x_ns;
-    const float* gi = BWD ? dy + n * dy_ns : nullptr;
-    float* oi = out + n * out_ns;
+    const T* xi = x + n * x_ns;
+    const T* gi = BWD ? dy + n * dy_ns : nullptr;
+    T* oi = out + n * out_ns;
     const int t0 = blockIdx.x * TPB + threadIdx.x, stride = gridDim.x * TPB;
     if (VEC) {
-        for (int i = t0; i < run / 4; i += stride) {
-            const float4 v = reinterpret_cast<const float4*>(xi)[i];
-            float4 g = BWD ? reinterpret_cast<const float4*>(gi)[i] : v;
-            g.x = v.x > 0.0f ? g.x : 0.0f; g.y = v.y > 0.0f ? g.y : 0.0f;
-            g.z = v.z > 0.0f ? g.z : 0.0f; g.w = v.w > 0.0f ? g.w : 0.0f;
-            reinterpret_cast<float4*>(oi)[i] = g;
+        constexpr int V = Pk<T>::N;
+        for (int i = t0; i < run / V; i += stride) {
+            float v[V], g[V];
+            Pk<T>::unpack(reinterpret_cast<const uint4*>(xi)[i], v);
+            if (BWD) Pk<T>::unpack(reinterpret_cast<const uint4*>(gi)[i], g);
+#pragma unroll
+            for (int e = 0; e < V; ++e) g[e] = v[e] > 0.0f ? (BWD ? g[e] : v[e]) : 0.0f;
+            reinterpret_cast<uint4*>(oi)[i] = Pk<T>::pack(g);
         }
     } else {
         for (int i = t0; i < run; i += stride) {
-            const float v = xi[i];
-            oi[i] = v > 0.0f ? (BWD ? gi[i] : v) : 0.0f;
+            const float v = ldf<T>(xi, i);
+            stf<T>(oi, i, v > 0.0f ? (BWD ? ldf<T>(gi, i) : v) : 0.0f);
         }
     }
 }
@@ -180,6 +182,34 @@ __global__ __launch_bounds__(TPB) void relu_view_kernel(const float* x, const fl
 __global__ __launch_bounds__(TPB) void bias_rows_kernel(const float* __restrict__ b, float* y, int K, size_t n) {
     const size_t stride = (size_t)gridDim.x * TPB;
     for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += stride) y[i] += b[i % (size_t)K];
+}
+
+// bf16 fully-connected forward, last step: y[n][k] = bf16(acc[n][k] + b[k]) from the fp32 product
+// matrix (one rounding, to nearest even, after the bias is added in fp32). b may be null.
+__global__ __launch_bounds__(TPB) void fc_finish_bf16_kernel(const float* __restrict__ acc, const uint16_t* __restrict__ b,
+                                                             uint16_t* __restrict__ y, int K, size_t n) {
+    const size_t stride = (size_t)gridDim.x * TPB;
+    for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += stride)
+        y[i] = f2bf(acc[i] + (b ? bf2f(b[i % (size_t)K]) : 0.0f));
+}
+
+// out[c][r] = in[r][c] for a dense 2-byte matrix of `rows` x `cols` elements; 64x64 tiles through
+// LDS (row pitch 65 elements: a tile column read walks through different banks in pairs)
+__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                          int rows, int cols) {
+    __shared__ uint16_t tile[64][66];
+    const int tiles_c = (cols + 63) / 64;
+    const int r0 = (int)(blockIdx.x / tiles_c) * 64, c0 = (int)(blockIdx.x % tiles_c) * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int j = ty; j < 64; j += 4) {
+        const int r = r0 + j, c = c0 + tx;
+        tile[j][tx] = (r < rows && c < cols) ? in[(size_t)r * cols + c] : (uint16_t)0;
+    }
+    __syncthreads();
+    for (int j = ty; j < 64; j += 4) {
+        const int c = c0 + j, r = r0 + tx;
+        if (c < cols && r < rows) out[(size_t)c * rows + r] = tile[tx][j];
+    }
 }
 
 // ---- SGD update: new_w = w - lr * dw (one fused multiply-add in fp32 per element) ---------------
@@ -557,17 +587,37 @@ hipError_t launch_bias_rows(const float* b, float* y, int N, int K, hipStream_t 
     return hipGetLastError();
 }
 
-hipError_t launch_relu_view(bool bwd, const float* x, const float* dy, float* out, int N, int run,
+hipError_t launch_fc_finish_bf16(const float* acc, const void* b, void* y, int N, int K, hipStream_t st) {
+    const size_t n = (size_t)N * K;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(fc_finish_bf16_kernel, dim3(blocks_for(n)), dim3(TPB), 0, st, acc, (const uint16_t*)b,
+                       (uint16_t*)y, K, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose16(const void* in, void* out, int rows, int cols, hipStream_t st) {
+    const long long tiles = (long long)((rows + 63) / 64) * ((cols + 63) / 64);
+    if (rows < 1 || cols < 1 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(transpose16_kernel, dim3((unsigned)tiles), dim3(256), 0, st, (const uint16_t*)in,
+                       (uint16_t*)out, rows, cols);
+    return hipGetLastError();
+}
+
+hipError_t launch_relu_view(int dtype, bool bwd, const void* x, const void* dy, void* out, int N, int run,
                             int64_t x_ns, int64_t dy_ns, int64_t out_ns, hipStream_t st) {
-    const bool vec = run % 4 == 0 && x_ns % 4 == 0 && dy_ns % 4 == 0 && out_ns % 4 == 0;
-    dim3 grid(blocks_for((size_t)(vec ? run / 4 : run), 64), (unsigned)N);
+    const int V = dtype == PURINE_BF16 ? 8 : 4;
+    const bool vec = run % V == 0 && x_ns % V == 0 && dy_ns % V == 0 && out_ns % V == 0;
+    dim3 grid(blocks_for((size_t)(vec ? run / V : run), 64), (unsigned)N);
     if (N > 65535) return hipErrorInvalidValue;
     ProbeScope probe(st);
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
-#define RV(B, V) hipLaunchKernelGGL((relu_view_kernel<B, V>), grid, dim3(TPB), 0, st, x, dy, out, run, \
-                                    (size_t)x_ns, (size_t)dy_ns, (size_t)out_ns)
-    if (bwd) { if (vec) RV(true, true); else RV(true, false); }
-    else     { if (vec) RV(false, true); else RV(false, false); }
+#define RV(T, B, V) hipLaunchKernelGGL((relu_view_kernel<T, B, V>), grid, dim3(TPB), 0, st, (const T*)x, (const T*)dy, \
+                                       (T*)out, run, (size_t)x_ns, (size_t)dy_ns, (size_t)out_ns)
+#define RV2(T) do { if (bwd) { if (vec) RV(T, true, true); else RV(T, true, false); }                     \
+                    else     { if (vec) RV(T, false, true); else RV(T, false, false); } } while (0)
+    if (dtype == PURINE_BF16) RV2(uint16_t); else RV2(float);
+#undef RV2
 #undef RV
     return hipGetLastError();
 }

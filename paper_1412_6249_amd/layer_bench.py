@@ -126,23 +126,25 @@ def time_whole(fn, iters, warmup=5):
     return ms[len(ms) // 2], ms[0]
 
 
-def bench_fc(N, C, K, iters, out=sys.stdout):
-    """The three passes of a fully-connected layer [N, C] x [K, C] (fp32)."""
+def bench_fc(N, C, K, iters, dtype="f32", out=sys.stdout):
+    """The three passes of a fully-connected layer [N, C] x [K, C]."""
     dev = "cuda:0"
-    x, w, b = torch.rand(N, C, device=dev), torch.randn(K, C, device=dev) * 0.01, torch.zeros(K, device=dev)
-    dy = torch.rand(N, K, device=dev) * 2 - 1
-    y, dx = torch.empty(N, K, device=dev), torch.empty(N, C, device=dev)
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    x, w, b = torch.rand(N, C, device=dev).to(td), (torch.randn(K, C, device=dev) * 0.01).to(td), torch.zeros(K, device=dev, dtype=td)
+    dy = (torch.rand(N, K, device=dev) * 2 - 1).to(td)
+    y, dx = torch.empty(N, K, device=dev, dtype=td), torch.empty(N, C, device=dev, dtype=td)
     dw, db = torch.empty(K, C, device=dev), torch.empty(K, device=dev)
-    ws = [torch.empty(max(256, B.purine_fc_workspace_bytes(p, N, C, K)), dtype=torch.uint8, device=dev) for p in (0, 1, 2)]
+    code = B.PURINE_BF16 if dtype == "bf16" else B.PURINE_F32
+    ws = [torch.empty(max(256, B.purine_fc_workspace_bytes(p, N, C, K, code)), dtype=torch.uint8, device=dev) for p in (0, 1, 2)]
     flop = 2.0 * N * C * K
-    w_bytes = 4.0 * K * C
+    w_bytes = (2.0 if dtype == "bf16" else 4.0) * K * C
     passes = (("fc_fwd", lambda: B.purine_fc_fwd(x, w, b, y, ws=ws[0])),
               ("fc_bwd_data", lambda: B.purine_fc_bwd_data(dy, w, dx, ws=ws[1])),
               ("fc_bwd_weight", lambda: B.purine_fc_bwd_weight(x, dy, dw, db, ws=ws[2])))
     for name, fn in passes:
         med, best = time_whole(fn, iters)
-        out.write("fc %dx%d->%d  %-14s %8.4f ms (best %8.4f)  %7.2f TFLOP/s  %5.1f%% of f32 MFMA peak  weights at %6.0f GB/s\n"
-                  % (N, C, K, name, med, best, flop / med / 1e9, 100 * flop / med / 1e9 / PEAK["f32"], w_bytes / med / 1e6))
+        out.write("fc %dx%d->%d %s %-14s %8.4f ms (best %8.4f)  %7.2f TFLOP/s  %5.1f%% of %s MFMA peak  weights at %6.0f GB/s\n"
+                  % (N, C, K, dtype, name, med, best, flop / med / 1e9, 100 * flop / med / 1e9 / PEAK[dtype], dtype, w_bytes / med / 1e6))
 
 
 def bench_grouped(L, groups, iters, out=sys.stdout):
@@ -179,13 +181,14 @@ def main():
     ap.add_argument("--copy-cal", type=int, default=0, metavar="MiB",
                     help="run only a plain device copy of this many MiB (counter calibration)")
     ap.add_argument("--fc", default=None, metavar="N,C,K", help="time a fully-connected layer instead")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"], help="dtype of the --fc layer")
     ap.add_argument("--groups", type=int, default=0, help="time the grouped variant of the selected layers")
     a = ap.parse_args()
     if a.copy_cal:
         copy_calibration(a.copy_cal)
         return
     if a.fc:
-        bench_fc(*[int(v) for v in a.fc.split(",")], a.iters)
+        bench_fc(*[int(v) for v in a.fc.split(",")], a.iters, a.dtype)
         return
     if a.tile:
         B.purine_debug_force_tile(*[int(v) for v in a.tile.split(",")])

@@ -191,8 +191,11 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_conv_bwd_data, d, y, w, xv, stream=s) == -5                # accepted up to the workspace
     assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, F32, (2, 3, 8, 8), nstride=3 * 64 - 4), w, y, stream=s) == -2
     assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, F32, (2, 3, 8, 8), nstride=12 * 64 + 2), w, y, stream=s) == -4
-    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, BF16, (2, 3, 8, 8), nstride=12 * 64),
-                  binding.raw_desc(fake + 0x100000, BF16, (4, 3, 3, 3)), binding.raw_desc(fake + 0x200000, BF16, (2, 4, 8, 8)), stream=s) == -4
+    wb3 = binding.raw_desc(fake + 0x100000, BF16, (4, 3, 3, 3))
+    yb3 = binding.raw_desc(fake + 0x200000, BF16, (2, 4, 8, 8))
+    # bf16 views: the distance between images is a whole number of 8-element packets
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, BF16, (2, 3, 8, 8), nstride=12 * 64 + 4), wb3, yb3, stream=s) == -4
+    assert status(pa.purine_conv_fwd, d, binding.raw_desc(fake, BF16, (2, 3, 8, 8), nstride=12 * 64), wb3, yb3, stream=s) == -5
     yv = binding.raw_desc(fake + 0x200000, F32, (2, 4, 8, 8), nstride=16 * 64)
     assert status(pa.purine_bias_fwd, binding.raw_desc(fake + 0x400000, F32, (4,)), yv, stream=s) == -4   # dense only
     assert status(pa.purine_bias_bwd, yv, db, stream=s) == -4
@@ -217,7 +220,10 @@ def test_operator_argument_validation_without_launch():
                   binding.raw_desc(fake + 0x200000, F32, (2, 8, 5, 5)), stream=s) == -4         # 3*25 elements per slice
     assert status(pa.purine_grouped_conv_fwd, d, 2, binding.raw_desc(fake, BF16, (2, 8, 6, 6)),
                   binding.raw_desc(fake + 0x100000, BF16, (8, 4, 3, 3)), None,
-                  binding.raw_desc(fake + 0x200000, BF16, (2, 8, 6, 6)), stream=s) == -3
+                  binding.raw_desc(fake + 0x200000, BF16, (2, 8, 6, 6)), stream=s) == -4         # K/G = 4 bf16 bias values
+    assert status(pa.purine_grouped_conv_fwd, d, 2, binding.raw_desc(fake, BF16, (2, 16, 6, 6)),
+                  binding.raw_desc(fake + 0x100000, BF16, (16, 8, 3, 3)), None,
+                  binding.raw_desc(fake + 0x200000, BF16, (2, 16, 6, 6)), stream=s) == -5        # accepted up to the workspace
     assert pa.purine_grouped_conv_workspace_bytes(0, d, 2, (2, 8, 6, 6), (8, 4, 3, 3), F32) == \
         pa.purine_conv_workspace_bytes(0, d, (2, 4, 6, 6), (4, 4, 3, 3), F32)
     fx = binding.raw_desc(fake, F32, (4, 20))
@@ -228,7 +234,13 @@ def test_operator_argument_validation_without_launch():
     assert status(pa.purine_fc_fwd, fx, fw, None, binding.raw_desc(fake + 0x200000, BF16, (4, 6)), stream=s) == -3
     assert status(pa.purine_fc_bwd_data, fy, fw, binding.raw_desc(fake, F32, (4, 21)), stream=s) == -2
     assert status(pa.purine_fc_bwd_weight, fx, fy, binding.raw_desc(fake + 0x300000, F32, (6, 20)), None, beta=0.5, stream=s) == -8
+    assert status(pa.purine_fc_fwd, binding.raw_desc(fake, BF16, (4, 20)), binding.raw_desc(fake + 0x100000, BF16, (6, 20)),
+                  None, binding.raw_desc(fake + 0x200000, BF16, (4, 6)), stream=s) == -5         # bf16: accepted up to the workspace
+    assert status(pa.purine_fc_bwd_weight, binding.raw_desc(fake, BF16, (4, 20)), binding.raw_desc(fake + 0x200000, BF16, (4, 6)),
+                  binding.raw_desc(fake + 0x300000, BF16, (6, 20)), None, stream=s) == -3        # dw is fp32
     assert pa.purine_fc_workspace_bytes(0, 4, 20, 6) > 0 and pa.purine_fc_workspace_bytes(7, 4, 20, 6) == 0
+    assert pa.purine_fc_workspace_bytes(0, 4, 20, 6, BF16) >= 4 * 6 * 4 and pa.purine_fc_workspace_bytes(2, 4, 20, 6, BF16) >= 2 * (4 * 20 + 4 * 6)
+    assert pa.purine_fc_workspace_bytes(0, 4, 20, 6, pa.PURINE_I32) == 0
     big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
     assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
     assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8

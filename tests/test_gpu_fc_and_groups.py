@@ -1,6 +1,7 @@
 """Fully-connected layer and grouped convolution on the GPU (compositions of the convolution
 operators: reinterpreted descriptors and channel-slice views) against the oracle, element by
-element. fp32: relative L2 <= 1e-5; small-integer inputs bit for bit."""
+element. fp32: relative L2 <= 1e-5; bf16: 1e-2 for bf16 results, 1e-4 for the fp32 gradients;
+small-integer inputs bit for bit."""
 import numpy as np
 import pytest
 
@@ -12,43 +13,49 @@ pytestmark = pytest.mark.gpu
 FC_CASES = [(1, 1, 1), (3, 5, 4), (7, 300, 33), (128, 1000, 130), (32, 2304, 512), (130, 64, 1000)]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("N,C,K", FC_CASES)
-def test_fc_layer(N, C, K):
+def test_fc_layer(N, C, K, dtype):
     import torch
     import paper_1412_6249_amd as pa
-    from gpu_util import rel_l2, workspace, DEV
+    from gpu_util import rel_l2, workspace, to_dev, to_host, tdtype, pcode, TOL, DEV
+    from synth import gen
     rs = np.random.default_rng(N * 1000003 + C * 1009 + K)
+    tol = TOL[dtype]
+    gtol = 1e-5 if dtype == "f32" else 1e-4       # dw and db: fp32 sums of exact products in both dtypes
     for integer in (False, True):
         d = (lambda *s: rs.integers(-2, 3, size=s).astype(np.float32)) if integer else \
             (lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32))
         x, w, b, dy = d(N, C), d(K, C), d(K), d(N, K)
-        dev = lambda a: torch.from_numpy(a).to(DEV)
-        tx, tw, tb, tdy = dev(x), dev(w), dev(b), dev(dy)
-        ty = torch.full((N, K), float("nan"), device=DEV)
-        tdx = torch.full((N, C), float("nan"), device=DEV)
+        if dtype == "bf16":
+            x, w, b, dy = (gen.quantize_bf16(a) for a in (x, w, b, dy))
+        tx, tw, tb, tdy = to_dev(x, dtype), to_dev(w, dtype), to_dev(b, dtype), to_dev(dy, dtype)
+        ty = torch.full((N, K), float("nan"), dtype=tdtype(dtype), device=DEV)
+        tdx = torch.full((N, C), float("nan"), dtype=tdtype(dtype), device=DEV)
         tdw = torch.full((K, C), float("nan"), device=DEV)
         tdb = torch.full((K,), float("nan"), device=DEV)
-        q = lambda which: workspace(pa.purine_fc_workspace_bytes(which, N, C, K))
+        q = lambda which: workspace(pa.purine_fc_workspace_bytes(which, N, C, K, pcode(dtype)))
         pa.purine_fc_fwd(tx, tw, tb, ty, ws=q(pa.PURINE_CONV_FWD))
         pa.purine_fc_bwd_data(tdy, tw, tdx, ws=q(pa.PURINE_CONV_BWD_DATA))
         pa.purine_fc_bwd_weight(tx, tdy, tdw, tdb, ws=q(pa.PURINE_CONV_BWD_WEIGHT))
         torch.cuda.synchronize()
         ref_dw, ref_db = oracle.fc_bwd_weight(x, dy)
-        pairs = (("y", ty, oracle.fc_fwd(x, w, b)), ("dx", tdx, oracle.fc_bwd_data(dy, w)),
-                 ("dw", tdw, ref_dw), ("db", tdb, ref_db))
-        for name, got, ref in pairs:
-            g = got.cpu().numpy()
-            if integer:
+        pairs = (("y", ty, oracle.fc_fwd(x, w, b), tol), ("dx", tdx, oracle.fc_bwd_data(dy, w), tol),
+                 ("dw", tdw, ref_dw, gtol), ("db", tdb, ref_db, gtol))
+        for name, got, ref, t in pairs:
+            g = to_host(got)
+            if integer and (dtype == "f32" or name in ("dw", "db") or np.abs(ref).max() <= 256):
+                # every sum is an integer below 2^24: exact in fp32; bf16 outputs hold integers up to 256 exactly
                 assert np.abs(ref).max() < 2 ** 24 and np.array_equal(g, ref.astype(np.float32)), name
             else:
-                assert np.isfinite(g).all() and rel_l2(g, ref) <= 1e-5, (name, rel_l2(g, ref))
+                assert np.isfinite(g).all() and rel_l2(g, ref) <= t, (name, rel_l2(g, ref))
         if not integer:
             # accumulate form of the weight and bias gradients, and a forward pass without bias
             pa.purine_fc_bwd_weight(tx, tdy, tdw, tdb, beta=1.0, ws=q(pa.PURINE_CONV_BWD_WEIGHT))
             pa.purine_fc_fwd(tx, tw, None, ty, ws=q(pa.PURINE_CONV_FWD))
             torch.cuda.synchronize()
-            assert rel_l2(tdw.cpu().numpy(), 2 * ref_dw) <= 1e-5 and rel_l2(tdb.cpu().numpy(), 2 * ref_db) <= 1e-5
-            assert rel_l2(ty.cpu().numpy(), oracle.fc_fwd(x, w)) <= 1e-5
+            assert rel_l2(tdw.cpu().numpy(), 2 * ref_dw) <= gtol and rel_l2(tdb.cpu().numpy(), 2 * ref_db) <= gtol
+            assert rel_l2(to_host(ty), oracle.fc_fwd(x, w)) <= tol
 
 
 # name, groups, N, C, H, W, K, R, S, stride, pad: AlexNet's two-group layers at reduced size, plus ragged ones
@@ -61,40 +68,48 @@ GROUP_CASES = [
 ]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", GROUP_CASES, ids=[c[0] for c in GROUP_CASES])
-def test_grouped_convolution(case):
+def test_grouped_convolution(case, dtype):
     import torch
     import paper_1412_6249_amd as pa
-    from gpu_util import rel_l2, workspace, DEV
+    from gpu_util import rel_l2, workspace, to_dev, to_host, tdtype, pcode, TOL, DEV
+    from synth import gen
     name, G, N, C, H, W, K, R, S, stride, pad = case
+    if dtype == "bf16" and G > 1 and ((C // G * H * W) % 8 or (K // G) % 8):
+        pytest.skip("bf16 group slices must start on whole 16-byte packets (8 elements)")
     rs = np.random.default_rng(len(name) * 7919 + C)
     u = lambda *s: rs.uniform(-1, 1, size=s).astype(np.float32)
     x, w, b = u(N, C, H, W), u(K, C // G, R, S), u(K)
+    if dtype == "bf16":
+        x, w, b = gen.quantize_bf16(x), gen.quantize_bf16(w), gen.quantize_bf16(b)
     ref_y = oracle.grouped_conv_fwd(x, w, G, stride, pad)
     dy = u(*ref_y.shape)
-    dev = lambda a: torch.from_numpy(a).to(DEV)
-    tx, tw, tb, tdy = dev(x), dev(w), dev(b), dev(dy)
-    ty = torch.full(ref_y.shape, float("nan"), device=DEV)
-    tdx = torch.full(x.shape, float("nan"), device=DEV)
+    if dtype == "bf16":
+        dy = gen.quantize_bf16(dy)
+    tx, tw, tb, tdy = to_dev(x, dtype), to_dev(w, dtype), to_dev(b, dtype), to_dev(dy, dtype)
+    ty = torch.full(ref_y.shape, float("nan"), dtype=tdtype(dtype), device=DEV)
+    tdx = torch.full(x.shape, float("nan"), dtype=tdtype(dtype), device=DEV)
     tdw = torch.full(w.shape, float("nan"), device=DEV)
     tdb = torch.full((K,), float("nan"), device=DEV)
     desc = pa.conv_desc(stride, pad)
-    q = lambda which: workspace(pa.purine_grouped_conv_workspace_bytes(which, desc, G, x.shape, w.shape, pa.PURINE_F32))
+    q = lambda which: workspace(pa.purine_grouped_conv_workspace_bytes(which, desc, G, x.shape, w.shape, pcode(dtype)))
     pa.purine_grouped_conv_fwd(desc, G, tx, tw, tb, ty, relu=True, ws=q(pa.PURINE_CONV_FWD))
     pa.purine_grouped_conv_bwd_data(desc, G, tdy, tw, tdx, ws=q(pa.PURINE_CONV_BWD_DATA))
     pa.purine_grouped_conv_bwd_weight(desc, G, tx, tdy, tdw, tdb, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))
     torch.cuda.synchronize()
-    tol = 1e-5
-    assert rel_l2(ty.cpu().numpy(), np.maximum(oracle.bias_fwd(ref_y, b), 0)) <= tol, "fwd"
-    assert rel_l2(tdx.cpu().numpy(), oracle.grouped_conv_bwd_data(dy, w, x.shape, G, stride, pad)) <= tol, "bwd_data"
-    assert rel_l2(tdw.cpu().numpy(), oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)) <= tol, "bwd_weight"
-    assert rel_l2(tdb.cpu().numpy(), oracle.bias_bwd(dy)) <= tol, "bias_bwd"
+    tol = TOL[dtype]
+    wtol = 1e-5 if dtype == "f32" else 1e-4                        # dw and db are fp32 sums of exact products
+    assert rel_l2(to_host(ty), np.maximum(oracle.bias_fwd(ref_y, b), 0)) <= tol, "fwd"
+    assert rel_l2(to_host(tdx), oracle.grouped_conv_bwd_data(dy, w, x.shape, G, stride, pad)) <= tol, "bwd_data"
+    assert rel_l2(tdw.cpu().numpy(), oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)) <= wtol, "bwd_weight"
+    assert rel_l2(tdb.cpu().numpy(), oracle.bias_bwd(dy)) <= 1e-5, "bias_bwd"
     # no bias, no db
     pa.purine_grouped_conv_fwd(desc, G, tx, tw, None, ty, relu=False, ws=q(pa.PURINE_CONV_FWD))
     pa.purine_grouped_conv_bwd_weight(desc, G, tx, tdy, tdw, None, beta=1.0, ws=q(pa.PURINE_CONV_BWD_WEIGHT_BIAS))
     torch.cuda.synchronize()
-    assert rel_l2(ty.cpu().numpy(), ref_y) <= tol
-    assert rel_l2(tdw.cpu().numpy(), 2 * oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)) <= tol
+    assert rel_l2(to_host(ty), ref_y) <= tol
+    assert rel_l2(tdw.cpu().numpy(), 2 * oracle.grouped_conv_bwd_weight(x, dy, w.shape, G, stride, pad)) <= wtol
 
 
 def test_fc_and_grouped_operators_in_a_graph():
