@@ -42,6 +42,11 @@ CASES = [
     ("pw_c16_k32", 5, 16, 9, 8, 32, 1, 1, (1, 1), (0, 0)),
     ("pw_c64_k64_hw42", 2, 64, 7, 6, 64, 1, 1, (1, 1), (0, 0)),
     ("pw_c160_k16_m_tail", 7, 160, 5, 14, 16, 1, 1, (1, 1), (0, 0)),
+    # ... with so few tiles and so long a reduction (at least four 128-channel stages) that the channels
+    # are split over workgroups and a second kernel adds the partial tiles: forward (C = 512, whole
+    # stages) and backward-data (K = 640: five stages in splits of two, the last split shorter)
+    ("pw_split_c512_k32", 2, 512, 6, 8, 32, 1, 1, (1, 1), (0, 0)),
+    ("pw_split_c64_k640", 2, 64, 4, 10, 640, 1, 1, (1, 1), (0, 0)),
     # strided layers whose filter fits inside one stride step: backward-data folds onto a single tap
     # and still needs the depth-to-space epilogue
     ("pw_stride2", 2, 32, 9, 10, 24, 1, 1, (2, 2), (0, 0)),
@@ -213,7 +218,7 @@ def test_delta_kernel_is_an_exact_shift(r0, s0, stride, pad, dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("case", [CASES[5], PW[1]], ids=lambda c: c[0])
+@pytest.mark.parametrize("case", [CASES[5], PW[1], PW[-2]], ids=lambda c: c[0])
 def test_beta_one_accumulates(case, dtype):
     from gpu_util import run_layer, rel_l2, TOL
     x, w, b, dy, stride, pad = make(case, dtype)

@@ -23,6 +23,8 @@ VIEW_CASES = [
     ("pw_c192_k96", 2, 192, 6, 10, 96, 1, 1, (1, 1), (0, 0)),
     ("pw_c64_k64_hw42", 2, 64, 7, 6, 64, 1, 1, (1, 1), (0, 0)),           # HW % 4 == 2
     ("inception_1x1_like", 2, 192, 28, 28, 176, 1, 1, (1, 1), (0, 0)),
+    ("pw_split_c512_k32", 2, 512, 6, 8, 32, 1, 1, (1, 1), (0, 0)),        # split reduction of the 1x1 kernel, forward
+    ("pw_split_c64_k640", 2, 64, 4, 10, 640, 1, 1, (1, 1), (0, 0)),       # ... and backward-data (plain and through the mask)
 ]
 
 
