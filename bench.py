@@ -52,7 +52,7 @@ def measured_traffic():
 KIND_NAMES = {0: "conv_fwd", 1: "bias_fwd", 2: "conv_bwd_data", 3: "conv_bwd_weight", 4: "bias_bwd",
               5: "relu_fwd", 6: "relu_bwd", 7: "maxpool_fwd", 8: "maxpool_bwd", 9: "concat_fwd",
               10: "concat_bwd", 11: "sum", 13: "conv_fwd_bias_relu", 14: "conv_bwd_data_relu",
-              15: "conv_bwd_weight_bias", 16: "sgd_update", 17: "alias"}
+              15: "conv_bwd_weight_bias", 16: "sgd_update", 17: "alias", 24: "maxpool_bwd_relu"}
 
 
 def cpu_baseline(cfg, budget_s=15.0):
@@ -122,7 +122,7 @@ def run_config(cfg, args, secondary_figures):
     from synth.configs import CONV_LAYERS, WORKLOAD_NAMES, total_flop
 
     merge = cfg == 3 and not args.no_merge_1x1 and not args.unfused
-    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, merge_1x1=merge)
+    gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, merge_1x1=merge, fan_in_add=merge)
     # Warm-up and one step per operator with that operator's main kernel bracketed (twice, keeping
     # the shorter): the per-operator table, and which kernel dominates. These steps run serially
     # (every operator alone on the device), so that each bracket measures its kernel and so that a
@@ -254,7 +254,7 @@ def run_config(cfg, args, secondary_figures):
         # operator per parameter tensor and the swap of old and new parameters, iterated natively
         gb.close()
         gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused,
-                            first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6, merge_1x1=merge)
+                            first_layer_dx=cfg not in (2, 4), sgd_lr=1e-6, merge_1x1=merge, fan_in_add=merge)
         if args.replay:
             pa.purine_graph_set_replay(gb.g, True)
         gb.iterate(max(2, args.warmup))

@@ -24,6 +24,7 @@ OP_CONCAT_FWD, OP_CONCAT_BWD, OP_SUM, OP_HOST_NOP = 9, 10, 11, 12
 OP_CONV_FWD_BIAS_RELU, OP_CONV_BWD_DATA_RELU, OP_CONV_BWD_WEIGHT_BIAS, OP_SGD_UPDATE, OP_ALIAS = 13, 14, 15, 16, 17
 OP_FC_FWD, OP_FC_BWD_DATA, OP_FC_BWD_WEIGHT = 18, 19, 20
 OP_GROUPED_CONV_FWD, OP_GROUPED_CONV_BWD_DATA, OP_GROUPED_CONV_BWD_WEIGHT = 21, 22, 23
+OP_MAXPOOL_BWD_RELU = 24
 
 STATUS = {0: "PURINE_OK", -1: "PURINE_E_NULL", -2: "PURINE_E_SHAPE", -3: "PURINE_E_DTYPE",
           -4: "PURINE_E_LAYOUT", -5: "PURINE_E_WORKSPACE", -6: "PURINE_E_GRAPH",
@@ -96,6 +97,7 @@ _SIGS = {
     "purine_relu_bwd": (ctypes.c_int, [_T, _T, _T, _vp]),
     "purine_maxpool_fwd": (ctypes.c_int, [_PD, _T, _T, _T, _vp]),
     "purine_maxpool_bwd": (ctypes.c_int, [_PD, _T, _T, _T, ctypes.c_float, _vp]),
+    "purine_maxpool_bwd_relu": (ctypes.c_int, [_PD, _T, _T, _T, _T, ctypes.c_float, _vp]),
     "purine_concat_fwd": (ctypes.c_int, [_P(_T), ctypes.c_int, _T, _vp]),
     "purine_concat_bwd": (ctypes.c_int, [_T, _P(_T), ctypes.c_int, _vp]),
     "purine_sum": (ctypes.c_int, [_P(_T), ctypes.c_int, _T, _vp]),
@@ -390,6 +392,12 @@ def purine_maxpool_bwd(desc, dy, arg, dx, beta=0.0, stream=None):
     _check(_lib.purine_maxpool_bwd(_ref(desc), _ref(tensor_desc(dy)), _ref(tensor_desc(arg)),
                                    _ref(tensor_desc(dx)), float(beta), _stream(stream)),
            "purine_maxpool_bwd")
+
+
+def purine_maxpool_bwd_relu(desc, dy, arg, act, dx, beta=0.0, stream=None):
+    _check(_lib.purine_maxpool_bwd_relu(_ref(desc), _ref(tensor_desc(dy)), _ref(tensor_desc(arg)),
+                                        _ref(tensor_desc(act)), _ref(tensor_desc(dx)), float(beta), _stream(stream)),
+           "purine_maxpool_bwd_relu")
 
 
 def _tensor_ptr_array(tensors):

@@ -112,6 +112,7 @@ bool arity_ok(int kind, int n_in, int n_out, float beta) {
         case PURINE_OP_RELU_BWD: return n_in == 2 && n_out == 1;
         case PURINE_OP_MAXPOOL_FWD: return n_in == 1 && n_out == 2;
         case PURINE_OP_MAXPOOL_BWD: return n_in == 2 + extra && n_out == 1;
+        case PURINE_OP_MAXPOOL_BWD_RELU: return n_in == 3 + extra && n_out == 1;
         case PURINE_OP_CONCAT_FWD: return n_in >= 1 && n_in <= 64 && n_out == 1;
         case PURINE_OP_CONCAT_BWD: return n_in == 1 && n_out >= 1 && n_out <= 64;
         case PURINE_OP_SUM: return n_in >= 1 && n_in <= 8 && n_out == 1;
@@ -252,6 +253,9 @@ int issue(purine_graph* g, purine_graph::Op& op, hipStream_t st) {
         case PURINE_OP_MAXPOOL_BWD:
             if (a.beta != 0.0f && T(op.in[2])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
             return purine_maxpool_bwd(&a.pool, T(op.in[0]), T(op.in[1]), T(op.out[0]), a.beta, st);
+        case PURINE_OP_MAXPOOL_BWD_RELU:
+            if (a.beta != 0.0f && T(op.in[3])->data != T(op.out[0])->data) return PURINE_E_LAYOUT;
+            return purine_maxpool_bwd_relu(&a.pool, T(op.in[0]), T(op.in[1]), T(op.in[2]), T(op.out[0]), a.beta, st);
         case PURINE_OP_CONCAT_FWD: {
             std::vector<const purine_tensor*> parts;
             for (int id : op.in) parts.push_back(T(id));

@@ -322,11 +322,13 @@ __global__ __launch_bounds__(TPB) void maxpool_fwd_kernel(const T* __restrict__ 
 }
 
 // Gather form of the pooling gradient: each input position visits the windows that cover it in
-// row-major (p,q) order and adds dy where that window's winner is this position.
+// row-major (p,q) order and adds dy where that window's winner is this position. `act` (may be
+// null): the pooled tensor, output of a ReLU; positions where it is not positive get no gradient
+// (the ReLU gradient that would otherwise be a pass of its own over dx).
 template <typename T, int K, int S>
 __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ dy,
                                                           const int32_t* __restrict__ arg,
-                                                          T* dx, const PoolParams pp) {
+                                                          T* dx, const T* __restrict__ act, const PoolParams pp) {
     const int k = K ? K : pp.k, st = K ? S : pp.stride;
     constexpr int NW = K ? (K + S - 1) / (S ? S : 1) : 1;   // windows per axis that can cover a position
     const int lim = min(pp.ppw * pp.HW, ((int)blockIdx.y + 1) * POOL_CHUNK);
@@ -345,7 +347,8 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
         q_lo = q_lo <= 0 ? 0 : (q_lo + st - 1) / st;
         const size_t obase = (size_t)nc * pp.PQ;
         const size_t at = (size_t)nc * pp.HW + e;
-        float acc = pp.beta != 0.0f ? ldf<T>(dx, at) : 0.0f;
+        const float old = pp.beta != 0.0f ? ldf<T>(dx, at) : 0.0f;
+        float acc = old;
         if (K) {
 #pragma unroll
             for (int a = 0; a < NW; ++a)
@@ -363,6 +366,7 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
                 for (int q = q_lo; q <= q_hi; ++q)
                     if (arg[obase + p * pp.Q + q] == e) acc += ldf<T>(dy, obase + p * pp.Q + q);
         }
+        if (act && !(ldf<T>(act, at) > 0.0f)) acc = old;
         stf<T>(dx, at, acc);
     }
 }
@@ -709,11 +713,11 @@ hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, i
     return hipGetLastError();
 }
 
-hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, float beta,
+hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, const void* act, float beta,
                               int NC, int H, int W, int P, int Q, int k, int stride, int pad,
                               hipStream_t st) {
     if ((long long)H * W > 0x3fffffffLL || (long long)P * Q > 0x3fffffffLL) return hipErrorInvalidValue;
-    if (pool3_vec_applies(dtype, NC, H, W, P, Q, k, stride, pad, dy, dx, arg)) {
+    if (!act && pool3_vec_applies(dtype, NC, H, W, P, Q, k, stride, pad, dy, dx, arg)) {
         const Pool3Params p3 = pool3_params(NC, H, W, beta);
         ProbeScope probe(st);
         (void)hipGetLastError();
@@ -728,8 +732,8 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
 #define CALL(K, S)                                                                                              \
     BY_DTYPE(dtype,                                                                                             \
-             hipLaunchKernelGGL((maxpool_bwd_kernel<float, K, S>), grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, pp),     \
-             hipLaunchKernelGGL((maxpool_bwd_kernel<uint16_t, K, S>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, pp))
+             hipLaunchKernelGGL((maxpool_bwd_kernel<float, K, S>), grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, (const float*)act, pp),     \
+             hipLaunchKernelGGL((maxpool_bwd_kernel<uint16_t, K, S>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)act, pp))
     POOL_SHAPES(CALL)
 #undef CALL
     return hipGetLastError();

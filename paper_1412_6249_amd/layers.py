@@ -117,10 +117,13 @@ class GraphBuilder:
         return out, rec
 
     def conv_backward(self, rec, dout, thread=T_MAIN, t_w=T_WGRAD, t_b=T_BGRAD, need_dx=True, dx=None,
-                      grad_in_place=False):
+                      grad_in_place=False, add_to=None):
         """dout is the gradient at the layer output (after ReLU if the layer has one). `dx`: an
         already bound vertex to receive the input gradient (e.g. a channel slice of a larger buffer);
-        `grad_in_place`: the ReLU gradient overwrites dout whatever the builder's default."""
+        `grad_in_place`: the ReLU gradient overwrites dout whatever the builder's default.
+        `add_to`: a vertex that already holds another branch's gradient of the same input; the
+        backward-data operator then adds to it (beta = 1) and the returned vertex is the next
+        version of that storage, so that no separate Sum operator runs for the fan-in."""
         L, p = rec["layer"], rec["prefix"]
         desc = B.conv_desc(L.stride, L.pad)
         dy = dout
@@ -145,10 +148,18 @@ class GraphBuilder:
         if not need_dx:
             dx = None
         else:
-            if dx is None:
-                dx = self.new(p + ".dx", L.x_shape, L.dtype)
             ws = self.workspace(B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_DATA, desc, L.x_shape,
                                                               L.w_shape, _pcode(L.dtype)))
+            if add_to is not None:
+                assert rec["x"] not in self.relu_outputs          # a mask would have to cover both terms
+                dx = self.bind(p + ".dx+", self.t[add_to])
+                self.op(B.OP_CONV_BWD_DATA, [dy, rec["w"], add_to], [dx], thread,
+                        B.op_attrs(conv=desc, ws=ws, beta=1.0))
+                rec["fused_bwd"] = False
+                rec.update(dy=dy, db=db, dw=dw, dx=dx, t_w=t_w, t_b=t_w if self.fuse else t_b)
+                return dx
+            if dx is None:
+                dx = self.new(p + ".dx", L.x_shape, L.dtype)
             if self.fuse and rec["x"] in self.relu_outputs:
                 # the layer below ends in a ReLU whose output is our input: apply its gradient mask here
                 self.op(B.OP_CONV_BWD_DATA_RELU, [dy, rec["w"], rec["x"]], [dx], thread,
@@ -193,7 +204,14 @@ class GraphBuilder:
 
     def maxpool_backward(self, rec, dy, thread=T_MAIN):
         dx = self.new(rec["prefix"] + ".dx", rec["x_shape"], rec["dtype"])
-        self.op(B.OP_MAXPOOL_BWD, [dy, rec["arg"]], [dx], thread, B.op_attrs(pool=rec["desc"]))
+        if self.fuse and rec["x"] in self.relu_outputs:
+            # the pooled tensor is a ReLU output: its gradient mask rides along (no ReLUBwd pass over dx)
+            self.op(B.OP_MAXPOOL_BWD_RELU, [dy, rec["arg"], rec["x"]], [dx], thread, B.op_attrs(pool=rec["desc"]))
+            self.masked_grads.add(dx)
+            rec["fused_relu"] = True
+        else:
+            self.op(B.OP_MAXPOOL_BWD, [dy, rec["arg"]], [dx], thread, B.op_attrs(pool=rec["desc"]))
+            rec["fused_relu"] = False
         rec.update(dy=dy, dx=dx)
         return dx
 
@@ -221,7 +239,7 @@ def _default_init(seed):
     return init
 
 
-def _build_inception_merged(gb, layers, src, params, multi_stream):
+def _build_inception_merged(gb, layers, src, params, multi_stream, fan_in_add=False):
     """The inception module with its three 1x1 convolutions on the module input merged into one
     operator (filters stacked along K: 96 + 16 + 64 = 176 output channels) and the concatenation done
     by address: every branch writes its channel slice of one activation buffer, and the gradients
@@ -277,16 +295,23 @@ def _build_inception_merged(gb, layers, src, params, multi_stream):
     dF = G("F", "merged_1x1.dout")
     gb.op(B.OP_ALIAS, [dm2, dm3, d1m], [dF], th(0))
     gb.masked_grads.add(dF)                                   # every slice already carries its ReLU mask
-    dxF = gb.conv_backward(rF, dF, th(0), tw3, tw3)
-    dx = gb.new("dx", b1.x_shape, "f32")
-    gb.op(B.OP_SUM, [dxF, dx4], [dx], th(0))                  # gradient fan-in, fixed order
+    if fan_in_add:
+        # the module input has two consumers left (merged 1x1, pooling): the merged operator's
+        # backward-data adds to the pooling gradient instead of a Sum over two full tensors
+        dx = gb.conv_backward(rF, dF, th(0), tw3, tw3, add_to=dx4)
+        gb.bind("dx", gb.t[dx])
+        gb.op(B.OP_ALIAS, [dx], ["dx"], th(0))
+    else:
+        dxF = gb.conv_backward(rF, dF, th(0), tw3, tw3)
+        dx = gb.new("dx", b1.x_shape, "f32")
+        gb.op(B.OP_SUM, [dxF, dx4], [dx], th(0))              # gradient fan-in, fixed order
     gb.pool_records = [rp]
     gb.slices = sl
     gb.merged_order = [L.name for L in order]
 
 
 def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, multi_stream=True,
-                   fuse=False, first_layer_dx=True, sgd_lr=None, merge_1x1=False):
+                   fuse=False, first_layer_dx=True, sgd_lr=None, merge_1x1=False, fan_in_add=False):
     """Builds the bi-graph of config `cfg` (1..5). `batch` overrides the batch size (tests).
     `init(name, shape, dtype, kind)` supplies source tensors (kind in x, w, b, dy); by default they
     are drawn on the device from the seed. `first_layer_dx=False` leaves out the backward-data
@@ -294,7 +319,9 @@ def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, mult
     does not need that gradient). `sgd_lr`: also add one SGD update operator per parameter tensor
     (gb.iterate(n) then runs n training iterations). `merge_1x1` (config 3 with fused operators):
     the module's three 1x1 convolutions on its input run as one operator and the concatenation is
-    done by address (channel-slice views), see _build_inception_merged. Returns the GraphBuilder; gb.run() performs one
+    done by address (channel-slice views), see _build_inception_merged; `fan_in_add` (with merge_1x1):
+    the gradient fan-in at the module input is an accumulating backward-data operator instead of a
+    Sum. Returns the GraphBuilder; gb.run() performs one
     full forward + backward step."""
     init = init or _default_init(seed)
     layers = [l.with_batch(batch) if batch else l for l in CONV_LAYERS[cfg]]
@@ -335,7 +362,7 @@ def build_workload(cfg, batch=None, inplace=True, init=None, seed=14126249, mult
         if not (fuse and inplace):
             raise ValueError("merge_1x1 needs the fused operators and in-place buffer versions")
         gb.init_value = init
-        _build_inception_merged(gb, layers, src, params, multi_stream)
+        _build_inception_merged(gb, layers, src, params, multi_stream, fan_in_add)
     elif cfg == 3:
         b1, b2r, b2, b3r, b3, b4 = layers
         N = b1.N

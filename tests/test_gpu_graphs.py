@@ -48,19 +48,25 @@ def check_conv_record(gb, rec, tol):
     assert rel_l2(host(gb, rec["db"]), oracle.bias_bwd(dy)) <= tol, (L.name, "db")
 
 
-def check_pool_record(gb, rec):
+def check_pool_record(gb, rec, check_dx=True):
     from gpu_util import rel_l2, pool_bwd_in_order
     x = host(gb, rec["x"])
     d = rec["desc"]
     ey, earg = oracle.maxpool_fwd(x, d.window, d.stride, d.pad)
     assert np.array_equal(host(gb, rec["y"]), ey)
     assert np.array_equal(gb.t[rec["arg"]].cpu().numpy(), earg)
+    if not check_dx:            # a later operator accumulated onto the pooling gradient's storage
+        return
     dy = host(gb, rec["dy"])
     dx = host(gb, rec["dx"])
     edx = oracle.maxpool_bwd(dy, earg, x.shape)
+    exact = pool_bwd_in_order(dy, earg, x.shape)
+    if rec.get("fused_relu"):
+        # MaxPoolBwd + the ReLU gradient of the pooled tensor as one operator
+        edx, exact = oracle.relu_bwd(x, edx), np.where(x > 0, exact, np.float32(0))
     assert rel_l2(dx, edx) <= 1e-6
     # exact operator: the fp32 sum over the windows in (p, q) order, bit for bit
-    assert np.array_equal(dx, pool_bwd_in_order(dy, earg, x.shape))
+    assert np.array_equal(dx, exact)
 
 
 def index_ops(gb):
@@ -98,6 +104,10 @@ def test_workload_graph_teacher_forced(cfg, batch, fuse):
             check_conv_record(gb, rec, tol)
         for rec in getattr(gb, "pool_records", []):
             check_pool_record(gb, rec)
+            assert rec["fused_relu"] == (fuse and cfg == 4)   # every pooled tensor of config 4 is a ReLU output
+        if cfg == 4 and fuse:
+            assert sum(op[1] == 6 for op in gb.ops) == 0      # no ReLUBwd pass left: three ride on the pooling gradients,
+            assert sum(op[1] == 14 for op in gb.ops) == 2     # two (conv3, conv4) on the backward-data of the layer above
         if cfg == 3:
             from gpu_util import rel_l2
             cat = host(gb, "cat")
@@ -168,15 +178,17 @@ def test_inplace_and_multistream_graphs_give_identical_bits(cfg, batch):
         fast.close()
 
 
-def test_inception_with_merged_1x1_and_concat_by_address():
+@pytest.mark.parametrize("fan_in_add", [False, True], ids=["fan_in_sum", "fan_in_add"])
+def test_inception_with_merged_1x1_and_concat_by_address(fan_in_add):
     """Config 3 with the three 1x1 convolutions on the module input merged into one operator and the
     concatenation done through channel-slice views: every operator against the oracle on the device
     values it actually read (the output gradient is saved before the in-place ReLU gradients
-    overwrite their slices), and the whole step against the plain graph on the same parameters."""
+    overwrite their slices), and the whole step against the plain graph on the same parameters.
+    fan_in_add: the merged operator's backward-data adds to the pooling branch's gradient (no Sum)."""
     from gpu_util import rel_l2, to_host
     from paper_1412_6249_amd.layers import build_workload
     plain = build_workload(3, batch=2, inplace=True, fuse=True)
-    gb = build_workload(3, batch=2, inplace=True, fuse=True, merge_1x1=True)
+    gb = build_workload(3, batch=2, inplace=True, fuse=True, merge_1x1=True, fan_in_add=fan_in_add)
     tol = 1e-5
     try:
         assert not any(op[1] in (9, 10) for op in gb.ops)             # no Concat operator either way
@@ -229,9 +241,17 @@ def test_inception_with_merged_1x1_and_concat_by_address():
         assert np.array_equal(dF[:, 0:96], H("b2_3x3.dx")) and np.array_equal(dF[:, 112:176], H("b1_1x1.dyb"))
         assert rel_l2(H(rF["dw"]), oracle.conv_bwd_weight(x, dF, w_m.shape, 1, 0)) <= tol
         assert rel_l2(H(rF["db"]), oracle.bias_bwd(dF)) <= tol
-        assert rel_l2(H(rF["dx"]), oracle.conv_bwd_data(dF, w_m, x.shape, 1, 0)) <= tol
-        assert rel_l2(H("dx"), oracle.fan_in_sum([H(rF["dx"]), H("pool.dx")])) <= 1e-6
-        check_pool_record(gb, gb.pool_records[0])
+        if fan_in_add:
+            assert not any(op[1] == 11 for op in gb.ops)              # no Sum operator
+            rp = gb.pool_records[0]
+            pool_dx = oracle.maxpool_bwd(H(rp["dy"]), gb.t[rp["arg"]].cpu().numpy(), x.shape)
+            assert rel_l2(H("dx"), oracle.conv_bwd_data(dF, w_m, x.shape, 1, 0) + pool_dx) <= tol
+            assert gb.t["dx"].data_ptr() == gb.t["pool.dx"].data_ptr()
+            check_pool_record(gb, rp, check_dx=False)
+        else:
+            assert rel_l2(H(rF["dx"]), oracle.conv_bwd_data(dF, w_m, x.shape, 1, 0)) <= tol
+            assert rel_l2(H("dx"), oracle.fan_in_sum([H(rF["dx"]), H("pool.dx")])) <= 1e-6
+            check_pool_record(gb, gb.pool_records[0])
         # against the plain graph (same parameters, same inputs): the whole step agrees
         assert rel_l2(H("dx"), to_host(plain.t["dx"])) <= tol
         lo = 0

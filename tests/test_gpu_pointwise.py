@@ -108,6 +108,43 @@ def test_maxpool_forward_and_backward(case, dtype, ties):
     assert np.array_equal(to_host(tdx2), pool_bwd_in_order(dy, earg, x.shape, dtype, prev=prev))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", POOLS, ids=[c[0] for c in POOLS])
+def test_maxpool_backward_with_relu_mask(case, dtype):
+    """MaxPoolBwd and the ReLU gradient of the pooled tensor as one operator: where act > 0 the bits
+    of purine_maxpool_bwd, elsewhere no pooling gradient; also accumulating, against the oracle's
+    two functions composed. act is drawn independently of the pooling winners (about half of the
+    positions are masked), which a real ReLU output would not give but the operator must honour."""
+    import paper_1412_6249_amd as pa
+    from gpu_util import to_dev, to_host, tdtype, rel_l2, pool_bwd_in_order, DEV
+    name, N, C, H, W, k, s, p = case
+    x, dy = pool_inputs(case, dtype, False)
+    act = np.maximum(x, 0.0)                                   # a ReLU output: zeros and positives
+    ey, earg = oracle.maxpool_fwd(act, k, s, p)
+    desc = pa.pool_desc(k, s, p)
+    tact, tdy = to_dev(act, dtype), to_dev(dy, dtype)
+    targ = torch.from_numpy(earg.astype(np.int32)).to(DEV)
+    rs = np.random.default_rng(11)
+    other = rs.uniform(-1, 1, size=x.shape).astype(np.float32)  # a mask unrelated to the winners
+    if dtype == "bf16":
+        other = gen.quantize_bf16(other)
+    prev = rs.uniform(-1, 1, size=x.shape).astype(np.float32)
+    if dtype == "bf16":
+        prev = gen.quantize_bf16(prev)
+    for mask, tmask in ((act, tact), (other, to_dev(other, dtype))):
+        tdx = torch.full(x.shape, float("nan"), dtype=tdtype(dtype), device=DEV)
+        pa.purine_maxpool_bwd_relu(desc, tdy, targ, tmask, tdx)
+        tdx2 = to_dev(prev, dtype)
+        pa.purine_maxpool_bwd_relu(desc, tdy, targ, tmask, tdx2, beta=1.0)
+        torch.cuda.synchronize()
+        ref = oracle.relu_bwd(mask, oracle.maxpool_bwd(dy, earg, x.shape))
+        assert rel_l2(to_host(tdx), ref) <= (1e-2 if dtype == "bf16" else 1e-6)
+        exact = pool_bwd_in_order(dy, earg, x.shape, dtype)
+        assert np.array_equal(to_host(tdx), np.where(mask > 0, exact, np.float32(0)))
+        exact2 = pool_bwd_in_order(dy, earg, x.shape, dtype, prev=prev)
+        assert np.array_equal(to_host(tdx2), np.where(mask > 0, exact2, prev))
+
+
 def test_maxpool_backward_is_deterministic():
     import paper_1412_6249_amd as pa
     from gpu_util import to_dev, DEV

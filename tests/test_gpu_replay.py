@@ -24,8 +24,8 @@ def test_every_replay_matches_direct_issue(cfg, batch, merge):
     import torch
     import paper_1412_6249_amd as pa
     from paper_1412_6249_amd.layers import build_workload
-    a = build_workload(cfg, batch=batch, fuse=True, merge_1x1=merge)
-    b = build_workload(cfg, batch=batch, fuse=True, merge_1x1=merge)
+    a = build_workload(cfg, batch=batch, fuse=True, merge_1x1=merge, fan_in_add=merge)
+    b = build_workload(cfg, batch=batch, fuse=True, merge_1x1=merge, fan_in_add=merge)
     try:
         a.run()
         ref = snapshot(a)
@@ -68,8 +68,8 @@ def test_every_replay_matches_direct_issue(cfg, batch, merge):
 def test_replayed_sgd_iterations_match_direct_ones(cfg, batch, merge):
     import paper_1412_6249_amd as pa
     from paper_1412_6249_amd.layers import build_workload
-    a = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge)
-    b = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge)
+    a = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge, fan_in_add=merge)
+    b = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge, fan_in_add=merge)
     try:
         pa.purine_graph_set_replay(b.g, True)
         a.iterate(5)

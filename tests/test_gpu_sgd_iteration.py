@@ -98,8 +98,8 @@ def test_iterate_in_one_call_equals_run_and_swap_by_hand(cfg, batch, merge, n):
     import paper_1412_6249_amd as pa
     from gpu_util import to_host
     from paper_1412_6249_amd.layers import build_workload
-    a = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge)
-    b = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge)
+    a = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge, fan_in_add=merge)
+    b = build_workload(cfg, batch=batch, fuse=True, sgd_lr=1e-3, merge_1x1=merge, fan_in_add=merge)
     try:
         a.iterate(n)
         for _ in range(n):
@@ -110,7 +110,7 @@ def test_iterate_in_one_call_equals_run_and_swap_by_hand(cfg, batch, merge, n):
         assert set(a.t) == set(b.t)
         for name in a.t:
             assert np.array_equal(to_host(a.t[name]), to_host(b.t[name]), equal_nan=True), name
-        start = build_workload(cfg, batch=batch, fuse=True, merge_1x1=merge)
+        start = build_workload(cfg, batch=batch, fuse=True, merge_1x1=merge, fan_in_add=merge)
         try:
             assert not np.array_equal(to_host(a.t["conv1.w" if cfg != 3 else a.swaps[0][0]]),
                                       to_host(start.t["conv1.w" if cfg != 3 else a.swaps[0][0]]))
