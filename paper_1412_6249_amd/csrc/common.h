@@ -84,6 +84,8 @@ struct PixPlan {
 };
 PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
 void force_pix_tile(int bm, int bn);
+bool patch_split_roles_forced();     // test hook: (-5, anything) gives it layers of few tiles too
+bool patch_split_roles_disabled();   // tuning hook: (-4, anything) keeps the bf16 patch kernel on its one-role form
 bool buffer_loads_disabled();   // tuning hook: (anything, -1) given to force_pix_tile
 
 // Split of the pixel reduction of the weight gradient: same answer for the workspace query and

@@ -556,6 +556,8 @@ hipError_t dispatch_flat(PixParams& p, int bm, int bn, hipStream_t st) {
 static int g_force_bm = 0, g_force_bn = 0;   // tuning hook, see purine_debug_force_tile
 static int g_no_buffer_loads = 0;            // tuning hook: bn == -1 in purine_debug_force_tile
 bool buffer_loads_disabled() { return g_no_buffer_loads != 0; }
+bool patch_split_roles_disabled() { return g_force_bm == -4; }   // tuning hook: force_pix_tile(-4, x)
+bool patch_split_roles_forced() { return g_force_bm == -5; }     // test hook: force_pix_tile(-5, x), also for layers of few tiles
 void force_pix_tile(int bm, int bn) {
     g_no_buffer_loads = (bn == -1 && bm != -2) ? 1 : 0;
     g_force_bm = bm; g_force_bn = bn;

@@ -258,6 +258,275 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
                                                      bias_s, i0, n * p.HoWo + pix_end, 1);
 }
 
+// ---- the same computation with the wavefronts of a workgroup split into two roles ----------------
+// Eight wavefronts, one workgroup per CU, persistent over pixel tiles of BM rows x 512 pixels.
+// Wavefronts 4-7 ("fill") bring the next stages' patch and filter rows from global memory into
+// registers, transpose, and store them into the OTHER of two LDS buffers; wavefronts 0-3
+// ("multiply") run the current stage (one 16-channel group, all taps) and, after a tile's last
+// stage, its epilogue. One barrier per stage hands a buffer over in each direction.
+//
+// A multiply lane owns FOUR adjacent pixels, and the patch is kept as eight planes (position mod 4,
+// 8-channel half) of 16-byte packets. The B fragments of a filter row's taps are then a sliding
+// window: pixel b at column tap s reads position base + b + s, so a row of ST taps needs 4 + ST - 1
+// fragment reads instead of 4 * ST, and with the filter rows read once per tap for all four pixel
+// tiles the LDS traffic per MFMA is half that of the one-role kernel, whose tap loop is bound by it.
+// Rows are taken in pairs, the next row's fragments requested before the current row's MFMAs.
+// Output rows are whole groups of four pixels, so a lane's four pixels share a row. Phase-folded
+// backward-data stays on the one-role kernel (measured no faster here: its time goes to the
+// depth-to-space stores).
+constexpr int RTN = 4;     // adjacent pixels per multiply lane
+template <bool MINUS, bool FUSED, int TM, int ST, int ROUNDS>
+__global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const PixParams p, const PatchGeom q) {
+    constexpr int NT = 256;                 // threads of each role
+    constexpr int TN = RTN;
+    constexpr int BM = TM * 32;
+    constexpr int BN = 4 * TN * 32;         // four multiply wavefronts side by side
+    constexpr int NWIN = TN + ST - 1;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    float* bias_s = reinterpret_cast<float*>(smem);                 // [i_pad]: every row tile's bias
+    const int PB = q.plane_bytes;
+    const int patch_bytes = 2 * TN * PB + 128;
+    const int buf_bytes = q.a_bytes + patch_bytes;                  // one stage: filter rows, then the patch
+    unsigned char* buf0 = smem + p.i_pad * 4;
+    const int APB = BM * 16 + 64;
+    // byte offset of position P, half h
+    auto patch_at = [&](int P, int h) { return ((P & (TN - 1)) * 2 + h) * PB + (P >> 2) * 16; };
+
+    const uint16_t* __restrict__ in = (const uint16_t*)p.in;
+    const uint16_t* __restrict__ wt = (const uint16_t*)p.wt;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rt = tid & (NT - 1);          // thread index inside its role
+
+    // once: both buffers to zero (halo columns are never written again: fill tasks write image columns
+    // only, and rows outside the image arrive as zeros), every row tile's bias
+    {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int i = tid; i < 2 * buf_bytes / 16; i += 512) *reinterpret_cast<u32x4*>(buf0 + i * 16) = z;
+        if (FUSED) {
+            const uint16_t* __restrict__ bias = (const uint16_t*)p.bias;
+            if (bias)
+                for (int r = tid; r < p.i_pad; r += 512) bias_s[r] = r < p.Co ? Elem<uint16_t>::load(bias, r) : 0.0f;
+        }
+    }
+    __syncthreads();
+
+    // this workgroup's tiles: logical index w (contiguous inside an XCD), tiles w, w + G, w + 2G, ...
+    const int G = gridDim.x;
+    const int total = p.tiles_i * p.tiles_pix;
+    const int w_id = (G & 7) == 0 ? ((int)blockIdx.x & 7) * (G >> 3) + ((int)blockIdx.x >> 3) : (int)blockIdx.x;
+    const int my_tiles = w_id < total ? (total - 1 - w_id) / G + 1 : 0;
+    const int n_taps = p.Rt * ST;
+    const int n_groups = p.Ci_pad / GC;
+    const int n_stages = my_tiles * n_groups;
+
+    if (wave >= 4) {
+        // ================= fill role =================
+        unsigned g_voff[ROUNDS];
+        int l_off[ROUNDS][4], l_step[ROUNDS], cg8[ROUNDS], t_pr[ROUNDS], t_chunk[ROUNDS];
+        bool t_live[ROUNDS];
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const int t = rt + r * NT;
+            const int pr = fastdiv(t, q.div_tpr);
+            const int u = t - pr * q.tasks_per_row;
+            const int cg = (u >> 2) & 1;
+            const int chunk = (u >> 3) * 4 + (u & 3);
+            const bool live = pr < q.pr_max && chunk < q.chunks;
+            const int P0 = pr * q.pw + chunk * 8 - q.w_lo;
+            // pixels px and px + 4 of the packet share a plane, 16 bytes apart; a thread without a task
+            // writes into the spare packets behind the planes
+#pragma unroll
+            for (int px = 0; px < 4; ++px) l_off[r][px] = live ? patch_at(P0 + px, cg) : 2 * TN * PB + (rt & 7) * 16;
+            l_step[r] = live ? 16 : 0;
+            cg8[r] = cg * 8;
+            t_pr[r] = pr; t_chunk[r] = chunk; t_live[r] = live;
+            g_voff[r] = 0x80000000u;
+        }
+        const __amdgpu_buffer_rsrc_t rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(in), (short)0, (int)p.in_bytes, 0x00020000);
+        int a_src[A_ROUNDS], a_dst[A_ROUNDS];
+#pragma unroll
+        for (int it = 0; it < A_ROUNDS; ++it) {
+            const int f = rt + it * NT;
+            const int tap = f / (BM * 2), rem = f - tap * (BM * 2);
+            const int row = rem >> 1, half = rem & 1;
+            const bool live = tap < n_taps;
+            a_src[it] = live ? (tap * p.i_pad + row) * GC + half * 8 : -1;      // + i0 * GC per tile
+            a_dst[it] = live ? (tap * 2 + half) * APB + row * 16 : BM * 16 + (rt & 3) * 16;
+        }
+        // DEPTH stages of requests are in flight at any time (one register set each)
+        constexpr int DEPTH = 2;
+        u32x4 pre[DEPTH][ROUNDS][8];
+        u32x4 a_reg[DEPTH][A_ROUNDS];
+        int i0 = 0;
+        int rq_group = 0, rq_tl = 0;
+        // requests of the next stage in order into one register set; `real` (uniform) = false past the
+        // workgroup's last stage: the same instructions, out of range (no memory traffic) or at offset 0
+        auto request = [&](u32x4 (&pr)[ROUNDS][8], u32x4 (&ar)[A_ROUNDS], bool real) {
+            if (rq_group == 0) {
+                const int tile = min(w_id + rq_tl * G, total - 1);   // (stages past the last: any valid tile)
+                i0 = (tile % p.tiles_i) * BM;
+                const int tp = tile / p.tiles_i;
+                const int n = fastdiv(tp, q.div_tpi);
+                const int pix0 = (tp - n * q.tiles_per_img) * BN;
+                const int h_lo = fastdiv(pix0, p.div_wo) + q.h_lo_add;
+#pragma unroll
+                for (int r = 0; r < ROUNDS; ++r) {
+                    const int hi = h_lo + t_pr[r];
+                    const bool row_ok = t_live[r] & ((unsigned)hi < (unsigned)p.Hi);
+                    g_voff[r] = row_ok ? (unsigned)(n * p.in_ns + cg8[r] * p.HiWi + hi * p.Wi + t_chunk[r] * 8) * 2u : 0x80000000u;
+                }
+            }
+            const int group = rq_group;
+            const int c0 = group * GC;
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+                const unsigned v = (real && c0 + cg8[r] < p.Ci) ? g_voff[r] : 0x80000000u;   // padding channels read as zeros
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    pr[r][e] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, v, (c0 + e) * p.HiWi * 2, 0);
+            }
+            const int base = real ? (group * n_taps * p.i_pad + i0) * GC : 0;
+#pragma unroll
+            for (int it = 0; it < A_ROUNDS; ++it) {
+                if (it >= q.a_rounds) break;                        // uniform
+                const int off = (real && a_src[it] >= 0) ? a_src[it] : 0;
+                ar[it] = *reinterpret_cast<const u32x4*>(wt + base + off);
+            }
+            rq_group += 1;
+            if (rq_group == n_groups) { rq_group = 0; rq_tl += 1; }
+        };
+        auto deposit = [&](unsigned char* buf, const u32x4 (&pr)[ROUNDS][8], const u32x4 (&ar)[A_ROUNDS]) {
+            unsigned char* patch = buf + q.a_bytes;
+#pragma unroll
+            for (int r = 0; r < ROUNDS; ++r) {
+#pragma unroll
+                for (int px = 0; px < 8; ++px) {
+                    // pixel px of the packet: channel pairs (0,1) (2,3) (4,5) (6,7), low or high halves of dword px/2
+                    const unsigned sel = (px & 1) ? 0x07060302u : 0x05040100u;
+                    u32x4 o;
+#pragma unroll
+                    for (int c2 = 0; c2 < 4; ++c2)
+                        o[c2] = __builtin_amdgcn_perm(pr[r][2 * c2 + 1][px >> 1], pr[r][2 * c2][px >> 1], sel);
+                    *reinterpret_cast<u32x4*>(patch + l_off[r][px & 3] + (px >> 2) * l_step[r]) = o;
+                }
+            }
+#pragma unroll
+            for (int it = 0; it < A_ROUNDS; ++it) {
+                if (it >= q.a_rounds) break;
+                *reinterpret_cast<u32x4*>(buf + a_dst[it]) = ar[it];
+            }
+        };
+        // stages 0 .. DEPTH-1 requested up front; then, per stage: deposit its set, request stage
+        // s + DEPTH into the same set, barrier. Whole rounds of DEPTH stages first (every trip issues the
+        // same instructions, so the waits stay counted), then the remaining stages one by one.
+#pragma unroll
+        for (int j = 0; j < DEPTH; ++j) request(pre[j], a_reg[j], j < n_stages);
+        int s = 0;
+        for (; s + DEPTH <= n_stages; s += DEPTH) {
+#pragma unroll
+            for (int j = 0; j < DEPTH; ++j) {
+                deposit(buf0 + ((s + j) & 1) * buf_bytes, pre[j], a_reg[j]);
+                request(pre[j], a_reg[j], s + j + DEPTH < n_stages);
+                __syncthreads();             // stage s + j is in place; the multiply role is done with the other buffer
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < DEPTH - 1; ++j) {
+            if (s + j < n_stages) {
+                deposit(buf0 + ((s + j) & 1) * buf_bytes, pre[j], a_reg[j]);
+                __syncthreads();
+            }
+        }
+        return;
+    }
+
+    // ================= multiply role =================
+    const int wn = wave;
+    const int a_row = (lane >> 5) * APB + (lane & 31) * 16;
+    const int hPB = (lane >> 5) * PB;
+    floatx16 acc[TM][TN];
+    int X0 = 0;                              // patch position of this lane's first pixel at tap (0, 0)
+    int i0 = 0, n = 0, pix0 = 0, pix_end = 0;
+    int group = 0, tl = 0;
+    struct RowFrags { bf16x8 a[ST][TM]; bf16x8 w[NWIN]; };
+    for (int s = 0; s < n_stages; ++s) {
+        if (group == 0) {
+            const int tile = w_id + tl * G;
+            i0 = (tile % p.tiles_i) * BM;
+            const int tp = tile / p.tiles_i;
+            n = fastdiv(tp, q.div_tpi);
+            pix0 = (tp - n * q.tiles_per_img) * BN;
+            pix_end = min(pix0 + BN, p.HoWo);
+            const int ho_first = fastdiv(pix0, p.div_wo);
+            // lanes past the tile's last pixel re-read its last four (their results are never stored)
+            const int pix = min(pix0 + wn * TN * 32 + TN * (lane & 31), pix_end - TN);
+            const int ho = fastdiv(pix, p.div_wo);
+            const int wo = pix - ho * p.Wo;
+            X0 = (ho - ho_first) * q.pw + wo + q.pos_add;
+#pragma unroll
+            for (int a = 0; a < TM; ++a)
+#pragma unroll
+                for (int b = 0; b < TN; ++b)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.0f;
+        }
+        __syncthreads();                     // stage s is in place
+        const unsigned char* As = buf0 + (s & 1) * buf_bytes;
+        const unsigned char* patch = As + q.a_bytes + hPB;
+        // `real` = false (uniform): past the last filter row; the reads are still issued, at row 0, so
+        // that every trip of the loop has the same number of LDS reads in flight
+        auto fetch_row = [&](RowFrags& f, int r, bool real) {
+            const int rr = real ? r : 0;
+            const unsigned char* ap = As + a_row + rr * (ST * 2) * APB;
+#pragma unroll
+            for (int t = 0; t < ST; ++t)
+#pragma unroll
+                for (int a = 0; a < TM; ++a) f.a[t][a] = *reinterpret_cast<const bf16x8*>(ap + t * 2 * APB + a * 32 * 16);
+            const int Xr = X0 + (MINUS ? -(rr * q.pw) - (ST - 1) : rr * q.pw);
+#pragma unroll
+            for (int j = 0; j < NWIN; ++j) {
+                const int X = Xr + j;
+                f.w[j] = *reinterpret_cast<const bf16x8*>(patch + (X & (TN - 1)) * 2 * PB + (X >> 2) * 16);
+            }
+        };
+        auto multiply_row = [&](const RowFrags& f) {
+#pragma unroll
+            for (int t = 0; t < ST; ++t)
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[t][a], f.w[MINUS ? b - t + ST - 1 : b + t],
+                                                                            acc[a][b], 0, 0, 0);
+        };
+        RowFrags f0, f1;
+        fetch_row(f0, 0, true);
+        int r = 0;
+        for (; r + 2 <= p.Rt; r += 2) {
+            fetch_row(f1, r + 1, true);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply_row(f0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_row(f0, r + 2, r + 2 < p.Rt);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply_row(f1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (r < p.Rt) multiply_row(f0);
+
+        group += 1;
+        if (group == n_groups) {
+            group = 0; tl += 1;
+            const int pix_first = pix0 + wn * TN * 32 + TN * (lane & 31);
+            store_adjacent<FUSED, TM, TN, !MINUS>(p, acc, i0, n, pix_first, pix_end, lane, bias_s + i0, i0);
+        }
+    }
+}
+
 // Filter copy for the kernel above: A[group][tap][i_pad][16] with
 //   mode 0 (forward)        : tap = (r, s),   ci = c, i = k
 //   mode 1 (bwd, stride 1)  : tap = (r, s),   ci = k, i = c
@@ -294,11 +563,35 @@ __global__ __launch_bounds__(256) void repack_groups_kernel(const GroupRepack g)
     }
 }
 
+template <bool MINUS, bool FUSED, int TM, int ST, int ROUNDS>
+hipError_t launch_roles(const PixParams& p, const PatchGeom& q, hipStream_t st) {
+    auto kern = igemm_patch_roles_bf16_kernel<MINUS, FUSED, TM, ST, ROUNDS>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, q.roles_lds);
+    if (e != hipSuccess) return e;
+    ProbeScope probe(st);
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(kern, dim3(256), dim3(512), (size_t)q.roles_lds, st, p, q);
+    return hipGetLastError();
+}
+template <bool MINUS, bool FUSED>
+hipError_t roles_by_shape(const PixParams& p, const PatchGeom& q, hipStream_t st) {
+#define ROLES_CALL(TM, ST) (q.rounds == 1 ? launch_roles<MINUS, FUSED, TM, ST, 1>(p, q, st) \
+                                          : launch_roles<MINUS, FUSED, TM, ST, 2>(p, q, st))
+    switch (q.bm * 10 + p.St) {
+        case 323: return ROLES_CALL(1, 3);
+        case 324: return ROLES_CALL(1, 4);
+        case 643: return ROLES_CALL(2, 3);
+        case 644: return ROLES_CALL(2, 4);
+        default: return hipErrorInvalidValue;
+    }
+#undef ROLES_CALL
+}
+
 template <bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN, int ROUNDS>
 hipError_t launch_one(const PixParams& p, const PatchGeom& q, hipStream_t st) {
-    auto kern = igemm_patch_bf16_kernel<MINUS, D2S, FUSED, TM, TN, WM, WN, ROUNDS>;
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
+    auto kern = igemm_patch_bf16_kernel<MINUS, D2S, FUSED, TM, TN, WM, WN, ROUNDS>;
     if (q.lds_bytes > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)q.lds_bytes);
@@ -328,9 +621,56 @@ hipError_t by_tile(const PixParams& p, const PatchGeom& q, hipStream_t st) {
 template <bool MINUS, bool D2S>
 hipError_t by_epilogue(const PixParams& p, const PatchGeom& q, hipStream_t st) {
     const bool fused = p.bias || p.relu || p.mask;
+    if (q.roles && !D2S) return fused ? roles_by_shape<MINUS, true>(p, q, st) : roles_by_shape<MINUS, false>(p, q, st);
     return fused ? by_tile<MINUS, D2S, true>(p, q, st) : by_tile<MINUS, D2S, false>(p, q, st);
 }
 
+}  // namespace
+
+namespace {
+// The two-role kernel takes layers with filter rows of 3 or 4 taps whose taps all fit one stage, whose
+// output rows are whole groups of four pixels (a lane's four pixels never straddle two rows) and, for
+// NCHW outputs, whose rows can be written as 8-byte packets; enough tiles to keep every CU's one
+// workgroup busy for several of them; two stage buffers within 156 KB of LDS. Tiles: 64 or 32 rows
+// x 512 pixels. On success q and p's tile fields describe that kernel's launch.
+void plan_roles(PixParams& p, int mode, PatchGeom& q) {
+    if (patch_split_roles_disabled()) return;
+    if (p.St != 3 && p.St != 4) return;
+    if (mode == 2 || (p.Wo & 3) || (p.out_ns & 3) || (((uintptr_t)p.out | (uintptr_t)p.mask) & 7u) != 0) return;
+    PatchGeom r = q;
+    r.bm = p.Co <= 32 ? 32 : 64;
+    r.bn = 512;
+    const int n_taps = p.Rt * p.St;
+    const int rows_spanned = (r.bn - 2) / p.Wo + 2;
+    r.pr_max = (rows_spanned < p.Ho ? rows_spanned : p.Ho) + p.Rt - 1;
+    const long long tasks = (long long)r.pr_max * r.tasks_per_row;
+    if (tasks > 2 * 256) return;
+    r.rounds = tasks > 256 ? 2 : 1;
+    const long long plane = ((long long)r.pr_max * r.pw + 3) / 4 * 16;
+    r.plane_bytes = (int)((plane + 95) / 128 * 128 + 32);      // 32 past a multiple of 128
+    const long long a_tap = 2LL * (r.bm * 16 + 64);
+    if ((long long)n_taps * r.bm * 2 > (long long)A_ROUNDS * 256) return;
+    r.taps_per_stage = n_taps;
+    r.a_rounds = (int)(((long long)n_taps * r.bm * 2 + 255) / 256);
+    r.a_bytes = (int)(n_taps * a_tap);
+    r.tiles_per_img = (p.HoWo + r.bn - 1) / r.bn;
+    const long long tiles_pix = (long long)p.N * r.tiles_per_img;
+    const int tiles_i = (p.Co + r.bm - 1) / r.bm;
+    if (tiles_pix * tiles_i > 0x7fffffffLL) return;
+    if (tiles_pix * tiles_i < 4 * 256 && !patch_split_roles_forced()) return;
+    const long long i_pad = (long long)tiles_i * r.bm;
+    const long long lds = i_pad * 4 + 2LL * (r.a_bytes + 2LL * RTN * r.plane_bytes + 128);
+    if (lds > 156 * 1024) return;
+    if ((long long)n_taps * i_pad * p.Ci_pad > 0x7fffffffLL) return;
+    r.div_tpi = make_fastdiv(r.tiles_per_img);
+    r.roles = 1;
+    r.roles_lds = (int)lds;
+    r.pairs = 1;
+    q = r;
+    p.tiles_i = tiles_i;
+    p.tiles_pix = (int)tiles_pix;
+    p.i_pad = (int)i_pad;
+}
 }  // namespace
 
 // p: the pass's geometry as the tap-major kernel gets it (Ci, Co, Rt, St, gather origin, extents).
@@ -401,6 +741,8 @@ bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* qg) {
     p.in_bytes = (unsigned)in_bytes;
     // 4-byte stores of pixel pairs: every row of every image starts at an even element
     q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out | (uintptr_t)p.mask) & 3u) == 0;
+    q.roles = 0;
+    plan_roles(p, mode, q);       // the two-role kernel where it applies: replaces tile, patch and stage geometry
     *qg = q;
     return true;
 }

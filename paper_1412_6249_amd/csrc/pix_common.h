@@ -334,6 +334,14 @@ __device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&ac
     const int obase = n * p.out_ns + pix_first;
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
+        // the bias of an accumulator quad's four consecutive rows as one 16-byte LDS read, all four
+        // quads requested before the first is used
+        floatx4 bq[4];
+        if (has_bias) {
+#pragma unroll
+            for (int qd = 0; qd < 4; ++qd)
+                bq[qd] = *reinterpret_cast<const floatx4*>(&bias_lds[i_base + a * 32 + qd * 8 + khalf * 4 - i_tile0]);
+        }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int row = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
@@ -343,7 +351,7 @@ __device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&ac
 #pragma unroll
             for (int b = 0; b < TN; ++b) x[b] = acc[a][b][e];
             if (has_bias) {
-                const float bv = bias_lds[row - i_tile0];
+                const float bv = bq[e >> 2][e & 3];
 #pragma unroll
                 for (int b = 0; b < TN; ++b) x[b] += bv;
             }
@@ -431,6 +439,8 @@ struct PatchGeom {
     int a_bytes, lds_bytes;
     int plane_bytes;     // bytes of one (position parity, channel half) plane of the patch
     int tasks_per_row;   // fill tasks per patch row: packets rounded up to fours x two halves
+    int roles;           // 1: the persistent kernel whose wavefronts split into fill and multiply roles
+    int roles_lds;       // its LDS bytes
     FastDiv div_tpi, div_tpr, div_chunks, div_halo, div_st;
 };
 bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* q);

@@ -63,6 +63,7 @@ def bench_layer(L, ops, iters, out=sys.stdout):
                                                              L.w_shape, code)), dtype=torch.uint8, device=dev)
     table = {
         "fwd": (lambda: B.purine_conv_fwd(desc, x, w, y, ws=wsf), L.flop_per_pass),
+        "fwd_fused": (lambda: B.purine_conv_fwd_bias_relu(desc, x, w, b, y, relu=True, ws=wsf), L.flop_per_pass),
         "bwd_data": (lambda: B.purine_conv_bwd_data(desc, dy, w, dx, ws=wsd), L.flop_per_pass),
         "bwd_weight": (lambda: B.purine_conv_bwd_weight(desc, x, dy, dw, ws=ws), L.flop_per_pass),
         "bias_fwd": (lambda: B.purine_bias_fwd(b, y), 0),
@@ -78,7 +79,7 @@ def bench_layer(L, ops, iters, out=sys.stdout):
             # algorithmic bytes of the pass: each operand tensor once; attainable = min(MFMA peak,
             # arithmetic intensity x 8 TB/s)
             es = x.element_size()
-            nb = {"fwd": (x.numel() + w.numel() + y.numel()) * es,
+            nb = {"fwd": (x.numel() + w.numel() + y.numel()) * es, "fwd_fused": (x.numel() + w.numel() + y.numel()) * es,
                   "bwd_data": (dy.numel() + w.numel() + dx.numel()) * es,
                   "bwd_weight": (x.numel() + dy.numel()) * es + dw.numel() * 4}[name]
             attainable = min(PEAK[L.dtype], flop / nb * HBM_TBS)

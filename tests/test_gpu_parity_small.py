@@ -289,6 +289,46 @@ def test_pointwise_backward_with_rows_past_the_last_channel(C):
         assert bool((db_[:guard] == 777.0).all()) and bool((mb[:guard] == 777.0).all())
 
 
+@pytest.mark.parametrize("case", [c for c in CASES if c[0].startswith("patch_")], ids=lambda c: c[0])
+def test_patch_kernel_with_fill_and_multiply_wavefronts(case):
+    """The bf16 patch kernel whose workgroups split into wavefronts that fill LDS and wavefronts that
+    multiply (persistent over tiles; picked by itself only for layers of a thousand tiles or more) on
+    the small patch shapes: against the oracle, and bit for bit against the one-role kernel (same
+    MFMAs in the same order). Forward with bias, backward-data plain, accumulating and masked."""
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import rel_l2, to_dev, to_host, workspace, TOL, DEV
+    x, w, b, dy, stride, pad = make(case, "bf16")
+    act = gen.quantize_bf16(np.random.default_rng(3).uniform(-1, 1, x.shape).astype(np.float32))
+    desc = pa.conv_desc(stride, pad)
+    q = lambda which: workspace(pa.purine_conv_workspace_bytes(which, desc, x.shape, w.shape, pa.PURINE_BF16))
+    tx, tw, tb, tdy, tact = (to_dev(a, "bf16") for a in (x, w, b, dy, act))
+
+    def run():
+        y = torch.full(dy.shape, float("nan"), dtype=torch.bfloat16, device=DEV)
+        dx, dxm = (torch.full(x.shape, float("nan"), dtype=torch.bfloat16, device=DEV) for _ in range(2))
+        dxa = to_dev(act, "bf16")
+        pa.purine_conv_fwd_bias_relu(desc, tx, tw, tb, y, relu=True, ws=q(pa.PURINE_CONV_FWD))
+        pa.purine_conv_bwd_data(desc, tdy, tw, dx, ws=q(pa.PURINE_CONV_BWD_DATA))
+        pa.purine_conv_bwd_data(desc, tdy, tw, dxa, beta=1.0, ws=q(pa.PURINE_CONV_BWD_DATA))
+        pa.purine_conv_bwd_data_relu(desc, tdy, tw, tact, dxm, ws=q(pa.PURINE_CONV_BWD_DATA))
+        torch.cuda.synchronize()
+        return [to_host(t) for t in (y, dx, dxa, dxm)]
+
+    base = run()
+    pa.purine_debug_force_tile(-5, 0)
+    try:
+        got = run()
+    finally:
+        pa.purine_debug_force_tile(0, 0)
+    ref_dx = oracle.conv_bwd_data(dy, w, x.shape, stride, pad)
+    refs = (np.maximum(oracle.bias_fwd(oracle.conv_fwd(x, w, stride, pad), b), 0), ref_dx, ref_dx + act,
+            np.where(act > 0, ref_dx, 0.0))
+    for name, g, b0, r in zip(("y", "dx", "dx accumulated", "dx masked"), got, base, refs):
+        assert np.isfinite(g).all() and rel_l2(g, r) <= TOL["bf16"], (name, rel_l2(g, r))
+        assert np.array_equal(g, b0), name
+
+
 def test_results_are_bit_identical_run_to_run():
     from gpu_util import run_layer
     x, w, b, dy, stride, pad = make(CASES[3], "f32")
