@@ -371,6 +371,68 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
     }
 }
 
+// The same with the windows' winners and gradients staged in LDS: a workgroup owns whole planes (a few
+// thousand input positions in all), copies their arg and dy planes into LDS with coalesced loads,
+// and every position then looks its up-to-NW x NW windows up there. What goes to and comes from
+// global memory is one coalesced pass per tensor (in the kernel above every position's gathers of
+// arg and dy go through the caches, and the kernel runs at half the rate of a copy). Same windows
+// in the same order: bit-identical results.
+template <typename T, int K, int S>
+__global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __restrict__ dy,
+                                                                 const int32_t* __restrict__ arg,
+                                                                 T* dx, const T* __restrict__ act, const PoolParams pp) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char pool_smem[];
+    int32_t* arg_s = reinterpret_cast<int32_t*>(pool_smem);           // [ppw][PQ]
+    float* dy_s = reinterpret_cast<float*>(pool_smem) + pp.ppw * pp.PQ;
+    const int k = K ? K : pp.k, st = K ? S : pp.stride;
+    constexpr int NW = K ? (K + S - 1) / (S ? S : 1) : 1;
+    const int nc0 = blockIdx.x * pp.ppw;
+    const int planes = min(pp.ppw, pp.NC - nc0);
+    {
+        const size_t base = (size_t)nc0 * pp.PQ;
+        const int n = planes * pp.PQ;
+        for (int i = threadIdx.x; i < n; i += TPB) {
+            arg_s[i] = arg[base + i];
+            dy_s[i] = ldf<T>(dy, base + i);
+        }
+    }
+    __syncthreads();
+    const int lim = planes * pp.HW;
+    for (int l = threadIdx.x; l < lim; l += TPB) {
+        const int pl = fastdiv(l, pp.div_hw);
+        const int e = l - pl * pp.HW;
+        const int h = fastdiv(e, pp.div_w), w = e - h * pp.W;
+        const int p_hi = min(pp.P - 1, (h + pp.pad) / st);
+        const int q_hi = min(pp.Q - 1, (w + pp.pad) / st);
+        int p_lo = h + pp.pad - k + 1;
+        p_lo = p_lo <= 0 ? 0 : (p_lo + st - 1) / st;
+        int q_lo = w + pp.pad - k + 1;
+        q_lo = q_lo <= 0 ? 0 : (q_lo + st - 1) / st;
+        const int obase = pl * pp.PQ;
+        const size_t at = (size_t)nc0 * pp.HW + l;
+        const float old = pp.beta != 0.0f ? ldf<T>(dx, at) : 0.0f;
+        float acc = old;
+        if (K) {
+#pragma unroll
+            for (int a = 0; a < NW; ++a)
+#pragma unroll
+                for (int b = 0; b < NW; ++b) {
+                    const int p = p_lo + a, q = q_lo + b;
+                    const bool in = (p <= p_hi) & (q <= q_hi);
+                    const int o = obase + (in ? p * pp.Q + q : 0);   // clamped, branch-free
+                    const bool hit = in & (arg_s[o] == e);
+                    acc += hit ? dy_s[o] : 0.0f;
+                }
+        } else {
+            for (int p = p_lo; p <= p_hi; ++p)
+                for (int q = q_lo; q <= q_hi; ++q)
+                    if (arg_s[obase + p * pp.Q + q] == e) acc += dy_s[obase + p * pp.Q + q];
+        }
+        if (act && !(ldf<T>(act, at) > 0.0f)) acc = old;
+        stf<T>(dx, at, acc);
+    }
+}
+
 // ---- 3x3 / stride 1 / pad 1 pooling on fp32 planes whose width is a multiple of 4 ----------------
 // (the pooling branch of an inception module). A lane owns four consecutive positions of one row:
 // per window row it needs the aligned packet of those four columns plus the column on either side,
@@ -725,7 +787,22 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
                            (const float*)dy, arg, (float*)dx, p3);
         return hipGetLastError();
     }
-    const PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, H * W, beta);
+    PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, H * W, beta);
+    // whole planes per workgroup with their arg and dy planes in LDS, when 8 bytes per window of a
+    // workgroup's planes fit 48 KB and a workgroup still has at most 16K positions to walk
+    if ((long long)pp.ppw * P * Q * 8 <= 48 * 1024 && (long long)pp.ppw * H * W <= 16384) {
+        const unsigned groups = (unsigned)((NC + pp.ppw - 1) / pp.ppw);
+        const size_t lds = (size_t)pp.ppw * P * Q * 8;
+        ProbeScope probe(st);
+        (void)hipGetLastError();
+#define CALL(K, S)                                                                                              \
+    BY_DTYPE(dtype,                                                                                             \
+             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<float, K, S>), dim3(groups), dim3(TPB), lds, st, (const float*)dy, arg, (float*)dx, (const float*)act, pp),     \
+             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<uint16_t, K, S>), dim3(groups), dim3(TPB), lds, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)act, pp))
+        POOL_SHAPES(CALL)
+#undef CALL
+        return hipGetLastError();
+    }
     const dim3 grid = pool_grid(pp, H * W);
     if (grid.y > 65535u) return hipErrorInvalidValue;
     ProbeScope probe(st);
