@@ -150,6 +150,12 @@ def test_benchmark_graph_of_the_five_layer_stack_at_full_batch():
                 assert rel_l2(to_host(gb.t[rec["dx"]][imgs]), ref_dx) <= tol, (L.name, "dx")
             assert rel_l2(host(gb, rec["dw"]), oracle.conv_bwd_weight(x, dy, w.shape, L.stride, L.pad)) <= tol, (L.name, "dw")
             assert rel_l2(host(gb, rec["db"]), oracle.bias_bwd(dy)) <= tol, (L.name, "db")
+        # the pooling operators of that graph, whole batch, bit for bit (the gradient goes through the
+        # fused MaxPoolBwd + ReLU-gradient operator: every pooled tensor here is a ReLU output)
+        assert len(gb.pool_records) == 3
+        for rec in gb.pool_records:
+            assert rec["fused_relu"]
+            check_pool_record(gb, rec)
     finally:
         gb.close()
 
