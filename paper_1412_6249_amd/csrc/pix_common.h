@@ -1,6 +1,7 @@
 // Device-side pieces shared by the forward / backward-data implicit-GEMM kernels (fp32 and bf16 MFMA).
 #pragma once
 #include "common.h"
+#include <type_traits>
 
 namespace purine {
 namespace pix {
@@ -319,68 +320,89 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 // 8-byte packet, so the 32 lanes of a half-wavefront cover 32 * TN consecutive pixels of one row,
 // whole 128-byte lines, and the fp32 -> bf16 conversion is the packed hardware one. Mask and old
 // values are read the same way.
+// The stores (and those reads) are raw buffer accesses on a resource that covers exactly image n's
+// Co output rows: the lane's part of the address (its pixel, its half's four rows) is one VGPR set
+// up once, the row's part a scalar, and a row at or past Co falls outside the resource and is dropped
+// by the hardware. With plain pointers every store carried a 64-bit multiply-add, a row test with
+// its exec-mask branch and the option flags' selects, about thirty instructions per store, and the
+// epilogue of a 3x3 tile took as long as its MFMAs.
 template <bool FUSED, int TM, int TN, bool FWD>
 __device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&acc)[TM][TN], int i_base, int n,
                                                int pix_first, int pix_end, int lane, const float* bias_lds,
                                                int i_tile0) {
     static_assert(TN == 2 || TN == 4, "4- or 8-byte packets");
     typedef uint32_t packet_t __attribute__((ext_vector_type(TN / 2)));
-    uint16_t* __restrict__ out = (uint16_t*)p.out;
-    const uint16_t* __restrict__ mask = (const uint16_t*)p.mask;
     const bool has_bias = FUSED && FWD && p.bias != nullptr, relu = FUSED && FWD && p.relu;
-    const bool has_mask = FUSED && !FWD && mask != nullptr, has_beta = !FWD && p.beta != 0.0f;
-    if (pix_first >= pix_end) return;
+    const bool has_mask = FUSED && !FWD && p.mask != nullptr, has_beta = !FWD && p.beta != 0.0f;
     const int khalf = lane >> 5;
-    const int obase = n * p.out_ns + pix_first;
+    const int img = __builtin_amdgcn_readfirstlane(n);
+    const int rows0 = __builtin_amdgcn_readfirstlane(i_base);
+    const int image_bytes = p.Co * p.HoWo * 2;
+    const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
+        (uint16_t*)p.out + (size_t)img * p.out_ns, (short)0, image_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_mask = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>((const uint16_t*)(has_mask ? p.mask : p.out)) + (size_t)img * p.out_ns, (short)0, image_bytes, 0x00020000);
+    // lanes past the tile's last pixel: an offset outside every resource
+    const unsigned voff = pix_first < pix_end ? (unsigned)(pix_first + khalf * 4 * p.HoWo) * 2u : 0x80000000u;
+    auto load_packet = [&](const __amdgpu_buffer_rsrc_t& r, int soff) {
+        packet_t v;
+        if constexpr (TN == 2) v[0] = __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, 0);
+        else v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+        return v;
+    };
+    auto rows = [&](auto relu_c) {
+        constexpr bool RELU = decltype(relu_c)::value;
 #pragma unroll
-    for (int a = 0; a < TM; ++a) {
-        // the bias of an accumulator quad's four consecutive rows as one 16-byte LDS read, all four
-        // quads requested before the first is used
-        floatx4 bq[4];
-        if (has_bias) {
+        for (int a = 0; a < TM; ++a) {
+            // the bias of an accumulator quad's four consecutive rows as one 16-byte LDS read, all four
+            // quads requested before the first is used
+            floatx4 bq[4];
+            if (FUSED && FWD) {
 #pragma unroll
-            for (int qd = 0; qd < 4; ++qd)
-                bq[qd] = *reinterpret_cast<const floatx4*>(&bias_lds[i_base + a * 32 + qd * 8 + khalf * 4 - i_tile0]);
-        }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = i_base + a * 32 + (e >> 2) * 8 + khalf * 4 + (e & 3);
-            if (row >= p.Co) continue;
-            const int off = obase + row * p.HoWo;
-            float x[TN];
-#pragma unroll
-            for (int b = 0; b < TN; ++b) x[b] = acc[a][b][e];
-            if (has_bias) {
-                const float bv = bq[e >> 2][e & 3];
-#pragma unroll
-                for (int b = 0; b < TN; ++b) x[b] += bv;
-            }
-            if (relu) {
-#pragma unroll
-                for (int b = 0; b < TN; ++b) x[b] = x[b] > 0.0f ? x[b] : 0.0f;
-            }
-            if (has_mask) {
-                const packet_t m = *reinterpret_cast<const packet_t*>(mask + off);
-#pragma unroll
-                for (int b = 0; b < TN; ++b) {
-                    const uint32_t w = m[b >> 1];
-                    x[b] = __uint_as_float((b & 1) ? (w & 0xffff0000u) : (w << 16)) > 0.0f ? x[b] : 0.0f;
+                for (int qd = 0; qd < 4; ++qd) {
+                    const floatx4 z = {0.0f, 0.0f, 0.0f, 0.0f};
+                    bq[qd] = has_bias ? *reinterpret_cast<const floatx4*>(&bias_lds[i_base + a * 32 + qd * 8 + khalf * 4 - i_tile0]) : z;
                 }
             }
-            if (has_beta) {
-                const packet_t o = *reinterpret_cast<const packet_t*>(out + off);
 #pragma unroll
-                for (int b = 0; b < TN; ++b) {
-                    const uint32_t w = o[b >> 1];
-                    x[b] += __uint_as_float((b & 1) ? (w & 0xffff0000u) : (w << 16));
+            for (int e = 0; e < 16; ++e) {
+                const int soff = (rows0 + a * 32 + (e >> 2) * 8 + (e & 3)) * p.HoWo * 2;   // scalar: the lane's khalf * 4 rows sit in voff
+                float x[TN];
+#pragma unroll
+                for (int b = 0; b < TN; ++b) x[b] = acc[a][b][e];
+                if (FUSED && FWD) {
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) x[b] += bq[e >> 2][e & 3];
                 }
-            }
-            packet_t r;
+                if (RELU) {
 #pragma unroll
-            for (int b = 0; b < TN; b += 2) r[b >> 1] = pack_bf16(x[b], x[b + 1]);
-            *reinterpret_cast<packet_t*>(out + off) = r;
+                    for (int b = 0; b < TN; ++b) x[b] = x[b] > 0.0f ? x[b] : 0.0f;
+                }
+                if (has_mask) {
+                    const packet_t m = load_packet(r_mask, soff);
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const uint32_t w = m[b >> 1];
+                        x[b] = __uint_as_float((b & 1) ? (w & 0xffff0000u) : (w << 16)) > 0.0f ? x[b] : 0.0f;
+                    }
+                }
+                if (has_beta) {
+                    const packet_t o = load_packet(r_out, soff);
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const uint32_t w = o[b >> 1];
+                        x[b] += __uint_as_float((b & 1) ? (w & 0xffff0000u) : (w << 16));
+                    }
+                }
+                packet_t r;
+#pragma unroll
+                for (int b = 0; b < TN; b += 2) r[b >> 1] = pack_bf16(x[b], x[b + 1]);
+                if constexpr (TN == 2) __builtin_amdgcn_raw_buffer_store_b32(r[0], r_out, voff, soff, 0);
+                else __builtin_amdgcn_raw_buffer_store_b64(r, r_out, voff, soff, 0);
+            }
         }
-    }
+    };
+    if (relu) rows(std::true_type{}); else rows(std::false_type{});
 }
 
 // Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). Give each
