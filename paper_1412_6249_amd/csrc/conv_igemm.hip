@@ -611,6 +611,9 @@ static PixParams make_pix_params(int dtype, const ConvGeom& g, const PixPlan& pl
         // offsets below 2^31
         const long long in_bytes = ((long long)(p.N - 1) * p.in_ns + (long long)p.Ci * p.HiWi) * 4;
         p.in_bytes = (dtype == PURINE_F32 && in_bytes < 0x7fffffffLL && g_no_buffer_loads == 0) ? (unsigned)in_bytes : 0u;
+        // raw-buffer stores of the epilogues into an NCHW output (not the depth-to-space one)
+        const long long out_bytes = ((long long)(p.N - 1) * p.out_ns + (long long)p.Co * p.HoWo) * (dtype == PURINE_BF16 ? 2 : 4);
+        p.out_bytes = (pl.mode != 2 && out_bytes < 0x7fffffffLL && g_no_buffer_loads == 0) ? (unsigned)out_bytes : 0u;
     }
 
     return p;

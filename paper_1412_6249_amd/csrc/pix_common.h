@@ -77,6 +77,7 @@ struct PixParams {
     int relu;
     int tiles_i, tiles_pix;
     unsigned in_bytes;   // span of the gathered tensor when the fp32 tap kernels may read it as a raw buffer, else 0
+    unsigned out_bytes;  // span of the NCHW output when the epilogues may write it as a raw buffer (below 2^31 bytes), else 0
     // elements between consecutive images of the gathered and of the produced tensor (the mask shares
     // the latter): Ci*Hi*Wi and the dense image size of `out` unless they are channel-slice views
     int in_ns, out_ns;
@@ -87,6 +88,14 @@ struct PixParams {
     float* partial;
 };
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// Two fp32 values to two bf16 (round to nearest even) in one dword, first value in the low half.
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const floatx2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
+}
 // The fused forward kernels stage their row tile's bias values in LDS at kernel start (zero past the
 // last output channel), so the epilogue does not wait on global memory for them. The caller's
 // first barrier orders the fill before any use.
@@ -149,10 +158,62 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
                                            floatx16 (&acc)[TM][TN], int i_base, int pix_base,
                                            int khalf, const float* bias_lds, int i_tile0,
                                            int pix_limit = 0x7fffffff, int bstep = 32) {
+    if ((!FUSED || FWD) && !D2S && p.out_bytes != 0) {
+        // NCHW output through raw buffer stores: a lane's pixel (and its half's four rows) is one
+        // offset register per column tile, set up once; a row's part of the address is a scalar; a
+        // row at or past Co gets an offset outside the resource and the hardware drops the store.
+        // (With plain pointers every element carried its own row test and exec-mask branch, a 64-bit
+        // address computation and, for a fused bias, an LDS round trip of its own: over twenty
+        // instructions per store.)
+        const bool fwd_bias = FUSED && FWD && p.bias != nullptr, fwd_relu = FUSED && FWD && p.relu;
+        const bool has_beta = !FWD && p.beta != 0.0f;
+        const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(out, (short)0, (int)p.out_bytes, 0x00020000);
+        unsigned voff[TN];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int pix = pix_base + b * bstep;
+            const bool live = pix < p.M && pix < pix_limit;
+            const int n = fastdiv(live ? pix : 0, p.div_howo);
+            voff[b] = live ? (unsigned)(n * p.out_ns + (pix - n * p.HoWo) + khalf * 4 * p.HoWo) * (unsigned)sizeof(T) : 0x80000000u;
+        }
+        const int rows0 = __builtin_amdgcn_readfirstlane(i_base);
+        auto rows = [&](auto relu_c) {
+            constexpr bool RELU = decltype(relu_c)::value;
+#pragma unroll
+            for (int a = 0; a < TM; ++a) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row_lo = rows0 + a * 32 + (e >> 2) * 8 + (e & 3);     // scalar; this lane's row is khalf * 4 further
+                    if (row_lo >= p.Co) continue;                                   // uniform
+                    const int soff = row_lo * p.HoWo * (int)sizeof(T);
+                    const bool row_ok = row_lo + khalf * 4 < p.Co;
+                    float bv = 0.0f;
+                    if (FUSED && FWD) bv = fwd_bias ? bias_lds[row_lo + khalf * 4 - i_tile0] : 0.0f;
+#pragma unroll
+                    for (int b = 0; b < TN; ++b) {
+                        const unsigned vo = row_ok ? voff[b] : 0x80000000u;
+                        float v = acc[a][b][e];
+                        if (FUSED && FWD) v += bv;
+                        if (RELU) v = v > 0.0f ? v : 0.0f;
+                        if (sizeof(T) == 4) {
+                            if (has_beta) v += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r_out, vo, soff, 0));
+                            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, v), r_out, vo, soff, 0);
+                        } else {
+                            if (has_beta) v += __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r_out, vo, soff, 0) << 16);
+                            __builtin_amdgcn_raw_buffer_store_b16((uint16_t)(pack_bf16(v, 0.0f) & 0xffffu), r_out, vo, soff, 0);
+                        }
+                    }
+                }
+            }
+        };
+        if (fwd_relu) rows(std::true_type{}); else rows(std::false_type{});
+        return;
+    }
     if (!FUSED || FWD) {
         // Plain store (backward-data: optionally accumulating) and the fused forward epilogue, which
         // needs nothing from global memory (bias comes from LDS): no staging arrays, so these
-        // kernels keep their register count and occupancy.
+        // kernels keep their register count and occupancy. (Depth-to-space outputs, and NCHW outputs
+        // of 2^31 bytes or more.)
         const bool fwd_bias = FUSED && FWD && !D2S && p.bias != nullptr, fwd_relu = FUSED && FWD && p.relu;
         constexpr bool QUAD = sizeof(T) == 2;   // bf16: bias of four consecutive rows as one 16-byte LDS read
 #pragma unroll
@@ -306,14 +367,6 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
     }
 }
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-
-// Two fp32 values to two bf16 (round to nearest even) in one dword, first value in the low half.
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    const floatx2 f = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
-}
 // Epilogue for kernels whose lanes own TN ADJACENT pixels (column tile b of lane l is pixel
 // TN * (l % 32) + b of the wavefront's strip) and NCHW bf16 outputs in which such a run is aligned
 // (HoWo and the image distance multiples of TN): a lane writes its TN pixels of one row as one 4- or
