@@ -253,6 +253,10 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
                                               lane, bias_s, i0);
         return;
     }
+    if (D2S && p.sh == 2 && p.sw == 2 && q.d2s_buffers) {
+        store_d2s2_adjacent<FUSED, TM, TN>(p, acc, i0 + wm * TM * 32, n, pix0 + wn * TN * 32 + TN * (lane & 31), pix_end, lane);
+        return;
+    }
     store_tile<uint16_t, D2S, FUSED, TM, TN, !MINUS>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
                                                      n * p.HoWo + pix0 + wn * TN * 32 + TN * (lane & 31), lane >> 5,
                                                      bias_s, i0, n * p.HoWo + pix_end, 1);
@@ -741,6 +745,8 @@ bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* qg) {
     p.in_bytes = (unsigned)in_bytes;
     // 4-byte stores of pixel pairs: every row of every image starts at an even element
     q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out | (uintptr_t)p.mask) & 3u) == 0;
+    // depth-to-space outputs through raw buffer stores: one image of dx below 2^31 bytes
+    q.d2s_buffers = mode == 2 && (long long)p.C * p.H * p.W * 2 < 0x7fffffffLL && !buffer_loads_disabled();
     q.roles = 0;
     plan_roles(p, mode, q);       // the two-role kernel where it applies: replaces tile, patch and stage geometry
     *qg = q;

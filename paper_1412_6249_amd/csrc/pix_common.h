@@ -458,6 +458,68 @@ __device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&ac
     if (relu) rows(std::true_type{}); else rows(std::false_type{});
 }
 
+// Depth-to-space epilogue of stride-2 x stride-2 phase-folded backward-data for kernels whose lanes
+// own TN adjacent coarse pixels of ONE image (bf16 dx, NCHW). Row i of the tile is (c, a, b) =
+// (i / 4, (i / 2) % 2, i % 2) and lands at dx[n, c, hq*2 + a - ph, wq*2 + b - pw]. For accumulator
+// register e of a lane, a and b depend on e alone and c is a scalar plus the lane's half, so a lane
+// needs, per coarse pixel, the four offsets of its (a, b) positions (outside the image: an offset
+// outside the resource), and a store is a conversion and one raw buffer store with a scalar channel
+// offset; channels at or past C fall outside the resource, which covers image n. (The general
+// depth-to-space epilogue decodes every element's row with reciprocal divisions and tests its
+// position, some forty instructions per 2-byte store.)
+template <bool FUSED, int TM, int TN>
+__device__ __forceinline__ void store_d2s2_adjacent(const PixParams& p, floatx16 (&acc)[TM][TN], int i_base, int n,
+                                                    int pix_first, int pix_end, int lane) {
+    const bool has_mask = FUSED && p.mask != nullptr, has_beta = p.beta != 0.0f;
+    const int khalf = lane >> 5;
+    const int img = __builtin_amdgcn_readfirstlane(n);
+    const int rows0 = __builtin_amdgcn_readfirstlane(i_base);
+    const int plane = p.H * p.W;
+    const int image_bytes = p.C * plane * 2;
+    const __amdgpu_buffer_rsrc_t r_out = __builtin_amdgcn_make_buffer_rsrc(
+        (uint16_t*)p.out + (size_t)img * p.out_ns, (short)0, image_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t r_mask = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>((const uint16_t*)(has_mask ? p.mask : p.out)) + (size_t)img * p.out_ns, (short)0, image_bytes, 0x00020000);
+    unsigned voff[TN][2][2];
+#pragma unroll
+    for (int b = 0; b < TN; ++b) {
+        const int pix = pix_first + b;
+        const bool live = pix < pix_end;
+        const int hq = fastdiv(live ? pix : 0, p.div_wo);
+        const int wq = (live ? pix : 0) - hq * p.Wo;
+        const int hb = (hq + p.hq_min) * 2 - p.ph, wb = (wq + p.wq_min) * 2 - p.pw;
+#pragma unroll
+        for (int pa = 0; pa < 2; ++pa)
+#pragma unroll
+            for (int pb = 0; pb < 2; ++pb) {
+                const int h = hb + pa, w = wb + pb;
+                const bool ok = live & ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
+                voff[b][pa][pb] = ok ? (unsigned)(khalf * plane + h * p.W + w) * 2u : 0x80000000u;
+            }
+    }
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            // row = rows0 + a*32 + (e>>2)*8 + khalf*4 + (e&3): channel (rows0 + a*32 + (e>>2)*8) / 4 + khalf, phase (e&3)
+            const int c_lo = (rows0 + a * 32 + (e >> 2) * 8) >> 2;      // scalar
+            if (c_lo >= p.C) continue;                                    // uniform: both halves past the last channel
+            const int soff = c_lo * plane * 2;
+            constexpr int dummy = 0; (void)dummy;
+            const int pa = (e & 3) >> 1, pb = e & 1;
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                const unsigned vo = voff[b][pa][pb];
+                float v = acc[a][b][e];
+                if (has_mask)
+                    v = __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r_mask, vo, soff, 0) << 16) > 0.0f ? v : 0.0f;
+                if (has_beta) v += __uint_as_float((uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r_out, vo, soff, 0) << 16);
+                __builtin_amdgcn_raw_buffer_store_b16((uint16_t)(pack_bf16(v, 0.0f) & 0xffffu), r_out, vo, soff, 0);
+            }
+        }
+    }
+}
+
 // Consecutive workgroup ids land on different XCDs (8 per chip, each with its own L2). Give each
 // XCD a contiguous run of tiles so that neighbouring pixel tiles share halo rows in one L2.
 __device__ __forceinline__ int xcd_tile(int bid, int total) {
@@ -514,6 +576,7 @@ struct PatchGeom {
     int a_bytes, lds_bytes;
     int plane_bytes;     // bytes of one (position parity, channel half) plane of the patch
     int tasks_per_row;   // fill tasks per patch row: packets rounded up to fours x two halves
+    int d2s_buffers;     // phase-folded backward-data: the depth-to-space epilogue may use raw buffer stores
     int roles;           // 1: the persistent kernel whose wavefronts split into fill and multiply roles
     int roles_lds;       // its LDS bytes
     FastDiv div_tpi, div_tpr, div_chunks, div_halo, div_st;
