@@ -641,6 +641,7 @@ void plan_roles(PixParams& p, int mode, PatchGeom& q) {
     if (patch_split_roles_disabled()) return;
     if (p.St != 3 && p.St != 4) return;
     if (mode == 2 || (p.Wo & 3) || (p.out_ns & 3) || (((uintptr_t)p.out | (uintptr_t)p.mask) & 7u) != 0) return;
+    if ((long long)p.Co * p.HoWo * 2 >= 0x7fffffffLL) return;      // its epilogue addresses one image as a raw buffer
     PatchGeom r = q;
     r.bm = p.Co <= 32 ? 32 : 64;
     r.bn = 512;
@@ -744,7 +745,9 @@ bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* qg) {
     if ((long long)n_taps * p.i_pad * p.Ci_pad > 0x7fffffffLL) return false;
     p.in_bytes = (unsigned)in_bytes;
     // 4-byte stores of pixel pairs: every row of every image starts at an even element
-    q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out | (uintptr_t)p.mask) & 3u) == 0;
+    // (the paired epilogue addresses one image of the output as a raw buffer: below 2^31 bytes)
+    q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out | (uintptr_t)p.mask) & 3u) == 0 &&
+              (long long)p.Co * p.HoWo * 2 < 0x7fffffffLL;
     // depth-to-space outputs through raw buffer stores: one image of dx below 2^31 bytes
     q.d2s_buffers = mode == 2 && (long long)p.C * p.H * p.W * 2 < 0x7fffffffLL && !buffer_loads_disabled();
     q.roles = 0;

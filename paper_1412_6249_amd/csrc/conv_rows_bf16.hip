@@ -273,7 +273,8 @@ bool plan_rows_bf16(PixParams& p, RowsGeom* qg) {
     q.div_tpi = make_fastdiv(q.tiles_per_img);
     q.div_chunks = make_fastdiv(q.chunks);
     q.div_pr = make_fastdiv(q.pr_max);
-    q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out) & 3u) == 0;   // TN = 2 adjacent pixels per lane
+    // TN = 2 adjacent pixels per lane; that epilogue addresses one image of the output as a raw buffer
+    q.pairs = ((p.HoWo | p.out_ns) & 1) == 0 && (((uintptr_t)p.out) & 3u) == 0 && (long long)p.Co * p.HoWo * 2 < 0x7fffffffLL;
     p.in_bytes = (unsigned)in_bytes;
     *qg = q;
     return true;
