@@ -324,7 +324,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
         "config": {"workload": main_res["workload"], "conv_gflop_per_step": main_res["conv_gflop_per_step"],
-                   "executor": "bi-graph, %s%s, %s" % ("1 stream" if args.single_stream else "3+ streams",
+                   "executor": "bi-graph, %s%s, %s" % ("1 stream" if args.single_stream or cfg == 5 else "3+ streams",
                                                         ", recorded pass replayed" if args.replay else "",
                                                       "separate bias/relu ops" if args.unfused
                                                       else "bias+relu fused into conv vertices"

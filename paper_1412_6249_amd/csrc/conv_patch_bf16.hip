@@ -254,7 +254,16 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
         return;
     }
     if (D2S && p.sh == 2 && p.sw == 2 && q.d2s_buffers) {
-        store_d2s2_adjacent<FUSED, TM, TN>(p, acc, i0 + wm * TM * 32, n, pix0 + wn * TN * 32 + TN * (lane & 31), pix_end, lane);
+        int hq_of[TN], wq_of[TN];
+        bool live_of[TN];
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int pix = pix0 + wn * TN * 32 + TN * (lane & 31) + b;
+            live_of[b] = pix < pix_end;
+            hq_of[b] = fastdiv(live_of[b] ? pix : 0, p.div_wo);
+            wq_of[b] = (live_of[b] ? pix : 0) - hq_of[b] * p.Wo;
+        }
+        store_d2s2_adjacent<FUSED, TM, TN>(p, acc, i0 + wm * TM * 32, n, hq_of, wq_of, live_of, lane);
         return;
     }
     store_tile<uint16_t, D2S, FUSED, TM, TN, !MINUS>(p, (uint16_t*)p.out, acc, i0 + wm * TM * 32,
@@ -275,11 +284,11 @@ __global__ __launch_bounds__(256, 2) void igemm_patch_bf16_kernel(const PixParam
 // fragment reads instead of 4 * ST, and with the filter rows read once per tap for all four pixel
 // tiles the LDS traffic per MFMA is half that of the one-role kernel, whose tap loop is bound by it.
 // Rows are taken in pairs, the next row's fragments requested before the current row's MFMAs.
-// Output rows are whole groups of four pixels, so a lane's four pixels share a row. Phase-folded
-// backward-data stays on the one-role kernel (measured no faster here: its time goes to the
-// depth-to-space stores).
+// Pixel tiles count in rows of q.wv pixels, the output width rounded up to a multiple of four, so
+// that a lane's four pixels share an output row; the up to three pixels past a row's end are
+// computed and not stored (only the depth-to-space epilogue of stride-2 layers takes such widths).
 constexpr int RTN = 4;     // adjacent pixels per multiply lane
-template <bool MINUS, bool FUSED, int TM, int ST, int ROUNDS>
+template <bool MINUS, bool D2S, bool FUSED, int TM, int ST, int ROUNDS>
 __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const PixParams p, const PatchGeom q) {
     constexpr int NT = 256;                 // threads of each role
     constexpr int TN = RTN;
@@ -376,7 +385,7 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
                 const int tp = tile / p.tiles_i;
                 const int n = fastdiv(tp, q.div_tpi);
                 const int pix0 = (tp - n * q.tiles_per_img) * BN;
-                const int h_lo = fastdiv(pix0, p.div_wo) + q.h_lo_add;
+                const int h_lo = fastdiv(pix0, q.div_wv) + q.h_lo_add;
 #pragma unroll
                 for (int r = 0; r < ROUNDS; ++r) {
                     const int hi = h_lo + t_pr[r];
@@ -464,12 +473,12 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
             const int tp = tile / p.tiles_i;
             n = fastdiv(tp, q.div_tpi);
             pix0 = (tp - n * q.tiles_per_img) * BN;
-            pix_end = min(pix0 + BN, p.HoWo);
-            const int ho_first = fastdiv(pix0, p.div_wo);
+            pix_end = min(pix0 + BN, p.Ho * q.wv);
+            const int ho_first = fastdiv(pix0, q.div_wv);
             // lanes past the tile's last pixel re-read its last four (their results are never stored)
             const int pix = min(pix0 + wn * TN * 32 + TN * (lane & 31), pix_end - TN);
-            const int ho = fastdiv(pix, p.div_wo);
-            const int wo = pix - ho * p.Wo;
+            const int ho = fastdiv(pix, q.div_wv);
+            const int wo = pix - ho * q.wv;
             X0 = (ho - ho_first) * q.pw + wo + q.pos_add;
 #pragma unroll
             for (int a = 0; a < TM; ++a)
@@ -526,7 +535,18 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
         if (group == n_groups) {
             group = 0; tl += 1;
             const int pix_first = pix0 + wn * TN * 32 + TN * (lane & 31);
-            store_adjacent<FUSED, TM, TN, !MINUS>(p, acc, i0, n, pix_first, pix_end, lane, bias_s + i0, i0);
+            if constexpr (!D2S) {
+                store_adjacent<FUSED, TM, TN, !MINUS>(p, acc, i0, n, pix_first, pix_end, lane, bias_s + i0, i0);   // q.wv == p.Wo here
+            } else {
+                // this lane's coarse pixels (ho, wo .. wo + 3) in rows of q.wv: those inside the folded row
+                const int ho = fastdiv(pix_first, q.div_wv);
+                const int wo = pix_first - ho * q.wv;
+                int hq_of[TN], wq_of[TN];
+                bool live_of[TN];
+#pragma unroll
+                for (int b = 0; b < TN; ++b) { hq_of[b] = ho; wq_of[b] = wo + b; live_of[b] = pix_first < pix_end && wo + b < p.Wo; }
+                store_d2s2_adjacent<FUSED, TM, TN>(p, acc, i0, n, hq_of, wq_of, live_of, lane);
+            }
         }
     }
 }
@@ -567,9 +587,9 @@ __global__ __launch_bounds__(256) void repack_groups_kernel(const GroupRepack g)
     }
 }
 
-template <bool MINUS, bool FUSED, int TM, int ST, int ROUNDS>
+template <bool MINUS, bool D2S, bool FUSED, int TM, int ST, int ROUNDS>
 hipError_t launch_roles(const PixParams& p, const PatchGeom& q, hipStream_t st) {
-    auto kern = igemm_patch_roles_bf16_kernel<MINUS, FUSED, TM, ST, ROUNDS>;
+    auto kern = igemm_patch_roles_bf16_kernel<MINUS, D2S, FUSED, TM, ST, ROUNDS>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, q.roles_lds);
     if (e != hipSuccess) return e;
     ProbeScope probe(st);
@@ -577,10 +597,10 @@ hipError_t launch_roles(const PixParams& p, const PatchGeom& q, hipStream_t st) 
     hipLaunchKernelGGL(kern, dim3(256), dim3(512), (size_t)q.roles_lds, st, p, q);
     return hipGetLastError();
 }
-template <bool MINUS, bool FUSED>
+template <bool MINUS, bool D2S, bool FUSED>
 hipError_t roles_by_shape(const PixParams& p, const PatchGeom& q, hipStream_t st) {
-#define ROLES_CALL(TM, ST) (q.rounds == 1 ? launch_roles<MINUS, FUSED, TM, ST, 1>(p, q, st) \
-                                          : launch_roles<MINUS, FUSED, TM, ST, 2>(p, q, st))
+#define ROLES_CALL(TM, ST) (q.rounds == 1 ? launch_roles<MINUS, D2S, FUSED, TM, ST, 1>(p, q, st) \
+                                          : launch_roles<MINUS, D2S, FUSED, TM, ST, 2>(p, q, st))
     switch (q.bm * 10 + p.St) {
         case 323: return ROLES_CALL(1, 3);
         case 324: return ROLES_CALL(1, 4);
@@ -625,7 +645,7 @@ hipError_t by_tile(const PixParams& p, const PatchGeom& q, hipStream_t st) {
 template <bool MINUS, bool D2S>
 hipError_t by_epilogue(const PixParams& p, const PatchGeom& q, hipStream_t st) {
     const bool fused = p.bias || p.relu || p.mask;
-    if (q.roles && !D2S) return fused ? roles_by_shape<MINUS, true>(p, q, st) : roles_by_shape<MINUS, false>(p, q, st);
+    if (q.roles) return fused ? roles_by_shape<MINUS, D2S, true>(p, q, st) : roles_by_shape<MINUS, D2S, false>(p, q, st);
     return fused ? by_tile<MINUS, D2S, true>(p, q, st) : by_tile<MINUS, D2S, false>(p, q, st);
 }
 
@@ -640,25 +660,29 @@ namespace {
 void plan_roles(PixParams& p, int mode, PatchGeom& q) {
     if (patch_split_roles_disabled()) return;
     if (p.St != 3 && p.St != 4) return;
-    if (mode == 2 || (p.Wo & 3) || (p.out_ns & 3) || (((uintptr_t)p.out | (uintptr_t)p.mask) & 7u) != 0) return;
-    if ((long long)p.Co * p.HoWo * 2 >= 0x7fffffffLL) return;      // its epilogue addresses one image as a raw buffer
+    if (mode != 2 && ((p.Wo & 3) || (p.out_ns & 3) || (((uintptr_t)p.out | (uintptr_t)p.mask) & 7u) != 0)) return;
+    if (mode != 2 && (long long)p.Co * p.HoWo * 2 >= 0x7fffffffLL) return;   // its epilogue addresses one image as a raw buffer
+    if (mode == 2 && !(p.sh == 2 && p.sw == 2 && q.d2s_buffers)) return;      // depth-to-space: the stride-2 raw-buffer epilogue only
     PatchGeom r = q;
+    r.wv = (p.Wo + 3) / 4 * 4;
+    r.div_wv = make_fastdiv(r.wv);
     r.bm = p.Co <= 32 ? 32 : 64;
     r.bn = 512;
     const int n_taps = p.Rt * p.St;
-    const int rows_spanned = (r.bn - 2) / p.Wo + 2;
+    const int rows_spanned = (r.bn - 2) / r.wv + 2;
     r.pr_max = (rows_spanned < p.Ho ? rows_spanned : p.Ho) + p.Rt - 1;
     const long long tasks = (long long)r.pr_max * r.tasks_per_row;
     if (tasks > 2 * 256) return;
     r.rounds = tasks > 256 ? 2 : 1;
-    const long long plane = ((long long)r.pr_max * r.pw + 3) / 4 * 16;
+    // (+ 4 positions: the windows of the pixels past a row's end run past the last patch row)
+    const long long plane = ((long long)r.pr_max * r.pw + 4 + 3) / 4 * 16;
     r.plane_bytes = (int)((plane + 95) / 128 * 128 + 32);      // 32 past a multiple of 128
     const long long a_tap = 2LL * (r.bm * 16 + 64);
     if ((long long)n_taps * r.bm * 2 > (long long)A_ROUNDS * 256) return;
     r.taps_per_stage = n_taps;
     r.a_rounds = (int)(((long long)n_taps * r.bm * 2 + 255) / 256);
     r.a_bytes = (int)(n_taps * a_tap);
-    r.tiles_per_img = (p.HoWo + r.bn - 1) / r.bn;
+    r.tiles_per_img = (p.Ho * r.wv + r.bn - 1) / r.bn;
     const long long tiles_pix = (long long)p.N * r.tiles_per_img;
     const int tiles_i = (p.Co + r.bm - 1) / r.bm;
     if (tiles_pix * tiles_i > 0x7fffffffLL) return;

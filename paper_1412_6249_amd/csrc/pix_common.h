@@ -459,7 +459,7 @@ __device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&ac
 }
 
 // Depth-to-space epilogue of stride-2 x stride-2 phase-folded backward-data for kernels whose lanes
-// own TN adjacent coarse pixels of ONE image (bf16 dx, NCHW). Row i of the tile is (c, a, b) =
+// own TN coarse pixels (hq_of[b], wq_of[b]) of ONE image (bf16 dx, NCHW). Row i of the tile is (c, a, b) =
 // (i / 4, (i / 2) % 2, i % 2) and lands at dx[n, c, hq*2 + a - ph, wq*2 + b - pw]. For accumulator
 // register e of a lane, a and b depend on e alone and c is a scalar plus the lane's half, so a lane
 // needs, per coarse pixel, the four offsets of its (a, b) positions (outside the image: an offset
@@ -469,7 +469,8 @@ __device__ __forceinline__ void store_adjacent(const PixParams& p, floatx16 (&ac
 // position, some forty instructions per 2-byte store.)
 template <bool FUSED, int TM, int TN>
 __device__ __forceinline__ void store_d2s2_adjacent(const PixParams& p, floatx16 (&acc)[TM][TN], int i_base, int n,
-                                                    int pix_first, int pix_end, int lane) {
+                                                    const int (&hq_of)[TN], const int (&wq_of)[TN], const bool (&live_of)[TN],
+                                                    int lane) {
     const bool has_mask = FUSED && p.mask != nullptr, has_beta = p.beta != 0.0f;
     const int khalf = lane >> 5;
     const int img = __builtin_amdgcn_readfirstlane(n);
@@ -483,11 +484,8 @@ __device__ __forceinline__ void store_d2s2_adjacent(const PixParams& p, floatx16
     unsigned voff[TN][2][2];
 #pragma unroll
     for (int b = 0; b < TN; ++b) {
-        const int pix = pix_first + b;
-        const bool live = pix < pix_end;
-        const int hq = fastdiv(live ? pix : 0, p.div_wo);
-        const int wq = (live ? pix : 0) - hq * p.Wo;
-        const int hb = (hq + p.hq_min) * 2 - p.ph, wb = (wq + p.wq_min) * 2 - p.pw;
+        const bool live = live_of[b];
+        const int hb = (hq_of[b] + p.hq_min) * 2 - p.ph, wb = (wq_of[b] + p.wq_min) * 2 - p.pw;
 #pragma unroll
         for (int pa = 0; pa < 2; ++pa)
 #pragma unroll
@@ -579,6 +577,8 @@ struct PatchGeom {
     int d2s_buffers;     // phase-folded backward-data: the depth-to-space epilogue may use raw buffer stores
     int roles;           // 1: the persistent kernel whose wavefronts split into fill and multiply roles
     int roles_lds;       // its LDS bytes
+    int wv;              // ... and the row width its pixel tiles count in: Wo rounded up to whole groups of four
+    FastDiv div_wv;
     FastDiv div_tpi, div_tpr, div_chunks, div_halo, div_st;
 };
 bool plan_patch_bf16(PixParams& p, int mode, PatchGeom* q);
