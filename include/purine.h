@@ -196,11 +196,14 @@ int purine_maxpool_fwd(const purine_pool_desc* desc, const purine_tensor* x, pur
 int purine_maxpool_bwd(const purine_pool_desc* desc, const purine_tensor* dy,
                        const purine_tensor* arg, purine_tensor* dx, float beta, void* hip_stream);
 /* The same followed by the ReLU gradient of the pooled tensor, as one operator (fusion in the
- * sense of paper section 3.4's note that adjacent operators may share a kernel): where
- * act[n,c,h,w] > 0, dx is what purine_maxpool_bwd gives, bit for bit; elsewhere the pooling sum is
- * dropped (dx = beta*dx). act: the tensor that was pooled (a ReLU output), extents and dtype of dx. */
+ * sense of paper section 3.4's note that adjacent operators may share a kernel). y: the pooling
+ * output of the forward pass (extents and dtype of dy). Only windows with y > 0 pass their dy on:
+ * dx[n,c,pos] = beta*dx + sum of dy over the windows that chose pos and have y > 0, same order of
+ * summation. A position that won a window holds that window's y, so when the pooled tensor is a
+ * ReLU output this is purine_maxpool_bwd followed by purine_relu_bwd on it: bit for bit the former
+ * where the pooled tensor is positive, beta*dx elsewhere. The pooled tensor itself is not read. */
 int purine_maxpool_bwd_relu(const purine_pool_desc* desc, const purine_tensor* dy,
-                            const purine_tensor* arg, const purine_tensor* act, purine_tensor* dx,
+                            const purine_tensor* arg, const purine_tensor* y, purine_tensor* dx,
                             float beta, void* hip_stream);
 /* Channel concatenation of n_parts NCHW tensors (same N,H,W,dtype) and its inverse. */
 int purine_concat_fwd(const purine_tensor* const* parts, int n_parts, purine_tensor* out,
@@ -294,7 +297,7 @@ typedef enum {
     PURINE_OP_GROUPED_CONV_FWD = 21,   /* in: x, w, b         out: y   (attrs.groups, attrs.relu)    */
     PURINE_OP_GROUPED_CONV_BWD_DATA = 22,   /* in: dy, w [, dx]      out: dx'  (attrs.groups)        */
     PURINE_OP_GROUPED_CONV_BWD_WEIGHT = 23, /* in: x, dy [, dw, db]  out: dw', db'  (attrs.groups)   */
-    PURINE_OP_MAXPOOL_BWD_RELU = 24         /* in: dy, arg, act [, dx]  out: dx'                     */
+    PURINE_OP_MAXPOOL_BWD_RELU = 24         /* in: dy, arg, y [, dx]    out: dx'                     */
 } purine_op_kind;
 
 /* PURINE_OP_ALIAS does no device work. It gives storage that other operators have written a tensor

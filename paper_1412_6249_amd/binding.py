@@ -394,9 +394,9 @@ def purine_maxpool_bwd(desc, dy, arg, dx, beta=0.0, stream=None):
            "purine_maxpool_bwd")
 
 
-def purine_maxpool_bwd_relu(desc, dy, arg, act, dx, beta=0.0, stream=None):
+def purine_maxpool_bwd_relu(desc, dy, arg, y, dx, beta=0.0, stream=None):
     _check(_lib.purine_maxpool_bwd_relu(_ref(desc), _ref(tensor_desc(dy)), _ref(tensor_desc(arg)),
-                                        _ref(tensor_desc(act)), _ref(tensor_desc(dx)), float(beta), _stream(stream)),
+                                        _ref(tensor_desc(y)), _ref(tensor_desc(dx)), float(beta), _stream(stream)),
            "purine_maxpool_bwd_relu")
 
 

@@ -492,18 +492,18 @@ int purine_maxpool_fwd(const purine_pool_desc* desc, const purine_tensor* x, pur
 
 namespace {
 int maxpool_bwd_impl(const purine_pool_desc* desc, const purine_tensor* dy, const purine_tensor* arg,
-                     const purine_tensor* act, purine_tensor* dx, float beta, void* hip_stream) {
+                     const purine_tensor* y, purine_tensor* dx, float beta, void* hip_stream) {
     int rc;
     if ((rc = check_tensor(dy, 4)) || (rc = check_tensor(arg, 4)) || (rc = check_tensor(dx, 4)) ||
-        (act && (rc = check_tensor(act, 4))) || (rc = check_beta(beta)))
+        (y && (rc = check_tensor(y, 4))) || (rc = check_beta(beta)))
         return rc;
     if (!is_float_dtype(dy->dtype) || dx->dtype != dy->dtype || arg->dtype != PURINE_I32) return PURINE_E_DTYPE;
-    if (act && act->dtype != dx->dtype) return PURINE_E_DTYPE;
+    if (y && y->dtype != dy->dtype) return PURINE_E_DTYPE;
     if ((rc = pool_geom(desc, dx, dy))) return rc;
-    if (!same_dims(dy, arg) || (act && !same_dims(act, dx))) return PURINE_E_SHAPE;
-    if (overlaps(dx, dy) || overlaps(dx, arg) || (act && overlaps(dx, act))) return PURINE_E_LAYOUT;
+    if (!same_dims(dy, arg) || (y && !same_dims(y, dy))) return PURINE_E_SHAPE;
+    if (overlaps(dx, dy) || overlaps(dx, arg) || (y && overlaps(dx, y))) return PURINE_E_LAYOUT;
     hipError_t e = launch_maxpool_bwd(dy->dtype, dy->data, (const int32_t*)arg->data, dx->data,
-                                      act ? act->data : nullptr, beta,
+                                      y ? y->data : nullptr, beta,
                                       (int)(dx->dim[0] * dx->dim[1]), (int)dx->dim[2],
                                       (int)dx->dim[3], (int)dy->dim[2], (int)dy->dim[3],
                                       desc->window, desc->stride, desc->pad, (hipStream_t)hip_stream);
@@ -517,9 +517,9 @@ int purine_maxpool_bwd(const purine_pool_desc* desc, const purine_tensor* dy,
 }
 
 int purine_maxpool_bwd_relu(const purine_pool_desc* desc, const purine_tensor* dy, const purine_tensor* arg,
-                            const purine_tensor* act, purine_tensor* dx, float beta, void* hip_stream) {
-    if (!act) return PURINE_E_NULL;
-    return maxpool_bwd_impl(desc, dy, arg, act, dx, beta, hip_stream);
+                            const purine_tensor* y, purine_tensor* dx, float beta, void* hip_stream) {
+    if (!y) return PURINE_E_NULL;
+    return maxpool_bwd_impl(desc, dy, arg, y, dx, beta, hip_stream);
 }
 
 static int concat_check(const purine_tensor* const* parts, int n_parts, const purine_tensor* whole) {

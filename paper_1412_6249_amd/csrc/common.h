@@ -164,7 +164,7 @@ hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* ne
                              int64_t n, hipStream_t st);
 hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, int NC, int H, int W,
                               int P, int Q, int k, int stride, int pad, hipStream_t st);
-hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, const void* act, float beta,
+hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, const void* y, float beta,
                               int NC, int H, int W, int P, int Q, int k, int stride, int pad,
                               hipStream_t st);
 hipError_t launch_copy_channels(int dtype, const void* src, void* dst, int N, int c_count,

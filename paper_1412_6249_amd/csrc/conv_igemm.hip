@@ -664,11 +664,11 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused) {
     }
     // GEMMs with at most 16, or 33..48, rows (first-layer backward-data after phase folding): tiles of
     // 16x16x4 MFMAs waste no half tile of rows
-    const bool rows16 = dtype == PURINE_F32 && !pl.flat && (Co <= 16 || (Co > 32 && Co <= 48));
+    const bool rows16 = dtype == PURINE_F32 && !pl.flat && (Co <= 16 || (Co > 32 && Co <= 48) || (Co > 80 && Co <= 96));
     if (rows16) {
         const int bm16 = Co <= 16 ? 16 : 48;
         for (int bn16 = 256; bn16 >= 128; bn16 /= 2) {
-            const long long per_cu = ((M + bn16 - 1) / bn16 + 255) / 256;
+            const long long per_cu = ((Co + bm16 - 1) / bm16 * ((M + bn16 - 1) / bn16) + 255) / 256;
             const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.95 : 0.6);
             const double eff = bn16 == 256 ? kEff16 : kEff16 * 0.96;
             const double load = (double)per_cu * bm16 * bn16 * (1.0 + gather / bm16) / (eff * hide);

@@ -322,13 +322,14 @@ __global__ __launch_bounds__(TPB) void maxpool_fwd_kernel(const T* __restrict__ 
 }
 
 // Gather form of the pooling gradient: each input position visits the windows that cover it in
-// row-major (p,q) order and adds dy where that window's winner is this position. `act` (may be
-// null): the pooled tensor, output of a ReLU; positions where it is not positive get no gradient
-// (the ReLU gradient that would otherwise be a pass of its own over dx).
+// row-major (p,q) order and adds dy where that window's winner is this position. `y` (may be
+// null): the pooling output of the forward pass; windows whose winner was not positive pass no
+// gradient. When the pooled tensor is a ReLU output that is its ReLU gradient (a position that won
+// a window holds that window's y), which would otherwise be a pass of its own over dx.
 template <typename T, int K, int S>
 __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ dy,
                                                           const int32_t* __restrict__ arg,
-                                                          T* dx, const T* __restrict__ act, const PoolParams pp) {
+                                                          T* dx, const T* __restrict__ y, const PoolParams pp) {
     const int k = K ? K : pp.k, st = K ? S : pp.stride;
     constexpr int NW = K ? (K + S - 1) / (S ? S : 1) : 1;   // windows per axis that can cover a position
     const int lim = min(pp.ppw * pp.HW, ((int)blockIdx.y + 1) * POOL_CHUNK);
@@ -357,16 +358,17 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
                     const int p = p_lo + a, q = q_lo + b;
                     const bool in = (p <= p_hi) & (q <= q_hi);
                     const int o = in ? p * pp.Q + q : 0;           // clamped, branch-free
-                    const bool hit = in & (arg[obase + o] == e);
+                    const bool hit = in & (arg[obase + o] == e) & (!y || ldf<T>(y, obase + o) > 0.0f);
                     const float g = ldf<T>(dy, obase + o);
                     acc += hit ? g : 0.0f;
                 }
         } else {
             for (int p = p_lo; p <= p_hi; ++p)
-                for (int q = q_lo; q <= q_hi; ++q)
-                    if (arg[obase + p * pp.Q + q] == e) acc += ldf<T>(dy, obase + p * pp.Q + q);
+                for (int q = q_lo; q <= q_hi; ++q) {
+                    const size_t o = obase + p * pp.Q + q;
+                    if (arg[o] == e && (!y || ldf<T>(y, o) > 0.0f)) acc += ldf<T>(dy, o);
+                }
         }
-        if (act && !(ldf<T>(act, at) > 0.0f)) acc = old;
         stf<T>(dx, at, acc);
     }
 }
@@ -380,7 +382,7 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
 template <typename T, int K, int S>
 __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __restrict__ dy,
                                                                  const int32_t* __restrict__ arg,
-                                                                 T* dx, const T* __restrict__ act, const PoolParams pp) {
+                                                                 T* dx, const T* __restrict__ y, const PoolParams pp) {
     extern __shared__ __attribute__((aligned(16))) unsigned char pool_smem[];
     int32_t* arg_s = reinterpret_cast<int32_t*>(pool_smem);           // [ppw][PQ]
     float* dy_s = reinterpret_cast<float*>(pool_smem) + pp.ppw * pp.PQ;
@@ -393,7 +395,8 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __rest
         const int n = planes * pp.PQ;
         for (int i = threadIdx.x; i < n; i += TPB) {
             arg_s[i] = arg[base + i];
-            dy_s[i] = ldf<T>(dy, base + i);
+            // the gradient of a window whose winner was not positive is dropped here, once per window
+            dy_s[i] = (!y || ldf<T>(y, base + i) > 0.0f) ? ldf<T>(dy, base + i) : 0.0f;
         }
     }
     __syncthreads();
@@ -428,7 +431,6 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __rest
                 for (int q = q_lo; q <= q_hi; ++q)
                     if (arg_s[obase + p * pp.Q + q] == e) acc += dy_s[obase + p * pp.Q + q];
         }
-        if (act && !(ldf<T>(act, at) > 0.0f)) acc = old;
         stf<T>(dx, at, acc);
     }
 }
@@ -775,11 +777,11 @@ hipError_t launch_maxpool_fwd(int dtype, const void* x, void* y, int32_t* arg, i
     return hipGetLastError();
 }
 
-hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, const void* act, float beta,
+hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, void* dx, const void* y, float beta,
                               int NC, int H, int W, int P, int Q, int k, int stride, int pad,
                               hipStream_t st) {
     if ((long long)H * W > 0x3fffffffLL || (long long)P * Q > 0x3fffffffLL) return hipErrorInvalidValue;
-    if (!act && pool3_vec_applies(dtype, NC, H, W, P, Q, k, stride, pad, dy, dx, arg)) {
+    if (!y && pool3_vec_applies(dtype, NC, H, W, P, Q, k, stride, pad, dy, dx, arg)) {
         const Pool3Params p3 = pool3_params(NC, H, W, beta);
         ProbeScope probe(st);
         (void)hipGetLastError();
@@ -797,8 +799,8 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
         (void)hipGetLastError();
 #define CALL(K, S)                                                                                              \
     BY_DTYPE(dtype,                                                                                             \
-             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<float, K, S>), dim3(groups), dim3(TPB), lds, st, (const float*)dy, arg, (float*)dx, (const float*)act, pp),     \
-             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<uint16_t, K, S>), dim3(groups), dim3(TPB), lds, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)act, pp))
+             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<float, K, S>), dim3(groups), dim3(TPB), lds, st, (const float*)dy, arg, (float*)dx, (const float*)y, pp),     \
+             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<uint16_t, K, S>), dim3(groups), dim3(TPB), lds, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)y, pp))
         POOL_SHAPES(CALL)
 #undef CALL
         return hipGetLastError();
@@ -809,8 +811,8 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
     (void)hipGetLastError();   // drop stale status left by earlier, unrelated runtime calls
 #define CALL(K, S)                                                                                              \
     BY_DTYPE(dtype,                                                                                             \
-             hipLaunchKernelGGL((maxpool_bwd_kernel<float, K, S>), grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, (const float*)act, pp),     \
-             hipLaunchKernelGGL((maxpool_bwd_kernel<uint16_t, K, S>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)act, pp))
+             hipLaunchKernelGGL((maxpool_bwd_kernel<float, K, S>), grid, dim3(TPB), 0, st, (const float*)dy, arg, (float*)dx, (const float*)y, pp),     \
+             hipLaunchKernelGGL((maxpool_bwd_kernel<uint16_t, K, S>), grid, dim3(TPB), 0, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)y, pp))
     POOL_SHAPES(CALL)
 #undef CALL
     return hipGetLastError();

@@ -205,8 +205,9 @@ class GraphBuilder:
     def maxpool_backward(self, rec, dy, thread=T_MAIN):
         dx = self.new(rec["prefix"] + ".dx", rec["x_shape"], rec["dtype"])
         if self.fuse and rec["x"] in self.relu_outputs:
-            # the pooled tensor is a ReLU output: its gradient mask rides along (no ReLUBwd pass over dx)
-            self.op(B.OP_MAXPOOL_BWD_RELU, [dy, rec["arg"], rec["x"]], [dx], thread, B.op_attrs(pool=rec["desc"]))
+            # the pooled tensor is a ReLU output: its gradient mask rides along, read off the pooling
+            # output (no ReLUBwd pass over dx, and the pooled tensor is not read again)
+            self.op(B.OP_MAXPOOL_BWD_RELU, [dy, rec["arg"], rec["y"]], [dx], thread, B.op_attrs(pool=rec["desc"]))
             self.masked_grads.add(dx)
             rec["fused_relu"] = True
         else:

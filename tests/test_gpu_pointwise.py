@@ -111,10 +111,12 @@ def test_maxpool_forward_and_backward(case, dtype, ties):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("case", POOLS, ids=[c[0] for c in POOLS])
 def test_maxpool_backward_with_relu_mask(case, dtype):
-    """MaxPoolBwd and the ReLU gradient of the pooled tensor as one operator: where act > 0 the bits
-    of purine_maxpool_bwd, elsewhere no pooling gradient; also accumulating, against the oracle's
-    two functions composed. act is drawn independently of the pooling winners (about half of the
-    positions are masked), which a real ReLU output would not give but the operator must honour."""
+    """MaxPoolBwd and the ReLU gradient of the pooled tensor as one operator, the mask read off the
+    pooling output y (a position that won a window holds that window's y). With the forward pass's
+    own y of a ReLU output: the oracle's two functions composed, and where the pooled tensor is
+    positive the bits of purine_maxpool_bwd, elsewhere no pooling gradient; also accumulating.
+    With a y unrelated to the winners (about half of the windows masked): the pooling gradient of
+    dy with those windows' entries dropped, which is what the operator is defined to compute."""
     import paper_1412_6249_amd as pa
     from gpu_util import to_dev, to_host, tdtype, rel_l2, pool_bwd_in_order, DEV
     name, N, C, H, W, k, s, p = case
@@ -122,27 +124,32 @@ def test_maxpool_backward_with_relu_mask(case, dtype):
     act = np.maximum(x, 0.0)                                   # a ReLU output: zeros and positives
     ey, earg = oracle.maxpool_fwd(act, k, s, p)
     desc = pa.pool_desc(k, s, p)
-    tact, tdy = to_dev(act, dtype), to_dev(dy, dtype)
+    tdy = to_dev(dy, dtype)
     targ = torch.from_numpy(earg.astype(np.int32)).to(DEV)
     rs = np.random.default_rng(11)
-    other = rs.uniform(-1, 1, size=x.shape).astype(np.float32)  # a mask unrelated to the winners
-    if dtype == "bf16":
-        other = gen.quantize_bf16(other)
+    other = rs.uniform(-1, 1, size=dy.shape).astype(np.float32)  # a "y" unrelated to the winners
     prev = rs.uniform(-1, 1, size=x.shape).astype(np.float32)
     if dtype == "bf16":
-        prev = gen.quantize_bf16(prev)
-    for mask, tmask in ((act, tact), (other, to_dev(other, dtype))):
+        other, prev = gen.quantize_bf16(other), gen.quantize_bf16(prev)
+    for y in (np.asarray(ey, dtype=np.float32), other):
         tdx = torch.full(x.shape, float("nan"), dtype=tdtype(dtype), device=DEV)
-        pa.purine_maxpool_bwd_relu(desc, tdy, targ, tmask, tdx)
+        pa.purine_maxpool_bwd_relu(desc, tdy, targ, to_dev(y, dtype), tdx)
         tdx2 = to_dev(prev, dtype)
-        pa.purine_maxpool_bwd_relu(desc, tdy, targ, tmask, tdx2, beta=1.0)
+        pa.purine_maxpool_bwd_relu(desc, tdy, targ, to_dev(y, dtype), tdx2, beta=1.0)
         torch.cuda.synchronize()
-        ref = oracle.relu_bwd(mask, oracle.maxpool_bwd(dy, earg, x.shape))
+        kept = np.where(y > 0, dy, np.float32(0))               # windows whose winner was positive
+        ref = oracle.maxpool_bwd(kept, earg, x.shape)
         assert rel_l2(to_host(tdx), ref) <= (1e-2 if dtype == "bf16" else 1e-6)
-        exact = pool_bwd_in_order(dy, earg, x.shape, dtype)
-        assert np.array_equal(to_host(tdx), np.where(mask > 0, exact, np.float32(0)))
-        exact2 = pool_bwd_in_order(dy, earg, x.shape, dtype, prev=prev)
-        assert np.array_equal(to_host(tdx2), np.where(mask > 0, exact2, prev))
+        assert np.array_equal(to_host(tdx), pool_bwd_in_order(kept, earg, x.shape, dtype))
+        assert np.array_equal(to_host(tdx2), pool_bwd_in_order(kept, earg, x.shape, dtype, prev=prev))
+        if y is not other:
+            # the forward pass's own y: MaxPoolBwd followed by ReLUBwd on the pooled tensor
+            composed = oracle.relu_bwd(act, oracle.maxpool_bwd(dy, earg, x.shape))
+            assert rel_l2(to_host(tdx), composed) <= (1e-2 if dtype == "bf16" else 1e-6)
+            exact = pool_bwd_in_order(dy, earg, x.shape, dtype)
+            assert np.array_equal(to_host(tdx), np.where(act > 0, exact, np.float32(0)))
+            exact2 = pool_bwd_in_order(dy, earg, x.shape, dtype, prev=prev)
+            assert np.array_equal(to_host(tdx2), np.where(act > 0, exact2, prev))
 
 
 def test_maxpool_backward_is_deterministic():
