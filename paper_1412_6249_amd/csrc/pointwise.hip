@@ -2,6 +2,7 @@
 // support operators (ReLU, max-pool, channel copy, fan-in sum) that chain layers together.
 // All of them stream each tensor once with coalesced accesses; none uses atomics.
 #include "common.h"
+#include <type_traits>
 
 namespace purine {
 namespace {
@@ -374,18 +375,21 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_kernel(const T* __restrict__ 
 }
 
 // The same with the windows' winners and gradients staged in LDS: a workgroup owns whole planes (a few
-// thousand input positions in all), copies their arg and dy planes into LDS with coalesced loads,
-// and every position then looks its up-to-NW x NW windows up there. What goes to and comes from
-// global memory is one coalesced pass per tensor (in the kernel above every position's gathers of
-// arg and dy go through the caches, and the kernel runs at half the rate of a copy). Same windows
-// in the same order: bit-identical results.
+// thousand input positions in all), copies their arg and dy planes into LDS with coalesced loads
+// (one {winner, gradient} pair per window, so a look-up is one 8-byte read), and every position
+// then looks its up-to-NW x NW windows up there. What goes to and comes from global memory is one
+// coalesced pass per tensor (in the kernel above every position's gathers of arg and dy go through
+// the caches, and the kernel runs at half the rate of a copy). Same windows in the same order:
+// bit-identical results. quads != 0 (a workgroup's first position is a multiple of four positions
+// from an aligned dx): a thread takes four consecutive positions, decodes the first and steps to
+// the others, and dx moves as packets of four.
 template <typename T, int K, int S>
 __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __restrict__ dy,
                                                                  const int32_t* __restrict__ arg,
-                                                                 T* dx, const T* __restrict__ y, const PoolParams pp) {
+                                                                 T* dx, const T* __restrict__ y, const PoolParams pp,
+                                                                 const int quads) {
     extern __shared__ __attribute__((aligned(16))) unsigned char pool_smem[];
-    int32_t* arg_s = reinterpret_cast<int32_t*>(pool_smem);           // [ppw][PQ]
-    float* dy_s = reinterpret_cast<float*>(pool_smem) + pp.ppw * pp.PQ;
+    int2* win_s = reinterpret_cast<int2*>(pool_smem);                 // [ppw][PQ] {winner, gradient bits}
     const int k = K ? K : pp.k, st = K ? S : pp.stride;
     constexpr int NW = K ? (K + S - 1) / (S ? S : 1) : 1;
     const int nc0 = blockIdx.x * pp.ppw;
@@ -394,17 +398,14 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __rest
         const size_t base = (size_t)nc0 * pp.PQ;
         const int n = planes * pp.PQ;
         for (int i = threadIdx.x; i < n; i += TPB) {
-            arg_s[i] = arg[base + i];
             // the gradient of a window whose winner was not positive is dropped here, once per window
-            dy_s[i] = (!y || ldf<T>(y, base + i) > 0.0f) ? ldf<T>(dy, base + i) : 0.0f;
+            const float g = (!y || ldf<T>(y, base + i) > 0.0f) ? ldf<T>(dy, base + i) : 0.0f;
+            win_s[i] = make_int2(arg[base + i], __float_as_int(g));
         }
     }
     __syncthreads();
-    const int lim = planes * pp.HW;
-    for (int l = threadIdx.x; l < lim; l += TPB) {
-        const int pl = fastdiv(l, pp.div_hw);
-        const int e = l - pl * pp.HW;
-        const int h = fastdiv(e, pp.div_w), w = e - h * pp.W;
+    // beta*dx + the gradients of the windows that chose position e = (h, w) of the workgroup's plane pl
+    auto gather = [&](int pl, int e, int h, int w, float old) -> float {
         const int p_hi = min(pp.P - 1, (h + pp.pad) / st);
         const int q_hi = min(pp.Q - 1, (w + pp.pad) / st);
         int p_lo = h + pp.pad - k + 1;
@@ -412,8 +413,6 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __rest
         int q_lo = w + pp.pad - k + 1;
         q_lo = q_lo <= 0 ? 0 : (q_lo + st - 1) / st;
         const int obase = pl * pp.PQ;
-        const size_t at = (size_t)nc0 * pp.HW + l;
-        const float old = pp.beta != 0.0f ? ldf<T>(dx, at) : 0.0f;
         float acc = old;
         if (K) {
 #pragma unroll
@@ -422,16 +421,56 @@ __global__ __launch_bounds__(TPB) void maxpool_bwd_staged_kernel(const T* __rest
                 for (int b = 0; b < NW; ++b) {
                     const int p = p_lo + a, q = q_lo + b;
                     const bool in = (p <= p_hi) & (q <= q_hi);
-                    const int o = obase + (in ? p * pp.Q + q : 0);   // clamped, branch-free
-                    const bool hit = in & (arg_s[o] == e);
-                    acc += hit ? dy_s[o] : 0.0f;
+                    const int2 win = win_s[obase + (in ? p * pp.Q + q : 0)];   // clamped, branch-free
+                    acc += (in & (win.x == e)) ? __int_as_float(win.y) : 0.0f;
                 }
         } else {
             for (int p = p_lo; p <= p_hi; ++p)
-                for (int q = q_lo; q <= q_hi; ++q)
-                    if (arg_s[obase + p * pp.Q + q] == e) acc += dy_s[obase + p * pp.Q + q];
+                for (int q = q_lo; q <= q_hi; ++q) {
+                    const int2 win = win_s[obase + p * pp.Q + q];
+                    if (win.x == e) acc += __int_as_float(win.y);
+                }
         }
-        stf<T>(dx, at, acc);
+        return acc;
+    };
+    const int lim = planes * pp.HW;
+    const size_t first = (size_t)nc0 * pp.HW;
+    int done = 0;
+    if (quads) {
+        typedef typename std::conditional<sizeof(T) == 4, float4, ushort4>::type Quad;
+        const int nq = lim >> 2;
+        for (int j = threadIdx.x; j < nq; j += TPB) {
+            const int l = j * 4;
+            int pl = fastdiv(l, pp.div_hw);
+            int e = l - pl * pp.HW;
+            int h = fastdiv(e, pp.div_w), w = e - h * pp.W;
+            Quad* at = reinterpret_cast<Quad*>(dx + first + l);
+            float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (pp.beta != 0.0f) {
+                const Quad o = *at;
+                if constexpr (sizeof(T) == 4) { v[0] = o.x; v[1] = o.y; v[2] = o.z; v[3] = o.w; }
+                else { v[0] = bf2f(o.x); v[1] = bf2f(o.y); v[2] = bf2f(o.z); v[3] = bf2f(o.w); }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                v[i] = gather(pl, e, h, w, v[i]);
+                ++e; ++w;
+                if (w == pp.W) { w = 0; ++h; }
+                if (e == pp.HW) { e = 0; h = 0; ++pl; }
+            }
+            Quad o;
+            if constexpr (sizeof(T) == 4) { o.x = v[0]; o.y = v[1]; o.z = v[2]; o.w = v[3]; }
+            else { o.x = f2bf(v[0]); o.y = f2bf(v[1]); o.z = f2bf(v[2]); o.w = f2bf(v[3]); }
+            *at = o;
+        }
+        done = nq * 4;
+    }
+    for (int l = done + threadIdx.x; l < lim; l += TPB) {
+        const int pl = fastdiv(l, pp.div_hw);
+        const int e = l - pl * pp.HW;
+        const int h = fastdiv(e, pp.div_w), w = e - h * pp.W;
+        const float old = pp.beta != 0.0f ? ldf<T>(dx, first + l) : 0.0f;
+        stf<T>(dx, first + l, gather(pl, e, h, w, old));
     }
 }
 
@@ -790,20 +829,33 @@ hipError_t launch_maxpool_bwd(int dtype, const void* dy, const int32_t* arg, voi
         return hipGetLastError();
     }
     PoolParams pp = pool_params(NC, H, W, P, Q, k, stride, pad, H * W, beta);
-    // whole planes per workgroup with their arg and dy planes in LDS, when 8 bytes per window of a
-    // workgroup's planes fit 48 KB and a workgroup still has at most 16K positions to walk
-    if ((long long)pp.ppw * P * Q * 8 <= 48 * 1024 && (long long)pp.ppw * H * W <= 16384) {
-        const unsigned groups = (unsigned)((NC + pp.ppw - 1) / pp.ppw);
-        const size_t lds = (size_t)pp.ppw * P * Q * 8;
-        ProbeScope probe(st);
-        (void)hipGetLastError();
+    // Whole planes per workgroup with their arg and dy planes in LDS: up to about 8K positions per
+    // workgroup, a multiple of four planes (then every workgroup starts a multiple of four positions
+    // into dx and dx moves as packets), when 8 bytes per window of those planes fit 48 KB and the
+    // workgroup has at most 16K positions to walk.
+    {
+        long long ppw = 8192 / ((long long)H * W);
+        if (ppw > NC / 2048) ppw = NC / 2048;         // at least 2048 workgroups, eight per CU
+        if (ppw >= 4) ppw = ppw / 4 * 4;
+        else if (4LL * H * W <= 16384) ppw = 4;
+        else if (ppw < 1) ppw = 1;
+        if (ppw > NC) ppw = NC;
+        if (ppw * P * Q * 8 <= 48 * 1024 && ppw * H * W <= 16384) {
+            pp.ppw = (int)ppw;
+            const unsigned groups = (unsigned)((NC + pp.ppw - 1) / pp.ppw);
+            const size_t lds = (size_t)pp.ppw * P * Q * 8;
+            const int elem = dtype == PURINE_BF16 ? 2 : 4;
+            const int quads = ((ppw * H * W) % 4 == 0 || groups == 1) && ((uintptr_t)dx % (4 * elem)) == 0;
+            ProbeScope probe(st);
+            (void)hipGetLastError();
 #define CALL(K, S)                                                                                              \
     BY_DTYPE(dtype,                                                                                             \
-             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<float, K, S>), dim3(groups), dim3(TPB), lds, st, (const float*)dy, arg, (float*)dx, (const float*)y, pp),     \
-             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<uint16_t, K, S>), dim3(groups), dim3(TPB), lds, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)y, pp))
-        POOL_SHAPES(CALL)
+             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<float, K, S>), dim3(groups), dim3(TPB), lds, st, (const float*)dy, arg, (float*)dx, (const float*)y, pp, quads),     \
+             hipLaunchKernelGGL((maxpool_bwd_staged_kernel<uint16_t, K, S>), dim3(groups), dim3(TPB), lds, st, (const uint16_t*)dy, arg, (uint16_t*)dx, (const uint16_t*)y, pp, quads))
+            POOL_SHAPES(CALL)
 #undef CALL
-        return hipGetLastError();
+            return hipGetLastError();
+        }
     }
     const dim3 grid = pool_grid(pp, H * W);
     if (grid.y > 65535u) return hipErrorInvalidValue;
