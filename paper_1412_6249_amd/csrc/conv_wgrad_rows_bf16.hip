@@ -10,8 +10,8 @@
 // of the input rows of its 64 input channels (consecutive output rows share two of their three
 // input rows, so each step brings in ONE new input row and one dy row, 16-byte packets straight
 // from global memory). The three column taps of a filter row read the same aligned packet plus the
-// dword on either side and are shifted into place in registers (funnel shifts), so a step of 16
-// pixels costs a wavefront 10 LDS reads (issued one step ahead) for 9 MFMAs. Each wavefront owns 32 output channels x 32
+// dword on either side, taken from the partner lane's registers, and are shifted into place in
+// registers (funnel shifts), so a step of 16 pixels costs a wavefront 4 LDS reads for 9 MFMAs. Each wavefront owns 32 output channels x 32
 // input channels x all nine taps (144 accumulators). Workgroups are persistent over a contiguous
 // range of (image, row) pairs; their fp32 partial tiles go to scratch as [split][tap][k][c] and the
 // fixed-order second pass of the general kernel adds them.
@@ -26,7 +26,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 64, CT = 64;     // output / input channels per workgroup
 constexpr int ORG = 8;              // element of an x row in LDS that holds image column 0
-constexpr int LOADS = 4;            // 16-byte packets per thread and step, at most, per operand
+constexpr int LOADS = 2;            // 16-byte packets per thread and step, at most, per operand (rows of up to 64 pixels)
 
 // LDS row pitch: at least `bytes`, and 16 bytes past a multiple of 128, so that the 16-byte reads of 8
 // consecutive rows (lanes run along channels) fall into distinct bank groups
@@ -161,33 +161,67 @@ __global__ __launch_bounds__(256, 2) void wgrad_rows3x3_bf16_kernel(const RowsWg
             const bool real = pe - 2 >= 0 && pe - 2 < p.P && g >= g0;
             if (real) {
                 const unsigned char* a_base = dys + dbuf * KT * p.dypitch + (wk * 32 + (lane & 31)) * p.dypitch + khalf * 16;
-                const int xrow = (wc * 32 + (lane & 31)) * p.xpitch + (ORG + khalf * 8) * 2;
+                const int xrow = (wc * 32 + (lane & 31)) * p.xpitch + (ORG + khalf * 8) * 2;   // column 8h of the lane's channel
                 const unsigned char* rowp[3];
 #pragma unroll
                 for (int r = 0; r < 3; ++r) rowp[r] = xs + ((pe - 3 + r) & 3) * CT * p.xpitch + xrow;
+                // Column taps by shifting dy, not x: with q' = q - 1 + s the sum over q of
+                // dy[q] * x[q - 1 + s] is the sum over the real columns q' of dy[q' + 1 - s] * x[q'] (the
+                // padding columns of x contribute nothing). The three input rows' packets then serve all
+                // three column taps as they are, and only the one dy fragment is shifted, by one pixel
+                // either way (funnel shifts). The dword next to a lane's dy packet is the last / first
+                // dword of its partner lane's packet (the other 8-pixel half of the same channel): the
+                // same step's for the inner side of the pair, the previous / next step's for the outer
+                // side. So the MFMAs of tap s = 0 (dy one pixel to the right) are issued one step late,
+                // when the next step's packet is in registers, and no dword is fetched from LDS on its
+                // own (4-byte reads at this row pitch fall on 8 banks: each cost as much as a 16-byte
+                // one). Every accumulator still takes its steps in ascending order.
+                u32x4 pav = {0u, 0u, 0u, 0u}, pd[3];       // previous step: dy fragment, x packets
+#pragma unroll
+                for (int r = 0; r < 3; ++r) pd[r] = u32x4{0u, 0u, 0u, 0u};
+                // tap s = 0 of the previous step: its dy fragment moved one pixel up; `first` = first dword
+                // of this lane's packet of the step after it
+                auto left_tap = [&](uint32_t first) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(pav[0], first, false, false);
+                    const uint32_t after = khalf ? sw[0] : sw[1];
+                    const u32x4 a0 = {__builtin_amdgcn_alignbit(pav[1], pav[0], 16),
+                                      __builtin_amdgcn_alignbit(pav[2], pav[1], 16),
+                                      __builtin_amdgcn_alignbit(pav[3], pav[2], 16),
+                                      __builtin_amdgcn_alignbit(after, pav[3], 16)};
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)
+                        acc[r * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, a0), __builtin_bit_cast(bf16x8, pd[r]), acc[r * 3 + 0], 0, 0, 0);
+                };
                 for (int st = 0; st < p.steps; ++st) {
                     const u32x4 av = *reinterpret_cast<const u32x4*>(a_base + st * 32);
+                    u32x4 d[3];
+#pragma unroll
+                    for (int r = 0; r < 3; ++r)   // columns q0 + 8h .. + 7 of the lane's channel
+                        d[r] = *reinterpret_cast<const u32x4*>(rowp[r] + st * 32);
+                    if (st > 0) left_tap(av[0]);
+                    // tap s = 2: dy one pixel down; the dword before the packet is the partner's last
+                    // dword, of the previous step for the lower half (zero before the first: dy[-1])
+                    const auto sm = __builtin_amdgcn_permlane32_swap(pav[3], av[3], false, false);
+                    const uint32_t before = khalf ? sm[0] : sm[1];
+                    const u32x4 a2 = {__builtin_amdgcn_alignbit(av[0], before, 16),
+                                      __builtin_amdgcn_alignbit(av[1], av[0], 16),
+                                      __builtin_amdgcn_alignbit(av[2], av[1], 16),
+                                      __builtin_amdgcn_alignbit(av[3], av[2], 16)};
 #pragma unroll
                     for (int r = 0; r < 3; ++r) {
-                        // pixels q0 + 8h .. + 7 of the lane's channel and the dword on either side of them
-                        // (the taps one column to the left / right)
-                        const u32x4 d = *reinterpret_cast<const u32x4*>(rowp[r] + st * 32);
-                        const uint32_t dm = *reinterpret_cast<const uint32_t*>(rowp[r] + st * 32 - 4);
-                        const uint32_t dp = *reinterpret_cast<const uint32_t*>(rowp[r] + st * 32 + 16);
-                        const uint32_t s01 = __builtin_amdgcn_alignbit(d[1], d[0], 16);
-                        const uint32_t s12 = __builtin_amdgcn_alignbit(d[2], d[1], 16);
-                        const uint32_t s23 = __builtin_amdgcn_alignbit(d[3], d[2], 16);
-                        const u32x4 b0 = {__builtin_amdgcn_alignbit(d[0], dm, 16), s01, s12, s23};   // columns q - 1
-                        const u32x4 b2 = {s01, s12, s23, __builtin_amdgcn_alignbit(dp, d[3], 16)};   // columns q + 1
-                        acc[r * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, b0), acc[r * 3 + 0], 0, 0, 0);
                         acc[r * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, d), acc[r * 3 + 1], 0, 0, 0);
+                            __builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, d[r]), acc[r * 3 + 1], 0, 0, 0);
                         acc[r * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, b2), acc[r * 3 + 2], 0, 0, 0);
+                            __builtin_bit_cast(bf16x8, a2), __builtin_bit_cast(bf16x8, d[r]), acc[r * 3 + 2], 0, 0, 0);
                     }
                     if (do_db) dbacc += sum8(av);
+                    pav = av;
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) pd[r] = d[r];
                 }
+                // tap s = 0 of the last step: past its upper half lies dy pixel 16 * steps, beyond the row
+                left_tap(0u);
             }
             // the next step's rows go to the ring slot nobody reads now and to the other dy buffer
             store_step(pe & 3, dbuf ^ 1);
