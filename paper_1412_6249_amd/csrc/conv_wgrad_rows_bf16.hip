@@ -5,17 +5,19 @@
 //
 // The reduction runs over pixels, and NCHW keeps the pixels of a row contiguous, so BOTH MFMA
 // operands (8 consecutive reduction elements per lane) are 16-byte windows of rows as they lie in
-// memory: dy[k][p][q0..q0+7] and x[c][p-1+r][q0-1+s .. q0+6+s]. A workgroup walks over output rows;
-// per row it holds in LDS, in their natural layout, the dy row of its 64 output channels and a ring
-// of the input rows of its 64 input channels (consecutive output rows share two of their three
-// input rows, so each step brings in ONE new input row and one dy row, 16-byte packets straight
-// from global memory). The three column taps of a filter row read the same aligned packet plus the
-// dword on either side, taken from the partner lane's registers, and are shifted into place in
-// registers (funnel shifts), so a step of 16 pixels costs a wavefront 4 LDS reads for 9 MFMAs. Each wavefront owns 32 output channels x 32
-// input channels x all nine taps (144 accumulators). Workgroups are persistent over a contiguous
-// range of (image, row) pairs; their fp32 partial tiles go to scratch as [split][tap][k][c] and the
-// fixed-order second pass of the general kernel adds them.
+// memory. A workgroup walks over output rows; per row it holds in LDS, in their natural layout, the
+// dy row of its 64 output channels and a ring of the input rows of its 64 input channels
+// (consecutive output rows share two of their three input rows, so each step brings in ONE new
+// input row and one dy row). The rows come in by loads that write LDS directly, requested two
+// steps ahead. The three column taps are had by shifting the dy fragment one pixel either way in
+// registers (funnel shifts; the neighbouring dword comes from the partner lane's registers), the
+// input rows' packets serve all taps as they are: a step of 16 pixels costs a wavefront 4 LDS reads
+// for 9 MFMAs. Each wavefront owns 32 output channels x 32 input channels x all nine taps (144
+// accumulators). Workgroups are persistent over a contiguous range of (image, row) pairs; their
+// fp32 partial tiles go to scratch as [split][tap][k][c] and the fixed-order second pass of the
+// general kernel adds them.
 #include "common.h"
+#include <type_traits>
 
 namespace purine {
 namespace {
@@ -26,7 +28,11 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 64, CT = 64;     // output / input channels per workgroup
 constexpr int ORG = 8;              // element of an x row in LDS that holds image column 0
-constexpr int LOADS = 2;            // 16-byte packets per thread and step, at most, per operand (rows of up to 64 pixels)
+constexpr int PITCH = 144;          // LDS bytes per staged row: 9 packets of 16 bytes (see row_pitch)
+constexpr int SLOT = 64 * PITCH;    // one staged row of each of 64 channels: 576 packets = 9 wavefront loads
+constexpr int XSLOTS = 5, DSLOTS = 3;   // rows being read (3 / 1) + rows in flight (2 / 2)
+constexpr int RQ = 5;               // loads per wavefront and step: two wavefronts share a slot's 9
+constexpr int LDS_BYTES = (XSLOTS + DSLOTS) * SLOT + 1024;   // + 1 KB that takes the loads nobody needs
 
 // LDS row pitch: at least `bytes`, and 16 bytes past a multiple of 128, so that the 16-byte reads of 8
 // consecutive rows (lanes run along channels) fall into distinct bank groups
@@ -39,11 +45,9 @@ struct RowsWgradParams {
     unsigned x_bytes, dy_bytes;
     int k_groups, c_groups, workers;   // grid = k_groups * c_groups * workers
     int rows_total, rows_per_worker;   // flattened (n, p) output rows
-    int xpitch, dypitch;               // LDS bytes per x row / dy row
     int xchunks, dychunks;             // 16-byte packets per x row (W / 8) and dy row (Q / 8)
     int steps;                         // 16-pixel MFMA steps per output row: ceil(Q / 16)
-    int x_rounds, d_rounds;            // 16-byte packets per thread and step for each operand
-    FastDiv div_p, div_xchunks, div_dychunks;
+    FastDiv div_p;
 };
 
 __device__ __forceinline__ float sum8(const u32x4 u) {
@@ -55,10 +59,12 @@ __device__ __forceinline__ float sum8(const u32x4 u) {
 
 __global__ __launch_bounds__(256, 2) void wgrad_rows3x3_bf16_kernel(const RowsWgradParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* xs = smem;                                   // [4 ring slots][CT] rows of xpitch bytes
-    unsigned char* dys = smem + 4 * CT * p.xpitch;              // [2][KT] rows of dypitch bytes
+    unsigned char* xs = smem;                                   // [XSLOTS][CT] rows of PITCH bytes
+    unsigned char* dys = smem + XSLOTS * SLOT;                  // [DSLOTS][KT] rows of PITCH bytes
+    unsigned char* spare = smem + (XSLOTS + DSLOTS) * SLOT;     // 1 KB
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int khalf = lane >> 5;
     const int wk = wave >> 1, wc = wave & 1;                    // this wavefront's 32-row k tile and 32-channel tile
 
@@ -73,62 +79,69 @@ __global__ __launch_bounds__(256, 2) void wgrad_rows3x3_bf16_kernel(const RowsWg
     const int g0 = worker * p.rows_per_worker;
     const int g1 = min(g0 + p.rows_per_worker, p.rows_total);
 
-    // ---- once: zero everything (halos of the x rows, the tail of the dy rows)
+    // ---- once: zero everything
     {
-        const int total = (4 * CT * p.xpitch + 2 * KT * p.dypitch) / 16;
         const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int i = tid; i < total; i += 256) *reinterpret_cast<u32x4*>(smem + i * 16) = z;
+        for (int i = tid; i < LDS_BYTES / 16; i += 256) *reinterpret_cast<u32x4*>(smem + i * 16) = z;
     }
 
-    // ---- load tasks of this thread (fixed): x packets (channel, packet) and dy packets (k, packet)
-    int x_goff[LOADS], x_lds[LOADS], d_goff[LOADS], d_lds[LOADS];
-    const int x_tasks = CT * p.xchunks, d_tasks = KT * p.dychunks;
+    // ---- Rows come in by loads that write LDS directly (no registers, so requests can run two steps
+    // ahead beside 144 accumulators). One such load of a wavefront fills 64 consecutive 16-byte
+    // packets of LDS, lane l the l-th, with the 16 bytes at the lane's own buffer offset, or with
+    // zeros when that offset lies outside the buffer. A staged row is 9 packets (x: a halo packet,
+    // up to 7 of data, zeros; dy: up to 7 of data, zeros), a slot 576 packets = 9 loads: wavefronts 0
+    // and 1 share the x slot's loads (t = parity, parity + 2, ...), wavefronts 2 and 3 the dy slot's.
+    // The lanes of halo / tail packets and of channels that do not exist keep an offset outside the
+    // buffer, which is also how rows above and below the image become zeros. A wavefront issues RQ
+    // loads per step whatever happens (those nobody needs go to the spare KB), so that a wait can
+    // count them.
+    const bool loads_x = wave < 2;
+    const int parity = wave & 1;
+    int goff[RQ];
 #pragma unroll
-    for (int r = 0; r < LOADS; ++r) {
-        const int t = tid + r * 256;
-        const int c = fastdiv(t, p.div_xchunks), ch = t - c * p.xchunks;
-        const bool xl = t < x_tasks && c0 + c < p.C;
-        x_goff[r] = xl ? ((c0 + c) * p.H * p.W + ch * 8) * 2 : -1;
-        x_lds[r] = t < x_tasks ? c * p.xpitch + (ORG + ch * 8) * 2 : -1;
-        const int k = fastdiv(t, p.div_dychunks), dch = t - k * p.dychunks;
-        const bool dl = t < d_tasks && k0 + k < p.K;
-        d_goff[r] = dl ? ((k0 + k) * p.P * p.Q + dch * 8) * 2 : -1;
-        d_lds[r] = t < d_tasks ? k * p.dypitch + dch * 16 : -1;
-    }
-    const __amdgpu_buffer_rsrc_t rs_x =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.x), (short)0, (int)p.x_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_dy =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.dy), (short)0, (int)p.dy_bytes, 0x00020000);
-    u32x4 xr[LOADS], dr[LOADS];
-    // input row h of image n (zeros when outside the image) and dy row (n, pp) (zeros unless `real`)
-    auto load_step = [&](int n, int h, bool real_dy, int pp) {
-        const bool x_ok = (unsigned)h < (unsigned)p.H;
-        const int xb = n * p.x_ns * 2 + h * p.W * 2;
-        const int db = n * p.dy_ns * 2 + pp * p.Q * 2;
-#pragma unroll
-        for (int r = 0; r < LOADS; ++r) {
-            if (r >= p.x_rounds) break;          // uniform
-            const unsigned vx = (x_ok && x_goff[r] >= 0) ? (unsigned)(xb + x_goff[r]) : 0x80000000u;
-            xr[r] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, vx, 0, 0);
+    for (int i = 0; i < RQ; ++i) {
+        const int t = parity + 2 * i;
+        const int pk = t * 64 + lane;
+        const int row = pk / 9, jp = pk - row * 9;
+        if (loads_x) {
+            const bool ok = t < 9 && c0 + row < p.C && jp >= 1 && jp <= p.xchunks;     // packet 0: the ORG elements
+            goff[i] = ok ? ((c0 + row) * p.H * p.W + (jp - 1) * 8) * 2 : -1;
+        } else {
+            const bool ok = t < 9 && k0 + row < p.K && jp < p.dychunks;
+            goff[i] = ok ? ((k0 + row) * p.P * p.Q + jp * 8) * 2 : -1;
         }
+    }
+    // (the descriptor has to sit in scalar registers: say so, or every load becomes a loop over lanes)
+    const uint64_t src = reinterpret_cast<uint64_t>(loads_x ? p.x : p.dy);
+    // (readfirstlane returns a signed int: through uint32_t, or the low word's top bit smears over the high word)
+    const uint32_t src_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)src);
+    const uint32_t src_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(src >> 32));
+    const uint64_t src_u = ((uint64_t)src_hi << 32) | (uint64_t)src_lo;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        reinterpret_cast<uint16_t*>(src_u), (short)0,
+        __builtin_amdgcn_readfirstlane((int)(loads_x ? p.x_bytes : p.dy_bytes)), 0x00020000);
+    // this wavefront's share of: input row h of image n into x slot `xslot`, dy row pp into dy slot `dslot`
+    // (zeros when the row is outside the image / when !real_dy); !exists: nothing needed
+    auto request = [&](bool exists, int n, int h, bool real_dy, int pp, int xslot, int dslot) {
+        const bool row_ok = exists && (loads_x ? (unsigned)h < (unsigned)p.H : real_dy);
+        const int base = loads_x ? n * p.x_ns * 2 + h * p.W * 2 : n * p.dy_ns * 2 + pp * p.Q * 2;
+        unsigned char* slot = loads_x ? xs + xslot * SLOT : dys + dslot * SLOT;
 #pragma unroll
-        for (int r = 0; r < LOADS; ++r) {
-            if (r >= p.d_rounds) break;
-            const unsigned vd = (real_dy && d_goff[r] >= 0) ? (unsigned)(db + d_goff[r]) : 0x80000000u;
-            dr[r] = __builtin_amdgcn_raw_buffer_load_b128(rs_dy, vd, 0, 0);
+        for (int i = 0; i < RQ; ++i) {
+            const int t = parity + 2 * i;
+            const unsigned v = (row_ok && goff[i] >= 0) ? (unsigned)(base + goff[i]) : 0x80000000u;
+            unsigned char* dst = (exists && t < 9) ? slot + t * 1024 : spare;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void*)dst, 16, v, 0, 0, 0);
         }
     };
-    auto store_step = [&](int slot, int dbuf) {
-#pragma unroll
-        for (int r = 0; r < LOADS; ++r) {
-            if (r >= p.x_rounds) break;
-            if (x_lds[r] >= 0) *reinterpret_cast<u32x4*>(xs + slot * CT * p.xpitch + x_lds[r]) = xr[r];
-        }
-#pragma unroll
-        for (int r = 0; r < LOADS; ++r) {
-            if (r >= p.d_rounds) break;
-            if (d_lds[r] >= 0) *reinterpret_cast<u32x4*>(dys + dbuf * KT * p.dypitch + d_lds[r]) = dr[r];
-        }
+    // every load of this wavefront but the `newest` youngest has written its packets; then all
+    // wavefronts meet. No fence: one would wait for the loads in flight as well. The empty asm
+    // statements keep the compiler from moving LDS accesses across.
+    auto rows_landed = [&](auto newest) {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_waitcnt(0x0070 | decltype(newest)::value);      // vmcnt(newest), lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
     };
 
     floatx16 acc[9];
@@ -140,31 +153,50 @@ __global__ __launch_bounds__(256, 2) void wgrad_rows3x3_bf16_kernel(const RowsWg
     const bool do_db = p.db_out != nullptr && c0 == 0 && wc == 0;
 
     if (g0 < g1) {
-        // Extended row index pe of an image runs from -1 to P + 1: step pe loads input row pe into ring
-        // slot pe & 3 and the dy row of step pe + 1, and multiplies output row pe - 2 (when that row
-        // exists and belongs to this worker) with input rows pe - 3 .. pe - 1. The first three steps of
-        // a range only fill the ring.
-        int n = fastdiv(g0, p.div_p);
-        int pe = g0 - n * p.P - 1;          // first step: loads row p0 - 1
-        int g = g0 - 3;                      // flattened output row this step multiplies (pe - 2 of image n)
+        // Extended row index pe of an image runs from -1 to P + 1: step pe brings in input row pe and
+        // the dy row of step pe + 1, and multiplies output row pe - 2 (when that row exists and
+        // belongs to this worker) with input rows pe - 3 .. pe - 1. The first three steps of a range
+        // only fill the ring. Step k's rows are requested at the start of step k - 1 and must have
+        // landed at the end of step k: two steps' requests are in flight.
+        struct Pos { int n, pe, g; };        // image, extended row, flattened output row the step multiplies
+        auto advance = [&](Pos& s) -> bool {
+            s.pe += 1; s.g += 1;
+            if (s.g >= g1) return false;
+            if (s.pe > p.P + 1) {            // image done: the next output row is row 0 of image n + 1
+                s.n += 1; s.pe = -1; s.g -= 3;   // three steps fill the ring again before that row is multiplied
+            }
+            return true;
+        };
+        // the rows step s brings in: input row pe, dy row of output row (pe + 1) - 2 = pe - 1
+        auto request_for = [&](const Pos& s, bool exists, int xslot, int dslot) {
+            const bool dy_real = s.pe - 1 >= 0 && s.pe - 1 < p.P && s.g + 1 >= g0 && s.g + 1 < g1;
+            request(exists, s.n, s.pe, dy_real, s.pe - 1, xslot, dslot);
+        };
+        Pos cur;
+        cur.n = fastdiv(g0, p.div_p);
+        cur.pe = g0 - cur.n * p.P - 1;       // first step: brings in row p0 - 1, multiplies nothing
+        cur.g = g0 - 3;
+        Pos nxt = cur;
+        bool has_next = advance(nxt);
+        int kx = 0, kd = 0;                  // step number mod XSLOTS / mod DSLOTS: the slots of this step's rows
         __syncthreads();                     // zeros in place
-        // step "pe - 1" of the walk: nothing in flight yet, so load the first row here
-        load_step(n, pe, false, 0);
-        store_step(pe & 3, 0);
-        __syncthreads();
-        pe += 1; g += 1;
-        int dbuf = 0;                        // dy buffer the CURRENT step reads
+        request_for(cur, true, 0, 0);
         while (true) {
-            // next step's operands: input row pe, dy row of output row (pe + 1) - 2 = pe - 1
-            const bool next_real = pe - 1 >= 0 && pe - 1 < p.P && g + 1 >= g0 && g + 1 < g1;
-            load_step(n, pe, next_real, pe - 1);
-            const bool real = pe - 2 >= 0 && pe - 2 < p.P && g >= g0;
+            const int kx1 = kx + 1 == XSLOTS ? 0 : kx + 1, kd1 = kd + 1 == DSLOTS ? 0 : kd + 1;
+            request_for(nxt, has_next, kx1, kd1);
+            const int pe = cur.pe;
+            const bool real = pe - 2 >= 0 && pe - 2 < p.P && cur.g >= g0;
             if (real) {
-                const unsigned char* a_base = dys + dbuf * KT * p.dypitch + (wk * 32 + (lane & 31)) * p.dypitch + khalf * 16;
-                const int xrow = (wc * 32 + (lane & 31)) * p.xpitch + (ORG + khalf * 8) * 2;   // column 8h of the lane's channel
+                // dy row of the step before this one; input rows of the three steps before it
+                const int dprev = kd == 0 ? DSLOTS - 1 : kd - 1;
+                const unsigned char* a_base = dys + dprev * SLOT + (wk * 32 + (lane & 31)) * PITCH + khalf * 16;
+                const int xrow = (wc * 32 + (lane & 31)) * PITCH + (ORG + khalf * 8) * 2;   // column 8h of the lane's channel
                 const unsigned char* rowp[3];
 #pragma unroll
-                for (int r = 0; r < 3; ++r) rowp[r] = xs + ((pe - 3 + r) & 3) * CT * p.xpitch + xrow;
+                for (int r = 0; r < 3; ++r) {
+                    const int sl = kx + 2 + r;           // (k - 3 + r) mod XSLOTS
+                    rowp[r] = xs + (sl >= XSLOTS ? sl - XSLOTS : sl) * SLOT + xrow;
+                }
                 // Column taps by shifting dy, not x: with q' = q - 1 + s the sum over q of
                 // dy[q] * x[q - 1 + s] is the sum over the real columns q' of dy[q' + 1 - s] * x[q'] (the
                 // padding columns of x contribute nothing). The three input rows' packets then serve all
@@ -223,16 +255,15 @@ __global__ __launch_bounds__(256, 2) void wgrad_rows3x3_bf16_kernel(const RowsWg
                 // tap s = 0 of the last step: past its upper half lies dy pixel 16 * steps, beyond the row
                 left_tap(0u);
             }
-            // the next step's rows go to the ring slot nobody reads now and to the other dy buffer
-            store_step(pe & 3, dbuf ^ 1);
-            __syncthreads();
-            dbuf ^= 1;
-            pe += 1; g += 1;
-            if (g >= g1) break;
-            if (pe > p.P + 1) {              // image done: the next output row is row 0 of image n + 1
-                n += 1; pe = -1; g -= 3;     // three steps fill the ring again before that row is multiplied
-            }
+            // this step's rows are in LDS (the next step's, requested above, may still be in flight)
+            rows_landed(std::integral_constant<int, RQ>());
+            if (!has_next) break;
+            cur = nxt;
+            has_next = advance(nxt);
+            kx = kx1; kd = kd1;
         }
+        // the last step's requests (to the spare KB) must not outlive the workgroup's LDS
+        __builtin_amdgcn_s_waitcnt(0x0070);
     }
 
     // ---- partial tile [split][tap][k][c]; the wavefronts of k rows / channels that do not exist write nothing
@@ -265,9 +296,8 @@ bool wgrad_rows_bf16_applies(const ConvGeom& g, int* workers) {
     const long long xb = ((long long)(g.N - 1) * g.x_ns + (long long)g.C * g.H * g.W) * 2;
     const long long dyb = ((long long)(g.N - 1) * g.y_ns + (long long)g.K * g.P * g.Q) * 2;
     if (xb >= 0x7fffffffLL || dyb >= 0x7fffffffLL) return false;
-    if (CT * (g.W / 8) > LOADS * 256 || KT * (g.Q / 8) > LOADS * 256) return false;
-    const int xpitch = row_pitch((ORG + g.W + 8) * 2), dypitch = row_pitch(((g.Q + 15) / 16 * 16) * 2);
-    if (4 * CT * xpitch + 2 * KT * dypitch > 80 * 1024) return false;
+    // staged rows of exactly PITCH bytes: rows of at most 56 pixels
+    if (row_pitch((ORG + g.W + 8) * 2) != PITCH || row_pitch(((g.Q + 15) / 16 * 16) * 2) != PITCH) return false;
     const int groups = ((g.K + KT - 1) / KT) * ((g.C + CT - 1) / CT);
     int w = 512 / groups / 8 * 8;            // two workgroups per CU in all, whole XCD rounds
     if (w < 8) return false;
@@ -288,13 +318,10 @@ hipError_t launch_wgrad_rows_bf16(const ConvGeom& g, int workers, const void* x,
     p.k_groups = (g.K + KT - 1) / KT; p.c_groups = (g.C + CT - 1) / CT; p.workers = workers;
     p.rows_total = g.N * g.P;
     p.rows_per_worker = (p.rows_total + workers - 1) / workers;
-    p.xpitch = row_pitch((ORG + g.W + 8) * 2);
-    p.dypitch = row_pitch(((g.Q + 15) / 16 * 16) * 2);
     p.xchunks = g.W / 8; p.dychunks = g.Q / 8;
     p.steps = (g.Q + 15) / 16;
-    p.x_rounds = (CT * p.xchunks + 255) / 256; p.d_rounds = (KT * p.dychunks + 255) / 256;
-    p.div_p = make_fastdiv(g.P); p.div_xchunks = make_fastdiv(p.xchunks); p.div_dychunks = make_fastdiv(p.dychunks);
-    const size_t lds = (size_t)4 * CT * p.xpitch + (size_t)2 * KT * p.dypitch;
+    p.div_p = make_fastdiv(g.P);
+    const size_t lds = LDS_BYTES;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad_rows3x3_bf16_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
