@@ -463,6 +463,7 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
     const int hPB = (lane >> 5) * PB;
     floatx16 acc[TM][TN];
     int X0 = 0;                              // patch position of this lane's first pixel at tap (0, 0)
+    int woff[NWIN];                          // byte offsets of the window's elements in filter row 0 (plane, half, quad)
     int i0 = 0, n = 0, pix0 = 0, pix_end = 0;
     int group = 0, tl = 0;
     struct RowFrags { bf16x8 a[ST][TM]; bf16x8 w[NWIN]; };
@@ -481,6 +482,11 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
             const int wo = pix - ho * q.wv;
             X0 = (ho - ho_first) * q.pw + wo + q.pos_add;
 #pragma unroll
+            for (int j = 0; j < NWIN; ++j) {
+                const int X = X0 + j - (MINUS ? ST - 1 : 0);
+                woff[j] = hPB + (X & (TN - 1)) * 2 * PB + (X >> 2) * 16;
+            }
+#pragma unroll
             for (int a = 0; a < TM; ++a)
 #pragma unroll
                 for (int b = 0; b < TN; ++b)
@@ -489,7 +495,7 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
         }
         __syncthreads();                     // stage s is in place
         const unsigned char* As = buf0 + (s & 1) * buf_bytes;
-        const unsigned char* patch = As + q.a_bytes + hPB;
+        const unsigned char* patch = As + q.a_bytes;
         // `real` = false (uniform): past the last filter row; the reads are still issued, at row 0, so
         // that every trip of the loop has the same number of LDS reads in flight
         auto fetch_row = [&](RowFrags& f, int r, bool real) {
@@ -499,12 +505,11 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
             for (int t = 0; t < ST; ++t)
 #pragma unroll
                 for (int a = 0; a < TM; ++a) f.a[t][a] = *reinterpret_cast<const bf16x8*>(ap + t * 2 * APB + a * 32 * 16);
-            const int Xr = X0 + (MINUS ? -(rr * q.pw) - (ST - 1) : rr * q.pw);
+            // q.pw is a multiple of four positions: a filter row further is q.pw / 4 packets further in
+            // the same plane (uniform), whatever the element
+            const unsigned char* prow = patch + (MINUS ? -rr : rr) * (q.pw * 4);
 #pragma unroll
-            for (int j = 0; j < NWIN; ++j) {
-                const int X = Xr + j;
-                f.w[j] = *reinterpret_cast<const bf16x8*>(patch + (X & (TN - 1)) * 2 * PB + (X >> 2) * 16);
-            }
+            for (int j = 0; j < NWIN; ++j) f.w[j] = *reinterpret_cast<const bf16x8*>(prow + woff[j]);
         };
         auto multiply_row = [&](const RowFrags& f) {
 #pragma unroll
@@ -664,6 +669,10 @@ void plan_roles(PixParams& p, int mode, PatchGeom& q) {
     if (mode != 2 && (long long)p.Co * p.HoWo * 2 >= 0x7fffffffLL) return;   // its epilogue addresses one image as a raw buffer
     if (mode == 2 && !(p.sh == 2 && p.sw == 2 && q.d2s_buffers)) return;      // depth-to-space: the stride-2 raw-buffer epilogue only
     PatchGeom r = q;
+    // patch rows of a whole number of position quads: a window element then lies in the same plane
+    // (position mod 4) in every filter row, and its address moves by a constant from row to row
+    r.pw = (q.pw + 3) / 4 * 4;
+    r.pos_add = mode != 0 ? (p.Rt - 1) * r.pw + (p.St - 1) : 0;
     r.wv = (p.Wo + 3) / 4 * 4;
     r.div_wv = make_fastdiv(r.wv);
     r.bm = p.Co <= 32 ? 32 : 64;
