@@ -524,15 +524,25 @@ __global__ __launch_bounds__(512, 1) void igemm_patch_roles_bf16_kernel(const Pi
         RowFrags f0, f1;
         fetch_row(f0, 0, true);
         int r = 0;
+        // The next row's address arithmetic and LDS reads are spread between the current row's MFMAs (an
+        // MFMA occupies the pipe for eight issue slots; issued in one block ahead of them, the reads
+        // leave the pipe idle meanwhile, and this role has one wavefront per SIMD).
+        auto spread = [&]() {
+#pragma unroll
+            for (int i = 0; i < ST * TM + NWIN; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, (ST * TM * TN) / (ST * TM + NWIN), 0);   // MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);                                  // VALU
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                  // LDS read
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
         for (; r + 2 <= p.Rt; r += 2) {
             fetch_row(f1, r + 1, true);
-            __builtin_amdgcn_sched_barrier(0);
             multiply_row(f0);
-            __builtin_amdgcn_sched_barrier(0);
+            spread();
             fetch_row(f0, r + 2, r + 2 < p.Rt);
-            __builtin_amdgcn_sched_barrier(0);
             multiply_row(f1);
-            __builtin_amdgcn_sched_barrier(0);
+            spread();
         }
         if (r < p.Rt) multiply_row(f0);
 
