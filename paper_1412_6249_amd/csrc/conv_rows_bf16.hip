@@ -108,19 +108,25 @@ __global__ __launch_bounds__(256, 2) void conv_rows_bf16_kernel(const PixParams 
 
     const int a_row = (wm * TM * 32 + (lane & 31)) * q.a_pitch + khalf * 16;
 
-    int tile = worker;
-    if (tile < q.n_tiles) load_rows(tile);
+    // A worker takes a contiguous range of pixel tiles: consecutive tiles of an image share most of
+    // their input rows, and the rows a tile loads again were fetched a tile ago by the same workgroup
+    // (tiles dealt out round-robin put neighbours on different XCDs, each fetching the shared rows
+    // into its own L2: the counters showed the input read 2.9 times from memory).
+    const int per_worker = (q.n_tiles + n_workers - 1) / n_workers;
+    int tile = worker * per_worker;
+    const int tile_end = min(tile + per_worker, q.n_tiles);
+    if (tile < tile_end) load_rows(tile);
     store_rows(0);
     __syncthreads();
 
     int buf = 0;
-    for (; tile < q.n_tiles; tile += n_workers) {
+    for (; tile < tile_end; ++tile) {
         const int n = fastdiv(tile, q.div_tpi);
         const int pix0 = (tile - n * q.tiles_per_img) * BN;
         const int pix_end = min(pix0 + BN, p.HoWo);
         const int ho_first = fastdiv(pix0, p.div_wo);
-        const int next = tile + n_workers;
-        if (next < q.n_tiles) load_rows(next);                      // lands during this tile's MFMAs
+        const int next = tile + 1;
+        if (next < tile_end) load_rows(next);                       // lands during this tile's MFMAs
 
         // this lane's window origin (element index inside the buffer) for tap row 0, block 0 of channel 0
         int b_el[TN];
