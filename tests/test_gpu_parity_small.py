@@ -80,6 +80,9 @@ CASES = [
     ("wgrows_c40_k72_w16_h5", 5, 40, 5, 16, 72, 3, 3, (1, 1), (1, 1)),
     ("wgrows_c130_k33_w40", 2, 130, 7, 40, 33, 3, 3, (1, 1), (1, 1)),
     ("wgrows_c32_k32_w8_h3", 7, 32, 3, 8, 32, 3, 3, (1, 1), (1, 1)),
+    # ... many short images: every worker's range of rows crosses several image boundaries, the
+    # widest rows the kernel takes (7 packets), requests in flight across the boundaries
+    ("wgrows_c64_k96_w56_many_images", 37, 64, 4, 56, 96, 3, 3, (1, 1), (1, 1)),
     # bf16 layers with at most 160 filter elements per output channel and a column stride of 1 or 2:
     # the weight gradient whose wavefronts each hold the whole filter tile (input rows de-interleaved
     # by column parity in LDS; an odd number of output rows per image, so that a pair of rows
