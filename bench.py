@@ -302,7 +302,7 @@ def main():
     ap.add_argument("--replay", action="store_true",
                     help="executor replay mode: the unbracketed steps launch a recorded HIP graph of the pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sample-every", type=int, default=4,
+    ap.add_argument("--sample-every", type=int, default=8,
                     help="bracket the dominant kernel (which then runs alone) on every n-th timed step")
     ap.add_argument("--ops", action="store_true", help="print the per-operator tables to stderr")
     args = ap.parse_args()
