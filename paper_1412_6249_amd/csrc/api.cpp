@@ -271,7 +271,7 @@ static int conv_bwd_data_impl(const purine_conv_desc* desc, const purine_tensor*
         if (overlaps(act, dx)) return PURINE_E_LAYOUT;
         epi.mask = act->data;
     }
-    const PixPlan plan = plan_conv_pix(g, true, dy->dtype, epi.mask != nullptr);
+    const PixPlan plan = plan_conv_pix(g, true, dy->dtype, epi.mask != nullptr, beta != 0.0f);
     if (blocked_copy_too_large(plan)) return PURINE_E_SHAPE;
     if (plan.ws_bytes && (!ws || ws_bytes < plan.ws_bytes)) return PURINE_E_WORKSPACE;
     if (plan.ws_bytes && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;

@@ -82,7 +82,7 @@ struct PixPlan {
     int gemm_splits, gemm_split_ci;
     size_t gemm_part_offset;   // byte offset of the fp32 partial tiles inside the scratch
 };
-PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused);
+PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused, bool accumulate = false);
 void force_pix_tile(int bm, int bn);
 bool patch_split_roles_forced();     // test hook: (-5, anything) gives it layers of few tiles too
 bool patch_split_roles_disabled();   // tuning hook: (-4, anything) keeps the bf16 patch kernel on its one-role form
