@@ -257,8 +257,10 @@ int purine_grouped_conv_bwd_weight(const purine_conv_desc* desc, int groups, con
  * filter bank): forward runs the weight-gradient kernel (split reduction over C, fixed-order
  * second pass; BF16: its fp32 result gets the bias added and is rounded once), backward-data the
  * forward kernel (with a split reduction over K when its tiles alone would leave most of the chip
- * idle), backward-weight the backward-data kernel (F32) or the weight-gradient kernel over the
- * batch as the pixel axis, on transposed copies of x and dy kept in ws (BF16: the result is fp32).
+ * idle), backward-weight the backward-data kernel (F32) or, for BF16 (the result is fp32), a
+ * contraction over the batch on transposed copies of x and dy kept in ws: a kernel that owns whole
+ * tiles of dw when N is a multiple of 8, else the weight-gradient kernel with the batch as the
+ * pixel axis. db is a column-sum kernel of its own (fixed summation order).
  * pass for the workspace query: PURINE_CONV_FWD, _BWD_DATA, _BWD_WEIGHT. b and db may be NULL. */
 size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K, int32_t dtype);
 int purine_fc_fwd(const purine_tensor* x, const purine_tensor* w, const purine_tensor* b,

@@ -727,26 +727,25 @@ size_t purine_fc_workspace_bytes(int pass, int64_t N, int64_t C, int64_t K, int3
     if (N < 1 || C < 1 || K < 1 || !is_float_dtype(dtype)) return 0;
     // one convolution geometry serves the three fp32 passes: a 1x1 filter bank [N, K] over the plane [1, K, 1, C]
     const int64_t xd[4] = {1, K, 1, C}, wd[4] = {N, K, 1, 1};
-    const int64_t dyd[4] = {N, K, 1, 1};
     switch (pass) {
         case PURINE_CONV_FWD:   // y = x w^T through the weight-gradient kernel (split reduction over C)
             return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xd, wd, dtype)) +
                    (dtype == PURINE_BF16 ? (size_t)N * K * 4 : 0);   // bf16: the fp32 product matrix before the bias
-        case PURINE_CONV_BWD_DATA:   // dx = dy w through the forward kernel
-            return purine_conv_workspace_bytes(PURINE_CONV_FWD, &kUnitConv, xd, wd, dtype);
+        case PURINE_CONV_BWD_DATA: {   // dx = dy w through the forward kernel, or (bf16) a kernel of its own
+            const size_t own = dtype == PURINE_BF16 ? fc_dgrad_bf16_plan(N, C, K, nullptr, nullptr) : SIZE_MAX;
+            return own != SIZE_MAX ? own : purine_conv_workspace_bytes(PURINE_CONV_FWD, &kUnitConv, xd, wd, dtype);
+        }
         case PURINE_CONV_BWD_WEIGHT:
         case PURINE_CONV_BWD_WEIGHT_BIAS: {
             if (dtype == PURINE_BF16) {
                 // dw = dy^T x through the weight-gradient kernel on the transposed matrices (the batch
-                // as the pixel axis): both transposes, that kernel's partial sums, BiasBwd's
+                // as the pixel axis): both transposes and that kernel's partial sums
                 const int64_t xt[4] = {1, C, 1, N}, wt[4] = {K, C, 1, 1};
                 return align256((size_t)N * C * 2) + align256((size_t)N * K * 2) +
-                       align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xt, wt, dtype)) +
-                       purine_bias_bwd_workspace_bytes(dyd, dtype);
+                       align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xt, wt, dtype));
             }
-            // fp32: dw = dy^T x through the backward-data kernel, db by BiasBwd
-            return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, dtype)) +
-                   purine_bias_bwd_workspace_bytes(dyd, dtype);
+            // fp32: dw = dy^T x through the backward-data kernel; db needs no scratch
+            return align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, dtype));
         }
         default: return 0;
     }
@@ -793,6 +792,17 @@ int purine_fc_bwd_data(const purine_tensor* dy, const purine_tensor* w, purine_t
     if ((rc = check_fc(dx, w, dy))) return rc;
     // dx[n][c] = sum_k dy[n][k] w[k][c]: a 1x1 convolution of the plane w [K channels x C pixels] with
     // the filter bank dy [N x K]
+    if (dy->dtype == PURINE_BF16) {
+        // rows of whole 16-byte packets: the kernel that stages w as it lies in memory
+        const size_t need = fc_dgrad_bf16_plan(dy->dim[0], w->dim[1], w->dim[0], nullptr, nullptr);
+        if (need != SIZE_MAX) {
+            if (overlaps(dx, dy) || overlaps(dx, w)) return PURINE_E_LAYOUT;
+            if (need && (!ws || ws_bytes < need)) return PURINE_E_WORKSPACE;
+            if (need && (((uintptr_t)ws) & 15u)) return PURINE_E_LAYOUT;
+            return hip_status(launch_fc_dgrad_bf16(dy->data, w->data, dx->data, (int)dy->dim[0], (int)w->dim[0],
+                                                   (int)w->dim[1], ws, (hipStream_t)hip_stream));
+        }
+    }
     const purine_tensor wp = as_plane(w), dyf = as_filter(dy);
     purine_tensor dxp = as_plane(dx);
     return conv_fwd_impl(&kUnitConv, &wp, &dyf, nullptr, &dxp, 0, ws, ws_bytes, hip_stream);
@@ -804,51 +814,49 @@ int purine_fc_bwd_weight(const purine_tensor* x, const purine_tensor* dy, purine
     if ((rc = check_fc(x, dw, dy, true)) || (rc = check_beta(beta))) return rc;
     const int64_t N = x->dim[0], C = x->dim[1], K = dw->dim[0];
     const purine_tensor dy4 = as_filter(dy);
-    const size_t bias_ws = db ? purine_bias_bwd_workspace_bytes(dy4.dim, x->dtype) : 0;
     if (db) {
         if ((rc = check_tensor(db, 1))) return rc;
         if (db->dtype != PURINE_F32) return PURINE_E_DTYPE;
         if (db->dim[0] != dw->dim[0]) return PURINE_E_SHAPE;
         if (overlaps(db, dy) || overlaps(db, x) || overlaps(db, dw)) return PURINE_E_LAYOUT;
     }
-    size_t conv_ws;   // bytes of ws in front of BiasBwd's part
     if (x->dtype == PURINE_BF16) {
         // dw[k][c] = sum_n dy[n][k] x[n][c] with an fp32 result: the weight-gradient contraction over
         // the batch as the pixel axis, on transposed copies x^T [C x N] and dy^T [K x N]
         const int64_t xt[4] = {1, C, 1, N}, wt[4] = {K, C, 1, 1};
         const size_t xt_bytes = align256((size_t)N * C * 2), dyt_bytes = align256((size_t)N * K * 2);
         const size_t wg_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_WEIGHT, &kUnitConv, xt, wt, PURINE_BF16));
-        conv_ws = xt_bytes + dyt_bytes + wg_ws;
-        if (!ws || ws_bytes < conv_ws + bias_ws) return PURINE_E_WORKSPACE;
+        if (!ws || ws_bytes < xt_bytes + dyt_bytes + wg_ws) return PURINE_E_WORKSPACE;
         if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+        if (overlaps(dw, x) || overlaps(dw, dy)) return PURINE_E_LAYOUT;
         purine_tensor xT = *x, dyT = *dy;
         xT.data = ws; dyT.data = (char*)ws + xt_bytes;
         xT.dim[0] = C; xT.dim[1] = N; dyT.dim[0] = K; dyT.dim[1] = N;
-        hipError_t e = launch_transpose16(x->data, xT.data, (int)N, (int)C, (hipStream_t)hip_stream);
-        if (e == hipSuccess) e = launch_transpose16(dy->data, dyT.data, (int)N, (int)K, (hipStream_t)hip_stream);
+        hipError_t e = launch_transpose16_pair(x->data, xT.data, (int)C, dy->data, dyT.data, (int)K, (int)N,
+                                               (hipStream_t)hip_stream);
         if (e != hipSuccess) return hip_status(e);
-        const purine_tensor xp = as_plane(&xT), dyp = as_plane(&dyT);
-        purine_tensor dwf = as_filter(dw);
-        if ((rc = conv_bwd_weight_impl(&kUnitConv, &xp, &dyp, &dwf, nullptr, beta, (char*)ws + xt_bytes + dyt_bytes, wg_ws,
-                                       hip_stream)))
-            return rc;
-    } else {
-        const int64_t xd[4] = {1, K, 1, C}, wd[4] = {N, K, 1, 1};
-        conv_ws = align256(purine_conv_workspace_bytes(PURINE_CONV_BWD_DATA, &kUnitConv, xd, wd, PURINE_F32));
-        if (db) {
-            if (!ws || ws_bytes < conv_ws + bias_ws) return PURINE_E_WORKSPACE;
-            if (((uintptr_t)ws) & 15u) return PURINE_E_LAYOUT;
+        if (fc_wgrad_bf16_applies(N, C, K)) {
+            // batches of whole 16-byte packets: one kernel that owns whole tiles of dw (no partial sums)
+            e = launch_fc_wgrad_bf16(dyT.data, xT.data, (float*)dw->data, (int)N, (int)K, (int)C, beta != 0.0f,
+                                     (hipStream_t)hip_stream);
+            if (e != hipSuccess) return hip_status(e);
+        } else {
+            const purine_tensor xp = as_plane(&xT), dyp = as_plane(&dyT);
+            purine_tensor dwf = as_filter(dw);
+            if ((rc = conv_bwd_weight_impl(&kUnitConv, &xp, &dyp, &dwf, nullptr, beta, (char*)ws + xt_bytes + dyt_bytes,
+                                           wg_ws, hip_stream)))
+                return rc;
         }
+    } else {
         // dw[k][c] = sum_n dy[n][k] x[n][c]: the backward-data contraction with dy := x (plane of N
         // channels) and w := dy (filter bank [N x K])
         const purine_tensor xp = as_plane(x);
         purine_tensor dwp = as_plane(dw);
-        if ((rc = conv_bwd_data_impl(&kUnitConv, &xp, &dy4, nullptr, &dwp, beta, ws, ws_bytes < conv_ws ? ws_bytes : conv_ws,
-                                     hip_stream)))
-            return rc;
+        if ((rc = conv_bwd_data_impl(&kUnitConv, &xp, &dy4, nullptr, &dwp, beta, ws, ws_bytes, hip_stream))) return rc;
     }
-    if (db)   // column sums of dy: BiasBwd on dy as [N, K, 1, 1]
-        return purine_bias_bwd(&dy4, db, beta, (char*)ws + conv_ws, ws_bytes - conv_ws, hip_stream);
+    if (db)   // column sums of dy
+        return hip_status(launch_fc_bias_bwd(dy->dtype, dy->data, (float*)db->data, (int)N, (int)K, beta,
+                                             (hipStream_t)hip_stream));
     return PURINE_OK;
 }
 

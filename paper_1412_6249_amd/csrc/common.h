@@ -157,7 +157,19 @@ hipError_t launch_relu_bwd(int dtype, const void* x, const void* dy, void* dx, i
                            hipStream_t st);
 hipError_t launch_bias_rows(const float* b, float* y, int N, int K, hipStream_t st);
 hipError_t launch_fc_finish_bf16(const float* acc, const void* b, void* y, int N, int K, hipStream_t st);
-hipError_t launch_transpose16(const void* in, void* out, int rows, int cols, hipStream_t st);
+// bf16 fully-connected data gradient: scratch bytes and slicing (SIZE_MAX: rows are not whole
+// 16-byte packets, the kernel does not apply)
+size_t fc_dgrad_bf16_plan(int64_t N, int64_t C, int64_t K, int* slices, int* k_per_slice);
+hipError_t launch_fc_dgrad_bf16(const void* dy, const void* w, void* dx, int N, int K, int C, void* ws, hipStream_t st);
+// db[k] = beta*db[k] + sum_n dy[n][k] for a dense [N][K] matrix (fixed summation order)
+hipError_t launch_fc_bias_bwd(int dtype, const void* dy, float* db, int N, int K, float beta, hipStream_t st);
+// out0 = in0^T and out1 = in1^T for dense 2-byte matrices of `rows` x cols0 / cols1 elements, one launch
+hipError_t launch_transpose16_pair(const void* in0, void* out0, int cols0, const void* in1, void* out1, int cols1, int rows,
+                                   hipStream_t st);
+// bf16 fully-connected weight gradient on the transposed matrices (batches of a multiple of 8 samples)
+bool fc_wgrad_bf16_applies(int64_t N, int64_t C, int64_t K);
+hipError_t launch_fc_wgrad_bf16(const void* dyT, const void* xT, float* dw, int N, int K, int C, bool accumulate,
+                                hipStream_t st);
 hipError_t launch_relu_view(int dtype, bool bwd, const void* x, const void* dy, void* out, int N, int run,
                             int64_t x_ns, int64_t dy_ns, int64_t out_ns, hipStream_t st);
 hipError_t launch_sgd_update(int dtype, const void* w, const float* dw, void* new_w, float lr,

@@ -185,6 +185,31 @@ __global__ __launch_bounds__(TPB) void bias_rows_kernel(const float* __restrict_
     for (size_t i = (size_t)blockIdx.x * TPB + threadIdx.x; i < n; i += stride) y[i] += b[i % (size_t)K];
 }
 
+// Bias gradient of a fully-connected layer: db[k] = beta*db[k] + sum_n dy[n][k] on a dense [N][K]
+// matrix. 64 columns per workgroup (a wavefront reads whole rows of them); wavefront g adds the rows
+// n = g, g + 4, ... in four interleaved chains, and the four partial sums are added in wavefront
+// order: a fixed order, the same result on every run.
+template <typename T>
+__global__ __launch_bounds__(256) void fc_bias_bwd_kernel(const T* __restrict__ dy, float* db, int N, int K, float beta) {
+    __shared__ float part[4][64];
+    const int lane = threadIdx.x & 63, g = threadIdx.x >> 6, k = (int)blockIdx.x * 64 + lane;
+    float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (k < K) {
+        int n = g;
+        for (; n + 12 < N; n += 16) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s[j] += ldf<T>(dy, (size_t)(n + 4 * j) * K + k);
+        }
+        for (int j = 0; n < N; n += 4, ++j) s[j] += ldf<T>(dy, (size_t)n * K + k);
+    }
+    part[g][lane] = (s[0] + s[1]) + (s[2] + s[3]);
+    __syncthreads();
+    if (g == 0 && k < K) {
+        const float t = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        db[k] = beta != 0.0f ? db[k] + t : t;
+    }
+}
+
 // bf16 fully-connected forward, last step: y[n][k] = bf16(acc[n][k] + b[k]) from the fp32 product
 // matrix (one rounding, to nearest even, after the bias is added in fp32). b may be null.
 __global__ __launch_bounds__(TPB) void fc_finish_bf16_kernel(const float* __restrict__ acc, const uint16_t* __restrict__ b,
@@ -194,13 +219,20 @@ __global__ __launch_bounds__(TPB) void fc_finish_bf16_kernel(const float* __rest
         y[i] = f2bf(acc[i] + (b ? bf2f(b[i % (size_t)K]) : 0.0f));
 }
 
-// out[c][r] = in[r][c] for a dense 2-byte matrix of `rows` x `cols` elements; 64x64 tiles through
-// LDS (row pitch 65 elements: a tile column read walks through different banks in pairs)
-__global__ __launch_bounds__(256) void transpose16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
-                                                          int rows, int cols) {
+// out[c][r] = in[r][c] for two dense 2-byte matrices of `rows` x cols0 and `rows` x cols1 elements in
+// one launch (the first tiles0 workgroups take the first matrix); 64x64 tiles through LDS (row pitch
+// 66 elements: a tile column read walks through different banks)
+__global__ __launch_bounds__(256) void transpose16_pair_kernel(const uint16_t* __restrict__ in0, uint16_t* __restrict__ out0,
+                                                               int cols0, unsigned tiles0, const uint16_t* __restrict__ in1,
+                                                               uint16_t* __restrict__ out1, int cols1, int rows) {
     __shared__ uint16_t tile[64][66];
+    const bool second = blockIdx.x >= tiles0;
+    const uint16_t* __restrict__ in = second ? in1 : in0;
+    uint16_t* __restrict__ out = second ? out1 : out0;
+    const int cols = second ? cols1 : cols0;
+    const unsigned b = second ? blockIdx.x - tiles0 : blockIdx.x;
     const int tiles_c = (cols + 63) / 64;
-    const int r0 = (int)(blockIdx.x / tiles_c) * 64, c0 = (int)(blockIdx.x % tiles_c) * 64;
+    const int r0 = (int)(b / tiles_c) * 64, c0 = (int)(b % tiles_c) * 64;
     const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
     for (int j = ty; j < 64; j += 4) {
         const int r = r0 + j, c = c0 + tx;
@@ -702,12 +734,26 @@ hipError_t launch_fc_finish_bf16(const float* acc, const void* b, void* y, int N
     return hipGetLastError();
 }
 
-hipError_t launch_transpose16(const void* in, void* out, int rows, int cols, hipStream_t st) {
-    const long long tiles = (long long)((rows + 63) / 64) * ((cols + 63) / 64);
-    if (rows < 1 || cols < 1 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+hipError_t launch_fc_bias_bwd(int dtype, const void* dy, float* db, int N, int K, float beta, hipStream_t st) {
+    if (N < 1 || K < 1) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((K + 63) / 64));
     (void)hipGetLastError();
-    hipLaunchKernelGGL(transpose16_kernel, dim3((unsigned)tiles), dim3(256), 0, st, (const uint16_t*)in,
-                       (uint16_t*)out, rows, cols);
+    if (dtype == PURINE_BF16)
+        hipLaunchKernelGGL(fc_bias_bwd_kernel<uint16_t>, grid, dim3(256), 0, st, (const uint16_t*)dy, db, N, K, beta);
+    else
+        hipLaunchKernelGGL(fc_bias_bwd_kernel<float>, grid, dim3(256), 0, st, (const float*)dy, db, N, K, beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose16_pair(const void* in0, void* out0, int cols0, const void* in1, void* out1, int cols1, int rows,
+                                   hipStream_t st) {
+    if (rows < 1 || cols0 < 1 || cols1 < 1) return hipErrorInvalidValue;
+    const long long row_tiles = (rows + 63) / 64;
+    const long long tiles0 = row_tiles * ((cols0 + 63) / 64), tiles1 = row_tiles * ((cols1 + 63) / 64);
+    if (tiles0 + tiles1 > 0x7fffffffLL) return hipErrorInvalidValue;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(transpose16_pair_kernel, dim3((unsigned)(tiles0 + tiles1)), dim3(256), 0, st, (const uint16_t*)in0,
+                       (uint16_t*)out0, cols0, (unsigned)tiles0, (const uint16_t*)in1, (uint16_t*)out1, cols1, rows);
     return hipGetLastError();
 }
 
