@@ -37,7 +37,11 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int NT = 256;             // four wavefronts
 constexpr int KT = 64;              // output channels per workgroup
-constexpr int ORG = 8;              // element of a plane that holds index 0 (left halo before it)
+// Element of a plane row that holds index 0 (left halo before it). Column stride 2: planes take
+// 8-byte stores (four pixels of a parity), so index 0 may sit 8 bytes past a 16-byte boundary, which
+// makes the 16 elements q - 4 .. q + 11 around a step's window two ALIGNED 16-byte reads; with
+// stride 1 the planes take whole 16-byte packets and index 0 stays on a boundary.
+constexpr int plane_org(int sw) { return sw == 2 ? 12 : 8; }
 constexpr int X_ROUNDS = 3;         // 16-byte packets per thread and iteration, at most: input rows
 constexpr int D_ROUNDS = 4;         // ... and the dy row
 
@@ -99,6 +103,7 @@ __global__ __launch_bounds__(NT, 2) void wgrad_taps_bf16_kernel(const TapsWgradP
     }
 
     // lanes past the last (c, r) pair repeat it; their columns are never stored
+    constexpr int ORG = plane_org(SW);
     const int b_row = p.d_bytes + min(lane & 31, p.cr - 1) * p.ppitch + (ORG + khalf * 8) * 2;
     const int a_addr = (kt * 32 + (lane & 31)) * p.dpitch + khalf * 16;
 
@@ -202,13 +207,22 @@ __global__ __launch_bounds__(NT, 2) void wgrad_taps_bf16_kernel(const TapsWgradP
                 if (lo > hi) continue;                            // no tap reads this plane
                 const unsigned char* pb = base + b_row + f * plane_bytes + st * 32;
                 uint32_t w[8];                                    // dwords of elements q - 4 .. q + 11
-                const u32x4 d = *reinterpret_cast<const u32x4*>(pb);
-                w[2] = d[0]; w[3] = d[1]; w[4] = d[2]; w[5] = d[3];
-                const int first = (4 + lo) >> 1, last = (4 + hi + 7) >> 1;
-                w[0] = first <= 0 ? *reinterpret_cast<const uint32_t*>(pb - 8) : 0u;
-                w[1] = first <= 1 ? *reinterpret_cast<const uint32_t*>(pb - 4) : 0u;
-                w[6] = last >= 6 ? *reinterpret_cast<const uint32_t*>(pb + 16) : 0u;
-                w[7] = last >= 7 ? *reinterpret_cast<const uint32_t*>(pb + 20) : 0u;
+                if (SW == 2) {
+                    // (4-byte reads of the dwords on either side would all fall into the 16 banks the
+                    // 16-byte row pitch allows: four lanes per bank)
+                    const u32x4 d0 = *reinterpret_cast<const u32x4*>(pb - 8);
+                    const u32x4 d1 = *reinterpret_cast<const u32x4*>(pb + 8);
+                    w[0] = d0[0]; w[1] = d0[1]; w[2] = d0[2]; w[3] = d0[3];
+                    w[4] = d1[0]; w[5] = d1[1]; w[6] = d1[2]; w[7] = d1[3];
+                } else {
+                    const u32x4 d = *reinterpret_cast<const u32x4*>(pb);
+                    w[2] = d[0]; w[3] = d[1]; w[4] = d[2]; w[5] = d[3];
+                    const int first = (4 + lo) >> 1, last = (4 + hi + 7) >> 1;
+                    w[0] = first <= 0 ? *reinterpret_cast<const uint32_t*>(pb - 8) : 0u;
+                    w[1] = first <= 1 ? *reinterpret_cast<const uint32_t*>(pb - 4) : 0u;
+                    w[6] = last >= 6 ? *reinterpret_cast<const uint32_t*>(pb + 16) : 0u;
+                    w[7] = last >= 7 ? *reinterpret_cast<const uint32_t*>(pb + 20) : 0u;
+                }
 #pragma unroll
                 for (int s = 0; s < S; ++s) {
                     if (tap_plane(s, PW, SW) != f) continue;
@@ -299,8 +313,9 @@ bool fill_params(const ConvGeom& g, TapsWgradParams* out) {
     p.xchunks = g.W / 8; p.dychunks = g.Q / 8;
     // a plane row holds the W / sw columns of its parity and every window of the steps (elements
     // q - 4 .. q + 11 around each aligned packet)
-    int elems = ORG + p.steps * 16 + 4;
-    if (elems < ORG + (g.W + g.sw - 1) / g.sw) elems = ORG + (g.W + g.sw - 1) / g.sw;
+    const int org = plane_org(g.sw);
+    int elems = org + p.steps * 16 + 4;
+    if (elems < org + (g.W + g.sw - 1) / g.sw) elems = org + (g.W + g.sw - 1) / g.sw;
     p.ppitch = odd16_pitch(elems * 2);
     p.dpitch = odd16_pitch(g.Q * 2);
     p.x_tasks = p.cr * p.xchunks;
