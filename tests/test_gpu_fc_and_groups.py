@@ -61,6 +61,45 @@ def test_fc_layer(N, C, K, dtype):
             assert rel_l2(to_host(ty), oracle.fc_fwd(x, w)) <= tol
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_fc_layer_full_shape(dtype):
+    """AlexNet's first fully-connected layer at the batch the paper trains with (9216 -> 4096,
+    N = 128): every element of y, dx, dw, db against the oracle, and the same bits on a second run
+    (the split reductions add their partial results in a fixed order)."""
+    import torch
+    import paper_1412_6249_amd as pa
+    from gpu_util import rel_l2, workspace, to_dev, to_host, tdtype, pcode, TOL, DEV
+    from synth import gen
+    N, C, K = 128, 9216, 4096
+    rs = np.random.default_rng(96)
+    x = rs.uniform(-1, 1, size=(N, C)).astype(np.float32)
+    w = (rs.standard_normal((K, C)) * 0.01).astype(np.float32)
+    b = rs.uniform(-1, 1, size=(K,)).astype(np.float32)
+    dy = rs.uniform(-1, 1, size=(N, K)).astype(np.float32)
+    if dtype == "bf16":
+        x, w, b, dy = (gen.quantize_bf16(a) for a in (x, w, b, dy))
+    tx, tw, tb, tdy = to_dev(x, dtype), to_dev(w, dtype), to_dev(b, dtype), to_dev(dy, dtype)
+    q = lambda which: workspace(pa.purine_fc_workspace_bytes(which, N, C, K, pcode(dtype)))
+    ws_f, ws_d, ws_w = q(pa.PURINE_CONV_FWD), q(pa.PURINE_CONV_BWD_DATA), q(pa.PURINE_CONV_BWD_WEIGHT)
+    runs = []
+    for _ in range(2):
+        ty = torch.full((N, K), float("nan"), dtype=tdtype(dtype), device=DEV)
+        tdx = torch.full((N, C), float("nan"), dtype=tdtype(dtype), device=DEV)
+        tdw = torch.full((K, C), float("nan"), device=DEV)
+        tdb = torch.full((K,), float("nan"), device=DEV)
+        pa.purine_fc_fwd(tx, tw, tb, ty, ws=ws_f)
+        pa.purine_fc_bwd_data(tdy, tw, tdx, ws=ws_d)
+        pa.purine_fc_bwd_weight(tx, tdy, tdw, tdb, ws=ws_w)
+        torch.cuda.synchronize()
+        runs.append([to_host(t) for t in (ty, tdx, tdw, tdb)])
+    ref_dw, ref_db = oracle.fc_bwd_weight(x, dy)
+    refs = (oracle.fc_fwd(x, w, b), oracle.fc_bwd_data(dy, w), ref_dw, ref_db)
+    gtol = 1e-5 if dtype == "f32" else 1e-4
+    for name, got, again, ref, t in zip(("y", "dx", "dw", "db"), runs[0], runs[1], refs, (TOL[dtype], TOL[dtype], gtol, gtol)):
+        assert np.isfinite(got).all() and rel_l2(got, ref) <= t, (name, rel_l2(got, ref))
+        assert np.array_equal(got, again), name
+
+
 # name, groups, N, C, H, W, K, R, S, stride, pad: AlexNet's two-group layers at reduced size, plus ragged ones
 GROUP_CASES = [
     ("alexnet_conv2_like", 2, 2, 96, 27, 27, 256, 5, 5, (1, 1), (2, 2)),      # 27*27 odd: (C/G)*HW % 4 == 0 via C/G = 48
