@@ -187,7 +187,9 @@ __global__ __launch_bounds__(NT, 2) void wgrad_taps_bf16_kernel(const TapsWgradP
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[s][e] = 0.0f;
     float dbacc = 0.0f;
-    const bool do_db = p.db_out != nullptr && parity == 0;    // bias sums: one step parity's wavefronts read every step
+    // bias sums: the wavefronts of step parity 1 (which have one MFMA step fewer per row when the step
+    // count is odd) read every step of their rows
+    const bool do_db = p.db_out != nullptr && parity == 1;
 
     // the MFMA steps of the output row staged in buffer `buf`: this wavefront's step parity
     auto multiply = [&](int buf) {
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(NT, 2) void wgrad_taps_bf16_kernel(const TapsWgradP
             if (do_db) dbacc += sum8(a);
         }
         if (do_db)      // ... so they take the other parity's steps of their own rows as well
-            for (int st = 1; st < p.steps; st += 2) dbacc += sum8(*reinterpret_cast<const u32x4*>(base + a_addr + st * 32));
+            for (int st = 0; st < p.steps; st += 2) dbacc += sum8(*reinterpret_cast<const u32x4*>(base + a_addr + st * 32));
     };
 
     if (g0 < g1) {
@@ -291,7 +293,7 @@ __global__ __launch_bounds__(NT, 2) void wgrad_taps_bf16_kernel(const TapsWgradP
     if (p.db_out != nullptr) {   // lanes l and l + 32 hold the two 8-pixel halves of row l's steps
         const float tot = dbacc + __shfl_xor(dbacc, 32);
         const int k = k0 + kt * 32 + (lane & 31);
-        if (parity == 0 && khalf == 0 && k < p.K) p.db_out[(size_t)worker * p.K + k] = tot;
+        if (parity == 1 && khalf == 0 && k < p.K) p.db_out[(size_t)worker * p.K + k] = tot;
     }
 }
 

@@ -52,7 +52,7 @@ def bench_layer(L, ops, iters, out=sys.stdout):
     dw = torch.empty(L.w_shape, dtype=torch.float32, device=dev)
     db = torch.empty((L.K,), dtype=torch.float32, device=dev)
     desc = B.conv_desc(L.stride, L.pad)
-    ws = torch.empty(max(256, B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT, desc, L.x_shape,
+    ws = torch.empty(max(256, B.purine_conv_workspace_bytes(B.PURINE_CONV_BWD_WEIGHT_BIAS, desc, L.x_shape,
                                                             L.w_shape, code)),
                      dtype=torch.uint8, device=dev)
     ws2 = torch.empty(max(256, B.purine_bias_bwd_workspace_bytes(L.y_shape, code)), dtype=torch.uint8,
@@ -66,6 +66,7 @@ def bench_layer(L, ops, iters, out=sys.stdout):
         "fwd_fused": (lambda: B.purine_conv_fwd_bias_relu(desc, x, w, b, y, relu=True, ws=wsf), L.flop_per_pass),
         "bwd_data": (lambda: B.purine_conv_bwd_data(desc, dy, w, dx, ws=wsd), L.flop_per_pass),
         "bwd_weight": (lambda: B.purine_conv_bwd_weight(desc, x, dy, dw, ws=ws), L.flop_per_pass),
+        "bwd_weight_bias": (lambda: B.purine_conv_bwd_weight_bias(desc, x, dy, dw, db, ws=ws), L.flop_per_pass),
         "bias_fwd": (lambda: B.purine_bias_fwd(b, y), 0),
         "bias_bwd": (lambda: B.purine_bias_bwd(dy, db, ws=ws2), 0),
     }
@@ -81,7 +82,8 @@ def bench_layer(L, ops, iters, out=sys.stdout):
             es = x.element_size()
             nb = {"fwd": (x.numel() + w.numel() + y.numel()) * es, "fwd_fused": (x.numel() + w.numel() + y.numel()) * es,
                   "bwd_data": (dy.numel() + w.numel() + dx.numel()) * es,
-                  "bwd_weight": (x.numel() + dy.numel()) * es + dw.numel() * 4}[name]
+                  "bwd_weight": (x.numel() + dy.numel()) * es + dw.numel() * 4,
+                  "bwd_weight_bias": (x.numel() + dy.numel()) * es + dw.numel() * 4}[name]
             attainable = min(PEAK[L.dtype], flop / nb * HBM_TBS)
             out.write("%-10s %-10s %9.4f ms (best %9.4f)  %8.2f TFLOP/s  %5.1f%% of %s MFMA peak  "
                       "%5.1f%% of attainable (%s-bound)  %7.1f GB/s algorithmic\n"
