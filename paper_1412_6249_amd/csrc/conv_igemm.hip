@@ -658,10 +658,11 @@ PixPlan plan_conv_pix(const ConvGeom& g, bool bwd_data, int dtype, bool fused, b
         const double hide = per_cu >= 3 ? 1.0 : (per_cu == 2 ? 0.95 : 0.6);
         // the bf16 element-gather modes fetch 32 elements per thread and slab at 256 pixels per
         // workgroup, which measured a third slower than 16 at 128
-        // ... and in the forward pass of a single-tap bf16 layer 64 pixels per workgroup measured 9 %
-        // faster again than 128 (64 -> 64 channels at 56x56: 0.062 -> 0.056 ms; backward-data: no difference)
+        // ... and in a single-tap bf16 layer 64 pixels per workgroup measured faster again than 128
+        // (64 -> 64 channels at 56x56 with the pixel-pair gather: forward 0.055 -> 0.048 ms,
+        // backward-data 0.045 -> 0.043 ms)
         const double eff = (flat_bf16 && t.bn == 256) ? t.eff * 0.65
-                         : (flat_bf16 && !bwd_data && !pl.flat && t.bm == 64 && t.bn == 64) ? 1.04 : t.eff;
+                         : (flat_bf16 && !pl.flat && t.bm == 64 && t.bn == 64) ? 1.04 : t.eff;
         const double load = (double)per_cu * t.bm * t.bn * (1.0 + gather / t.bm) / (eff * hide);
         if (best < 0 || load < best) { best = load; pl.bm = t.bm; pl.bn = t.bn; }
     }

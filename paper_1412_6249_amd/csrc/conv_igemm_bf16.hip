@@ -27,9 +27,14 @@ constexpr int LDK = BKH + 8;   // LDS row pitch in bf16 elements
 // values padded to a multiple of 32, the filter copy is A[i][Kg_pad], and every gathered element
 // has its own tap, walked incrementally on the scalar unit (the rows of a slab are uniform per
 // wavefront) and its own bounds test, recorded as one validity bit.
-// NCHW (single-tap layers, where every element is gathered exactly once and a blocked copy would
+// NCHW = 1 (single-tap layers, where every element is gathered exactly once and a blocked copy would
 // only add traffic): tap-major walk, 2-byte gathers straight from the NCHW tensor.
-template <bool FLAT, bool NCHW, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+// NCHW = 2: the same for layers whose gather is the identity (1x1 filter, stride 1, no padding) and
+// whose planes hold an even number of pixels: a thread loads the dword that holds TWO adjacent
+// pixels of a channel, and one byte-permute per output dword splits its channels' dwords into the
+// two pixels' [8 channels] packets: half the load instructions and an eighth of the packing work
+// of the element gather.
+template <bool FLAT, int NCHW, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixParams p) {
     constexpr int NT = WM * WN * 64;
     constexpr int BM = WM * TM * 32;
@@ -41,8 +46,12 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     constexpr int A_CPR = BKH / 8;             // 16-byte pieces per filter row
     constexpr int A_VEC = BM * A_CPR;
     constexpr int A_ITERS = (A_VEC + NT - 1) / NT;
-    constexpr bool ELEMS = FLAT || NCHW;       // 2-byte gathers with per-element validity bits
-    static_assert(!(FLAT && NCHW), "one gather mode");
+    constexpr int PAIRS = BN / 2;              // pixel pairs of the tile
+    constexpr int TPP2 = NT / PAIRS;           // threads sharing one pixel pair
+    constexpr int CH2 = BKH / TPP2;            // channels per thread per slab in the pair mode
+    constexpr bool PAIR = NCHW == 2 && CH2 >= 4;   // narrower tiles keep the element gather
+    constexpr bool ELEMS = FLAT || (NCHW != 0 && !PAIR);   // 2-byte gathers with per-element validity bits
+    static_assert(!(FLAT && NCHW != 0), "one gather mode");
 
     __shared__ __attribute__((aligned(16))) uint16_t As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BN * LDK];
@@ -77,6 +86,22 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         g_off = n * (ELEMS ? p.in_ns : (p.Ci_pad / 8) * p.HiWi) + g_h * p.Wi + g_w;
     }
     const int ch_base = __builtin_amdgcn_readfirstlane(tid / BN) * CH;   // uniform per wavefront
+    // pair mode: this thread's pixel pair (2*pp, 2*pp + 1 of the tile) and its CH2 channels of a slab
+    int p_off = 0, p_cg = 0, p_row = 0;
+    bool p_live = false, p_swap = false;
+    if (PAIR) {
+        const int pp = tid % PAIRS;
+        p_cg = (tid / PAIRS) * CH2;
+        const int pix = j0 + 2 * pp;
+        p_live = pix < p.M;                    // M is even: the pair is inside or outside as a whole
+        const int pc = p_live ? pix : 0;
+        const int n = fastdiv(pc, p.div_howo);
+        p_off = n * p.in_ns + (pc - n * p.HoWo);
+        p_row = 2 * pp;
+        // rows are 80 bytes: the 16 lanes of a store would hit 8 bank groups twice if all wrote their even
+        // pixel; every second group of 8 lanes writes its odd pixel first
+        p_swap = (pp >> 3) & 1;
+    }
     // the blocked copy as a raw buffer (not used by the 2-byte gather modes)
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t*>(in), (short)0, ELEMS ? 0 : (int)p.in_bytes, 0x00020000);
@@ -93,6 +118,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
     typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));   // native vector: stays in registers
     u32x4_t a_reg[A_ITERS];
     uint32_t b_reg[ELEMS ? CH : 1];  // FLAT / NCHW: raw 16-bit values
+    uint32_t pr_reg[PAIR ? CH2 : 1]; // pair mode: one dword (two pixels) per channel
     uint4 blk_reg[CH / 8];           // blocked input: 8 channels of this thread's pixel per piece
     bool b_ok = false;
     uint32_t b_bits = 0;             // FLAT / NCHW: validity of each gathered element
@@ -134,12 +160,25 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
             nx_c0 = nx_c0 >= p.Ci_pad ? 0 : nx_c0;
             return;
         }
+        if (PAIR) {
+            b_bits = 0;
+#pragma unroll
+            for (int e = 0; e < (PAIR ? CH2 : 0); ++e) {
+                const int ci = nx_c0 + p_cg + e;
+                const bool ok = p_live & (ci < p.Ci);
+                pr_reg[PAIR ? e : 0] = *reinterpret_cast<const uint32_t*>(in + (ok ? p_off + ci * p.HiWi : 0));   // clamped: masked at the store
+                b_bits |= (ok ? 1u : 0u) << e;
+            }
+            nx_c0 += BKH;
+            nx_c0 = nx_c0 >= p.Ci_pad ? 0 : nx_c0;
+            return;
+        }
         const int hi = MINUS ? g_h - nx_r : g_h + nx_r;
         const int wi = MINUS ? g_w - nx_s : g_w + nx_s;
         const int tap_off = nx_r * p.Wi + nx_s;
         b_ok = g_live & ((unsigned)hi < (unsigned)p.Hi) & ((unsigned)wi < (unsigned)p.Wi);
         const int base = MINUS ? g_off - tap_off : g_off + tap_off;
-        if (NCHW) {
+        if (NCHW != 0) {
             b_bits = 0;
 #pragma unroll
             for (int e = 0; e < CH; ++e) {
@@ -153,7 +192,7 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
         // hardware range check answers with zeros (the copy is below 2^31 bytes, checked on the host)
         const unsigned vbase = b_ok ? (unsigned)base * 16u : 0x80000000u;
 #pragma unroll
-        for (int q = 0; q < (NCHW ? 0 : CH / 8); ++q) {
+        for (int q = 0; q < (NCHW != 0 ? 0 : CH / 8); ++q) {
             const int cb = ((nx_c0 + ch_base) >> 3) + q;                 // zero blocks pad Ci to Ci_pad
             typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
             const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, vbase, cb * p.HiWi * 16, 0);
@@ -173,6 +212,26 @@ __global__ __launch_bounds__(WM * WN * 64) void igemm_tap_bf16_kernel(const PixP
 #pragma unroll
         for (int it = 0; it < A_ITERS; ++it)
             if (a_src[it] >= 0) *reinterpret_cast<u32x4_t*>(&As[buf][a_dst[it]]) = a_reg[it];
+        if (PAIR) {
+            uint32_t ev[CH2 / 2], od[CH2 / 2];   // channel pairs of the even and of the odd pixel
+#pragma unroll
+            for (int h = 0; h < CH2 / 2; ++h) {
+                const uint32_t c0 = ((b_bits >> (2 * h)) & 1u) ? pr_reg[PAIR ? 2 * h : 0] : 0u;
+                const uint32_t c1 = ((b_bits >> (2 * h + 1)) & 1u) ? pr_reg[PAIR ? 2 * h + 1 : 0] : 0u;
+                ev[h] = __builtin_amdgcn_perm(c1, c0, 0x05040100u);
+                od[h] = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+            }
+            uint16_t* first = &Bs[buf][(p_row + (p_swap ? 1 : 0)) * LDK + p_cg];
+            uint16_t* second = &Bs[buf][(p_row + (p_swap ? 0 : 1)) * LDK + p_cg];
+#pragma unroll
+            for (int q = 0; q < CH2 / 4; ++q) {   // 8-byte pieces (4 channels)
+                const uint2 f = make_uint2(p_swap ? od[2 * q] : ev[2 * q], p_swap ? od[2 * q + 1] : ev[2 * q + 1]);
+                const uint2 g = make_uint2(p_swap ? ev[2 * q] : od[2 * q], p_swap ? ev[2 * q + 1] : od[2 * q + 1]);
+                *reinterpret_cast<uint2*>(first + q * 4) = f;
+                *reinterpret_cast<uint2*>(second + q * 4) = g;
+            }
+            return;
+        }
         uint16_t* row = &Bs[buf][(tid % BN) * LDK + ch_base];
         if (!ELEMS) {
 #pragma unroll
@@ -254,7 +313,7 @@ __global__ __launch_bounds__(256) void blockify_kernel(const uint16_t* __restric
     }
 }
 
-template <bool FLAT, bool NCHW, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
+template <bool FLAT, int NCHW, bool MINUS, bool D2S, bool FUSED, int TM, int TN, int WM, int WN>
 hipError_t launch_one(PixParams& p, hipStream_t st) {
     const long long total = (long long)p.tiles_i * p.tiles_pix;
     if (total <= 0 || total > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -265,13 +324,13 @@ hipError_t launch_one(PixParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool FLAT, bool NCHW, bool MINUS, bool D2S, bool FUSED>
+template <bool FLAT, int NCHW, bool MINUS, bool D2S, bool FUSED>
 hipError_t by_tile2(PixParams& p, int bm, int bn, hipStream_t st) {
 #define CALL(TM, TN, WM, WN) launch_one<FLAT, NCHW, MINUS, D2S, FUSED, TM, TN, WM, WN>(p, st)
     PURINE_TILE_SWITCH(CALL)
 #undef CALL
 }
-template <bool FLAT, bool NCHW, bool MINUS, bool D2S>
+template <bool FLAT, int NCHW, bool MINUS, bool D2S>
 hipError_t by_tile(PixParams& p, int bm, int bn, hipStream_t st) {
     const bool fused = p.bias || p.relu || p.mask;
     return fused ? by_tile2<FLAT, NCHW, MINUS, D2S, true>(p, bm, bn, st)
@@ -297,24 +356,31 @@ hipError_t blockify_input(PixParams& p, void* blocked, hipStream_t st) {
 }
 
 hipError_t dispatch_tap_bf16(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
-    if (mode == 0) return by_tile<false, false, false, false>(p, bm, bn, st);
-    if (mode == 1) return by_tile<false, false, true, false>(p, bm, bn, st);
-    return by_tile<false, false, true, true>(p, bm, bn, st);
+    if (mode == 0) return by_tile<false, 0, false, false>(p, bm, bn, st);
+    if (mode == 1) return by_tile<false, 0, true, false>(p, bm, bn, st);
+    return by_tile<false, 0, true, true>(p, bm, bn, st);
 }
 
 // single-tap layers: gathers from the NCHW tensor p.in itself. A strided backward-data pass whose
 // filter fits inside one stride step (R <= sh, S <= sw) is phase-folded onto a single tap too, and
 // needs the depth-to-space epilogue like any other phase-folded pass.
 hipError_t dispatch_tap_bf16_nchw(PixParams& p, int mode, int bm, int bn, hipStream_t st) {
-    if (mode == 0) return by_tile<false, true, false, false>(p, bm, bn, st);
-    if (mode == 1) return by_tile<false, true, true, false>(p, bm, bn, st);
-    return by_tile<false, true, true, true>(p, bm, bn, st);
+    // identity gather with whole pixel pairs: the pair mode
+    const bool identity = p.Rt == 1 && p.St == 1 && p.g_mul_h == 1 && p.g_mul_w == 1 && p.g_add_h == 0 && p.g_add_w == 0 &&
+                          p.Hi == p.Ho && p.Wi == p.Wo;
+    if (identity && mode != 2 && ((p.HoWo | p.in_ns) & 1) == 0 && (((uintptr_t)p.in) & 3u) == 0) {
+        if (mode == 0) return by_tile<false, 2, false, false>(p, bm, bn, st);
+        return by_tile<false, 2, true, false>(p, bm, bn, st);
+    }
+    if (mode == 0) return by_tile<false, 1, false, false>(p, bm, bn, st);
+    if (mode == 1) return by_tile<false, 1, true, false>(p, bm, bn, st);
+    return by_tile<false, 1, true, true>(p, bm, bn, st);
 }
 
 // forward, flattened (c, r, s) reduction; p.wt is the filter copy A[i_pad][Ci_pad] with Ci_pad = Kg
 // rounded up to a multiple of 32, p.Rt = p.St = 1
 hipError_t dispatch_flat_bf16(PixParams& p, int bm, int bn, hipStream_t st) {
-    return by_tile<true, false, false, false>(p, bm, bn, st);
+    return by_tile<true, 0, false, false>(p, bm, bn, st);
 }
 
 }  // namespace pix
