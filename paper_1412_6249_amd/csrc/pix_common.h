@@ -181,6 +181,7 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
             constexpr bool RELU = decltype(relu_c)::value;
 #pragma unroll
             for (int a = 0; a < TM; ++a) {
+                floatx4 bq = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const int row_lo = rows0 + a * 32 + (e >> 2) * 8 + (e & 3);     // scalar; this lane's row is khalf * 4 further
@@ -188,7 +189,14 @@ __device__ __forceinline__ void store_tile(const PixParams& p, T* __restrict__ o
                     const int soff = row_lo * p.HoWo * (int)sizeof(T);
                     const bool row_ok = row_lo + khalf * 4 < p.Co;
                     float bv = 0.0f;
-                    if (FUSED && FWD) bv = fwd_bias ? bias_lds[row_lo + khalf * 4 - i_tile0] : 0.0f;
+                    if (FUSED && FWD && sizeof(T) == 2) {
+                        // bf16 kernels are short per wavefront: the bias of the four consecutive rows of an
+                        // accumulator quad comes as one 16-byte LDS read instead of four round trips
+                        if ((e & 3) == 0 && fwd_bias) bq = *reinterpret_cast<const floatx4*>(&bias_lds[row_lo + khalf * 4 - i_tile0]);
+                        bv = bq[e & 3];
+                    } else if (FUSED && FWD) {
+                        bv = fwd_bias ? bias_lds[row_lo + khalf * 4 - i_tile0] : 0.0f;
+                    }
 #pragma unroll
                     for (int b = 0; b < TN; ++b) {
                         const unsigned vo = row_ok ? voff[b] : 0x80000000u;
