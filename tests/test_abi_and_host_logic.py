@@ -241,6 +241,19 @@ def test_operator_argument_validation_without_launch():
     assert pa.purine_fc_workspace_bytes(0, 4, 20, 6) > 0 and pa.purine_fc_workspace_bytes(7, 4, 20, 6) == 0
     assert pa.purine_fc_workspace_bytes(0, 4, 20, 6, BF16) >= 4 * 6 * 4 and pa.purine_fc_workspace_bytes(2, 4, 20, 6, BF16) >= 2 * (4 * 20 + 4 * 6)
     assert pa.purine_fc_workspace_bytes(0, 4, 20, 6, pa.PURINE_I32) == 0
+    # bf16 backward-data with rows of whole 16-byte packets: fp32 tiles of the slices of the reduction
+    # (whole multiples of N*C*4 bytes, none when one slice covers it); other shapes size the forward kernel's scratch
+    n_, c_, k_ = 128, 9216, 4096
+    sliced = pa.purine_fc_workspace_bytes(1, n_, c_, k_, BF16)
+    assert sliced % (n_ * c_ * 4) == 0 and 2 <= sliced // (n_ * c_ * 4) <= 64
+    assert pa.purine_fc_workspace_bytes(1, 8, 4096, 64, BF16) == 0                 # 32 column tiles, too short a reduction to slice
+    assert pa.purine_fc_workspace_bytes(1, n_, c_, k_ + 4, BF16) == \
+        pa.purine_conv_workspace_bytes(0, pa.conv_desc((1, 1), (0, 0)), (1, k_ + 4, 1, c_), (n_, k_ + 4, 1, 1), BF16)
+    bdy = binding.raw_desc(fake, BF16, (n_, k_))
+    bw = binding.raw_desc(fake + 0x10000000, BF16, (k_, c_))
+    bdx = binding.raw_desc(fake + 0x20000000, BF16, (n_, c_))
+    assert status(pa.purine_fc_bwd_data, bdy, bw, bdx, stream=s) == -5             # needs the slices' scratch
+    assert status(pa.purine_fc_bwd_data, bdy, bw, bdy, stream=s) == -2             # dx of the wrong extent
     big = binding.raw_desc(fake, F32, (1 << 12, 1 << 12, 1 << 4, 1 << 4))           # 2^32 elements
     assert status(pa.purine_relu_fwd, big, big, stream=s) == -2
     assert status(pa.purine_maxpool_fwd, pa.pool_desc(3, 2, 3), x, y, binding.raw_desc(fake + 0x500000, pa.PURINE_I32, (2, 4, 8, 8)), stream=s) == -8
