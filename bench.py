@@ -123,6 +123,7 @@ def run_config(cfg, args, secondary_figures):
 
     merge = cfg == 3 and not args.no_merge_1x1 and not args.unfused
     gb = build_workload(cfg, multi_stream=not args.single_stream, fuse=not args.unfused, merge_1x1=merge, fan_in_add=merge)
+    n_streams = len(gb.threads)      # `thread` ids of the timed graph: one HIP stream each
     # Warm-up and one step per operator with that operator's main kernel bracketed (twice, keeping
     # the shorter): the per-operator table, and which kernel dominates. These steps run serially
     # (every operator alone on the device), so that each bracket measures its kernel and so that a
@@ -280,7 +281,7 @@ def run_config(cfg, args, secondary_figures):
     return {"workload": WORKLOAD_NAMES[cfg], "ms_per_step": round(ms_per_step, 4), "value": round(value, 3),
             "dtype": dtype, "conv_gflop_per_step": round(flop / 1e9, 2),
             "frac_of_mfma_peak": round(value / PEAK_TFLOPS[dtype], 4),
-            "roofline": roofline, "secondary": secondary, "merge": merge}
+            "roofline": roofline, "secondary": secondary, "merge": merge, "streams": n_streams}
 
 
 def main():
@@ -324,7 +325,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": main_res["dtype"], "data": "synthetic",
         "config": {"workload": main_res["workload"], "conv_gflop_per_step": main_res["conv_gflop_per_step"],
-                   "executor": "bi-graph, %s%s, %s" % ("1 stream" if args.single_stream or cfg == 5 else "3+ streams",
+                   "executor": "bi-graph, %s%s, %s" % ("%d stream%s" % (main_res["streams"], "" if main_res["streams"] == 1 else "s"),
                                                         ", recorded pass replayed" if args.replay else "",
                                                       "separate bias/relu ops" if args.unfused
                                                       else "bias+relu fused into conv vertices"
@@ -343,7 +344,7 @@ def main():
                 continue
             r = run_config(c, args, secondary_figures=False)
             per[r["workload"]] = {k: r[k] for k in ("ms_per_step", "value", "dtype", "conv_gflop_per_step",
-                                                    "frac_of_mfma_peak", "roofline")}
+                                                    "frac_of_mfma_peak", "roofline", "streams")}
         result["per_config"] = per
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg)

@@ -36,6 +36,7 @@ class GraphBuilder:
         self.t = {}          # name -> torch tensor (storage)
         self.ids = {}        # name -> tensor vertex id
         self.ops = []        # (op id, kind, in names, out names, attrs kept alive)
+        self.threads = set() # `thread` ids in use: one HIP stream each
         self.conv_records = []   # one dict per conv layer, naming the vertices around each operator
         self.swaps = []          # (old, new) parameter vertices exchanged after every iteration
         self._keep = []
@@ -74,6 +75,7 @@ class GraphBuilder:
         oid = B.purine_graph_add_op(self.g, kind, [self.ids[n] for n in ins],
                                     [self.ids[n] for n in outs], thread, attrs)
         self.ops.append((oid, kind, list(ins), list(outs), attrs))
+        self.threads.add(int(thread))
         return oid
 
     # ---- layer-level wiring
